@@ -1,0 +1,432 @@
+/*
+ * CPU oracle for frame-synchronous WFST token-passing beam search over a CTC decoding graph.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, single-threaded, scalar fp32
+ * implementation used only to check the GPU decoder and to serve as a timed CPU baseline.
+ * It shares no code with the GPU path and must never be called from the product path.
+ *
+ * What it follows (paper: "GPU-Accelerated WFST Beam Search Decoder for CTC-based Speech
+ * Recognition"):
+ *   - Section "Algorithm description": one iteration per acoustic frame with the stages
+ *     ExpandArcs -> Prune -> store tokens and backpointers; the least-cost path is built
+ *     from the stored backpointers afterwards.
+ *   - Figure "Pseudo-code of Expand Arcs": new_cost = token cost + acoustic_cost[ilabel]
+ *     + arc graph cost, for every token of the main queue and every out-arc.
+ *   - Section "Offline inference": beam = largest allowed score gap from the best
+ *     hypothesis; max-active = largest number of hypotheses, counted in graph states
+ *     (states entered over epsilon arcs included).
+ * The paper defers all remaining detail to earlier work.  The readings taken here:
+ *   R1  ilabel 0 = epsilon; ilabel k>=1 reads log-likelihood column k-1; olabel 0 = none.
+ *   R2  cost update is ((c + w) + (-loglike)) in fp32, in exactly that association.
+ *   R3  recombination keeps, per destination state, the lexicographic minimum of
+ *       (cost, global arc id); emitting arcs are numbered 0..Ae-1 in (source state,
+ *       given order), epsilon arcs Ae..Ae+Ax-1 likewise.
+ *   R4  a token is in the beam iff (c - best) <= beam, computed in fp32.
+ *   R5  max-active uses a fixed 256-bin histogram over [best, best+beam]:
+ *       bin(c) = clamp(floor((c-best) * (256/beam)), 0, 255); if more than max_active
+ *       tokens are in the beam, only bins below k_keep survive, k_keep being the first bin
+ *       at which the running count exceeds max_active, but never less than 1.
+ *   R6  pruning is applied to the recombined emitting result; the epsilon closure then runs
+ *       under the same, frozen, (best, k_keep) predicate and updates tokens in place.
+ *   R7  candidates whose cost is not finite are discarded when created.
+ *   R8  final choice: min over (cost + final_cost, state) if any token is final, else min
+ *       over (cost, state) with the reached_final flag clear.
+ *
+ * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
+ * Viterbi, greedy CTC collapse on the normal CTC topology, closed-form histogram cases,
+ * Dijkstra for the epsilon closure, traceback cost re-summation).  Absolute outputs are
+ * "parity unpinned" against the paper itself: it prints no decoder output to compare to.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+  int32_t num_states, start_state, num_classes;
+  int64_t num_arcs;
+  const int64_t *row_offsets;
+  const int32_t *next_state, *ilabel, *olabel;
+  const float *weight;
+  const float *final_cost; /* NULL: every state final with cost 0 */
+} oracle_graph;
+
+typedef struct {
+  int32_t S, start, V;
+  int64_t Ae, Ax;
+  int64_t *e_off, *x_off;                 /* [S+1] */
+  int32_t *e_next, *e_il, *e_ol;          /* [Ae] */
+  float *e_w;
+  int32_t *x_next, *x_ol;                 /* [Ax] */
+  float *x_w;
+  int64_t *e_orig, *x_orig;               /* index of the arc in the caller's arrays */
+  float *final_cost;                      /* [S] */
+} oracle_prepared;
+
+typedef struct {
+  float beam;
+  int32_t max_active;
+  int32_t max_words;
+  int32_t finalize;        /* 1: use final costs (R8); 0: best token regardless */
+  int32_t worklist_order;  /* 0 FIFO, 1 LIFO, 2 seeded random pick */
+  uint64_t order_seed;
+} oracle_opts;
+
+typedef struct {
+  int32_t nwords;
+  float cost;
+  int32_t flags;           /* bit0 reached_final, bit1 words truncated, bit2 dead */
+  int32_t path_len;        /* number of arcs on the best path */
+  int64_t counters[8];     /* see README of counters below */
+} oracle_result;
+/* counters: 0 sum |A_t| over expanded frames, 1 emitting arcs out of those sets,
+ * 2 epsilon arcs out of every closed set (initial one included), 3 tokens in the beam after
+ * recombination, 4 tokens stored (all closed sets), 5 frames where max-active pruned,
+ * 6 frames where bin 0 alone exceeded max_active, 7 recombined destinations before pruning */
+
+enum { FLAG_FINAL = 1, FLAG_TRUNC = 2, FLAG_DEAD = 4 };
+
+/* ------------------------------------------------------------------ graph preparation */
+void oracle_free(oracle_prepared *p) {
+  if (!p) return;
+  free(p->e_off); free(p->x_off); free(p->e_next); free(p->e_il); free(p->e_ol); free(p->e_w);
+  free(p->x_next); free(p->x_ol); free(p->x_w); free(p->e_orig); free(p->x_orig);
+  free(p->final_cost); free(p);
+}
+
+/* Returns NULL for a malformed graph (bad offsets, labels, destinations, non-finite weight,
+ * or a cycle of epsilon arcs). */
+oracle_prepared *oracle_prepare(const oracle_graph *g) {
+  int32_t S = g->num_states;
+  if (S <= 0 || g->start_state < 0 || g->start_state >= S || g->num_classes <= 0) return NULL;
+  if (g->row_offsets[0] != 0 || g->row_offsets[S] != g->num_arcs) return NULL;
+  for (int32_t s = 0; s < S; ++s)
+    if (g->row_offsets[s + 1] < g->row_offsets[s]) return NULL;
+  int64_t Ae = 0, Ax = 0;
+  for (int64_t a = 0; a < g->num_arcs; ++a) {
+    if (g->next_state[a] < 0 || g->next_state[a] >= S) return NULL;
+    if (g->ilabel[a] < 0 || g->ilabel[a] > g->num_classes) return NULL;
+    if (!isfinite(g->weight[a])) return NULL;
+    if (g->ilabel[a] == 0) ++Ax; else ++Ae;
+  }
+  oracle_prepared *p = (oracle_prepared *)calloc(1, sizeof(*p));
+  p->S = S; p->start = g->start_state; p->V = g->num_classes; p->Ae = Ae; p->Ax = Ax;
+  p->e_off = (int64_t *)malloc(sizeof(int64_t) * (S + 1));
+  p->x_off = (int64_t *)malloc(sizeof(int64_t) * (S + 1));
+  p->e_next = (int32_t *)malloc(sizeof(int32_t) * (Ae + 1));
+  p->e_il = (int32_t *)malloc(sizeof(int32_t) * (Ae + 1));
+  p->e_ol = (int32_t *)malloc(sizeof(int32_t) * (Ae + 1));
+  p->e_w = (float *)malloc(sizeof(float) * (Ae + 1));
+  p->e_orig = (int64_t *)malloc(sizeof(int64_t) * (Ae + 1));
+  p->x_next = (int32_t *)malloc(sizeof(int32_t) * (Ax + 1));
+  p->x_ol = (int32_t *)malloc(sizeof(int32_t) * (Ax + 1));
+  p->x_w = (float *)malloc(sizeof(float) * (Ax + 1));
+  p->x_orig = (int64_t *)malloc(sizeof(int64_t) * (Ax + 1));
+  p->final_cost = (float *)malloc(sizeof(float) * S);
+  int64_t ne = 0, nx = 0;
+  for (int32_t s = 0; s < S; ++s) {
+    p->e_off[s] = ne; p->x_off[s] = nx;
+    for (int64_t a = g->row_offsets[s]; a < g->row_offsets[s + 1]; ++a) {
+      if (g->ilabel[a] == 0) {
+        p->x_next[nx] = g->next_state[a]; p->x_ol[nx] = g->olabel[a];
+        p->x_w[nx] = g->weight[a]; p->x_orig[nx] = a; ++nx;
+      } else {
+        p->e_next[ne] = g->next_state[a]; p->e_il[ne] = g->ilabel[a];
+        p->e_ol[ne] = g->olabel[a]; p->e_w[ne] = g->weight[a]; p->e_orig[ne] = a; ++ne;
+      }
+    }
+    p->final_cost[s] = g->final_cost ? g->final_cost[s] : 0.0f;
+    if (isnan(p->final_cost[s])) { oracle_free(p); return NULL; }
+  }
+  p->e_off[S] = ne; p->x_off[S] = nx;
+  /* epsilon sub-graph must be acyclic: Kahn's algorithm on in-degrees */
+  int32_t *indeg = (int32_t *)calloc(S, sizeof(int32_t));
+  int32_t *stack = (int32_t *)malloc(sizeof(int32_t) * S);
+  for (int64_t a = 0; a < nx; ++a) indeg[p->x_next[a]]++;
+  int32_t top = 0, seen = 0;
+  for (int32_t s = 0; s < S; ++s) if (indeg[s] == 0) stack[top++] = s;
+  while (top > 0) {
+    int32_t s = stack[--top]; ++seen;
+    for (int64_t a = p->x_off[s]; a < p->x_off[s + 1]; ++a)
+      if (--indeg[p->x_next[a]] == 0) stack[top++] = p->x_next[a];
+  }
+  free(indeg); free(stack);
+  if (seen != S) { oracle_free(p); return NULL; }
+  return p;
+}
+
+int64_t oracle_num_emitting(const oracle_prepared *p) { return p->Ae; }
+int64_t oracle_num_epsilon(const oracle_prepared *p) { return p->Ax; }
+/* global arc id -> index of that arc in the arrays the caller passed to oracle_prepare */
+int64_t oracle_arc_original_index(const oracle_prepared *p, int64_t gid) {
+  if (gid < 0 || gid >= p->Ae + p->Ax) return -1;
+  return gid < p->Ae ? p->e_orig[gid] : p->x_orig[gid - p->Ae];
+}
+
+/* ------------------------------------------------------------------ pruning rule (R4, R5) */
+typedef struct { float best, beam, scale; int32_t k_keep; } cutoff_t;
+
+static int32_t bin_of(float c, const cutoff_t *k) {
+  if (k->beam == 0.0f) return 0;
+  float x = floorf((c - k->best) * k->scale);
+  if (!(x > 0.0f)) return 0;          /* negative gap, zero, or NaN from inf*0 */
+  if (x > 255.0f) return 255;
+  return (int32_t)x;
+}
+static int keep(float c, const cutoff_t *k) {
+  return ((c - k->best) <= k->beam) && (bin_of(c, k) < k->k_keep);
+}
+
+/* Cutoff of a set of recombined costs.  Outputs best and k_keep; returns the number of
+ * tokens in the beam.  hist_out (256 ints) may be NULL. */
+int32_t oracle_cutoff(const float *costs, int32_t n, float beam, int32_t max_active,
+                      float *best_out, int32_t *k_keep_out, int32_t *hist_out) {
+  cutoff_t k; k.beam = beam; k.scale = 256.0f / beam; k.k_keep = 256;
+  float best = INFINITY;
+  for (int32_t i = 0; i < n; ++i) if (costs[i] < best) best = costs[i];
+  k.best = best;
+  int32_t hist[256]; memset(hist, 0, sizeof(hist));
+  int32_t n_in = 0;
+  for (int32_t i = 0; i < n; ++i)
+    if ((costs[i] - best) <= beam) { hist[bin_of(costs[i], &k)]++; ++n_in; }
+  int32_t k_keep = 256;
+  if (n_in > max_active) {
+    int64_t run = 0;
+    for (int32_t j = 0; j < 256; ++j) { run += hist[j]; if (run > max_active) { k_keep = j; break; } }
+    if (k_keep < 1) k_keep = 1;
+  }
+  *best_out = best; *k_keep_out = k_keep;
+  if (hist_out) memcpy(hist_out, hist, sizeof(hist));
+  return n_in;
+}
+int32_t oracle_keep(float c, float best, float beam, int32_t k_keep) {
+  cutoff_t k; k.best = best; k.beam = beam; k.scale = 256.0f / beam; k.k_keep = k_keep;
+  return keep(c, &k);
+}
+
+/* ------------------------------------------------------------------ token sets */
+typedef struct { int32_t state; float cost; int32_t prev; int32_t arc; } token_t;
+typedef struct { token_t *t; int32_t n, cap; } tokvec;
+
+static void tv_push(tokvec *v, token_t x) {
+  if (v->n == v->cap) { v->cap = v->cap ? v->cap * 2 : 1024; v->t = (token_t *)realloc(v->t, sizeof(token_t) * v->cap); }
+  v->t[v->n++] = x;
+}
+static float canon(float x) { return x == 0.0f ? 0.0f : x; }   /* -0.0 -> +0.0 */
+
+static uint64_t mix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+static uint64_t rng_next(uint64_t *s) { *s += 0x9E3779B97F4A7C15ull; return mix64(*s); }
+
+/* Epsilon closure (R6) of the token set `v` in place, under the frozen predicate `k`.
+ * map[state] = index of the state's token in v, or -1.  The worklist is consumed from the
+ * front (order 0), from the back (1) or at a seeded random position (2); `head` only moves
+ * in order 0.  The result does not depend on the order. */
+static void eps_closure(const oracle_prepared *p, tokvec *v, int32_t *map, const cutoff_t *k,
+                        int32_t order, uint64_t seed) {
+  int32_t *wl = NULL; int32_t wn = 0, wcap = 0, head = 0;
+  for (int32_t i = 0; i < v->n; ++i) {
+    if (wn == wcap) { wcap = wcap ? wcap * 2 : 1024; wl = (int32_t *)realloc(wl, sizeof(int32_t) * wcap); }
+    wl[wn++] = i;
+  }
+  while (head < wn) {
+    int32_t j;
+    if (order == 0) j = wl[head++];
+    else if (order == 1) j = wl[--wn];
+    else { int32_t r = head + (int32_t)(rng_next(&seed) % (uint64_t)(wn - head)); j = wl[r]; wl[r] = wl[--wn]; }
+    int32_t s = v->t[j].state; float c = v->t[j].cost;
+    for (int64_t a = p->x_off[s]; a < p->x_off[s + 1]; ++a) {
+      float nc = canon(c + p->x_w[a]);
+      if (!(nc < INFINITY)) continue;
+      if (!keep(nc, k)) continue;
+      int32_t d = p->x_next[a]; int32_t gid = (int32_t)(p->Ae + a);
+      int32_t q = map[d];
+      if (q < 0) {
+        token_t t = { d, nc, j, gid }; map[d] = v->n; q = v->n; tv_push(v, t);
+      } else if (nc < v->t[q].cost || (nc == v->t[q].cost && gid < v->t[q].arc)) {
+        v->t[q].cost = nc; v->t[q].prev = j; v->t[q].arc = gid;
+      } else continue;
+      if (wn == wcap) { wcap = wcap ? wcap * 2 : 1024; wl = (int32_t *)realloc(wl, sizeof(int32_t) * wcap); }
+      wl[wn++] = q;
+    }
+  }
+  free(wl);
+}
+
+/* Closure of an arbitrary seed set, exported for tests of R6.
+ * in: n seed tokens (states distinct); out arrays must hold `cap` entries. Returns count or -1. */
+int32_t oracle_eps_closure(const oracle_prepared *p, const int32_t *states, const float *costs,
+                           int32_t n, float best, float beam, int32_t k_keep, int32_t order,
+                           uint64_t seed, int32_t *out_states, float *out_costs,
+                           int32_t *out_prev, int32_t *out_arc, int32_t cap) {
+  cutoff_t k; k.best = best; k.beam = beam; k.scale = 256.0f / beam; k.k_keep = k_keep;
+  int32_t *map = (int32_t *)malloc(sizeof(int32_t) * p->S);
+  for (int32_t s = 0; s < p->S; ++s) map[s] = -1;
+  tokvec v = { 0, 0, 0 };
+  for (int32_t i = 0; i < n; ++i) { token_t t = { states[i], costs[i], -1, -1 }; map[states[i]] = v.n; tv_push(&v, t); }
+  eps_closure(p, &v, map, &k, order, seed);
+  int32_t ret = v.n;
+  if (ret > cap) ret = -1;
+  else for (int32_t i = 0; i < v.n; ++i) {
+    out_states[i] = v.t[i].state; out_costs[i] = v.t[i].cost;
+    if (out_prev) out_prev[i] = v.t[i].prev;
+    if (out_arc) out_arc[i] = v.t[i].arc;
+  }
+  free(v.t); free(map);
+  return ret;
+}
+
+/* ------------------------------------------------------------------ the decoder */
+typedef struct { int32_t prev, arc; } bp_t;
+
+/*
+ * Decode one utterance.  loglikes: [len][V] row-major (row stride `row_stride` floats).
+ * words: [opts->max_words].  Optional outputs (NULL to skip):
+ *   digest_count/digest_sum [len+1]: per closed token set A_0..A_len, its size and the sum
+ *     over tokens of mix64(state<<32 | cost bits) modulo 2^64;
+ *   path_arcs [path_cap]: global arc ids of the best path in order (res->path_len of them);
+ *   dump_off [len+2], dump_states/dump_costs [dump_cap]: every closed token set.
+ * Returns 0, or -1 on bad arguments, -2 if a dump/path buffer is too small.
+ */
+int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t row_stride,
+                      int32_t len, const oracle_opts *o, int32_t *words, oracle_result *res,
+                      int32_t *digest_count, uint64_t *digest_sum,
+                      int32_t *path_arcs, int32_t path_cap,
+                      int64_t *dump_off, int32_t *dump_states, float *dump_costs, int64_t dump_cap) {
+  if (!p || !o || !res || len < 0 || o->max_words < 0 || !(o->beam >= 0.0f)) return -1;
+  memset(res, 0, sizeof(*res));
+  int32_t rc = 0;
+  int32_t *map = (int32_t *)malloc(sizeof(int32_t) * p->S);
+  for (int32_t s = 0; s < p->S; ++s) map[s] = -1;
+  bp_t **lat = (bp_t **)calloc((size_t)len + 1, sizeof(bp_t *));
+  int32_t *lat_n = (int32_t *)calloc((size_t)len + 1, sizeof(int32_t));
+  tokvec cur = { 0, 0, 0 }, nxt = { 0, 0, 0 };
+  int64_t dump_used = 0;
+  cutoff_t k; k.beam = o->beam; k.scale = 256.0f / o->beam;
+
+  /* initial set: start token, closed over epsilon arcs with best = 0 and no bin limit */
+  { token_t t = { p->start, 0.0f, -1, -1 }; map[p->start] = 0; tv_push(&cur, t); }
+  k.best = 0.0f; k.k_keep = 256;
+  eps_closure(p, &cur, map, &k, o->worklist_order, o->order_seed);
+
+  for (int32_t t = 0; t <= len; ++t) {
+    /* ---- store the closed set A_t: backpointers, digest, counters, dump */
+    lat_n[t] = cur.n;
+    lat[t] = (bp_t *)malloc(sizeof(bp_t) * (cur.n ? cur.n : 1));
+    uint64_t dsum = 0;
+    for (int32_t i = 0; i < cur.n; ++i) {
+      lat[t][i].prev = cur.t[i].prev; lat[t][i].arc = cur.t[i].arc;
+      uint32_t cb; memcpy(&cb, &cur.t[i].cost, 4);
+      dsum += mix64(((uint64_t)(uint32_t)cur.t[i].state << 32) | cb);
+      res->counters[2] += p->x_off[cur.t[i].state + 1] - p->x_off[cur.t[i].state];
+    }
+    res->counters[4] += cur.n;
+    if (digest_count) digest_count[t] = cur.n;
+    if (digest_sum) digest_sum[t] = dsum;
+    if (dump_off) {
+      dump_off[t] = dump_used;
+      if (dump_used + cur.n > dump_cap) { rc = -2; goto done; }
+      for (int32_t i = 0; i < cur.n; ++i) { dump_states[dump_used + i] = cur.t[i].state; dump_costs[dump_used + i] = cur.t[i].cost; }
+      dump_used += cur.n; dump_off[t + 1] = dump_used;
+    }
+    if (t == len) break;
+
+    /* ---- ExpandArcs over emitting arcs + recombination (R2, R3) */
+    const float *L = loglikes + (int64_t)t * row_stride;
+    for (int32_t i = 0; i < cur.n; ++i) map[cur.t[i].state] = -1;
+    nxt.n = 0;
+    res->counters[0] += cur.n;
+    for (int32_t i = 0; i < cur.n; ++i) {
+      int32_t s = cur.t[i].state; float c = cur.t[i].cost;
+      res->counters[1] += p->e_off[s + 1] - p->e_off[s];
+      for (int64_t a = p->e_off[s]; a < p->e_off[s + 1]; ++a) {
+        float ac = -L[p->e_il[a] - 1];
+        float nc = canon((c + p->e_w[a]) + ac);
+        if (!(nc < INFINITY)) continue;
+        int32_t d = p->e_next[a]; int32_t q = map[d];
+        if (q < 0) { token_t nt = { d, nc, i, (int32_t)a }; map[d] = nxt.n; tv_push(&nxt, nt); }
+        else if (nc < nxt.t[q].cost || (nc == nxt.t[q].cost && (int32_t)a < nxt.t[q].arc)) {
+          nxt.t[q].cost = nc; nxt.t[q].prev = i; nxt.t[q].arc = (int32_t)a;
+        }
+      }
+    }
+    res->counters[7] += nxt.n;
+    /* ---- Prune: beam from the best cost, max-active through the histogram (R4, R5) */
+    float best = INFINITY;
+    for (int32_t i = 0; i < nxt.n; ++i) if (nxt.t[i].cost < best) best = nxt.t[i].cost;
+    k.best = best; k.k_keep = 256;
+    int32_t hist[256]; memset(hist, 0, sizeof(hist));
+    int32_t n_in = 0;
+    for (int32_t i = 0; i < nxt.n; ++i)
+      if ((nxt.t[i].cost - best) <= k.beam) { hist[bin_of(nxt.t[i].cost, &k)]++; ++n_in; }
+    res->counters[3] += n_in;
+    if (n_in > o->max_active) {
+      int64_t run = 0; int32_t ks = 256;
+      for (int32_t j = 0; j < 256; ++j) { run += hist[j]; if (run > o->max_active) { ks = j; break; } }
+      if (ks < 1) { ks = 1; res->counters[6]++; }
+      k.k_keep = ks; res->counters[5]++;
+    }
+    int32_t m = 0;
+    for (int32_t i = 0; i < nxt.n; ++i) {
+      if (keep(nxt.t[i].cost, &k)) { nxt.t[m] = nxt.t[i]; map[nxt.t[m].state] = m; ++m; }
+      else map[nxt.t[i].state] = -1;
+    }
+    nxt.n = m;
+    /* ---- epsilon closure under the frozen predicate (R6) */
+    eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1);
+    { tokvec tmp = cur; cur = nxt; nxt = tmp; }
+  }
+
+  /* ---- final choice (R8) and traceback */
+  if (cur.n == 0) {
+    res->flags = FLAG_DEAD; res->cost = INFINITY; res->nwords = 0; res->path_len = 0;
+  } else {
+    int32_t bi = -1; float bf = INFINITY; int any_final = 0;
+    if (o->finalize) {
+      for (int32_t i = 0; i < cur.n; ++i) {
+        float f = cur.t[i].cost + p->final_cost[cur.t[i].state];
+        if (!(f < INFINITY)) continue;
+        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }
+        any_final = 1;
+      }
+    }
+    if (!any_final) {
+      for (int32_t i = 0; i < cur.n; ++i) {
+        float f = cur.t[i].cost;
+        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }
+      }
+    }
+    res->cost = bf; res->flags = any_final ? FLAG_FINAL : 0;
+    /* walk back: an epsilon arc's prev indexes the same frame, an emitting arc's the one before */
+    int32_t plen = 0, pcap = 1024; int32_t *rev = (int32_t *)malloc(sizeof(int32_t) * pcap);
+    int32_t f = len, i = bi;
+    while (lat[f][i].arc >= 0) {
+      int32_t a = lat[f][i].arc;
+      if (plen == pcap) { pcap *= 2; rev = (int32_t *)realloc(rev, sizeof(int32_t) * pcap); }
+      rev[plen++] = a;
+      i = lat[f][i].prev;
+      if ((int64_t)a < p->Ae) --f;
+    }
+    res->path_len = plen;
+    int32_t nw = 0;
+    for (int32_t q = plen - 1; q >= 0; --q) {
+      int32_t a = rev[q];
+      int32_t ol = (int64_t)a < p->Ae ? p->e_ol[a] : p->x_ol[a - p->Ae];
+      if (ol != 0) { if (nw < o->max_words) words[nw++] = ol; else res->flags |= FLAG_TRUNC; }
+    }
+    res->nwords = nw;
+    if (path_arcs) {
+      if (plen > path_cap) rc = -2;
+      else for (int32_t q = 0; q < plen; ++q) path_arcs[q] = rev[plen - 1 - q];
+    }
+    free(rev);
+  }
+done:
+  for (int32_t t = 0; t <= len; ++t) free(lat[t]);
+  free(lat); free(lat_n); free(cur.t); free(nxt.t); free(map);
+  return rc;
+}

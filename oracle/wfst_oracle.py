@@ -1,0 +1,193 @@
+"""ctypes loader for the C oracle in wfst_oracle.c (test infrastructure only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+ORACLE_LIB = os.path.join(_HERE, "liboracle.so")
+_SRC = os.path.join(_HERE, "wfst_oracle.c")
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the oracle with strict fp32 semantics (no contraction, no fast-math)."""
+    if force or not os.path.exists(ORACLE_LIB) or os.path.getmtime(ORACLE_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math",
+                               "-fPIC", "-shared", "-o", ORACLE_LIB, _SRC, "-lm"])
+    return ORACLE_LIB
+
+
+class _Graph(C.Structure):
+    _fields_ = [("num_states", C.c_int32), ("start_state", C.c_int32), ("num_classes", C.c_int32),
+                ("num_arcs", C.c_int64), ("row_offsets", C.c_void_p), ("next_state", C.c_void_p),
+                ("ilabel", C.c_void_p), ("olabel", C.c_void_p), ("weight", C.c_void_p),
+                ("final_cost", C.c_void_p)]
+
+
+class _Opts(C.Structure):
+    _fields_ = [("beam", C.c_float), ("max_active", C.c_int32), ("max_words", C.c_int32),
+                ("finalize", C.c_int32), ("worklist_order", C.c_int32), ("order_seed", C.c_uint64)]
+
+
+class _Result(C.Structure):
+    _fields_ = [("nwords", C.c_int32), ("cost", C.c_float), ("flags", C.c_int32),
+                ("path_len", C.c_int32), ("counters", C.c_int64 * 8)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build_oracle()
+        _lib = C.CDLL(ORACLE_LIB)
+        _lib.oracle_prepare.restype = C.c_void_p
+        _lib.oracle_prepare.argtypes = [C.POINTER(_Graph)]
+        _lib.oracle_free.argtypes = [C.c_void_p]
+        _lib.oracle_num_emitting.restype = C.c_int64
+        _lib.oracle_num_emitting.argtypes = [C.c_void_p]
+        _lib.oracle_num_epsilon.restype = C.c_int64
+        _lib.oracle_num_epsilon.argtypes = [C.c_void_p]
+        _lib.oracle_arc_original_index.restype = C.c_int64
+        _lib.oracle_arc_original_index.argtypes = [C.c_void_p, C.c_int64]
+        _lib.oracle_cutoff.restype = C.c_int32
+        _lib.oracle_cutoff.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32,
+                                       C.POINTER(C.c_float), C.POINTER(C.c_int32), C.c_void_p]
+        _lib.oracle_keep.restype = C.c_int32
+        _lib.oracle_keep.argtypes = [C.c_float, C.c_float, C.c_float, C.c_int32]
+        _lib.oracle_eps_closure.restype = C.c_int32
+        _lib.oracle_eps_closure.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                            C.c_float, C.c_float, C.c_int32, C.c_int32,
+                                            C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_int32]
+        _lib.oracle_decode.restype = C.c_int32
+        _lib.oracle_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                       C.POINTER(_Opts), C.c_void_p, C.POINTER(_Result),
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
+    return _lib
+
+
+def oracle_cutoff(costs, beam: float, max_active: int):
+    """(best, k_keep, n_in_beam, hist[256]) of a set of recombined token costs."""
+    lib = _load()
+    c = np.ascontiguousarray(costs, dtype=np.float32)
+    best, kk = C.c_float(), C.c_int32()
+    hist = np.zeros(256, dtype=np.int32)
+    n_in = lib.oracle_cutoff(c.ctypes.data, len(c), beam, max_active, C.byref(best),
+                             C.byref(kk), hist.ctypes.data)
+    return best.value, kk.value, n_in, hist
+
+
+def oracle_keep(c: float, best: float, beam: float, k_keep: int) -> bool:
+    return bool(_load().oracle_keep(c, best, beam, k_keep))
+
+
+@dataclass
+class OracleResult:
+    words: np.ndarray
+    cost: float
+    flags: int
+    counters: np.ndarray
+    path_arcs: np.ndarray | None = None          # global arc ids, in path order
+    digest_count: np.ndarray | None = None       # [len+1]
+    digest_sum: np.ndarray | None = None         # [len+1] uint64
+    frames: list | None = field(default=None)    # per closed set: (states, costs)
+
+    @property
+    def reached_final(self) -> bool:
+        return bool(self.flags & 1)
+
+    @property
+    def truncated(self) -> bool:
+        return bool(self.flags & 2)
+
+    @property
+    def dead(self) -> bool:
+        return bool(self.flags & 4)
+
+
+class Oracle:
+    """Prepared graph + decode calls.  `graph` is a workloads.Graph (or any object with the
+    same array attributes); the arrays are only read."""
+
+    def __init__(self, graph):
+        lib = _load()
+        self._keep = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
+                      np.ascontiguousarray(graph.next_state, dtype=np.int32),
+                      np.ascontiguousarray(graph.ilabel, dtype=np.int32),
+                      np.ascontiguousarray(graph.olabel, dtype=np.int32),
+                      np.ascontiguousarray(graph.weight, dtype=np.float32),
+                      None if graph.final_cost is None else
+                      np.ascontiguousarray(graph.final_cost, dtype=np.float32)]
+        g = _Graph(graph.num_states, graph.start_state, graph.num_classes,
+                   int(self._keep[0][-1]), *[None if a is None else a.ctypes.data for a in self._keep])
+        self.V = graph.num_classes
+        self._p = lib.oracle_prepare(C.byref(g))
+        if not self._p:
+            raise ValueError("oracle_prepare rejected the graph")
+        self.num_emitting = lib.oracle_num_emitting(self._p)
+        self.num_epsilon = lib.oracle_num_epsilon(self._p)
+
+    def __del__(self):
+        if getattr(self, "_p", None) and _lib is not None:
+            _lib.oracle_free(self._p)
+            self._p = None
+
+    def original_arc(self, gid: int) -> int:
+        return int(_load().oracle_arc_original_index(self._p, int(gid)))
+
+    def decode(self, loglikes, length=None, beam=17.0, max_active=10000, max_words=1024,
+               finalize=True, worklist_order=0, order_seed=0, want_path=False,
+               want_digests=False, want_frames=False, frames_cap=None) -> OracleResult:
+        lib = _load()
+        ll = np.asarray(loglikes, dtype=np.float32)
+        assert ll.ndim == 2 and ll.shape[1] == self.V and ll.strides[1] == 4
+        n = ll.shape[0] if length is None else int(length)
+        assert n <= ll.shape[0]
+        o = _Opts(beam, max_active, max_words, int(bool(finalize)), worklist_order, order_seed)
+        res = _Result()
+        words = np.zeros(max(1, max_words), dtype=np.int32)
+        dc = np.zeros(n + 1, dtype=np.int32) if want_digests else None
+        ds = np.zeros(n + 1, dtype=np.uint64) if want_digests else None
+        pcap = 8 * (n + 8) + 64
+        path = np.zeros(pcap, dtype=np.int32) if want_path else None
+        if want_frames:
+            cap = frames_cap or (n + 1) * max(4096, 4 * min(max_active, 1 << 20))
+            doff = np.zeros(n + 2, dtype=np.int64)
+            dst = np.zeros(cap, dtype=np.int32)
+            dco = np.zeros(cap, dtype=np.float32)
+        else:
+            cap, doff, dst, dco = 0, None, None, None
+        ptr = lambda a: None if a is None else a.ctypes.data
+        rc = lib.oracle_decode(self._p, ll.ctypes.data, ll.strides[0] // 4, n, C.byref(o),
+                               words.ctypes.data, C.byref(res), ptr(dc), ptr(ds), ptr(path), pcap,
+                               ptr(doff), ptr(dst), ptr(dco), cap)
+        if rc != 0:
+            raise RuntimeError(f"oracle_decode failed: {rc}")
+        frames = None
+        if want_frames:
+            frames = [(dst[doff[t]:doff[t + 1]].copy(), dco[doff[t]:doff[t + 1]].copy())
+                      for t in range(n + 1)]
+        return OracleResult(words[:res.nwords].copy(), float(res.cost), int(res.flags),
+                            np.array(list(res.counters), dtype=np.int64),
+                            None if path is None else path[:res.path_len].copy(), dc, ds, frames)
+
+    def eps_closure(self, states, costs, best, beam, k_keep=256, order=0, seed=0):
+        lib = _load()
+        st = np.ascontiguousarray(states, dtype=np.int32)
+        co = np.ascontiguousarray(costs, dtype=np.float32)
+        cap = max(1024, 64 * len(st) + 65536)
+        os_, oc = np.zeros(cap, np.int32), np.zeros(cap, np.float32)
+        op, oa = np.zeros(cap, np.int32), np.zeros(cap, np.int32)
+        n = lib.oracle_eps_closure(self._p, st.ctypes.data, co.ctypes.data, len(st), best, beam,
+                                   k_keep, order, seed, os_.ctypes.data, oc.ctypes.data,
+                                   op.ctypes.data, oa.ctypes.data, cap)
+        if n < 0:
+            raise RuntimeError("closure output overflow")
+        return os_[:n].copy(), oc[:n].copy(), op[:n].copy(), oa[:n].copy()
