@@ -1,0 +1,168 @@
+/*
+ * wfst_decoder.h -- C ABI of the MI355X (gfx950) WFST beam-search decoder for CTC models.
+ *
+ * The library implements the per-frame iteration of the paper's Section "Algorithm
+ * description" (ExpandArcs -> Prune -> store tokens and backpointers, then least-cost
+ * path from the stored backpointers), with the frame loop, the backpointer lattice and the
+ * traceback all resident on the GPU, plus the per-stream saved decoder state of Section
+ * "Streaming inference".  All arithmetic on costs is fp32.
+ *
+ * Conventions
+ *   - Every call returns a status (0 = WFST_OK, negative = error).  Nothing throws or aborts
+ *     across this boundary.  wfst_last_error() gives a library-owned message for the last
+ *     failing call on that decoder (or on creation when passed NULL).
+ *   - "host" / "device" on a pointer says where the memory lives.  The library never takes
+ *     ownership of caller memory; graph arrays are copied during create.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it; device outputs are valid once the stream has reached the end of the
+ *     call's work.  With opts.outputs_on_host != 0 the call copies results to host memory and
+ *     synchronises the stream before returning.
+ *   - Calls on one decoder must not overlap in time (one stream at a time per decoder).
+ *   - Labels: ilabel 0 = epsilon; ilabel k >= 1 reads log-likelihood column k-1 (so the CTC
+ *     blank, class 0, is ilabel 1); olabel 0 = no output (cf. the olabel != 0 test in the
+ *     figure "Pseudo-code of Expand Arcs").
+ */
+#ifndef WFST_DECODER_H_
+#define WFST_DECODER_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  WFST_OK = 0,
+  WFST_ERR_INVALID_ARG = -1,
+  WFST_ERR_BAD_GRAPH = -2,       /* malformed CSR, label out of range, non-finite weight, epsilon cycle */
+  WFST_ERR_OOM = -3,
+  WFST_ERR_LATTICE_OVERFLOW = -4,
+  WFST_ERR_BAD_CHANNEL = -5,
+  WFST_ERR_HIP = -6,
+  WFST_ERR_CAPACITY = -7         /* a per-channel work buffer (state map, queues) overflowed */
+};
+
+/* bits of the per-utterance `flags` output */
+enum {
+  WFST_FLAG_REACHED_FINAL = 1,   /* cost includes a final cost */
+  WFST_FLAG_TRUNCATED = 2,       /* more than max_words words; the first max_words are returned */
+  WFST_FLAG_DEAD = 4,            /* no token survived (no emitting arc could be taken) */
+  WFST_FLAG_LATTICE_OVERFLOW = 8,/* the channel ran out of lattice memory and stopped */
+  WFST_FLAG_CAPACITY = 16        /* a work buffer overflowed and the channel stopped */
+};
+
+typedef struct wfst_decoder wfst_decoder; /* opaque, owned by the library */
+
+/* Decoding graph (the TLG transducer shared by all utterances, Section "Word boosting",
+ * first paragraph) as CSR over states.  All arrays are HOST memory, read during create. */
+typedef struct {
+  int32_t num_states;
+  int32_t start_state;
+  int32_t num_classes;            /* V: width of a log-likelihood row */
+  int64_t num_arcs;
+  const int64_t *row_offsets;     /* [num_states+1]; arcs of s are [off[s], off[s+1]) */
+  const int32_t *next_state;      /* [num_arcs] */
+  const int32_t *ilabel;          /* [num_arcs], 0..V */
+  const int32_t *olabel;          /* [num_arcs], 0 = none */
+  const float *weight;            /* [num_arcs], finite */
+  const float *final_cost;        /* [num_states], +inf = not final; NULL = all final, cost 0 */
+} wfst_graph_csr;
+
+typedef struct {
+  int32_t max_channels;           /* channel slots (>= largest batch and streaming channel id+1) */
+  int32_t max_frames_per_channel; /* frames a channel can consume between two inits */
+  int32_t max_words;              /* row width of the `words` output */
+  int64_t lattice_bytes_per_channel; /* 0 = 8 B * max_frames * 1.5 * max_active_hint */
+  int32_t outputs_on_host;        /* 0: outputs are device pointers; 1: host pointers */
+  int32_t max_active_hint;        /* sizes the per-channel work buffers; 0 = 10000 */
+  int32_t state_map_capacity;     /* power of two, 0 = derived (32 * max_active_hint rounded up) */
+  int32_t record_digests;         /* 1: keep per-frame token-set digests (slower; for tests) */
+} wfst_opts;
+
+/*
+ * Build a decoder: validates the graph, splits emitting and epsilon arcs (global arc ids:
+ * emitting arcs 0..Ae-1 in (state, given order), epsilon arcs Ae.. likewise), uploads it and
+ * allocates the per-channel state.  Errors: INVALID_ARG, BAD_GRAPH, OOM, HIP.
+ */
+int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, wfst_decoder **out);
+int32_t wfst_decoder_destroy(wfst_decoder *dec);
+
+/*
+ * Offline batch decode (Section "Offline inference"): utterance b uses channel slot b, which
+ * is reset first.  For each frame t < lengths[b]:
+ *   ExpandArcs over emitting arcs, cost = (token cost + arc weight) + (-loglikes[b][t][ilabel-1])
+ *   (figure "Pseudo-code of Expand Arcs"); one token per destination state, lowest (cost,
+ *   arc id) wins; Prune: keep tokens with (cost - best) <= beam, and if more than max_active
+ *   remain, only those in the lowest bins of a 256-bin histogram over [best, best+beam];
+ *   epsilon closure under the same cutoff; backpointers appended to the channel's lattice.
+ * Then the best token (with final costs if any token is final) is traced back.
+ *   loglikes : DEVICE, float [B][T][V] contiguous, V == graph.num_classes; rows t >= lengths[b]
+ *              are never read.  Must stay valid until the stream has finished the call.
+ *   lengths  : HOST, int32 [B], 0 <= lengths[b] <= min(T, max_frames_per_channel)
+ *   words    : [B][max_words] int32, nwords [B] int32, cost [B] float, flags [B] int32
+ *              (device or host pointers according to opts.outputs_on_host)
+ * Identical in result to wfst_init_channel + wfst_advance_chunk (any chunking) +
+ * wfst_get_partial(finalize=1).  Errors: INVALID_ARG, BAD_CHANNEL (B > max_channels), HIP;
+ * with host outputs also LATTICE_OVERFLOW / CAPACITY if any utterance hit them (the flags
+ * say which).
+ */
+int32_t wfst_decode_batch(wfst_decoder *dec, const float *loglikes, const int32_t *lengths,
+                          int32_t B, int32_t T, int32_t V, float beam, int32_t max_active,
+                          void *stream, int32_t *words, int32_t *nwords, float *cost,
+                          int32_t *flags);
+
+/*
+ * Streaming (Section "Streaming inference": the decoder state kept per audio stream is its
+ * set of active tokens; here it lives permanently in the channel's slot in GPU memory, so
+ * no gather/scatter is needed between chunks).
+ *   wfst_init_channel : reset channel `ch` to the start token closed over epsilon arcs, and
+ *                       fix its beam / max_active.  `boost` is reserved (pass NULL).
+ *   wfst_advance_chunk: feed n channels (HOST int32 channels[n], distinct) nframes[i] <= C
+ *                       frames each from DEVICE loglikes [n][C][V]; nframes is HOST.
+ *   wfst_get_partial  : best hypothesis of channel `ch` so far.  finalize = 0 ignores final
+ *                       costs (partial result), 1 applies them.  words [cap], nwords [1],
+ *                       cost [1], flags [1] follow opts.outputs_on_host.
+ */
+int32_t wfst_init_channel(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
+                          const void *boost, void *stream);
+int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n,
+                           const float *loglikes, const int32_t *nframes, int32_t C, int32_t V,
+                           void *stream);
+int32_t wfst_get_partial(wfst_decoder *dec, int32_t ch, int32_t finalize, int32_t *words,
+                         int32_t cap, int32_t *nwords, float *cost, int32_t *flags, void *stream);
+
+/*
+ * Test and measurement hooks.  All outputs are HOST memory; each call synchronises the
+ * device first.
+ *   wfst_debug_frame_digests: needs opts.record_digests.  For the closed token sets A_0..A_f
+ *     of channel ch (f = frames consumed): count[t] = |A_t| and digest[t] = sum over tokens
+ *     of mix(state, cost bits) modulo 2^64.  Writes min(f+1, cap) entries, *n = f+1.
+ *   wfst_debug_get_tokens: current token set of channel ch (any order).
+ *   wfst_get_counters: sums over all channels since create or the last reset:
+ *     [0] tokens expanded, [1] emitting arcs out of them, [2] epsilon arcs out of every
+ *     closed token set, [3] tokens in the beam after recombination, [4] tokens stored,
+ *     [5] frames where max-active pruned, [6] frames where bin 0 alone exceeded max-active,
+ *     [7] frames decoded.   reset != 0 zeroes them after reading.
+ */
+int32_t wfst_debug_frame_digests(wfst_decoder *dec, int32_t ch, uint64_t *digest, int32_t *count,
+                                 int32_t cap, int32_t *n);
+int32_t wfst_debug_get_tokens(wfst_decoder *dec, int32_t ch, int32_t *states, float *costs,
+                              int32_t cap, int32_t *n);
+int32_t wfst_get_counters(wfst_decoder *dec, int64_t counters[8], int32_t reset);
+
+/* Device memory the decoder holds, in bytes (graph + channel state). */
+int64_t wfst_device_bytes(const wfst_decoder *dec);
+
+/*
+ * Time of the most recent decode/advance kernel in milliseconds, measured with HIP events
+ * recorded on the stream the kernel was launched on.  Synchronises on the stop event.
+ * Returns a negative value if no kernel has been launched.
+ */
+float wfst_last_kernel_ms(wfst_decoder *dec);
+
+const char *wfst_last_error(const wfst_decoder *dec);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WFST_DECODER_H_ */

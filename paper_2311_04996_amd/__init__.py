@@ -1,0 +1,7 @@
+"""MI355X-native WFST beam-search decoder for CTC models (HIP kernels behind a C ABI)."""
+from .binding import (Decoder, WfstError, load_library, EXPORTS, FLAG_REACHED_FINAL, FLAG_TRUNCATED,
+                      FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPACITY)
+from .build import build_library, LIB_PATH
+
+__all__ = ["Decoder", "WfstError", "load_library", "build_library", "LIB_PATH", "EXPORTS",
+           "FLAG_REACHED_FINAL", "FLAG_TRUNCATED", "FLAG_DEAD", "FLAG_LATTICE_OVERFLOW", "FLAG_CAPACITY"]

@@ -1,0 +1,213 @@
+"""Thin ctypes binding over libwfstdec.so (include/wfst_decoder.h).
+
+Argument marshalling only: every step of decoding runs in the HIP kernels.  PyTorch supplies
+device memory and streams.  There is no CPU fallback: if the library is missing or cannot
+be loaded, importing this module's entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from .build import LIB_PATH
+
+WFST_OK = 0
+ERRORS = {-1: "INVALID_ARG", -2: "BAD_GRAPH", -3: "OOM", -4: "LATTICE_OVERFLOW",
+          -5: "BAD_CHANNEL", -6: "HIP", -7: "CAPACITY"}
+FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPACITY = 1, 2, 4, 8, 16
+
+EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_init_channel",
+           "wfst_advance_chunk", "wfst_get_partial", "wfst_debug_frame_digests",
+           "wfst_debug_get_tokens", "wfst_get_counters", "wfst_device_bytes",
+           "wfst_last_kernel_ms", "wfst_last_error"]
+
+
+class WfstError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{ERRORS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class wfst_graph_csr(C.Structure):
+    _fields_ = [("num_states", C.c_int32), ("start_state", C.c_int32), ("num_classes", C.c_int32),
+                ("num_arcs", C.c_int64), ("row_offsets", C.c_void_p), ("next_state", C.c_void_p),
+                ("ilabel", C.c_void_p), ("olabel", C.c_void_p), ("weight", C.c_void_p),
+                ("final_cost", C.c_void_p)]
+
+
+class wfst_opts(C.Structure):
+    _fields_ = [("max_channels", C.c_int32), ("max_frames_per_channel", C.c_int32),
+                ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
+                ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
+                ("state_map_capacity", C.c_int32), ("record_digests", C.c_int32)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2311_04996_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no CPU fallback")
+    # PyTorch ships its own HIP runtime; import it first so that this library binds to the
+    # same libamdhip64 instance (two runtimes in one process do not share the device).
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    p, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    lib.wfst_decoder_create.argtypes = [C.POINTER(wfst_graph_csr), C.POINTER(wfst_opts), C.POINTER(p)]
+    lib.wfst_decoder_destroy.argtypes = [p]
+    lib.wfst_decode_batch.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p]
+    lib.wfst_init_channel.argtypes = [p, i32, f32, i32, p, p]
+    lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
+    lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
+    lib.wfst_debug_frame_digests.argtypes = [p, i32, p, p, i32, p]
+    lib.wfst_debug_get_tokens.argtypes = [p, i32, p, p, i32, p]
+    lib.wfst_get_counters.argtypes = [p, p, i32]
+    lib.wfst_device_bytes.argtypes = [p]
+    lib.wfst_device_bytes.restype = i64
+    lib.wfst_last_kernel_ms.argtypes = [p]
+    lib.wfst_last_kernel_ms.restype = f32
+    lib.wfst_last_error.argtypes = [p]
+    lib.wfst_last_error.restype = C.c_char_p
+    for name in EXPORTS[:9]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+class Decoder:
+    """Owns one wfst_decoder handle.  Method names mirror the C entry points."""
+
+    def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
+                 lattice_bytes_per_channel=0, outputs_on_host=False, state_map_capacity=0,
+                 record_digests=False):
+        self.lib = load_library()
+        arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
+                np.ascontiguousarray(graph.next_state, dtype=np.int32),
+                np.ascontiguousarray(graph.ilabel, dtype=np.int32),
+                np.ascontiguousarray(graph.olabel, dtype=np.int32),
+                np.ascontiguousarray(graph.weight, dtype=np.float32),
+                None if graph.final_cost is None else np.ascontiguousarray(graph.final_cost, dtype=np.float32)]
+        g = wfst_graph_csr(graph.num_states, graph.start_state, graph.num_classes, int(arrs[0][-1]),
+                           *[None if a is None else a.ctypes.data for a in arrs])
+        self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
+                              int(outputs_on_host), max_active_hint, state_map_capacity,
+                              int(record_digests))
+        self.V = graph.num_classes
+        self.max_words = max_words
+        self.outputs_on_host = bool(outputs_on_host)
+        h = C.c_void_p()
+        rc = self.lib.wfst_decoder_create(C.byref(g), C.byref(self.opts), C.byref(h))
+        if rc != WFST_OK:
+            raise WfstError(rc, self.lib.wfst_last_error(None).decode())
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.wfst_decoder_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != WFST_OK:
+            raise WfstError(rc, self.lib.wfst_last_error(self.h).decode())
+
+    # ---- offline
+    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None):
+        """loglikes: CUDA float32 tensor [B, T, V]; lengths: int32 host array [B].
+        Returns (words [B, max_words], nwords [B], cost [B], flags [B]); torch CUDA tensors, or
+        numpy arrays when the decoder was created with outputs_on_host."""
+        import torch
+        assert loglikes.is_cuda and loglikes.dtype == torch.float32 and loglikes.is_contiguous()
+        B, T, V = loglikes.shape
+        lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+        assert lengths.shape == (B,)
+        if out is None:
+            if self.outputs_on_host:
+                out = (np.zeros((B, self.max_words), np.int32), np.zeros(B, np.int32),
+                       np.zeros(B, np.float32), np.zeros(B, np.int32))
+            else:
+                dev = loglikes.device
+                out = (torch.zeros((B, self.max_words), dtype=torch.int32, device=dev),
+                       torch.zeros(B, dtype=torch.int32, device=dev),
+                       torch.zeros(B, dtype=torch.float32, device=dev),
+                       torch.zeros(B, dtype=torch.int32, device=dev))
+        ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
+        self._check(self.lib.wfst_decode_batch(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
+                                               beam, max_active, _stream_ptr(stream),
+                                               ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3])))
+        return out
+
+    # ---- streaming
+    def init_channel(self, ch, beam, max_active, stream=None):
+        self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, None, _stream_ptr(stream)))
+
+    def advance_chunk(self, channels, loglikes, nframes, stream=None):
+        """loglikes: CUDA float32 [n, C, V]; channels, nframes: host int32 [n]."""
+        import torch
+        assert loglikes.is_cuda and loglikes.dtype == torch.float32 and loglikes.is_contiguous()
+        n, Cn, V = loglikes.shape
+        channels = np.ascontiguousarray(channels, dtype=np.int32)
+        nframes = np.ascontiguousarray(nframes, dtype=np.int32)
+        assert channels.shape == (n,) and nframes.shape == (n,)
+        self._check(self.lib.wfst_advance_chunk(self.h, channels.ctypes.data, n, loglikes.data_ptr(),
+                                                nframes.ctypes.data, Cn, V, _stream_ptr(stream)))
+
+    def get_partial(self, ch, finalize=False, stream=None):
+        """Returns (words ndarray, cost, flags) of the channel's best hypothesis so far."""
+        import torch
+        cap = self.max_words
+        if self.outputs_on_host:
+            w, n = np.zeros(cap, np.int32), np.zeros(1, np.int32)
+            c, f = np.zeros(1, np.float32), np.zeros(1, np.int32)
+            self._check(self.lib.wfst_get_partial(self.h, ch, int(finalize), w.ctypes.data, cap, n.ctypes.data,
+                                                  c.ctypes.data, f.ctypes.data, _stream_ptr(stream)))
+            return w[:n[0]].copy(), float(c[0]), int(f[0])
+        w = torch.zeros(cap, dtype=torch.int32, device="cuda")
+        n = torch.zeros(1, dtype=torch.int32, device="cuda")
+        c = torch.zeros(1, dtype=torch.float32, device="cuda")
+        f = torch.zeros(1, dtype=torch.int32, device="cuda")
+        self._check(self.lib.wfst_get_partial(self.h, ch, int(finalize), w.data_ptr(), cap, n.data_ptr(),
+                                              c.data_ptr(), f.data_ptr(), _stream_ptr(stream)))
+        k = int(n.item())
+        return w[:k].cpu().numpy(), float(c.item()), int(f.item())
+
+    # ---- hooks
+    def debug_frame_digests(self, ch):
+        cap = self.opts.max_frames_per_channel + 1
+        dig, cnt, n = np.zeros(cap, np.uint64), np.zeros(cap, np.int32), C.c_int32()
+        self._check(self.lib.wfst_debug_frame_digests(self.h, ch, dig.ctypes.data, cnt.ctypes.data, cap, C.byref(n)))
+        return cnt[:n.value].copy(), dig[:n.value].copy()
+
+    def debug_get_tokens(self, ch, cap=1 << 20):
+        st, co, n = np.zeros(cap, np.int32), np.zeros(cap, np.float32), C.c_int32()
+        self._check(self.lib.wfst_debug_get_tokens(self.h, ch, st.ctypes.data, co.ctypes.data, cap, C.byref(n)))
+        return st[:n.value].copy(), co[:n.value].copy()
+
+    def get_counters(self, reset=False):
+        c = np.zeros(8, np.int64)
+        self._check(self.lib.wfst_get_counters(self.h, c.ctypes.data, int(reset)))
+        return c
+
+    def device_bytes(self):
+        return int(self.lib.wfst_device_bytes(self.h))
+
+    def last_kernel_ms(self):
+        return float(self.lib.wfst_last_kernel_ms(self.h))

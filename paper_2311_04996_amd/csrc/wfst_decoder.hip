@@ -1,0 +1,1079 @@
+// WFST token-passing beam search for CTC models on MI355X (gfx950, wave64).
+//
+// One persistent 1024-thread workgroup owns one channel (utterance / audio stream) and runs
+// the whole per-frame iteration of the paper's Section "Algorithm description" on the
+// device: ExpandArcs over emitting arcs -> recombination -> Prune (beam + max-active) ->
+// epsilon closure -> backpointer store, frame after frame, synchronising only with
+// workgroup barriers.  There is no per-frame kernel launch (the overhead the paper removes
+// with CUDA graphs) and no per-frame device-to-host copy (the lattice stays in HBM and the
+// traceback runs on the device).
+//
+// Data structures (per channel, all in HBM):
+//   token queue   2 x qcap records {state, cost, first emitting arc, emitting degree}
+//   state map     open-addressing hash  state -> {(orderable cost << 32 | arc id), token idx}
+//                 recombination is a 64-bit atomicMin on the packed word
+//   candidates    records {slot, source token, cost, arc id} of arcs that lowered a map entry
+//   winners       recombined in-beam tokens before the max-active cutoff is known
+//   lattice       {prev token, arc id} per stored token, frame after frame
+// LDS holds the negated log-likelihood row, the 256-bin cost histogram, the running best
+// cost and, per chunk of 2048 tokens, the prefix sums of their arc counts so that every
+// lane owns one arc of the flattened (token x arc) space regardless of state degree.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "wfst_decoder.h"
+
+namespace {
+
+constexpr int kBlock = 1024;
+constexpr int kWaves = kBlock / 64;
+constexpr int kTPT = 2;                       // tokens per thread per chunk
+constexpr int kChunk = kBlock * kTPT;
+constexpr int kMaxV = 2048;
+constexpr unsigned long long kValEmpty = ~0ull;
+constexpr int kKeyEmpty = -1;
+constexpr unsigned kOrdNone = 0xFFFFFFFFu;
+constexpr int kModeInit = 1, kModeFinal = 2;
+constexpr int kStLattice = WFST_FLAG_LATTICE_OVERFLOW, kStCapacity = WFST_FLAG_CAPACITY;
+
+struct HashEntry {            // 16 B: key CAS and value atomicMin touch one cache line
+  unsigned long long val;     // (orderable cost << 32) | global arc id ; kValEmpty when free
+  int key;                    // state id, kKeyEmpty when free
+  int tok;                    // index of the state's token in the next queue, -1 if none
+};
+
+struct ChanState {            // persists between calls (the per-stream decoder state)
+  int frame;                  // frames consumed since init
+  int n_tok;                  // size of the current closed token set
+  int cur;                    // which queue buffer holds it
+  int status;                 // sticky WFST_FLAG_* overflow bits
+  unsigned lat_used;          // lattice entries in use
+  int max_active;
+  float beam, scale;          // scale = 256 / beam, computed once on the host
+};
+
+struct DevGraph {
+  const int2 *off2;           // [S+1] {first emitting arc, first epsilon arc}
+  const int4 *earc;           // [Ae]  {next state, weight bits, ilabel, olabel}
+  const int2 *xarc;           // [Ax]  {next state, weight bits}
+  const int *olabel;          // [Ae+Ax] by global arc id (traceback only)
+  const float *final_cost;    // [S] or nullptr (all final, cost 0)
+  int S, start, Ae, Ax;
+};
+
+struct DevChannels {
+  ChanState *st;
+  HashEntry *hash;  unsigned hash_mask; int hash_cap;
+  int *claim;       int claim_cap, claim_limit;
+  int4 *cand;       int cand_cap;
+  int2 *win_sc, *win_pa; int *win_slot; int win_cap;
+  int4 *queue;      int qcap;
+  int *wl;
+  int2 *lattice;    unsigned lat_cap;
+  unsigned *frame_off; int max_frames;
+  unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
+  long long *counters;                         // [8]
+};
+
+struct LaunchArgs {
+  const int *chan, *nfr, *io;  // device [n]: channel id, frames to consume, row in loglikes/outputs
+  const float *ll; long long ll_stride; int V;
+  int mode, finalize;
+  float beam, scale; int max_active;
+  int *words, *nwords; float *cost; int *flags; int max_words;
+};
+
+struct Smem {
+  float ac[kMaxV];
+  unsigned pre[kChunk + 1];
+  int abase[kChunk];
+  float tcost[kChunk];
+  int ttok[kChunk];
+  unsigned hist[256];
+  unsigned wave_tot[kWaves];
+  unsigned best_ord;
+  int n_claim, n_cand, n_win, n_next, n_wl_next, status, k_keep, n_in;
+  unsigned long long red64, red64b;
+  long long xarcs;
+  int sel_idx;
+};
+
+// ------------------------------------------------------------------------------ helpers
+__device__ __forceinline__ unsigned f2ord(float f) {
+  unsigned u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ord2f(unsigned o) {
+  return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+__device__ __forceinline__ float canon(float x) { return x == 0.0f ? 0.0f : x; }
+__device__ __forceinline__ unsigned hash_state(int s) { return (unsigned)s * 0x9E3779B1u; }
+__device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+template <class T> __device__ __forceinline__ T ld_dev(const T *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <class T> __device__ __forceinline__ void st_dev(T *p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Index from an LDS counter for every lane with pred set; one LDS atomic per wave.
+__device__ __forceinline__ int wave_alloc(int *counter, bool pred) {
+  int idx = -1;
+  if (pred) {
+    unsigned long long m = __ballot(1);
+    int lane = threadIdx.x & 63;
+    int leader = __ffsll((long long)m) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(counter, __popcll(m));
+    base = __shfl(base, leader, 64);
+    idx = base + __popcll(m & ((1ull << lane) - 1ull));
+  }
+  return idx;
+}
+
+struct Cutoff {
+  float best, beam, scale; int k_keep;
+  __device__ __forceinline__ int bin(float c) const {
+    if (beam == 0.0f) return 0;
+    float x = floorf((c - best) * scale);
+    if (!(x > 0.0f)) return 0;
+    if (x > 255.0f) return 255;
+    return (int)x;
+  }
+  __device__ __forceinline__ bool in_beam(float c) const { return (c - best) <= beam; }
+  __device__ __forceinline__ bool keep(float c) const { return in_beam(c) && bin(c) < k_keep; }
+};
+
+struct Ctx {                  // block-uniform view of one channel
+  const DevGraph &g; const DevChannels &c; Smem &sm;
+  HashEntry *hash; int *claim; int4 *cand; int2 *win_sc, *win_pa; int *win_slot;
+  int4 *q[2]; int *wl[2]; int2 *lat; unsigned *frame_off;
+  unsigned long long *dig_sum; int *dig_cnt;
+  ChanState s;
+  // per-launch counters (thread 0 accumulates the uniform ones)
+  long long k_tok = 0, k_earc = 0, k_in = 0, k_stored = 0, k_maxact = 0, k_bin0 = 0, k_frames = 0;
+};
+
+// Block-wide exclusive scan of two values per thread (thread t owns items 2t, 2t+1).
+__device__ __forceinline__ unsigned block_scan2(Smem &sm, unsigned d0, unsigned d1,
+                                                unsigned &ex0, unsigned &ex1) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned s = d0 + d1, inc = s;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    unsigned t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) sm.wave_tot[wave] = inc;
+  __syncthreads();
+  unsigned base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    unsigned t = sm.wave_tot[w];
+    if (w < wave) base += t;
+    total += t;
+  }
+  ex0 = base + inc - s;
+  ex1 = ex0 + d0;
+  return total;
+}
+
+// Which of the chunk's tokens owns flattened arc f: last j with pre[j] <= f.
+__device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
+  int lo = 0, hi = kChunk;
+#pragma unroll
+  for (int it = 0; it < 11; ++it) {
+    int mid = (lo + hi) >> 1;
+    if (sm.pre[mid] <= f) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Recombination: lower the destination state's map entry to `key` (64-bit atomicMin),
+// claiming a slot on first touch.  Returns true if this candidate lowered the entry.
+__device__ __forceinline__ bool map_upsert(Ctx &x, int d, unsigned long long key, int &slot) {
+  HashEntry *tab = x.hash;
+  const unsigned mask = x.c.hash_mask;
+  unsigned h = (hash_state(d) >> 7) & mask;
+  for (;;) {
+    int k = ld_dev(&tab[h].key);
+    if (k == d) break;
+    if (k == kKeyEmpty) {
+      if (*(volatile int *)&x.sm.n_claim >= x.c.claim_limit) {   // table too full: stop the channel
+        atomicOr(&x.sm.status, kStCapacity);
+        return false;
+      }
+      int old = atomicCAS(&tab[h].key, kKeyEmpty, d);
+      if (old == kKeyEmpty) {
+        int ci = atomicAdd(&x.sm.n_claim, 1);
+        if (ci < x.c.claim_cap) x.claim[ci] = (int)h;
+        break;
+      }
+      if (old == d) break;
+    }
+    h = (h + 1) & mask;
+  }
+  slot = (int)h;
+  unsigned long long old = atomicMin(&tab[h].val, key);
+  return old > key;
+}
+
+// ------------------------------------------------------------------ ExpandArcs (emitting)
+// For every token of the current set and every emitting arc:
+//   cost = (token cost + arc weight) + (-loglike[ilabel-1])      (Expand Arcs pseudo-code)
+// Candidates that cannot be in the beam relative to the running best are dropped early;
+// the running best is never lower than the final one, so this never drops a survivor.
+__device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
+  Smem &sm = x.sm;
+  const int tid = threadIdx.x;
+  const float beam = x.s.beam;
+  for (int cb = 0; cb < n_tok; cb += kChunk) {
+    const int i0 = cb + kTPT * tid;
+    int4 t0 = make_int4(0, 0, 0, 0), t1 = t0;
+    if (i0 < n_tok) t0 = Q[i0];
+    if (i0 + 1 < n_tok) t1 = Q[i0 + 1];
+    unsigned ex0, ex1;
+    const unsigned M = block_scan2(sm, (unsigned)t0.w, (unsigned)t1.w, ex0, ex1);
+    sm.pre[kTPT * tid] = ex0;          sm.pre[kTPT * tid + 1] = ex1;
+    sm.abase[kTPT * tid] = t0.z - (int)ex0; sm.abase[kTPT * tid + 1] = t1.z - (int)ex1;
+    sm.tcost[kTPT * tid] = __int_as_float(t0.y); sm.tcost[kTPT * tid + 1] = __int_as_float(t1.y);
+    if (tid == kBlock - 1) sm.pre[kChunk] = M;
+    __syncthreads();
+    if (tid == 0) x.k_earc += M;
+    for (unsigned f0 = 0; f0 < M; f0 += kBlock) {
+      const unsigned f = f0 + tid;
+      const bool act = f < M;
+      bool ok = false; float nc = 0.0f; int dst = 0, arc = 0, j = 0;
+      if (act) {
+        j = owner_of(sm, f);
+        arc = sm.abase[j] + (int)f;
+        const int4 a = x.g.earc[arc];
+        dst = a.x;
+        nc = canon((sm.tcost[j] + __int_as_float(a.y)) + sm.ac[a.z - 1]);
+        const unsigned bo = *(volatile unsigned *)&sm.best_ord;
+        const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
+        ok = (nc < INFINITY) && !((nc - rb) > beam);
+      }
+      // running best: wave minimum first, one LDS atomic per wave
+      unsigned o = ok ? f2ord(nc) : kOrdNone;
+#pragma unroll
+      for (int sft = 32; sft > 0; sft >>= 1) o = min(o, (unsigned)__shfl_xor((int)o, sft, 64));
+      if ((tid & 63) == 0 && o != kOrdNone) atomicMin(&sm.best_ord, o);
+      bool improved = false; int slot = 0;
+      if (ok) improved = map_upsert(x, dst, ((unsigned long long)f2ord(nc) << 32) | (unsigned)arc, slot);
+      const int ci = wave_alloc(&sm.n_cand, improved);
+      if (improved) {
+        if (ci < x.c.cand_cap) x.cand[ci] = make_int4(slot, cb + j, __float_as_int(nc), arc);
+        else atomicOr(&sm.status, kStCapacity);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------ Prune
+// Winners of the recombination (candidate whose key is still the map entry) that are inside
+// the beam are histogrammed into 256 bins over [best, best+beam] and parked; the max-active
+// cutoff k_keep is the first bin where the running count exceeds max_active (at least 1).
+__device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &cut) {
+  Smem &sm = x.sm;
+  const int tid = threadIdx.x;
+  const int n_cand = min(sm.n_cand, x.c.cand_cap);
+  const unsigned bo = sm.best_ord;
+  cut.best = bo == kOrdNone ? INFINITY : ord2f(bo);
+  cut.beam = x.s.beam; cut.scale = x.s.scale; cut.k_keep = 256;
+  for (int i0 = 0; i0 < n_cand; i0 += kBlock) {
+    const int i = i0 + tid;
+    bool win = false; int4 cd = make_int4(0, 0, 0, 0); int state = 0;
+    if (i < n_cand) {
+      cd = x.cand[i];
+      const float c = __int_as_float(cd.z);
+      const unsigned long long key = ((unsigned long long)f2ord(c) << 32) | (unsigned)cd.w;
+      if (ld_dev(&x.hash[cd.x].val) == key && cut.in_beam(c)) {
+        win = true;
+        state = ld_dev(&x.hash[cd.x].key);
+        atomicAdd(&sm.hist[cut.bin(c)], 1u);
+      }
+    }
+    const int wi = wave_alloc(&sm.n_win, win);
+    if (win) {
+      if (wi < x.c.win_cap) {
+        x.win_sc[wi] = make_int2(state, cd.z);
+        x.win_pa[wi] = make_int2(cd.y, cd.w);
+        x.win_slot[wi] = cd.x;
+      } else atomicOr(&sm.status, kStCapacity);
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {                       // wave 0: scan the histogram, 4 bins per lane
+    unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
+    unsigned s = h0 + h1 + h2 + h3, inc = s;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { unsigned t = __shfl_up(inc, o, 64); if (tid >= o) inc += t; }
+    const unsigned n_in = __shfl(inc, 63, 64);
+    const unsigned ma = (unsigned)x.s.max_active;
+    int kk = 256;
+    if (n_in > ma) {
+      unsigned run = inc - s;
+      int first = 256;
+      run += h0; if (run > ma && first == 256) first = 4 * tid;
+      run += h1; if (run > ma && first == 256) first = 4 * tid + 1;
+      run += h2; if (run > ma && first == 256) first = 4 * tid + 2;
+      run += h3; if (run > ma && first == 256) first = 4 * tid + 3;
+#pragma unroll
+      for (int sft = 32; sft > 0; sft >>= 1) first = min(first, __shfl_xor(first, sft, 64));
+      kk = first;
+      if (tid == 0) { x.k_maxact++; if (kk < 1) x.k_bin0++; }
+      if (kk < 1) kk = 1;
+    }
+    if (tid == 0) { sm.k_keep = kk; sm.n_in = (int)n_in; x.k_in += n_in; }
+  }
+  __syncthreads();
+  cut.k_keep = sm.k_keep;
+  const int n_win = min(sm.n_win, x.c.win_cap);
+  for (int i0 = 0; i0 < n_win; i0 += kBlock) {
+    const int i = i0 + tid;
+    bool kp = false; int2 sc = make_int2(0, 0);
+    if (i < n_win) { sc = x.win_sc[i]; kp = cut.bin(__int_as_float(sc.y)) < cut.k_keep; }
+    const int ti = wave_alloc(&sm.n_next, kp);
+    if (kp) {
+      if (ti >= x.c.qcap) atomicOr(&sm.status, kStCapacity);
+      else if (lat_base + (unsigned)ti >= x.c.lat_cap) atomicOr(&sm.status, kStLattice);
+      else {
+        NQ[ti] = make_int4(sc.x, sc.y, 0, 0);
+        x.lat[lat_base + ti] = x.win_pa[i];
+        st_dev(&x.hash[x.win_slot[i]].tok, ti);
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------ epsilon closure
+// Least fixpoint under the frozen predicate `cut`: tokens improved (or created) in one round
+// are re-expanded in the next.  The first expansion of a token also fetches its arc ranges
+// (one {emitting, epsilon} offset pair per state) and caches the emitting range in the queue
+// record for the next frame's ExpandArcs.
+__device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const Cutoff &cut) {
+  Smem &sm = x.sm;
+  const int tid = threadIdx.x;
+  int n_wl = nP, sel = 0;
+  bool implicit = true;
+  for (int round = 0; n_wl > 0; ++round) {
+    if (round > (1 << 20)) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
+    const int *WL = x.wl[sel]; int *WLN = x.wl[sel ^ 1];
+    long long my_x = 0;
+    for (int cb = 0; cb < n_wl; cb += kChunk) {
+      unsigned deg[kTPT]; int base[kTPT], tk[kTPT]; float cs[kTPT];
+#pragma unroll
+      for (int k = 0; k < kTPT; ++k) {
+        const int i = cb + kTPT * tid + k;
+        deg[k] = 0; base[k] = 0; tk[k] = 0; cs[k] = 0.0f;
+        if (i < n_wl) {
+          const int e = implicit ? (i | 0x80000000) : WL[i];
+          const int ti = e & 0x7fffffff;
+          const int2 sc = *reinterpret_cast<const int2 *>(&NQ[ti]);
+          const int2 o0 = x.g.off2[sc.x], o1 = x.g.off2[sc.x + 1];
+          if (e < 0) {                       // first expansion of this token
+            reinterpret_cast<int2 *>(&NQ[ti])[1] = make_int2(o0.x, o1.x - o0.x);
+            my_x += o1.y - o0.y;
+          }
+          deg[k] = (unsigned)(o1.y - o0.y); base[k] = o0.y; tk[k] = ti; cs[k] = __int_as_float(sc.y);
+        }
+      }
+      unsigned ex0, ex1;
+      const unsigned M = block_scan2(sm, deg[0], deg[1], ex0, ex1);
+      sm.pre[kTPT * tid] = ex0;              sm.pre[kTPT * tid + 1] = ex1;
+      sm.abase[kTPT * tid] = base[0] - (int)ex0; sm.abase[kTPT * tid + 1] = base[1] - (int)ex1;
+      sm.tcost[kTPT * tid] = cs[0];          sm.tcost[kTPT * tid + 1] = cs[1];
+      sm.ttok[kTPT * tid] = tk[0];           sm.ttok[kTPT * tid + 1] = tk[1];
+      if (tid == kBlock - 1) sm.pre[kChunk] = M;
+      __syncthreads();
+      for (unsigned f0 = 0; f0 < M; f0 += kBlock) {
+        const unsigned f = f0 + tid;
+        bool ok = false; float nc = 0.0f; int dst = 0, arc = 0, j = 0;
+        if (f < M) {
+          j = owner_of(sm, f);
+          arc = sm.abase[j] + (int)f;
+          const int2 a = x.g.xarc[arc];
+          dst = a.x;
+          nc = canon(sm.tcost[j] + __int_as_float(a.y));
+          ok = (nc < INFINITY) && cut.keep(nc);
+        }
+        bool improved = false; int slot = 0;
+        const int gid = x.g.Ae + arc;
+        if (ok) improved = map_upsert(x, dst, ((unsigned long long)f2ord(nc) << 32) | (unsigned)gid, slot);
+        const int ci = wave_alloc(&sm.n_cand, improved);
+        if (improved) {
+          if (ci < x.c.cand_cap) x.cand[ci] = make_int4(slot, sm.ttok[j], __float_as_int(nc), gid);
+          else atomicOr(&sm.status, kStCapacity);
+        }
+      }
+      __syncthreads();
+    }
+    if (my_x) atomicAdd((unsigned long long *)&sm.xarcs, (unsigned long long)my_x);
+    // winners of this round update their token in place (or create it) and are re-queued
+    const int n_cand = min(sm.n_cand, x.c.cand_cap);
+    for (int i0 = 0; i0 < n_cand; i0 += kBlock) {
+      const int i = i0 + tid;
+      bool win = false, fresh = false; int4 cd = make_int4(0, 0, 0, 0); int tok = -1;
+      if (i < n_cand) {
+        cd = x.cand[i];
+        const unsigned long long key = ((unsigned long long)f2ord(__int_as_float(cd.z)) << 32) | (unsigned)cd.w;
+        if (ld_dev(&x.hash[cd.x].val) == key) {
+          win = true;
+          tok = ld_dev(&x.hash[cd.x].tok);
+          fresh = tok < 0;
+        }
+      }
+      const int ni = wave_alloc(&sm.n_next, fresh);
+      if (fresh) tok = ni;
+      bool good = win;
+      if (win) {
+        if (tok >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
+        else if (lat_base + (unsigned)tok >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+      }
+      if (good) {
+        if (fresh) st_dev(&x.hash[cd.x].tok, tok);
+        const int state = ld_dev(&x.hash[cd.x].key);
+        *reinterpret_cast<int2 *>(&NQ[tok]) = make_int2(state, cd.z);
+        x.lat[lat_base + tok] = make_int2(cd.y, cd.w);
+      }
+      const int wi = wave_alloc(&sm.n_wl_next, good);
+      if (good) WLN[wi] = tok | (fresh ? 0x80000000 : 0);
+    }
+    __syncthreads();
+    n_wl = min(sm.n_wl_next, x.c.qcap);
+    const bool stop = sm.status != 0;
+    __syncthreads();
+    if (tid == 0) { sm.n_wl_next = 0; sm.n_cand = 0; }
+    __syncthreads();
+    if (stop) break;
+    sel ^= 1; implicit = false;
+  }
+}
+
+// Close the token set in NQ, publish it as A_f (f = x.s.frame), clear the state map.
+// Returns true (uniformly) if an overflow was flagged and the channel has to stop.
+__device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
+  Smem &sm = x.sm;
+  const int tid = threadIdx.x;
+  const int n = min(sm.n_next, x.c.qcap);
+  const int f = x.s.frame;
+  if (x.dig_sum) {
+    unsigned long long s = 0;
+    for (int i = tid; i < n; i += kBlock) {
+      const int2 sc = *reinterpret_cast<const int2 *>(&NQ[i]);
+      s += mix64(((unsigned long long)(unsigned)sc.x << 32) | (unsigned)sc.y);
+    }
+    if (s) atomicAdd(&sm.red64, s);
+  }
+  const int n_claim = min(sm.n_claim, x.c.claim_cap);
+  for (int i = tid; i < n_claim; i += kBlock) {
+    HashEntry *e = &x.hash[x.claim[i]];
+    st_dev(&e->val, kValEmpty);
+    st_dev(reinterpret_cast<unsigned long long *>(&e->key), ~0ull);   // key = -1, tok = -1
+  }
+  __syncthreads();
+  if (tid == 0) {
+    x.frame_off[f] = lat_base;
+    x.frame_off[f + 1] = lat_base + (unsigned)n;
+    if (x.dig_sum) { x.dig_sum[f] = sm.red64; x.dig_cnt[f] = n; }
+    x.k_stored += n;
+    sm.red64 = 0; sm.n_claim = 0; sm.n_cand = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.best_ord = kOrdNone;
+  }
+  if (tid < 256) sm.hist[tid] = 0;
+  x.s.lat_used = lat_base + (unsigned)n;
+  x.s.n_tok = n;
+  x.s.cur ^= 1;
+  const bool stop = sm.status != 0;     // nobody writes status between these two barriers
+  __syncthreads();
+  return stop;
+}
+
+// ------------------------------------------------------------------ final choice + traceback
+// Best token by (cost + final cost, state) if any token is final, else by (cost, state);
+// then the backpointers are followed to the start token and the non-zero output labels of
+// the arcs are written in path order.
+__device__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
+  Smem &sm = x.sm;
+  const int tid = threadIdx.x;
+  const int n = x.s.n_tok;
+  const int4 *Q = x.q[x.s.cur];
+  int *words = a.words + (long long)io * a.max_words;
+  int flags = x.s.status;
+  if (n == 0) {
+    if (tid == 0) { a.nwords[io] = 0; a.cost[io] = INFINITY; a.flags[io] = flags | WFST_FLAG_DEAD; }
+    return;
+  }
+  if (tid == 0) { sm.red64 = ~0ull; sm.red64b = ~0ull; sm.sel_idx = -1; }
+  __syncthreads();
+  unsigned long long mf = ~0ull, mr = ~0ull;
+  for (int i = tid; i < n; i += kBlock) {
+    const int4 t = Q[i];
+    const float c = __int_as_float(t.y);
+    mr = min(mr, ((unsigned long long)f2ord(c) << 32) | (unsigned)t.x);
+    if (a.finalize) {
+      const float fc = x.g.final_cost ? x.g.final_cost[t.x] : 0.0f;
+      const float f = c + fc;
+      if (f < INFINITY) mf = min(mf, ((unsigned long long)f2ord(f) << 32) | (unsigned)t.x);
+    }
+  }
+  if (mf != ~0ull) atomicMin(&sm.red64, mf);
+  atomicMin(&sm.red64b, mr);
+  __syncthreads();
+  const bool any_final = sm.red64 != ~0ull;
+  const unsigned long long best = any_final ? sm.red64 : sm.red64b;
+  const int best_state = (int)(unsigned)(best & 0xffffffffull);
+  for (int i = tid; i < n; i += kBlock)
+    if (Q[i].x == best_state) sm.sel_idx = i;
+  __syncthreads();
+  if (tid == 0) {
+    const int Ae = x.g.Ae;
+    int nw = 0;
+    bool broken = false;
+    for (int pass = 0; pass < 2; ++pass) {
+      int f = x.s.frame, i = sm.sel_idx, k = 0;
+      for (unsigned step = 0;; ++step) {
+        // every chain ends at the start token; the bounds only guard against a damaged lattice
+        if (f < 0 || i < 0 || step > x.s.lat_used) { broken = true; break; }
+        const unsigned li = x.frame_off[f] + (unsigned)i;
+        if (li >= x.s.lat_used) { broken = true; break; }
+        const int2 bp = x.lat[li];
+        if (bp.y < 0) break;
+        const int ol = x.g.olabel[bp.y];
+        if (ol != 0) {
+          if (pass == 1) { const int pos = nw - 1 - k; if (pos < a.max_words) words[pos] = ol; }
+          ++k;
+        }
+        i = bp.x;
+        if (bp.y < Ae) --f;
+      }
+      nw = k;
+    }
+    if (any_final) flags |= WFST_FLAG_REACHED_FINAL;
+    if (nw > a.max_words) flags |= WFST_FLAG_TRUNCATED;
+    if (broken) { flags |= WFST_FLAG_CAPACITY; nw = 0; }
+    a.nwords[io] = min(nw, a.max_words);
+    a.cost[io] = ord2f((unsigned)(best >> 32));
+    a.flags[io] = flags;
+    sm.red64 = 0;
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------ the channel kernel
+__global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
+  __shared__ Smem sm;
+  const int tid = threadIdx.x;
+  const int ch = a.chan[blockIdx.x], nfr = a.nfr[blockIdx.x], io = a.io[blockIdx.x];
+  Ctx x{g, c, sm};
+  x.hash = c.hash + (size_t)ch * c.hash_cap;
+  x.claim = c.claim + (size_t)ch * c.claim_cap;
+  x.cand = c.cand + (size_t)ch * c.cand_cap;
+  x.win_sc = c.win_sc + (size_t)ch * c.win_cap;
+  x.win_pa = c.win_pa + (size_t)ch * c.win_cap;
+  x.win_slot = c.win_slot + (size_t)ch * c.win_cap;
+  x.q[0] = c.queue + (size_t)ch * 2 * c.qcap; x.q[1] = x.q[0] + c.qcap;
+  x.wl[0] = c.wl + (size_t)ch * 2 * c.qcap;   x.wl[1] = x.wl[0] + c.qcap;
+  x.lat = c.lattice + (size_t)ch * c.lat_cap;
+  x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
+  x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
+  x.dig_cnt = c.dig_cnt ? c.dig_cnt + (size_t)ch * (c.max_frames + 1) : nullptr;
+  x.s = c.st[ch];
+
+  if (tid == 0) {
+    sm.best_ord = kOrdNone; sm.n_claim = 0; sm.n_cand = 0; sm.n_win = 0; sm.n_next = 0;
+    sm.n_wl_next = 0; sm.status = 0; sm.red64 = 0; sm.xarcs = 0; sm.k_keep = 256; sm.n_in = 0;
+  }
+  if (tid < 256) sm.hist[tid] = 0;
+  __syncthreads();
+
+  bool stop = false;
+  if (a.mode & kModeInit) {
+    // start token, closed over epsilon arcs with best = 0 and no bin limit
+    x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
+    x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active;
+    int4 *NQ = x.q[1];
+    if (tid == 0) {
+      int slot = 0;
+      map_upsert(x, g.start, ((unsigned long long)f2ord(0.0f) << 32) | 0xFFFFFFFFull, slot);
+      st_dev(&x.hash[slot].tok, 0);
+      NQ[0] = make_int4(g.start, __float_as_int(0.0f), 0, 0);
+      x.lat[0] = make_int2(-1, -1);
+      sm.n_next = 1;
+    }
+    __syncthreads();
+    Cutoff cut{0.0f, x.s.beam, x.s.scale, 256};
+    eps_closure(x, NQ, 0u, 1, cut);
+    stop = finish_set(x, NQ, 0u);
+  }
+
+  const float *ll = a.ll + (long long)io * a.ll_stride;
+  for (int t = 0; t < nfr; ++t) {
+    if (stop || x.s.status) break;
+    if (x.s.frame >= c.max_frames) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
+    const float *row = ll + (long long)t * a.V;
+    for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -row[v];
+    __syncthreads();
+    const int4 *Q = x.q[x.s.cur];
+    int4 *NQ = x.q[x.s.cur ^ 1];
+    const unsigned lat_base = x.s.lat_used;
+    if (tid == 0) { x.k_tok += x.s.n_tok; x.k_frames++; }
+    emit_expand(x, Q, x.s.n_tok);
+    Cutoff cut;
+    prune_and_compact(x, NQ, lat_base, cut);
+    if (tid == 0) { sm.n_cand = 0; }
+    __syncthreads();
+    const int nP = min(sm.n_next, c.qcap);
+    eps_closure(x, NQ, lat_base, nP, cut);
+    x.s.frame++;
+    stop = finish_set(x, NQ, lat_base);
+  }
+  __syncthreads();
+  if (sm.status) {            // overflow: the channel stops with an empty token set
+    x.s.status |= sm.status;
+    x.s.n_tok = 0;
+    // leave the state map clean for the next init
+    const int n_claim = min(sm.n_claim, c.claim_cap);
+    for (int i = tid; i < n_claim; i += kBlock) {
+      HashEntry *e = &x.hash[x.claim[i]];
+      st_dev(&e->val, kValEmpty);
+      st_dev(reinterpret_cast<unsigned long long *>(&e->key), ~0ull);
+    }
+    __syncthreads();
+  }
+  if (a.mode & kModeFinal) select_and_trace(x, a, io);
+  if (tid == 0) {
+    c.st[ch] = x.s;
+    atomicAdd((unsigned long long *)&c.counters[0], (unsigned long long)x.k_tok);
+    atomicAdd((unsigned long long *)&c.counters[1], (unsigned long long)x.k_earc);
+    atomicAdd((unsigned long long *)&c.counters[2], (unsigned long long)sm.xarcs);
+    atomicAdd((unsigned long long *)&c.counters[3], (unsigned long long)x.k_in);
+    atomicAdd((unsigned long long *)&c.counters[4], (unsigned long long)x.k_stored);
+    atomicAdd((unsigned long long *)&c.counters[5], (unsigned long long)x.k_maxact);
+    atomicAdd((unsigned long long *)&c.counters[6], (unsigned long long)x.k_bin0);
+    atomicAdd((unsigned long long *)&c.counters[7], (unsigned long long)x.k_frames);
+  }
+}
+
+__global__ void fill_hash_kernel(HashEntry *h, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) { h[i].val = kValEmpty; h[i].key = kKeyEmpty; h[i].tok = -1; }
+}
+
+}  // namespace
+
+// =================================================================================== host
+struct wfst_decoder {
+  DevGraph g{};
+  DevChannels c{};
+  wfst_opts opts{};
+  int V = 0;
+  std::vector<void *> allocs;
+  int64_t dev_bytes = 0;
+  // per-launch parameter staging (ring, so back-to-back async launches never share a slot)
+  static constexpr int kRing = 8;
+  int *d_params = nullptr;  int ring_pos = 0;
+  std::vector<int> h_params[kRing];
+  // device staging for host-side outputs
+  int *o_words = nullptr, *o_nwords = nullptr, *o_flags = nullptr; float *o_cost = nullptr;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
+  std::string err;
+};
+
+namespace {
+std::string g_create_err;
+
+#define HIP_TRY(dec, expr)                                                              \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) {                                                             \
+      (dec)->err = std::string(#expr) + ": " + hipGetErrorString(e_);                   \
+      return e_ == hipErrorOutOfMemory ? WFST_ERR_OOM : WFST_ERR_HIP;                   \
+    }                                                                                   \
+  } while (0)
+
+template <class T> int dev_alloc(wfst_decoder *d, T **p, size_t n) {
+  void *q = nullptr;
+  size_t bytes = std::max<size_t>(n, 1) * sizeof(T);
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) {
+    d->err = "hipMalloc of " + std::to_string(bytes) + " bytes: " + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return WFST_ERR_OOM;
+  }
+  d->allocs.push_back(q);
+  d->dev_bytes += (int64_t)bytes;
+  *p = static_cast<T *>(q);
+  return WFST_OK;
+}
+
+int fail(wfst_decoder *d, int code, const std::string &msg) {
+  if (d) d->err = msg; else g_create_err = msg;
+  return code;
+}
+
+// Graph checks: CSR shape, label and destination ranges, finite weights, acyclic epsilon arcs.
+int validate_graph(const wfst_graph_csr *g, std::string &why, int64_t &Ae, int64_t &Ax) {
+  const int32_t S = g->num_states;
+  if (S <= 0 || g->num_arcs < 0 || g->num_classes <= 0) { why = "empty graph or no classes"; return WFST_ERR_BAD_GRAPH; }
+  if (g->start_state < 0 || g->start_state >= S) { why = "start state out of range"; return WFST_ERR_BAD_GRAPH; }
+  if (!g->row_offsets || (g->num_arcs && (!g->next_state || !g->ilabel || !g->olabel || !g->weight))) {
+    why = "null graph array"; return WFST_ERR_INVALID_ARG;
+  }
+  if (g->row_offsets[0] != 0 || g->row_offsets[S] != g->num_arcs) { why = "row_offsets must start at 0 and end at num_arcs"; return WFST_ERR_BAD_GRAPH; }
+  for (int32_t s = 0; s < S; ++s)
+    if (g->row_offsets[s + 1] < g->row_offsets[s]) { why = "row_offsets not monotone at state " + std::to_string(s); return WFST_ERR_BAD_GRAPH; }
+  Ae = Ax = 0;
+  for (int64_t i = 0; i < g->num_arcs; ++i) {
+    if (g->next_state[i] < 0 || g->next_state[i] >= S) { why = "next_state out of range at arc " + std::to_string(i); return WFST_ERR_BAD_GRAPH; }
+    if (g->ilabel[i] < 0 || g->ilabel[i] > g->num_classes) { why = "ilabel out of range at arc " + std::to_string(i); return WFST_ERR_BAD_GRAPH; }
+    if (g->olabel[i] < 0) { why = "negative olabel at arc " + std::to_string(i); return WFST_ERR_BAD_GRAPH; }
+    if (!std::isfinite(g->weight[i])) { why = "non-finite weight at arc " + std::to_string(i); return WFST_ERR_BAD_GRAPH; }
+    if (g->ilabel[i] == 0) ++Ax; else ++Ae;
+  }
+  if (Ae + Ax >= (int64_t)0x7fffffff) { why = "more than 2^31-1 arcs"; return WFST_ERR_BAD_GRAPH; }
+  if (g->final_cost)
+    for (int32_t s = 0; s < S; ++s)
+      if (std::isnan(g->final_cost[s])) { why = "NaN final cost"; return WFST_ERR_BAD_GRAPH; }
+  // epsilon sub-graph must be a DAG (the closure is a fixpoint iteration): peel sources
+  std::vector<int32_t> indeg(S, 0), ready;
+  for (int64_t i = 0; i < g->num_arcs; ++i) if (g->ilabel[i] == 0) indeg[g->next_state[i]]++;
+  for (int32_t s = 0; s < S; ++s) if (!indeg[s]) ready.push_back(s);
+  int64_t peeled = 0;
+  while (!ready.empty()) {
+    int32_t s = ready.back(); ready.pop_back(); ++peeled;
+    for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i)
+      if (g->ilabel[i] == 0 && --indeg[g->next_state[i]] == 0) ready.push_back(g->next_state[i]);
+  }
+  if (peeled != S) { why = "epsilon arcs form a cycle"; return WFST_ERR_BAD_GRAPH; }
+  return WFST_OK;
+}
+
+int upload_graph(wfst_decoder *d, const wfst_graph_csr *g, int64_t Ae, int64_t Ax) {
+  const int32_t S = g->num_states;
+  std::vector<int2> off2(S + 1);
+  std::vector<int4> earc(Ae);
+  std::vector<int2> xarc(Ax);
+  std::vector<int> ol(Ae + Ax);
+  int64_t ne = 0, nx = 0;
+  for (int32_t s = 0; s < S; ++s) {
+    off2[s] = make_int2((int)ne, (int)nx);
+    for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i) {
+      int wbits; std::memcpy(&wbits, &g->weight[i], 4);
+      if (g->ilabel[i] == 0) { xarc[nx] = make_int2(g->next_state[i], wbits); ol[Ae + nx] = g->olabel[i]; ++nx; }
+      else { earc[ne] = make_int4(g->next_state[i], wbits, g->ilabel[i], g->olabel[i]); ol[ne] = g->olabel[i]; ++ne; }
+    }
+  }
+  off2[S] = make_int2((int)ne, (int)nx);
+  int2 *d_off; int4 *d_e; int2 *d_x; int *d_ol; float *d_fc = nullptr;
+  int rc;
+  if ((rc = dev_alloc(d, &d_off, off2.size()))) return rc;
+  if ((rc = dev_alloc(d, &d_e, earc.size()))) return rc;
+  if ((rc = dev_alloc(d, &d_x, xarc.size()))) return rc;
+  if ((rc = dev_alloc(d, &d_ol, ol.size()))) return rc;
+  HIP_TRY(d, hipMemcpy(d_off, off2.data(), off2.size() * sizeof(int2), hipMemcpyHostToDevice));
+  if (Ae) HIP_TRY(d, hipMemcpy(d_e, earc.data(), earc.size() * sizeof(int4), hipMemcpyHostToDevice));
+  if (Ax) HIP_TRY(d, hipMemcpy(d_x, xarc.data(), xarc.size() * sizeof(int2), hipMemcpyHostToDevice));
+  if (Ae + Ax) HIP_TRY(d, hipMemcpy(d_ol, ol.data(), ol.size() * sizeof(int), hipMemcpyHostToDevice));
+  if (g->final_cost) {
+    bool all_zero = true;
+    for (int32_t s = 0; s < S && all_zero; ++s) all_zero = g->final_cost[s] == 0.0f;
+    if (!all_zero) {
+      if ((rc = dev_alloc(d, &d_fc, (size_t)S))) return rc;
+      HIP_TRY(d, hipMemcpy(d_fc, g->final_cost, (size_t)S * sizeof(float), hipMemcpyHostToDevice));
+    }
+  }
+  d->g = DevGraph{d_off, d_e, d_x, d_ol, d_fc, S, g->start_state, (int)Ae, (int)Ax};
+  return WFST_OK;
+}
+
+int next_pow2(int64_t v) { int64_t p = 1; while (p < v) p <<= 1; return (int)p; }
+
+int alloc_channels(wfst_decoder *d) {
+  const wfst_opts &o = d->opts;
+  DevChannels &c = d->c;
+  const size_t N = (size_t)o.max_channels;
+  const int ma = o.max_active_hint > 0 ? o.max_active_hint : 10000;
+  c.hash_cap = o.state_map_capacity > 0 ? o.state_map_capacity : next_pow2(std::max<int64_t>(8192, 32LL * ma));
+  c.hash_mask = (unsigned)c.hash_cap - 1u;
+  c.claim_limit = c.hash_cap / 2 - kBlock;
+  c.claim_cap = c.hash_cap / 2;
+  c.cand_cap = c.hash_cap;
+  c.win_cap = c.claim_cap;
+  c.qcap = c.claim_cap;
+  c.max_frames = o.max_frames_per_channel;
+  int64_t lat_bytes = o.lattice_bytes_per_channel > 0 ? o.lattice_bytes_per_channel
+                                                      : (int64_t)(8.0 * 1.5 * ma * ((double)c.max_frames + 1.0));
+  int64_t lat_entries = std::max<int64_t>(lat_bytes / 8, 4096);
+  if (lat_entries >= (int64_t)0x7fffffff) lat_entries = 0x7ffffffe;
+  c.lat_cap = (unsigned)lat_entries;
+  int rc;
+  if ((rc = dev_alloc(d, &c.st, N))) return rc;
+  if ((rc = dev_alloc(d, &c.hash, N * c.hash_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.claim, N * c.claim_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.cand, N * c.cand_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.win_sc, N * c.win_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.win_pa, N * c.win_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.win_slot, N * c.win_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.queue, N * 2 * c.qcap))) return rc;
+  if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
+  if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.frame_off, N * (size_t)(c.max_frames + 2)))) return rc;
+  if (o.record_digests) {
+    if ((rc = dev_alloc(d, &c.dig_sum, N * (size_t)(c.max_frames + 1)))) return rc;
+    if ((rc = dev_alloc(d, &c.dig_cnt, N * (size_t)(c.max_frames + 1)))) return rc;
+  }
+  if ((rc = dev_alloc(d, &c.counters, (size_t)8))) return rc;
+  HIP_TRY(d, hipMemset(c.st, 0, N * sizeof(ChanState)));
+  HIP_TRY(d, hipMemset(c.counters, 0, 8 * sizeof(long long)));
+  HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
+  fill_hash_kernel<<<2048, 256>>>(c.hash, N * (size_t)c.hash_cap);
+  HIP_TRY(d, hipGetLastError());
+  if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
+  if (o.outputs_on_host) {
+    if ((rc = dev_alloc(d, &d->o_words, N * (size_t)o.max_words))) return rc;
+    if ((rc = dev_alloc(d, &d->o_nwords, N))) return rc;
+    if ((rc = dev_alloc(d, &d->o_flags, N))) return rc;
+    if ((rc = dev_alloc(d, &d->o_cost, N))) return rc;
+  }
+  HIP_TRY(d, hipDeviceSynchronize());
+  return WFST_OK;
+}
+
+// Stage {channel, frames, io row} triples and launch one workgroup per entry.
+int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int> &nfr,
+           const std::vector<int> &io, LaunchArgs a, hipStream_t st) {
+  const int n = (int)chan.size();
+  if (n == 0) return WFST_OK;
+  const size_t N = (size_t)d->opts.max_channels;
+  int *slot = d->d_params + (size_t)d->ring_pos * 3 * N;
+  std::vector<int> &pack = d->h_params[d->ring_pos];
+  pack.resize(3 * (size_t)n);
+  std::copy(chan.begin(), chan.end(), pack.begin());
+  std::copy(nfr.begin(), nfr.end(), pack.begin() + n);
+  std::copy(io.begin(), io.end(), pack.begin() + 2 * n);
+  d->ring_pos = (d->ring_pos + 1) % wfst_decoder::kRing;
+  HIP_TRY(d, hipMemcpyAsync(slot, pack.data(), pack.size() * sizeof(int), hipMemcpyHostToDevice, st));
+  a.chan = slot; a.nfr = slot + n; a.io = slot + 2 * n;
+  HIP_TRY(d, hipEventRecord(d->ev0, st));
+  hipLaunchKernelGGL(wfst_channel_kernel, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  HIP_TRY(d, hipGetLastError());
+  HIP_TRY(d, hipEventRecord(d->ev1, st));
+  d->timed = true;
+  return WFST_OK;
+}
+
+bool valid_prune(float beam, int max_active) { return beam >= 0.0f && max_active >= 1; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, wfst_decoder **out) {
+  if (!graph || !opts || !out) return fail(nullptr, WFST_ERR_INVALID_ARG, "null argument");
+  *out = nullptr;
+  if (opts->max_channels < 1 || opts->max_frames_per_channel < 1 || opts->max_words < 1)
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "max_channels, max_frames_per_channel and max_words must be >= 1");
+  if (opts->state_map_capacity && (opts->state_map_capacity < 8192 || (opts->state_map_capacity & (opts->state_map_capacity - 1))))
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "state_map_capacity must be a power of two >= 8192");
+  if (graph->num_classes > kMaxV)
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "num_classes above " + std::to_string(kMaxV));
+  std::string why; int64_t Ae = 0, Ax = 0;
+  int rc = validate_graph(graph, why, Ae, Ax);
+  if (rc) return fail(nullptr, rc, why);
+  wfst_decoder *d = new wfst_decoder();
+  d->opts = *opts; d->V = graph->num_classes;
+  rc = upload_graph(d, graph, Ae, Ax);
+  if (!rc) rc = alloc_channels(d);
+  if (!rc && (hipEventCreate(&d->ev0) != hipSuccess || hipEventCreate(&d->ev1) != hipSuccess)) {
+    d->err = "hipEventCreate failed"; rc = WFST_ERR_HIP;
+  }
+  if (rc) { g_create_err = d->err; wfst_decoder_destroy(d); return rc; }
+  *out = d;
+  return WFST_OK;
+}
+
+int32_t wfst_decoder_destroy(wfst_decoder *d) {
+  if (!d) return WFST_OK;
+  (void)hipDeviceSynchronize();
+  for (void *p : d->allocs) (void)hipFree(p);
+  if (d->ev0) (void)hipEventDestroy(d->ev0);
+  if (d->ev1) (void)hipEventDestroy(d->ev1);
+  delete d;
+  return WFST_OK;
+}
+
+int32_t wfst_decode_batch(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+                          int32_t T, int32_t V, float beam, int32_t max_active, void *stream,
+                          int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (B < 0 || T < 0) return fail(d, WFST_ERR_INVALID_ARG, "negative B or T");
+  if (B == 0) return WFST_OK;              // nothing to decode; pointers may be null
+  if (!lengths || !words || !nwords || !cost || !flags || (T > 0 && !loglikes))
+    return fail(d, WFST_ERR_INVALID_ARG, "null argument");
+  if (V != d->V) return fail(d, WFST_ERR_INVALID_ARG, "V differs from the graph's num_classes");
+  if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
+  if (B > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "batch larger than max_channels");
+  for (int b = 0; b < B; ++b)
+    if (lengths[b] < 0 || lengths[b] > T || lengths[b] > d->opts.max_frames_per_channel)
+      return fail(d, WFST_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, min(T, max_frames_per_channel)]");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // longest utterances first: workgroups are dispatched in order, so the long ones start
+  // at once and the short ones fill in behind them
+  std::vector<int> order(B), nfr(B);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return lengths[x] > lengths[y]; });
+  for (int i = 0; i < B; ++i) nfr[i] = lengths[order[i]];
+  const bool host_out = d->opts.outputs_on_host != 0;
+  LaunchArgs a{};
+  a.ll = loglikes; a.ll_stride = (long long)T * V; a.V = V;
+  a.mode = kModeInit | kModeFinal; a.finalize = 1;
+  a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
+  a.words = host_out ? d->o_words : words; a.nwords = host_out ? d->o_nwords : nwords;
+  a.cost = host_out ? d->o_cost : cost;    a.flags = host_out ? d->o_flags : flags;
+  a.max_words = d->opts.max_words;
+  int rc = launch(d, order, nfr, order, a, st);
+  if (rc) return rc;
+  if (host_out) {
+    const size_t mw = (size_t)d->opts.max_words;
+    HIP_TRY(d, hipMemcpyAsync(words, d->o_words, B * mw * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(nwords, d->o_nwords, B * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(cost, d->o_cost, B * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(flags, d->o_flags, B * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipStreamSynchronize(st));
+    for (int b = 0; b < B; ++b) {
+      if (flags[b] & WFST_FLAG_LATTICE_OVERFLOW) return fail(d, WFST_ERR_LATTICE_OVERFLOW, "utterance " + std::to_string(b) + " ran out of lattice memory");
+      if (flags[b] & WFST_FLAG_CAPACITY) return fail(d, WFST_ERR_CAPACITY, "utterance " + std::to_string(b) + " overflowed a work buffer");
+    }
+  }
+  return WFST_OK;
+}
+
+int32_t wfst_init_channel(wfst_decoder *d, int32_t ch, float beam, int32_t max_active,
+                          const void *boost, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (boost) return fail(d, WFST_ERR_INVALID_ARG, "boost tables are not supported by this build");
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
+  LaunchArgs a{};
+  a.V = d->V; a.mode = kModeInit;
+  a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
+  return launch(d, {ch}, {0}, {0}, a, static_cast<hipStream_t>(stream));
+}
+
+int32_t wfst_advance_chunk(wfst_decoder *d, const int32_t *channels, int32_t n, const float *loglikes,
+                           const int32_t *nframes, int32_t C, int32_t V, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (n < 0 || C < 0 || !channels || !nframes || (n > 0 && C > 0 && !loglikes))
+    return fail(d, WFST_ERR_INVALID_ARG, "null or negative argument");
+  if (V != d->V) return fail(d, WFST_ERR_INVALID_ARG, "V differs from the graph's num_classes");
+  if (n > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "more channels than max_channels");
+  std::vector<char> seen(d->opts.max_channels, 0);
+  std::vector<int> chan(n), nfr(n), io(n);
+  for (int i = 0; i < n; ++i) {
+    if (channels[i] < 0 || channels[i] >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+    if (seen[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel listed twice");
+    seen[channels[i]] = 1;
+    if (nframes[i] < 0 || nframes[i] > C) return fail(d, WFST_ERR_INVALID_ARG, "nframes outside [0, C]");
+    chan[i] = channels[i]; nfr[i] = nframes[i]; io[i] = i;
+  }
+  LaunchArgs a{};
+  a.ll = loglikes; a.ll_stride = (long long)C * V; a.V = V; a.mode = 0;
+  return launch(d, chan, nfr, io, a, static_cast<hipStream_t>(stream));
+}
+
+int32_t wfst_get_partial(wfst_decoder *d, int32_t ch, int32_t finalize, int32_t *words, int32_t cap,
+                         int32_t *nwords, float *cost, int32_t *flags, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (!words || !nwords || !cost || !flags || cap < 1) return fail(d, WFST_ERR_INVALID_ARG, "null output or cap < 1");
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool host_out = d->opts.outputs_on_host != 0;
+  if (host_out && cap > d->opts.max_words) cap = d->opts.max_words;
+  LaunchArgs a{};
+  a.V = d->V; a.mode = kModeFinal; a.finalize = finalize ? 1 : 0;
+  a.words = host_out ? d->o_words : words; a.nwords = host_out ? d->o_nwords : nwords;
+  a.cost = host_out ? d->o_cost : cost;    a.flags = host_out ? d->o_flags : flags;
+  a.max_words = cap;
+  int rc = launch(d, {ch}, {0}, {0}, a, st);
+  if (rc) return rc;
+  if (host_out) {
+    HIP_TRY(d, hipMemcpyAsync(nwords, d->o_nwords, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(cost, d->o_cost, sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(flags, d->o_flags, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(words, d->o_words, (size_t)cap * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipStreamSynchronize(st));
+  }
+  return WFST_OK;
+}
+
+int32_t wfst_debug_frame_digests(wfst_decoder *d, int32_t ch, uint64_t *digest, int32_t *count,
+                                 int32_t cap, int32_t *n) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (!d->c.dig_sum) return fail(d, WFST_ERR_INVALID_ARG, "decoder was created without record_digests");
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  if (!digest || !count || !n || cap < 0) return fail(d, WFST_ERR_INVALID_ARG, "null output");
+  HIP_TRY(d, hipDeviceSynchronize());
+  ChanState s;
+  HIP_TRY(d, hipMemcpy(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost));
+  *n = s.frame + 1;
+  const size_t m = (size_t)std::min(cap, s.frame + 1);
+  const size_t base = (size_t)ch * (d->c.max_frames + 1);
+  HIP_TRY(d, hipMemcpy(digest, d->c.dig_sum + base, m * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  HIP_TRY(d, hipMemcpy(count, d->c.dig_cnt + base, m * sizeof(int), hipMemcpyDeviceToHost));
+  return WFST_OK;
+}
+
+int32_t wfst_debug_get_tokens(wfst_decoder *d, int32_t ch, int32_t *states, float *costs, int32_t cap, int32_t *n) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  if (!states || !costs || !n || cap < 0) return fail(d, WFST_ERR_INVALID_ARG, "null output");
+  HIP_TRY(d, hipDeviceSynchronize());
+  ChanState s;
+  HIP_TRY(d, hipMemcpy(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost));
+  *n = s.n_tok;
+  const int m = std::min(cap, s.n_tok);
+  std::vector<int4> q((size_t)m);
+  const int4 *src = d->c.queue + ((size_t)ch * 2 + s.cur) * d->c.qcap;
+  if (m) HIP_TRY(d, hipMemcpy(q.data(), src, (size_t)m * sizeof(int4), hipMemcpyDeviceToHost));
+  for (int i = 0; i < m; ++i) { states[i] = q[i].x; std::memcpy(&costs[i], &q[i].y, 4); }
+  return WFST_OK;
+}
+
+int32_t wfst_get_counters(wfst_decoder *d, int64_t counters[8], int32_t reset) {
+  if (!d || !counters) return WFST_ERR_INVALID_ARG;
+  HIP_TRY(d, hipDeviceSynchronize());
+  HIP_TRY(d, hipMemcpy(counters, d->c.counters, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
+  if (reset) HIP_TRY(d, hipMemset(d->c.counters, 0, 8 * sizeof(int64_t)));
+  return WFST_OK;
+}
+
+int64_t wfst_device_bytes(const wfst_decoder *d) { return d ? d->dev_bytes : 0; }
+
+float wfst_last_kernel_ms(wfst_decoder *d) {
+  if (!d || !d->timed) return -1.0f;
+  if (hipEventSynchronize(d->ev1) != hipSuccess) return -1.0f;
+  float ms = -1.0f;
+  if (hipEventElapsedTime(&ms, d->ev0, d->ev1) != hipSuccess) return -1.0f;
+  return ms;
+}
+
+const char *wfst_last_error(const wfst_decoder *d) { return d ? d->err.c_str() : g_create_err.c_str(); }
+
+}  // extern "C"

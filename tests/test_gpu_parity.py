@@ -1,0 +1,271 @@
+"""GPU parity: the HIP decoder against the CPU oracle, element by element, through the C ABI.
+
+Bar: token sets of every frame identical (size and digest; full dumps on the small
+cases), word sequences bit-exact, path cost equal (bit-exact is expected; 1e-4 relative is
+the stated tolerance), flags equal.
+"""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+INF = float("inf")
+IMAX = 2**31 - 1
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch
+
+
+def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, threads=16, **kw):
+    from oracle import Oracle
+    o = Oracle(graph)
+
+    def one(b):
+        return o.decode(loglikes[b], length=int(lengths[b]), beam=beam, max_active=max_active,
+                        max_words=max_words, want_digests=True, **kw)
+    with ThreadPoolExecutor(threads) as ex:
+        return list(ex.map(one, range(len(lengths))))
+
+
+def check_batch(torch, graph, loglikes, lengths, beam, max_active, max_words=256, refs=None,
+                max_active_hint=None, check_counters=True, **deckw):
+    from paper_2311_04996_amd import Decoder
+    B, T, V = loglikes.shape
+    dec = Decoder(graph, max_channels=max(B, 1), max_frames=max(T, 1), max_words=max_words,
+                  max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True, **deckw)
+    ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda()
+    words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active)
+    torch.cuda.synchronize()
+    words, nwords, cost, flags = words.cpu().numpy(), nwords.cpu().numpy(), cost.cpu().numpy(), flags.cpu().numpy()
+    if refs is None:
+        refs = oracle_batch(graph, loglikes, lengths, beam, max_active, max_words)
+    near_ties = 0
+    for b, r in enumerate(refs):
+        cnt, dig = dec.debug_frame_digests(b)
+        assert len(cnt) == lengths[b] + 1, f"utt {b}: frames {len(cnt) - 1} != {lengths[b]}"
+        bad = np.nonzero((cnt != r.digest_count) | (dig != r.digest_sum))[0]
+        assert len(bad) == 0, f"utt {b}: token set differs first at frame {bad[0]}: |A|={cnt[bad[0]]} vs {r.digest_count[bad[0]]}"
+        assert int(flags[b]) == r.flags, f"utt {b}: flags {flags[b]} vs {r.flags}"
+        assert words[b, :nwords[b]].tolist() == r.words.tolist(), f"utt {b}: words differ"
+        if np.isfinite(r.cost):
+            assert cost[b] == pytest.approx(r.cost, rel=1e-4)
+            near_ties += int(cost[b] != np.float32(r.cost))
+        else:
+            assert cost[b] == r.cost
+    assert near_ties == 0, f"{near_ties} utterances with a cost that is not bit-equal"
+    if check_counters:
+        want = np.sum([r.counters for r in refs], axis=0)
+        got = dec.get_counters()
+        assert got[:7].tolist() == want[:7].tolist(), (got, want)
+        assert got[7] == int(np.sum(lengths))
+    dec.close()
+    return refs
+
+
+# ------------------------------------------------------------------------------- config 1
+def test_c1_tiny_matches_oracle(torch_cuda, c1):
+    check_batch(torch_cuda, c1.graph, c1.loglikes, c1.lengths, c1.beam, c1.max_active)
+
+
+def test_c1_token_sets_of_every_frame(torch_cuda, c1):
+    """Streaming one frame at a time and dumping the live token set after each frame."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    ref = Oracle(c1.graph).decode(c1.loglikes[0], beam=c1.beam, max_active=c1.max_active, want_frames=True)
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active)
+    ll = torch.from_numpy(c1.loglikes).cuda()
+    dec.init_channel(0, c1.beam, c1.max_active)
+    for t in range(101):
+        st, co = dec.debug_get_tokens(0)
+        got = sorted(zip(st.tolist(), co.view(np.uint32).tolist()))
+        want = sorted(zip(ref.frames[t][0].tolist(), ref.frames[t][1].view(np.uint32).tolist()))
+        assert got == want, f"frame {t}"
+        if t < 100:
+            dec.advance_chunk([0], ll[:, t:t + 1, :].contiguous(), [1])
+    dec.close()
+
+
+@pytest.mark.parametrize("beam,max_active", [(INF, IMAX), (4.0, 1000), (10.0, 37), (25.0, 3), (0.0, 10)])
+def test_c1_pruning_settings(torch_cuda, c1, beam, max_active):
+    check_batch(torch_cuda, c1.graph, c1.loglikes, c1.lengths, beam, max_active, max_active_hint=2000)
+
+
+# ------------------------------------------------------------------------------- micro graphs
+def test_micro_graphs_with_ties_and_negative_epsilon(torch_cuda):
+    """Exact cost ties (dyadic weights) are broken by arc id on both sides, so even the
+    backpointers, hence the words, must agree."""
+    from workloads import micro_graph
+    for seed in range(25):
+        rng = np.random.default_rng(seed)
+        V, T, B = 3, 9, 4
+        g = micro_graph(seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+        ll = -(rng.integers(0, 40, size=(B, T, V)).astype(np.float32) / 8.0)
+        lengths = rng.integers(0, T + 1, size=B).astype(np.int32)
+        for beam, ma in ((INF, IMAX), (3.0, 6), (1.0, 2)):
+            check_batch(torch_cuda, g, ll, lengths, beam, ma, max_active_hint=1000)
+
+
+def test_greedy_ctc_on_normal_topology(torch_cuda):
+    from checkers import greedy_ctc
+    from workloads import ctc_loglikes, ctc_topology_graph
+    V, T = 12, 80
+    g = ctc_topology_graph(V)
+    lengths = np.array([T, T, T], np.int32)
+    ll = ctc_loglikes(0, lengths, T, V, sigma=1.5, p_blank=0.5, blank_boost=3.0, token_boost=3.0)
+    for beam in (0.0, 3.0, 17.0):
+        refs = check_batch(torch_cuda, g, ll, lengths, beam, IMAX, max_active_hint=1000)
+        for b, r in enumerate(refs):
+            words, cost = greedy_ctc(ll[b])
+            assert r.words.tolist() == words.tolist() and r.cost == cost
+
+
+# ------------------------------------------------------------------------------- edge cases
+def _chain():
+    from workloads.graphs import _from_arc_list
+    arcs = [(0, 1, 2, 7, 0.5), (1, 2, 1, 0, 1.25), (2, 2, 3, 9, 0.125)]
+    return _from_arc_list(3, 0, 3, arcs, [INF, INF, 0.75])
+
+
+def test_empty_batch_and_zero_length(torch_cuda):
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    g = _chain()
+    dec = Decoder(g, max_channels=2, max_frames=4, max_words=4, max_active_hint=100)
+    ll = torch.zeros((0, 3, 3), dtype=torch.float32, device="cuda")
+    out = dec.decode_batch(ll, np.zeros(0, np.int32), 5.0, 10)
+    assert out[1].numel() == 0
+    dec.close()
+    ll = np.array([[[-1, -2, -3], [-.5, -9, -9], [-9, -9, -.25]]] * 2, np.float32)
+    check_batch(torch, g, ll, np.array([0, 3], np.int32), 100.0, 10, max_active_hint=100)
+
+
+def test_dead_and_nonfinal_and_minus_inf(torch_cuda):
+    from workloads.graphs import _from_arc_list
+    torch = torch_cuda
+    dead = _from_arc_list(2, 0, 2, [(0, 1, 1, 5, 0.0)], [INF, 0.0])
+    refs = check_batch(torch, dead, np.zeros((1, 3, 2), np.float32), np.array([3], np.int32), 10.0, 10, max_active_hint=100)
+    assert refs[0].dead
+    nonfinal = _from_arc_list(2, 0, 1, [(0, 1, 1, 5, 1.0), (1, 1, 1, 0, 0.0)], [INF, INF])
+    refs = check_batch(torch, nonfinal, np.full((1, 2, 1), -0.5, np.float32), np.array([2], np.int32), 10.0, 10, max_active_hint=100)
+    assert not refs[0].reached_final
+    g = _from_arc_list(3, 0, 2, [(0, 1, 1, 1, 0.0), (0, 2, 2, 2, 0.0), (1, 1, 1, 0, 0.0), (2, 2, 1, 0, 0.0)], np.zeros(3, np.float32))
+    ll = np.array([[[-np.inf, -3.0], [-0.1, -0.2]]], np.float32)
+    check_batch(torch, g, ll, np.array([2], np.int32), INF, IMAX, max_active_hint=100)
+
+
+def test_word_truncation(torch_cuda, c1):
+    refs = check_batch(torch_cuda, c1.graph, c1.loglikes, c1.lengths, c1.beam, c1.max_active, max_words=2)
+    assert refs[0].truncated
+
+
+def test_lattice_overflow_is_reported_not_fatal(torch_cuda, c1):
+    from paper_2311_04996_amd import Decoder, FLAG_LATTICE_OVERFLOW, FLAG_DEAD, WfstError
+    torch = torch_cuda
+    ll = torch.from_numpy(c1.loglikes).cuda()
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active,
+                  lattice_bytes_per_channel=8 * 5000)
+    _, nwords, cost, flags = dec.decode_batch(ll, c1.lengths, c1.beam, c1.max_active)
+    torch.cuda.synchronize()
+    assert int(flags[0]) & FLAG_LATTICE_OVERFLOW and int(flags[0]) & FLAG_DEAD and int(nwords[0]) == 0
+    dec.close()
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active,
+                  lattice_bytes_per_channel=8 * 5000, outputs_on_host=True)
+    with pytest.raises(WfstError) as e:
+        dec.decode_batch(ll, c1.lengths, c1.beam, c1.max_active)
+    assert e.value.code == -4
+    # the channel is usable again after the failure
+    dec.close()
+
+
+def test_argument_errors(torch_cuda, c1):
+    from paper_2311_04996_amd import Decoder, WfstError
+    torch = torch_cuda
+    dec = Decoder(c1.graph, max_channels=2, max_frames=50, max_active_hint=1000)
+    ll = torch.from_numpy(c1.loglikes).cuda()
+    with pytest.raises(WfstError) as e:
+        dec.decode_batch(ll, c1.lengths, c1.beam, c1.max_active)       # 100 frames > max_frames
+    assert e.value.code == -1
+    with pytest.raises(WfstError) as e:
+        dec.init_channel(2, 10.0, 100)
+    assert e.value.code == -5
+    with pytest.raises(WfstError) as e:
+        dec.advance_chunk([0, 0], ll[:, :2].repeat(2, 1, 1).contiguous(), [1, 1])
+    assert e.value.code == -5
+    with pytest.raises(WfstError) as e:
+        dec.decode_batch(ll[:, :50].contiguous(), [50], -1.0, 100)
+    assert e.value.code == -1
+    dec.close()
+
+
+def test_host_outputs(torch_cuda, c1):
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active, outputs_on_host=True)
+    words, nwords, cost, flags = dec.decode_batch(torch.from_numpy(c1.loglikes).cuda(), c1.lengths, c1.beam, c1.max_active)
+    ref = Oracle(c1.graph).decode(c1.loglikes[0], beam=c1.beam, max_active=c1.max_active)
+    assert words[0, :nwords[0]].tolist() == ref.words.tolist() and cost[0] == np.float32(ref.cost) and flags[0] == ref.flags
+    w, c, f = dec.get_partial(0, finalize=True)
+    assert w.tolist() == ref.words.tolist() and c == ref.cost
+    dec.close()
+
+
+# ------------------------------------------------------------------------------- config 2
+@pytest.fixture(scope="module")
+def c2_refs(c2):
+    return oracle_batch(c2.graph, c2.loglikes, c2.lengths, c2.beam, c2.max_active)
+
+
+def test_c2_medium_batch_matches_oracle(torch_cuda, c2, c2_refs):
+    check_batch(torch_cuda, c2.graph, c2.loglikes, c2.lengths, c2.beam, c2.max_active, refs=c2_refs)
+
+
+def test_c2_alone_equals_in_batch(torch_cuda, c2, c2_refs):
+    b = 5
+    check_batch(torch_cuda, c2.graph, c2.loglikes[b:b + 1], c2.lengths[b:b + 1], c2.beam, c2.max_active,
+                refs=c2_refs[b:b + 1])
+
+
+@pytest.mark.parametrize("chunk", [1, 16, 37])
+def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk):
+    """Per-stream state persists between chunks (Section 'Streaming inference'): any chunking
+    gives the offline result bit for bit, and partial hypotheses depend on the frame count only."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    chans = [3, 0, 6, 1]                      # channel ids need not be ordered or dense
+    utts = [0, 2, 4, 7]
+    lens = np.minimum(c2.lengths[utts], 120 if chunk == 1 else 10**6)
+    T = int(lens.max())
+    dec = Decoder(c2.graph, max_channels=8, max_frames=T, max_active_hint=c2.max_active, record_digests=True)
+    ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[utts, :T])).cuda()
+    for ch in chans:
+        dec.init_channel(ch, c2.beam, c2.max_active)
+    o = Oracle(c2.graph)
+    probe_at = {chunk * 2, chunk * 5}
+    for t0 in range(0, T, chunk):
+        nfr = np.clip(lens - t0, 0, chunk).astype(np.int32)
+        block = torch.zeros((4, chunk, ll.shape[2]), device="cuda")
+        block[:, :min(chunk, T - t0)] = ll[:, t0:t0 + chunk]
+        dec.advance_chunk(chans, block, nfr)
+        if t0 + chunk in probe_at:
+            for i, ch in enumerate(chans[:2]):
+                n = min(t0 + chunk, int(lens[i]))
+                w, c, f = dec.get_partial(ch, finalize=False)
+                r = o.decode(c2.loglikes[utts[i]], length=n, beam=c2.beam, max_active=c2.max_active, finalize=False)
+                assert w.tolist() == r.words.tolist() and c == r.cost and f == r.flags
+    for i, ch in enumerate(chans):
+        r = o.decode(c2.loglikes[utts[i]], length=int(lens[i]), beam=c2.beam, max_active=c2.max_active, want_digests=True)
+        cnt, dig = dec.debug_frame_digests(ch)
+        assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all()
+        w, c, f = dec.get_partial(ch, finalize=True)
+        assert w.tolist() == r.words.tolist() and c == r.cost and f == r.flags
+    dec.close()
