@@ -1,0 +1,142 @@
+"""Benchmark: decoder-only RTFx of the HIP WFST beam-search decoder on one MI355X.
+
+A step is one wfst_decode_batch call over the whole batch (init, every frame of every
+utterance, final choice and traceback) with the log-likelihoods already resident in HBM.
+Prints ONE JSON line; see the roofline and cpu_baseline objects in it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+KERNEL = "wfst_channel_kernel"
+
+
+def algorithmic_bytes(counters, V):
+    """Bytes the method has to move, from the deterministic counters (identical for the
+    oracle and the GPU path): per frame one log-likelihood row; per expanded token its queue
+    record and one {emitting, epsilon} offset pair; per emitting arc next state + weight +
+    ilabel; per epsilon arc next state + weight; per in-beam recombined destination one
+    8-byte map read-modify-write; per stored token its queue record and backpointer."""
+    tok, earc, xarc, n_in, stored, _, _, frames = [int(x) for x in counters]
+    return (frames * V * 4 + tok * (8 + 16) + earc * 12 + xarc * 8 + n_in * 16 + stored * (8 + 8))
+
+
+def cpu_baseline(w, threads, budget_s=20.0):
+    """The oracle, as it stands, one utterance per thread on a bounded sample of the batch."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import Oracle
+    o = Oracle(w.graph)
+    # shortest-first prefix of the batch, so that the sample stays bounded
+    order = np.argsort(w.lengths, kind="stable")
+    t0 = time.perf_counter()
+    o.decode(w.loglikes[order[0]], length=int(w.lengths[order[0]]), beam=w.beam, max_active=w.max_active)
+    per_frame = (time.perf_counter() - t0) / max(1, int(w.lengths[order[0]]))
+    frames_budget = budget_s * threads / max(per_frame, 1e-9)
+    take, acc = [], 0
+    for b in order:
+        if take and acc + int(w.lengths[b]) > frames_budget:
+            break
+        take.append(int(b)); acc += int(w.lengths[b])
+        if len(take) >= 4 * threads:
+            break
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda b: o.decode(w.loglikes[b], length=int(w.lengths[b]), beam=w.beam,
+                                       max_active=w.max_active), take))
+    dt = time.perf_counter() - t0
+    audio = float(w.lengths[take].sum()) * 0.040
+    return {"value": audio / dt, "unit": "audio-s/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(take)} shortest utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c3_large")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (utterances are independent; more GPUs "
+              "would each take a share of the batch with a replicated graph); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_04996_amd import Decoder
+    from workloads import make_config
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    t0 = time.perf_counter()
+    w = make_config(args.workload, batch=args.batch)
+    B, T, V = w.loglikes.shape
+    print(f"[bench] {args.workload}: S={w.graph.num_states} A={w.graph.num_arcs} B={B} T={T} V={V} "
+          f"audio={w.audio_seconds:.1f}s generated in {time.perf_counter() - t0:.1f}s", file=sys.stderr, flush=True)
+    t0 = time.perf_counter()
+    dec = Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active)
+    ll = torch.from_numpy(w.loglikes).cuda()
+    out = None
+    torch.cuda.synchronize()
+    print(f"[bench] decoder ready in {time.perf_counter() - t0:.1f}s, {dec.device_bytes() / 2**30:.1f} GiB on device",
+          file=sys.stderr, flush=True)
+
+    for _ in range(args.warmup):
+        out = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, out=out)
+    torch.cuda.synchronize()
+    dec.get_counters(reset=True)
+    kernel_ms = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, out=out)
+        kernel_ms.append(dec.last_kernel_ms())      # HIP events on the launch stream; waits for the kernel
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    counters = dec.get_counters() // max(1, args.steps)
+    flags = out[3].cpu().numpy()
+    assert not (flags & (8 | 16)).any(), "an utterance overflowed a buffer: the run is invalid"
+
+    ms_per_step = 1e3 * wall / args.steps
+    rtfx = w.audio_seconds / (wall / args.steps)
+    arcs = int(counters[1] + counters[2])
+    kms = float(np.mean(kernel_ms))
+    abytes = algorithmic_bytes(counters, V)
+    achieved = abytes / (kms * 1e-3) / 1e9
+    line = {
+        "metric": "RTFx (audio-s decoded/s) at batch 256", "value": rtfx, "unit": "audio-s/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
+                   "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
+                   "beam": w.beam, "max_active": w.max_active},
+        "arcs_expanded_per_s": arcs / (wall / args.steps),
+        "arcs_expanded_per_step": arcs,
+        "tokens_per_frame": float(counters[4]) / max(1, int(counters[7])),
+        "hbm_frac_of_peak": achieved / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": KERNEL, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms},
+    }
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        line["cpu_baseline"] = cpu_baseline(w, threads)
+    dec.close()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -37,6 +37,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kTPT = 2;                       // tokens per thread per chunk
 constexpr int kChunk = kBlock * kTPT;
 constexpr int kMaxV = 2048;
+constexpr int kU = 4;                         // independent memory requests per lane per phase
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
 constexpr unsigned kOrdNone = 0xFFFFFFFFu;
@@ -114,6 +115,7 @@ __device__ __forceinline__ float ord2f(unsigned o) {
   return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
 }
 __device__ __forceinline__ float canon(float x) { return x == 0.0f ? 0.0f : x; }
+__device__ __forceinline__ unsigned ord2bits(unsigned long long o) { return __float_as_uint(ord2f((unsigned)o)); }
 __device__ __forceinline__ unsigned hash_state(int s) { return (unsigned)s * 0x9E3779B1u; }
 __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   x += 0x9E3779B97F4A7C15ull;
@@ -201,33 +203,76 @@ __device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
   return lo;
 }
 
-// Recombination: lower the destination state's map entry to `key` (64-bit atomicMin),
-// claiming a slot on first touch.  Returns true if this candidate lowered the entry.
-__device__ __forceinline__ bool map_upsert(Ctx &x, int d, unsigned long long key, int &slot) {
+// ---- state map ---------------------------------------------------------------------------
+// Slot lookup is CAS-first: one round trip when the home slot is free or already holds the
+// state; linear probing only on a collision.
+__device__ __forceinline__ unsigned map_home(const Ctx &x, int d) {
+  return (hash_state(d) >> 7) & x.c.hash_mask;
+}
+// Continue probing after a collision at slot h.  Returns the slot or -1 when the table is full.
+__device__ __noinline__ int map_probe(Ctx &x, int d, unsigned h) {
   HashEntry *tab = x.hash;
   const unsigned mask = x.c.hash_mask;
-  unsigned h = (hash_state(d) >> 7) & mask;
   for (;;) {
-    int k = ld_dev(&tab[h].key);
-    if (k == d) break;
-    if (k == kKeyEmpty) {
-      if (*(volatile int *)&x.sm.n_claim >= x.c.claim_limit) {   // table too full: stop the channel
-        atomicOr(&x.sm.status, kStCapacity);
-        return false;
-      }
-      int old = atomicCAS(&tab[h].key, kKeyEmpty, d);
-      if (old == kKeyEmpty) {
-        int ci = atomicAdd(&x.sm.n_claim, 1);
-        if (ci < x.c.claim_cap) x.claim[ci] = (int)h;
-        break;
-      }
-      if (old == d) break;
-    }
     h = (h + 1) & mask;
+    if (*(volatile int *)&x.sm.n_claim >= x.c.claim_limit) {
+      atomicOr(&x.sm.status, kStCapacity);
+      return -1;
+    }
+    const int old = atomicCAS(&tab[h].key, kKeyEmpty, d);
+    if (old == kKeyEmpty) {
+      const int ci = atomicAdd(&x.sm.n_claim, 1);
+      if (ci < x.c.claim_cap) x.claim[ci] = (int)h;
+      return (int)h;
+    }
+    if (old == d) return (int)h;
   }
-  slot = (int)h;
-  unsigned long long old = atomicMin(&tab[h].val, key);
-  return old > key;
+}
+
+// Recombination of kU candidates per lane: claim/find the destination's slot, lower its
+// entry to `key` with a 64-bit atomicMin, and record the candidates that lowered it.  The
+// three memory round trips (CAS, atomicMin, record) are issued kU at a time.
+__device__ __forceinline__ void map_update_batch(Ctx &x, bool (&ok)[kU], const int (&dst)[kU],
+                                                 const unsigned long long (&key)[kU],
+                                                 const int (&src)[kU]) {
+  Smem &sm = x.sm;
+  HashEntry *tab = x.hash;
+  int slot[kU], old[kU];
+  const bool full = *(volatile int *)&sm.n_claim >= x.c.claim_limit;
+  if (full) atomicOr(&sm.status, kStCapacity);
+#pragma unroll
+  for (int u = 0; u < kU; ++u) {
+    ok[u] = ok[u] && !full;
+    slot[u] = (int)map_home(x, dst[u]);
+    old[u] = 0;
+    if (ok[u]) old[u] = atomicCAS(&tab[slot[u]].key, kKeyEmpty, dst[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kU; ++u) {
+    const bool claimed = ok[u] && old[u] == kKeyEmpty;
+    const int ci = wave_alloc(&sm.n_claim, claimed);
+    if (claimed && ci < x.c.claim_cap) x.claim[ci] = slot[u];
+    if (ok[u] && old[u] != kKeyEmpty && old[u] != dst[u]) {
+      slot[u] = map_probe(x, dst[u], (unsigned)slot[u]);
+      ok[u] = slot[u] >= 0;
+    }
+  }
+  unsigned long long prev[kU];
+#pragma unroll
+  for (int u = 0; u < kU; ++u) {
+    prev[u] = 0;
+    if (ok[u]) prev[u] = atomicMin(&tab[slot[u]].val, key[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kU; ++u) {
+    const bool improved = ok[u] && prev[u] > key[u];
+    const int ci = wave_alloc(&sm.n_cand, improved);
+    if (improved) {
+      if (ci < x.c.cand_cap)
+        x.cand[ci] = make_int4(slot[u], src[u], (int)(ord2bits(key[u] >> 32)), (int)(unsigned)key[u]);
+      else atomicOr(&sm.status, kStCapacity);
+    }
+  }
 }
 
 // ------------------------------------------------------------------ ExpandArcs (emitting)
@@ -252,32 +297,37 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
     if (tid == kBlock - 1) sm.pre[kChunk] = M;
     __syncthreads();
     if (tid == 0) x.k_earc += M;
-    for (unsigned f0 = 0; f0 < M; f0 += kBlock) {
-      const unsigned f = f0 + tid;
-      const bool act = f < M;
-      bool ok = false; float nc = 0.0f; int dst = 0, arc = 0, j = 0;
-      if (act) {
-        j = owner_of(sm, f);
-        arc = sm.abase[j] + (int)f;
-        const int4 a = x.g.earc[arc];
-        dst = a.x;
-        nc = canon((sm.tcost[j] + __int_as_float(a.y)) + sm.ac[a.z - 1]);
-        const unsigned bo = *(volatile unsigned *)&sm.best_ord;
-        const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
-        ok = (nc < INFINITY) && !((nc - rb) > beam);
+    for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
+      bool ok[kU]; int dst[kU], src[kU]; unsigned long long key[kU];
+      int4 a[kU]; int arc[kU]; float tc[kU];
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {          // owner search + arc fetch, kU in flight
+        const unsigned f = f0 + u * kBlock + tid;
+        ok[u] = f < M;
+        const int j = ok[u] ? owner_of(sm, f) : 0;
+        arc[u] = sm.abase[j] + (int)f;
+        src[u] = cb + j;
+        tc[u] = sm.tcost[j];
+        a[u] = make_int4(0, 0, 1, 0);
+        if (ok[u]) a[u] = x.g.earc[arc[u]];
+      }
+      const unsigned bo = *(volatile unsigned *)&sm.best_ord;
+      const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
+      unsigned o = kOrdNone;
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const float nc = canon((tc[u] + __int_as_float(a[u].y)) + sm.ac[a[u].z - 1]);
+        ok[u] = ok[u] && (nc < INFINITY) && !((nc - rb) > beam);
+        dst[u] = a[u].x;
+        const unsigned oc = f2ord(nc);
+        key[u] = ((unsigned long long)oc << 32) | (unsigned)arc[u];
+        if (ok[u]) o = min(o, oc);
       }
       // running best: wave minimum first, one LDS atomic per wave
-      unsigned o = ok ? f2ord(nc) : kOrdNone;
 #pragma unroll
       for (int sft = 32; sft > 0; sft >>= 1) o = min(o, (unsigned)__shfl_xor((int)o, sft, 64));
       if ((tid & 63) == 0 && o != kOrdNone) atomicMin(&sm.best_ord, o);
-      bool improved = false; int slot = 0;
-      if (ok) improved = map_upsert(x, dst, ((unsigned long long)f2ord(nc) << 32) | (unsigned)arc, slot);
-      const int ci = wave_alloc(&sm.n_cand, improved);
-      if (improved) {
-        if (ci < x.c.cand_cap) x.cand[ci] = make_int4(slot, cb + j, __float_as_int(nc), arc);
-        else atomicOr(&sm.status, kStCapacity);
-      }
+      map_update_batch(x, ok, dst, key, src);
     }
     __syncthreads();
   }
@@ -294,26 +344,34 @@ __device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &c
   const unsigned bo = sm.best_ord;
   cut.best = bo == kOrdNone ? INFINITY : ord2f(bo);
   cut.beam = x.s.beam; cut.scale = x.s.scale; cut.k_keep = 256;
-  for (int i0 = 0; i0 < n_cand; i0 += kBlock) {
-    const int i = i0 + tid;
-    bool win = false; int4 cd = make_int4(0, 0, 0, 0); int state = 0;
-    if (i < n_cand) {
-      cd = x.cand[i];
-      const float c = __int_as_float(cd.z);
-      const unsigned long long key = ((unsigned long long)f2ord(c) << 32) | (unsigned)cd.w;
-      if (ld_dev(&x.hash[cd.x].val) == key && cut.in_beam(c)) {
-        win = true;
-        state = ld_dev(&x.hash[cd.x].key);
-        atomicAdd(&sm.hist[cut.bin(c)], 1u);
-      }
+  for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
+    int4 cd[kU]; unsigned long long val[kU]; int state[kU]; bool act[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int i = i0 + u * kBlock + tid;
+      act[u] = i < n_cand;
+      cd[u] = make_int4(0, 0, 0, 0);
+      if (act[u]) cd[u] = x.cand[i];
     }
-    const int wi = wave_alloc(&sm.n_win, win);
-    if (win) {
-      if (wi < x.c.win_cap) {
-        x.win_sc[wi] = make_int2(state, cd.z);
-        x.win_pa[wi] = make_int2(cd.y, cd.w);
-        x.win_slot[wi] = cd.x;
-      } else atomicOr(&sm.status, kStCapacity);
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      val[u] = 0; state[u] = 0;
+      if (act[u]) { val[u] = ld_dev(&x.hash[cd[u].x].val); state[u] = ld_dev(&x.hash[cd[u].x].key); }
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const float c = __int_as_float(cd[u].z);
+      const unsigned long long key = ((unsigned long long)f2ord(c) << 32) | (unsigned)cd[u].w;
+      const bool win = act[u] && val[u] == key && cut.in_beam(c);
+      if (win) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+      const int wi = wave_alloc(&sm.n_win, win);
+      if (win) {
+        if (wi < x.c.win_cap) {
+          x.win_sc[wi] = make_int2(state[u], cd[u].z);
+          x.win_pa[wi] = make_int2(cd[u].y, cd[u].w);
+          x.win_slot[wi] = cd[u].x;
+        } else atomicOr(&sm.status, kStCapacity);
+      }
     }
   }
   __syncthreads();
@@ -343,18 +401,29 @@ __device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &c
   __syncthreads();
   cut.k_keep = sm.k_keep;
   const int n_win = min(sm.n_win, x.c.win_cap);
-  for (int i0 = 0; i0 < n_win; i0 += kBlock) {
-    const int i = i0 + tid;
-    bool kp = false; int2 sc = make_int2(0, 0);
-    if (i < n_win) { sc = x.win_sc[i]; kp = cut.bin(__int_as_float(sc.y)) < cut.k_keep; }
-    const int ti = wave_alloc(&sm.n_next, kp);
-    if (kp) {
-      if (ti >= x.c.qcap) atomicOr(&sm.status, kStCapacity);
-      else if (lat_base + (unsigned)ti >= x.c.lat_cap) atomicOr(&sm.status, kStLattice);
-      else {
-        NQ[ti] = make_int4(sc.x, sc.y, 0, 0);
-        x.lat[lat_base + ti] = x.win_pa[i];
-        st_dev(&x.hash[x.win_slot[i]].tok, ti);
+  for (int i0 = 0; i0 < n_win; i0 += kBlock * kU) {
+    int2 sc[kU], pa[kU]; int ws[kU]; bool kp[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int i = i0 + u * kBlock + tid;
+      kp[u] = false; sc[u] = make_int2(0, 0); pa[u] = sc[u]; ws[u] = 0;
+      if (i < n_win) {
+        sc[u] = x.win_sc[i];
+        kp[u] = cut.bin(__int_as_float(sc[u].y)) < cut.k_keep;
+        if (kp[u]) { pa[u] = x.win_pa[i]; ws[u] = x.win_slot[i]; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int ti = wave_alloc(&sm.n_next, kp[u]);
+      if (kp[u]) {
+        if (ti >= x.c.qcap) atomicOr(&sm.status, kStCapacity);
+        else if (lat_base + (unsigned)ti >= x.c.lat_cap) atomicOr(&sm.status, kStLattice);
+        else {
+          NQ[ti] = make_int4(sc[u].x, sc[u].y, 0, 0);
+          x.lat[lat_base + ti] = pa[u];
+          st_dev(&x.hash[ws[u]].tok, ti);
+        }
       }
     }
   }
@@ -376,22 +445,35 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const C
     const int *WL = x.wl[sel]; int *WLN = x.wl[sel ^ 1];
     long long my_x = 0;
     for (int cb = 0; cb < n_wl; cb += kChunk) {
-      unsigned deg[kTPT]; int base[kTPT], tk[kTPT]; float cs[kTPT];
+      unsigned deg[kTPT]; int base[kTPT], tk[kTPT]; float cs[kTPT]; int2 sc[kTPT]; int en[kTPT];
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
         const int i = cb + kTPT * tid + k;
-        deg[k] = 0; base[k] = 0; tk[k] = 0; cs[k] = 0.0f;
-        if (i < n_wl) {
-          const int e = implicit ? (i | 0x80000000) : WL[i];
-          const int ti = e & 0x7fffffff;
-          const int2 sc = *reinterpret_cast<const int2 *>(&NQ[ti]);
-          const int2 o0 = x.g.off2[sc.x], o1 = x.g.off2[sc.x + 1];
-          if (e < 0) {                       // first expansion of this token
-            reinterpret_cast<int2 *>(&NQ[ti])[1] = make_int2(o0.x, o1.x - o0.x);
-            my_x += o1.y - o0.y;
-          }
-          deg[k] = (unsigned)(o1.y - o0.y); base[k] = o0.y; tk[k] = ti; cs[k] = __int_as_float(sc.y);
+        en[k] = 0;
+        if (i < n_wl) en[k] = implicit ? (i | 0x80000000) : WL[i];
+      }
+#pragma unroll
+      for (int k = 0; k < kTPT; ++k) {
+        const int i = cb + kTPT * tid + k;
+        sc[k] = make_int2(0, 0);
+        if (i < n_wl) sc[k] = *reinterpret_cast<const int2 *>(&NQ[en[k] & 0x7fffffff]);
+      }
+      int2 o0[kTPT], o1[kTPT];
+#pragma unroll
+      for (int k = 0; k < kTPT; ++k) {
+        const int i = cb + kTPT * tid + k;
+        o0[k] = make_int2(0, 0); o1[k] = o0[k];
+        if (i < n_wl) { o0[k] = x.g.off2[sc[k].x]; o1[k] = x.g.off2[sc[k].x + 1]; }
+      }
+#pragma unroll
+      for (int k = 0; k < kTPT; ++k) {
+        const int i = cb + kTPT * tid + k;
+        const int ti = en[k] & 0x7fffffff;
+        if (i < n_wl && en[k] < 0) {           // first expansion of this token
+          reinterpret_cast<int2 *>(&NQ[ti])[1] = make_int2(o0[k].x, o1[k].x - o0[k].x);
+          my_x += o1[k].y - o0[k].y;
         }
+        deg[k] = (unsigned)(o1[k].y - o0[k].y); base[k] = o0[k].y; tk[k] = ti; cs[k] = __int_as_float(sc[k].y);
       }
       unsigned ex0, ex1;
       const unsigned M = block_scan2(sm, deg[0], deg[1], ex0, ex1);
@@ -401,58 +483,72 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const C
       sm.ttok[kTPT * tid] = tk[0];           sm.ttok[kTPT * tid + 1] = tk[1];
       if (tid == kBlock - 1) sm.pre[kChunk] = M;
       __syncthreads();
-      for (unsigned f0 = 0; f0 < M; f0 += kBlock) {
-        const unsigned f = f0 + tid;
-        bool ok = false; float nc = 0.0f; int dst = 0, arc = 0, j = 0;
-        if (f < M) {
-          j = owner_of(sm, f);
-          arc = sm.abase[j] + (int)f;
-          const int2 a = x.g.xarc[arc];
-          dst = a.x;
-          nc = canon(sm.tcost[j] + __int_as_float(a.y));
-          ok = (nc < INFINITY) && cut.keep(nc);
+      for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
+        bool ok[kU]; int dst[kU], src[kU]; unsigned long long key[kU];
+        int2 a[kU]; int arc[kU]; float tc[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+          const unsigned f = f0 + u * kBlock + tid;
+          ok[u] = f < M;
+          const int j = ok[u] ? owner_of(sm, f) : 0;
+          arc[u] = sm.abase[j] + (int)f;
+          src[u] = sm.ttok[j];
+          tc[u] = sm.tcost[j];
+          a[u] = make_int2(0, 0);
+          if (ok[u]) a[u] = x.g.xarc[arc[u]];
         }
-        bool improved = false; int slot = 0;
-        const int gid = x.g.Ae + arc;
-        if (ok) improved = map_upsert(x, dst, ((unsigned long long)f2ord(nc) << 32) | (unsigned)gid, slot);
-        const int ci = wave_alloc(&sm.n_cand, improved);
-        if (improved) {
-          if (ci < x.c.cand_cap) x.cand[ci] = make_int4(slot, sm.ttok[j], __float_as_int(nc), gid);
-          else atomicOr(&sm.status, kStCapacity);
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+          const float nc = canon(tc[u] + __int_as_float(a[u].y));
+          ok[u] = ok[u] && (nc < INFINITY) && cut.keep(nc);
+          dst[u] = a[u].x;
+          key[u] = ((unsigned long long)f2ord(nc) << 32) | (unsigned)(x.g.Ae + arc[u]);
         }
+        map_update_batch(x, ok, dst, key, src);
       }
       __syncthreads();
     }
     if (my_x) atomicAdd((unsigned long long *)&sm.xarcs, (unsigned long long)my_x);
     // winners of this round update their token in place (or create it) and are re-queued
     const int n_cand = min(sm.n_cand, x.c.cand_cap);
-    for (int i0 = 0; i0 < n_cand; i0 += kBlock) {
-      const int i = i0 + tid;
-      bool win = false, fresh = false; int4 cd = make_int4(0, 0, 0, 0); int tok = -1;
-      if (i < n_cand) {
-        cd = x.cand[i];
-        const unsigned long long key = ((unsigned long long)f2ord(__int_as_float(cd.z)) << 32) | (unsigned)cd.w;
-        if (ld_dev(&x.hash[cd.x].val) == key) {
-          win = true;
-          tok = ld_dev(&x.hash[cd.x].tok);
-          fresh = tok < 0;
+    for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
+      int4 cd[kU]; unsigned long long val[kU]; int tok[kU], state[kU]; bool act[kU];
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int i = i0 + u * kBlock + tid;
+        act[u] = i < n_cand;
+        cd[u] = make_int4(0, 0, 0, 0);
+        if (act[u]) cd[u] = x.cand[i];
+      }
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        val[u] = 0; tok[u] = -1; state[u] = 0;
+        if (act[u]) {
+          val[u] = ld_dev(&x.hash[cd[u].x].val);
+          tok[u] = ld_dev(&x.hash[cd[u].x].tok);
+          state[u] = ld_dev(&x.hash[cd[u].x].key);
         }
       }
-      const int ni = wave_alloc(&sm.n_next, fresh);
-      if (fresh) tok = ni;
-      bool good = win;
-      if (win) {
-        if (tok >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
-        else if (lat_base + (unsigned)tok >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const unsigned long long key = ((unsigned long long)f2ord(__int_as_float(cd[u].z)) << 32) | (unsigned)cd[u].w;
+        const bool win = act[u] && val[u] == key;
+        const bool fresh = win && tok[u] < 0;
+        const int ni = wave_alloc(&sm.n_next, fresh);
+        int t = fresh ? ni : tok[u];
+        bool good = win;
+        if (win) {
+          if (t >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
+          else if (lat_base + (unsigned)t >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+        }
+        if (good) {
+          if (fresh) st_dev(&x.hash[cd[u].x].tok, t);
+          *reinterpret_cast<int2 *>(&NQ[t]) = make_int2(state[u], cd[u].z);
+          x.lat[lat_base + t] = make_int2(cd[u].y, cd[u].w);
+        }
+        const int wi = wave_alloc(&sm.n_wl_next, good);
+        if (good) WLN[wi] = t | (fresh ? 0x80000000 : 0);
       }
-      if (good) {
-        if (fresh) st_dev(&x.hash[cd.x].tok, tok);
-        const int state = ld_dev(&x.hash[cd.x].key);
-        *reinterpret_cast<int2 *>(&NQ[tok]) = make_int2(state, cd.z);
-        x.lat[lat_base + tok] = make_int2(cd.y, cd.w);
-      }
-      const int wi = wave_alloc(&sm.n_wl_next, good);
-      if (good) WLN[wi] = tok | (fresh ? 0x80000000 : 0);
     }
     __syncthreads();
     n_wl = min(sm.n_wl_next, x.c.qcap);
@@ -481,10 +577,17 @@ __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
     if (s) atomicAdd(&sm.red64, s);
   }
   const int n_claim = min(sm.n_claim, x.c.claim_cap);
-  for (int i = tid; i < n_claim; i += kBlock) {
-    HashEntry *e = &x.hash[x.claim[i]];
-    st_dev(&e->val, kValEmpty);
-    st_dev(reinterpret_cast<unsigned long long *>(&e->key), ~0ull);   // key = -1, tok = -1
+  for (int i0 = 0; i0 < n_claim; i0 += kBlock * kU) {
+    int sl[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) { const int i = i0 + u * kBlock + tid; sl[u] = i < n_claim ? x.claim[i] : -1; }
+#pragma unroll
+    for (int u = 0; u < kU; ++u)
+      if (sl[u] >= 0) {
+        HashEntry *e = &x.hash[sl[u]];
+        st_dev(&e->val, kValEmpty);
+        st_dev(reinterpret_cast<unsigned long long *>(&e->key), ~0ull);   // key = -1, tok = -1
+      }
   }
   __syncthreads();
   if (tid == 0) {
@@ -609,9 +712,11 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active;
     int4 *NQ = x.q[1];
     if (tid == 0) {
-      int slot = 0;
-      map_upsert(x, g.start, ((unsigned long long)f2ord(0.0f) << 32) | 0xFFFFFFFFull, slot);
+      const int slot = (int)map_home(x, g.start);      // the map is empty: the home slot is free
+      st_dev(&x.hash[slot].key, g.start);
+      st_dev(&x.hash[slot].val, ((unsigned long long)f2ord(0.0f) << 32) | 0xFFFFFFFFull);
       st_dev(&x.hash[slot].tok, 0);
+      x.claim[0] = slot; sm.n_claim = 1;
       NQ[0] = make_int4(g.start, __float_as_int(0.0f), 0, 0);
       x.lat[0] = make_int2(-1, -1);
       sm.n_next = 1;
