@@ -75,7 +75,7 @@ typedef struct {
   int64_t lattice_bytes_per_channel; /* 0 = 8 B * max_frames * 1.5 * max_active_hint */
   int32_t outputs_on_host;        /* 0: outputs are device pointers; 1: host pointers */
   int32_t max_active_hint;        /* sizes the per-channel work buffers; 0 = 10000 */
-  int32_t state_map_capacity;     /* power of two, 0 = derived (32 * max_active_hint rounded up) */
+  int32_t num_partitions;         /* candidate partitions per channel: power of two in [2,64], 0 = derived */
   int32_t record_digests;         /* 1: keep per-frame token-set digests (slower; for tests) */
 } wfst_opts;
 

@@ -41,7 +41,7 @@ class wfst_opts(C.Structure):
     _fields_ = [("max_channels", C.c_int32), ("max_frames_per_channel", C.c_int32),
                 ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
                 ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
-                ("state_map_capacity", C.c_int32), ("record_digests", C.c_int32)]
+                ("num_partitions", C.c_int32), ("record_digests", C.c_int32)]
 
 
 _lib = None
@@ -91,7 +91,7 @@ class Decoder:
     """Owns one wfst_decoder handle.  Method names mirror the C entry points."""
 
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
-                 lattice_bytes_per_channel=0, outputs_on_host=False, state_map_capacity=0,
+                 lattice_bytes_per_channel=0, outputs_on_host=False, num_partitions=0,
                  record_digests=False):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
@@ -103,7 +103,7 @@ class Decoder:
         g = wfst_graph_csr(graph.num_states, graph.start_state, graph.num_classes, int(arrs[0][-1]),
                            *[None if a is None else a.ctypes.data for a in arrs])
         self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
-                              int(outputs_on_host), max_active_hint, state_map_capacity,
+                              int(outputs_on_host), max_active_hint, num_partitions,
                               int(record_digests))
         self.V = graph.num_classes
         self.max_words = max_words

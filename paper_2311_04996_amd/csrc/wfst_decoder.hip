@@ -8,16 +8,25 @@
 // with CUDA graphs) and no per-frame device-to-host copy (the lattice stays in HBM and the
 // traceback runs on the device).
 //
-// Data structures (per channel, all in HBM):
+// Recombination (one token per destination state, lowest (cost, arc id) wins) uses NO global
+// atomics: measured on MI355X, 64-bit global atomics top out near 25 G/s for the whole chip,
+// which bounded an earlier global-hash design.  Instead ExpandArcs appends candidates
+// {dst, cost, source token, arc} to per-partition regions of a candidate buffer (partition =
+// hash of the destination state), and each group of partitions is then reduced in an
+// open-addressing table that lives in LDS (160 KB per CU on gfx950), with LDS compare-and-swap.
+// A dense per-state index (tagged with the frame epoch, so it never needs clearing) answers
+// "does this state already have a token" for the epsilon closure.
+//
+// Per channel, in HBM:
 //   token queue   2 x qcap records {state, cost, first emitting arc, emitting degree}
-//   state map     open-addressing hash  state -> {(orderable cost << 32 | arc id), token idx}
-//                 recombination is a 64-bit atomicMin on the packed word
-//   candidates    records {slot, source token, cost, arc id} of arcs that lowered a map entry
+//   candidates    num_parts x region_cap records {dst state, cost, source token, arc id}
 //   winners       recombined in-beam tokens before the max-active cutoff is known
+//   state index   S x 4 B: (epoch tag << 16) | token index
 //   lattice       {prev token, arc id} per stored token, frame after frame
-// LDS holds the negated log-likelihood row, the 256-bin cost histogram, the running best
-// cost and, per chunk of 2048 tokens, the prefix sums of their arc counts so that every
-// lane owns one arc of the flattened (token x arc) space regardless of state degree.
+// LDS holds, per phase, either the expansion tables (negated log-likelihood row and, per chunk
+// of 2048 tokens, the prefix sums of their arc counts so that every lane owns one arc of the
+// flattened (token x arc) space regardless of state degree) or the recombination table, plus
+// the 256-bin cost histogram and the running best cost.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -38,17 +47,16 @@ constexpr int kTPT = 2;                       // tokens per thread per chunk
 constexpr int kChunk = kBlock * kTPT;
 constexpr int kMaxV = 2048;
 constexpr int kU = 4;                         // independent memory requests per lane per phase
+constexpr int kTabSlots = 8192;               // LDS recombination table
+constexpr unsigned kTabMask = kTabSlots - 1;
+constexpr int kGroupMax = 5120;               // candidates reduced per table pass (load <= 0.63)
+constexpr int kMaxParts = 64;
+constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
 constexpr unsigned kOrdNone = 0xFFFFFFFFu;
 constexpr int kModeInit = 1, kModeFinal = 2;
 constexpr int kStLattice = WFST_FLAG_LATTICE_OVERFLOW, kStCapacity = WFST_FLAG_CAPACITY;
-
-struct HashEntry {            // 16 B: key CAS and value atomicMin touch one cache line
-  unsigned long long val;     // (orderable cost << 32) | global arc id ; kValEmpty when free
-  int key;                    // state id, kKeyEmpty when free
-  int tok;                    // index of the state's token in the next queue, -1 if none
-};
 
 struct ChanState {            // persists between calls (the per-stream decoder state)
   int frame;                  // frames consumed since init
@@ -58,6 +66,7 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   unsigned lat_used;          // lattice entries in use
   int max_active;
   float beam, scale;          // scale = 256 / beam, computed once on the host
+  unsigned epoch;             // closed sets published since create (tags the state index)
 };
 
 struct DevGraph {
@@ -71,12 +80,11 @@ struct DevGraph {
 
 struct DevChannels {
   ChanState *st;
-  HashEntry *hash;  unsigned hash_mask; int hash_cap;
-  int *claim;       int claim_cap, claim_limit;
-  int4 *cand;       int cand_cap;
-  int2 *win_sc, *win_pa; int *win_slot; int win_cap;
+  int4 *cand;       int num_parts, part_shift, region_cap;   // [num_parts][region_cap]
+  int2 *win_sc;     int *win_ci; int win_cap;
   int4 *queue;      int qcap;
   int *wl;
+  unsigned *index;  // [S] per channel
   int2 *lattice;    unsigned lat_cap;
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
@@ -91,16 +99,24 @@ struct LaunchArgs {
   int *words, *nwords; float *cost; int *flags; int max_words;
 };
 
-struct Smem {
+struct ExpandLds {            // live while arcs are being expanded
   float ac[kMaxV];
   unsigned pre[kChunk + 1];
   int abase[kChunk];
   float tcost[kChunk];
   int ttok[kChunk];
+};
+struct TableLds {             // live while candidates are being recombined
+  unsigned long long vals[kTabSlots];   // (orderable cost << 32) | candidate index
+  int keys[kTabSlots];                  // destination state, kKeyEmpty when free
+};
+struct Smem {
+  union { ExpandLds e; TableLds t; } u;
   unsigned hist[256];
   unsigned wave_tot[kWaves];
+  int part_cnt[kMaxParts];
   unsigned best_ord;
-  int n_claim, n_cand, n_win, n_next, n_wl_next, status, k_keep, n_in;
+  int n_win, n_next, n_wl_next, n_tab, status, k_keep, n_in;
   unsigned long long red64, red64b;
   long long xarcs;
   int sel_idx;
@@ -115,19 +131,12 @@ __device__ __forceinline__ float ord2f(unsigned o) {
   return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
 }
 __device__ __forceinline__ float canon(float x) { return x == 0.0f ? 0.0f : x; }
-__device__ __forceinline__ unsigned ord2bits(unsigned long long o) { return __float_as_uint(ord2f((unsigned)o)); }
 __device__ __forceinline__ unsigned hash_state(int s) { return (unsigned)s * 0x9E3779B1u; }
 __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   x += 0x9E3779B97F4A7C15ull;
   x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
   x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
   return x ^ (x >> 31);
-}
-template <class T> __device__ __forceinline__ T ld_dev(const T *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <class T> __device__ __forceinline__ void st_dev(T *p, T v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Index from an LDS counter for every lane with pred set; one LDS atomic per wave.
@@ -160,13 +169,16 @@ struct Cutoff {
 
 struct Ctx {                  // block-uniform view of one channel
   const DevGraph &g; const DevChannels &c; Smem &sm;
-  HashEntry *hash; int *claim; int4 *cand; int2 *win_sc, *win_pa; int *win_slot;
-  int4 *q[2]; int *wl[2]; int2 *lat; unsigned *frame_off;
+  int4 *cand; int2 *win_sc; int *win_ci;
+  int4 *q[2]; int *wl[2]; unsigned *index; int2 *lat; unsigned *frame_off;
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
   // per-launch counters (thread 0 accumulates the uniform ones)
   long long k_tok = 0, k_earc = 0, k_in = 0, k_stored = 0, k_maxact = 0, k_bin0 = 0, k_frames = 0;
 };
+
+// Tag of the token set under construction; 0 is never a valid tag (the index starts zeroed).
+__device__ __forceinline__ unsigned set_tag(unsigned epoch) { return epoch % 65535u + 1u; }
 
 // Block-wide exclusive scan of two values per thread (thread t owns items 2t, 2t+1).
 __device__ __forceinline__ unsigned block_scan2(Smem &sm, unsigned d0, unsigned d1,
@@ -198,80 +210,18 @@ __device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
 #pragma unroll
   for (int it = 0; it < 11; ++it) {
     int mid = (lo + hi) >> 1;
-    if (sm.pre[mid] <= f) lo = mid; else hi = mid;
+    if (sm.u.e.pre[mid] <= f) lo = mid; else hi = mid;
   }
   return lo;
 }
 
-// ---- state map ---------------------------------------------------------------------------
-// Slot lookup is CAS-first: one round trip when the home slot is free or already holds the
-// state; linear probing only on a collision.
-__device__ __forceinline__ unsigned map_home(const Ctx &x, int d) {
-  return (hash_state(d) >> 7) & x.c.hash_mask;
-}
-// Continue probing after a collision at slot h.  Returns the slot or -1 when the table is full.
-__device__ __noinline__ int map_probe(Ctx &x, int d, unsigned h) {
-  HashEntry *tab = x.hash;
-  const unsigned mask = x.c.hash_mask;
-  for (;;) {
-    h = (h + 1) & mask;
-    if (*(volatile int *)&x.sm.n_claim >= x.c.claim_limit) {
-      atomicOr(&x.sm.status, kStCapacity);
-      return -1;
-    }
-    const int old = atomicCAS(&tab[h].key, kKeyEmpty, d);
-    if (old == kKeyEmpty) {
-      const int ci = atomicAdd(&x.sm.n_claim, 1);
-      if (ci < x.c.claim_cap) x.claim[ci] = (int)h;
-      return (int)h;
-    }
-    if (old == d) return (int)h;
-  }
-}
-
-// Recombination of kU candidates per lane: claim/find the destination's slot, lower its
-// entry to `key` with a 64-bit atomicMin, and record the candidates that lowered it.  The
-// three memory round trips (CAS, atomicMin, record) are issued kU at a time.
-__device__ __forceinline__ void map_update_batch(Ctx &x, bool (&ok)[kU], const int (&dst)[kU],
-                                                 const unsigned long long (&key)[kU],
-                                                 const int (&src)[kU]) {
-  Smem &sm = x.sm;
-  HashEntry *tab = x.hash;
-  int slot[kU], old[kU];
-  const bool full = *(volatile int *)&sm.n_claim >= x.c.claim_limit;
-  if (full) atomicOr(&sm.status, kStCapacity);
-#pragma unroll
-  for (int u = 0; u < kU; ++u) {
-    ok[u] = ok[u] && !full;
-    slot[u] = (int)map_home(x, dst[u]);
-    old[u] = 0;
-    if (ok[u]) old[u] = atomicCAS(&tab[slot[u]].key, kKeyEmpty, dst[u]);
-  }
-#pragma unroll
-  for (int u = 0; u < kU; ++u) {
-    const bool claimed = ok[u] && old[u] == kKeyEmpty;
-    const int ci = wave_alloc(&sm.n_claim, claimed);
-    if (claimed && ci < x.c.claim_cap) x.claim[ci] = slot[u];
-    if (ok[u] && old[u] != kKeyEmpty && old[u] != dst[u]) {
-      slot[u] = map_probe(x, dst[u], (unsigned)slot[u]);
-      ok[u] = slot[u] >= 0;
-    }
-  }
-  unsigned long long prev[kU];
-#pragma unroll
-  for (int u = 0; u < kU; ++u) {
-    prev[u] = 0;
-    if (ok[u]) prev[u] = atomicMin(&tab[slot[u]].val, key[u]);
-  }
-#pragma unroll
-  for (int u = 0; u < kU; ++u) {
-    const bool improved = ok[u] && prev[u] > key[u];
-    const int ci = wave_alloc(&sm.n_cand, improved);
-    if (improved) {
-      if (ci < x.c.cand_cap)
-        x.cand[ci] = make_int4(slot[u], src[u], (int)(ord2bits(key[u] >> 32)), (int)(unsigned)key[u]);
-      else atomicOr(&sm.status, kStCapacity);
-    }
+// Append one candidate to the region of its destination's partition.
+__device__ __forceinline__ void push_cand(Ctx &x, bool ok, int dst, float nc, int src, int arc) {
+  if (ok) {
+    const int p = (int)(hash_state(dst) >> x.c.part_shift);
+    const int off = atomicAdd(&x.sm.part_cnt[p], 1);
+    if (off < x.c.region_cap) x.cand[p * x.c.region_cap + off] = make_int4(dst, __float_as_int(nc), src, arc);
+    else atomicOr(&x.sm.status, kStCapacity);
   }
 }
 
@@ -282,6 +232,7 @@ __device__ __forceinline__ void map_update_batch(Ctx &x, bool (&ok)[kU], const i
 // the running best is never lower than the final one, so this never drops a survivor.
 __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
   Smem &sm = x.sm;
+  ExpandLds &e = sm.u.e;
   const int tid = threadIdx.x;
   const float beam = x.s.beam;
   for (int cb = 0; cb < n_tok; cb += kChunk) {
@@ -291,95 +242,158 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
     if (i0 + 1 < n_tok) t1 = Q[i0 + 1];
     unsigned ex0, ex1;
     const unsigned M = block_scan2(sm, (unsigned)t0.w, (unsigned)t1.w, ex0, ex1);
-    sm.pre[kTPT * tid] = ex0;          sm.pre[kTPT * tid + 1] = ex1;
-    sm.abase[kTPT * tid] = t0.z - (int)ex0; sm.abase[kTPT * tid + 1] = t1.z - (int)ex1;
-    sm.tcost[kTPT * tid] = __int_as_float(t0.y); sm.tcost[kTPT * tid + 1] = __int_as_float(t1.y);
-    if (tid == kBlock - 1) sm.pre[kChunk] = M;
+    e.pre[kTPT * tid] = ex0;          e.pre[kTPT * tid + 1] = ex1;
+    e.abase[kTPT * tid] = t0.z - (int)ex0; e.abase[kTPT * tid + 1] = t1.z - (int)ex1;
+    e.tcost[kTPT * tid] = __int_as_float(t0.y); e.tcost[kTPT * tid + 1] = __int_as_float(t1.y);
+    if (tid == kBlock - 1) e.pre[kChunk] = M;
     __syncthreads();
     if (tid == 0) x.k_earc += M;
     for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-      bool ok[kU]; int dst[kU], src[kU]; unsigned long long key[kU];
-      int4 a[kU]; int arc[kU]; float tc[kU];
+      bool ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU];
 #pragma unroll
       for (int u = 0; u < kU; ++u) {          // owner search + arc fetch, kU in flight
         const unsigned f = f0 + u * kBlock + tid;
         ok[u] = f < M;
         const int j = ok[u] ? owner_of(sm, f) : 0;
-        arc[u] = sm.abase[j] + (int)f;
+        arc[u] = e.abase[j] + (int)f;
         src[u] = cb + j;
-        tc[u] = sm.tcost[j];
+        tc[u] = e.tcost[j];
         a[u] = make_int4(0, 0, 1, 0);
         if (ok[u]) a[u] = x.g.earc[arc[u]];
       }
       const unsigned bo = *(volatile unsigned *)&sm.best_ord;
       const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
       unsigned o = kOrdNone;
+      float nc[kU];
 #pragma unroll
       for (int u = 0; u < kU; ++u) {
-        const float nc = canon((tc[u] + __int_as_float(a[u].y)) + sm.ac[a[u].z - 1]);
-        ok[u] = ok[u] && (nc < INFINITY) && !((nc - rb) > beam);
-        dst[u] = a[u].x;
-        const unsigned oc = f2ord(nc);
-        key[u] = ((unsigned long long)oc << 32) | (unsigned)arc[u];
-        if (ok[u]) o = min(o, oc);
+        nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + e.ac[a[u].z - 1]);
+        ok[u] = ok[u] && (nc[u] < INFINITY) && !((nc[u] - rb) > beam);
+        if (ok[u]) o = min(o, f2ord(nc[u]));
       }
       // running best: wave minimum first, one LDS atomic per wave
 #pragma unroll
       for (int sft = 32; sft > 0; sft >>= 1) o = min(o, (unsigned)__shfl_xor((int)o, sft, 64));
       if ((tid & 63) == 0 && o != kOrdNone) atomicMin(&sm.best_ord, o);
-      map_update_batch(x, ok, dst, key, src);
+#pragma unroll
+      for (int u = 0; u < kU; ++u) push_cand(x, ok[u], a[u].x, nc[u], src[u], arc[u]);
     }
     __syncthreads();
   }
 }
 
+// ------------------------------------------------------------------ recombination in LDS
+// Lower the destination's table entry to this candidate if (cost, arc id) is smaller.
+// The value word carries the candidate's index, so the winner's record can be fetched
+// afterwards; exact cost ties are decided by the arc ids of the two records.
+__device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int arc, int idx) {
+  TableLds &t = x.sm.u.t;
+  unsigned s = (hash_state(dst) >> 6) & kTabMask;
+  for (;;) {
+    const int k = t.keys[s];
+    if (k == dst) break;
+    if (k == kKeyEmpty) {
+      const int old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
+      if (old == kKeyEmpty || old == dst) break;
+    }
+    s = (s + 1) & kTabMask;
+  }
+  const unsigned oc = f2ord(cost);
+  const unsigned long long mine = ((unsigned long long)oc << 32) | (unsigned)idx;
+  unsigned long long cur = t.vals[s];
+  for (;;) {
+    const unsigned cc = (unsigned)(cur >> 32);
+    bool better = oc < cc;
+    if (oc == cc && cur != kValEmpty)
+      better = (unsigned)arc < (unsigned)x.cand[(unsigned)cur].w;     // exact tie: lower arc id
+    if (!better) break;
+    const unsigned long long prev = atomicCAS(&t.vals[s], cur, mine);
+    if (prev == cur) break;
+    cur = prev;
+  }
+}
+
+// Partitions [p0, p1) form the next group: as many as fit the table.  Uniform across the block.
+__device__ __forceinline__ int next_group(const Ctx &x, int p0, int &total) {
+  int p1 = p0; total = 0;
+  while (p1 < x.c.num_parts) {
+    const int n = min(x.sm.part_cnt[p1], x.c.region_cap);
+    if (p1 > p0 && total + n > kGroupMax) break;
+    total += n; ++p1;
+  }
+  return p1;
+}
+
+__device__ __forceinline__ void table_clear(Smem &sm) {
+  for (int s = threadIdx.x; s < kTabSlots; s += kBlock) { sm.u.t.vals[s] = kValEmpty; sm.u.t.keys[s] = kKeyEmpty; }
+}
+
+// Insert every candidate of partitions [p0, p1) into the (cleared) table.
+__device__ __forceinline__ void table_fill(Ctx &x, int p0, int p1) {
+  const int tid = threadIdx.x;
+  for (int p = p0; p < p1; ++p) {
+    const int n = min(x.sm.part_cnt[p], x.c.region_cap);
+    const int base = p * x.c.region_cap;
+    for (int i0 = 0; i0 < n; i0 += kBlock * kU) {
+      int4 cd[kU];
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int i = i0 + u * kBlock + tid;
+        cd[u] = make_int4(-1, 0, 0, 0);
+        if (i < n) cd[u] = x.cand[base + i];
+      }
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int i = i0 + u * kBlock + tid;
+        if (i < n) table_insert(x, cd[u].x, __int_as_float(cd[u].y), cd[u].w, base + i);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ Prune
-// Winners of the recombination (candidate whose key is still the map entry) that are inside
+// Every occupied table slot is the recombined token of one destination state.  Those inside
 // the beam are histogrammed into 256 bins over [best, best+beam] and parked; the max-active
 // cutoff k_keep is the first bin where the running count exceeds max_active (at least 1).
-__device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &cut) {
+__device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &cut) {
   Smem &sm = x.sm;
+  TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
-  const int n_cand = min(sm.n_cand, x.c.cand_cap);
   const unsigned bo = sm.best_ord;
   cut.best = bo == kOrdNone ? INFINITY : ord2f(bo);
   cut.beam = x.s.beam; cut.scale = x.s.scale; cut.k_keep = 256;
-  for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
-    int4 cd[kU]; unsigned long long val[kU]; int state[kU]; bool act[kU];
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int i = i0 + u * kBlock + tid;
-      act[u] = i < n_cand;
-      cd[u] = make_int4(0, 0, 0, 0);
-      if (act[u]) cd[u] = x.cand[i];
-    }
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      val[u] = 0; state[u] = 0;
-      if (act[u]) { val[u] = ld_dev(&x.hash[cd[u].x].val); state[u] = ld_dev(&x.hash[cd[u].x].key); }
-    }
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const float c = __int_as_float(cd[u].z);
-      const unsigned long long key = ((unsigned long long)f2ord(c) << 32) | (unsigned)cd[u].w;
-      const bool win = act[u] && val[u] == key && cut.in_beam(c);
-      if (win) atomicAdd(&sm.hist[cut.bin(c)], 1u);
-      const int wi = wave_alloc(&sm.n_win, win);
-      if (win) {
-        if (wi < x.c.win_cap) {
-          x.win_sc[wi] = make_int2(state[u], cd[u].z);
-          x.win_pa[wi] = make_int2(cd[u].y, cd[u].w);
-          x.win_slot[wi] = cd[u].x;
-        } else atomicOr(&sm.status, kStCapacity);
+  for (int p0 = 0; p0 < x.c.num_parts;) {
+    int total;
+    const int p1 = next_group(x, p0, total);
+    if (total > kTabSlots - kBlock) { if (tid == 0) atomicOr(&sm.status, kStCapacity); total = 0; }
+    if (total > 0) {
+      table_clear(sm);
+      __syncthreads();
+      table_fill(x, p0, p1);
+      __syncthreads();
+      for (int s0 = 0; s0 < kTabSlots; s0 += kBlock) {
+        const int s = s0 + tid;
+        const int key = t.keys[s];
+        const unsigned long long v = t.vals[s];
+        const float c = ord2f((unsigned)(v >> 32));
+        const bool win = key != kKeyEmpty && cut.in_beam(c);
+        if (win) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+        const int wi = wave_alloc(&sm.n_win, win);
+        if (win) {
+          if (wi < x.c.win_cap) { x.win_sc[wi] = make_int2(key, __float_as_int(c)); x.win_ci[wi] = (int)(unsigned)v; }
+          else atomicOr(&sm.status, kStCapacity);
+        }
       }
+      __syncthreads();
     }
+    p0 = p1;
   }
   __syncthreads();
   if (tid < 64) {                       // wave 0: scan the histogram, 4 bins per lane
     unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
     unsigned s = h0 + h1 + h2 + h3, inc = s;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { unsigned t = __shfl_up(inc, o, 64); if (tid >= o) inc += t; }
+    for (int o = 1; o < 64; o <<= 1) { unsigned tt = __shfl_up(inc, o, 64); if (tid >= o) inc += tt; }
     const unsigned n_in = __shfl(inc, 63, 64);
     const unsigned ma = (unsigned)x.s.max_active;
     int kk = 256;
@@ -398,21 +412,26 @@ __device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &c
     }
     if (tid == 0) { sm.k_keep = kk; sm.n_in = (int)n_in; x.k_in += n_in; }
   }
+  if (tid < kMaxParts) sm.part_cnt[tid] = 0;
   __syncthreads();
   cut.k_keep = sm.k_keep;
+  // survivors: queue record, backpointer (from the winning candidate's record), state index
+  const unsigned tag = set_tag(x.s.epoch) << 16;
   const int n_win = min(sm.n_win, x.c.win_cap);
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kU) {
-    int2 sc[kU], pa[kU]; int ws[kU]; bool kp[kU];
+    int2 sc[kU]; int ci[kU]; bool kp[kU]; int4 rec[kU];
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
       const int i = i0 + u * kBlock + tid;
-      kp[u] = false; sc[u] = make_int2(0, 0); pa[u] = sc[u]; ws[u] = 0;
+      kp[u] = false; sc[u] = make_int2(0, 0); ci[u] = 0;
       if (i < n_win) {
         sc[u] = x.win_sc[i];
         kp[u] = cut.bin(__int_as_float(sc[u].y)) < cut.k_keep;
-        if (kp[u]) { pa[u] = x.win_pa[i]; ws[u] = x.win_slot[i]; }
+        if (kp[u]) ci[u] = x.win_ci[i];
       }
     }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) { rec[u] = make_int4(0, 0, 0, 0); if (kp[u]) rec[u] = x.cand[ci[u]]; }
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
       const int ti = wave_alloc(&sm.n_next, kp[u]);
@@ -421,8 +440,8 @@ __device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &c
         else if (lat_base + (unsigned)ti >= x.c.lat_cap) atomicOr(&sm.status, kStLattice);
         else {
           NQ[ti] = make_int4(sc[u].x, sc[u].y, 0, 0);
-          x.lat[lat_base + ti] = pa[u];
-          st_dev(&x.hash[ws[u]].tok, ti);
+          x.lat[lat_base + ti] = make_int2(rec[u].z, rec[u].w);
+          x.index[sc[u].x] = tag | (unsigned)ti;
         }
       }
     }
@@ -434,10 +453,15 @@ __device__ void prune_and_compact(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &c
 // Least fixpoint under the frozen predicate `cut`: tokens improved (or created) in one round
 // are re-expanded in the next.  The first expansion of a token also fetches its arc ranges
 // (one {emitting, epsilon} offset pair per state) and caches the emitting range in the queue
-// record for the next frame's ExpandArcs.
+// record for the next frame's ExpandArcs.  Each round's candidates are recombined in the LDS
+// table; the per-destination best is then compared with the state's existing token, found
+// through the state index.
 __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const Cutoff &cut) {
   Smem &sm = x.sm;
+  ExpandLds &e = sm.u.e;
+  TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
+  const unsigned tag = set_tag(x.s.epoch);
   int n_wl = nP, sel = 0;
   bool implicit = true;
   for (int round = 0; n_wl > 0; ++round) {
@@ -477,91 +501,94 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const C
       }
       unsigned ex0, ex1;
       const unsigned M = block_scan2(sm, deg[0], deg[1], ex0, ex1);
-      sm.pre[kTPT * tid] = ex0;              sm.pre[kTPT * tid + 1] = ex1;
-      sm.abase[kTPT * tid] = base[0] - (int)ex0; sm.abase[kTPT * tid + 1] = base[1] - (int)ex1;
-      sm.tcost[kTPT * tid] = cs[0];          sm.tcost[kTPT * tid + 1] = cs[1];
-      sm.ttok[kTPT * tid] = tk[0];           sm.ttok[kTPT * tid + 1] = tk[1];
-      if (tid == kBlock - 1) sm.pre[kChunk] = M;
+      e.pre[kTPT * tid] = ex0;              e.pre[kTPT * tid + 1] = ex1;
+      e.abase[kTPT * tid] = base[0] - (int)ex0; e.abase[kTPT * tid + 1] = base[1] - (int)ex1;
+      e.tcost[kTPT * tid] = cs[0];          e.tcost[kTPT * tid + 1] = cs[1];
+      e.ttok[kTPT * tid] = tk[0];           e.ttok[kTPT * tid + 1] = tk[1];
+      if (tid == kBlock - 1) e.pre[kChunk] = M;
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-        bool ok[kU]; int dst[kU], src[kU]; unsigned long long key[kU];
-        int2 a[kU]; int arc[kU]; float tc[kU];
+        bool ok[kU]; int src[kU]; int2 a[kU]; int arc[kU]; float tc[kU];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           const unsigned f = f0 + u * kBlock + tid;
           ok[u] = f < M;
           const int j = ok[u] ? owner_of(sm, f) : 0;
-          arc[u] = sm.abase[j] + (int)f;
-          src[u] = sm.ttok[j];
-          tc[u] = sm.tcost[j];
+          arc[u] = e.abase[j] + (int)f;
+          src[u] = e.ttok[j];
+          tc[u] = e.tcost[j];
           a[u] = make_int2(0, 0);
           if (ok[u]) a[u] = x.g.xarc[arc[u]];
         }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           const float nc = canon(tc[u] + __int_as_float(a[u].y));
-          ok[u] = ok[u] && (nc < INFINITY) && cut.keep(nc);
-          dst[u] = a[u].x;
-          key[u] = ((unsigned long long)f2ord(nc) << 32) | (unsigned)(x.g.Ae + arc[u]);
+          push_cand(x, ok[u] && (nc < INFINITY) && cut.keep(nc), a[u].x, nc, src[u], x.g.Ae + arc[u]);
         }
-        map_update_batch(x, ok, dst, key, src);
       }
       __syncthreads();
     }
     if (my_x) atomicAdd((unsigned long long *)&sm.xarcs, (unsigned long long)my_x);
-    // winners of this round update their token in place (or create it) and are re-queued
-    const int n_cand = min(sm.n_cand, x.c.cand_cap);
-    for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
-      int4 cd[kU]; unsigned long long val[kU]; int tok[kU], state[kU]; bool act[kU];
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int i = i0 + u * kBlock + tid;
-        act[u] = i < n_cand;
-        cd[u] = make_int4(0, 0, 0, 0);
-        if (act[u]) cd[u] = x.cand[i];
-      }
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        val[u] = 0; tok[u] = -1; state[u] = 0;
-        if (act[u]) {
-          val[u] = ld_dev(&x.hash[cd[u].x].val);
-          tok[u] = ld_dev(&x.hash[cd[u].x].tok);
-          state[u] = ld_dev(&x.hash[cd[u].x].key);
+    // this round's best candidate per destination updates the state's token in place, or
+    // creates it; either way the token is expanded again in the next round
+    for (int p0 = 0; p0 < x.c.num_parts;) {
+      int total;
+      const int p1 = next_group(x, p0, total);
+      if (total > kTabSlots - kBlock) { if (tid == 0) atomicOr(&sm.status, kStCapacity); total = 0; }
+      if (total > 0) {
+        table_clear(sm);
+        __syncthreads();
+        table_fill(x, p0, p1);
+        __syncthreads();
+        for (int s0 = 0; s0 < kTabSlots; s0 += kBlock) {
+          const int s = s0 + tid;
+          const int d = t.keys[s];
+          const unsigned long long v = t.vals[s];
+          const bool occ = d != kKeyEmpty;
+          int4 rec = make_int4(0, 0, 0, 0); unsigned ix = 0;
+          if (occ) { rec = x.cand[(unsigned)v]; ix = x.index[d]; }
+          const bool exists = occ && (ix >> 16) == tag;
+          int tok = (int)(ix & 0xffffu);
+          bool better = occ;
+          if (exists) {
+            const float oc = __int_as_float(NQ[tok].y);
+            const float nc = __int_as_float(rec.y);
+            const unsigned oa = (unsigned)x.lat[lat_base + tok].y;
+            better = nc < oc || (nc == oc && (unsigned)rec.w < oa);
+          }
+          const bool fresh = occ && !exists;
+          const int ni = wave_alloc(&sm.n_next, fresh);
+          if (fresh) tok = ni;
+          bool good = better;
+          if (better) {
+            if (tok >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
+            else if (lat_base + (unsigned)tok >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+          }
+          if (good) {
+            if (fresh) x.index[d] = (tag << 16) | (unsigned)tok;
+            *reinterpret_cast<int2 *>(&NQ[tok]) = make_int2(d, rec.y);
+            x.lat[lat_base + tok] = make_int2(rec.z, rec.w);
+          }
+          const int wi = wave_alloc(&sm.n_wl_next, good);
+          if (good) WLN[wi] = tok | (fresh ? 0x80000000 : 0);
         }
+        __syncthreads();
       }
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const unsigned long long key = ((unsigned long long)f2ord(__int_as_float(cd[u].z)) << 32) | (unsigned)cd[u].w;
-        const bool win = act[u] && val[u] == key;
-        const bool fresh = win && tok[u] < 0;
-        const int ni = wave_alloc(&sm.n_next, fresh);
-        int t = fresh ? ni : tok[u];
-        bool good = win;
-        if (win) {
-          if (t >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
-          else if (lat_base + (unsigned)t >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
-        }
-        if (good) {
-          if (fresh) st_dev(&x.hash[cd[u].x].tok, t);
-          *reinterpret_cast<int2 *>(&NQ[t]) = make_int2(state[u], cd[u].z);
-          x.lat[lat_base + t] = make_int2(cd[u].y, cd[u].w);
-        }
-        const int wi = wave_alloc(&sm.n_wl_next, good);
-        if (good) WLN[wi] = t | (fresh ? 0x80000000 : 0);
-      }
+      p0 = p1;
     }
     __syncthreads();
     n_wl = min(sm.n_wl_next, x.c.qcap);
     const bool stop = sm.status != 0;
     __syncthreads();
-    if (tid == 0) { sm.n_wl_next = 0; sm.n_cand = 0; }
+    if (tid == 0) sm.n_wl_next = 0;
+    if (tid < kMaxParts) sm.part_cnt[tid] = 0;
     __syncthreads();
     if (stop) break;
     sel ^= 1; implicit = false;
   }
 }
 
-// Close the token set in NQ, publish it as A_f (f = x.s.frame), clear the state map.
+// Publish the closed token set in NQ as A_f (f = x.s.frame).
 // Returns true (uniformly) if an overflow was flagged and the channel has to stop.
 __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
   Smem &sm = x.sm;
@@ -576,35 +603,33 @@ __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
     }
     if (s) atomicAdd(&sm.red64, s);
   }
-  const int n_claim = min(sm.n_claim, x.c.claim_cap);
-  for (int i0 = 0; i0 < n_claim; i0 += kBlock * kU) {
-    int sl[kU];
-#pragma unroll
-    for (int u = 0; u < kU; ++u) { const int i = i0 + u * kBlock + tid; sl[u] = i < n_claim ? x.claim[i] : -1; }
-#pragma unroll
-    for (int u = 0; u < kU; ++u)
-      if (sl[u] >= 0) {
-        HashEntry *e = &x.hash[sl[u]];
-        st_dev(&e->val, kValEmpty);
-        st_dev(reinterpret_cast<unsigned long long *>(&e->key), ~0ull);   // key = -1, tok = -1
-      }
-  }
   __syncthreads();
   if (tid == 0) {
     x.frame_off[f] = lat_base;
     x.frame_off[f + 1] = lat_base + (unsigned)n;
     if (x.dig_sum) { x.dig_sum[f] = sm.red64; x.dig_cnt[f] = n; }
     x.k_stored += n;
-    sm.red64 = 0; sm.n_claim = 0; sm.n_cand = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.red64 = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
     sm.best_ord = kOrdNone;
   }
   if (tid < 256) sm.hist[tid] = 0;
+  if (tid < kMaxParts) sm.part_cnt[tid] = 0;
   x.s.lat_used = lat_base + (unsigned)n;
   x.s.n_tok = n;
   x.s.cur ^= 1;
+  x.s.epoch++;
   const bool stop = sm.status != 0;     // nobody writes status between these two barriers
   __syncthreads();
   return stop;
+}
+
+// The state index is tagged with epoch % 65535 + 1: when the tag is about to repeat, entries
+// written 65535 sets ago would look current again, so the whole index is zeroed first.
+__device__ void renew_index_if_wrapping(Ctx &x) {
+  if (x.s.epoch != 0 && x.s.epoch % 65535u == 0) {
+    for (int s = threadIdx.x; s < x.g.S; s += kBlock) x.index[s] = 0;
+    __syncthreads();
+  }
 }
 
 // ------------------------------------------------------------------ final choice + traceback
@@ -684,14 +709,12 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
   const int tid = threadIdx.x;
   const int ch = a.chan[blockIdx.x], nfr = a.nfr[blockIdx.x], io = a.io[blockIdx.x];
   Ctx x{g, c, sm};
-  x.hash = c.hash + (size_t)ch * c.hash_cap;
-  x.claim = c.claim + (size_t)ch * c.claim_cap;
-  x.cand = c.cand + (size_t)ch * c.cand_cap;
+  x.cand = c.cand + (size_t)ch * c.num_parts * c.region_cap;
   x.win_sc = c.win_sc + (size_t)ch * c.win_cap;
-  x.win_pa = c.win_pa + (size_t)ch * c.win_cap;
-  x.win_slot = c.win_slot + (size_t)ch * c.win_cap;
+  x.win_ci = c.win_ci + (size_t)ch * c.win_cap;
   x.q[0] = c.queue + (size_t)ch * 2 * c.qcap; x.q[1] = x.q[0] + c.qcap;
   x.wl[0] = c.wl + (size_t)ch * 2 * c.qcap;   x.wl[1] = x.wl[0] + c.qcap;
+  x.index = c.index + (size_t)ch * g.S;
   x.lat = c.lattice + (size_t)ch * c.lat_cap;
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
@@ -699,10 +722,11 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
   x.s = c.st[ch];
 
   if (tid == 0) {
-    sm.best_ord = kOrdNone; sm.n_claim = 0; sm.n_cand = 0; sm.n_win = 0; sm.n_next = 0;
-    sm.n_wl_next = 0; sm.status = 0; sm.red64 = 0; sm.xarcs = 0; sm.k_keep = 256; sm.n_in = 0;
+    sm.best_ord = kOrdNone; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0; sm.n_tab = 0;
+    sm.status = 0; sm.red64 = 0; sm.xarcs = 0; sm.k_keep = 256; sm.n_in = 0;
   }
   if (tid < 256) sm.hist[tid] = 0;
+  if (tid < kMaxParts) sm.part_cnt[tid] = 0;
   __syncthreads();
 
   bool stop = false;
@@ -710,15 +734,12 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
     // start token, closed over epsilon arcs with best = 0 and no bin limit
     x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active;
+    renew_index_if_wrapping(x);
     int4 *NQ = x.q[1];
     if (tid == 0) {
-      const int slot = (int)map_home(x, g.start);      // the map is empty: the home slot is free
-      st_dev(&x.hash[slot].key, g.start);
-      st_dev(&x.hash[slot].val, ((unsigned long long)f2ord(0.0f) << 32) | 0xFFFFFFFFull);
-      st_dev(&x.hash[slot].tok, 0);
-      x.claim[0] = slot; sm.n_claim = 1;
       NQ[0] = make_int4(g.start, __float_as_int(0.0f), 0, 0);
       x.lat[0] = make_int2(-1, -1);
+      x.index[g.start] = (set_tag(x.s.epoch) << 16) | 0u;
       sm.n_next = 1;
     }
     __syncthreads();
@@ -731,8 +752,9 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
   for (int t = 0; t < nfr; ++t) {
     if (stop || x.s.status) break;
     if (x.s.frame >= c.max_frames) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
+    renew_index_if_wrapping(x);
     const float *row = ll + (long long)t * a.V;
-    for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -row[v];
+    for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
     __syncthreads();
     const int4 *Q = x.q[x.s.cur];
     int4 *NQ = x.q[x.s.cur ^ 1];
@@ -740,9 +762,7 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
     if (tid == 0) { x.k_tok += x.s.n_tok; x.k_frames++; }
     emit_expand(x, Q, x.s.n_tok);
     Cutoff cut;
-    prune_and_compact(x, NQ, lat_base, cut);
-    if (tid == 0) { sm.n_cand = 0; }
-    __syncthreads();
+    recombine_and_prune(x, NQ, lat_base, cut);
     const int nP = min(sm.n_next, c.qcap);
     eps_closure(x, NQ, lat_base, nP, cut);
     x.s.frame++;
@@ -752,14 +772,6 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
   if (sm.status) {            // overflow: the channel stops with an empty token set
     x.s.status |= sm.status;
     x.s.n_tok = 0;
-    // leave the state map clean for the next init
-    const int n_claim = min(sm.n_claim, c.claim_cap);
-    for (int i = tid; i < n_claim; i += kBlock) {
-      HashEntry *e = &x.hash[x.claim[i]];
-      st_dev(&e->val, kValEmpty);
-      st_dev(reinterpret_cast<unsigned long long *>(&e->key), ~0ull);
-    }
-    __syncthreads();
   }
   if (a.mode & kModeFinal) select_and_trace(x, a, io);
   if (tid == 0) {
@@ -773,12 +785,6 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
     atomicAdd((unsigned long long *)&c.counters[6], (unsigned long long)x.k_bin0);
     atomicAdd((unsigned long long *)&c.counters[7], (unsigned long long)x.k_frames);
   }
-}
-
-__global__ void fill_hash_kernel(HashEntry *h, size_t n) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) { h[i].val = kValEmpty; h[i].key = kKeyEmpty; h[i].tok = -1; }
 }
 
 }  // namespace
@@ -915,13 +921,14 @@ int alloc_channels(wfst_decoder *d) {
   DevChannels &c = d->c;
   const size_t N = (size_t)o.max_channels;
   const int ma = o.max_active_hint > 0 ? o.max_active_hint : 10000;
-  c.hash_cap = o.state_map_capacity > 0 ? o.state_map_capacity : next_pow2(std::max<int64_t>(8192, 32LL * ma));
-  c.hash_mask = (unsigned)c.hash_cap - 1u;
-  c.claim_limit = c.hash_cap / 2 - kBlock;
-  c.claim_cap = c.hash_cap / 2;
-  c.cand_cap = c.hash_cap;
-  c.win_cap = c.claim_cap;
-  c.qcap = c.claim_cap;
+  // candidate partitions: enough that a frame with ~8 candidates per kept token still fits
+  c.num_parts = o.num_partitions > 0 ? o.num_partitions
+                                     : std::min(kMaxParts, std::max(4, next_pow2((8LL * ma + 2047) / 2048)));
+  c.part_shift = 32;
+  for (int p = c.num_parts; p > 1; p >>= 1) c.part_shift--;
+  c.region_cap = kTabSlots;
+  c.win_cap = std::min(c.num_parts * c.region_cap, 262144);
+  c.qcap = std::min(kQueueMax, std::max(8192, next_pow2(4LL * ma)));
   c.max_frames = o.max_frames_per_channel;
   int64_t lat_bytes = o.lattice_bytes_per_channel > 0 ? o.lattice_bytes_per_channel
                                                       : (int64_t)(8.0 * 1.5 * ma * ((double)c.max_frames + 1.0));
@@ -930,12 +937,10 @@ int alloc_channels(wfst_decoder *d) {
   c.lat_cap = (unsigned)lat_entries;
   int rc;
   if ((rc = dev_alloc(d, &c.st, N))) return rc;
-  if ((rc = dev_alloc(d, &c.hash, N * c.hash_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.claim, N * c.claim_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.cand, N * c.cand_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.cand, N * (size_t)c.num_parts * c.region_cap))) return rc;
   if ((rc = dev_alloc(d, &c.win_sc, N * c.win_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.win_pa, N * c.win_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.win_slot, N * c.win_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.win_ci, N * c.win_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.index, N * (size_t)d->g.S))) return rc;
   if ((rc = dev_alloc(d, &c.queue, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
@@ -948,8 +953,7 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipMemset(c.st, 0, N * sizeof(ChanState)));
   HIP_TRY(d, hipMemset(c.counters, 0, 8 * sizeof(long long)));
   HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
-  fill_hash_kernel<<<2048, 256>>>(c.hash, N * (size_t)c.hash_cap);
-  HIP_TRY(d, hipGetLastError());
+  HIP_TRY(d, hipMemset(c.index, 0, N * (size_t)d->g.S * sizeof(unsigned)));   // tag 0 = no token
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
   if (o.outputs_on_host) {
     if ((rc = dev_alloc(d, &d->o_words, N * (size_t)o.max_words))) return rc;
@@ -995,8 +999,9 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
   *out = nullptr;
   if (opts->max_channels < 1 || opts->max_frames_per_channel < 1 || opts->max_words < 1)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "max_channels, max_frames_per_channel and max_words must be >= 1");
-  if (opts->state_map_capacity && (opts->state_map_capacity < 8192 || (opts->state_map_capacity & (opts->state_map_capacity - 1))))
-    return fail(nullptr, WFST_ERR_INVALID_ARG, "state_map_capacity must be a power of two >= 8192");
+  if (opts->num_partitions && (opts->num_partitions < 2 || opts->num_partitions > kMaxParts ||
+                               (opts->num_partitions & (opts->num_partitions - 1))))
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "num_partitions must be a power of two in [2, 64]");
   if (graph->num_classes > kMaxV)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "num_classes above " + std::to_string(kMaxV));
   std::string why; int64_t Ae = 0, Ax = 0;
