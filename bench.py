@@ -106,6 +106,13 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     counters = dec.get_counters() // max(1, args.steps)
+    ticks = dec.debug_phase_ticks()
+    names = ["expand", "recombine", "cutoff+compact", "eps_expand", "eps_recombine", "publish", "trace", "other",
+             "tab_clear", "tab_fill", "tab_scan", "eps_tab_fill", "eps_tab_scan", "-", "-", "-"]
+    print("[bench] phase share of workgroup time: " +
+          ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks)) +
+          f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / (args.steps + args.warmup):.1f} ms",
+          file=sys.stderr, flush=True)
     flags = out[3].cpu().numpy()
     assert not (flags & (8 | 16)).any(), "an utterance overflowed a buffer: the run is invalid"
 

@@ -75,7 +75,7 @@ typedef struct {
   int64_t lattice_bytes_per_channel; /* 0 = 8 B * max_frames * 1.5 * max_active_hint */
   int32_t outputs_on_host;        /* 0: outputs are device pointers; 1: host pointers */
   int32_t max_active_hint;        /* sizes the per-channel work buffers; 0 = 10000 */
-  int32_t num_partitions;         /* candidate partitions per channel: power of two in [2,64], 0 = derived */
+  int32_t candidate_capacity;     /* candidate records per channel and frame, 0 = 16 * max_active_hint */
   int32_t record_digests;         /* 1: keep per-frame token-set digests (slower; for tests) */
 } wfst_opts;
 
@@ -140,7 +140,7 @@ int32_t wfst_get_partial(wfst_decoder *dec, int32_t ch, int32_t finalize, int32_
  *   wfst_debug_get_tokens: current token set of channel ch (any order).
  *   wfst_get_counters: sums over all channels since create or the last reset:
  *     [0] tokens expanded, [1] emitting arcs out of them, [2] epsilon arcs out of every
- *     closed token set, [3] tokens in the beam after recombination, [4] tokens stored,
+ *     closed token set, [3] tokens surviving the prune step (before the closure), [4] tokens stored,
  *     [5] frames where max-active pruned, [6] frames where bin 0 alone exceeded max-active,
  *     [7] frames decoded.   reset != 0 zeroes them after reading.
  */
@@ -149,6 +149,17 @@ int32_t wfst_debug_frame_digests(wfst_decoder *dec, int32_t ch, uint64_t *digest
 int32_t wfst_debug_get_tokens(wfst_decoder *dec, int32_t ch, int32_t *states, float *costs,
                               int32_t cap, int32_t *n);
 int32_t wfst_get_counters(wfst_decoder *dec, int64_t counters[8], int32_t reset);
+
+/*
+ * Where the channel workgroups spend their time: sums over all channels of 100 MHz
+ * wall-clock ticks per phase since create or the last reset (HOST output, synchronises):
+ *   [0] ExpandArcs over emitting arcs, [1] recombination, [2] cutoff + compaction,
+ *   [3] epsilon expansion, [4] epsilon recombination, [5] publishing the token set,
+ *   [6] final choice + traceback, [7] everything else (row staging, init);
+ *   [8..12] split of [1] and [4]: table clear, fill, scan; epsilon table clear+fill, scan
+ *   (these are counted instead of, not on top of, [1] and [4]); [13..15] unused.
+ */
+int32_t wfst_debug_phase_ticks(wfst_decoder *dec, int64_t ticks[16], int32_t reset);
 
 /* Device memory the decoder holds, in bytes (graph + channel state). */
 int64_t wfst_device_bytes(const wfst_decoder *dec);

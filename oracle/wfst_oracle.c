@@ -80,8 +80,8 @@ typedef struct {
   int64_t counters[8];     /* see README of counters below */
 } oracle_result;
 /* counters: 0 sum |A_t| over expanded frames, 1 emitting arcs out of those sets,
- * 2 epsilon arcs out of every closed set (initial one included), 3 tokens in the beam after
- * recombination, 4 tokens stored (all closed sets), 5 frames where max-active pruned,
+ * 2 epsilon arcs out of every closed set (initial one included), 3 tokens that survive the
+ * prune step (before the epsilon closure), 4 tokens stored (all closed sets), 5 frames where max-active pruned,
  * 6 frames where bin 0 alone exceeded max_active, 7 recombined destinations before pruning */
 
 enum { FLAG_FINAL = 1, FLAG_TRUNC = 2, FLAG_DEAD = 4 };
@@ -363,7 +363,6 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     int32_t n_in = 0;
     for (int32_t i = 0; i < nxt.n; ++i)
       if ((nxt.t[i].cost - best) <= k.beam) { hist[bin_of(nxt.t[i].cost, &k)]++; ++n_in; }
-    res->counters[3] += n_in;
     if (n_in > o->max_active) {
       int64_t run = 0; int32_t ks = 256;
       for (int32_t j = 0; j < 256; ++j) { run += hist[j]; if (run > o->max_active) { ks = j; break; } }
@@ -376,6 +375,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       else map[nxt.t[i].state] = -1;
     }
     nxt.n = m;
+    res->counters[3] += m;
     /* ---- epsilon closure under the frozen predicate (R6) */
     eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1);
     { tokvec tmp = cur; cur = nxt; nxt = tmp; }

@@ -20,7 +20,7 @@ FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPAC
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_init_channel",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_debug_frame_digests",
-           "wfst_debug_get_tokens", "wfst_get_counters", "wfst_device_bytes",
+           "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
 
 
@@ -41,7 +41,7 @@ class wfst_opts(C.Structure):
     _fields_ = [("max_channels", C.c_int32), ("max_frames_per_channel", C.c_int32),
                 ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
                 ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
-                ("num_partitions", C.c_int32), ("record_digests", C.c_int32)]
+                ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32)]
 
 
 _lib = None
@@ -58,7 +58,7 @@ def load_library():
     # PyTorch ships its own HIP runtime; import it first so that this library binds to the
     # same libamdhip64 instance (two runtimes in one process do not share the device).
     import torch  # noqa: F401
-    lib = C.CDLL(LIB_PATH)
+    lib = C.CDLL(os.environ.get("WFST_DECODER_LIB", LIB_PATH))   # override: tuning builds only
     p, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     lib.wfst_decoder_create.argtypes = [C.POINTER(wfst_graph_csr), C.POINTER(wfst_opts), C.POINTER(p)]
     lib.wfst_decoder_destroy.argtypes = [p]
@@ -69,13 +69,14 @@ def load_library():
     lib.wfst_debug_frame_digests.argtypes = [p, i32, p, p, i32, p]
     lib.wfst_debug_get_tokens.argtypes = [p, i32, p, p, i32, p]
     lib.wfst_get_counters.argtypes = [p, p, i32]
+    lib.wfst_debug_phase_ticks.argtypes = [p, p, i32]
     lib.wfst_device_bytes.argtypes = [p]
     lib.wfst_device_bytes.restype = i64
     lib.wfst_last_kernel_ms.argtypes = [p]
     lib.wfst_last_kernel_ms.restype = f32
     lib.wfst_last_error.argtypes = [p]
     lib.wfst_last_error.restype = C.c_char_p
-    for name in EXPORTS[:9]:
+    for name in EXPORTS[:10]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -91,7 +92,7 @@ class Decoder:
     """Owns one wfst_decoder handle.  Method names mirror the C entry points."""
 
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
-                 lattice_bytes_per_channel=0, outputs_on_host=False, num_partitions=0,
+                 lattice_bytes_per_channel=0, outputs_on_host=False, candidate_capacity=0,
                  record_digests=False):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
@@ -103,7 +104,7 @@ class Decoder:
         g = wfst_graph_csr(graph.num_states, graph.start_state, graph.num_classes, int(arrs[0][-1]),
                            *[None if a is None else a.ctypes.data for a in arrs])
         self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
-                              int(outputs_on_host), max_active_hint, num_partitions,
+                              int(outputs_on_host), max_active_hint, candidate_capacity,
                               int(record_digests))
         self.V = graph.num_classes
         self.max_words = max_words
@@ -205,6 +206,11 @@ class Decoder:
         c = np.zeros(8, np.int64)
         self._check(self.lib.wfst_get_counters(self.h, c.ctypes.data, int(reset)))
         return c
+
+    def debug_phase_ticks(self, reset=False):
+        t = np.zeros(16, np.int64)
+        self._check(self.lib.wfst_debug_phase_ticks(self.h, t.ctypes.data, int(reset)))
+        return t
 
     def device_bytes(self):
         return int(self.lib.wfst_device_bytes(self.h))

@@ -11,17 +11,19 @@
 // Recombination (one token per destination state, lowest (cost, arc id) wins) uses NO global
 // atomics: measured on MI355X, 64-bit global atomics top out near 25 G/s for the whole chip,
 // which bounded an earlier global-hash design.  Instead ExpandArcs appends candidates
-// {dst, cost, source token, arc} to per-partition regions of a candidate buffer (partition =
-// hash of the destination state), and each group of partitions is then reduced in an
-// open-addressing table that lives in LDS (160 KB per CU on gfx950), with LDS compare-and-swap.
-// A dense per-state index (tagged with the frame epoch, so it never needs clearing) answers
-// "does this state already have a token" for the epsilon closure.
+// {dst, cost, source token, arc} to a flat buffer (wave-aggregated, so the stores coalesce);
+// a histogram of the candidate costs selects the few that can survive max-active, and those
+// are reduced in an open-addressing table that lives in LDS (160 KB per CU on gfx950) with
+// LDS compare-and-swap, in as many passes (by hash range of the destination) as the table
+// needs.  A dense per-state index (tagged with the frame epoch, so it never needs clearing)
+// answers "does this state already have a token" for the epsilon closure.
 //
 // Per channel, in HBM:
 //   token queue   2 x qcap records {state, cost, first emitting arc, emitting degree}
-//   candidates    num_parts x region_cap records {dst state, cost, source token, arc id}
+//   candidates    cand_cap records {dst state, cost, source token, arc id}
 //   winners       recombined in-beam tokens before the max-active cutoff is known
 //   state index   S x 4 B: (epoch tag << 16) | token index
+//   worklists     2 x qcap records {token, first epsilon arc, epsilon degree}
 //   lattice       {prev token, arc id} per stored token, frame after frame
 // LDS holds, per phase, either the expansion tables (negated log-likelihood row and, per chunk
 // of 2048 tokens, the prefix sums of their arc counts so that every lane owns one arc of the
@@ -43,14 +45,21 @@ namespace {
 
 constexpr int kBlock = 1024;
 constexpr int kWaves = kBlock / 64;
-constexpr int kTPT = 2;                       // tokens per thread per chunk
+#ifndef WFST_TPT
+#define WFST_TPT 2
+#endif
+#ifndef WFST_U
+#define WFST_U 2
+#endif
+constexpr int kTPT = WFST_TPT;                // work items per thread per chunk (1, 2 or 4)
 constexpr int kChunk = kBlock * kTPT;
+constexpr int kChunkLog2 = kTPT == 4 ? 12 : (kTPT == 2 ? 11 : 10);
+static_assert((1 << kChunkLog2) == kChunk, "owner_of searches log2(kChunk) levels");
 constexpr int kMaxV = 2048;
-constexpr int kU = 4;                         // independent memory requests per lane per phase
+constexpr int kU = WFST_U;                    // independent memory requests per lane per phase
 constexpr int kTabSlots = 8192;               // LDS recombination table
 constexpr unsigned kTabMask = kTabSlots - 1;
-constexpr int kGroupMax = 5120;               // candidates reduced per table pass (load <= 0.63)
-constexpr int kMaxParts = 64;
+constexpr int kGroupTarget = 4608;            // mean candidates reduced per table pass (load 0.56)
 constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
@@ -67,10 +76,12 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   int max_active;
   float beam, scale;          // scale = 256 / beam, computed once on the host
   unsigned epoch;             // closed sets published since create (tags the state index)
+  float sel_ratio;            // candidates taken into recombination per max_active (adaptive)
 };
 
 struct DevGraph {
-  const int2 *off2;           // [S+1] {first emitting arc, first epsilon arc}
+  const int4 *state;          // [S] {first emitting arc, first epsilon arc, emitting degree,
+                              //      epsilon degree | sign bit: some epsilon arc enters this state}
   const int4 *earc;           // [Ae]  {next state, weight bits, ilabel, olabel}
   const int2 *xarc;           // [Ax]  {next state, weight bits}
   const int *olabel;          // [Ae+Ax] by global arc id (traceback only)
@@ -80,15 +91,15 @@ struct DevGraph {
 
 struct DevChannels {
   ChanState *st;
-  int4 *cand;       int num_parts, part_shift, region_cap;   // [num_parts][region_cap]
-  int2 *win_sc;     int *win_ci; int win_cap;
-  int4 *queue;      int qcap;
-  int *wl;
-  unsigned *index;  // [S] per channel
-  int2 *lattice;    unsigned lat_cap;
+  int4 *cand;       int cand_cap;              // {dst state, cost, source token, arc id}
+  int2 *win_sc;     int *win_ci; int win_cap;  // recombined tokens before the max-active cutoff
+  int4 *queue;      int qcap;                  // 2 buffers {state, cost, first emitting arc, degree}
+  int4 *wl;                                    // 2 buffers {token, first epsilon arc, degree, -}
+  unsigned *index;                             // [S] (epoch tag << 16) | token index
+  int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
-  long long *counters;                         // [8]
+  long long *counters;                         // [24]: 8 workload counters, 16 phase tick sums
 };
 
 struct LaunchArgs {
@@ -114,11 +125,13 @@ struct Smem {
   union { ExpandLds e; TableLds t; } u;
   unsigned hist[256];
   unsigned wave_tot[kWaves];
-  int part_cnt[kMaxParts];
   unsigned best_ord;
-  int n_win, n_next, n_wl_next, n_tab, status, k_keep, n_in;
+  int n_cand, n_win, n_next, n_wl_next, status;
+  int k_sel, n_sel, k_keep, redo;
   unsigned long long red64, red64b;
-  long long xarcs;
+  long long ctr[8];
+  long long prof[16];         // wall-clock ticks per phase (thread 0)
+  long long prof_t0;
   int sel_idx;
 };
 
@@ -139,7 +152,14 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   return x ^ (x >> 31);
 }
 
-// Index from an LDS counter for every lane with pred set; one LDS atomic per wave.
+// Values read from LDS or global memory that are the same in every lane: tell the compiler,
+// so that they live in scalar registers and control flow on them is scalar.
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+
+// Index from an LDS counter for every lane with pred set; one LDS atomic per wave, and the
+// lanes of a wave get consecutive indices (their stores coalesce).
 __device__ __forceinline__ int wave_alloc(int *counter, bool pred) {
   int idx = -1;
   if (pred) {
@@ -170,21 +190,35 @@ struct Cutoff {
 struct Ctx {                  // block-uniform view of one channel
   const DevGraph &g; const DevChannels &c; Smem &sm;
   int4 *cand; int2 *win_sc; int *win_ci;
-  int4 *q[2]; int *wl[2]; unsigned *index; int2 *lat; unsigned *frame_off;
+  int4 *q0; int4 *wl0; unsigned *index; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
-  // per-launch counters (thread 0 accumulates the uniform ones)
-  long long k_tok = 0, k_earc = 0, k_in = 0, k_stored = 0, k_maxact = 0, k_bin0 = 0, k_frames = 0;
 };
+// workload counters of this launch, kept in LDS (thread 0 adds the block-uniform ones)
+enum { kCtTok = 0, kCtEarc, kCtXarc, kCtKept, kCtStored, kCtMaxAct, kCtBin0, kCtFrames };
+
+// Phase timing with the constant-rate wall clock (thread 0 only; a few scalar reads per frame).
+enum { kPhExpand = 0, kPhSelect, kPhCutoff, kPhEpsExpand, kPhEpsRecombine, kPhFinish, kPhTrace, kPhOther,
+       kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan };
+__device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
+  if (threadIdx.x == 0) {
+    const long long now = (long long)wall_clock64();
+    sm.prof[phase] += now - sm.prof_t0;
+    sm.prof_t0 = now;
+  }
+}
 
 // Tag of the token set under construction; 0 is never a valid tag (the index starts zeroed).
 __device__ __forceinline__ unsigned set_tag(unsigned epoch) { return epoch % 65535u + 1u; }
 
-// Block-wide exclusive scan of two values per thread (thread t owns items 2t, 2t+1).
-__device__ __forceinline__ unsigned block_scan2(Smem &sm, unsigned d0, unsigned d1,
-                                                unsigned &ex0, unsigned &ex1) {
+// Block-wide exclusive scan of kTPT values per thread (thread t owns items kTPT*t ..).
+// Returns the total; ex[k] receives the exclusive prefix of the thread's k-th item.
+__device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[kTPT], unsigned (&ex)[kTPT]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  unsigned s = d0 + d1, inc = s;
+  unsigned s = 0;
+#pragma unroll
+  for (int k = 0; k < kTPT; ++k) s += d[k];
+  unsigned inc = s;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
     unsigned t = __shfl_up(inc, o, 64);
@@ -199,28 +233,28 @@ __device__ __forceinline__ unsigned block_scan2(Smem &sm, unsigned d0, unsigned 
     if (w < wave) base += t;
     total += t;
   }
-  ex0 = base + inc - s;
-  ex1 = ex0 + d0;
-  return total;
+  unsigned run = base + inc - s;
+#pragma unroll
+  for (int k = 0; k < kTPT; ++k) { ex[k] = run; run += d[k]; }
+  return uni(total);
 }
 
-// Which of the chunk's tokens owns flattened arc f: last j with pre[j] <= f.
+// Which of the chunk's work items owns flattened arc f: last j with pre[j] <= f.
 __device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
   int lo = 0, hi = kChunk;
 #pragma unroll
-  for (int it = 0; it < 11; ++it) {
+  for (int it = 0; it < kChunkLog2; ++it) {
     int mid = (lo + hi) >> 1;
     if (sm.u.e.pre[mid] <= f) lo = mid; else hi = mid;
   }
   return lo;
 }
 
-// Append one candidate to the region of its destination's partition.
+// Append one candidate; the lanes of a wave write consecutive 16-byte records.
 __device__ __forceinline__ void push_cand(Ctx &x, bool ok, int dst, float nc, int src, int arc) {
+  const int ci = wave_alloc(&x.sm.n_cand, ok);
   if (ok) {
-    const int p = (int)(hash_state(dst) >> x.c.part_shift);
-    const int off = atomicAdd(&x.sm.part_cnt[p], 1);
-    if (off < x.c.region_cap) x.cand[p * x.c.region_cap + off] = make_int4(dst, __float_as_int(nc), src, arc);
+    if (ci < x.c.cand_cap) x.cand[ci] = make_int4(dst, __float_as_int(nc), src, arc);
     else atomicOr(&x.sm.status, kStCapacity);
   }
 }
@@ -236,18 +270,24 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
   const int tid = threadIdx.x;
   const float beam = x.s.beam;
   for (int cb = 0; cb < n_tok; cb += kChunk) {
-    const int i0 = cb + kTPT * tid;
-    int4 t0 = make_int4(0, 0, 0, 0), t1 = t0;
-    if (i0 < n_tok) t0 = Q[i0];
-    if (i0 + 1 < n_tok) t1 = Q[i0 + 1];
-    unsigned ex0, ex1;
-    const unsigned M = block_scan2(sm, (unsigned)t0.w, (unsigned)t1.w, ex0, ex1);
-    e.pre[kTPT * tid] = ex0;          e.pre[kTPT * tid + 1] = ex1;
-    e.abase[kTPT * tid] = t0.z - (int)ex0; e.abase[kTPT * tid + 1] = t1.z - (int)ex1;
-    e.tcost[kTPT * tid] = __int_as_float(t0.y); e.tcost[kTPT * tid + 1] = __int_as_float(t1.y);
+    int4 tk[kTPT]; unsigned deg[kTPT], ex[kTPT];
+#pragma unroll
+    for (int k = 0; k < kTPT; ++k) {
+      const int i = cb + kTPT * tid + k;
+      tk[k] = make_int4(0, 0, 0, 0);
+      if (i < n_tok) tk[k] = Q[i];
+      deg[k] = (unsigned)tk[k].w;
+    }
+    const unsigned M = block_scan(sm, deg, ex);
+#pragma unroll
+    for (int k = 0; k < kTPT; ++k) {
+      e.pre[kTPT * tid + k] = ex[k];
+      e.abase[kTPT * tid + k] = tk[k].z - (int)ex[k];
+      e.tcost[kTPT * tid + k] = __int_as_float(tk[k].y);
+    }
     if (tid == kBlock - 1) e.pre[kChunk] = M;
     __syncthreads();
-    if (tid == 0) x.k_earc += M;
+    if (tid == 0) sm.ctr[kCtEarc] += M;
     for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
       bool ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU];
 #pragma unroll
@@ -289,6 +329,7 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
 __device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int arc, int idx) {
   TableLds &t = x.sm.u.t;
   unsigned s = (hash_state(dst) >> 6) & kTabMask;
+  int probes = 0;
   for (;;) {
     const int k = t.keys[s];
     if (k == dst) break;
@@ -297,6 +338,7 @@ __device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int ar
       if (old == kKeyEmpty || old == dst) break;
     }
     s = (s + 1) & kTabMask;
+    if (++probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return; }   // table full
   }
   const unsigned oc = f2ord(cost);
   const unsigned long long mine = ((unsigned long long)oc << 32) | (unsigned)idx;
@@ -313,70 +355,139 @@ __device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int ar
   }
 }
 
-// Partitions [p0, p1) form the next group: as many as fit the table.  Uniform across the block.
-__device__ __forceinline__ int next_group(const Ctx &x, int p0, int &total) {
-  int p1 = p0; total = 0;
-  while (p1 < x.c.num_parts) {
-    const int n = min(x.sm.part_cnt[p1], x.c.region_cap);
-    if (p1 > p0 && total + n > kGroupMax) break;
-    total += n; ++p1;
-  }
-  return p1;
-}
-
 __device__ __forceinline__ void table_clear(Smem &sm) {
   for (int s = threadIdx.x; s < kTabSlots; s += kBlock) { sm.u.t.vals[s] = kValEmpty; sm.u.t.keys[s] = kKeyEmpty; }
 }
 
-// Insert every candidate of partitions [p0, p1) into the (cleared) table.
-__device__ __forceinline__ void table_fill(Ctx &x, int p0, int p1) {
+// Group of a destination state when the candidates are reduced in G table passes.
+__device__ __forceinline__ int group_of(int dst, int G) {
+  return (int)(((hash_state(dst) >> 19) * (unsigned)G) >> 13);       // top 13 hash bits scaled to [0, G)
+}
+
+// One table pass: every candidate of group g that passes `sel` (cost bin below k_sel, inside
+// the beam) is inserted.  The candidate buffer is read in full, coalesced, on every pass.
+template <bool kSelect>
+__device__ __forceinline__ void table_fill(Ctx &x, int n_cand, int g, int G, const Cutoff &cut, int k_sel) {
   const int tid = threadIdx.x;
-  for (int p = p0; p < p1; ++p) {
-    const int n = min(x.sm.part_cnt[p], x.c.region_cap);
-    const int base = p * x.c.region_cap;
-    for (int i0 = 0; i0 < n; i0 += kBlock * kU) {
-      int4 cd[kU];
+  for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
+    int4 cd[kU];
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int i = i0 + u * kBlock + tid;
-        cd[u] = make_int4(-1, 0, 0, 0);
-        if (i < n) cd[u] = x.cand[base + i];
-      }
+    for (int u = 0; u < kU; ++u) {
+      const int i = i0 + u * kBlock + tid;
+      cd[u] = make_int4(-1, 0, 0, 0);
+      if (i < n_cand) cd[u] = x.cand[i];
+    }
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int i = i0 + u * kBlock + tid;
-        if (i < n) table_insert(x, cd[u].x, __int_as_float(cd[u].y), cd[u].w, base + i);
-      }
+    for (int u = 0; u < kU; ++u) {
+      const int i = i0 + u * kBlock + tid;
+      const float c = __int_as_float(cd[u].y);
+      bool take = i < n_cand && (G == 1 || group_of(cd[u].x, G) == g);
+      if (kSelect) take = take && cut.in_beam(c) && cut.bin(c) < k_sel;
+      if (take) table_insert(x, cd[u].x, c, cd[u].w, i);
     }
   }
 }
 
+// ------------------------------------------------------------------ token creation
+// A new token of the set under construction: queue record with the state's emitting arc
+// range, backpointer, state index entry (only states that an epsilon arc can enter are ever
+// looked up), and an entry in the next epsilon worklist if the state has epsilon arcs.
+// `rec` is the state's record.  Converged call (uses wave-aggregated appends).
+__device__ __forceinline__ void make_token(Ctx &x, bool make, int ti, int state, int costbits, int prev, int arc,
+                                           const int4 &rec, int4 *NQ, unsigned lat_base, int4 *WLN,
+                                           unsigned tag16) {
+  const int xdeg = rec.w & 0x7fffffff;
+  const bool eps = make && xdeg > 0;
+  if (make) {
+    NQ[ti] = make_int4(state, costbits, rec.x, rec.z);
+    x.lat[lat_base + ti] = make_int2(prev, arc);
+    if (rec.w < 0) x.index[state] = tag16 | (unsigned)ti;
+    if (xdeg) atomicAdd((unsigned long long *)&x.sm.ctr[kCtXarc], (unsigned long long)xdeg);
+  }
+  const int wi = wave_alloc(&x.sm.n_wl_next, eps);
+  if (eps) WLN[wi] = make_int4(ti, rec.y, xdeg, 0);      // wi < qcap because ti < qcap
+}
+
 // ------------------------------------------------------------------ Prune
-// Every occupied table slot is the recombined token of one destination state.  Those inside
-// the beam are histogrammed into 256 bins over [best, best+beam] and parked; the max-active
-// cutoff k_keep is the first bin where the running count exceeds max_active (at least 1).
-__device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff &cut) {
+// 1. select: a histogram of the CANDIDATE costs (before recombination) gives a bin limit
+//    k_sel below which a bit more than max_active candidates lie; only those can survive
+//    the max-active cutoff, so only those are recombined (k_sel = 256 if everything may).
+// 2. recombine the selected candidates in G passes over the LDS table; every occupied
+//    slot is the recombined token of one destination; they are histogrammed (256 bins over
+//    [best, best+beam]) and parked.
+// 3. cutoff: k_keep = first bin where the running count of recombined tokens exceeds
+//    max_active (at least 1).  If the selection turns out too small to decide that
+//    (duplicate destinations), step 2 is redone with everything selected.
+// 4. the survivors become tokens.
+__device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *WLN, Cutoff &cut) {
   Smem &sm = x.sm;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
-  const unsigned bo = sm.best_ord;
+  const unsigned bo = uni(sm.best_ord);
   cut.best = bo == kOrdNone ? INFINITY : ord2f(bo);
   cut.beam = x.s.beam; cut.scale = x.s.scale; cut.k_keep = 256;
-  for (int p0 = 0; p0 < x.c.num_parts;) {
-    int total;
-    const int p1 = next_group(x, p0, total);
-    if (total > kTabSlots - kBlock) { if (tid == 0) atomicOr(&sm.status, kStCapacity); total = 0; }
-    if (total > 0) {
+  const int n_cand = uni(min(sm.n_cand, x.c.cand_cap));
+  const unsigned ma = (unsigned)x.s.max_active;
+
+  // ---- 1. select
+  for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
+    int cb[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) { const int i = i0 + u * kBlock + tid; cb[u] = i < n_cand ? x.cand[i].y : 0; }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const float c = __int_as_float(cb[u]);
+      if (i0 + u * kBlock + tid < n_cand && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {
+    const unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
+    unsigned s = h0 + h1 + h2 + h3, inc = s;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { unsigned tt = __shfl_up(inc, o, 64); if (tid >= o) inc += tt; }
+    const unsigned n_in = __shfl(inc, 63, 64);
+    const float want = (float)ma * x.s.sel_ratio + 256.0f;
+    const unsigned target = want < 2.0e9f ? (unsigned)want : 2000000000u;
+    int ks = 256; unsigned nsel = n_in;
+    if (n_in > target) {
+      unsigned run = inc - s;
+      int first = 256; unsigned at = 0;
+      run += h0; if (run >= target && first == 256) { first = 4 * tid; at = run; }
+      run += h1; if (run >= target && first == 256) { first = 4 * tid + 1; at = run; }
+      run += h2; if (run >= target && first == 256) { first = 4 * tid + 2; at = run; }
+      run += h3; if (run >= target && first == 256) { first = 4 * tid + 3; at = run; }
+      int fm = first;
+#pragma unroll
+      for (int sft = 32; sft > 0; sft >>= 1) fm = min(fm, __shfl_xor(fm, sft, 64));
+      const unsigned long long own = __ballot(first == fm && fm != 256);
+      nsel = __shfl(at, __ffsll((long long)own) - 1, 64);
+      ks = fm + 1;                                   // bins [0, ks) are selected
+    }
+    if (tid == 0) { sm.k_sel = ks; sm.n_sel = (int)nsel; }
+  }
+  __syncthreads();
+  if (tid < 256) sm.hist[tid] = 0;
+  int k_sel = uni(sm.k_sel), n_sel = uni(sm.n_sel);
+  __syncthreads();
+  prof_mark(sm, kPhSelect);
+
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    // ---- 2. recombine the selected candidates, G table passes
+    const int G = max(1, (n_sel + kGroupTarget - 1) / kGroupTarget);
+    for (int g = 0; g < G; ++g) {
       table_clear(sm);
       __syncthreads();
-      table_fill(x, p0, p1);
+      prof_mark(sm, kPhTabClear);
+      table_fill<true>(x, n_cand, g, G, cut, k_sel);
       __syncthreads();
+      prof_mark(sm, kPhTabFill);
       for (int s0 = 0; s0 < kTabSlots; s0 += kBlock) {
         const int s = s0 + tid;
         const int key = t.keys[s];
         const unsigned long long v = t.vals[s];
         const float c = ord2f((unsigned)(v >> 32));
-        const bool win = key != kKeyEmpty && cut.in_beam(c);
+        const bool win = key != kKeyEmpty;           // everything in the table is inside the beam
         if (win) atomicAdd(&sm.hist[cut.bin(c)], 1u);
         const int wi = wave_alloc(&sm.n_win, win);
         if (win) {
@@ -385,126 +496,124 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, Cutoff 
         }
       }
       __syncthreads();
+      prof_mark(sm, kPhTabScan);
     }
-    p0 = p1;
-  }
-  __syncthreads();
-  if (tid < 64) {                       // wave 0: scan the histogram, 4 bins per lane
-    unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
-    unsigned s = h0 + h1 + h2 + h3, inc = s;
+    // ---- 3. cutoff from the histogram of recombined tokens
+    if (tid < 64) {
+      const unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
+      unsigned s = h0 + h1 + h2 + h3, inc = s;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { unsigned tt = __shfl_up(inc, o, 64); if (tid >= o) inc += tt; }
-    const unsigned n_in = __shfl(inc, 63, 64);
-    const unsigned ma = (unsigned)x.s.max_active;
-    int kk = 256;
-    if (n_in > ma) {
-      unsigned run = inc - s;
-      int first = 256;
-      run += h0; if (run > ma && first == 256) first = 4 * tid;
-      run += h1; if (run > ma && first == 256) first = 4 * tid + 1;
-      run += h2; if (run > ma && first == 256) first = 4 * tid + 2;
-      run += h3; if (run > ma && first == 256) first = 4 * tid + 3;
+      for (int o = 1; o < 64; o <<= 1) { unsigned tt = __shfl_up(inc, o, 64); if (tid >= o) inc += tt; }
+      const unsigned n_u = __shfl(inc, 63, 64);
+      int kk = 256, redo = 0;
+      if (n_u > ma) {
+        unsigned run = inc - s;
+        int first = 256;
+        run += h0; if (run > ma && first == 256) first = 4 * tid;
+        run += h1; if (run > ma && first == 256) first = 4 * tid + 1;
+        run += h2; if (run > ma && first == 256) first = 4 * tid + 2;
+        run += h3; if (run > ma && first == 256) first = 4 * tid + 3;
 #pragma unroll
-      for (int sft = 32; sft > 0; sft >>= 1) first = min(first, __shfl_xor(first, sft, 64));
-      kk = first;
-      if (tid == 0) { x.k_maxact++; if (kk < 1) x.k_bin0++; }
-      if (kk < 1) kk = 1;
+        for (int sft = 32; sft > 0; sft >>= 1) first = min(first, __shfl_xor(first, sft, 64));
+        kk = first;
+        if (tid == 0) { sm.ctr[kCtMaxAct]++; if (kk < 1) sm.ctr[kCtBin0]++; }
+        if (kk < 1) kk = 1;
+      } else if (k_sel < 256) {
+        redo = 1;                                   // too many duplicates among the selected
+      }
+      if (tid == 0) {
+        sm.k_keep = kk; sm.redo = redo;
+        // next frame's selection: enough candidates for max_active distinct destinations
+        float r = redo ? x.s.sel_ratio * 2.0f : 1.2f * (float)n_sel / (float)max(1u, n_u);
+        sm.red64b = (unsigned long long)__float_as_uint(fminf(fmaxf(r, 1.2f), 16.0f));
+      }
     }
-    if (tid == 0) { sm.k_keep = kk; sm.n_in = (int)n_in; x.k_in += n_in; }
+    __syncthreads();
+    const bool redo = uni(sm.redo) != 0;
+    x.s.sel_ratio = uni(__uint_as_float((unsigned)sm.red64b));
+    if (!redo) break;
+    __syncthreads();
+    if (tid < 256) sm.hist[tid] = 0;
+    if (tid == 0) { sm.n_win = 0; sm.redo = 0; }
+    k_sel = 256; n_sel = n_cand;
+    __syncthreads();
   }
-  if (tid < kMaxParts) sm.part_cnt[tid] = 0;
-  __syncthreads();
-  cut.k_keep = sm.k_keep;
-  // survivors: queue record, backpointer (from the winning candidate's record), state index
-  const unsigned tag = set_tag(x.s.epoch) << 16;
-  const int n_win = min(sm.n_win, x.c.win_cap);
+  cut.k_keep = uni(sm.k_keep);
+  prof_mark(sm, kPhOther);
+
+  // ---- 4. survivors become tokens
+  const unsigned tag16 = set_tag(x.s.epoch) << 16;
+  const int n_win = uni(min(sm.n_win, x.c.win_cap));
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kU) {
-    int2 sc[kU]; int ci[kU]; bool kp[kU]; int4 rec[kU];
+    int2 sc[kU]; int ci[kU]; bool kp[kU]; int4 cr[kU], sr[kU];
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
       const int i = i0 + u * kBlock + tid;
-      kp[u] = false; sc[u] = make_int2(0, 0); ci[u] = 0;
-      if (i < n_win) {
-        sc[u] = x.win_sc[i];
-        kp[u] = cut.bin(__int_as_float(sc[u].y)) < cut.k_keep;
-        if (kp[u]) ci[u] = x.win_ci[i];
-      }
+      sc[u] = make_int2(0, 0); ci[u] = 0;
+      if (i < n_win) { sc[u] = x.win_sc[i]; ci[u] = x.win_ci[i]; }
+      kp[u] = i < n_win && cut.bin(__int_as_float(sc[u].y)) < cut.k_keep;
     }
 #pragma unroll
-    for (int u = 0; u < kU; ++u) { rec[u] = make_int4(0, 0, 0, 0); if (kp[u]) rec[u] = x.cand[ci[u]]; }
+    for (int u = 0; u < kU; ++u) {
+      cr[u] = make_int4(0, 0, 0, 0); sr[u] = cr[u];
+      if (kp[u]) { cr[u] = x.cand[ci[u]]; sr[u] = x.g.state[sc[u].x]; }
+    }
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
       const int ti = wave_alloc(&sm.n_next, kp[u]);
+      bool good = kp[u];
       if (kp[u]) {
-        if (ti >= x.c.qcap) atomicOr(&sm.status, kStCapacity);
-        else if (lat_base + (unsigned)ti >= x.c.lat_cap) atomicOr(&sm.status, kStLattice);
-        else {
-          NQ[ti] = make_int4(sc[u].x, sc[u].y, 0, 0);
-          x.lat[lat_base + ti] = make_int2(rec[u].z, rec[u].w);
-          x.index[sc[u].x] = tag | (unsigned)ti;
-        }
+        if (ti >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
+        else if (lat_base + (unsigned)ti >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
       }
+      make_token(x, good, ti, sc[u].x, sc[u].y, cr[u].z, cr[u].w, sr[u], NQ, lat_base, WLN, tag16);
     }
   }
   __syncthreads();
+  if (tid == 0) { sm.ctr[kCtKept] += min(sm.n_next, x.c.qcap); sm.n_cand = 0; }
+  __syncthreads();
+  prof_mark(sm, kPhCutoff);
 }
 
 // ------------------------------------------------------------------ epsilon closure
-// Least fixpoint under the frozen predicate `cut`: tokens improved (or created) in one round
-// are re-expanded in the next.  The first expansion of a token also fetches its arc ranges
-// (one {emitting, epsilon} offset pair per state) and caches the emitting range in the queue
-// record for the next frame's ExpandArcs.  Each round's candidates are recombined in the LDS
-// table; the per-destination best is then compared with the state's existing token, found
-// through the state index.
-__device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const Cutoff &cut) {
+// Least fixpoint under the frozen predicate `cut`.  The worklist holds the tokens created
+// or improved in the previous round that have epsilon arcs, with their arc ranges.  Each
+// round's candidates are recombined in the LDS table; the per-destination best is compared
+// with the state's existing token (found through the state index) and updates it in place
+// or becomes a new token; either way that token is expanded in the next round.
+// On entry WL0 = x.wl0 + sel*qcap holds n_wl entries.
+__device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
   const unsigned tag = set_tag(x.s.epoch);
-  int n_wl = nP, sel = 0;
-  bool implicit = true;
+  int n_wl = uni(min(sm.n_wl_next, x.c.qcap));
+  __syncthreads();
+  if (tid == 0) sm.n_wl_next = 0;
+  __syncthreads();
   for (int round = 0; n_wl > 0; ++round) {
     if (round > (1 << 20)) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
-    const int *WL = x.wl[sel]; int *WLN = x.wl[sel ^ 1];
-    long long my_x = 0;
+    const int4 *WL = x.wl0 + sel * x.c.qcap; int4 *WLN = x.wl0 + (sel ^ 1) * x.c.qcap;
     for (int cb = 0; cb < n_wl; cb += kChunk) {
-      unsigned deg[kTPT]; int base[kTPT], tk[kTPT]; float cs[kTPT]; int2 sc[kTPT]; int en[kTPT];
+      unsigned deg[kTPT], ex[kTPT]; int4 w[kTPT]; int cs[kTPT];
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
         const int i = cb + kTPT * tid + k;
-        en[k] = 0;
-        if (i < n_wl) en[k] = implicit ? (i | 0x80000000) : WL[i];
+        w[k] = make_int4(0, 0, 0, 0);
+        if (i < n_wl) w[k] = WL[i];
+        deg[k] = (unsigned)w[k].z;
       }
 #pragma unroll
-      for (int k = 0; k < kTPT; ++k) {
-        const int i = cb + kTPT * tid + k;
-        sc[k] = make_int2(0, 0);
-        if (i < n_wl) sc[k] = *reinterpret_cast<const int2 *>(&NQ[en[k] & 0x7fffffff]);
-      }
-      int2 o0[kTPT], o1[kTPT];
+      for (int k = 0; k < kTPT; ++k) cs[k] = deg[k] ? NQ[w[k].x].y : 0;     // the token's current cost
+      const unsigned M = block_scan(sm, deg, ex);
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
-        const int i = cb + kTPT * tid + k;
-        o0[k] = make_int2(0, 0); o1[k] = o0[k];
-        if (i < n_wl) { o0[k] = x.g.off2[sc[k].x]; o1[k] = x.g.off2[sc[k].x + 1]; }
+        e.pre[kTPT * tid + k] = ex[k];
+        e.abase[kTPT * tid + k] = w[k].y - (int)ex[k];
+        e.tcost[kTPT * tid + k] = __int_as_float(cs[k]);
+        e.ttok[kTPT * tid + k] = w[k].x;
       }
-#pragma unroll
-      for (int k = 0; k < kTPT; ++k) {
-        const int i = cb + kTPT * tid + k;
-        const int ti = en[k] & 0x7fffffff;
-        if (i < n_wl && en[k] < 0) {           // first expansion of this token
-          reinterpret_cast<int2 *>(&NQ[ti])[1] = make_int2(o0[k].x, o1[k].x - o0[k].x);
-          my_x += o1[k].y - o0[k].y;
-        }
-        deg[k] = (unsigned)(o1[k].y - o0[k].y); base[k] = o0[k].y; tk[k] = ti; cs[k] = __int_as_float(sc[k].y);
-      }
-      unsigned ex0, ex1;
-      const unsigned M = block_scan2(sm, deg[0], deg[1], ex0, ex1);
-      e.pre[kTPT * tid] = ex0;              e.pre[kTPT * tid + 1] = ex1;
-      e.abase[kTPT * tid] = base[0] - (int)ex0; e.abase[kTPT * tid + 1] = base[1] - (int)ex1;
-      e.tcost[kTPT * tid] = cs[0];          e.tcost[kTPT * tid + 1] = cs[1];
-      e.ttok[kTPT * tid] = tk[0];           e.ttok[kTPT * tid + 1] = tk[1];
       if (tid == kBlock - 1) e.pre[kChunk] = M;
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
@@ -528,63 +637,72 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const C
       }
       __syncthreads();
     }
-    if (my_x) atomicAdd((unsigned long long *)&sm.xarcs, (unsigned long long)my_x);
-    // this round's best candidate per destination updates the state's token in place, or
-    // creates it; either way the token is expanded again in the next round
-    for (int p0 = 0; p0 < x.c.num_parts;) {
-      int total;
-      const int p1 = next_group(x, p0, total);
-      if (total > kTabSlots - kBlock) { if (tid == 0) atomicOr(&sm.status, kStCapacity); total = 0; }
-      if (total > 0) {
-        table_clear(sm);
-        __syncthreads();
-        table_fill(x, p0, p1);
-        __syncthreads();
-        for (int s0 = 0; s0 < kTabSlots; s0 += kBlock) {
-          const int s = s0 + tid;
-          const int d = t.keys[s];
-          const unsigned long long v = t.vals[s];
-          const bool occ = d != kKeyEmpty;
-          int4 rec = make_int4(0, 0, 0, 0); unsigned ix = 0;
-          if (occ) { rec = x.cand[(unsigned)v]; ix = x.index[d]; }
-          const bool exists = occ && (ix >> 16) == tag;
-          int tok = (int)(ix & 0xffffu);
-          bool better = occ;
-          if (exists) {
-            const float oc = __int_as_float(NQ[tok].y);
-            const float nc = __int_as_float(rec.y);
-            const unsigned oa = (unsigned)x.lat[lat_base + tok].y;
-            better = nc < oc || (nc == oc && (unsigned)rec.w < oa);
-          }
-          const bool fresh = occ && !exists;
-          const int ni = wave_alloc(&sm.n_next, fresh);
-          if (fresh) tok = ni;
-          bool good = better;
-          if (better) {
-            if (tok >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
-            else if (lat_base + (unsigned)tok >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
-          }
-          if (good) {
-            if (fresh) x.index[d] = (tag << 16) | (unsigned)tok;
-            *reinterpret_cast<int2 *>(&NQ[tok]) = make_int2(d, rec.y);
-            x.lat[lat_base + tok] = make_int2(rec.z, rec.w);
-          }
-          const int wi = wave_alloc(&sm.n_wl_next, good);
-          if (good) WLN[wi] = tok | (fresh ? 0x80000000 : 0);
+    prof_mark(sm, kPhEpsExpand);
+    const int n_cand = uni(min(sm.n_cand, x.c.cand_cap));
+    const int G = max(1, (n_cand + kGroupTarget - 1) / kGroupTarget);
+    for (int g = 0; g < G && n_cand > 0; ++g) {
+      table_clear(sm);
+      __syncthreads();
+      table_fill<false>(x, n_cand, g, G, cut, 256);
+      __syncthreads();
+      prof_mark(sm, kPhEpsTabFill);
+      // each thread owns kTabSlots / kBlock slots; their dependent global reads (winning
+      // candidate, state index, state record -> existing token) are issued level by level
+      constexpr int kS = 2;
+#pragma unroll 1
+      for (int h = 0; h < kTabSlots / kBlock; h += kS) {
+        int d[kS]; unsigned long long v[kS]; int4 rec[kS], sr[kS]; unsigned ix[kS]; int tok[kS];
+        float oc[kS]; unsigned oa[kS]; bool occ[kS], exists[kS];
+#pragma unroll
+        for (int k = 0; k < kS; ++k) {
+          d[k] = t.keys[(h + k) * kBlock + tid]; v[k] = t.vals[(h + k) * kBlock + tid]; occ[k] = d[k] != kKeyEmpty;
         }
-        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kS; ++k) {
+          rec[k] = make_int4(0, 0, 0, 0); sr[k] = rec[k]; ix[k] = 0;
+          if (occ[k]) { rec[k] = x.cand[(unsigned)v[k]]; ix[k] = x.index[d[k]]; sr[k] = x.g.state[d[k]]; }
+        }
+#pragma unroll
+        for (int k = 0; k < kS; ++k) {
+          exists[k] = occ[k] && (ix[k] >> 16) == tag;
+          tok[k] = (int)(ix[k] & 0xffffu);
+          oc[k] = 0.0f; oa[k] = 0;
+          if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
+        }
+#pragma unroll
+        for (int k = 0; k < kS; ++k) {
+          const float nc = __int_as_float(rec[k].y);
+          const bool improve = exists[k] && (nc < oc[k] || (nc == oc[k] && (unsigned)rec[k].w < oa[k]));
+          const bool fresh = occ[k] && !exists[k];
+          const int ni = wave_alloc(&sm.n_next, fresh);
+          bool good = fresh;
+          if (fresh) {
+            if (ni >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
+            else if (lat_base + (unsigned)ni >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+          }
+          make_token(x, good, ni, d[k], rec[k].y, rec[k].z, rec[k].w, sr[k], NQ, lat_base, WLN, tag << 16);
+          // an existing token that got better: new cost and backpointer in place, expand again
+          const int xdeg = sr[k].w & 0x7fffffff;
+          if (improve) {
+            NQ[tok[k]].y = rec[k].y;
+            x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
+          }
+          const int wi = wave_alloc(&sm.n_wl_next, improve && xdeg > 0);
+          if (improve && xdeg > 0) WLN[wi] = make_int4(tok[k], sr[k].y, xdeg, 0);
+        }
       }
-      p0 = p1;
+      __syncthreads();
+      prof_mark(sm, kPhEpsTabScan);
     }
     __syncthreads();
-    n_wl = min(sm.n_wl_next, x.c.qcap);
-    const bool stop = sm.status != 0;
+    n_wl = uni(min(sm.n_wl_next, x.c.qcap));
+    const bool stop = uni(sm.status) != 0;
     __syncthreads();
-    if (tid == 0) sm.n_wl_next = 0;
-    if (tid < kMaxParts) sm.part_cnt[tid] = 0;
+    if (tid == 0) { sm.n_wl_next = 0; sm.n_cand = 0; }
     __syncthreads();
+    prof_mark(sm, kPhEpsRecombine);
     if (stop) break;
-    sel ^= 1; implicit = false;
+    sel ^= 1;
   }
 }
 
@@ -593,7 +711,7 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int nP, const C
 __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
   Smem &sm = x.sm;
   const int tid = threadIdx.x;
-  const int n = min(sm.n_next, x.c.qcap);
+  const int n = uni(min(sm.n_next, x.c.qcap));
   const int f = x.s.frame;
   if (x.dig_sum) {
     unsigned long long s = 0;
@@ -608,17 +726,16 @@ __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
     x.frame_off[f] = lat_base;
     x.frame_off[f + 1] = lat_base + (unsigned)n;
     if (x.dig_sum) { x.dig_sum[f] = sm.red64; x.dig_cnt[f] = n; }
-    x.k_stored += n;
-    sm.red64 = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.ctr[kCtStored] += n;
+    sm.red64 = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0; sm.n_cand = 0;
     sm.best_ord = kOrdNone;
   }
   if (tid < 256) sm.hist[tid] = 0;
-  if (tid < kMaxParts) sm.part_cnt[tid] = 0;
   x.s.lat_used = lat_base + (unsigned)n;
   x.s.n_tok = n;
   x.s.cur ^= 1;
   x.s.epoch++;
-  const bool stop = sm.status != 0;     // nobody writes status between these two barriers
+  const bool stop = uni(sm.status) != 0;     // nobody writes status between these two barriers
   __syncthreads();
   return stop;
 }
@@ -636,11 +753,11 @@ __device__ void renew_index_if_wrapping(Ctx &x) {
 // Best token by (cost + final cost, state) if any token is final, else by (cost, state);
 // then the backpointers are followed to the start token and the non-zero output labels of
 // the arcs are written in path order.
-__device__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
+__device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
   Smem &sm = x.sm;
   const int tid = threadIdx.x;
   const int n = x.s.n_tok;
-  const int4 *Q = x.q[x.s.cur];
+  const int4 *Q = x.q0 + x.s.cur * x.c.qcap;
   int *words = a.words + (long long)io * a.max_words;
   int flags = x.s.status;
   if (n == 0) {
@@ -707,44 +824,46 @@ __device__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
 __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
-  const int ch = a.chan[blockIdx.x], nfr = a.nfr[blockIdx.x], io = a.io[blockIdx.x];
+  const int ch = uni(a.chan[blockIdx.x]), nfr = uni(a.nfr[blockIdx.x]), io = uni(a.io[blockIdx.x]);
   Ctx x{g, c, sm};
-  x.cand = c.cand + (size_t)ch * c.num_parts * c.region_cap;
+  x.cand = c.cand + (size_t)ch * c.cand_cap;
   x.win_sc = c.win_sc + (size_t)ch * c.win_cap;
   x.win_ci = c.win_ci + (size_t)ch * c.win_cap;
-  x.q[0] = c.queue + (size_t)ch * 2 * c.qcap; x.q[1] = x.q[0] + c.qcap;
-  x.wl[0] = c.wl + (size_t)ch * 2 * c.qcap;   x.wl[1] = x.wl[0] + c.qcap;
+  x.q0 = c.queue + (size_t)ch * 2 * c.qcap;
+  x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
   x.index = c.index + (size_t)ch * g.S;
   x.lat = c.lattice + (size_t)ch * c.lat_cap;
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
   x.dig_cnt = c.dig_cnt ? c.dig_cnt + (size_t)ch * (c.max_frames + 1) : nullptr;
   x.s = c.st[ch];
+  x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
+  x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
+  x.s.scale = uni(x.s.scale); x.s.epoch = uni(x.s.epoch); x.s.sel_ratio = uni(x.s.sel_ratio);
 
   if (tid == 0) {
-    sm.best_ord = kOrdNone; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0; sm.n_tab = 0;
-    sm.status = 0; sm.red64 = 0; sm.xarcs = 0; sm.k_keep = 256; sm.n_in = 0;
+    sm.best_ord = kOrdNone; sm.n_cand = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.status = 0; sm.red64 = 0; sm.red64b = 0; sm.k_keep = 256; sm.k_sel = 256; sm.n_sel = 0; sm.redo = 0;
+    for (int i = 0; i < 16; ++i) sm.prof[i] = 0;
+    for (int i = 0; i < 8; ++i) sm.ctr[i] = 0;
+    sm.prof_t0 = (long long)wall_clock64();
   }
   if (tid < 256) sm.hist[tid] = 0;
-  if (tid < kMaxParts) sm.part_cnt[tid] = 0;
   __syncthreads();
 
   bool stop = false;
   if (a.mode & kModeInit) {
     // start token, closed over epsilon arcs with best = 0 and no bin limit
     x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
-    x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active;
+    x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
     renew_index_if_wrapping(x);
-    int4 *NQ = x.q[1];
-    if (tid == 0) {
-      NQ[0] = make_int4(g.start, __float_as_int(0.0f), 0, 0);
-      x.lat[0] = make_int2(-1, -1);
-      x.index[g.start] = (set_tag(x.s.epoch) << 16) | 0u;
-      sm.n_next = 1;
-    }
+    int4 *NQ = x.q0 + c.qcap;
+    const int4 sr = g.state[g.start];
+    if (tid == 0) sm.n_next = 1;
+    make_token(x, tid == 0, 0, g.start, __float_as_int(0.0f), -1, -1, sr, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
     __syncthreads();
     Cutoff cut{0.0f, x.s.beam, x.s.scale, 256};
-    eps_closure(x, NQ, 0u, 1, cut);
+    eps_closure(x, NQ, 0u, 0, cut);
     stop = finish_set(x, NQ, 0u);
   }
 
@@ -756,34 +875,32 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
     const float *row = ll + (long long)t * a.V;
     for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
     __syncthreads();
-    const int4 *Q = x.q[x.s.cur];
-    int4 *NQ = x.q[x.s.cur ^ 1];
+    const int4 *Q = x.q0 + x.s.cur * c.qcap;
+    int4 *NQ = x.q0 + (x.s.cur ^ 1) * c.qcap;
     const unsigned lat_base = x.s.lat_used;
-    if (tid == 0) { x.k_tok += x.s.n_tok; x.k_frames++; }
+    if (tid == 0) { sm.ctr[kCtTok] += x.s.n_tok; sm.ctr[kCtFrames]++; }
+    prof_mark(sm, kPhOther);
     emit_expand(x, Q, x.s.n_tok);
+    prof_mark(sm, kPhExpand);
     Cutoff cut;
-    recombine_and_prune(x, NQ, lat_base, cut);
-    const int nP = min(sm.n_next, c.qcap);
-    eps_closure(x, NQ, lat_base, nP, cut);
+    recombine_and_prune(x, NQ, lat_base, x.wl0, cut);
+    eps_closure(x, NQ, lat_base, 0, cut);
     x.s.frame++;
     stop = finish_set(x, NQ, lat_base);
+    prof_mark(sm, kPhFinish);
   }
   __syncthreads();
-  if (sm.status) {            // overflow: the channel stops with an empty token set
-    x.s.status |= sm.status;
+  if (uni(sm.status)) {       // overflow: the channel stops with an empty token set
+    x.s.status |= uni(sm.status);
     x.s.n_tok = 0;
   }
+  prof_mark(sm, kPhOther);
   if (a.mode & kModeFinal) select_and_trace(x, a, io);
+  prof_mark(sm, kPhTrace);
   if (tid == 0) {
     c.st[ch] = x.s;
-    atomicAdd((unsigned long long *)&c.counters[0], (unsigned long long)x.k_tok);
-    atomicAdd((unsigned long long *)&c.counters[1], (unsigned long long)x.k_earc);
-    atomicAdd((unsigned long long *)&c.counters[2], (unsigned long long)sm.xarcs);
-    atomicAdd((unsigned long long *)&c.counters[3], (unsigned long long)x.k_in);
-    atomicAdd((unsigned long long *)&c.counters[4], (unsigned long long)x.k_stored);
-    atomicAdd((unsigned long long *)&c.counters[5], (unsigned long long)x.k_maxact);
-    atomicAdd((unsigned long long *)&c.counters[6], (unsigned long long)x.k_bin0);
-    atomicAdd((unsigned long long *)&c.counters[7], (unsigned long long)x.k_frames);
+    for (int i = 0; i < 16; ++i) atomicAdd((unsigned long long *)&c.counters[8 + i], (unsigned long long)sm.prof[i]);
+    for (int i = 0; i < 8; ++i) atomicAdd((unsigned long long *)&c.counters[i], (unsigned long long)sm.ctr[i]);
   }
 }
 
@@ -878,27 +995,30 @@ int validate_graph(const wfst_graph_csr *g, std::string &why, int64_t &Ae, int64
 
 int upload_graph(wfst_decoder *d, const wfst_graph_csr *g, int64_t Ae, int64_t Ax) {
   const int32_t S = g->num_states;
-  std::vector<int2> off2(S + 1);
+  std::vector<int4> srec(S);
+  std::vector<char> eps_in(S, 0);
+  for (int64_t i = 0; i < g->num_arcs; ++i) if (g->ilabel[i] == 0) eps_in[g->next_state[i]] = 1;
   std::vector<int4> earc(Ae);
   std::vector<int2> xarc(Ax);
   std::vector<int> ol(Ae + Ax);
   int64_t ne = 0, nx = 0;
   for (int32_t s = 0; s < S; ++s) {
-    off2[s] = make_int2((int)ne, (int)nx);
+    const int64_t e0 = ne, x0 = nx;
     for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i) {
       int wbits; std::memcpy(&wbits, &g->weight[i], 4);
       if (g->ilabel[i] == 0) { xarc[nx] = make_int2(g->next_state[i], wbits); ol[Ae + nx] = g->olabel[i]; ++nx; }
       else { earc[ne] = make_int4(g->next_state[i], wbits, g->ilabel[i], g->olabel[i]); ol[ne] = g->olabel[i]; ++ne; }
     }
+    // one 16-byte record per state: both arc ranges and whether an epsilon arc can enter it
+    srec[s] = make_int4((int)e0, (int)x0, (int)(ne - e0), (int)(nx - x0) | (eps_in[s] ? (int)0x80000000 : 0));
   }
-  off2[S] = make_int2((int)ne, (int)nx);
-  int2 *d_off; int4 *d_e; int2 *d_x; int *d_ol; float *d_fc = nullptr;
+  int4 *d_off; int4 *d_e; int2 *d_x; int *d_ol; float *d_fc = nullptr;
   int rc;
-  if ((rc = dev_alloc(d, &d_off, off2.size()))) return rc;
+  if ((rc = dev_alloc(d, &d_off, srec.size()))) return rc;
   if ((rc = dev_alloc(d, &d_e, earc.size()))) return rc;
   if ((rc = dev_alloc(d, &d_x, xarc.size()))) return rc;
   if ((rc = dev_alloc(d, &d_ol, ol.size()))) return rc;
-  HIP_TRY(d, hipMemcpy(d_off, off2.data(), off2.size() * sizeof(int2), hipMemcpyHostToDevice));
+  HIP_TRY(d, hipMemcpy(d_off, srec.data(), srec.size() * sizeof(int4), hipMemcpyHostToDevice));
   if (Ae) HIP_TRY(d, hipMemcpy(d_e, earc.data(), earc.size() * sizeof(int4), hipMemcpyHostToDevice));
   if (Ax) HIP_TRY(d, hipMemcpy(d_x, xarc.data(), xarc.size() * sizeof(int2), hipMemcpyHostToDevice));
   if (Ae + Ax) HIP_TRY(d, hipMemcpy(d_ol, ol.data(), ol.size() * sizeof(int), hipMemcpyHostToDevice));
@@ -921,13 +1041,9 @@ int alloc_channels(wfst_decoder *d) {
   DevChannels &c = d->c;
   const size_t N = (size_t)o.max_channels;
   const int ma = o.max_active_hint > 0 ? o.max_active_hint : 10000;
-  // candidate partitions: enough that a frame with ~8 candidates per kept token still fits
-  c.num_parts = o.num_partitions > 0 ? o.num_partitions
-                                     : std::min(kMaxParts, std::max(4, next_pow2((8LL * ma + 2047) / 2048)));
-  c.part_shift = 32;
-  for (int p = c.num_parts; p > 1; p >>= 1) c.part_shift--;
-  c.region_cap = kTabSlots;
-  c.win_cap = std::min(c.num_parts * c.region_cap, 262144);
+  // candidates of one frame: ~16 per kept token before the buffer overflows (flagged, not fatal)
+  c.cand_cap = o.candidate_capacity > 0 ? o.candidate_capacity : next_pow2(std::max<int64_t>(16384, 16LL * ma));
+  c.win_cap = c.cand_cap;
   c.qcap = std::min(kQueueMax, std::max(8192, next_pow2(4LL * ma)));
   c.max_frames = o.max_frames_per_channel;
   int64_t lat_bytes = o.lattice_bytes_per_channel > 0 ? o.lattice_bytes_per_channel
@@ -937,7 +1053,7 @@ int alloc_channels(wfst_decoder *d) {
   c.lat_cap = (unsigned)lat_entries;
   int rc;
   if ((rc = dev_alloc(d, &c.st, N))) return rc;
-  if ((rc = dev_alloc(d, &c.cand, N * (size_t)c.num_parts * c.region_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.cand, N * (size_t)c.cand_cap))) return rc;
   if ((rc = dev_alloc(d, &c.win_sc, N * c.win_cap))) return rc;
   if ((rc = dev_alloc(d, &c.win_ci, N * c.win_cap))) return rc;
   if ((rc = dev_alloc(d, &c.index, N * (size_t)d->g.S))) return rc;
@@ -949,9 +1065,9 @@ int alloc_channels(wfst_decoder *d) {
     if ((rc = dev_alloc(d, &c.dig_sum, N * (size_t)(c.max_frames + 1)))) return rc;
     if ((rc = dev_alloc(d, &c.dig_cnt, N * (size_t)(c.max_frames + 1)))) return rc;
   }
-  if ((rc = dev_alloc(d, &c.counters, (size_t)8))) return rc;
+  if ((rc = dev_alloc(d, &c.counters, (size_t)24))) return rc;
   HIP_TRY(d, hipMemset(c.st, 0, N * sizeof(ChanState)));
-  HIP_TRY(d, hipMemset(c.counters, 0, 8 * sizeof(long long)));
+  HIP_TRY(d, hipMemset(c.counters, 0, 24 * sizeof(long long)));
   HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
   HIP_TRY(d, hipMemset(c.index, 0, N * (size_t)d->g.S * sizeof(unsigned)));   // tag 0 = no token
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
@@ -999,9 +1115,8 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
   *out = nullptr;
   if (opts->max_channels < 1 || opts->max_frames_per_channel < 1 || opts->max_words < 1)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "max_channels, max_frames_per_channel and max_words must be >= 1");
-  if (opts->num_partitions && (opts->num_partitions < 2 || opts->num_partitions > kMaxParts ||
-                               (opts->num_partitions & (opts->num_partitions - 1))))
-    return fail(nullptr, WFST_ERR_INVALID_ARG, "num_partitions must be a power of two in [2, 64]");
+  if (opts->candidate_capacity < 0 || (opts->candidate_capacity > 0 && opts->candidate_capacity < 4096))
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "candidate_capacity must be 0 or >= 4096");
   if (graph->num_classes > kMaxV)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "num_classes above " + std::to_string(kMaxV));
   std::string why; int64_t Ae = 0, Ax = 0;
@@ -1171,6 +1286,14 @@ int32_t wfst_get_counters(wfst_decoder *d, int64_t counters[8], int32_t reset) {
   HIP_TRY(d, hipDeviceSynchronize());
   HIP_TRY(d, hipMemcpy(counters, d->c.counters, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
   if (reset) HIP_TRY(d, hipMemset(d->c.counters, 0, 8 * sizeof(int64_t)));
+  return WFST_OK;
+}
+
+int32_t wfst_debug_phase_ticks(wfst_decoder *d, int64_t ticks[16], int32_t reset) {
+  if (!d || !ticks) return WFST_ERR_INVALID_ARG;
+  HIP_TRY(d, hipDeviceSynchronize());
+  HIP_TRY(d, hipMemcpy(ticks, d->c.counters + 8, 16 * sizeof(int64_t), hipMemcpyDeviceToHost));
+  if (reset) HIP_TRY(d, hipMemset(d->c.counters + 8, 0, 16 * sizeof(int64_t)));
   return WFST_OK;
 }
 

@@ -277,11 +277,12 @@ def test_digest_is_a_function_of_the_token_set(c1):
 
 
 def test_max_active_bounds_the_pruned_set(c2):
-    """Counters: tokens in the beam vs stored; max-active binds on this workload."""
+    """Counters: recombined destinations vs stored tokens; max-active binds on this workload."""
     o = Oracle(c2.graph)
     r = o.decode(c2.loglikes[0, :60], beam=c2.beam, max_active=c2.max_active, want_digests=True)
     assert r.counters[5] > 0                      # frames where the histogram pruned
-    assert r.counters[3] > r.counters[4]          # in-beam candidates exceed stored tokens
+    assert r.counters[7] > r.counters[4]          # recombined destinations exceed stored tokens
+    assert r.counters[3] <= r.counters[4]         # the closure only adds tokens
     assert r.digest_count.sum() == r.counters[4]
 
 
