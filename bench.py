@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--workload", default="c3_large")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipeline", type=int, default=1,
+                    help="decoders (each with its own stream) that take the steps in turn, so that the "
+                         "next batch fills the compute units the previous one no longer uses")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (utterances are independent; more GPUs "
@@ -86,35 +89,49 @@ def main():
     print(f"[bench] {args.workload}: S={w.graph.num_states} A={w.graph.num_arcs} B={B} T={T} V={V} "
           f"audio={w.audio_seconds:.1f}s generated in {time.perf_counter() - t0:.1f}s", file=sys.stderr, flush=True)
     t0 = time.perf_counter()
-    dec = Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active)
+    decs = [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active)
+            for _ in range(max(1, args.pipeline))]
+    streams = [torch.cuda.Stream() for _ in decs]
+    dec = decs[0]
     ll = torch.from_numpy(w.loglikes).cuda()
-    out = None
+    outs = [None] * len(decs)
     torch.cuda.synchronize()
     print(f"[bench] decoder ready in {time.perf_counter() - t0:.1f}s, {dec.device_bytes() / 2**30:.1f} GiB on device",
           file=sys.stderr, flush=True)
 
-    for _ in range(args.warmup):
-        out = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, out=out)
+    def step(i):
+        k = i % len(decs)
+        outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k])
+
+    for i in range(max(args.warmup, len(decs) if args.warmup else 0)):
+        step(i)
     torch.cuda.synchronize()
-    dec.get_counters(reset=True)
+    for d in decs:
+        d.get_counters(reset=True)
+        d.debug_phase_ticks(reset=True)
     kernel_ms = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        out = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, out=out)
-        kernel_ms.append(dec.last_kernel_ms())      # HIP events on the launch stream; waits for the kernel
+    for i in range(args.steps):
+        step(i)
+        if len(decs) == 1:
+            kernel_ms.append(dec.last_kernel_ms())  # HIP events on the launch stream; waits for the kernel
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    counters = dec.get_counters() // max(1, args.steps)
-    ticks = dec.debug_phase_ticks()
+    if len(decs) > 1:                                # overlapping kernels: each one's own duration
+        kernel_ms = [d.last_kernel_ms() for d in decs]
+    counters = sum(d.get_counters() for d in decs) // max(1, args.steps)
+    ticks = sum(d.debug_phase_ticks() for d in decs)
+    out = outs[0]
     names = ["expand", "recombine", "cutoff+compact", "eps_expand", "eps_recombine", "publish", "trace", "other",
-             "tab_clear", "tab_fill", "tab_scan", "eps_tab_fill", "eps_tab_scan", "-", "-", "-"]
+             "tab_clear", "tab_fill", "tab_scan", "eps_tab_fill", "eps_tab_scan", "exp_setup", "exp_loop", "-"]
     print("[bench] phase share of workgroup time: " +
           ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks)) +
-          f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / (args.steps + args.warmup):.1f} ms",
+          f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / args.steps:.1f} ms",
           file=sys.stderr, flush=True)
-    flags = out[3].cpu().numpy()
-    assert not (flags & (8 | 16)).any(), "an utterance overflowed a buffer: the run is invalid"
+    for o in outs:
+        if o is not None:
+            assert not (o[3].cpu().numpy() & (8 | 16)).any(), "an utterance overflowed a buffer: the run is invalid"
 
     ms_per_step = 1e3 * wall / args.steps
     rtfx = w.audio_seconds / (wall / args.steps)
@@ -129,7 +146,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
                    "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
-                   "beam": w.beam, "max_active": w.max_active},
+                   "beam": w.beam, "max_active": w.max_active, "batches_in_flight": len(decs)},
         "arcs_expanded_per_s": arcs / (wall / args.steps),
         "arcs_expanded_per_step": arcs,
         "tokens_per_frame": float(counters[4]) / max(1, int(counters[7])),
@@ -141,7 +158,8 @@ def main():
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         line["cpu_baseline"] = cpu_baseline(w, threads)
-    dec.close()
+    for d in decs:
+        d.close()
     print(json.dumps(line), flush=True)
 
 

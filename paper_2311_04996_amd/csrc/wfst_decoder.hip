@@ -57,6 +57,15 @@ constexpr int kChunkLog2 = kTPT == 4 ? 12 : (kTPT == 2 ? 11 : 10);
 static_assert((1 << kChunkLog2) == kChunk, "owner_of searches log2(kChunk) levels");
 constexpr int kMaxV = 2048;
 constexpr int kU = WFST_U;                    // independent memory requests per lane per phase
+#ifndef WFST_UE
+#define WFST_UE 4
+#endif
+#ifndef WFST_UC
+#define WFST_UC 4
+#endif
+constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
+constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
+constexpr int kRegions = 4;                   // candidate buffer regions (by destination hash)
 constexpr int kTabSlots = 8192;               // LDS recombination table
 constexpr unsigned kTabMask = kTabSlots - 1;
 constexpr int kGroupTarget = 4608;            // mean candidates reduced per table pass (load 0.56)
@@ -91,7 +100,7 @@ struct DevGraph {
 
 struct DevChannels {
   ChanState *st;
-  int4 *cand;       int cand_cap;              // {dst state, cost, source token, arc id}
+  int4 *cand;       int cand_cap, region_cap;  // kRegions x region_cap {dst state, cost, source token, arc id}
   int2 *win_sc;     int *win_ci; int win_cap;  // recombined tokens before the max-active cutoff
   int4 *queue;      int qcap;                  // 2 buffers {state, cost, first emitting arc, degree}
   int4 *wl;                                    // 2 buffers {token, first epsilon arc, degree, -}
@@ -126,10 +135,13 @@ struct Smem {
   unsigned hist[256];
   unsigned wave_tot[kWaves];
   unsigned best_ord;
-  int n_cand, n_win, n_next, n_wl_next, status;
+  int n_reg[kRegions];        // candidates per region
+  int n_occ;
+  int n_win, n_next, n_wl_next, status;
   int k_sel, n_sel, k_keep, redo;
   unsigned long long red64, red64b;
   long long ctr[8];
+  unsigned short occ[kTabSlots];   // occupied table slots, compacted
   long long prof[16];         // wall-clock ticks per phase (thread 0)
   long long prof_t0;
   int sel_idx;
@@ -158,20 +170,21 @@ __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlan
 __device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
 
-// Index from an LDS counter for every lane with pred set; one LDS atomic per wave, and the
-// lanes of a wave get consecutive indices (their stores coalesce).
-__device__ __forceinline__ int wave_alloc(int *counter, bool pred) {
-  int idx = -1;
-  if (pred) {
-    unsigned long long m = __ballot(1);
-    int lane = threadIdx.x & 63;
-    int leader = __ffsll((long long)m) - 1;
-    int base = 0;
-    if (lane == leader) base = atomicAdd(counter, __popcll(m));
-    base = __shfl(base, leader, 64);
-    idx = base + __popcll(m & ((1ull << lane) - 1ull));
-  }
-  return idx;
+// Indices from an LDS counter for every (lane, u) with pred[u] set: ONE LDS atomic per wave,
+// and the lanes of a wave get consecutive indices, so their stores coalesce.  Must be called
+// by all 64 lanes of the wave (every call site is inside block-uniform control flow).
+template <int N>
+__device__ __forceinline__ void wave_alloc_n(int *counter, const bool (&pred)[N], int (&idx)[N]) {
+  const int lane = threadIdx.x & 63;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  unsigned long long m[N]; int off[N], tot = 0;
+#pragma unroll
+  for (int u = 0; u < N; ++u) { m[u] = __ballot(pred[u]); off[u] = tot; tot += __popcll(m[u]); }
+  int base = 0;
+  if (lane == 0 && tot) base = atomicAdd(counter, tot);
+  base = uni(base);
+#pragma unroll
+  for (int u = 0; u < N; ++u) idx[u] = pred[u] ? base + off[u] + __popcll(m[u] & lt) : -1;
 }
 
 struct Cutoff {
@@ -199,7 +212,7 @@ enum { kCtTok = 0, kCtEarc, kCtXarc, kCtKept, kCtStored, kCtMaxAct, kCtBin0, kCt
 
 // Phase timing with the constant-rate wall clock (thread 0 only; a few scalar reads per frame).
 enum { kPhExpand = 0, kPhSelect, kPhCutoff, kPhEpsExpand, kPhEpsRecombine, kPhFinish, kPhTrace, kPhOther,
-       kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan };
+       kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan, kPhExpSetup, kPhExpLoop };
 __device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
   if (threadIdx.x == 0) {
     const long long now = (long long)wall_clock64();
@@ -250,12 +263,76 @@ __device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
   return lo;
 }
 
-// Append one candidate; the lanes of a wave write consecutive 16-byte records.
-__device__ __forceinline__ void push_cand(Ctx &x, bool ok, int dst, float nc, int src, int arc) {
-  const int ci = wave_alloc(&x.sm.n_cand, ok);
-  if (ok) {
-    if (ci < x.c.cand_cap) x.cand[ci] = make_int4(dst, __float_as_int(nc), src, arc);
-    else atomicOr(&x.sm.status, kStCapacity);
+// Owners of the N arcs a lane handles in one step: arc u of the lane is f0 + u*kBlock + tid,
+// so the 64 lanes of a wave hold 64 consecutive arcs for every u.  One full search per wave
+// (2N lanes look up the owners of the first and last arc of each run of 64) bounds every
+// lane's own search to the few items its run spans: 0 steps inside a high-degree state,
+// ~5 where degrees are small, instead of log2(kChunk) for every arc.
+template <int N>
+__device__ __forceinline__ void owners_of(const Smem &sm, unsigned f0, unsigned M, bool (&ok)[N], int (&j)[N]) {
+  static_assert(2 * N <= 64, "bounds are looked up by 2N lanes");
+  const int lane = threadIdx.x & 63;
+  const unsigned wave_f = f0 + (threadIdx.x & ~63u);
+  unsigned fq = wave_f + (unsigned)(lane >> 1) * kBlock + ((lane & 1) ? 63u : 0u);
+  if (lane >= 2 * N || fq >= M) fq = M - 1;
+  const int bound = owner_of(sm, fq);
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    const unsigned f = f0 + u * kBlock + threadIdx.x;
+    ok[u] = f < M;
+    int lo = __builtin_amdgcn_readlane(bound, 2 * u), hi = __builtin_amdgcn_readlane(bound, 2 * u + 1) + 1;
+    const int steps = 32 - __clz(max(hi - lo, 1) - 1 | 0);      // ceil(log2(width)), 0 for width 1
+    const unsigned fs = ok[u] ? f : M - 1;
+    for (int it = 0; it < steps; ++it) {
+      const int mid = (lo + hi) >> 1;
+      if (sm.u.e.pre[mid] <= fs) lo = mid; else hi = mid;
+    }
+    j[u] = lo;
+  }
+}
+
+// Region of the candidate buffer a destination state belongs to (top hash bits).
+__device__ __forceinline__ int region_of(int dst) { return (int)(hash_state(dst) >> 30); }
+static_assert(kRegions == 4, "region_of takes two hash bits");
+
+// Append a batch of N candidates per lane to their destinations' regions.  The wave counts
+// its candidates per region with ballots, lane 0 reserves one run per region (kRegions
+// independent LDS atomics), and every candidate gets a slot in its region's run; lanes
+// that hit the same region write consecutive 16-byte records, so the stores coalesce.
+// Must be called by all 64 lanes of the wave.
+template <int N>
+__device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const int (&dst)[N], const float (&nc)[N],
+                                           const int (&src)[N], const int (&arc)[N]) {
+  const int lane = threadIdx.x & 63;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  int r[N]; unsigned long long m[N][kRegions]; int cnt[kRegions], base[kRegions];
+#pragma unroll
+  for (int q = 0; q < kRegions; ++q) cnt[q] = 0;
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    r[u] = region_of(dst[u]);
+#pragma unroll
+    for (int q = 0; q < kRegions; ++q) { m[u][q] = __ballot(ok[u] && r[u] == q); cnt[q] += __popcll(m[u][q]); }
+  }
+#pragma unroll
+  for (int q = 0; q < kRegions; ++q) {
+    base[q] = 0;
+    if (lane == 0 && cnt[q]) base[q] = atomicAdd(&x.sm.n_reg[q], cnt[q]);
+  }
+#pragma unroll
+  for (int q = 0; q < kRegions; ++q) base[q] = uni(base[q]);
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    int slot = 0;
+#pragma unroll
+    for (int q = 0; q < kRegions; ++q) {
+      if (r[u] == q) slot = base[q] + __popcll(m[u][q] & lt);
+      base[q] += __popcll(m[u][q]);
+    }
+    if (ok[u]) {
+      if (slot < x.c.region_cap) x.cand[r[u] * x.c.region_cap + slot] = make_int4(dst[u], __float_as_int(nc[u]), src[u], arc[u]);
+      else atomicOr(&x.sm.status, kStCapacity);
+    }
   }
 }
 
@@ -287,26 +364,25 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
     }
     if (tid == kBlock - 1) e.pre[kChunk] = M;
     __syncthreads();
+    prof_mark(sm, kPhExpSetup);
     if (tid == 0) sm.ctr[kCtEarc] += M;
-    for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-      bool ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU];
+    for (unsigned f0 = 0; f0 < M; f0 += kBlock * kUE) {
+      bool ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
+      owners_of<kUE>(sm, f0, M, ok, j);
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {          // owner search + arc fetch, kU in flight
-        const unsigned f = f0 + u * kBlock + tid;
-        ok[u] = f < M;
-        const int j = ok[u] ? owner_of(sm, f) : 0;
-        arc[u] = e.abase[j] + (int)f;
-        src[u] = cb + j;
-        tc[u] = e.tcost[j];
+      for (int u = 0; u < kUE; ++u) {          // arc fetch, kUE in flight
+        arc[u] = e.abase[j[u]] + (int)(f0 + u * kBlock + tid);
+        src[u] = cb + j[u];
+        tc[u] = e.tcost[j[u]];
         a[u] = make_int4(0, 0, 1, 0);
         if (ok[u]) a[u] = x.g.earc[arc[u]];
       }
       const unsigned bo = *(volatile unsigned *)&sm.best_ord;
       const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
       unsigned o = kOrdNone;
-      float nc[kU];
+      float nc[kUE];
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
+      for (int u = 0; u < kUE; ++u) {
         nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + e.ac[a[u].z - 1]);
         ok[u] = ok[u] && (nc[u] < INFINITY) && !((nc[u] - rb) > beam);
         if (ok[u]) o = min(o, f2ord(nc[u]));
@@ -315,10 +391,13 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
 #pragma unroll
       for (int sft = 32; sft > 0; sft >>= 1) o = min(o, (unsigned)__shfl_xor((int)o, sft, 64));
       if ((tid & 63) == 0 && o != kOrdNone) atomicMin(&sm.best_ord, o);
+      int dst[kUE];
 #pragma unroll
-      for (int u = 0; u < kU; ++u) push_cand(x, ok[u], a[u].x, nc[u], src[u], arc[u]);
+      for (int u = 0; u < kUE; ++u) dst[u] = a[u].x;
+      push_cands<kUE>(x, ok, dst, nc, src, arc);
     }
     __syncthreads();
+    prof_mark(sm, kPhExpLoop);
   }
 }
 
@@ -359,53 +438,102 @@ __device__ __forceinline__ void table_clear(Smem &sm) {
   for (int s = threadIdx.x; s < kTabSlots; s += kBlock) { sm.u.t.vals[s] = kValEmpty; sm.u.t.keys[s] = kKeyEmpty; }
 }
 
-// Group of a destination state when the candidates are reduced in G table passes.
+// Sub-group of a destination state when one region is reduced in G table passes.
 __device__ __forceinline__ int group_of(int dst, int G) {
-  return (int)(((hash_state(dst) >> 19) * (unsigned)G) >> 13);       // top 13 hash bits scaled to [0, G)
+  return (int)((((hash_state(dst) >> 19) & 0x7ffu) * (unsigned)G) >> 11);   // hash bits 19..29 scaled to [0, G)
 }
 
-// One table pass: every candidate of group g that passes `sel` (cost bin below k_sel, inside
-// the beam) is inserted.  The candidate buffer is read in full, coalesced, on every pass.
+// One table pass over regions [r0, r1): every candidate of sub-group g (of G) that is selected
+// (inside the beam, cost bin below k_sel) is inserted.  Reads are coalesced 16-byte records.
 template <bool kSelect>
-__device__ __forceinline__ void table_fill(Ctx &x, int n_cand, int g, int G, const Cutoff &cut, int k_sel) {
+__device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G, const Cutoff &cut, int k_sel) {
   const int tid = threadIdx.x;
-  for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
-    int4 cd[kU];
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int i = i0 + u * kBlock + tid;
-      cd[u] = make_int4(-1, 0, 0, 0);
-      if (i < n_cand) cd[u] = x.cand[i];
-    }
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int i = i0 + u * kBlock + tid;
-      const float c = __int_as_float(cd[u].y);
-      bool take = i < n_cand && (G == 1 || group_of(cd[u].x, G) == g);
+  for (int r = r0; r < r1; ++r) {
+    const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
+    const int base = r * x.c.region_cap;
+    // software pipeline: the next record is in flight while this one goes into the table
+    int4 nxt = make_int4(-1, 0, 0, 0);
+    if (tid < n) nxt = x.cand[base + tid];
+    for (int i = tid; i < n; i += kBlock) {
+      const int4 cd = nxt;
+      if (i + kBlock < n) nxt = x.cand[base + i + kBlock];
+      const float c = __int_as_float(cd.y);
+      bool take = G == 1 || group_of(cd.x, G) == g;
       if (kSelect) take = take && cut.in_beam(c) && cut.bin(c) < k_sel;
-      if (take) table_insert(x, cd[u].x, c, cd[u].w, i);
+      if (take) table_insert(x, cd.x, c, cd.w, base + i);
     }
   }
+}
+
+// The table passes that reduce n_sel selected candidates: one pass over everything if they
+// fit one table, else every region on its own in as many sub-group passes as it needs.
+struct PassPlan {
+  int n_pass; bool whole; int per_region[kRegions];
+  __device__ __forceinline__ void make(const Ctx &x, int n_sel, int n_all) {
+    whole = n_sel <= kGroupTarget;
+    n_pass = whole ? 1 : 0;
+#pragma unroll
+    for (int r = 0; r < kRegions; ++r) {
+      const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
+      // selected candidates of the region, estimated from its share of all candidates
+      const float est = (float)n_sel * (float)n / (float)max(1, n_all) * 1.15f + 64.0f;
+      per_region[r] = (whole || n == 0) ? 0 : (int)(est / (float)kGroupTarget) + 1;
+      n_pass += per_region[r];
+    }
+  }
+  // pass p covers regions [r0, r1) and sub-group g of G
+  __device__ __forceinline__ void get(int p, int &r0, int &r1, int &g, int &G) const {
+    if (whole) { r0 = 0; r1 = kRegions; g = 0; G = 1; return; }
+    int r = 0;
+#pragma unroll
+    for (int q = 0; q < kRegions - 1; ++q) if (r == q && p >= per_region[q]) { p -= per_region[q]; r = q + 1; }
+    r0 = r; r1 = r + 1; g = p; G = max(1, per_region[r]);
+  }
+};
+
+__device__ __forceinline__ int total_candidates(const Ctx &x) {
+  int n = 0;
+#pragma unroll
+  for (int r = 0; r < kRegions; ++r) n += min(x.sm.n_reg[r], x.c.region_cap);
+  return uni(n);
 }
 
 // ------------------------------------------------------------------ token creation
-// A new token of the set under construction: queue record with the state's emitting arc
-// range, backpointer, state index entry (only states that an epsilon arc can enter are ever
-// looked up), and an entry in the next epsilon worklist if the state has epsilon arcs.
-// `rec` is the state's record.  Converged call (uses wave-aggregated appends).
-__device__ __forceinline__ void make_token(Ctx &x, bool make, int ti, int state, int costbits, int prev, int arc,
-                                           const int4 &rec, int4 *NQ, unsigned lat_base, int4 *WLN,
-                                           unsigned tag16) {
-  const int xdeg = rec.w & 0x7fffffff;
-  const bool eps = make && xdeg > 0;
-  if (make) {
-    NQ[ti] = make_int4(state, costbits, rec.x, rec.z);
-    x.lat[lat_base + ti] = make_int2(prev, arc);
-    if (rec.w < 0) x.index[state] = tag16 | (unsigned)ti;
-    if (xdeg) atomicAdd((unsigned long long *)&x.sm.ctr[kCtXarc], (unsigned long long)xdeg);
+// New tokens of the set under construction (N per lane): queue record with the state's
+// emitting arc range, backpointer, state index entry (only states that an epsilon arc can
+// enter are ever looked up), and an entry in the next epsilon worklist if the state has
+// epsilon arcs.  rec[] are the states' records.  `also[]` appends existing tokens (tok[])
+// that were improved and must be expanded again.  Called by all lanes of the wave.
+template <int N>
+__device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const int (&ti)[N], const int (&state)[N],
+                                            const int (&costbits)[N], const int (&prev)[N], const int (&arc)[N],
+                                            const int4 (&rec)[N], const bool (&also)[N], const int (&tok)[N],
+                                            int4 *NQ, unsigned lat_base, int4 *WLN, unsigned tag16) {
+  bool want[2 * N]; int wi[2 * N];
+  unsigned xsum = 0;
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    const int xdeg = rec[u].w & 0x7fffffff;
+    if (make[u]) {
+      NQ[ti[u]] = make_int4(state[u], costbits[u], rec[u].x, rec[u].z);
+      x.lat[lat_base + ti[u]] = make_int2(prev[u], arc[u]);
+      if (rec[u].w < 0) x.index[state[u]] = tag16 | (unsigned)ti[u];
+      xsum += (unsigned)xdeg;
+    }
+    want[u] = make[u] && xdeg > 0;
+    want[N + u] = also[u] && xdeg > 0;
   }
-  const int wi = wave_alloc(&x.sm.n_wl_next, eps);
-  if (eps) WLN[wi] = make_int4(ti, rec.y, xdeg, 0);      // wi < qcap because ti < qcap
+  // epsilon arcs out of the set (a counter): wave sum, one LDS atomic per wave
+#pragma unroll
+  for (int sft = 32; sft > 0; sft >>= 1) xsum += (unsigned)__shfl_xor((int)xsum, sft, 64);
+  if ((threadIdx.x & 63) == 0 && xsum) atomicAdd((unsigned long long *)&x.sm.ctr[kCtXarc], (unsigned long long)xsum);
+  wave_alloc_n<2 * N>(&x.sm.n_wl_next, want, wi);
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    const int xdeg = rec[u].w & 0x7fffffff;
+    if (want[u]) WLN[wi[u]] = make_int4(ti[u], rec[u].y, xdeg, 0);          // wi < qcap because ti < qcap
+    if (want[N + u]) WLN[wi[N + u]] = make_int4(tok[u], rec[u].y, xdeg, 0);
+  }
 }
 
 // ------------------------------------------------------------------ Prune
@@ -426,18 +554,22 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
   const unsigned bo = uni(sm.best_ord);
   cut.best = bo == kOrdNone ? INFINITY : ord2f(bo);
   cut.beam = x.s.beam; cut.scale = x.s.scale; cut.k_keep = 256;
-  const int n_cand = uni(min(sm.n_cand, x.c.cand_cap));
+  const int n_cand = total_candidates(x);
   const unsigned ma = (unsigned)x.s.max_active;
 
   // ---- 1. select
-  for (int i0 = 0; i0 < n_cand; i0 += kBlock * kU) {
-    int cb[kU];
+  for (int r = 0; r < kRegions; ++r) {
+    const int n = uni(min(sm.n_reg[r], x.c.region_cap));
+    const int4 *cr = x.cand + r * x.c.region_cap;
+    for (int i0 = 0; i0 < n; i0 += kBlock * kUC) {
+      int cb[kUC];
 #pragma unroll
-    for (int u = 0; u < kU; ++u) { const int i = i0 + u * kBlock + tid; cb[u] = i < n_cand ? x.cand[i].y : 0; }
+      for (int u = 0; u < kUC; ++u) { const int i = i0 + u * kBlock + tid; cb[u] = i < n ? cr[i].y : 0; }
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const float c = __int_as_float(cb[u]);
-      if (i0 + u * kBlock + tid < n_cand && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+      for (int u = 0; u < kUC; ++u) {
+        const float c = __int_as_float(cb[u]);
+        if (i0 + u * kBlock + tid < n && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+      }
     }
   }
   __syncthreads();
@@ -474,26 +606,35 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
 
   for (int attempt = 0; attempt < 2; ++attempt) {
     // ---- 2. recombine the selected candidates, G table passes
-    const int G = max(1, (n_sel + kGroupTarget - 1) / kGroupTarget);
-    for (int g = 0; g < G; ++g) {
+    PassPlan plan;
+    plan.make(x, n_sel, n_cand);
+    for (int ps = 0; ps < plan.n_pass; ++ps) {
+      int r0, r1, g, G;
+      plan.get(ps, r0, r1, g, G);
       table_clear(sm);
       __syncthreads();
       prof_mark(sm, kPhTabClear);
-      table_fill<true>(x, n_cand, g, G, cut, k_sel);
+      table_fill<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
       prof_mark(sm, kPhTabFill);
-      for (int s0 = 0; s0 < kTabSlots; s0 += kBlock) {
-        const int s = s0 + tid;
-        const int key = t.keys[s];
-        const unsigned long long v = t.vals[s];
-        const float c = ord2f((unsigned)(v >> 32));
-        const bool win = key != kKeyEmpty;           // everything in the table is inside the beam
-        if (win) atomicAdd(&sm.hist[cut.bin(c)], 1u);
-        const int wi = wave_alloc(&sm.n_win, win);
-        if (win) {
-          if (wi < x.c.win_cap) { x.win_sc[wi] = make_int2(key, __float_as_int(c)); x.win_ci[wi] = (int)(unsigned)v; }
-          else atomicOr(&sm.status, kStCapacity);
+      {
+        constexpr int kS = kTabSlots / kBlock;
+        int key[kS]; unsigned long long v[kS]; bool win[kS]; int wi[kS];
+#pragma unroll
+        for (int k = 0; k < kS; ++k) {
+          key[k] = t.keys[k * kBlock + tid]; v[k] = t.vals[k * kBlock + tid];
+          win[k] = key[k] != kKeyEmpty;              // everything in the table is inside the beam
+          if (win[k]) atomicAdd(&sm.hist[cut.bin(ord2f((unsigned)(v[k] >> 32)))], 1u);
         }
+        wave_alloc_n<kS>(&sm.n_win, win, wi);
+#pragma unroll
+        for (int k = 0; k < kS; ++k)
+          if (win[k]) {
+            if (wi[k] < x.c.win_cap) {
+              x.win_sc[wi[k]] = make_int2(key[k], (int)__float_as_uint(ord2f((unsigned)(v[k] >> 32))));
+              x.win_ci[wi[k]] = (int)(unsigned)v[k];
+            } else atomicOr(&sm.status, kStCapacity);
+          }
       }
       __syncthreads();
       prof_mark(sm, kPhTabScan);
@@ -544,33 +685,36 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
   // ---- 4. survivors become tokens
   const unsigned tag16 = set_tag(x.s.epoch) << 16;
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
-  for (int i0 = 0; i0 < n_win; i0 += kBlock * kU) {
-    int2 sc[kU]; int ci[kU]; bool kp[kU]; int4 cr[kU], sr[kU];
+  for (int i0 = 0; i0 < n_win; i0 += kBlock * kUC) {
+    int2 sc[kUC]; int ci[kUC]; bool kp[kUC]; int4 cr[kUC], sr[kUC];
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
+    for (int u = 0; u < kUC; ++u) {
       const int i = i0 + u * kBlock + tid;
       sc[u] = make_int2(0, 0); ci[u] = 0;
       if (i < n_win) { sc[u] = x.win_sc[i]; ci[u] = x.win_ci[i]; }
       kp[u] = i < n_win && cut.bin(__int_as_float(sc[u].y)) < cut.k_keep;
     }
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
+    for (int u = 0; u < kUC; ++u) {
       cr[u] = make_int4(0, 0, 0, 0); sr[u] = cr[u];
       if (kp[u]) { cr[u] = x.cand[ci[u]]; sr[u] = x.g.state[sc[u].x]; }
     }
+    int ti[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; bool good[kUC], no[kUC];
+    wave_alloc_n<kUC>(&sm.n_next, kp, ti);
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const int ti = wave_alloc(&sm.n_next, kp[u]);
-      bool good = kp[u];
+    for (int u = 0; u < kUC; ++u) {
+      good[u] = kp[u]; no[u] = false; none[u] = 0;
       if (kp[u]) {
-        if (ti >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
-        else if (lat_base + (unsigned)ti >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+        if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
+        else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
       }
-      make_token(x, good, ti, sc[u].x, sc[u].y, cr[u].z, cr[u].w, sr[u], NQ, lat_base, WLN, tag16);
+      st[u] = sc[u].x; cb[u] = sc[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
     }
+    make_tokens<kUC>(x, good, ti, st, cb, pv, ar, sr, no, none, NQ, lat_base, WLN, tag16);
   }
   __syncthreads();
-  if (tid == 0) { sm.ctr[kCtKept] += min(sm.n_next, x.c.qcap); sm.n_cand = 0; }
+  if (tid == 0) sm.ctr[kCtKept] += min(sm.n_next, x.c.qcap);
+  if (tid < kRegions) sm.n_reg[tid] = 0;
   __syncthreads();
   prof_mark(sm, kPhCutoff);
 }
@@ -617,79 +761,98 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
       if (tid == kBlock - 1) e.pre[kChunk] = M;
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-        bool ok[kU]; int src[kU]; int2 a[kU]; int arc[kU]; float tc[kU];
+        bool ok[kU]; int src[kU]; int2 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
+        owners_of<kU>(sm, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-          const unsigned f = f0 + u * kBlock + tid;
-          ok[u] = f < M;
-          const int j = ok[u] ? owner_of(sm, f) : 0;
-          arc[u] = e.abase[j] + (int)f;
-          src[u] = e.ttok[j];
-          tc[u] = e.tcost[j];
+          arc[u] = e.abase[j[u]] + (int)(f0 + u * kBlock + tid);
+          src[u] = e.ttok[j[u]];
+          tc[u] = e.tcost[j[u]];
           a[u] = make_int2(0, 0);
           if (ok[u]) a[u] = x.g.xarc[arc[u]];
         }
+        int dst[kU]; float nc[kU];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-          const float nc = canon(tc[u] + __int_as_float(a[u].y));
-          push_cand(x, ok[u] && (nc < INFINITY) && cut.keep(nc), a[u].x, nc, src[u], x.g.Ae + arc[u]);
+          nc[u] = canon(tc[u] + __int_as_float(a[u].y));
+          ok[u] = ok[u] && (nc[u] < INFINITY) && cut.keep(nc[u]);
+          dst[u] = a[u].x; arc[u] += x.g.Ae;
         }
+        push_cands<kU>(x, ok, dst, nc, src, arc);
       }
       __syncthreads();
     }
     prof_mark(sm, kPhEpsExpand);
-    const int n_cand = uni(min(sm.n_cand, x.c.cand_cap));
-    const int G = max(1, (n_cand + kGroupTarget - 1) / kGroupTarget);
-    for (int g = 0; g < G && n_cand > 0; ++g) {
+    const int n_cand = total_candidates(x);
+    PassPlan plan;
+    plan.make(x, n_cand, n_cand);
+    for (int ps = 0; ps < plan.n_pass && n_cand > 0; ++ps) {
+      int r0, r1, g, G;
+      plan.get(ps, r0, r1, g, G);
       table_clear(sm);
+      if (tid == 0) sm.n_occ = 0;
       __syncthreads();
-      table_fill<false>(x, n_cand, g, G, cut, 256);
+      table_fill<false>(x, r0, r1, g, G, cut, 256);
       __syncthreads();
       prof_mark(sm, kPhEpsTabFill);
-      // each thread owns kTabSlots / kBlock slots; their dependent global reads (winning
-      // candidate, state index, state record -> existing token) are issued level by level
-      constexpr int kS = 2;
-#pragma unroll 1
-      for (int h = 0; h < kTabSlots / kBlock; h += kS) {
-        int d[kS]; unsigned long long v[kS]; int4 rec[kS], sr[kS]; unsigned ix[kS]; int tok[kS];
-        float oc[kS]; unsigned oa[kS]; bool occ[kS], exists[kS];
+      // occupied slots, compacted, so that the dependent global reads below run on full waves
+      {
+        constexpr int kS = kTabSlots / kBlock;
+        bool oc[kS]; int oi[kS];
 #pragma unroll
-        for (int k = 0; k < kS; ++k) {
-          d[k] = t.keys[(h + k) * kBlock + tid]; v[k] = t.vals[(h + k) * kBlock + tid]; occ[k] = d[k] != kKeyEmpty;
+        for (int k = 0; k < kS; ++k) oc[k] = t.keys[k * kBlock + tid] != kKeyEmpty;
+        wave_alloc_n<kS>(&sm.n_occ, oc, oi);
+#pragma unroll
+        for (int k = 0; k < kS; ++k) if (oc[k]) sm.occ[oi[k]] = (unsigned short)(k * kBlock + tid);
+      }
+      __syncthreads();
+      const int n_occ = uni(sm.n_occ);
+      // per destination: winning candidate, state index, state record -> existing token
+      for (int i0 = 0; i0 < n_occ; i0 += kBlock * kU) {
+        int d[kU]; int4 rec[kU], sr[kU]; unsigned ix[kU]; int tok[kU];
+        float oc[kU]; unsigned oa[kU]; bool occ[kU], exists[kU]; unsigned ci[kU];
+#pragma unroll
+        for (int k = 0; k < kU; ++k) {
+          const int i = i0 + k * kBlock + tid;
+          occ[k] = i < n_occ;
+          const int sl = occ[k] ? sm.occ[i] : 0;
+          d[k] = t.keys[sl]; ci[k] = (unsigned)t.vals[sl];
         }
 #pragma unroll
-        for (int k = 0; k < kS; ++k) {
+        for (int k = 0; k < kU; ++k) {
           rec[k] = make_int4(0, 0, 0, 0); sr[k] = rec[k]; ix[k] = 0;
-          if (occ[k]) { rec[k] = x.cand[(unsigned)v[k]]; ix[k] = x.index[d[k]]; sr[k] = x.g.state[d[k]]; }
+          if (occ[k]) { rec[k] = x.cand[ci[k]]; ix[k] = x.index[d[k]]; sr[k] = x.g.state[d[k]]; }
         }
 #pragma unroll
-        for (int k = 0; k < kS; ++k) {
+        for (int k = 0; k < kU; ++k) {
           exists[k] = occ[k] && (ix[k] >> 16) == tag;
           tok[k] = (int)(ix[k] & 0xffffu);
           oc[k] = 0.0f; oa[k] = 0;
           if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
         }
+        bool fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU];
 #pragma unroll
-        for (int k = 0; k < kS; ++k) {
+        for (int k = 0; k < kU; ++k) {
           const float nc = __int_as_float(rec[k].y);
-          const bool improve = exists[k] && (nc < oc[k] || (nc == oc[k] && (unsigned)rec[k].w < oa[k]));
-          const bool fresh = occ[k] && !exists[k];
-          const int ni = wave_alloc(&sm.n_next, fresh);
-          bool good = fresh;
-          if (fresh) {
-            if (ni >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good = false; }
-            else if (lat_base + (unsigned)ni >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good = false; }
+          improve[k] = exists[k] && (nc < oc[k] || (nc == oc[k] && (unsigned)rec[k].w < oa[k]));
+          fresh[k] = occ[k] && !exists[k];
+        }
+        wave_alloc_n<kU>(&sm.n_next, fresh, ni);
+#pragma unroll
+        for (int k = 0; k < kU; ++k) {
+          good[k] = fresh[k];
+          if (fresh[k]) {
+            if (ni[k] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[k] = false; }
+            else if (lat_base + (unsigned)ni[k] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[k] = false; }
           }
-          make_token(x, good, ni, d[k], rec[k].y, rec[k].z, rec[k].w, sr[k], NQ, lat_base, WLN, tag << 16);
           // an existing token that got better: new cost and backpointer in place, expand again
-          const int xdeg = sr[k].w & 0x7fffffff;
-          if (improve) {
+          if (improve[k]) {
             NQ[tok[k]].y = rec[k].y;
             x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
           }
-          const int wi = wave_alloc(&sm.n_wl_next, improve && xdeg > 0);
-          if (improve && xdeg > 0) WLN[wi] = make_int4(tok[k], sr[k].y, xdeg, 0);
+          cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w;
         }
+        make_tokens<kU>(x, good, ni, d, cb, pv, ar, sr, improve, tok, NQ, lat_base, WLN, tag << 16);
       }
       __syncthreads();
       prof_mark(sm, kPhEpsTabScan);
@@ -698,7 +861,8 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
     n_wl = uni(min(sm.n_wl_next, x.c.qcap));
     const bool stop = uni(sm.status) != 0;
     __syncthreads();
-    if (tid == 0) { sm.n_wl_next = 0; sm.n_cand = 0; }
+    if (tid == 0) sm.n_wl_next = 0;
+    if (tid < kRegions) sm.n_reg[tid] = 0;
     __syncthreads();
     prof_mark(sm, kPhEpsRecombine);
     if (stop) break;
@@ -727,10 +891,11 @@ __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
     x.frame_off[f + 1] = lat_base + (unsigned)n;
     if (x.dig_sum) { x.dig_sum[f] = sm.red64; x.dig_cnt[f] = n; }
     sm.ctr[kCtStored] += n;
-    sm.red64 = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0; sm.n_cand = 0;
+    sm.red64 = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
     sm.best_ord = kOrdNone;
   }
   if (tid < 256) sm.hist[tid] = 0;
+  if (tid < kRegions) sm.n_reg[tid] = 0;
   x.s.lat_used = lat_base + (unsigned)n;
   x.s.n_tok = n;
   x.s.cur ^= 1;
@@ -842,7 +1007,8 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
   x.s.scale = uni(x.s.scale); x.s.epoch = uni(x.s.epoch); x.s.sel_ratio = uni(x.s.sel_ratio);
 
   if (tid == 0) {
-    sm.best_ord = kOrdNone; sm.n_cand = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.best_ord = kOrdNone; sm.n_occ = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    for (int r = 0; r < kRegions; ++r) sm.n_reg[r] = 0;
     sm.status = 0; sm.red64 = 0; sm.red64b = 0; sm.k_keep = 256; sm.k_sel = 256; sm.n_sel = 0; sm.redo = 0;
     for (int i = 0; i < 16; ++i) sm.prof[i] = 0;
     for (int i = 0; i < 8; ++i) sm.ctr[i] = 0;
@@ -860,7 +1026,11 @@ __global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevCha
     int4 *NQ = x.q0 + c.qcap;
     const int4 sr = g.state[g.start];
     if (tid == 0) sm.n_next = 1;
-    make_token(x, tid == 0, 0, g.start, __float_as_int(0.0f), -1, -1, sr, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
+    {
+      const bool mk[1] = {tid == 0}, no[1] = {false};
+      const int z[1] = {0}, st[1] = {g.start}, m1[1] = {-1}; const int4 rc[1] = {sr};
+      make_tokens<1>(x, mk, z, st, z, m1, m1, rc, no, z, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
+    }
     __syncthreads();
     Cutoff cut{0.0f, x.s.beam, x.s.scale, 256};
     eps_closure(x, NQ, 0u, 0, cut);
@@ -1043,6 +1213,7 @@ int alloc_channels(wfst_decoder *d) {
   const int ma = o.max_active_hint > 0 ? o.max_active_hint : 10000;
   // candidates of one frame: ~16 per kept token before the buffer overflows (flagged, not fatal)
   c.cand_cap = o.candidate_capacity > 0 ? o.candidate_capacity : next_pow2(std::max<int64_t>(16384, 16LL * ma));
+  c.region_cap = c.cand_cap / kRegions;
   c.win_cap = c.cand_cap;
   c.qcap = std::min(kQueueMax, std::max(8192, next_pow2(4LL * ma)));
   c.max_frames = o.max_frames_per_channel;
