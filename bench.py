@@ -32,24 +32,34 @@ def algorithmic_bytes(counters, V):
     return (frames * V * 4 + tok * (8 + 16) + earc * 12 + xarc * 8 + n_in * 16 + stored * (8 + 8))
 
 
-def cpu_baseline(w, threads, budget_s=20.0):
-    """The oracle, as it stands, one utterance per thread on a bounded sample of the batch."""
+def read_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 counters (see profiles/); None if absent."""
+    path = os.path.join(ROOT, "profiles", f"wfst_channel_kernel_{workload}_hbm_traffic.md")
+    try:
+        for ln in open(path):
+            if ln.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                return int(float(ln.split("=", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, threads, budget_s=15.0):
+    """The oracle, as it stands, one utterance per thread on a bounded sample of the batch:
+    the first N utterances in batch order, N chosen for about budget_s seconds of wall time."""
     from concurrent.futures import ThreadPoolExecutor
     from oracle import Oracle
     o = Oracle(w.graph)
-    # shortest-first prefix of the batch, so that the sample stays bounded
-    order = np.argsort(w.lengths, kind="stable")
+    probe = int(np.argmax(w.lengths >= min(120, int(w.lengths.max()))))
     t0 = time.perf_counter()
-    o.decode(w.loglikes[order[0]], length=int(w.lengths[order[0]]), beam=w.beam, max_active=w.max_active)
-    per_frame = (time.perf_counter() - t0) / max(1, int(w.lengths[order[0]]))
+    o.decode(w.loglikes[probe], length=min(120, int(w.lengths[probe])), beam=w.beam, max_active=w.max_active)
+    per_frame = (time.perf_counter() - t0) / min(120, int(w.lengths[probe]))
     frames_budget = budget_s * threads / max(per_frame, 1e-9)
     take, acc = [], 0
-    for b in order:
-        if take and acc + int(w.lengths[b]) > frames_budget:
+    for b in range(len(w.lengths)):
+        if len(take) >= threads and acc + int(w.lengths[b]) > frames_budget:
             break
-        take.append(int(b)); acc += int(w.lengths[b])
-        if len(take) >= 4 * threads:
-            break
+        take.append(b); acc += int(w.lengths[b])
     t0 = time.perf_counter()
     with ThreadPoolExecutor(threads) as ex:
         list(ex.map(lambda b: o.decode(w.loglikes[b], length=int(w.lengths[b]), beam=w.beam,
@@ -57,7 +67,7 @@ def cpu_baseline(w, threads, budget_s=20.0):
     dt = time.perf_counter() - t0
     audio = float(w.lengths[take].sum()) * 0.040
     return {"value": audio / dt, "unit": "audio-s/s", "cores": threads, "kind": "oracle",
-            "sample": f"{len(take)} shortest utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall"}
+            "sample": f"first {len(take)} utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall"}
 
 
 def main():
@@ -68,7 +78,8 @@ def main():
     ap.add_argument("--workload", default="c3_large")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pipeline", type=int, default=1,
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (profiling aid)")
+    ap.add_argument("--pipeline", type=int, default=2,
                     help="decoders (each with its own stream) that take the steps in turn, so that the "
                          "next batch fills the compute units the previous one no longer uses")
     args = ap.parse_args()
@@ -99,39 +110,50 @@ def main():
     print(f"[bench] decoder ready in {time.perf_counter() - t0:.1f}s, {dec.device_bytes() / 2**30:.1f} GiB on device",
           file=sys.stderr, flush=True)
 
-    def step(i):
-        k = i % len(decs)
-        outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k])
+    def run_steps(n_dec, nsteps, record_ms):
+        """nsteps decode_batch calls taken in turn by the first n_dec decoders (each on its own
+        stream); returns the wall time between two device synchronisations."""
+        ms = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(nsteps):
+            k = i % n_dec
+            outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k])
+            if record_ms:
+                ms.append(decs[k].last_kernel_ms())   # HIP events on the launch stream; waits for the kernel
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ms
 
-    for i in range(max(args.warmup, len(decs) if args.warmup else 0)):
-        step(i)
+    for k in range(len(decs)):                       # warmup: every decoder, every buffer touched
+        for _ in range(max(1, args.warmup) if args.warmup else 0):
+            outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k])
     torch.cuda.synchronize()
     for d in decs:
         d.get_counters(reset=True)
         d.debug_phase_ticks(reset=True)
-    kernel_ms = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-        if len(decs) == 1:
-            kernel_ms.append(dec.last_kernel_ms())  # HIP events on the launch stream; waits for the kernel
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    if len(decs) > 1:                                # overlapping kernels: each one's own duration
-        kernel_ms = [d.last_kernel_ms() for d in decs]
-    counters = sum(d.get_counters() for d in decs) // max(1, args.steps)
-    ticks = sum(d.debug_phase_ticks() for d in decs)
-    out = outs[0]
-    names = ["expand", "recombine", "cutoff+compact", "eps_expand", "eps_recombine", "publish", "trace", "other",
+    # one batch in flight: the kernel's own duration (for the roofline) and the unpipelined rate
+    wall_one, kernel_ms = run_steps(1, args.steps, True)
+    counters = decs[0].get_counters() // max(1, args.steps)
+    ticks = decs[0].debug_phase_ticks()
+    # the timed region proper: `pipeline` batches in flight
+    wall = run_steps(len(decs), args.steps, False)[0] if len(decs) > 1 else wall_one
+    names = ["expand", "select", "cutoff+tokens", "eps_expand", "eps_other", "publish", "trace", "other",
              "tab_clear", "tab_fill", "tab_scan", "eps_tab_fill", "eps_tab_scan", "exp_setup", "exp_loop", "-"]
-    print("[bench] phase share of workgroup time: " +
-          ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks)) +
+    print("[bench] phase share of workgroup time (one batch in flight): " +
+          ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks) if t) +
           f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / args.steps:.1f} ms",
           file=sys.stderr, flush=True)
     for o in outs:
         if o is not None:
             assert not (o[3].cpu().numpy() & (8 | 16)).any(), "an utterance overflowed a buffer: the run is invalid"
+    if args.calibrate_copy:
+        # a plain copy of known size in the same process, to scale the profiler's byte counters
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(f"[bench] calibration copy: {src.numel() * 4} bytes read and written", file=sys.stderr, flush=True)
 
     ms_per_step = 1e3 * wall / args.steps
     rtfx = w.audio_seconds / (wall / args.steps)
@@ -139,6 +161,7 @@ def main():
     kms = float(np.mean(kernel_ms))
     abytes = algorithmic_bytes(counters, V)
     achieved = abytes / (kms * 1e-3) / 1e9
+    traffic = read_traffic(args.workload)
     line = {
         "metric": "RTFx (audio-s decoded/s) at batch 256", "value": rtfx, "unit": "audio-s/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -147,12 +170,14 @@ def main():
         "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
                    "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
                    "beam": w.beam, "max_active": w.max_active, "batches_in_flight": len(decs)},
+        "one_batch_in_flight": {"value": w.audio_seconds / (wall_one / args.steps),
+                                "ms_per_step": 1e3 * wall_one / args.steps},
         "arcs_expanded_per_s": arcs / (wall / args.steps),
         "arcs_expanded_per_step": arcs,
         "tokens_per_frame": float(counters[4]) / max(1, int(counters[7])),
         "hbm_frac_of_peak": achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": KERNEL, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms},
     }
     if not args.no_cpu_baseline:

@@ -43,7 +43,16 @@
 
 namespace {
 
-constexpr int kBlock = 1024;
+#ifndef WFST_BLOCK
+#define WFST_BLOCK 1024
+#endif
+#ifndef WFST_TAB
+#define WFST_TAB 8192
+#endif
+#ifndef WFST_MIN_WAVES
+#define WFST_MIN_WAVES 4
+#endif
+constexpr int kBlock = WFST_BLOCK;            // threads of the workgroup that owns a channel
 constexpr int kWaves = kBlock / 64;
 #ifndef WFST_TPT
 #define WFST_TPT 2
@@ -53,7 +62,7 @@ constexpr int kWaves = kBlock / 64;
 #endif
 constexpr int kTPT = WFST_TPT;                // work items per thread per chunk (1, 2 or 4)
 constexpr int kChunk = kBlock * kTPT;
-constexpr int kChunkLog2 = kTPT == 4 ? 12 : (kTPT == 2 ? 11 : 10);
+constexpr int kChunkLog2 = (kTPT == 4 ? 2 : (kTPT == 2 ? 1 : 0)) + (kBlock == 1024 ? 10 : (kBlock == 512 ? 9 : 8));
 static_assert((1 << kChunkLog2) == kChunk, "owner_of searches log2(kChunk) levels");
 constexpr int kMaxV = 2048;
 constexpr int kU = WFST_U;                    // independent memory requests per lane per phase
@@ -66,9 +75,9 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
 constexpr int kRegions = 4;                   // candidate buffer regions (by destination hash)
-constexpr int kTabSlots = 8192;               // LDS recombination table
+constexpr int kTabSlots = WFST_TAB;           // LDS recombination table (power of two)
 constexpr unsigned kTabMask = kTabSlots - 1;
-constexpr int kGroupTarget = 4608;            // mean candidates reduced per table pass (load 0.56)
+constexpr int kGroupTarget = kTabSlots * 9 / 16;  // mean candidates reduced per table pass (load 0.56)
 constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
@@ -986,7 +995,7 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
 }
 
 // ------------------------------------------------------------------ the channel kernel
-__global__ __launch_bounds__(kBlock) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
+__global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
   const int ch = uni(a.chan[blockIdx.x]), nfr = uni(a.nfr[blockIdx.x]), io = uni(a.io[blockIdx.x]);
