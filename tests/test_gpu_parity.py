@@ -269,3 +269,41 @@ def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk):
         w, c, f = dec.get_partial(ch, finalize=True)
         assert w.tolist() == r.words.tolist() and c == r.cost and f == r.flags
     dec.close()
+
+
+# ------------------------------------------------------------------------------- config 3, full size
+def test_c3_full_batch_sampled_against_oracle(torch_cuda):
+    """The batch-256 configuration bench.py times (10 M states, 30 M arcs), decoded in one
+    launch; a seeded sample of utterances is checked frame by frame against the oracle, and
+    the whole batch's counters against the properties that hold at any size."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    from workloads import make_config
+    torch = torch_cuda
+    w = make_config("c3_large")
+    B, T, V = w.loglikes.shape
+    dec = Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active,
+                  record_digests=True)
+    ll = torch.from_numpy(w.loglikes).cuda()
+    words, nwords, cost, flags = dec.decode_batch(ll, w.lengths, w.beam, w.max_active)
+    torch.cuda.synchronize()
+    words, nwords, cost, flags = words.cpu().numpy(), nwords.cpu().numpy(), cost.cpu().numpy(), flags.cpu().numpy()
+    assert (flags == 1).all(), "every utterance must reach a final state without overflow"
+    counters = dec.get_counters()
+    assert counters[7] == int(w.lengths.sum()) and counters[5] <= counters[7]
+    assert counters[3] <= counters[4] and counters[1] >= counters[0]     # every state has a self-loop
+    sample = np.random.default_rng(3).choice(B, size=8, replace=False)
+    sample = np.concatenate([sample, [int(np.argmax(w.lengths)), int(np.argmin(w.lengths))]])
+    o = Oracle(w.graph)
+
+    def one(b):
+        return o.decode(w.loglikes[b], length=int(w.lengths[b]), beam=w.beam, max_active=w.max_active,
+                        max_words=512, want_digests=True)
+    with ThreadPoolExecutor(10) as ex:
+        refs = list(ex.map(one, sample.tolist()))
+    for b, r in zip(sample.tolist(), refs):
+        cnt, dig = dec.debug_frame_digests(b)
+        assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all(), f"utt {b}: token sets differ"
+        assert words[b, :nwords[b]].tolist() == r.words.tolist(), f"utt {b}: words differ"
+        assert cost[b] == np.float32(r.cost) and int(flags[b]) == r.flags
+    dec.close()
