@@ -682,6 +682,7 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
     const bool redo = uni(sm.redo) != 0;
     x.s.sel_ratio = uni(__uint_as_float((unsigned)sm.red64b));
     if (!redo) break;
+    if (tid == 0) sm.prof[15]++;                   // counted, not timed: re-recombinations
     __syncthreads();
     if (tid < 256) sm.hist[tid] = 0;
     if (tid == 0) { sm.n_win = 0; sm.redo = 0; }

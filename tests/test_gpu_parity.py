@@ -307,3 +307,46 @@ def test_c3_full_batch_sampled_against_oracle(torch_cuda):
         assert words[b, :nwords[b]].tolist() == r.words.tolist(), f"utt {b}: words differ"
         assert cost[b] == np.float32(r.cost) and int(flags[b]) == r.flags
     dec.close()
+
+
+# ------------------------------------------------------------------------------- internal paths
+def test_many_duplicate_destinations(torch_cuda):
+    """A small dense graph: ~50 candidates per destination state.  The candidates pre-selected
+    for recombination then hold too few distinct states to decide the max-active cutoff, which
+    forces the decoder's re-recombination of everything; the result must not change."""
+    from workloads import ctc_loglikes, tlg_shaped_graph
+    g = tlg_shaped_graph(11, 600, 30000, num_classes=33, alpha=3.0, k_max=200, p_eps=0.1, num_words=50)
+    lengths = np.array([40, 25, 40], np.int32)
+    ll = ctc_loglikes(11, lengths, 40, 33, sigma=2.0, p_blank=0.5, blank_boost=4.0, token_boost=3.0)
+    from paper_2311_04996_amd import Decoder
+    for ma in (100, 300, 550):
+        check_batch(torch_cuda, g, ll, lengths, 17.0, ma, max_active_hint=2000)
+    # the path under test was really taken
+    dec = Decoder(g, max_channels=3, max_frames=40, max_active_hint=2000)
+    dec.decode_batch(torch_cuda.from_numpy(ll).cuda(), lengths, 17.0, 550)
+    assert dec.debug_phase_ticks()[15] > 0
+    dec.close()
+
+
+def test_state_index_tag_wraps_after_65535_token_sets(torch_cuda, c1):
+    """The per-state token index is tagged with a 16-bit epoch; a channel that lives longer
+    than 65,535 frames must renew it.  66,000 frames of the tiny configuration, streamed."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    reps, T = 660, 100
+    ll_host = np.tile(c1.loglikes[0], (reps, 1))
+    ref = Oracle(c1.graph).decode(ll_host, beam=8.0, max_active=300, want_digests=True, max_words=64)
+    dec = Decoder(c1.graph, max_channels=1, max_frames=reps * T, max_words=64, max_active_hint=300,
+                  record_digests=True, lattice_bytes_per_channel=8 * 400 * (reps * T + 1))
+    chunk = torch.from_numpy(c1.loglikes).cuda()
+    dec.init_channel(0, 8.0, 300)
+    for _ in range(reps):
+        dec.advance_chunk([0], chunk, [T])
+    cnt, dig = dec.debug_frame_digests(0)
+    assert len(cnt) == reps * T + 1
+    bad = np.nonzero((cnt != ref.digest_count) | (dig != ref.digest_sum))[0]
+    assert len(bad) == 0, f"first difference at frame {bad[0]}"
+    w, c, f = dec.get_partial(0, finalize=True)
+    assert w.tolist() == ref.words.tolist() and c == ref.cost and f == ref.flags
+    dec.close()
