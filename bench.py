@@ -70,8 +70,62 @@ def cpu_baseline(w, threads, budget_s=15.0):
             "sample": f"first {len(take)} utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall"}
 
 
+def main_streaming(args):
+    """Streaming configuration: the c3_large graph, `channels` concurrent audio streams fed
+    16-frame (640 ms) chunks with wfst_advance_chunk, partial hypotheses of every channel
+    fetched after every chunk.  One JSON line: per-chunk latency and channels sustainable
+    at real time."""
+    import torch
+    from paper_2311_04996_amd import Decoder
+    from workloads import CONFIGS, ctc_loglikes
+    from workloads.configs import make_graph
+    C, n_chunks, warm = 16, args.chunks, 5
+    n = args.channels
+    c = CONFIGS["c3_large"]
+    g = make_graph("c3_large")
+    T = C * (n_chunks + warm)
+    lengths = np.full(n, T, np.int32)
+    ll = ctc_loglikes(4, lengths, T, g.num_classes, **c["ll"])                 # seed 4: the streaming config
+    # chunk-major copy: [chunk][channel][C][V], the layout a batching server hands over
+    chunks = torch.from_numpy(np.ascontiguousarray(
+        ll.reshape(n, n_chunks + warm, C, g.num_classes).transpose(1, 0, 2, 3))).cuda()
+    dec = Decoder(g, max_channels=n, max_frames=T, max_words=512, max_active_hint=c["max_active"],
+                  outputs_on_host=True)
+    chans = np.arange(n, dtype=np.int32)
+    nfr = np.full(n, C, np.int32)
+    for ch in range(n):
+        dec.init_channel(ch, float(c["beam"]), int(c["max_active"]))
+    torch.cuda.synchronize()
+    print(f"[bench] streaming: {n} channels x {n_chunks}+{warm} chunks of {C} frames, "
+          f"{dec.device_bytes() / 2**30:.1f} GiB on device", file=sys.stderr, flush=True)
+    lat, out = [], None
+    for k in range(n_chunks + warm):
+        t0 = time.perf_counter()
+        dec.advance_chunk(chans, chunks[k], nfr)
+        out = dec.get_partial_batch(chans, finalize=False, out=out)          # host outputs: synchronises
+        lat.append(time.perf_counter() - t0)
+    assert not (out[3] & (8 | 16)).any(), "a channel overflowed a buffer: the run is invalid"
+    lat = np.array(lat[warm:]) * 1e3
+    p50, p99 = float(np.percentile(lat, 50)), float(np.percentile(lat, 99))
+    chunk_s = C * 0.040
+    line = {"metric": "streaming chunk latency p50 (ms), advance 16 frames + partial hypotheses, all channels",
+            "value": p50, "unit": "ms", "n_gpus": 1, "steps": n_chunks, "warmup": warm, "ms_per_step": float(lat.mean()),
+            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "c4_streaming", "channels": n, "chunk_frames": C, "states": g.num_states,
+                       "arcs": g.num_arcs, "beam": c["beam"], "max_active": c["max_active"]},
+            "p50_ms": p50, "p99_ms": p99, "max_ms": float(lat.max()),
+            "rtfx": n * chunk_s / (float(lat.mean()) * 1e-3),
+            "channels_at_realtime_p99": int(n * chunk_s * 1e3 / p99),
+            "channels_at_realtime_p50": int(n * chunk_s * 1e3 / p50),
+            "mean_words_per_partial": float(out[1].mean())}
+    dec.close()
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--channels", type=int, default=512, help="streaming mode: concurrent channels")
+    ap.add_argument("--chunks", type=int, default=50, help="streaming mode: timed chunks")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
@@ -93,6 +147,8 @@ def main():
     from paper_2311_04996_amd import Decoder
     from workloads import make_config
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "c4_streaming":
+        return main_streaming(args)
 
     t0 = time.perf_counter()
     w = make_config(args.workload, batch=args.batch)

@@ -122,6 +122,8 @@ int32_t wfst_decode_batch(wfst_decoder *dec, const float *loglikes, const int32_
  *   wfst_get_partial  : best hypothesis of channel `ch` so far.  finalize = 0 ignores final
  *                       costs (partial result), 1 applies them.  words [cap], nwords [1],
  *                       cost [1], flags [1] follow opts.outputs_on_host.
+ *   wfst_get_partial_batch: the same for n channels (HOST int32 channels[n]) in one launch;
+ *                       words [n][max_words], nwords [n], cost [n], flags [n].
  */
 int32_t wfst_init_channel(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
                           const void *boost, void *stream);
@@ -130,6 +132,9 @@ int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n
                            void *stream);
 int32_t wfst_get_partial(wfst_decoder *dec, int32_t ch, int32_t finalize, int32_t *words,
                          int32_t cap, int32_t *nwords, float *cost, int32_t *flags, void *stream);
+int32_t wfst_get_partial_batch(wfst_decoder *dec, const int32_t *channels, int32_t n, int32_t finalize,
+                               int32_t *words, int32_t *nwords, float *cost, int32_t *flags,
+                               void *stream);
 
 /*
  * Test and measurement hooks.  All outputs are HOST memory; each call synchronises the

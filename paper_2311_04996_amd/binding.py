@@ -19,7 +19,7 @@ ERRORS = {-1: "INVALID_ARG", -2: "BAD_GRAPH", -3: "OOM", -4: "LATTICE_OVERFLOW",
 FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPACITY = 1, 2, 4, 8, 16
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_init_channel",
-           "wfst_advance_chunk", "wfst_get_partial", "wfst_debug_frame_digests",
+           "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
 
@@ -66,6 +66,7 @@ def load_library():
     lib.wfst_init_channel.argtypes = [p, i32, f32, i32, p, p]
     lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
     lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
+    lib.wfst_get_partial_batch.argtypes = [p, p, i32, i32, p, p, p, p, p]
     lib.wfst_debug_frame_digests.argtypes = [p, i32, p, p, i32, p]
     lib.wfst_debug_get_tokens.argtypes = [p, i32, p, p, i32, p]
     lib.wfst_get_counters.argtypes = [p, p, i32]
@@ -76,7 +77,7 @@ def load_library():
     lib.wfst_last_kernel_ms.restype = f32
     lib.wfst_last_error.argtypes = [p]
     lib.wfst_last_error.restype = C.c_char_p
-    for name in EXPORTS[:10]:
+    for name in EXPORTS[:11]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -189,6 +190,27 @@ class Decoder:
                                               c.data_ptr(), f.data_ptr(), _stream_ptr(stream)))
         k = int(n.item())
         return w[:k].cpu().numpy(), float(c.item()), int(f.item())
+
+    def get_partial_batch(self, channels, finalize=False, stream=None, out=None):
+        """Best hypotheses of several channels in one launch.  Returns (words [n, max_words],
+        nwords [n], cost [n], flags [n]) as CUDA tensors, or numpy arrays with outputs_on_host."""
+        import torch
+        channels = np.ascontiguousarray(channels, dtype=np.int32)
+        n = len(channels)
+        if out is None:
+            if self.outputs_on_host:
+                out = (np.zeros((n, self.max_words), np.int32), np.zeros(n, np.int32),
+                       np.zeros(n, np.float32), np.zeros(n, np.int32))
+            else:
+                out = (torch.zeros((n, self.max_words), dtype=torch.int32, device="cuda"),
+                       torch.zeros(n, dtype=torch.int32, device="cuda"),
+                       torch.zeros(n, dtype=torch.float32, device="cuda"),
+                       torch.zeros(n, dtype=torch.int32, device="cuda"))
+        ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
+        self._check(self.lib.wfst_get_partial_batch(self.h, channels.ctypes.data, n, int(finalize),
+                                                    ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3]),
+                                                    _stream_ptr(stream)))
+        return out
 
     # ---- hooks
     def debug_frame_digests(self, ch):

@@ -1429,6 +1429,38 @@ int32_t wfst_get_partial(wfst_decoder *d, int32_t ch, int32_t finalize, int32_t 
   return WFST_OK;
 }
 
+int32_t wfst_get_partial_batch(wfst_decoder *d, const int32_t *channels, int32_t n, int32_t finalize,
+                               int32_t *words, int32_t *nwords, float *cost, int32_t *flags, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (n < 0) return fail(d, WFST_ERR_INVALID_ARG, "negative n");
+  if (n == 0) return WFST_OK;
+  if (!channels || !words || !nwords || !cost || !flags) return fail(d, WFST_ERR_INVALID_ARG, "null argument");
+  if (n > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "more channels than max_channels");
+  std::vector<int> chan(n), nfr(n, 0), io(n);
+  for (int i = 0; i < n; ++i) {
+    if (channels[i] < 0 || channels[i] >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+    chan[i] = channels[i]; io[i] = i;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool host_out = d->opts.outputs_on_host != 0;
+  LaunchArgs a{};
+  a.V = d->V; a.mode = kModeFinal; a.finalize = finalize ? 1 : 0;
+  a.words = host_out ? d->o_words : words; a.nwords = host_out ? d->o_nwords : nwords;
+  a.cost = host_out ? d->o_cost : cost;    a.flags = host_out ? d->o_flags : flags;
+  a.max_words = d->opts.max_words;
+  int rc = launch(d, chan, nfr, io, a, st);
+  if (rc) return rc;
+  if (host_out) {
+    const size_t mw = (size_t)d->opts.max_words;
+    HIP_TRY(d, hipMemcpyAsync(words, d->o_words, n * mw * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(nwords, d->o_nwords, n * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(cost, d->o_cost, n * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(flags, d->o_flags, n * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipStreamSynchronize(st));
+  }
+  return WFST_OK;
+}
+
 int32_t wfst_debug_frame_digests(wfst_decoder *d, int32_t ch, uint64_t *digest, int32_t *count,
                                  int32_t cap, int32_t *n) {
   if (!d) return WFST_ERR_INVALID_ARG;

@@ -262,8 +262,10 @@ def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk):
                 w, c, f = dec.get_partial(ch, finalize=False)
                 r = o.decode(c2.loglikes[utts[i]], length=n, beam=c2.beam, max_active=c2.max_active, finalize=False)
                 assert w.tolist() == r.words.tolist() and c == r.cost and f == r.flags
+    bw, bn, bc, bf = dec.get_partial_batch(chans, finalize=True)           # all channels in one launch
     for i, ch in enumerate(chans):
         r = o.decode(c2.loglikes[utts[i]], length=int(lens[i]), beam=c2.beam, max_active=c2.max_active, want_digests=True)
+        assert bw[i, :int(bn[i])].cpu().numpy().tolist() == r.words.tolist() and float(bc[i]) == r.cost and int(bf[i]) == r.flags
         cnt, dig = dec.debug_frame_digests(ch)
         assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all()
         w, c, f = dec.get_partial(ch, finalize=True)
