@@ -31,6 +31,10 @@
  *   R7  candidates whose cost is not finite are discarded when created.
  *   R8  final choice: min over (cost + final_cost, state) if any token is final, else min
  *       over (cost, state) with the reached_final flag clear.
+ *   R9  word boosting (Section "Word boosting" and the green lines of the Expand Arcs
+ *       pseudo-code): on every arc, emitting or epsilon, whose olabel is in the utterance's
+ *       boost table, the table's score is added after the other terms:
+ *       ((c + w) + (-loglike)) + b[olabel], resp. (c + w) + b[olabel].
  *
  * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
  * Viterbi, greedy CTC collapse on the normal CTC topology, closed-form histogram cases,
@@ -70,6 +74,11 @@ typedef struct {
   int32_t finalize;        /* 1: use final costs (R8); 0: best token regardless */
   int32_t worklist_order;  /* 0 FIFO, 1 LIFO, 2 seeded random pick */
   uint64_t order_seed;
+  /* word boosting (Section "Word boosting"): table word id -> score of the single-state
+   * boosting acceptor B; decoding behaves as if the graph were TLG o B */
+  int32_t boost_n;
+  const int32_t *boost_ids;
+  const float *boost_scores;
 } oracle_opts;
 
 typedef struct {
@@ -227,7 +236,7 @@ static uint64_t rng_next(uint64_t *s) { *s += 0x9E3779B97F4A7C15ull; return mix6
  * front (order 0), from the back (1) or at a seeded random position (2); `head` only moves
  * in order 0.  The result does not depend on the order. */
 static void eps_closure(const oracle_prepared *p, tokvec *v, int32_t *map, const cutoff_t *k,
-                        int32_t order, uint64_t seed) {
+                        int32_t order, uint64_t seed, const float *boost) {
   int32_t *wl = NULL; int32_t wn = 0, wcap = 0, head = 0;
   for (int32_t i = 0; i < v->n; ++i) {
     if (wn == wcap) { wcap = wcap ? wcap * 2 : 1024; wl = (int32_t *)realloc(wl, sizeof(int32_t) * wcap); }
@@ -241,6 +250,7 @@ static void eps_closure(const oracle_prepared *p, tokvec *v, int32_t *map, const
     int32_t s = v->t[j].state; float c = v->t[j].cost;
     for (int64_t a = p->x_off[s]; a < p->x_off[s + 1]; ++a) {
       float nc = canon(c + p->x_w[a]);
+      if (boost && p->x_ol[a] != 0) nc = canon(nc + boost[p->x_ol[a]]);
       if (!(nc < INFINITY)) continue;
       if (!keep(nc, k)) continue;
       int32_t d = p->x_next[a]; int32_t gid = (int32_t)(p->Ae + a);
@@ -268,7 +278,7 @@ int32_t oracle_eps_closure(const oracle_prepared *p, const int32_t *states, cons
   for (int32_t s = 0; s < p->S; ++s) map[s] = -1;
   tokvec v = { 0, 0, 0 };
   for (int32_t i = 0; i < n; ++i) { token_t t = { states[i], costs[i], -1, -1 }; map[states[i]] = v.n; tv_push(&v, t); }
-  eps_closure(p, &v, map, &k, order, seed);
+  eps_closure(p, &v, map, &k, order, seed, NULL);
   int32_t ret = v.n;
   if (ret > cap) ret = -1;
   else for (int32_t i = 0; i < v.n; ++i) {
@@ -307,11 +317,21 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
   tokvec cur = { 0, 0, 0 }, nxt = { 0, 0, 0 };
   int64_t dump_used = 0;
   cutoff_t k; k.beam = o->beam; k.scale = 256.0f / o->beam;
+  /* boost table as a dense array over output labels (absent words add exactly 0) */
+  float *boost = NULL;
+  if (o->boost_n > 0) {
+    int32_t max_ol = 0;
+    for (int64_t a = 0; a < p->Ae; ++a) if (p->e_ol[a] > max_ol) max_ol = p->e_ol[a];
+    for (int64_t a = 0; a < p->Ax; ++a) if (p->x_ol[a] > max_ol) max_ol = p->x_ol[a];
+    boost = (float *)calloc((size_t)max_ol + 1, sizeof(float));
+    for (int32_t i = 0; i < o->boost_n; ++i)
+      if (o->boost_ids[i] > 0 && o->boost_ids[i] <= max_ol) boost[o->boost_ids[i]] = o->boost_scores[i];
+  }
 
   /* initial set: start token, closed over epsilon arcs with best = 0 and no bin limit */
   { token_t t = { p->start, 0.0f, -1, -1 }; map[p->start] = 0; tv_push(&cur, t); }
   k.best = 0.0f; k.k_keep = 256;
-  eps_closure(p, &cur, map, &k, o->worklist_order, o->order_seed);
+  eps_closure(p, &cur, map, &k, o->worklist_order, o->order_seed, boost);
 
   for (int32_t t = 0; t <= len; ++t) {
     /* ---- store the closed set A_t: backpointers, digest, counters, dump */
@@ -346,6 +366,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       for (int64_t a = p->e_off[s]; a < p->e_off[s + 1]; ++a) {
         float ac = -L[p->e_il[a] - 1];
         float nc = canon((c + p->e_w[a]) + ac);
+        if (boost && p->e_ol[a] != 0) nc = canon(nc + boost[p->e_ol[a]]);
         if (!(nc < INFINITY)) continue;
         int32_t d = p->e_next[a]; int32_t q = map[d];
         if (q < 0) { token_t nt = { d, nc, i, (int32_t)a }; map[d] = nxt.n; tv_push(&nxt, nt); }
@@ -377,7 +398,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     nxt.n = m;
     res->counters[3] += m;
     /* ---- epsilon closure under the frozen predicate (R6) */
-    eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1);
+    eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1, boost);
     { tokvec tmp = cur; cur = nxt; nxt = tmp; }
   }
 
@@ -427,6 +448,6 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
   }
 done:
   for (int32_t t = 0; t <= len; ++t) free(lat[t]);
-  free(lat); free(lat_n); free(cur.t); free(nxt.t); free(map);
+  free(lat); free(lat_n); free(cur.t); free(nxt.t); free(map); free(boost);
   return rc;
 }
