@@ -80,6 +80,21 @@ typedef struct {
 } wfst_opts;
 
 /*
+ * Word boosting (paper, Section "Word boosting"): the table of a single-state boosting
+ * acceptor B, word id (an output label of the graph, > 0) -> score; boosted words get a
+ * NEGATIVE score since the decoder minimises.  The utterance is decoded as if the graph were
+ * TLG o B: on every arc, emitting or epsilon, whose olabel is in the table the score is
+ * added after the other terms (the green lines of the figure "Pseudo-code of Expand Arcs").
+ * Words absent from the graph's output labels have no effect.  HOST arrays, copied during
+ * the call; at most 1024 entries, no word twice, finite scores.
+ */
+typedef struct {
+  int32_t n;
+  const int32_t *word_ids;        /* [n] */
+  const float *scores;            /* [n] */
+} wfst_boost_table;
+
+/*
  * Build a decoder: validates the graph, splits emitting and epsilon arcs (global arc ids:
  * emitting arcs 0..Ae-1 in (state, given order), epsilon arcs Ae.. likewise), uploads it and
  * allocates the per-channel state.  Errors: INVALID_ARG, BAD_GRAPH, OOM, HIP.
@@ -110,13 +125,19 @@ int32_t wfst_decode_batch(wfst_decoder *dec, const float *loglikes, const int32_
                           int32_t B, int32_t T, int32_t V, float beam, int32_t max_active,
                           void *stream, int32_t *words, int32_t *nwords, float *cost,
                           int32_t *flags);
+/* The same with a word-boost table per utterance: boosts is a HOST array of B pointers (a NULL
+ * pointer, or NULL for the whole array, means no boosting for that utterance). */
+int32_t wfst_decode_batch_boosted(wfst_decoder *dec, const float *loglikes, const int32_t *lengths,
+                                  int32_t B, int32_t T, int32_t V, float beam, int32_t max_active,
+                                  const wfst_boost_table *const *boosts, void *stream,
+                                  int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
 
 /*
  * Streaming (Section "Streaming inference": the decoder state kept per audio stream is its
  * set of active tokens; here it lives permanently in the channel's slot in GPU memory, so
  * no gather/scatter is needed between chunks).
  *   wfst_init_channel : reset channel `ch` to the start token closed over epsilon arcs, and
- *                       fix its beam / max_active.  `boost` is reserved (pass NULL).
+ *                       fix its beam / max_active and its word-boost table (NULL = none).
  *   wfst_advance_chunk: feed n channels (HOST int32 channels[n], distinct) nframes[i] <= C
  *                       frames each from DEVICE loglikes [n][C][V]; nframes is HOST.
  *   wfst_get_partial  : best hypothesis of channel `ch` so far.  finalize = 0 ignores final
@@ -126,7 +147,7 @@ int32_t wfst_decode_batch(wfst_decoder *dec, const float *loglikes, const int32_
  *                       words [n][max_words], nwords [n], cost [n], flags [n].
  */
 int32_t wfst_init_channel(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
-                          const void *boost, void *stream);
+                          const wfst_boost_table *boost, void *stream);
 int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n,
                            const float *loglikes, const int32_t *nframes, int32_t C, int32_t V,
                            void *stream);

@@ -18,7 +18,8 @@ ERRORS = {-1: "INVALID_ARG", -2: "BAD_GRAPH", -3: "OOM", -4: "LATTICE_OVERFLOW",
           -5: "BAD_CHANNEL", -6: "HIP", -7: "CAPACITY"}
 FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPACITY = 1, 2, 4, 8, 16
 
-EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_init_channel",
+EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
+           "wfst_init_channel",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
@@ -35,6 +36,18 @@ class wfst_graph_csr(C.Structure):
                 ("num_arcs", C.c_int64), ("row_offsets", C.c_void_p), ("next_state", C.c_void_p),
                 ("ilabel", C.c_void_p), ("olabel", C.c_void_p), ("weight", C.c_void_p),
                 ("final_cost", C.c_void_p)]
+
+
+class wfst_boost_table(C.Structure):
+    _fields_ = [("n", C.c_int32), ("word_ids", C.c_void_p), ("scores", C.c_void_p)]
+
+
+def _boost_struct(boost):
+    """(word_ids, scores) -> (wfst_boost_table, arrays to keep alive)."""
+    ids = np.ascontiguousarray(boost[0], dtype=np.int32)
+    sc = np.ascontiguousarray(boost[1], dtype=np.float32)
+    assert ids.shape == sc.shape and ids.ndim == 1
+    return wfst_boost_table(len(ids), ids.ctypes.data, sc.ctypes.data), (ids, sc)
 
 
 class wfst_opts(C.Structure):
@@ -63,6 +76,7 @@ def load_library():
     lib.wfst_decoder_create.argtypes = [C.POINTER(wfst_graph_csr), C.POINTER(wfst_opts), C.POINTER(p)]
     lib.wfst_decoder_destroy.argtypes = [p]
     lib.wfst_decode_batch.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p]
+    lib.wfst_decode_batch_boosted.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p, p]
     lib.wfst_init_channel.argtypes = [p, i32, f32, i32, p, p]
     lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
     lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
@@ -77,7 +91,7 @@ def load_library():
     lib.wfst_last_kernel_ms.restype = f32
     lib.wfst_last_error.argtypes = [p]
     lib.wfst_last_error.restype = C.c_char_p
-    for name in EXPORTS[:11]:
+    for name in EXPORTS[:12]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -132,8 +146,9 @@ class Decoder:
             raise WfstError(rc, self.lib.wfst_last_error(self.h).decode())
 
     # ---- offline
-    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None):
+    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None, boosts=None):
         """loglikes: CUDA float32 tensor [B, T, V]; lengths: int32 host array [B].
+        boosts: optional list of B entries, each None or a (word_ids, scores) table.
         Returns (words [B, max_words], nwords [B], cost [B], flags [B]); torch CUDA tensors, or
         numpy arrays when the decoder was created with outputs_on_host."""
         import torch
@@ -152,14 +167,27 @@ class Decoder:
                        torch.zeros(B, dtype=torch.float32, device=dev),
                        torch.zeros(B, dtype=torch.int32, device=dev))
         ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
-        self._check(self.lib.wfst_decode_batch(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
-                                               beam, max_active, _stream_ptr(stream),
-                                               ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3])))
+        if boosts is None:
+            self._check(self.lib.wfst_decode_batch(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
+                                                   beam, max_active, _stream_ptr(stream),
+                                                   ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3])))
+            return out
+        assert len(boosts) == B
+        keep = [None if t is None else _boost_struct(t) for t in boosts]
+        arr = (C.c_void_p * B)(*[None if k is None else C.addressof(k[0]) for k in keep])
+        self._check(self.lib.wfst_decode_batch_boosted(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
+                                                       beam, max_active, arr, _stream_ptr(stream),
+                                                       ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3])))
         return out
 
     # ---- streaming
-    def init_channel(self, ch, beam, max_active, stream=None):
-        self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, None, _stream_ptr(stream)))
+    def init_channel(self, ch, beam, max_active, stream=None, boost=None):
+        """boost: None or a (word_ids, scores) table for this stream."""
+        if boost is None:
+            self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, None, _stream_ptr(stream)))
+        else:
+            t, keep = _boost_struct(boost)
+            self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, C.byref(t), _stream_ptr(stream)))
 
     def advance_chunk(self, channels, loglikes, nframes, stream=None):
         """loglikes: CUDA float32 [n, C, V]; channels, nframes: host int32 [n]."""

@@ -78,6 +78,8 @@ constexpr int kRegions = 4;                   // candidate buffer regions (by de
 constexpr int kTabSlots = WFST_TAB;           // LDS recombination table (power of two)
 constexpr unsigned kTabMask = kTabSlots - 1;
 constexpr int kGroupTarget = kTabSlots * 9 / 16;  // mean candidates reduced per table pass (load 0.56)
+constexpr int kBoostSlots = 2048;             // per-channel word-boost table (open addressing)
+constexpr int kBoostMax = 1024;               // entries it may hold
 constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
@@ -95,6 +97,7 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   float beam, scale;          // scale = 256 / beam, computed once on the host
   unsigned epoch;             // closed sets published since create (tags the state index)
   float sel_ratio;            // candidates taken into recombination per max_active (adaptive)
+  int boost_n;                // entries of the channel's word-boost table (0 = none); set by the host
 };
 
 struct DevGraph {
@@ -118,6 +121,7 @@ struct DevChannels {
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
   long long *counters;                         // [24]: 8 workload counters, 16 phase tick sums
+  int *boost_keys; float *boost_vals;          // [channels][kBoostSlots]; key 0 = free slot
 };
 
 struct LaunchArgs {
@@ -151,6 +155,7 @@ struct Smem {
   unsigned long long red64, red64b;
   long long ctr[8];
   unsigned short occ[kTabSlots];   // occupied table slots, compacted
+  int bk[kBoostSlots]; float bv[kBoostSlots];   // the channel's word-boost table, if it has one
   long long prof[16];         // wall-clock ticks per phase (thread 0)
   long long prof_t0;
   int sel_idx;
@@ -166,12 +171,17 @@ __device__ __forceinline__ float ord2f(unsigned o) {
 }
 __device__ __forceinline__ float canon(float x) { return x == 0.0f ? 0.0f : x; }
 __device__ __forceinline__ unsigned hash_state(int s) { return (unsigned)s * 0x9E3779B1u; }
+__host__ __device__ inline unsigned boost_slot(int word) { return ((unsigned)word * 0x9E3779B1u) >> 21; }   // 11 bits
 __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   x += 0x9E3779B97F4A7C15ull;
   x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
   x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
   return x ^ (x >> 31);
 }
+
+// Word boosting (paper, Section "Word boosting"): score of the single-state boosting acceptor
+// for output label `word` (never 0), 0 if the word is not in the utterance's table.
+__device__ __forceinline__ float boost_of(const Smem &sm, int word);
 
 // Values read from LDS or global memory that are the same in every lane: tell the compiler,
 // so that they live in scalar registers and control flow on them is scalar.
@@ -218,6 +228,16 @@ struct Ctx {                  // block-uniform view of one channel
 };
 // workload counters of this launch, kept in LDS (thread 0 adds the block-uniform ones)
 enum { kCtTok = 0, kCtEarc, kCtXarc, kCtKept, kCtStored, kCtMaxAct, kCtBin0, kCtFrames };
+
+__device__ __forceinline__ float boost_of(const Smem &sm, int word) {
+  unsigned h = boost_slot(word);
+  for (;;) {
+    const int k = sm.bk[h];
+    if (k == word) return sm.bv[h];
+    if (k == 0) return 0.0f;                 // the table is never full (kBoostMax < kBoostSlots)
+    h = (h + 1) & (kBoostSlots - 1);
+  }
+}
 
 // Phase timing with the constant-rate wall clock (thread 0 only; a few scalar reads per frame).
 enum { kPhExpand = 0, kPhSelect, kPhCutoff, kPhEpsExpand, kPhEpsRecombine, kPhFinish, kPhTrace, kPhOther,
@@ -355,6 +375,7 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
   ExpandLds &e = sm.u.e;
   const int tid = threadIdx.x;
   const float beam = x.s.beam;
+  const bool boosted = x.s.boost_n > 0;
   for (int cb = 0; cb < n_tok; cb += kChunk) {
     int4 tk[kTPT]; unsigned deg[kTPT], ex[kTPT];
 #pragma unroll
@@ -393,6 +414,7 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
 #pragma unroll
       for (int u = 0; u < kUE; ++u) {
         nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + e.ac[a[u].z - 1]);
+        if (boosted && a[u].w != 0 && ok[u]) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // + b[olabel]
         ok[u] = ok[u] && (nc[u] < INFINITY) && !((nc[u] - rb) > beam);
         if (ok[u]) o = min(o, f2ord(nc[u]));
       }
@@ -742,6 +764,7 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
   const unsigned tag = set_tag(x.s.epoch);
+  const bool boosted = x.s.boost_n > 0;
   int n_wl = uni(min(sm.n_wl_next, x.c.qcap));
   __syncthreads();
   if (tid == 0) sm.n_wl_next = 0;
@@ -785,6 +808,10 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           nc[u] = canon(tc[u] + __int_as_float(a[u].y));
+          if (boosted && ok[u]) {                 // epsilon arcs can carry output labels too
+            const int ol = x.g.olabel[x.g.Ae + arc[u]];
+            if (ol != 0) nc[u] = canon(nc[u] + boost_of(sm, ol));
+          }
           ok[u] = ok[u] && (nc[u] < INFINITY) && cut.keep(nc[u]);
           dst[u] = a[u].x; arc[u] += x.g.Ae;
         }
@@ -1015,6 +1042,12 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
   x.s.scale = uni(x.s.scale); x.s.epoch = uni(x.s.epoch); x.s.sel_ratio = uni(x.s.sel_ratio);
+  x.s.boost_n = uni(x.s.boost_n);
+  if (x.s.boost_n > 0)
+    for (int i = tid; i < kBoostSlots; i += kBlock) {
+      sm.bk[i] = c.boost_keys[(size_t)ch * kBoostSlots + i];
+      sm.bv[i] = c.boost_vals[(size_t)ch * kBoostSlots + i];
+    }
 
   if (tid == 0) {
     sm.best_ord = kOrdNone; sm.n_occ = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
@@ -1100,6 +1133,9 @@ struct wfst_decoder {
   std::vector<int> h_params[kRing];
   // device staging for host-side outputs
   int *o_words = nullptr, *o_nwords = nullptr, *o_flags = nullptr; float *o_cost = nullptr;
+  // word-boost tables: pinned host staging per channel (keys, values, count) + what is on the device
+  int *h_boost = nullptr;            // [channels][2 * kBoostSlots + 1]
+  std::vector<int> boost_on_dev;     // entries of the table each channel currently has on the device
   hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
   std::string err;
 };
@@ -1251,6 +1287,12 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipMemset(c.counters, 0, 24 * sizeof(long long)));
   HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
   HIP_TRY(d, hipMemset(c.index, 0, N * (size_t)d->g.S * sizeof(unsigned)));   // tag 0 = no token
+  if ((rc = dev_alloc(d, &c.boost_keys, N * kBoostSlots))) return rc;
+  if ((rc = dev_alloc(d, &c.boost_vals, N * kBoostSlots))) return rc;
+  HIP_TRY(d, hipMemset(c.boost_keys, 0, N * kBoostSlots * sizeof(int)));
+  HIP_TRY(d, hipMemset(c.boost_vals, 0, N * kBoostSlots * sizeof(float)));
+  HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_boost), N * (2 * kBoostSlots + 1) * sizeof(int)));
+  d->boost_on_dev.assign(N, 0);
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
   if (o.outputs_on_host) {
     if ((rc = dev_alloc(d, &d->o_words, N * (size_t)o.max_words))) return rc;
@@ -1287,6 +1329,38 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
 
 bool valid_prune(float beam, int max_active) { return beam >= 0.0f && max_active >= 1; }
 
+// Give channel `ch` the word-boost table `t` (nullptr or n == 0: none) before its next init.
+// The table becomes an open-addressing hash (key 0 = free) in the channel's slot; the copies
+// are ordered on `st` before the init kernel.
+int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st) {
+  const int n = t ? t->n : 0;
+  if (n == 0 && d->boost_on_dev[ch] == 0) return WFST_OK;
+  if (n < 0 || n > kBoostMax) return fail(d, WFST_ERR_INVALID_ARG, "boost table with more than " + std::to_string(kBoostMax) + " entries");
+  if (n > 0 && (!t->word_ids || !t->scores)) return fail(d, WFST_ERR_INVALID_ARG, "null boost table arrays");
+  int *h = d->h_boost + (size_t)ch * (2 * kBoostSlots + 1);
+  int *keys = h; float *vals = reinterpret_cast<float *>(h + kBoostSlots); int *cnt = h + 2 * kBoostSlots;
+  std::memset(h, 0, (2 * kBoostSlots + 1) * sizeof(int));
+  for (int i = 0; i < n; ++i) {
+    const int w = t->word_ids[i];
+    if (w <= 0) return fail(d, WFST_ERR_INVALID_ARG, "boost word ids must be positive output labels");
+    if (!std::isfinite(t->scores[i])) return fail(d, WFST_ERR_INVALID_ARG, "non-finite boost score");
+    unsigned s = boost_slot(w);
+    while (keys[s] != 0) {
+      if (keys[s] == w) return fail(d, WFST_ERR_INVALID_ARG, "word id " + std::to_string(w) + " appears twice in the boost table");
+      s = (s + 1) & (kBoostSlots - 1);
+    }
+    keys[s] = w; vals[s] = t->scores[i];
+  }
+  *cnt = n;
+  if (n > 0) {
+    HIP_TRY(d, hipMemcpyAsync(d->c.boost_keys + (size_t)ch * kBoostSlots, keys, kBoostSlots * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(d, hipMemcpyAsync(d->c.boost_vals + (size_t)ch * kBoostSlots, vals, kBoostSlots * sizeof(float), hipMemcpyHostToDevice, st));
+  }
+  HIP_TRY(d, hipMemcpyAsync(&d->c.st[ch].boost_n, cnt, sizeof(int), hipMemcpyHostToDevice, st));
+  d->boost_on_dev[ch] = n;
+  return WFST_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1319,6 +1393,7 @@ int32_t wfst_decoder_destroy(wfst_decoder *d) {
   if (!d) return WFST_OK;
   (void)hipDeviceSynchronize();
   for (void *p : d->allocs) (void)hipFree(p);
+  if (d->h_boost) (void)hipHostFree(d->h_boost);
   if (d->ev0) (void)hipEventDestroy(d->ev0);
   if (d->ev1) (void)hipEventDestroy(d->ev1);
   delete d;
@@ -1328,6 +1403,14 @@ int32_t wfst_decoder_destroy(wfst_decoder *d) {
 int32_t wfst_decode_batch(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
                           int32_t T, int32_t V, float beam, int32_t max_active, void *stream,
                           int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
+  return wfst_decode_batch_boosted(d, loglikes, lengths, B, T, V, beam, max_active, nullptr, stream,
+                                   words, nwords, cost, flags);
+}
+
+int32_t wfst_decode_batch_boosted(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+                                  int32_t T, int32_t V, float beam, int32_t max_active,
+                                  const wfst_boost_table *const *boosts, void *stream,
+                                  int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
   if (!d) return WFST_ERR_INVALID_ARG;
   if (B < 0 || T < 0) return fail(d, WFST_ERR_INVALID_ARG, "negative B or T");
   if (B == 0) return WFST_OK;              // nothing to decode; pointers may be null
@@ -1340,6 +1423,10 @@ int32_t wfst_decode_batch(wfst_decoder *d, const float *loglikes, const int32_t 
     if (lengths[b] < 0 || lengths[b] > T || lengths[b] > d->opts.max_frames_per_channel)
       return fail(d, WFST_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, min(T, max_frames_per_channel)]");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int b = 0; b < B; ++b) {
+    const int rcb = set_boost(d, b, boosts ? boosts[b] : nullptr, st);
+    if (rcb) return rcb;
+  }
   // longest utterances first: workgroups are dispatched in order, so the long ones start
   // at once and the short ones fill in behind them
   std::vector<int> order(B), nfr(B);
@@ -1372,11 +1459,12 @@ int32_t wfst_decode_batch(wfst_decoder *d, const float *loglikes, const int32_t 
 }
 
 int32_t wfst_init_channel(wfst_decoder *d, int32_t ch, float beam, int32_t max_active,
-                          const void *boost, void *stream) {
+                          const wfst_boost_table *boost, void *stream) {
   if (!d) return WFST_ERR_INVALID_ARG;
-  if (boost) return fail(d, WFST_ERR_INVALID_ARG, "boost tables are not supported by this build");
   if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
   if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
+  const int rcb = set_boost(d, ch, boost, static_cast<hipStream_t>(stream));
+  if (rcb) return rcb;
   LaunchArgs a{};
   a.V = d->V; a.mode = kModeInit;
   a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;

@@ -23,29 +23,29 @@ def torch_cuda():
     return torch
 
 
-def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, threads=16, **kw):
+def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, threads=16, boosts=None, **kw):
     from oracle import Oracle
     o = Oracle(graph)
 
     def one(b):
         return o.decode(loglikes[b], length=int(lengths[b]), beam=beam, max_active=max_active,
-                        max_words=max_words, want_digests=True, **kw)
+                        max_words=max_words, want_digests=True, boost=None if boosts is None else boosts[b], **kw)
     with ThreadPoolExecutor(threads) as ex:
         return list(ex.map(one, range(len(lengths))))
 
 
 def check_batch(torch, graph, loglikes, lengths, beam, max_active, max_words=256, refs=None,
-                max_active_hint=None, check_counters=True, **deckw):
+                max_active_hint=None, check_counters=True, boosts=None, **deckw):
     from paper_2311_04996_amd import Decoder
     B, T, V = loglikes.shape
     dec = Decoder(graph, max_channels=max(B, 1), max_frames=max(T, 1), max_words=max_words,
                   max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True, **deckw)
     ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda()
-    words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active)
+    words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active, boosts=boosts)
     torch.cuda.synchronize()
     words, nwords, cost, flags = words.cpu().numpy(), nwords.cpu().numpy(), cost.cpu().numpy(), flags.cpu().numpy()
     if refs is None:
-        refs = oracle_batch(graph, loglikes, lengths, beam, max_active, max_words)
+        refs = oracle_batch(graph, loglikes, lengths, beam, max_active, max_words, boosts=boosts)
     near_ties = 0
     for b, r in enumerate(refs):
         cnt, dig = dec.debug_frame_digests(b)
@@ -352,3 +352,66 @@ def test_state_index_tag_wraps_after_65535_token_sets(torch_cuda, c1):
     w, c, f = dec.get_partial(0, finalize=True)
     assert w.tolist() == ref.words.tolist() and c == ref.cost and f == ref.flags
     dec.close()
+
+
+# ------------------------------------------------------------------------------- word boosting
+def test_boost_on_micro_graphs(torch_cuda):
+    """Output labels on emitting and epsilon arcs, dyadic weights and boosts (exact ties),
+    a different table per utterance, one utterance without a table."""
+    from workloads import micro_graph
+    for seed in range(15):
+        rng = np.random.default_rng(100 + seed)
+        V, T, B = 3, 9, 4
+        g = micro_graph(900 + seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+        ll = -(rng.integers(0, 40, size=(B, T, V)).astype(np.float32) / 8.0)
+        lengths = rng.integers(1, T + 1, size=B).astype(np.int32)
+        boosts = [(rng.choice(5, size=3, replace=False).astype(np.int32) + 1,
+                   -(rng.integers(1, 9, size=3).astype(np.float32) / 4.0)) for _ in range(B)]
+        boosts[1] = None
+        for beam, ma in ((INF, IMAX), (3.0, 6)):
+            check_batch(torch_cuda, g, ll, lengths, beam, ma, max_active_hint=1000, boosts=boosts)
+
+
+def test_boost_changes_the_result_and_plain_decode_resets_it(torch_cuda, c1):
+    """A boosted decode followed by a plain one on the same channel: the table must not linger."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    ids = np.arange(1, 101, dtype=np.int32)
+    boost = (ids, np.full(100, -2.0, np.float32))
+    o = Oracle(c1.graph)
+    plain = o.decode(c1.loglikes[0], beam=c1.beam, max_active=c1.max_active)
+    boosted = o.decode(c1.loglikes[0], beam=c1.beam, max_active=c1.max_active, boost=boost)
+    assert boosted.cost != plain.cost
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active, outputs_on_host=True)
+    ll = torch.from_numpy(c1.loglikes).cuda()
+    for want, b in ((boosted, [boost]), (plain, None), (boosted, [boost]), (plain, [None])):
+        words, nwords, cost, flags = dec.decode_batch(ll, c1.lengths, c1.beam, c1.max_active, boosts=b)
+        assert words[0, :nwords[0]].tolist() == want.words.tolist() and cost[0] == np.float32(want.cost)
+    # streaming: the table is given when the stream is created
+    dec.init_channel(0, c1.beam, c1.max_active, boost=boost)
+    dec.advance_chunk([0], ll, [100])
+    w, c, f = dec.get_partial(0, finalize=True)
+    assert w.tolist() == boosted.words.tolist() and c == boosted.cost
+    dec.close()
+
+
+def test_boost_table_errors(torch_cuda, c1):
+    from paper_2311_04996_amd import Decoder, WfstError
+    dec = Decoder(c1.graph, max_channels=1, max_frames=10, max_active_hint=100)
+    for bad in (([3, 3], [-1.0, -1.0]), ([0], [-1.0]), ([5], [float("nan")]),
+                (np.arange(1, 1026), np.full(1025, -1.0))):
+        with pytest.raises(WfstError) as e:
+            dec.init_channel(0, 10.0, 100, boost=bad)
+        assert e.value.code == -1
+    dec.close()
+
+
+def test_c5_boosted_medium_batch_matches_oracle(torch_cuda):
+    """Configuration 5: the medium graph and batch, every utterance with its own table of 100
+    vocabulary words at -2.0, applied on the fly (the product graph is never built)."""
+    from workloads import make_config
+    w = make_config("c5_boost")
+    refs = check_batch(torch_cuda, w.graph, w.loglikes, w.lengths, w.beam, w.max_active, boosts=w.boosts)
+    plain = oracle_batch(w.graph, w.loglikes[:4], w.lengths[:4], w.beam, w.max_active)
+    assert any(r.cost != p.cost for r, p in zip(refs, plain)), "the tables must matter"

@@ -7,8 +7,8 @@ and benchmark.  Everything is a deterministic function of an integer seed.
 from .graphs import (Graph, tiny_lexicon_graph, tlg_shaped_graph, ctc_topology_graph,
                      micro_graph, permute_arcs_within_states)
 from .loglikes import ctc_loglikes, random_lengths
-from .configs import CONFIGS, make_config
+from .configs import CONFIGS, make_config, boost_tables
 
 __all__ = ["Graph", "tiny_lexicon_graph", "tlg_shaped_graph", "ctc_topology_graph",
            "micro_graph", "permute_arcs_within_states", "ctc_loglikes", "random_lengths",
-           "CONFIGS", "make_config"]
+           "CONFIGS", "make_config", "boost_tables"]

@@ -29,6 +29,13 @@ CONFIGS = {
                      batch=256, len_lo=50, len_hi=875, seed=3,
                      ll=dict(sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0),
                      beam=17.0, max_active=10000),
+    # config 2 with a word-boost table per utterance (100 words of the vocabulary at -2.0)
+    "c5_boost": dict(graph=("tlg", dict(seed=2, num_states=200_000, target_arcs=1_000_000,
+                                        num_classes=129, alpha=1.8, k_max=5000, p_eps=0.15,
+                                        num_words=20_000)),
+                     batch=32, len_lo=50, len_hi=875, seed=2,
+                     ll=dict(sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0),
+                     beam=17.0, max_active=7000, boost=dict(seed=5, per_utt=100, score=-2.0)),
     # a scaled-down graph of the c3 family for quick runs (not a reported configuration)
     "c3_mini": dict(graph=("tlg", dict(seed=3, num_states=1_000_000, target_arcs=3_000_000,
                                        num_classes=129, alpha=1.8, k_max=5000, p_eps=0.20,
@@ -39,6 +46,17 @@ CONFIGS = {
 }
 
 
+def boost_tables(seed: int, batch: int, num_words: int, per_utt: int = 100, score: float = -2.0):
+    """Per-utterance word-boost tables: per_utt distinct word ids uniform over the graph's
+    vocabulary, every one boosted by `score` (negative = preferred).  List of (ids, scores)."""
+    out = []
+    for b in range(batch):
+        rng = np.random.default_rng([seed, 0xB005, b])
+        ids = rng.choice(num_words, size=per_utt, replace=False).astype(np.int32) + 1
+        out.append((ids, np.full(per_utt, score, dtype=np.float32)))
+    return out
+
+
 @dataclass
 class Workload:
     name: str
@@ -47,6 +65,7 @@ class Workload:
     loglikes: np.ndarray     # float32 [B, T, V]
     beam: float
     max_active: int
+    boosts: list | None = None   # per-utterance (word ids, scores) or None
 
     @property
     def audio_seconds(self) -> float:
@@ -65,4 +84,7 @@ def make_config(name: str, batch: int | None = None, graph: Graph | None = None)
     lengths = random_lengths(c["seed"], B, c["len_lo"], c["len_hi"])
     T = int(lengths.max())
     ll = ctc_loglikes(c["seed"], lengths, T, g.num_classes, **c["ll"])
-    return Workload(name, g, lengths, ll, float(c["beam"]), int(c["max_active"]))
+    boosts = None
+    if "boost" in c:
+        boosts = boost_tables(c["boost"]["seed"], B, int(g.meta["num_words"]), c["boost"]["per_utt"], c["boost"]["score"])
+    return Workload(name, g, lengths, ll, float(c["beam"]), int(c["max_active"]), boosts)
