@@ -132,12 +132,15 @@ struct LaunchArgs {
   int *words, *nwords; float *cost; int *flags; int max_words;
 };
 
+struct ChunkLds {             // one chunk of work items, flattened over their arcs
+  unsigned pre[kChunk + 1];   // exclusive prefix sums of the items' arc counts
+  int abase[kChunk];          // first arc of the item minus its prefix
+  float tcost[kChunk];        // cost of the item's token
+  int ttok[kChunk];           // the item's token (epsilon expansion only)
+};
 struct ExpandLds {            // live while arcs are being expanded
   float ac[kMaxV];
-  unsigned pre[kChunk + 1];
-  int abase[kChunk];
-  float tcost[kChunk];
-  int ttok[kChunk];
+  ChunkLds ch[2];             // double-buffered: a wave may start the next chunk while others finish this one
 };
 struct TableLds {             // live while candidates are being recombined
   unsigned long long vals[kTabSlots];   // (orderable cost << 32) | candidate index
@@ -282,12 +285,12 @@ __device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[kTP
 }
 
 // Which of the chunk's work items owns flattened arc f: last j with pre[j] <= f.
-__device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
+__device__ __forceinline__ int owner_of(const ChunkLds &ck, unsigned f) {
   int lo = 0, hi = kChunk;
 #pragma unroll
   for (int it = 0; it < kChunkLog2; ++it) {
     int mid = (lo + hi) >> 1;
-    if (sm.u.e.pre[mid] <= f) lo = mid; else hi = mid;
+    if (ck.pre[mid] <= f) lo = mid; else hi = mid;
   }
   return lo;
 }
@@ -298,13 +301,13 @@ __device__ __forceinline__ int owner_of(const Smem &sm, unsigned f) {
 // lane's own search to the few items its run spans: 0 steps inside a high-degree state,
 // ~5 where degrees are small, instead of log2(kChunk) for every arc.
 template <int N>
-__device__ __forceinline__ void owners_of(const Smem &sm, unsigned f0, unsigned M, bool (&ok)[N], int (&j)[N]) {
+__device__ __forceinline__ void owners_of(const ChunkLds &ck, unsigned f0, unsigned M, bool (&ok)[N], int (&j)[N]) {
   static_assert(2 * N <= 64, "bounds are looked up by 2N lanes");
   const int lane = threadIdx.x & 63;
   const unsigned wave_f = f0 + (threadIdx.x & ~63u);
   unsigned fq = wave_f + (unsigned)(lane >> 1) * kBlock + ((lane & 1) ? 63u : 0u);
   if (lane >= 2 * N || fq >= M) fq = M - 1;
-  const int bound = owner_of(sm, fq);
+  const int bound = owner_of(ck, fq);
 #pragma unroll
   for (int u = 0; u < N; ++u) {
     const unsigned f = f0 + u * kBlock + threadIdx.x;
@@ -314,7 +317,7 @@ __device__ __forceinline__ void owners_of(const Smem &sm, unsigned f0, unsigned 
     const unsigned fs = ok[u] ? f : M - 1;
     for (int it = 0; it < steps; ++it) {
       const int mid = (lo + hi) >> 1;
-      if (sm.u.e.pre[mid] <= fs) lo = mid; else hi = mid;
+      if (ck.pre[mid] <= fs) lo = mid; else hi = mid;
     }
     j[u] = lo;
   }
@@ -376,7 +379,8 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
   const int tid = threadIdx.x;
   const float beam = x.s.beam;
   const bool boosted = x.s.boost_n > 0;
-  for (int cb = 0; cb < n_tok; cb += kChunk) {
+  for (int cb = 0, par = 0; cb < n_tok; cb += kChunk, par ^= 1) {
+    ChunkLds &ck = e.ch[par];
     int4 tk[kTPT]; unsigned deg[kTPT], ex[kTPT];
 #pragma unroll
     for (int k = 0; k < kTPT; ++k) {
@@ -388,22 +392,22 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
     const unsigned M = block_scan(sm, deg, ex);
 #pragma unroll
     for (int k = 0; k < kTPT; ++k) {
-      e.pre[kTPT * tid + k] = ex[k];
-      e.abase[kTPT * tid + k] = tk[k].z - (int)ex[k];
-      e.tcost[kTPT * tid + k] = __int_as_float(tk[k].y);
+      ck.pre[kTPT * tid + k] = ex[k];
+      ck.abase[kTPT * tid + k] = tk[k].z - (int)ex[k];
+      ck.tcost[kTPT * tid + k] = __int_as_float(tk[k].y);
     }
-    if (tid == kBlock - 1) e.pre[kChunk] = M;
+    if (tid == kBlock - 1) ck.pre[kChunk] = M;
     __syncthreads();
     prof_mark(sm, kPhExpSetup);
     if (tid == 0) sm.ctr[kCtEarc] += M;
     for (unsigned f0 = 0; f0 < M; f0 += kBlock * kUE) {
       bool ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
-      owners_of<kUE>(sm, f0, M, ok, j);
+      owners_of<kUE>(ck, f0, M, ok, j);
 #pragma unroll
       for (int u = 0; u < kUE; ++u) {          // arc fetch, kUE in flight
-        arc[u] = e.abase[j[u]] + (int)(f0 + u * kBlock + tid);
+        arc[u] = ck.abase[j[u]] + (int)(f0 + u * kBlock + tid);
         src[u] = cb + j[u];
-        tc[u] = e.tcost[j[u]];
+        tc[u] = ck.tcost[j[u]];
         a[u] = make_int4(0, 0, 1, 0);
         if (ok[u]) a[u] = x.g.earc[arc[u]];
       }
@@ -427,9 +431,9 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
       for (int u = 0; u < kUE; ++u) dst[u] = a[u].x;
       push_cands<kUE>(x, ok, dst, nc, src, arc);
     }
-    __syncthreads();
-    prof_mark(sm, kPhExpLoop);
+    prof_mark(sm, kPhExpLoop);        // no barrier: the next chunk uses the other table buffer
   }
+  __syncthreads();
 }
 
 // ------------------------------------------------------------------ recombination in LDS
@@ -772,7 +776,8 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
   for (int round = 0; n_wl > 0; ++round) {
     if (round > (1 << 20)) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
     const int4 *WL = x.wl0 + sel * x.c.qcap; int4 *WLN = x.wl0 + (sel ^ 1) * x.c.qcap;
-    for (int cb = 0; cb < n_wl; cb += kChunk) {
+    for (int cb = 0, par = 0; cb < n_wl; cb += kChunk, par ^= 1) {
+      ChunkLds &ck = e.ch[par];
       unsigned deg[kTPT], ex[kTPT]; int4 w[kTPT]; int cs[kTPT];
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
@@ -786,21 +791,21 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
       const unsigned M = block_scan(sm, deg, ex);
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
-        e.pre[kTPT * tid + k] = ex[k];
-        e.abase[kTPT * tid + k] = w[k].y - (int)ex[k];
-        e.tcost[kTPT * tid + k] = __int_as_float(cs[k]);
-        e.ttok[kTPT * tid + k] = w[k].x;
+        ck.pre[kTPT * tid + k] = ex[k];
+        ck.abase[kTPT * tid + k] = w[k].y - (int)ex[k];
+        ck.tcost[kTPT * tid + k] = __int_as_float(cs[k]);
+        ck.ttok[kTPT * tid + k] = w[k].x;
       }
-      if (tid == kBlock - 1) e.pre[kChunk] = M;
+      if (tid == kBlock - 1) ck.pre[kChunk] = M;
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
         bool ok[kU]; int src[kU]; int2 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
-        owners_of<kU>(sm, f0, M, ok, j);
+        owners_of<kU>(ck, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-          arc[u] = e.abase[j[u]] + (int)(f0 + u * kBlock + tid);
-          src[u] = e.ttok[j[u]];
-          tc[u] = e.tcost[j[u]];
+          arc[u] = ck.abase[j[u]] + (int)(f0 + u * kBlock + tid);
+          src[u] = ck.ttok[j[u]];
+          tc[u] = ck.tcost[j[u]];
           a[u] = make_int2(0, 0);
           if (ok[u]) a[u] = x.g.xarc[arc[u]];
         }
@@ -817,8 +822,8 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
         }
         push_cands<kU>(x, ok, dst, nc, src, arc);
       }
-      __syncthreads();
     }
+    __syncthreads();
     prof_mark(sm, kPhEpsExpand);
     const int n_cand = total_candidates(x);
     PassPlan plan;
@@ -1108,7 +1113,14 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     x.s.n_tok = 0;
   }
   prof_mark(sm, kPhOther);
-  if (a.mode & kModeFinal) select_and_trace(x, a, io);
+  if (a.mode & kModeFinal) {
+    // The traceback is a separate function that takes its context by reference.  It gets
+    // copies, so that the pointers of the frame loop above never live in memory: only then
+    // does the compiler know they are global and keep them in registers.
+    const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
+    Ctx x2{g2, c2, sm, x.cand, x.win_sc, x.win_ci, x.q0, x.wl0, x.index, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
+    select_and_trace(x2, a2, io);
+  }
   prof_mark(sm, kPhTrace);
   if (tid == 0) {
     c.st[ch] = x.s;
