@@ -18,12 +18,22 @@
 // needs.  A dense per-state index (tagged with the frame epoch, so it never needs clearing)
 // answers "does this state already have a token" for the epsilon closure.
 //
+// The graph is stored as one array of 16-byte units, a block per state: a header
+// {emitting degree, epsilon degree, state id, final cost}, then the state's epsilon arcs, then
+// its emitting arcs, every arc {next, weight, ilabel, olabel}, padded to 32 bytes.  A state is
+// named by its block number (byte offset / 32), which is also the recombination key and grows
+// with the state id.  `next` of an arc is the destination's block number plus two flag bits
+// (the destination has epsilon arcs / an epsilon arc enters it), so a token is created from
+// the arc alone and the only random graph read per token is the 32-byte header + first arc
+// when the token is expanded.  An arc's id is its unit address (epsilon arcs have bit 30 set),
+// which orders arcs exactly as (emitting before epsilon, state, position) does.
+//
 // Per channel, in HBM:
-//   token queue   2 x qcap records {state, cost, first emitting arc, emitting degree}
-//   candidates    cand_cap records {dst state, cost, source token, arc id}
+//   token queue   2 x qcap records {block number, cost}
+//   candidates    cand_cap records {next (block number + flags), cost, source token, arc id}
 //   winners       recombined in-beam tokens before the max-active cutoff is known
-//   state index   S x 4 B: (epoch tag << 16) | token index
-//   worklists     2 x qcap records {token, first epsilon arc, epsilon degree}
+//   state index   one 4-byte entry per 32 bytes of graph: (epoch tag << 16) | token index
+//   worklists     2 x qcap records {token, block number, cost, first time}
 //   lattice       {prev token, arc id} per stored token, frame after frame
 // LDS holds, per phase, either the expansion tables (negated log-likelihood row and, per chunk
 // of 2048 tokens, the prefix sums of their arc counts so that every lane owns one arc of the
@@ -85,6 +95,11 @@ constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
 constexpr unsigned kOrdNone = 0xFFFFFFFFu;
 constexpr int kModeInit = 1, kModeFinal = 2;
+constexpr unsigned kKeyMask = 0x1fffffffu;     // block number of a state (32-byte units)
+constexpr unsigned kFlagHasEps = 0x80000000u;  // `next` of an arc: the destination has epsilon arcs
+constexpr unsigned kFlagEpsIn = 0x40000000u;   //                   an epsilon arc enters the destination
+constexpr unsigned kArcEps = 0x40000000u;      // arc ids: unit address, plus this bit for epsilon arcs
+constexpr unsigned kArcMask = 0x3fffffffu;
 constexpr int kStLattice = WFST_FLAG_LATTICE_OVERFLOW, kStCapacity = WFST_FLAG_CAPACITY;
 
 struct ChanState {            // persists between calls (the per-stream decoder state)
@@ -101,22 +116,21 @@ struct ChanState {            // persists between calls (the per-stream decoder 
 };
 
 struct DevGraph {
-  const int4 *state;          // [S] {first emitting arc, first epsilon arc, emitting degree,
-                              //      epsilon degree | sign bit: some epsilon arc enters this state}
-  const int4 *earc;           // [Ae]  {next state, weight bits, ilabel, olabel}
-  const int2 *xarc;           // [Ax]  {next state, weight bits}
-  const int *olabel;          // [Ae+Ax] by global arc id (traceback only)
-  const float *final_cost;    // [S] or nullptr (all final, cost 0)
-  int S, start, Ae, Ax;
+  const int4 *unit;           // state blocks: header {emitting degree, epsilon degree, state id, final cost},
+                              // epsilon arcs, emitting arcs {next, weight bits, ilabel, olabel}
+  unsigned n_blk;             // 32-byte blocks in `unit` (the state index has one entry per block)
+  unsigned start;             // start state: block number + flags, like `next` of an arc
+  int has_final;              // 0: every state is final with cost 0
+  int S;
 };
 
 struct DevChannels {
   ChanState *st;
-  int4 *cand;       int cand_cap, region_cap;  // kRegions x region_cap {dst state, cost, source token, arc id}
+  int4 *cand;       int cand_cap, region_cap;  // kRegions x region_cap {next, cost, source token, arc id}
   int2 *win_sc;     int *win_ci; int win_cap;  // recombined tokens before the max-active cutoff
-  int4 *queue;      int qcap;                  // 2 buffers {state, cost, first emitting arc, degree}
-  int4 *wl;                                    // 2 buffers {token, first epsilon arc, degree, -}
-  unsigned *index;                             // [S] (epoch tag << 16) | token index
+  int2 *queue;      int qcap;                  // 2 buffers {block number, cost}
+  int4 *wl;                                    // 2 buffers {token, block number, cost, 1 = new token}
+  unsigned *index;                             // [n_blk] (epoch tag << 16) | token index
   int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
@@ -134,7 +148,7 @@ struct LaunchArgs {
 
 struct ChunkLds {             // one chunk of work items, flattened over their arcs
   unsigned pre[kChunk + 1];   // exclusive prefix sums of the items' arc counts
-  int abase[kChunk];          // first arc of the item minus its prefix
+  int abase[kChunk];          // unit address of the item's first arc minus its prefix
   float tcost[kChunk];        // cost of the item's token
   int ttok[kChunk];           // the item's token (epsilon expansion only)
 };
@@ -225,7 +239,7 @@ struct Cutoff {
 struct Ctx {                  // block-uniform view of one channel
   const DevGraph &g; const DevChannels &c; Smem &sm;
   int4 *cand; int2 *win_sc; int *win_ci;
-  int4 *q0; int4 *wl0; unsigned *index; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
+  int2 *q0; int4 *wl0; unsigned *index; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
 };
@@ -324,7 +338,8 @@ __device__ __forceinline__ void owners_of(const ChunkLds &ck, unsigned f0, unsig
 }
 
 // Region of the candidate buffer a destination state belongs to (top hash bits).
-__device__ __forceinline__ int region_of(int dst) { return (int)(hash_state(dst) >> 30); }
+__device__ __forceinline__ int key_of(int next) { return (int)((unsigned)next & kKeyMask); }
+__device__ __forceinline__ int region_of(int key) { return (int)(hash_state(key) >> 30); }
 static_assert(kRegions == 4, "region_of takes two hash bits");
 
 // Append a batch of N candidates per lane to their destinations' regions.  The wave counts
@@ -333,19 +348,26 @@ static_assert(kRegions == 4, "region_of takes two hash bits");
 // that hit the same region write consecutive 16-byte records, so the stores coalesce.
 // Must be called by all 64 lanes of the wave.
 template <int N>
-__device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const int (&dst)[N], const float (&nc)[N],
+__device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const int (&next)[N], const float (&nc)[N],
                                            const int (&src)[N], const int (&arc)[N]) {
   const int lane = threadIdx.x & 63;
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  int r[N]; unsigned long long m[N][kRegions]; int cnt[kRegions], base[kRegions];
+  typedef unsigned long long u64;
+  int r[N], rank[N]; int off[N][kRegions]; int cnt[kRegions];
 #pragma unroll
   for (int q = 0; q < kRegions; ++q) cnt[q] = 0;
 #pragma unroll
   for (int u = 0; u < N; ++u) {
-    r[u] = region_of(dst[u]);
+    r[u] = region_of(key_of(next[u]));
+    // three ballots give the four per-region lane masks with scalar logic
+    const u64 bk = __ballot(ok[u]), b0 = __ballot((r[u] & 1) != 0), b1 = __ballot((r[u] & 2) != 0);
+    const u64 m[kRegions] = {bk & ~b1 & ~b0, bk & ~b1 & b0, bk & b1 & ~b0, bk & b1 & b0};
+    const u64 lo = (r[u] & 1) ? m[1] : m[0], hi = (r[u] & 1) ? m[3] : m[2];
+    const u64 own = (r[u] & 2) ? hi : lo;                    // lanes of this lane's region
+    rank[u] = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(own >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)own, 0u));
 #pragma unroll
-    for (int q = 0; q < kRegions; ++q) { m[u][q] = __ballot(ok[u] && r[u] == q); cnt[q] += __popcll(m[u][q]); }
+    for (int q = 0; q < kRegions; ++q) { off[u][q] = cnt[q]; cnt[q] += __popcll(m[q]); }
   }
+  int base[kRegions];
 #pragma unroll
   for (int q = 0; q < kRegions; ++q) {
     base[q] = 0;
@@ -353,16 +375,14 @@ __device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const in
   }
 #pragma unroll
   for (int q = 0; q < kRegions; ++q) base[q] = uni(base[q]);
+  const int cap = x.c.region_cap;
 #pragma unroll
   for (int u = 0; u < N; ++u) {
-    int slot = 0;
-#pragma unroll
-    for (int q = 0; q < kRegions; ++q) {
-      if (r[u] == q) slot = base[q] + __popcll(m[u][q] & lt);
-      base[q] += __popcll(m[u][q]);
-    }
+    const int s0 = (r[u] & 1) ? base[1] + off[u][1] : base[0] + off[u][0];
+    const int s1 = (r[u] & 1) ? base[3] + off[u][3] : base[2] + off[u][2];
+    const int slot = ((r[u] & 2) ? s1 : s0) + rank[u];
     if (ok[u]) {
-      if (slot < x.c.region_cap) x.cand[r[u] * x.c.region_cap + slot] = make_int4(dst[u], __float_as_int(nc[u]), src[u], arc[u]);
+      if (slot < cap) x.cand[r[u] * cap + slot] = make_int4(next[u], __float_as_int(nc[u]), src[u], arc[u]);
       else atomicOr(&x.sm.status, kStCapacity);
     }
   }
@@ -373,33 +393,94 @@ __device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const in
 //   cost = (token cost + arc weight) + (-loglike[ilabel-1])      (Expand Arcs pseudo-code)
 // Candidates that cannot be in the beam relative to the running best are dropped early;
 // the running best is never lower than the final one, so this never drops a survivor.
-__device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
+// Cost, beam test and append for N emitting arcs per lane (all 64 lanes of the wave call it).
+template <int N>
+__device__ __forceinline__ void emit_arcs(Ctx &x, bool (&ok)[N], const int4 (&a)[N], const float (&tc)[N],
+                                          const int (&src)[N], const int (&arc)[N], float beam, bool boosted) {
+  Smem &sm = x.sm;
+  const unsigned bo = *(volatile unsigned *)&sm.best_ord;
+  const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
+  unsigned o = kOrdNone;
+  float nc[N]; int next[N];
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + sm.u.e.ac[a[u].z - 1]);
+    if (boosted && a[u].w != 0 && ok[u]) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // + b[olabel]
+    ok[u] = ok[u] && (nc[u] < INFINITY) && !((nc[u] - rb) > beam);
+    if (ok[u]) o = min(o, f2ord(nc[u]));
+    next[u] = a[u].x;
+  }
+  // running best: only lanes that would lower it touch the LDS word (rare after the first arcs)
+  if (o < bo) atomicMin(&sm.best_ord, o);
+  push_cands<N>(x, ok, next, nc, src, arc);
+}
+
+__device__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
   const int tid = threadIdx.x;
   const float beam = x.s.beam;
   const bool boosted = x.s.boost_n > 0;
+  // Tokens are processed in chunks of kChunk.  A lane reads the 32 bytes at the start of its
+  // tokens' state blocks (header + first arc).  Most states have one emitting arc and no
+  // epsilon arcs: that arc is expanded right away by the lane that owns the token.  Only the
+  // remaining arcs go through the flattened, load-balanced loop.  The loads run one chunk
+  // ahead (tokens two), so a chunk starts with its headers already there.
+  int2 tk[kTPT], tkn[kTPT]; int4 hd[kTPT], fu[kTPT];
+#pragma unroll
+  for (int k = 0; k < kTPT; ++k) {
+    const int i = kTPT * tid + k;
+    tk[k] = make_int2(0, 0);
+    if (i < n_tok) tk[k] = Q[i];
+  }
+#pragma unroll
+  for (int k = 0; k < kTPT; ++k) {
+    const int i = kTPT * tid + k;
+    hd[k] = make_int4(0, 0, 0, 0); fu[k] = make_int4(0, 0, 1, 0);
+    if (i < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk[k].x; hd[k] = b[0]; fu[k] = b[1]; }
+    tkn[k] = make_int2(0, 0);
+    if (kChunk + i < n_tok) tkn[k] = Q[kChunk + i];
+  }
   for (int cb = 0, par = 0; cb < n_tok; cb += kChunk, par ^= 1) {
     ChunkLds &ck = e.ch[par];
-    int4 tk[kTPT]; unsigned deg[kTPT], ex[kTPT];
+    unsigned deg[kTPT], ex[kTPT]; int first[kTPT];
+    {
+      bool has[kTPT]; float tc[kTPT]; int src[kTPT], arc[kTPT]; int4 a0[kTPT];
+      int n_first = 0;
 #pragma unroll
-    for (int k = 0; k < kTPT; ++k) {
-      const int i = cb + kTPT * tid + k;
-      tk[k] = make_int4(0, 0, 0, 0);
-      if (i < n_tok) tk[k] = Q[i];
-      deg[k] = (unsigned)tk[k].w;
+      for (int k = 0; k < kTPT; ++k) {
+        const int ne = hd[k].x, nx = hd[k].y;
+        has[k] = ne > 0 && nx == 0;                     // the unit after the header is an emitting arc
+        deg[k] = (unsigned)(ne - (has[k] ? 1 : 0));
+        first[k] = 2 * tk[k].x + 1 + nx + (has[k] ? 1 : 0);   // unit address of the first arc left
+        tc[k] = __int_as_float(tk[k].y); src[k] = cb + kTPT * tid + k; arc[k] = 2 * tk[k].x + 1;
+        a0[k] = has[k] ? fu[k] : make_int4(0, 0, 1, 0);
+        n_first += __popcll(__ballot(has[k]));
+      }
+      if ((tid & 63) == 0 && n_first) atomicAdd((unsigned long long *)&sm.ctr[kCtEarc], (unsigned long long)n_first);
+      emit_arcs<kTPT>(x, has, a0, tc, src, arc, beam, boosted);
     }
     const unsigned M = block_scan(sm, deg, ex);
 #pragma unroll
     for (int k = 0; k < kTPT; ++k) {
       ck.pre[kTPT * tid + k] = ex[k];
-      ck.abase[kTPT * tid + k] = tk[k].z - (int)ex[k];
+      ck.abase[kTPT * tid + k] = first[k] - (int)ex[k];
       ck.tcost[kTPT * tid + k] = __int_as_float(tk[k].y);
     }
     if (tid == kBlock - 1) ck.pre[kChunk] = M;
+    if (tid == 0) sm.ctr[kCtEarc] += M;
     __syncthreads();
     prof_mark(sm, kPhExpSetup);
-    if (tid == 0) sm.ctr[kCtEarc] += M;
+    // the next chunk's headers and the tokens of the chunk after it
+#pragma unroll
+    for (int k = 0; k < kTPT; ++k) {
+      const int i = cb + kChunk + kTPT * tid + k;
+      tk[k] = tkn[k];
+      hd[k] = make_int4(0, 0, 0, 0); fu[k] = make_int4(0, 0, 1, 0);
+      if (i < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk[k].x; hd[k] = b[0]; fu[k] = b[1]; }
+      tkn[k] = make_int2(0, 0);
+      if (i + kChunk < n_tok) tkn[k] = Q[i + kChunk];
+    }
     for (unsigned f0 = 0; f0 < M; f0 += kBlock * kUE) {
       bool ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
       owners_of<kUE>(ck, f0, M, ok, j);
@@ -409,27 +490,9 @@ __device__ void emit_expand(Ctx &x, const int4 *Q, int n_tok) {
         src[u] = cb + j[u];
         tc[u] = ck.tcost[j[u]];
         a[u] = make_int4(0, 0, 1, 0);
-        if (ok[u]) a[u] = x.g.earc[arc[u]];
+        if (ok[u]) a[u] = x.g.unit[arc[u]];
       }
-      const unsigned bo = *(volatile unsigned *)&sm.best_ord;
-      const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
-      unsigned o = kOrdNone;
-      float nc[kUE];
-#pragma unroll
-      for (int u = 0; u < kUE; ++u) {
-        nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + e.ac[a[u].z - 1]);
-        if (boosted && a[u].w != 0 && ok[u]) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // + b[olabel]
-        ok[u] = ok[u] && (nc[u] < INFINITY) && !((nc[u] - rb) > beam);
-        if (ok[u]) o = min(o, f2ord(nc[u]));
-      }
-      // running best: wave minimum first, one LDS atomic per wave
-#pragma unroll
-      for (int sft = 32; sft > 0; sft >>= 1) o = min(o, (unsigned)__shfl_xor((int)o, sft, 64));
-      if ((tid & 63) == 0 && o != kOrdNone) atomicMin(&sm.best_ord, o);
-      int dst[kUE];
-#pragma unroll
-      for (int u = 0; u < kUE; ++u) dst[u] = a[u].x;
-      push_cands<kUE>(x, ok, dst, nc, src, arc);
+      emit_arcs<kUE>(x, ok, a, tc, src, arc, beam, boosted);
     }
     prof_mark(sm, kPhExpLoop);        // no barrier: the next chunk uses the other table buffer
   }
@@ -493,9 +556,10 @@ __device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G,
       const int4 cd = nxt;
       if (i + kBlock < n) nxt = x.cand[base + i + kBlock];
       const float c = __int_as_float(cd.y);
-      bool take = G == 1 || group_of(cd.x, G) == g;
+      const int key = key_of(cd.x);
+      bool take = G == 1 || group_of(key, G) == g;
       if (kSelect) take = take && cut.in_beam(c) && cut.bin(c) < k_sel;
-      if (take) table_insert(x, cd.x, c, cd.w, base + i);
+      if (take) table_insert(x, key, c, cd.w, base + i);
     }
   }
 }
@@ -534,40 +598,36 @@ __device__ __forceinline__ int total_candidates(const Ctx &x) {
 }
 
 // ------------------------------------------------------------------ token creation
-// New tokens of the set under construction (N per lane): queue record with the state's
-// emitting arc range, backpointer, state index entry (only states that an epsilon arc can
-// enter are ever looked up), and an entry in the next epsilon worklist if the state has
-// epsilon arcs.  rec[] are the states' records.  `also[]` appends existing tokens (tok[])
-// that were improved and must be expanded again.  Called by all lanes of the wave.
+// New tokens of the set under construction (N per lane), made from the winning arc alone:
+// queue record, backpointer, state index entry if an epsilon arc can enter the state (only
+// those are ever looked up), and an entry in the next epsilon worklist if the state has
+// epsilon arcs.  next[] is the arc's destination with its flag bits.  `also[]` appends
+// existing tokens (tok[]) that were improved and must be expanded again.  Called by all
+// lanes of the wave.
 template <int N>
-__device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const int (&ti)[N], const int (&state)[N],
+__device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const int (&ti)[N], const int (&next)[N],
                                             const int (&costbits)[N], const int (&prev)[N], const int (&arc)[N],
-                                            const int4 (&rec)[N], const bool (&also)[N], const int (&tok)[N],
-                                            int4 *NQ, unsigned lat_base, int4 *WLN, unsigned tag16) {
+                                            const bool (&also)[N], const int (&tok)[N],
+                                            int2 *NQ, unsigned lat_base, int4 *WLN, unsigned tag16) {
   bool want[2 * N]; int wi[2 * N];
-  unsigned xsum = 0;
 #pragma unroll
   for (int u = 0; u < N; ++u) {
-    const int xdeg = rec[u].w & 0x7fffffff;
+    const int key = key_of(next[u]);
+    const bool has_eps = ((unsigned)next[u] & kFlagHasEps) != 0;
     if (make[u]) {
-      NQ[ti[u]] = make_int4(state[u], costbits[u], rec[u].x, rec[u].z);
+      NQ[ti[u]] = make_int2(key, costbits[u]);
       x.lat[lat_base + ti[u]] = make_int2(prev[u], arc[u]);
-      if (rec[u].w < 0) x.index[state[u]] = tag16 | (unsigned)ti[u];
-      xsum += (unsigned)xdeg;
+      if ((unsigned)next[u] & kFlagEpsIn) x.index[key] = tag16 | (unsigned)ti[u];
     }
-    want[u] = make[u] && xdeg > 0;
-    want[N + u] = also[u] && xdeg > 0;
+    want[u] = make[u] && has_eps;
+    want[N + u] = also[u] && has_eps;
   }
-  // epsilon arcs out of the set (a counter): wave sum, one LDS atomic per wave
-#pragma unroll
-  for (int sft = 32; sft > 0; sft >>= 1) xsum += (unsigned)__shfl_xor((int)xsum, sft, 64);
-  if ((threadIdx.x & 63) == 0 && xsum) atomicAdd((unsigned long long *)&x.sm.ctr[kCtXarc], (unsigned long long)xsum);
   wave_alloc_n<2 * N>(&x.sm.n_wl_next, want, wi);
 #pragma unroll
   for (int u = 0; u < N; ++u) {
-    const int xdeg = rec[u].w & 0x7fffffff;
-    if (want[u]) WLN[wi[u]] = make_int4(ti[u], rec[u].y, xdeg, 0);          // wi < qcap because ti < qcap
-    if (want[N + u]) WLN[wi[N + u]] = make_int4(tok[u], rec[u].y, xdeg, 0);
+    const int key = key_of(next[u]);
+    if (want[u]) WLN[wi[u]] = make_int4(ti[u], key, costbits[u], 1);          // wi < qcap because ti < qcap
+    if (want[N + u]) WLN[wi[N + u]] = make_int4(tok[u], key, costbits[u], 0);
   }
 }
 
@@ -582,7 +642,7 @@ __device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const
 //    max_active (at least 1).  If the selection turns out too small to decide that
 //    (duplicate destinations), step 2 is redone with everything selected.
 // 4. the survivors become tokens.
-__device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *WLN, Cutoff &cut) {
+__device__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned lat_base, int4 *WLN, Cutoff &cut) {
   Smem &sm = x.sm;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
@@ -722,7 +782,7 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
   const unsigned tag16 = set_tag(x.s.epoch) << 16;
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kUC) {
-    int2 sc[kUC]; int ci[kUC]; bool kp[kUC]; int4 cr[kUC], sr[kUC];
+    int2 sc[kUC]; int ci[kUC]; bool kp[kUC]; int4 cr[kUC];
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
       const int i = i0 + u * kBlock + tid;
@@ -732,8 +792,8 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
     }
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
-      cr[u] = make_int4(0, 0, 0, 0); sr[u] = cr[u];
-      if (kp[u]) { cr[u] = x.cand[ci[u]]; sr[u] = x.g.state[sc[u].x]; }
+      cr[u] = make_int4(0, 0, 0, 0);
+      if (kp[u]) cr[u] = x.cand[ci[u]];
     }
     int ti[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; bool good[kUC], no[kUC];
     wave_alloc_n<kUC>(&sm.n_next, kp, ti);
@@ -744,9 +804,9 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
         if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
         else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
       }
-      st[u] = sc[u].x; cb[u] = sc[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
+      st[u] = cr[u].x; cb[u] = sc[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
     }
-    make_tokens<kUC>(x, good, ti, st, cb, pv, ar, sr, no, none, NQ, lat_base, WLN, tag16);
+    make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN, tag16);
   }
   __syncthreads();
   if (tid == 0) sm.ctr[kCtKept] += min(sm.n_next, x.c.qcap);
@@ -762,7 +822,7 @@ __device__ void recombine_and_prune(Ctx &x, int4 *NQ, unsigned lat_base, int4 *W
 // with the state's existing token (found through the state index) and updates it in place
 // or becomes a new token; either way that token is expanded in the next round.
 // On entry WL0 = x.wl0 + sel*qcap holds n_wl entries.
-__device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
+__device__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
   TableLds &t = sm.u.t;
@@ -778,49 +838,53 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
     const int4 *WL = x.wl0 + sel * x.c.qcap; int4 *WLN = x.wl0 + (sel ^ 1) * x.c.qcap;
     for (int cb = 0, par = 0; cb < n_wl; cb += kChunk, par ^= 1) {
       ChunkLds &ck = e.ch[par];
-      unsigned deg[kTPT], ex[kTPT]; int4 w[kTPT]; int cs[kTPT];
+      unsigned deg[kTPT], ex[kTPT]; int4 w[kTPT]; unsigned xsum = 0;
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
         const int i = cb + kTPT * tid + k;
         w[k] = make_int4(0, 0, 0, 0);
         if (i < n_wl) w[k] = WL[i];
-        deg[k] = (unsigned)w[k].z;
       }
 #pragma unroll
-      for (int k = 0; k < kTPT; ++k) cs[k] = deg[k] ? NQ[w[k].x].y : 0;     // the token's current cost
+      for (int k = 0; k < kTPT; ++k) {
+        const int i = cb + kTPT * tid + k;
+        deg[k] = i < n_wl ? (unsigned)x.g.unit[2 * (size_t)(unsigned)w[k].y].y : 0u;   // the state's header
+        if (w[k].w) xsum += deg[k];
+      }
+      // epsilon arcs out of the set (a counter): every token is listed as new exactly once
+#pragma unroll
+      for (int sft = 32; sft > 0; sft >>= 1) xsum += (unsigned)__shfl_xor((int)xsum, sft, 64);
+      if ((tid & 63) == 0 && xsum) atomicAdd((unsigned long long *)&sm.ctr[kCtXarc], (unsigned long long)xsum);
       const unsigned M = block_scan(sm, deg, ex);
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
         ck.pre[kTPT * tid + k] = ex[k];
-        ck.abase[kTPT * tid + k] = w[k].y - (int)ex[k];
-        ck.tcost[kTPT * tid + k] = __int_as_float(cs[k]);
+        ck.abase[kTPT * tid + k] = 2 * w[k].y + 1 - (int)ex[k];
+        ck.tcost[kTPT * tid + k] = __int_as_float(w[k].z);       // the token's cost when it was listed
         ck.ttok[kTPT * tid + k] = w[k].x;
       }
       if (tid == kBlock - 1) ck.pre[kChunk] = M;
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-        bool ok[kU]; int src[kU]; int2 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
+        bool ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
         owners_of<kU>(ck, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           arc[u] = ck.abase[j[u]] + (int)(f0 + u * kBlock + tid);
           src[u] = ck.ttok[j[u]];
           tc[u] = ck.tcost[j[u]];
-          a[u] = make_int2(0, 0);
-          if (ok[u]) a[u] = x.g.xarc[arc[u]];
+          a[u] = make_int4(0, 0, 0, 0);
+          if (ok[u]) a[u] = x.g.unit[arc[u]];
         }
-        int dst[kU]; float nc[kU];
+        int next[kU]; float nc[kU];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           nc[u] = canon(tc[u] + __int_as_float(a[u].y));
-          if (boosted && ok[u]) {                 // epsilon arcs can carry output labels too
-            const int ol = x.g.olabel[x.g.Ae + arc[u]];
-            if (ol != 0) nc[u] = canon(nc[u] + boost_of(sm, ol));
-          }
+          if (boosted && ok[u] && a[u].w != 0) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // epsilon arcs can carry output labels too
           ok[u] = ok[u] && (nc[u] < INFINITY) && cut.keep(nc[u]);
-          dst[u] = a[u].x; arc[u] += x.g.Ae;
+          next[u] = a[u].x; arc[u] |= (int)kArcEps;
         }
-        push_cands<kU>(x, ok, dst, nc, src, arc);
+        push_cands<kU>(x, ok, next, nc, src, arc);
       }
     }
     __syncthreads();
@@ -851,7 +915,7 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
       const int n_occ = uni(sm.n_occ);
       // per destination: winning candidate, state index, state record -> existing token
       for (int i0 = 0; i0 < n_occ; i0 += kBlock * kU) {
-        int d[kU]; int4 rec[kU], sr[kU]; unsigned ix[kU]; int tok[kU];
+        int d[kU]; int4 rec[kU]; unsigned ix[kU]; int tok[kU];
         float oc[kU]; unsigned oa[kU]; bool occ[kU], exists[kU]; unsigned ci[kU];
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
@@ -862,8 +926,8 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
         }
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
-          rec[k] = make_int4(0, 0, 0, 0); sr[k] = rec[k]; ix[k] = 0;
-          if (occ[k]) { rec[k] = x.cand[ci[k]]; ix[k] = x.index[d[k]]; sr[k] = x.g.state[d[k]]; }
+          rec[k] = make_int4(0, 0, 0, 0); ix[k] = 0;
+          if (occ[k]) { rec[k] = x.cand[ci[k]]; ix[k] = x.index[d[k]]; }
         }
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
@@ -872,7 +936,7 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
           oc[k] = 0.0f; oa[k] = 0;
           if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
         }
-        bool fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU];
+        bool fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
           const float nc = __int_as_float(rec[k].y);
@@ -892,9 +956,9 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
             NQ[tok[k]].y = rec[k].y;
             x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
           }
-          cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w;
+          cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w; nx[k] = rec[k].x;
         }
-        make_tokens<kU>(x, good, ni, d, cb, pv, ar, sr, improve, tok, NQ, lat_base, WLN, tag << 16);
+        make_tokens<kU>(x, good, ni, nx, cb, pv, ar, improve, tok, NQ, lat_base, WLN, tag << 16);
       }
       __syncthreads();
       prof_mark(sm, kPhEpsTabScan);
@@ -914,7 +978,7 @@ __device__ void eps_closure(Ctx &x, int4 *NQ, unsigned lat_base, int sel, const 
 
 // Publish the closed token set in NQ as A_f (f = x.s.frame).
 // Returns true (uniformly) if an overflow was flagged and the channel has to stop.
-__device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
+__device__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) {
   Smem &sm = x.sm;
   const int tid = threadIdx.x;
   const int n = uni(min(sm.n_next, x.c.qcap));
@@ -922,8 +986,9 @@ __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
   if (x.dig_sum) {
     unsigned long long s = 0;
     for (int i = tid; i < n; i += kBlock) {
-      const int2 sc = *reinterpret_cast<const int2 *>(&NQ[i]);
-      s += mix64(((unsigned long long)(unsigned)sc.x << 32) | (unsigned)sc.y);
+      const int2 sc = NQ[i];
+      const int state = x.g.unit[2 * (size_t)(unsigned)sc.x].z;     // the header names the state
+      s += mix64(((unsigned long long)(unsigned)state << 32) | (unsigned)sc.y);
     }
     if (s) atomicAdd(&sm.red64, s);
   }
@@ -951,20 +1016,21 @@ __device__ bool finish_set(Ctx &x, int4 *NQ, unsigned lat_base) {
 // written 65535 sets ago would look current again, so the whole index is zeroed first.
 __device__ void renew_index_if_wrapping(Ctx &x) {
   if (x.s.epoch != 0 && x.s.epoch % 65535u == 0) {
-    for (int s = threadIdx.x; s < x.g.S; s += kBlock) x.index[s] = 0;
+    for (unsigned s = threadIdx.x; s < x.g.n_blk; s += kBlock) x.index[s] = 0;
     __syncthreads();
   }
 }
 
 // ------------------------------------------------------------------ final choice + traceback
-// Best token by (cost + final cost, state) if any token is final, else by (cost, state);
+// Best token by (cost + final cost, state) if any token is final, else by (cost, state)
+// (block numbers grow with state ids, so they order the same way);
 // then the backpointers are followed to the start token and the non-zero output labels of
 // the arcs are written in path order.
 __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
   Smem &sm = x.sm;
   const int tid = threadIdx.x;
   const int n = x.s.n_tok;
-  const int4 *Q = x.q0 + x.s.cur * x.c.qcap;
+  const int2 *Q = x.q0 + x.s.cur * x.c.qcap;
   int *words = a.words + (long long)io * a.max_words;
   int flags = x.s.status;
   if (n == 0) {
@@ -975,11 +1041,11 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   __syncthreads();
   unsigned long long mf = ~0ull, mr = ~0ull;
   for (int i = tid; i < n; i += kBlock) {
-    const int4 t = Q[i];
+    const int2 t = Q[i];
     const float c = __int_as_float(t.y);
     mr = min(mr, ((unsigned long long)f2ord(c) << 32) | (unsigned)t.x);
     if (a.finalize) {
-      const float fc = x.g.final_cost ? x.g.final_cost[t.x] : 0.0f;
+      const float fc = x.g.has_final ? __int_as_float(x.g.unit[2 * (size_t)(unsigned)t.x].w) : 0.0f;
       const float f = c + fc;
       if (f < INFINITY) mf = min(mf, ((unsigned long long)f2ord(f) << 32) | (unsigned)t.x);
     }
@@ -994,7 +1060,6 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     if (Q[i].x == best_state) sm.sel_idx = i;
   __syncthreads();
   if (tid == 0) {
-    const int Ae = x.g.Ae;
     int nw = 0;
     bool broken = false;
     for (int pass = 0; pass < 2; ++pass) {
@@ -1006,13 +1071,13 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
         if (li >= x.s.lat_used) { broken = true; break; }
         const int2 bp = x.lat[li];
         if (bp.y < 0) break;
-        const int ol = x.g.olabel[bp.y];
+        const int ol = x.g.unit[(unsigned)bp.y & kArcMask].w;
         if (ol != 0) {
           if (pass == 1) { const int pos = nw - 1 - k; if (pos < a.max_words) words[pos] = ol; }
           ++k;
         }
         i = bp.x;
-        if (bp.y < Ae) --f;
+        if (!((unsigned)bp.y & kArcEps)) --f;                  // an emitting arc consumed a frame
       }
       nw = k;
     }
@@ -1038,7 +1103,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.win_ci = c.win_ci + (size_t)ch * c.win_cap;
   x.q0 = c.queue + (size_t)ch * 2 * c.qcap;
   x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
-  x.index = c.index + (size_t)ch * g.S;
+  x.index = c.index + (size_t)ch * g.n_blk;
   x.lat = c.lattice + (size_t)ch * c.lat_cap;
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
@@ -1071,13 +1136,12 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
     renew_index_if_wrapping(x);
-    int4 *NQ = x.q0 + c.qcap;
-    const int4 sr = g.state[g.start];
+    int2 *NQ = x.q0 + c.qcap;
     if (tid == 0) sm.n_next = 1;
     {
       const bool mk[1] = {tid == 0}, no[1] = {false};
-      const int z[1] = {0}, st[1] = {g.start}, m1[1] = {-1}; const int4 rc[1] = {sr};
-      make_tokens<1>(x, mk, z, st, z, m1, m1, rc, no, z, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
+      const int z[1] = {0}, st[1] = {(int)g.start}, m1[1] = {-1};
+      make_tokens<1>(x, mk, z, st, z, m1, m1, no, z, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
     }
     __syncthreads();
     Cutoff cut{0.0f, x.s.beam, x.s.scale, 256};
@@ -1093,8 +1157,8 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     const float *row = ll + (long long)t * a.V;
     for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
     __syncthreads();
-    const int4 *Q = x.q0 + x.s.cur * c.qcap;
-    int4 *NQ = x.q0 + (x.s.cur ^ 1) * c.qcap;
+    const int2 *Q = x.q0 + x.s.cur * c.qcap;
+    int2 *NQ = x.q0 + (x.s.cur ^ 1) * c.qcap;
     const unsigned lat_base = x.s.lat_used;
     if (tid == 0) { sm.ctr[kCtTok] += x.s.n_tok; sm.ctr[kCtFrames]++; }
     prof_mark(sm, kPhOther);
@@ -1148,6 +1212,8 @@ struct wfst_decoder {
   // word-boost tables: pinned host staging per channel (keys, values, count) + what is on the device
   int *h_boost = nullptr;            // [channels][2 * kBoostSlots + 1]
   std::vector<int> boost_on_dev;     // entries of the table each channel currently has on the device
+  std::vector<unsigned> blk_of_state;  // [S + 1] block number of every state (and the block count)
+  std::vector<int> state_of_blk;       // inverse, built when a debug call first needs it
   hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
   std::string err;
 };
@@ -1221,44 +1287,46 @@ int validate_graph(const wfst_graph_csr *g, std::string &why, int64_t &Ae, int64
   return WFST_OK;
 }
 
-int upload_graph(wfst_decoder *d, const wfst_graph_csr *g, int64_t Ae, int64_t Ax) {
+// Lay the graph out as state blocks (see the top of this file).
+int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
   const int32_t S = g->num_states;
-  std::vector<int4> srec(S);
-  std::vector<char> eps_in(S, 0);
-  for (int64_t i = 0; i < g->num_arcs; ++i) if (g->ilabel[i] == 0) eps_in[g->next_state[i]] = 1;
-  std::vector<int4> earc(Ae);
-  std::vector<int2> xarc(Ax);
-  std::vector<int> ol(Ae + Ax);
-  int64_t ne = 0, nx = 0;
+  std::vector<char> eps_in(S, 0), has_eps(S, 0);
+  std::vector<unsigned> &blk = d->blk_of_state;
+  blk.assign((size_t)S + 1, 0);
+  uint64_t units = 0;
   for (int32_t s = 0; s < S; ++s) {
-    const int64_t e0 = ne, x0 = nx;
-    for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i) {
+    blk[s] = (unsigned)(units / 2);
+    uint64_t n = 1 + (uint64_t)(g->row_offsets[s + 1] - g->row_offsets[s]);
+    units += n + (n & 1);
+    if (units / 2 > (uint64_t)kKeyMask) return fail(d, WFST_ERR_BAD_GRAPH, "graph larger than 2^29 blocks of 32 bytes");
+    for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i)
+      if (g->ilabel[i] == 0) { eps_in[g->next_state[i]] = 1; has_eps[s] = 1; }
+  }
+  blk[S] = (unsigned)(units / 2);
+  auto named = [&](int32_t s) { return blk[s] | (has_eps[s] ? kFlagHasEps : 0u) | (eps_in[s] ? kFlagEpsIn : 0u); };
+  std::vector<int4> unit(units, make_int4(0, 0, 0, 0));
+  bool all_zero = true;
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t r0 = g->row_offsets[s], r1 = g->row_offsets[s + 1];
+    int ne = 0, nx = 0;
+    for (int64_t i = r0; i < r1; ++i) if (g->ilabel[i] == 0) ++nx; else ++ne;
+    const float fc = g->final_cost ? g->final_cost[s] : 0.0f;
+    all_zero = all_zero && fc == 0.0f;
+    int fbits; std::memcpy(&fbits, &fc, 4);
+    int4 *b = unit.data() + 2 * (size_t)blk[s];
+    b[0] = make_int4(ne, nx, s, fbits);
+    int4 *xa = b + 1, *ea = b + 1 + nx;
+    for (int64_t i = r0; i < r1; ++i) {
       int wbits; std::memcpy(&wbits, &g->weight[i], 4);
-      if (g->ilabel[i] == 0) { xarc[nx] = make_int2(g->next_state[i], wbits); ol[Ae + nx] = g->olabel[i]; ++nx; }
-      else { earc[ne] = make_int4(g->next_state[i], wbits, g->ilabel[i], g->olabel[i]); ol[ne] = g->olabel[i]; ++ne; }
+      const int4 arc = make_int4((int)named(g->next_state[i]), wbits, g->ilabel[i], g->olabel[i]);
+      if (g->ilabel[i] == 0) *xa++ = arc; else *ea++ = arc;
     }
-    // one 16-byte record per state: both arc ranges and whether an epsilon arc can enter it
-    srec[s] = make_int4((int)e0, (int)x0, (int)(ne - e0), (int)(nx - x0) | (eps_in[s] ? (int)0x80000000 : 0));
   }
-  int4 *d_off; int4 *d_e; int2 *d_x; int *d_ol; float *d_fc = nullptr;
+  int4 *d_unit;
   int rc;
-  if ((rc = dev_alloc(d, &d_off, srec.size()))) return rc;
-  if ((rc = dev_alloc(d, &d_e, earc.size()))) return rc;
-  if ((rc = dev_alloc(d, &d_x, xarc.size()))) return rc;
-  if ((rc = dev_alloc(d, &d_ol, ol.size()))) return rc;
-  HIP_TRY(d, hipMemcpy(d_off, srec.data(), srec.size() * sizeof(int4), hipMemcpyHostToDevice));
-  if (Ae) HIP_TRY(d, hipMemcpy(d_e, earc.data(), earc.size() * sizeof(int4), hipMemcpyHostToDevice));
-  if (Ax) HIP_TRY(d, hipMemcpy(d_x, xarc.data(), xarc.size() * sizeof(int2), hipMemcpyHostToDevice));
-  if (Ae + Ax) HIP_TRY(d, hipMemcpy(d_ol, ol.data(), ol.size() * sizeof(int), hipMemcpyHostToDevice));
-  if (g->final_cost) {
-    bool all_zero = true;
-    for (int32_t s = 0; s < S && all_zero; ++s) all_zero = g->final_cost[s] == 0.0f;
-    if (!all_zero) {
-      if ((rc = dev_alloc(d, &d_fc, (size_t)S))) return rc;
-      HIP_TRY(d, hipMemcpy(d_fc, g->final_cost, (size_t)S * sizeof(float), hipMemcpyHostToDevice));
-    }
-  }
-  d->g = DevGraph{d_off, d_e, d_x, d_ol, d_fc, S, g->start_state, (int)Ae, (int)Ax};
+  if ((rc = dev_alloc(d, &d_unit, unit.size()))) return rc;
+  HIP_TRY(d, hipMemcpy(d_unit, unit.data(), unit.size() * sizeof(int4), hipMemcpyHostToDevice));
+  d->g = DevGraph{d_unit, blk[S], named(g->start_state), all_zero ? 0 : 1, S};
   return WFST_OK;
 }
 
@@ -1285,7 +1353,7 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.cand, N * (size_t)c.cand_cap))) return rc;
   if ((rc = dev_alloc(d, &c.win_sc, N * c.win_cap))) return rc;
   if ((rc = dev_alloc(d, &c.win_ci, N * c.win_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.index, N * (size_t)d->g.S))) return rc;
+  if ((rc = dev_alloc(d, &c.index, N * (size_t)d->g.n_blk))) return rc;
   if ((rc = dev_alloc(d, &c.queue, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
@@ -1298,7 +1366,7 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipMemset(c.st, 0, N * sizeof(ChanState)));
   HIP_TRY(d, hipMemset(c.counters, 0, 24 * sizeof(long long)));
   HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
-  HIP_TRY(d, hipMemset(c.index, 0, N * (size_t)d->g.S * sizeof(unsigned)));   // tag 0 = no token
+  HIP_TRY(d, hipMemset(c.index, 0, N * (size_t)d->g.n_blk * sizeof(unsigned)));   // tag 0 = no token
   if ((rc = dev_alloc(d, &c.boost_keys, N * kBoostSlots))) return rc;
   if ((rc = dev_alloc(d, &c.boost_vals, N * kBoostSlots))) return rc;
   HIP_TRY(d, hipMemset(c.boost_keys, 0, N * kBoostSlots * sizeof(int)));
@@ -1391,7 +1459,7 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
   if (rc) return fail(nullptr, rc, why);
   wfst_decoder *d = new wfst_decoder();
   d->opts = *opts; d->V = graph->num_classes;
-  rc = upload_graph(d, graph, Ae, Ax);
+  rc = upload_graph(d, graph);
   if (!rc) rc = alloc_channels(d);
   if (!rc && (hipEventCreate(&d->ev0) != hipSuccess || hipEventCreate(&d->ev1) != hipSuccess)) {
     d->err = "hipEventCreate failed"; rc = WFST_ERR_HIP;
@@ -1587,10 +1655,14 @@ int32_t wfst_debug_get_tokens(wfst_decoder *d, int32_t ch, int32_t *states, floa
   HIP_TRY(d, hipMemcpy(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost));
   *n = s.n_tok;
   const int m = std::min(cap, s.n_tok);
-  std::vector<int4> q((size_t)m);
-  const int4 *src = d->c.queue + ((size_t)ch * 2 + s.cur) * d->c.qcap;
-  if (m) HIP_TRY(d, hipMemcpy(q.data(), src, (size_t)m * sizeof(int4), hipMemcpyDeviceToHost));
-  for (int i = 0; i < m; ++i) { states[i] = q[i].x; std::memcpy(&costs[i], &q[i].y, 4); }
+  std::vector<int2> q((size_t)m);
+  const int2 *src = d->c.queue + ((size_t)ch * 2 + s.cur) * d->c.qcap;
+  if (m) HIP_TRY(d, hipMemcpy(q.data(), src, (size_t)m * sizeof(int2), hipMemcpyDeviceToHost));
+  if (d->state_of_blk.empty()) {            // tokens name their state by its block number
+    d->state_of_blk.assign((size_t)d->g.n_blk + 1, -1);
+    for (int32_t st = 0; st < d->g.S; ++st) d->state_of_blk[d->blk_of_state[st]] = st;
+  }
+  for (int i = 0; i < m; ++i) { states[i] = d->state_of_blk[(unsigned)q[i].x]; std::memcpy(&costs[i], &q[i].y, 4); }
   return WFST_OK;
 }
 
