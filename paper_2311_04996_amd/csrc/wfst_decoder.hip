@@ -367,14 +367,15 @@ __device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const in
 #pragma unroll
     for (int q = 0; q < kRegions; ++q) { off[u][q] = cnt[q]; cnt[q] += __popcll(m[q]); }
   }
+  // lanes 0..3 reserve the runs of regions 0..3 with one LDS atomic instruction
   int base[kRegions];
+  {
+    const int mine = lane == 0 ? cnt[0] : lane == 1 ? cnt[1] : lane == 2 ? cnt[2] : cnt[3];
+    int got = 0;
+    if (lane < kRegions && mine) got = atomicAdd(&x.sm.n_reg[lane], mine);
 #pragma unroll
-  for (int q = 0; q < kRegions; ++q) {
-    base[q] = 0;
-    if (lane == 0 && cnt[q]) base[q] = atomicAdd(&x.sm.n_reg[q], cnt[q]);
+    for (int q = 0; q < kRegions; ++q) base[q] = __builtin_amdgcn_readlane(got, q);
   }
-#pragma unroll
-  for (int q = 0; q < kRegions; ++q) base[q] = uni(base[q]);
   const int cap = x.c.region_cap;
 #pragma unroll
   for (int u = 0; u < N; ++u) {
@@ -415,7 +416,7 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, bool (&ok)[N], const int4 (&a)
   push_cands<N>(x, ok, next, nc, src, arc);
 }
 
-__device__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
+__device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
   const int tid = threadIdx.x;
@@ -583,10 +584,10 @@ struct PassPlan {
   // pass p covers regions [r0, r1) and sub-group g of G
   __device__ __forceinline__ void get(int p, int &r0, int &r1, int &g, int &G) const {
     if (whole) { r0 = 0; r1 = kRegions; g = 0; G = 1; return; }
-    int r = 0;
+    int r = 0, n = per_region[0];               // no dynamic indexing: the plan stays in registers
 #pragma unroll
-    for (int q = 0; q < kRegions - 1; ++q) if (r == q && p >= per_region[q]) { p -= per_region[q]; r = q + 1; }
-    r0 = r; r1 = r + 1; g = p; G = max(1, per_region[r]);
+    for (int q = 0; q < kRegions - 1; ++q) if (r == q && p >= per_region[q]) { p -= per_region[q]; r = q + 1; n = per_region[q + 1]; }
+    r0 = r; r1 = r + 1; g = p; G = max(1, n);
   }
 };
 
@@ -642,7 +643,7 @@ __device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const
 //    max_active (at least 1).  If the selection turns out too small to decide that
 //    (duplicate destinations), step 2 is redone with everything selected.
 // 4. the survivors become tokens.
-__device__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned lat_base, int4 *WLN, Cutoff &cut) {
+__device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned lat_base, int4 *WLN, Cutoff &cut) {
   Smem &sm = x.sm;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
@@ -822,7 +823,7 @@ __device__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned lat_base, int4 *W
 // with the state's existing token (found through the state index) and updates it in place
 // or becomes a new token; either way that token is expanded in the next round.
 // On entry WL0 = x.wl0 + sel*qcap holds n_wl entries.
-__device__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
+__device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
   TableLds &t = sm.u.t;
@@ -978,7 +979,7 @@ __device__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const 
 
 // Publish the closed token set in NQ as A_f (f = x.s.frame).
 // Returns true (uniformly) if an overflow was flagged and the channel has to stop.
-__device__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) {
+__device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) {
   Smem &sm = x.sm;
   const int tid = threadIdx.x;
   const int n = uni(min(sm.n_next, x.c.qcap));
@@ -1014,7 +1015,7 @@ __device__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) {
 
 // The state index is tagged with epoch % 65535 + 1: when the tag is about to repeat, entries
 // written 65535 sets ago would look current again, so the whole index is zeroed first.
-__device__ void renew_index_if_wrapping(Ctx &x) {
+__device__ __forceinline__ void renew_index_if_wrapping(Ctx &x) {
   if (x.s.epoch != 0 && x.s.epoch % 65535u == 0) {
     for (unsigned s = threadIdx.x; s < x.g.n_blk; s += kBlock) x.index[s] = 0;
     __syncthreads();
