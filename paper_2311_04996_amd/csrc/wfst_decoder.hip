@@ -72,6 +72,9 @@ constexpr int kWaves = kBlock / 64;
 #endif
 constexpr int kTPT = WFST_TPT;                // work items per thread per chunk (1, 2 or 4)
 constexpr int kChunk = kBlock * kTPT;
+constexpr int kWaveTok = 128;                 // tokens a wave expands at a time (2 per lane)
+constexpr int kHubCap = 512;                  // listed high-degree tokens per frame (more are expanded by their wave)
+constexpr int kHubDeg = 256;                  // arcs beyond which a token is listed there
 constexpr int kChunkLog2 = (kTPT == 4 ? 2 : (kTPT == 2 ? 1 : 0)) + (kBlock == 1024 ? 10 : (kBlock == 512 ? 9 : 8));
 static_assert((1 << kChunkLog2) == kChunk, "owner_of searches log2(kChunk) levels");
 constexpr int kMaxV = 2048;
@@ -152,9 +155,22 @@ struct ChunkLds {             // one chunk of work items, flattened over their a
   float tcost[kChunk];        // cost of the item's token
   int ttok[kChunk];           // the item's token (epsilon expansion only)
 };
+struct WaveLds {              // ExpandArcs: the work items of one wave (2 tokens per lane)
+  unsigned pre[kWaveTok + 1];
+  int abase[kWaveTok];
+  float tcost[kWaveTok];
+};
+struct HubLds {               // ExpandArcs: states with so many arcs that the whole block expands them
+  unsigned pre[kHubCap + 1];
+  int abase[kHubCap];
+  float tcost[kHubCap];
+  int ttok[kHubCap];
+};
 struct ExpandLds {            // live while arcs are being expanded
   float ac[kMaxV];
-  ChunkLds ch[2];             // double-buffered: a wave may start the next chunk while others finish this one
+  ChunkLds ch[2];             // epsilon expansion; double-buffered: a wave may start the next chunk while others finish this one
+  WaveLds w[kWaves];
+  HubLds hub;
 };
 struct TableLds {             // live while candidates are being recombined
   unsigned long long vals[kTabSlots];   // (orderable cost << 32) | candidate index
@@ -166,7 +182,7 @@ struct Smem {
   unsigned wave_tot[kWaves];
   unsigned best_ord;
   int n_reg[kRegions];        // candidates per region
-  int n_occ;
+  int n_occ, n_hub;
   int n_win, n_next, n_wl_next, status;
   int k_sel, n_sel, k_keep, redo;
   unsigned long long red64, red64b;
@@ -270,13 +286,14 @@ __device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
 // Tag of the token set under construction; 0 is never a valid tag (the index starts zeroed).
 __device__ __forceinline__ unsigned set_tag(unsigned epoch) { return epoch % 65535u + 1u; }
 
-// Block-wide exclusive scan of kTPT values per thread (thread t owns items kTPT*t ..).
+// Block-wide exclusive scan of N values per thread (thread t owns items N*t ..).
 // Returns the total; ex[k] receives the exclusive prefix of the thread's k-th item.
-__device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[kTPT], unsigned (&ex)[kTPT]) {
+template <int N>
+__device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[N], unsigned (&ex)[N]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   unsigned s = 0;
 #pragma unroll
-  for (int k = 0; k < kTPT; ++k) s += d[k];
+  for (int k = 0; k < N; ++k) s += d[k];
   unsigned inc = s;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -294,34 +311,34 @@ __device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[kTP
   }
   unsigned run = base + inc - s;
 #pragma unroll
-  for (int k = 0; k < kTPT; ++k) { ex[k] = run; run += d[k]; }
+  for (int k = 0; k < N; ++k) { ex[k] = run; run += d[k]; }
   return uni(total);
 }
 
-// Which of the chunk's work items owns flattened arc f: last j with pre[j] <= f.
-__device__ __forceinline__ int owner_of(const ChunkLds &ck, unsigned f) {
-  int lo = 0, hi = kChunk;
-#pragma unroll
-  for (int it = 0; it < kChunkLog2; ++it) {
-    int mid = (lo + hi) >> 1;
-    if (ck.pre[mid] <= f) lo = mid; else hi = mid;
+// Which of n work items owns flattened arc f: last j < n with pre[j] <= f (pre[0] = 0).
+__device__ __forceinline__ int owner_of(const unsigned *pre, int n, unsigned f) {
+  int lo = 0, hi = n;
+  const int steps = 32 - __clz(max(n, 1) - 1 | 0);              // ceil(log2(n)), uniform
+  for (int it = 0; it < steps; ++it) {
+    const int mid = (lo + hi) >> 1;
+    if (pre[mid] <= f) lo = mid; else hi = mid;
   }
   return lo;
 }
 
-// Owners of the N arcs a lane handles in one step: arc u of the lane is f0 + u*kBlock + tid,
-// so the 64 lanes of a wave hold 64 consecutive arcs for every u.  One full search per wave
-// (2N lanes look up the owners of the first and last arc of each run of 64) bounds every
-// lane's own search to the few items its run spans: 0 steps inside a high-degree state,
-// ~5 where degrees are small, instead of log2(kChunk) for every arc.
+// Owners of the N arcs a lane handles in one step of a block-wide flattened loop: arc u of
+// the lane is f0 + u*kBlock + tid, so the 64 lanes of a wave hold 64 consecutive arcs for
+// every u.  One full search per wave (2N lanes look up the owners of the first and last arc
+// of each run of 64) bounds every lane's own search to the few items its run spans: 0 steps
+// inside a high-degree state, a few where degrees are small.
 template <int N>
-__device__ __forceinline__ void owners_of(const ChunkLds &ck, unsigned f0, unsigned M, bool (&ok)[N], int (&j)[N]) {
+__device__ __forceinline__ void owners_of(const unsigned *pre, int n, unsigned f0, unsigned M, bool (&ok)[N], int (&j)[N]) {
   static_assert(2 * N <= 64, "bounds are looked up by 2N lanes");
   const int lane = threadIdx.x & 63;
   const unsigned wave_f = f0 + (threadIdx.x & ~63u);
   unsigned fq = wave_f + (unsigned)(lane >> 1) * kBlock + ((lane & 1) ? 63u : 0u);
   if (lane >= 2 * N || fq >= M) fq = M - 1;
-  const int bound = owner_of(ck, fq);
+  const int bound = owner_of(pre, n, fq);
 #pragma unroll
   for (int u = 0; u < N; ++u) {
     const unsigned f = f0 + u * kBlock + threadIdx.x;
@@ -331,7 +348,7 @@ __device__ __forceinline__ void owners_of(const ChunkLds &ck, unsigned f0, unsig
     const unsigned fs = ok[u] ? f : M - 1;
     for (int it = 0; it < steps; ++it) {
       const int mid = (lo + hi) >> 1;
-      if (ck.pre[mid] <= fs) lo = mid; else hi = mid;
+      if (pre[mid] <= fs) lo = mid; else hi = mid;
     }
     j[u] = lo;
   }
@@ -416,88 +433,148 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, bool (&ok)[N], const int4 (&a)
   push_cands<N>(x, ok, next, nc, src, arc);
 }
 
+// One step of a wave's flattened loop: arcs f0 + u*64 + lane of its listed work items.
+template <int N>
+__device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, unsigned f0, unsigned M, float beam, bool boosted) {
+  const int lane = threadIdx.x & 63;
+  bool ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N];
+#pragma unroll
+  for (int u = 0; u < N; ++u) {                // arc fetch, N in flight
+    const unsigned f = f0 + u * 64 + lane;
+    ok[u] = f < M;
+    const int j = owner_of(wl.pre, kWaveTok, ok[u] ? f : M - 1);
+    arc[u] = wl.abase[j] + (int)f;
+    src[u] = base + j;
+    tc[u] = wl.tcost[j];
+    a[u] = make_int4(0, 0, 1, 0);
+    if (ok[u]) a[u] = x.g.unit[arc[u]];
+  }
+  emit_arcs<N>(x, ok, a, tc, src, arc, beam, boosted);
+}
+
 __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float beam = x.s.beam;
   const bool boosted = x.s.boost_n > 0;
-  // Tokens are processed in chunks of kChunk.  A lane reads the 32 bytes at the start of its
-  // tokens' state blocks (header + first arc).  Most states have one emitting arc and no
-  // epsilon arcs: that arc is expanded right away by the lane that owns the token.  Only the
-  // remaining arcs go through the flattened, load-balanced loop.  The loads run one chunk
-  // ahead (tokens two), so a chunk starts with its headers already there.
-  int2 tk[kTPT], tkn[kTPT]; int4 hd[kTPT], fu[kTPT];
+  // Every wave expands its own runs of kWaveTok tokens, at its own pace: no block barrier
+  // until all tokens are done, so the waves drift apart and one wave's loads overlap
+  // another's arithmetic.  A lane reads the 32 bytes at the start of its tokens' state
+  // blocks (header + first arc).  Most states have one emitting arc and no epsilon arcs:
+  // that arc is expanded right away by the lane that owns the token.  The remaining arcs of
+  // the wave's tokens are flattened over its 64 lanes (prefix sums in the wave's slice of
+  // LDS, one short binary search per arc).  States with more than kHubDeg arcs are listed
+  // and expanded afterwards by the whole block.  Loads run one run ahead (tokens two).
+  WaveLds &wl = e.w[wave];
+  constexpr int kPer = kWaveTok / 64;
+  constexpr int kStride = kWaves * kWaveTok;
+  int2 tk[kPer], tkn[kPer]; int4 hd[kPer], fu[kPer];
+  int base = wave * kWaveTok;
 #pragma unroll
-  for (int k = 0; k < kTPT; ++k) {
-    const int i = kTPT * tid + k;
+  for (int k = 0; k < kPer; ++k) {
+    const int i = base + k * 64 + lane;
     tk[k] = make_int2(0, 0);
     if (i < n_tok) tk[k] = Q[i];
   }
 #pragma unroll
-  for (int k = 0; k < kTPT; ++k) {
-    const int i = kTPT * tid + k;
+  for (int k = 0; k < kPer; ++k) {
+    const int i = base + k * 64 + lane;
     hd[k] = make_int4(0, 0, 0, 0); fu[k] = make_int4(0, 0, 1, 0);
     if (i < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk[k].x; hd[k] = b[0]; fu[k] = b[1]; }
     tkn[k] = make_int2(0, 0);
-    if (kChunk + i < n_tok) tkn[k] = Q[kChunk + i];
+    if (i + kStride < n_tok) tkn[k] = Q[i + kStride];
   }
-  for (int cb = 0, par = 0; cb < n_tok; cb += kChunk, par ^= 1) {
-    ChunkLds &ck = e.ch[par];
-    unsigned deg[kTPT], ex[kTPT]; int first[kTPT];
+  unsigned long long n_arcs = 0;                       // wave-uniform: emitting arcs this wave expanded
+  for (; base < n_tok; base += kStride) {
+    unsigned deg[kPer], ex[kPer]; int first[kPer];
     {
-      bool has[kTPT]; float tc[kTPT]; int src[kTPT], arc[kTPT]; int4 a0[kTPT];
-      int n_first = 0;
+      bool has[kPer]; float tc[kPer]; int src[kPer], arc[kPer]; int4 a0[kPer];
 #pragma unroll
-      for (int k = 0; k < kTPT; ++k) {
+      for (int k = 0; k < kPer; ++k) {
         const int ne = hd[k].x, nx = hd[k].y;
         has[k] = ne > 0 && nx == 0;                     // the unit after the header is an emitting arc
         deg[k] = (unsigned)(ne - (has[k] ? 1 : 0));
         first[k] = 2 * tk[k].x + 1 + nx + (has[k] ? 1 : 0);   // unit address of the first arc left
-        tc[k] = __int_as_float(tk[k].y); src[k] = cb + kTPT * tid + k; arc[k] = 2 * tk[k].x + 1;
+        tc[k] = __int_as_float(tk[k].y); src[k] = base + k * 64 + lane; arc[k] = 2 * tk[k].x + 1;
         a0[k] = has[k] ? fu[k] : make_int4(0, 0, 1, 0);
-        n_first += __popcll(__ballot(has[k]));
+        n_arcs += (unsigned)__popcll(__ballot(has[k]));
+        if (deg[k] > (unsigned)kHubDeg) {               // to the block's list, if it has room
+          const int h = atomicAdd(&sm.n_hub, 1);
+          if (h < kHubCap) {
+            e.hub.pre[h] = deg[k]; e.hub.abase[h] = first[k]; e.hub.tcost[h] = tc[k]; e.hub.ttok[h] = src[k];
+            deg[k] = 0;
+          }
+        }
       }
-      if ((tid & 63) == 0 && n_first) atomicAdd((unsigned long long *)&sm.ctr[kCtEarc], (unsigned long long)n_first);
-      emit_arcs<kTPT>(x, has, a0, tc, src, arc, beam, boosted);
+      emit_arcs<kPer>(x, has, a0, tc, src, arc, beam, boosted);
     }
-    const unsigned M = block_scan(sm, deg, ex);
+    // exclusive prefix sums of the wave's kWaveTok counts (item j = k*64 + lane)
+    unsigned M = 0;
 #pragma unroll
-    for (int k = 0; k < kTPT; ++k) {
-      ck.pre[kTPT * tid + k] = ex[k];
-      ck.abase[kTPT * tid + k] = first[k] - (int)ex[k];
-      ck.tcost[kTPT * tid + k] = __int_as_float(tk[k].y);
+    for (int k = 0; k < kPer; ++k) {
+      unsigned inc = deg[k];
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) { const unsigned t = __shfl_up(inc, o, 64); if (lane >= o) inc += t; }
+      ex[k] = M + inc - deg[k];
+      M += (unsigned)__shfl((int)inc, 63, 64);
     }
-    if (tid == kBlock - 1) ck.pre[kChunk] = M;
-    if (tid == 0) sm.ctr[kCtEarc] += M;
-    __syncthreads();
-    prof_mark(sm, kPhExpSetup);
-    // the next chunk's headers and the tokens of the chunk after it
 #pragma unroll
-    for (int k = 0; k < kTPT; ++k) {
-      const int i = cb + kChunk + kTPT * tid + k;
+    for (int k = 0; k < kPer; ++k) {
+      wl.pre[k * 64 + lane] = ex[k];
+      wl.abase[k * 64 + lane] = first[k] - (int)ex[k];
+      wl.tcost[k * 64 + lane] = __int_as_float(tk[k].y);
+    }
+    if (lane == 0) wl.pre[kWaveTok] = M;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    n_arcs += M;
+    // the next run's headers and the tokens of the run after it
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const int i = base + kStride + k * 64 + lane;
       tk[k] = tkn[k];
       hd[k] = make_int4(0, 0, 0, 0); fu[k] = make_int4(0, 0, 1, 0);
       if (i < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk[k].x; hd[k] = b[0]; fu[k] = b[1]; }
       tkn[k] = make_int2(0, 0);
-      if (i + kChunk < n_tok) tkn[k] = Q[i + kChunk];
+      if (i + kStride < n_tok) tkn[k] = Q[i + kStride];
     }
+    // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
+    unsigned f0 = 0;
+    for (; f0 + 64 < M; f0 += 64 * kUE) wave_arcs<kUE>(x, wl, base, f0, M, beam, boosted);
+    if (f0 < M) wave_arcs<1>(x, wl, base, f0, M, beam, boosted);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (lane == 0 && n_arcs) atomicAdd((unsigned long long *)&sm.ctr[kCtEarc], n_arcs);
+  __syncthreads();
+  prof_mark(sm, kPhExpSetup);
+  // the listed high-degree states, flattened over the whole block
+  const int n_hub = uni(min(sm.n_hub, kHubCap));
+  if (n_hub > 0) {
+    HubLds &hb = e.hub;
+    unsigned d[1], ex[1];
+    d[0] = tid < n_hub ? hb.pre[tid] : 0u;
+    const unsigned M = block_scan<1>(sm, d, ex);
+    if (tid < n_hub) { hb.pre[tid] = ex[0]; hb.abase[tid] -= (int)ex[0]; }
+    if (tid == 0) { hb.pre[n_hub] = M; sm.ctr[kCtEarc] += M; sm.n_hub = 0; }
+    __syncthreads();
     for (unsigned f0 = 0; f0 < M; f0 += kBlock * kUE) {
       bool ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
-      owners_of<kUE>(ck, f0, M, ok, j);
+      owners_of<kUE>(hb.pre, n_hub, f0, M, ok, j);
 #pragma unroll
-      for (int u = 0; u < kUE; ++u) {          // arc fetch, kUE in flight
-        arc[u] = ck.abase[j[u]] + (int)(f0 + u * kBlock + tid);
-        src[u] = cb + j[u];
-        tc[u] = ck.tcost[j[u]];
+      for (int u = 0; u < kUE; ++u) {
+        arc[u] = hb.abase[j[u]] + (int)(f0 + u * kBlock + tid);
+        src[u] = hb.ttok[j[u]];
+        tc[u] = hb.tcost[j[u]];
         a[u] = make_int4(0, 0, 1, 0);
         if (ok[u]) a[u] = x.g.unit[arc[u]];
       }
       emit_arcs<kUE>(x, ok, a, tc, src, arc, beam, boosted);
     }
-    prof_mark(sm, kPhExpLoop);        // no barrier: the next chunk uses the other table buffer
+    __syncthreads();
   }
-  __syncthreads();
+  prof_mark(sm, kPhExpLoop);
 }
 
 // ------------------------------------------------------------------ recombination in LDS
@@ -856,7 +933,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
 #pragma unroll
       for (int sft = 32; sft > 0; sft >>= 1) xsum += (unsigned)__shfl_xor((int)xsum, sft, 64);
       if ((tid & 63) == 0 && xsum) atomicAdd((unsigned long long *)&sm.ctr[kCtXarc], (unsigned long long)xsum);
-      const unsigned M = block_scan(sm, deg, ex);
+      const unsigned M = block_scan<kTPT>(sm, deg, ex);
 #pragma unroll
       for (int k = 0; k < kTPT; ++k) {
         ck.pre[kTPT * tid + k] = ex[k];
@@ -868,7 +945,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
         bool ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
-        owners_of<kU>(ck, f0, M, ok, j);
+        owners_of<kU>(ck.pre, kChunk, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           arc[u] = ck.abase[j[u]] + (int)(f0 + u * kBlock + tid);
@@ -1121,7 +1198,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     }
 
   if (tid == 0) {
-    sm.best_ord = kOrdNone; sm.n_occ = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.best_ord = kOrdNone; sm.n_occ = 0; sm.n_hub = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
     for (int r = 0; r < kRegions; ++r) sm.n_reg[r] = 0;
     sm.status = 0; sm.red64 = 0; sm.red64b = 0; sm.k_keep = 256; sm.k_sel = 256; sm.n_sel = 0; sm.redo = 0;
     for (int i = 0; i < 16; ++i) sm.prof[i] = 0;
