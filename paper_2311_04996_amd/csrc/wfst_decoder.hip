@@ -243,10 +243,8 @@ struct Cutoff {
   float best, beam, scale; int k_keep;
   __device__ __forceinline__ int bin(float c) const {
     if (beam == 0.0f) return 0;
-    float x = floorf((c - best) * scale);
-    if (!(x > 0.0f)) return 0;
-    if (x > 255.0f) return 255;
-    return (int)x;
+    // clamp to [0, 255] without branches; a NaN (inf - inf) lands in bin 0 like every x <= 0
+    return (int)fminf(fmaxf(floorf((c - best) * scale), 0.0f), 255.0f);
   }
   __device__ __forceinline__ bool in_beam(float c) const { return (c - best) <= beam; }
   __device__ __forceinline__ bool keep(float c) const { return in_beam(c) && bin(c) < k_keep; }
@@ -584,16 +582,12 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
 __device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int arc, int idx) {
   TableLds &t = x.sm.u.t;
   unsigned s = (hash_state(dst) >> 6) & kTabMask;
-  int probes = 0;
-  for (;;) {
-    const int k = t.keys[s];
-    if (k == dst) break;
-    if (k == kKeyEmpty) {
-      const int old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
-      if (old == kKeyEmpty || old == dst) break;
-    }
+  // one compare-and-swap per probe: it returns the slot's key, or claims the slot if it was free
+  for (int probes = 0;; ++probes) {
+    const int old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
+    if (old == kKeyEmpty || old == dst) break;
     s = (s + 1) & kTabMask;
-    if (++probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return; }   // table full
+    if (probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return; }   // table full
   }
   const unsigned oc = f2ord(cost);
   const unsigned long long mine = ((unsigned long long)oc << 32) | (unsigned)idx;
