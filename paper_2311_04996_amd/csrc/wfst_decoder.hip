@@ -195,14 +195,16 @@ struct Smem {
 };
 
 // ------------------------------------------------------------------------------ helpers
+// Order-preserving map of float bits to unsigned (negative: all bits flipped, else sign set).
 __device__ __forceinline__ unsigned f2ord(float f) {
-  unsigned u = __float_as_uint(f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  const unsigned u = __float_as_uint(f);
+  return u ^ ((unsigned)((int)u >> 31) | 0x80000000u);
 }
 __device__ __forceinline__ float ord2f(unsigned o) {
-  return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+  return __uint_as_float(o ^ ((unsigned)((int)~o >> 31) | 0x80000000u));
 }
-__device__ __forceinline__ float canon(float x) { return x == 0.0f ? 0.0f : x; }
+// -0 becomes +0 (costs are compared by their bits); every other value is unchanged.
+__device__ __forceinline__ float canon(float x) { return x + 0.0f; }
 __device__ __forceinline__ unsigned hash_state(int s) { return (unsigned)s * 0x9E3779B1u; }
 __host__ __device__ inline unsigned boost_slot(int word) { return ((unsigned)word * 0x9E3779B1u) >> 21; }   // 11 bits
 __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
@@ -221,6 +223,22 @@ __device__ __forceinline__ float boost_of(const Smem &sm, int word);
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive adds: four
+// shifts inside each row of 16 lanes, then the last lane of row 0 (2) onto row 1 (3) and lane
+// 31 onto rows 2 and 3.  Six vector instructions, no LDS traffic.
+__device__ __forceinline__ unsigned wave_scan_add(unsigned v) {
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
+  return v;
+}
+__device__ __forceinline__ unsigned wave_sum(unsigned v) {
+  return (unsigned)__builtin_amdgcn_readlane((int)wave_scan_add(v), 63);
+}
 
 // Indices from an LDS counter for every (lane, u) with pred[u] set: ONE LDS atomic per wave,
 // and the lanes of a wave get consecutive indices, so their stores coalesce.  Must be called
@@ -292,12 +310,7 @@ __device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[N],
   unsigned s = 0;
 #pragma unroll
   for (int k = 0; k < N; ++k) s += d[k];
-  unsigned inc = s;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    unsigned t = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += t;
-  }
+  const unsigned inc = wave_scan_add(s);
   if (lane == 63) sm.wave_tot[wave] = inc;
   __syncthreads();
   unsigned base = 0, total = 0;
@@ -311,6 +324,15 @@ __device__ __forceinline__ unsigned block_scan(Smem &sm, const unsigned (&d)[N],
 #pragma unroll
   for (int k = 0; k < N; ++k) { ex[k] = run; run += d[k]; }
   return uni(total);
+}
+
+// The same over a table of exactly kWaveTok items: one compare and one select per step.
+__device__ __forceinline__ int wave_owner_of(const unsigned *pre, unsigned f) {
+  int j = 0;
+#pragma unroll
+  for (int step = kWaveTok / 2; step >= 1; step >>= 1)
+    if (pre[j + step] <= f) j += step;
+  return j;
 }
 
 // Which of n work items owns flattened arc f: last j < n with pre[j] <= f (pre[0] = 0).
@@ -440,12 +462,12 @@ __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, u
   for (int u = 0; u < N; ++u) {                // arc fetch, N in flight
     const unsigned f = f0 + u * 64 + lane;
     ok[u] = f < M;
-    const int j = owner_of(wl.pre, kWaveTok, ok[u] ? f : M - 1);
-    arc[u] = wl.abase[j] + (int)f;
+    const unsigned fs = ok[u] ? f : M - 1;       // lanes past the end repeat the last arc (no branch)
+    const int j = wave_owner_of(wl.pre, fs);
+    arc[u] = wl.abase[j] + (int)fs;
     src[u] = base + j;
     tc[u] = wl.tcost[j];
-    a[u] = make_int4(0, 0, 1, 0);
-    if (ok[u]) a[u] = x.g.unit[arc[u]];
+    a[u] = x.g.unit[arc[u]];
   }
   emit_arcs<N>(x, ok, a, tc, src, arc, beam, boosted);
 }
@@ -511,11 +533,9 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
     unsigned M = 0;
 #pragma unroll
     for (int k = 0; k < kPer; ++k) {
-      unsigned inc = deg[k];
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) { const unsigned t = __shfl_up(inc, o, 64); if (lane >= o) inc += t; }
+      const unsigned inc = wave_scan_add(deg[k]);
       ex[k] = M + inc - deg[k];
-      M += (unsigned)__shfl((int)inc, 63, 64);
+      M += (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
     }
 #pragma unroll
     for (int k = 0; k < kPer; ++k) {
@@ -743,9 +763,8 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   if (tid < 64) {
     const unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
     unsigned s = h0 + h1 + h2 + h3, inc = s;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { unsigned tt = __shfl_up(inc, o, 64); if (tid >= o) inc += tt; }
-    const unsigned n_in = __shfl(inc, 63, 64);
+    inc = wave_scan_add(inc);
+    const unsigned n_in = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
     const float want = (float)ma * x.s.sel_ratio + 256.0f;
     const unsigned target = want < 2.0e9f ? (unsigned)want : 2000000000u;
     int ks = 256; unsigned nsel = n_in;
@@ -810,9 +829,8 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     if (tid < 64) {
       const unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
       unsigned s = h0 + h1 + h2 + h3, inc = s;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) { unsigned tt = __shfl_up(inc, o, 64); if (tid >= o) inc += tt; }
-      const unsigned n_u = __shfl(inc, 63, 64);
+      inc = wave_scan_add(inc);
+      const unsigned n_u = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
       int kk = 256, redo = 0;
       if (n_u > ma) {
         unsigned run = inc - s;
@@ -924,8 +942,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         if (w[k].w) xsum += deg[k];
       }
       // epsilon arcs out of the set (a counter): every token is listed as new exactly once
-#pragma unroll
-      for (int sft = 32; sft > 0; sft >>= 1) xsum += (unsigned)__shfl_xor((int)xsum, sft, 64);
+      xsum = wave_sum(xsum);
       if ((tid & 63) == 0 && xsum) atomicAdd((unsigned long long *)&sm.ctr[kCtXarc], (unsigned long long)xsum);
       const unsigned M = block_scan<kTPT>(sm, deg, ex);
 #pragma unroll
