@@ -240,11 +240,12 @@ __device__ __forceinline__ unsigned wave_sum(unsigned v) {
   return (unsigned)__builtin_amdgcn_readlane((int)wave_scan_add(v), 63);
 }
 
+// (Per-lane predicates travel as int arrays: bool arrays get packed into bytes of one register.)
 // Indices from an LDS counter for every (lane, u) with pred[u] set: ONE LDS atomic per wave,
 // and the lanes of a wave get consecutive indices, so their stores coalesce.  Must be called
 // by all 64 lanes of the wave (every call site is inside block-uniform control flow).
 template <int N>
-__device__ __forceinline__ void wave_alloc_n(int *counter, const bool (&pred)[N], int (&idx)[N]) {
+__device__ __forceinline__ void wave_alloc_n(int *counter, const int (&pred)[N], int (&idx)[N]) {
   const int lane = threadIdx.x & 63;
   const unsigned long long lt = (1ull << lane) - 1ull;
   unsigned long long m[N]; int off[N], tot = 0;
@@ -265,7 +266,7 @@ struct Cutoff {
     return (int)fminf(fmaxf(floorf((c - best) * scale), 0.0f), 255.0f);
   }
   __device__ __forceinline__ bool in_beam(float c) const { return (c - best) <= beam; }
-  __device__ __forceinline__ bool keep(float c) const { return in_beam(c) && bin(c) < k_keep; }
+  __device__ __forceinline__ bool keep(float c) const { return (int)in_beam(c) & (int)(bin(c) < k_keep); }
 };
 
 struct Ctx {                  // block-uniform view of one channel
@@ -352,7 +353,7 @@ __device__ __forceinline__ int owner_of(const unsigned *pre, int n, unsigned f) 
 // of each run of 64) bounds every lane's own search to the few items its run spans: 0 steps
 // inside a high-degree state, a few where degrees are small.
 template <int N>
-__device__ __forceinline__ void owners_of(const unsigned *pre, int n, unsigned f0, unsigned M, bool (&ok)[N], int (&j)[N]) {
+__device__ __forceinline__ void owners_of(const unsigned *pre, int n, unsigned f0, unsigned M, int (&ok)[N], int (&j)[N]) {
   static_assert(2 * N <= 64, "bounds are looked up by 2N lanes");
   const int lane = threadIdx.x & 63;
   const unsigned wave_f = f0 + (threadIdx.x & ~63u);
@@ -385,7 +386,7 @@ static_assert(kRegions == 4, "region_of takes two hash bits");
 // that hit the same region write consecutive 16-byte records, so the stores coalesce.
 // Must be called by all 64 lanes of the wave.
 template <int N>
-__device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const int (&next)[N], const float (&nc)[N],
+__device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int (&next)[N], const float (&nc)[N],
                                            const int (&src)[N], const int (&arc)[N]) {
   const int lane = threadIdx.x & 63;
   typedef unsigned long long u64;
@@ -433,10 +434,10 @@ __device__ __forceinline__ void push_cands(Ctx &x, const bool (&ok)[N], const in
 // the running best is never lower than the final one, so this never drops a survivor.
 // Cost, beam test and append for N emitting arcs per lane (all 64 lanes of the wave call it).
 template <int N>
-__device__ __forceinline__ void emit_arcs(Ctx &x, bool (&ok)[N], const int4 (&a)[N], const float (&tc)[N],
+__device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[N], const float (&tc)[N],
                                           const int (&src)[N], const int (&arc)[N], float beam, bool boosted) {
   Smem &sm = x.sm;
-  const unsigned bo = *(volatile unsigned *)&sm.best_ord;
+  const unsigned bo = __hip_atomic_load(&sm.best_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
   unsigned o = kOrdNone;
   float nc[N]; int next[N];
@@ -444,8 +445,9 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, bool (&ok)[N], const int4 (&a)
   for (int u = 0; u < N; ++u) {
     nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + sm.u.e.ac[a[u].z - 1]);
     if (boosted && a[u].w != 0 && ok[u]) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // + b[olabel]
-    ok[u] = ok[u] && (nc[u] < INFINITY) && !((nc[u] - rb) > beam);
-    if (ok[u]) o = min(o, f2ord(nc[u]));
+    // predicates are combined with & and selects: no short-circuit branches in the hot loop
+    ok[u] &= (int)(nc[u] < INFINITY) & (int)!((nc[u] - rb) > beam);
+    o = min(o, ok[u] ? f2ord(nc[u]) : kOrdNone);
     next[u] = a[u].x;
   }
   // running best: only lanes that would lower it touch the LDS word (rare after the first arcs)
@@ -457,7 +459,7 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, bool (&ok)[N], const int4 (&a)
 template <int N>
 __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, unsigned f0, unsigned M, float beam, bool boosted) {
   const int lane = threadIdx.x & 63;
-  bool ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N];
+  int ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N];
 #pragma unroll
   for (int u = 0; u < N; ++u) {                // arc fetch, N in flight
     const unsigned f = f0 + u * 64 + lane;
@@ -509,7 +511,7 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   for (; base < n_tok; base += kStride) {
     unsigned deg[kPer], ex[kPer]; int first[kPer];
     {
-      bool has[kPer]; float tc[kPer]; int src[kPer], arc[kPer]; int4 a0[kPer];
+      int has[kPer]; float tc[kPer]; int src[kPer], arc[kPer]; int4 a0[kPer];
 #pragma unroll
       for (int k = 0; k < kPer; ++k) {
         const int ne = hd[k].x, nx = hd[k].y;
@@ -578,7 +580,7 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
     if (tid == 0) { hb.pre[n_hub] = M; sm.ctr[kCtEarc] += M; sm.n_hub = 0; }
     __syncthreads();
     for (unsigned f0 = 0; f0 < M; f0 += kBlock * kUE) {
-      bool ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
+      int ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
       owners_of<kUE>(hb.pre, n_hub, f0, M, ok, j);
 #pragma unroll
       for (int u = 0; u < kUE; ++u) {
@@ -649,8 +651,8 @@ __device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G,
       if (i + kBlock < n) nxt = x.cand[base + i + kBlock];
       const float c = __int_as_float(cd.y);
       const int key = key_of(cd.x);
-      bool take = G == 1 || group_of(key, G) == g;
-      if (kSelect) take = take && cut.in_beam(c) && cut.bin(c) < k_sel;
+      int take = (int)(G == 1) | (int)(group_of(key, G) == g);
+      if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
       if (take) table_insert(x, key, c, cd.w, base + i);
     }
   }
@@ -697,11 +699,11 @@ __device__ __forceinline__ int total_candidates(const Ctx &x) {
 // existing tokens (tok[]) that were improved and must be expanded again.  Called by all
 // lanes of the wave.
 template <int N>
-__device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const int (&ti)[N], const int (&next)[N],
+__device__ __forceinline__ void make_tokens(Ctx &x, const int (&make)[N], const int (&ti)[N], const int (&next)[N],
                                             const int (&costbits)[N], const int (&prev)[N], const int (&arc)[N],
-                                            const bool (&also)[N], const int (&tok)[N],
+                                            const int (&also)[N], const int (&tok)[N],
                                             int2 *NQ, unsigned lat_base, int4 *WLN, unsigned tag16) {
-  bool want[2 * N]; int wi[2 * N];
+  int want[2 * N]; int wi[2 * N];
 #pragma unroll
   for (int u = 0; u < N; ++u) {
     const int key = key_of(next[u]);
@@ -711,8 +713,8 @@ __device__ __forceinline__ void make_tokens(Ctx &x, const bool (&make)[N], const
       x.lat[lat_base + ti[u]] = make_int2(prev[u], arc[u]);
       if ((unsigned)next[u] & kFlagEpsIn) x.index[key] = tag16 | (unsigned)ti[u];
     }
-    want[u] = make[u] && has_eps;
-    want[N + u] = also[u] && has_eps;
+    want[u] = make[u] & (int)has_eps;
+    want[N + u] = also[u] & (int)has_eps;
   }
   wave_alloc_n<2 * N>(&x.sm.n_wl_next, want, wi);
 #pragma unroll
@@ -805,7 +807,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       prof_mark(sm, kPhTabFill);
       {
         constexpr int kS = kTabSlots / kBlock;
-        int key[kS]; unsigned long long v[kS]; bool win[kS]; int wi[kS];
+        int key[kS]; unsigned long long v[kS]; int win[kS]; int wi[kS];
 #pragma unroll
         for (int k = 0; k < kS; ++k) {
           key[k] = t.keys[k * kBlock + tid]; v[k] = t.vals[k * kBlock + tid];
@@ -872,20 +874,20 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   const unsigned tag16 = set_tag(x.s.epoch) << 16;
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kUC) {
-    int2 sc[kUC]; int ci[kUC]; bool kp[kUC]; int4 cr[kUC];
+    int2 sc[kUC]; int ci[kUC]; int kp[kUC]; int4 cr[kUC];
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
       const int i = i0 + u * kBlock + tid;
       sc[u] = make_int2(0, 0); ci[u] = 0;
       if (i < n_win) { sc[u] = x.win_sc[i]; ci[u] = x.win_ci[i]; }
-      kp[u] = i < n_win && cut.bin(__int_as_float(sc[u].y)) < cut.k_keep;
+      kp[u] = (int)(i < n_win) & (int)(cut.bin(__int_as_float(sc[u].y)) < cut.k_keep);
     }
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
       cr[u] = make_int4(0, 0, 0, 0);
       if (kp[u]) cr[u] = x.cand[ci[u]];
     }
-    int ti[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; bool good[kUC], no[kUC];
+    int ti[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; int good[kUC], no[kUC];
     wave_alloc_n<kUC>(&sm.n_next, kp, ti);
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
@@ -955,7 +957,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       if (tid == kBlock - 1) ck.pre[kChunk] = M;
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-        bool ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
+        int ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
         owners_of<kU>(ck.pre, kChunk, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
@@ -970,7 +972,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         for (int u = 0; u < kU; ++u) {
           nc[u] = canon(tc[u] + __int_as_float(a[u].y));
           if (boosted && ok[u] && a[u].w != 0) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // epsilon arcs can carry output labels too
-          ok[u] = ok[u] && (nc[u] < INFINITY) && cut.keep(nc[u]);
+          ok[u] &= (int)(nc[u] < INFINITY) & (int)cut.keep(nc[u]);
           next[u] = a[u].x; arc[u] |= (int)kArcEps;
         }
         push_cands<kU>(x, ok, next, nc, src, arc);
@@ -993,7 +995,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       // occupied slots, compacted, so that the dependent global reads below run on full waves
       {
         constexpr int kS = kTabSlots / kBlock;
-        bool oc[kS]; int oi[kS];
+        int oc[kS]; int oi[kS];
 #pragma unroll
         for (int k = 0; k < kS; ++k) oc[k] = t.keys[k * kBlock + tid] != kKeyEmpty;
         wave_alloc_n<kS>(&sm.n_occ, oc, oi);
@@ -1005,7 +1007,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       // per destination: winning candidate, state index, state record -> existing token
       for (int i0 = 0; i0 < n_occ; i0 += kBlock * kU) {
         int d[kU]; int4 rec[kU]; unsigned ix[kU]; int tok[kU];
-        float oc[kU]; unsigned oa[kU]; bool occ[kU], exists[kU]; unsigned ci[kU];
+        float oc[kU]; unsigned oa[kU]; int occ[kU], exists[kU]; unsigned ci[kU];
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
           const int i = i0 + k * kBlock + tid;
@@ -1020,17 +1022,17 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         }
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
-          exists[k] = occ[k] && (ix[k] >> 16) == tag;
+          exists[k] = occ[k] & (int)((ix[k] >> 16) == tag);
           tok[k] = (int)(ix[k] & 0xffffu);
           oc[k] = 0.0f; oa[k] = 0;
           if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
         }
-        bool fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
+        int fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
 #pragma unroll
         for (int k = 0; k < kU; ++k) {
           const float nc = __int_as_float(rec[k].y);
-          improve[k] = exists[k] && (nc < oc[k] || (nc == oc[k] && (unsigned)rec[k].w < oa[k]));
-          fresh[k] = occ[k] && !exists[k];
+          improve[k] = exists[k] & ((int)(nc < oc[k]) | ((int)(nc == oc[k]) & (int)((unsigned)rec[k].w < oa[k])));
+          fresh[k] = occ[k] & (int)!exists[k];
         }
         wave_alloc_n<kU>(&sm.n_next, fresh, ni);
 #pragma unroll
@@ -1228,7 +1230,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     int2 *NQ = x.q0 + c.qcap;
     if (tid == 0) sm.n_next = 1;
     {
-      const bool mk[1] = {tid == 0}, no[1] = {false};
+      const int mk[1] = {tid == 0}, no[1] = {false};
       const int z[1] = {0}, st[1] = {(int)g.start}, m1[1] = {-1};
       make_tokens<1>(x, mk, z, st, z, m1, m1, no, z, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
     }
