@@ -72,7 +72,7 @@ constexpr int kWaves = kBlock / 64;
 #endif
 constexpr int kTPT = WFST_TPT;                // work items per thread per chunk (1, 2 or 4)
 constexpr int kChunk = kBlock * kTPT;
-constexpr int kWaveTok = 128;                 // tokens a wave expands at a time (2 per lane)
+constexpr int kWaveTok = 64;                  // tokens a wave expands at a time (2 per lane)
 constexpr int kHubCap = 512;                  // listed high-degree tokens per frame (more are expanded by their wave)
 constexpr int kHubDeg = 256;                  // arcs beyond which a token is listed there
 constexpr int kChunkLog2 = (kTPT == 4 ? 2 : (kTPT == 2 ? 1 : 0)) + (kBlock == 1024 ? 10 : (kBlock == 512 ? 9 : 8));
