@@ -86,6 +86,7 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 #define WFST_UC 4
 #endif
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
+constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
 constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
 constexpr int kRegions = 4;                   // candidate buffer regions (by destination hash)
 constexpr int kTabSlots = WFST_TAB;           // LDS recombination table (power of two)
@@ -160,11 +161,13 @@ struct WaveLds {              // ExpandArcs: the work items of one wave (2 token
   int abase[kWaveTok];
   float tcost[kWaveTok];
 };
-struct HubLds {               // ExpandArcs: states with so many arcs that the whole block expands them
-  unsigned pre[kHubCap + 1];
-  int abase[kHubCap];
+struct HubLds {               // ExpandArcs: states with so many arcs that all waves share them
+  int first[kHubCap];         // unit address of the first arc to expand
+  int deg[kHubCap];           // arcs to expand
   float tcost[kHubCap];
   int ttok[kHubCap];
+  int ready[kHubCap];         // set after the entry is written
+  int seg_next[kHubCap];      // next segment of kHubSeg arcs nobody has taken yet
 };
 struct ExpandLds {            // live while arcs are being expanded
   float ac[kMaxV];
@@ -182,7 +185,7 @@ struct Smem {
   unsigned wave_tot[kWaves];
   unsigned best_ord;
   int n_reg[kRegions];        // candidates per region
-  int n_occ, n_hub;
+  int n_occ, n_hub, next_run, done_waves;
   int n_win, n_next, n_wl_next, status;
   int k_sel, n_sel, k_keep, redo;
   unsigned long long red64, red64b;
@@ -474,127 +477,137 @@ __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, u
   emit_arcs<N>(x, ok, a, tc, src, arc, beam, boosted);
 }
 
+// Arcs [f0, f0 + 64N) of one listed high-degree state (all lanes of the wave call it).
+template <int N>
+__device__ __forceinline__ void hub_arcs(Ctx &x, int first, int deg, float cost, int tok, int f0, float beam, bool boosted) {
+  const int lane = threadIdx.x & 63;
+  int ok[N], src[N], arc[N]; int4 a[N]; float tc[N];
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    const int f = f0 + u * 64 + lane;
+    ok[u] = f < deg;
+    arc[u] = first + (ok[u] ? f : deg - 1);      // lanes past the end repeat the last arc (no branch)
+    src[u] = tok; tc[u] = cost;
+    a[u] = x.g.unit[arc[u]];
+  }
+  emit_arcs<N>(x, ok, a, tc, src, arc, beam, boosted);
+}
+
+// Next run of kWaveTok tokens for this wave (a block-wide counter in LDS; wave-uniform).
+__device__ __forceinline__ int next_run(Smem &sm) {
+  int r = 0;
+  if ((threadIdx.x & 63) == 0) r = atomicAdd(&sm.next_run, 1);
+  return uni(r);
+}
+
+// On entry sm.next_run == kWaves, sm.done_waves == 0, sm.n_hub == 0 and the hub list's ready
+// and seg_next words are zero (the caller sets them before its barrier).
 __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
+  HubLds &hb = e.hub;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float beam = x.s.beam;
   const bool boosted = x.s.boost_n > 0;
-  // Every wave expands its own runs of kWaveTok tokens, at its own pace: no block barrier
-  // until all tokens are done, so the waves drift apart and one wave's loads overlap
-  // another's arithmetic.  A lane reads the 32 bytes at the start of its tokens' state
-  // blocks (header + first arc).  Most states have one emitting arc and no epsilon arcs:
-  // that arc is expanded right away by the lane that owns the token.  The remaining arcs of
-  // the wave's tokens are flattened over its 64 lanes (prefix sums in the wave's slice of
-  // LDS, one short binary search per arc).  States with more than kHubDeg arcs are listed
-  // and expanded afterwards by the whole block.  Loads run one run ahead (tokens two).
+  // Every wave expands runs of kWaveTok tokens at its own pace: it takes the next run from a
+  // counter, so no wave waits for another until all tokens are done, and one wave's loads
+  // overlap another's arithmetic.  A lane reads the 32 bytes at the start of its token's
+  // state block (header + first arc).  Most states have one emitting arc and no epsilon
+  // arcs: that arc is expanded right away by the lane that owns the token.  The remaining
+  // arcs of the run are flattened over the 64 lanes (prefix sums in the wave's slice of LDS,
+  // one short search per arc).  States with more than kHubDeg arcs are listed instead; when
+  // a wave finds no run left it takes segments of listed states until those are done too.
+  // Loads run one run ahead (tokens two).
+  static_assert(kWaveTok == 64, "one token per lane");
   WaveLds &wl = e.w[wave];
-  constexpr int kPer = kWaveTok / 64;
-  constexpr int kStride = kWaves * kWaveTok;
-  int2 tk[kPer], tkn[kPer]; int4 hd[kPer], fu[kPer];
-  int base = wave * kWaveTok;
-#pragma unroll
-  for (int k = 0; k < kPer; ++k) {
-    const int i = base + k * 64 + lane;
-    tk[k] = make_int2(0, 0);
-    if (i < n_tok) tk[k] = Q[i];
-  }
-#pragma unroll
-  for (int k = 0; k < kPer; ++k) {
-    const int i = base + k * 64 + lane;
-    hd[k] = make_int4(0, 0, 0, 0); fu[k] = make_int4(0, 0, 1, 0);
-    if (i < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk[k].x; hd[k] = b[0]; fu[k] = b[1]; }
-    tkn[k] = make_int2(0, 0);
-    if (i + kStride < n_tok) tkn[k] = Q[i + kStride];
-  }
+  const int R = (n_tok + kWaveTok - 1) / kWaveTok;
+  int r = wave, rn = next_run(sm);
+  int2 tk = make_int2(0, 0), tkn = make_int2(0, 0); int4 hd = make_int4(0, 0, 0, 0), fu = make_int4(0, 0, 1, 0);
+  if (r * kWaveTok + lane < n_tok) tk = Q[r * kWaveTok + lane];
+  if (rn < R && rn * kWaveTok + lane < n_tok) tkn = Q[rn * kWaveTok + lane];
+  if (r * kWaveTok + lane < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk.x; hd = b[0]; fu = b[1]; }
   unsigned long long n_arcs = 0;                       // wave-uniform: emitting arcs this wave expanded
-  for (; base < n_tok; base += kStride) {
-    unsigned deg[kPer], ex[kPer]; int first[kPer];
+  while (r < R) {
+    const int base = r * kWaveTok;
+    unsigned deg; int first;
     {
-      int has[kPer]; float tc[kPer]; int src[kPer], arc[kPer]; int4 a0[kPer];
-#pragma unroll
-      for (int k = 0; k < kPer; ++k) {
-        const int ne = hd[k].x, nx = hd[k].y;
-        has[k] = ne > 0 && nx == 0;                     // the unit after the header is an emitting arc
-        deg[k] = (unsigned)(ne - (has[k] ? 1 : 0));
-        first[k] = 2 * tk[k].x + 1 + nx + (has[k] ? 1 : 0);   // unit address of the first arc left
-        tc[k] = __int_as_float(tk[k].y); src[k] = base + k * 64 + lane; arc[k] = 2 * tk[k].x + 1;
-        a0[k] = has[k] ? fu[k] : make_int4(0, 0, 1, 0);
-        n_arcs += (unsigned)__popcll(__ballot(has[k]));
-        if (deg[k] > (unsigned)kHubDeg) {               // to the block's list, if it has room
-          const int h = atomicAdd(&sm.n_hub, 1);
-          if (h < kHubCap) {
-            e.hub.pre[h] = deg[k]; e.hub.abase[h] = first[k]; e.hub.tcost[h] = tc[k]; e.hub.ttok[h] = src[k];
-            deg[k] = 0;
-          }
+      int has[1], src[1], arc[1]; float tc[1]; int4 a0[1];
+      const int ne = hd.x, nx = hd.y;
+      has[0] = (int)(ne > 0) & (int)(nx == 0);          // the unit after the header is an emitting arc
+      deg = (unsigned)(ne - has[0]);
+      first = 2 * tk.x + 1 + nx + has[0];               // unit address of the first arc left
+      tc[0] = __int_as_float(tk.y); src[0] = base + lane; arc[0] = 2 * tk.x + 1;
+      a0[0] = has[0] ? fu : make_int4(0, 0, 1, 0);
+      n_arcs += (unsigned)__popcll(__ballot(has[0]));
+      if (deg > (unsigned)kHubDeg) {                    // to the shared list, if it has room
+        const int h = atomicAdd(&sm.n_hub, 1);
+        if (h < kHubCap) {
+          hb.first[h] = first; hb.deg[h] = (int)deg; hb.tcost[h] = tc[0]; hb.ttok[h] = src[0];
+          __hip_atomic_store(&hb.ready[h], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+          deg = 0;
         }
       }
-      emit_arcs<kPer>(x, has, a0, tc, src, arc, beam, boosted);
+      emit_arcs<1>(x, has, a0, tc, src, arc, beam, boosted);
     }
-    // exclusive prefix sums of the wave's kWaveTok counts (item j = k*64 + lane)
-    unsigned M = 0;
-#pragma unroll
-    for (int k = 0; k < kPer; ++k) {
-      const unsigned inc = wave_scan_add(deg[k]);
-      ex[k] = M + inc - deg[k];
-      M += (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
-    }
-#pragma unroll
-    for (int k = 0; k < kPer; ++k) {
-      wl.pre[k * 64 + lane] = ex[k];
-      wl.abase[k * 64 + lane] = first[k] - (int)ex[k];
-      wl.tcost[k * 64 + lane] = __int_as_float(tk[k].y);
-    }
+    // exclusive prefix sums of the run's arc counts (item j = lane)
+    const unsigned inc = wave_scan_add(deg);
+    const unsigned M = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
+    wl.pre[lane] = inc - deg;
+    wl.abase[lane] = first - (int)(inc - deg);
+    wl.tcost[lane] = __int_as_float(tk.y);
     if (lane == 0) wl.pre[kWaveTok] = M;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     n_arcs += M;
-    // the next run's headers and the tokens of the run after it
-#pragma unroll
-    for (int k = 0; k < kPer; ++k) {
-      const int i = base + kStride + k * 64 + lane;
-      tk[k] = tkn[k];
-      hd[k] = make_int4(0, 0, 0, 0); fu[k] = make_int4(0, 0, 1, 0);
-      if (i < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk[k].x; hd[k] = b[0]; fu[k] = b[1]; }
-      tkn[k] = make_int2(0, 0);
-      if (i + kStride < n_tok) tkn[k] = Q[i + kStride];
-    }
+    // the next run's header and the token of the run after it
+    const int rnn = next_run(sm);
+    tk = tkn;
+    hd = make_int4(0, 0, 0, 0); fu = make_int4(0, 0, 1, 0);
+    if (rn < R && rn * kWaveTok + lane < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk.x; hd = b[0]; fu = b[1]; }
+    tkn = make_int2(0, 0);
+    if (rnn < R && rnn * kWaveTok + lane < n_tok) tkn = Q[rnn * kWaveTok + lane];
     // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
     unsigned f0 = 0;
     for (; f0 + 64 < M; f0 += 64 * kUE) wave_arcs<kUE>(x, wl, base, f0, M, beam, boosted);
     if (f0 < M) wave_arcs<1>(x, wl, base, f0, M, beam, boosted);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    r = rn; rn = rnn;
+  }
+  // this wave lists no more states
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  if (lane == 0) atomicAdd(&sm.done_waves, 1);
+  // ---- listed states, a segment at a time, until every wave is done listing and none is left
+  {
+    int h = 0, spins = 0;
+    while (h < kHubCap) {
+      int ready = uni(__hip_atomic_load(&hb.ready[h], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+      if (!ready) {
+        const int done = uni(__hip_atomic_load(&sm.done_waves, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+        if (done == kWaves) {                           // nobody lists any more: is the entry really absent?
+          ready = uni(__hip_atomic_load(&hb.ready[h], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+          if (!ready) break;
+        } else {
+          if (++spins > (1 << 22)) { if (lane == 0) atomicOr(&sm.status, kStCapacity); break; }   // never expected
+          __builtin_amdgcn_s_sleep(4);
+          continue;
+        }
+      }
+      int seg = 0;
+      if (lane == 0) seg = atomicAdd(&hb.seg_next[h], 1);
+      seg = uni(seg);
+      const int deg = uni(hb.deg[h]);
+      const int f0 = seg * kHubSeg;
+      if (f0 >= deg) { ++h; continue; }
+      const int first = uni(hb.first[h]), tok = uni(hb.ttok[h]); const float cost = uni(hb.tcost[h]);
+      if (deg - f0 > 64) hub_arcs<kUE>(x, first, deg, cost, tok, f0, beam, boosted);
+      else hub_arcs<1>(x, first, deg, cost, tok, f0, beam, boosted);
+      n_arcs += (unsigned)min(kHubSeg, deg - f0);
+    }
   }
   if (lane == 0 && n_arcs) atomicAdd((unsigned long long *)&sm.ctr[kCtEarc], n_arcs);
   __syncthreads();
   prof_mark(sm, kPhExpSetup);
-  // the listed high-degree states, flattened over the whole block
-  const int n_hub = uni(min(sm.n_hub, kHubCap));
-  if (n_hub > 0) {
-    HubLds &hb = e.hub;
-    unsigned d[1], ex[1];
-    d[0] = tid < n_hub ? hb.pre[tid] : 0u;
-    const unsigned M = block_scan<1>(sm, d, ex);
-    if (tid < n_hub) { hb.pre[tid] = ex[0]; hb.abase[tid] -= (int)ex[0]; }
-    if (tid == 0) { hb.pre[n_hub] = M; sm.ctr[kCtEarc] += M; sm.n_hub = 0; }
-    __syncthreads();
-    for (unsigned f0 = 0; f0 < M; f0 += kBlock * kUE) {
-      int ok[kUE]; int src[kUE]; int4 a[kUE]; int arc[kUE]; float tc[kUE]; int j[kUE];
-      owners_of<kUE>(hb.pre, n_hub, f0, M, ok, j);
-#pragma unroll
-      for (int u = 0; u < kUE; ++u) {
-        arc[u] = hb.abase[j[u]] + (int)(f0 + u * kBlock + tid);
-        src[u] = hb.ttok[j[u]];
-        tc[u] = hb.tcost[j[u]];
-        a[u] = make_int4(0, 0, 1, 0);
-        if (ok[u]) a[u] = x.g.unit[arc[u]];
-      }
-      emit_arcs<kUE>(x, ok, a, tc, src, arc, beam, boosted);
-    }
-    __syncthreads();
-  }
-  prof_mark(sm, kPhExpLoop);
 }
 
 // ------------------------------------------------------------------ recombination in LDS
@@ -1247,6 +1260,8 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     renew_index_if_wrapping(x);
     const float *row = ll + (long long)t * a.V;
     for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
+    for (int h = tid; h < kHubCap; h += kBlock) { sm.u.e.hub.ready[h] = 0; sm.u.e.hub.seg_next[h] = 0; }
+    if (tid == 0) { sm.next_run = kWaves; sm.done_waves = 0; sm.n_hub = 0; }
     __syncthreads();
     const int2 *Q = x.q0 + x.s.cur * c.qcap;
     int2 *NQ = x.q0 + (x.s.cur ^ 1) * c.qcap;
