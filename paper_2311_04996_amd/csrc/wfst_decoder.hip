@@ -131,7 +131,7 @@ struct DevGraph {
 struct DevChannels {
   ChanState *st;
   int4 *cand;       int cand_cap, region_cap;  // kRegions x region_cap {next, cost, source token, arc id}
-  int2 *win_sc;     int *win_ci; int win_cap;  // recombined tokens before the max-active cutoff
+  int4 *win;        int win_cap;               // recombined tokens before the max-active cutoff (their candidate records)
   int2 *queue;      int qcap;                  // 2 buffers {block number, cost}
   int4 *wl;                                    // 2 buffers {token, block number, cost, 1 = new token}
   unsigned *index;                             // [n_blk] (epoch tag << 16) | token index
@@ -274,7 +274,7 @@ struct Cutoff {
 
 struct Ctx {                  // block-uniform view of one channel
   const DevGraph &g; const DevChannels &c; Smem &sm;
-  int4 *cand; int2 *win_sc; int *win_ci;
+  int4 *cand; int4 *win;
   int2 *q0; int4 *wl0; unsigned *index; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
@@ -614,7 +614,7 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
 // Lower the destination's table entry to this candidate if (cost, arc id) is smaller.
 // The value word carries the candidate's index, so the winner's record can be fetched
 // afterwards; exact cost ties are decided by the arc ids of the two records.
-__device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int arc, int idx) {
+__device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc, int idx) {
   TableLds &t = x.sm.u.t;
   unsigned s = (hash_state(dst) >> 6) & kTabMask;
   // one compare-and-swap per probe: it returns the slot's key, or claims the slot if it was free
@@ -622,7 +622,7 @@ __device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int ar
     const int old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
     if (old == kKeyEmpty || old == dst) break;
     s = (s + 1) & kTabMask;
-    if (probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return; }   // table full
+    if (probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return -1; }   // table full
   }
   const unsigned oc = f2ord(cost);
   const unsigned long long mine = ((unsigned long long)oc << 32) | (unsigned)idx;
@@ -637,6 +637,7 @@ __device__ __forceinline__ void table_insert(Ctx &x, int dst, float cost, int ar
     if (prev == cur) break;
     cur = prev;
   }
+  return (int)s;
 }
 
 __device__ __forceinline__ void table_clear(Smem &sm) {
@@ -650,9 +651,13 @@ __device__ __forceinline__ int group_of(int dst, int G) {
 
 // One table pass over regions [r0, r1): every candidate of sub-group g (of G) that is selected
 // (inside the beam, cost bin below k_sel) is inserted.  Reads are coalesced 16-byte records.
+// The slot every candidate of the pass went to is noted in LDS (sm.occ, by the candidate's
+// position in the pass, 0xFFFF = not inserted) for the first kTabSlots positions, so that the
+// second sweep finds it without probing again.
 template <bool kSelect>
 __device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G, const Cutoff &cut, int k_sel) {
   const int tid = threadIdx.x;
+  int pos0 = 0;                               // position of the region's first candidate in this pass
   for (int r = r0; r < r1; ++r) {
     const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
     const int base = r * x.c.region_cap;
@@ -666,8 +671,67 @@ __device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G,
       const int key = key_of(cd.x);
       int take = (int)(G == 1) | (int)(group_of(key, G) == g);
       if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
-      if (take) table_insert(x, key, c, cd.w, base + i);
+      int slot = -1;
+      if (take) slot = table_insert(x, key, c, cd.w, base + i);
+      if (pos0 + i < kTabSlots) x.sm.occ[pos0 + i] = (unsigned short)slot;
     }
+    pos0 += (n + kBlock - 1) / kBlock * kBlock;
+  }
+}
+
+// Second sweep of a table pass: every candidate that was inserted looks at its slot again;
+// the one whose index is still in the value word is the recombined token of that
+// destination.  It is histogrammed and its record is appended to the winners (winners of
+// neighbouring lanes are neighbouring records, so the reads coalesce, and nobody has to scan
+// the table or fetch records by index afterwards).  Candidates beyond the noted positions
+// (more than kTabSlots in one pass) find their slot by probing again.
+template <bool kSelect>
+__device__ __forceinline__ void table_winners(Ctx &x, int r0, int r1, int g, int G, const Cutoff &cut, int k_sel) {
+  TableLds &t = x.sm.u.t;
+  const int tid = threadIdx.x;
+  constexpr int kW = 4;
+  int pos0 = 0;
+  for (int r = r0; r < r1; ++r) {
+    const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
+    const int base = r * x.c.region_cap;
+    for (int i0 = 0; i0 < n; i0 += kBlock * kW) {
+      int win[kW], wi[kW]; unsigned long long v[kW];
+#pragma unroll
+      for (int u = 0; u < kW; ++u) {
+        const int i = i0 + u * kBlock + tid;
+        int slot = -1;
+        if (i < n) {
+          if (pos0 + i < kTabSlots) {
+            const unsigned short sl = x.sm.occ[pos0 + i];
+            slot = sl == 0xFFFFu ? -1 : (int)sl;
+          } else {                                   // not noted: same test as the fill, then probe
+            const int4 cd = x.cand[base + i];
+            const float c = __int_as_float(cd.y);
+            const int key = key_of(cd.x);
+            int take = (int)(G == 1) | (int)(group_of(key, G) == g);
+            if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
+            if (take) {
+              unsigned s = (hash_state(key) >> 6) & kTabMask;
+              int probes = 0;
+              while (t.keys[s] != key && probes < kTabSlots) { s = (s + 1) & kTabMask; ++probes; }
+              if (probes < kTabSlots) slot = (int)s;
+            }
+          }
+        }
+        v[u] = slot >= 0 ? t.vals[slot] : kValEmpty;
+        win[u] = (int)(slot >= 0) & (int)((unsigned)v[u] == (unsigned)(base + i));
+        if (win[u]) atomicAdd(&x.sm.hist[cut.bin(ord2f((unsigned)(v[u] >> 32)))], 1u);
+      }
+      wave_alloc_n<kW>(&x.sm.n_win, win, wi);
+#pragma unroll
+      for (int u = 0; u < kW; ++u)
+        if (win[u]) {
+          const int i = i0 + u * kBlock + tid;
+          if (wi[u] < x.c.win_cap) x.win[wi[u]] = x.cand[base + i];
+          else atomicOr(&x.sm.status, kStCapacity);
+        }
+    }
+    pos0 += (n + kBlock - 1) / kBlock * kBlock;
   }
 }
 
@@ -818,25 +882,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       table_fill<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
       prof_mark(sm, kPhTabFill);
-      {
-        constexpr int kS = kTabSlots / kBlock;
-        int key[kS]; unsigned long long v[kS]; int win[kS]; int wi[kS];
-#pragma unroll
-        for (int k = 0; k < kS; ++k) {
-          key[k] = t.keys[k * kBlock + tid]; v[k] = t.vals[k * kBlock + tid];
-          win[k] = key[k] != kKeyEmpty;              // everything in the table is inside the beam
-          if (win[k]) atomicAdd(&sm.hist[cut.bin(ord2f((unsigned)(v[k] >> 32)))], 1u);
-        }
-        wave_alloc_n<kS>(&sm.n_win, win, wi);
-#pragma unroll
-        for (int k = 0; k < kS; ++k)
-          if (win[k]) {
-            if (wi[k] < x.c.win_cap) {
-              x.win_sc[wi[k]] = make_int2(key[k], (int)__float_as_uint(ord2f((unsigned)(v[k] >> 32))));
-              x.win_ci[wi[k]] = (int)(unsigned)v[k];
-            } else atomicOr(&sm.status, kStCapacity);
-          }
-      }
+      table_winners<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
       prof_mark(sm, kPhTabScan);
     }
@@ -887,18 +933,12 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   const unsigned tag16 = set_tag(x.s.epoch) << 16;
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kUC) {
-    int2 sc[kUC]; int ci[kUC]; int kp[kUC]; int4 cr[kUC];
+    int kp[kUC]; int4 cr[kUC];
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
       const int i = i0 + u * kBlock + tid;
-      sc[u] = make_int2(0, 0); ci[u] = 0;
-      if (i < n_win) { sc[u] = x.win_sc[i]; ci[u] = x.win_ci[i]; }
-      kp[u] = (int)(i < n_win) & (int)(cut.bin(__int_as_float(sc[u].y)) < cut.k_keep);
-    }
-#pragma unroll
-    for (int u = 0; u < kUC; ++u) {
-      cr[u] = make_int4(0, 0, 0, 0);
-      if (kp[u]) cr[u] = x.cand[ci[u]];
+      cr[u] = x.win[min(i, n_win - 1)];
+      kp[u] = (int)(i < n_win) & (int)(cut.bin(__int_as_float(cr[u].y)) < cut.k_keep);
     }
     int ti[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; int good[kUC], no[kUC];
     wave_alloc_n<kUC>(&sm.n_next, kp, ti);
@@ -909,7 +949,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
         if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
         else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
       }
-      st[u] = cr[u].x; cb[u] = sc[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
+      st[u] = cr[u].x; cb[u] = cr[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
     }
     make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN, tag16);
   }
@@ -1203,8 +1243,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   const int ch = uni(a.chan[blockIdx.x]), nfr = uni(a.nfr[blockIdx.x]), io = uni(a.io[blockIdx.x]);
   Ctx x{g, c, sm};
   x.cand = c.cand + (size_t)ch * c.cand_cap;
-  x.win_sc = c.win_sc + (size_t)ch * c.win_cap;
-  x.win_ci = c.win_ci + (size_t)ch * c.win_cap;
+  x.win = c.win + (size_t)ch * c.win_cap;
   x.q0 = c.queue + (size_t)ch * 2 * c.qcap;
   x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
   x.index = c.index + (size_t)ch * g.n_blk;
@@ -1288,7 +1327,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     // copies, so that the pointers of the frame loop above never live in memory: only then
     // does the compiler know they are global and keep them in registers.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
-    Ctx x2{g2, c2, sm, x.cand, x.win_sc, x.win_ci, x.q0, x.wl0, x.index, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
+    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.index, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
     select_and_trace(x2, a2, io);
   }
   prof_mark(sm, kPhTrace);
@@ -1457,8 +1496,7 @@ int alloc_channels(wfst_decoder *d) {
   int rc;
   if ((rc = dev_alloc(d, &c.st, N))) return rc;
   if ((rc = dev_alloc(d, &c.cand, N * (size_t)c.cand_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.win_sc, N * c.win_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.win_ci, N * c.win_cap))) return rc;
+  if ((rc = dev_alloc(d, &c.win, N * c.win_cap))) return rc;
   if ((rc = dev_alloc(d, &c.index, N * (size_t)d->g.n_blk))) return rc;
   if ((rc = dev_alloc(d, &c.queue, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
