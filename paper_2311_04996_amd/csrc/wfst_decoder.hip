@@ -679,6 +679,27 @@ __device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G,
   }
 }
 
+// Slot that candidate `idx` (position `pos` of the pass) was inserted into, or -1.  Positions
+// beyond the noted ones repeat the fill's test and probe for the key.
+template <bool kSelect>
+__device__ __forceinline__ int slot_of_candidate(Ctx &x, int pos, int idx, int g, int G, const Cutoff &cut, int k_sel) {
+  TableLds &t = x.sm.u.t;
+  if (pos < kTabSlots) {
+    const unsigned short sl = x.sm.occ[pos];
+    return sl == 0xFFFFu ? -1 : (int)sl;
+  }
+  const int4 cd = x.cand[idx];
+  const float c = __int_as_float(cd.y);
+  const int key = key_of(cd.x);
+  int take = (int)(G == 1) | (int)(group_of(key, G) == g);
+  if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
+  if (!take) return -1;
+  unsigned s = (hash_state(key) >> 6) & kTabMask;
+  int probes = 0;
+  while (t.keys[s] != key && probes < kTabSlots) { s = (s + 1) & kTabMask; ++probes; }
+  return probes < kTabSlots ? (int)s : -1;
+}
+
 // Second sweep of a table pass: every candidate that was inserted looks at its slot again;
 // the one whose index is still in the value word is the recombined token of that
 // destination.  It is histogrammed and its record is appended to the winners (winners of
@@ -700,24 +721,7 @@ __device__ __forceinline__ void table_winners(Ctx &x, int r0, int r1, int g, int
       for (int u = 0; u < kW; ++u) {
         const int i = i0 + u * kBlock + tid;
         int slot = -1;
-        if (i < n) {
-          if (pos0 + i < kTabSlots) {
-            const unsigned short sl = x.sm.occ[pos0 + i];
-            slot = sl == 0xFFFFu ? -1 : (int)sl;
-          } else {                                   // not noted: same test as the fill, then probe
-            const int4 cd = x.cand[base + i];
-            const float c = __int_as_float(cd.y);
-            const int key = key_of(cd.x);
-            int take = (int)(G == 1) | (int)(group_of(key, G) == g);
-            if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
-            if (take) {
-              unsigned s = (hash_state(key) >> 6) & kTabMask;
-              int probes = 0;
-              while (t.keys[s] != key && probes < kTabSlots) { s = (s + 1) & kTabMask; ++probes; }
-              if (probes < kTabSlots) slot = (int)s;
-            }
-          }
-        }
+        if (i < n) slot = slot_of_candidate<kSelect>(x, pos0 + i, base + i, g, G, cut, k_sel);
         v[u] = slot >= 0 ? t.vals[slot] : kValEmpty;
         win[u] = (int)(slot >= 0) & (int)((unsigned)v[u] == (unsigned)(base + i));
         if (win[u]) atomicAdd(&x.sm.hist[cut.bin(ord2f((unsigned)(v[u] >> 32)))], 1u);
@@ -1045,64 +1049,57 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       table_fill<false>(x, r0, r1, g, G, cut, 256);
       __syncthreads();
       prof_mark(sm, kPhEpsTabFill);
-      // occupied slots, compacted, so that the dependent global reads below run on full waves
-      {
-        constexpr int kS = kTabSlots / kBlock;
-        int oc[kS]; int oi[kS];
+      // the winners of the pass apply themselves: per destination, the winning candidate is
+      // compared with the state's existing token, found through the state index
+      int pos0 = 0;
+      for (int r = r0; r < r1; ++r) {
+        const int n = uni(min(sm.n_reg[r], x.c.region_cap));
+        const int base = r * x.c.region_cap;
+        for (int i0 = 0; i0 < n; i0 += kBlock * kU) {
+          int4 rec[kU]; unsigned ix[kU]; int tok[kU];
+          float oc[kU]; unsigned oa[kU]; int occ[kU], exists[kU];
 #pragma unroll
-        for (int k = 0; k < kS; ++k) oc[k] = t.keys[k * kBlock + tid] != kKeyEmpty;
-        wave_alloc_n<kS>(&sm.n_occ, oc, oi);
-#pragma unroll
-        for (int k = 0; k < kS; ++k) if (oc[k]) sm.occ[oi[k]] = (unsigned short)(k * kBlock + tid);
-      }
-      __syncthreads();
-      const int n_occ = uni(sm.n_occ);
-      // per destination: winning candidate, state index, state record -> existing token
-      for (int i0 = 0; i0 < n_occ; i0 += kBlock * kU) {
-        int d[kU]; int4 rec[kU]; unsigned ix[kU]; int tok[kU];
-        float oc[kU]; unsigned oa[kU]; int occ[kU], exists[kU]; unsigned ci[kU];
-#pragma unroll
-        for (int k = 0; k < kU; ++k) {
-          const int i = i0 + k * kBlock + tid;
-          occ[k] = i < n_occ;
-          const int sl = occ[k] ? sm.occ[i] : 0;
-          d[k] = t.keys[sl]; ci[k] = (unsigned)t.vals[sl];
-        }
-#pragma unroll
-        for (int k = 0; k < kU; ++k) {
-          rec[k] = make_int4(0, 0, 0, 0); ix[k] = 0;
-          if (occ[k]) { rec[k] = x.cand[ci[k]]; ix[k] = x.index[d[k]]; }
-        }
-#pragma unroll
-        for (int k = 0; k < kU; ++k) {
-          exists[k] = occ[k] & (int)((ix[k] >> 16) == tag);
-          tok[k] = (int)(ix[k] & 0xffffu);
-          oc[k] = 0.0f; oa[k] = 0;
-          if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
-        }
-        int fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
-#pragma unroll
-        for (int k = 0; k < kU; ++k) {
-          const float nc = __int_as_float(rec[k].y);
-          improve[k] = exists[k] & ((int)(nc < oc[k]) | ((int)(nc == oc[k]) & (int)((unsigned)rec[k].w < oa[k])));
-          fresh[k] = occ[k] & (int)!exists[k];
-        }
-        wave_alloc_n<kU>(&sm.n_next, fresh, ni);
-#pragma unroll
-        for (int k = 0; k < kU; ++k) {
-          good[k] = fresh[k];
-          if (fresh[k]) {
-            if (ni[k] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[k] = false; }
-            else if (lat_base + (unsigned)ni[k] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[k] = false; }
+          for (int k = 0; k < kU; ++k) {
+            const int i = i0 + k * kBlock + tid;
+            int slot = -1;
+            if (i < n) slot = slot_of_candidate<false>(x, pos0 + i, base + i, g, G, cut, 256);
+            occ[k] = (int)(slot >= 0);
+            if (occ[k]) occ[k] = (int)((unsigned)t.vals[slot] == (unsigned)(base + i));
+            rec[k] = make_int4(0, 0, 0, 0); ix[k] = 0;
+            if (occ[k]) { rec[k] = x.cand[base + i]; ix[k] = x.index[t.keys[slot]]; }
           }
-          // an existing token that got better: new cost and backpointer in place, expand again
-          if (improve[k]) {
-            NQ[tok[k]].y = rec[k].y;
-            x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
+#pragma unroll
+          for (int k = 0; k < kU; ++k) {
+            exists[k] = occ[k] & (int)((ix[k] >> 16) == tag);
+            tok[k] = (int)(ix[k] & 0xffffu);
+            oc[k] = 0.0f; oa[k] = 0;
+            if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
           }
-          cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w; nx[k] = rec[k].x;
+          int fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
+#pragma unroll
+          for (int k = 0; k < kU; ++k) {
+            const float nc = __int_as_float(rec[k].y);
+            improve[k] = exists[k] & ((int)(nc < oc[k]) | ((int)(nc == oc[k]) & (int)((unsigned)rec[k].w < oa[k])));
+            fresh[k] = occ[k] & (int)!exists[k];
+          }
+          wave_alloc_n<kU>(&sm.n_next, fresh, ni);
+#pragma unroll
+          for (int k = 0; k < kU; ++k) {
+            good[k] = fresh[k];
+            if (fresh[k]) {
+              if (ni[k] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[k] = false; }
+              else if (lat_base + (unsigned)ni[k] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[k] = false; }
+            }
+            // an existing token that got better: new cost and backpointer in place, expand again
+            if (improve[k]) {
+              NQ[tok[k]].y = rec[k].y;
+              x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
+            }
+            cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w; nx[k] = rec[k].x;
+          }
+          make_tokens<kU>(x, good, ni, nx, cb, pv, ar, improve, tok, NQ, lat_base, WLN, tag << 16);
         }
-        make_tokens<kU>(x, good, ni, nx, cb, pv, ar, improve, tok, NQ, lat_base, WLN, tag << 16);
+        pos0 += (n + kBlock - 1) / kBlock * kBlock;
       }
       __syncthreads();
       prof_mark(sm, kPhEpsTabScan);
