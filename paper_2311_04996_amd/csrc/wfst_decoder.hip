@@ -150,11 +150,11 @@ struct LaunchArgs {
   int *words, *nwords; float *cost; int *flags; int max_words;
 };
 
-struct ChunkLds {             // one chunk of work items, flattened over their arcs
-  unsigned pre[kChunk + 1];   // exclusive prefix sums of the items' arc counts
-  int abase[kChunk];          // unit address of the item's first arc minus its prefix
-  float tcost[kChunk];        // cost of the item's token
-  int ttok[kChunk];           // the item's token (epsilon expansion only)
+struct EpsLds {               // epsilon expansion: one worklist item per thread, flattened over their arcs
+  unsigned pre[kBlock + 1];   // exclusive prefix sums of the items' arc counts
+  int abase[kBlock];          // unit address of the item's first arc minus its prefix
+  float tcost[kBlock];        // cost of the item's token
+  int ttok[kBlock];           // the item's token
 };
 struct WaveLds {              // ExpandArcs: the work items of one wave (2 tokens per lane)
   unsigned pre[kWaveTok + 1];
@@ -171,7 +171,6 @@ struct HubLds {               // ExpandArcs: states with so many arcs that all w
 };
 struct ExpandLds {            // live while arcs are being expanded
   float ac[kMaxV];
-  ChunkLds ch[2];             // epsilon expansion; double-buffered: a wave may start the next chunk while others finish this one
   WaveLds w[kWaves];
   HubLds hub;
 };
@@ -181,6 +180,7 @@ struct TableLds {             // live while candidates are being recombined
 };
 struct Smem {
   union { ExpandLds e; TableLds t; } u;
+  EpsLds ek;                  // beside the table: a small round's candidates go into it while they are made
   unsigned hist[256];
   unsigned wave_tot[kWaves];
   unsigned best_ord;
@@ -973,7 +973,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
 // On entry WL0 = x.wl0 + sel*qcap holds n_wl entries.
 __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
   Smem &sm = x.sm;
-  ExpandLds &e = sm.u.e;
+  EpsLds &ek = sm.ek;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
   const unsigned tag = set_tag(x.s.epoch);
@@ -985,42 +985,38 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
   for (int round = 0; n_wl > 0; ++round) {
     if (round > (1 << 20)) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
     const int4 *WL = x.wl0 + sel * x.c.qcap; int4 *WLN = x.wl0 + (sel ^ 1) * x.c.qcap;
-    for (int cb = 0, par = 0; cb < n_wl; cb += kChunk, par ^= 1) {
-      ChunkLds &ck = e.ch[par];
-      unsigned deg[kTPT], ex[kTPT]; int4 w[kTPT]; unsigned xsum = 0;
-#pragma unroll
-      for (int k = 0; k < kTPT; ++k) {
-        const int i = cb + kTPT * tid + k;
-        w[k] = make_int4(0, 0, 0, 0);
-        if (i < n_wl) w[k] = WL[i];
+    // A round whose items fit one chunk and whose arcs fit one table is "fused": the table is
+    // cleared up front and every candidate is inserted by the lane that made it, so the
+    // candidates are not read back before the winners are known.
+    bool fused = false;
+    for (int cb = 0; cb < n_wl; cb += kBlock) {
+      const int n_items = min(kBlock, n_wl - cb);
+      unsigned deg[1], ex[1];
+      int4 w = make_int4(0, 0, 0, 0);
+      if (tid < n_items) w = WL[cb + tid];
+      deg[0] = tid < n_items ? (unsigned)x.g.unit[2 * (size_t)(unsigned)w.y].y : 0u;   // the state's header
+      if (n_wl <= kBlock) table_clear(sm);         // while the loads are in flight
+      {
+        // epsilon arcs out of the set (a counter): every token is listed as new exactly once
+        const unsigned xsum = wave_sum(w.w ? deg[0] : 0u);
+        if ((tid & 63) == 0 && xsum) atomicAdd((unsigned long long *)&sm.ctr[kCtXarc], (unsigned long long)xsum);
       }
-#pragma unroll
-      for (int k = 0; k < kTPT; ++k) {
-        const int i = cb + kTPT * tid + k;
-        deg[k] = i < n_wl ? (unsigned)x.g.unit[2 * (size_t)(unsigned)w[k].y].y : 0u;   // the state's header
-        if (w[k].w) xsum += deg[k];
-      }
-      // epsilon arcs out of the set (a counter): every token is listed as new exactly once
-      xsum = wave_sum(xsum);
-      if ((tid & 63) == 0 && xsum) atomicAdd((unsigned long long *)&sm.ctr[kCtXarc], (unsigned long long)xsum);
-      const unsigned M = block_scan<kTPT>(sm, deg, ex);
-#pragma unroll
-      for (int k = 0; k < kTPT; ++k) {
-        ck.pre[kTPT * tid + k] = ex[k];
-        ck.abase[kTPT * tid + k] = 2 * w[k].y + 1 - (int)ex[k];
-        ck.tcost[kTPT * tid + k] = __int_as_float(w[k].z);       // the token's cost when it was listed
-        ck.ttok[kTPT * tid + k] = w[k].x;
-      }
-      if (tid == kBlock - 1) ck.pre[kChunk] = M;
+      const unsigned M = block_scan<1>(sm, deg, ex);
+      ek.pre[tid] = ex[0];
+      ek.abase[tid] = 2 * w.y + 1 - (int)ex[0];
+      ek.tcost[tid] = __int_as_float(w.z);         // the token's cost when it was listed
+      ek.ttok[tid] = w.x;
+      if (tid == kBlock - 1) ek.pre[kBlock] = M;
+      fused = n_wl <= kBlock && M <= (unsigned)min(kGroupTarget, x.c.region_cap);
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
         int ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
-        owners_of<kU>(ck.pre, kChunk, f0, M, ok, j);
+        owners_of<kU>(ek.pre, n_items, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-          arc[u] = ck.abase[j[u]] + (int)(f0 + u * kBlock + tid);
-          src[u] = ck.ttok[j[u]];
-          tc[u] = ck.tcost[j[u]];
+          arc[u] = ek.abase[j[u]] + (int)(f0 + u * kBlock + tid);
+          src[u] = ek.ttok[j[u]];
+          tc[u] = ek.tcost[j[u]];
           a[u] = make_int4(0, 0, 0, 0);
           if (ok[u]) a[u] = x.g.unit[arc[u]];
         }
@@ -1032,22 +1028,36 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
           ok[u] &= (int)(nc[u] < INFINITY) & (int)cut.keep(nc[u]);
           next[u] = a[u].x; arc[u] |= (int)kArcEps;
         }
-        push_cands<kU>(x, ok, next, nc, src, arc);
+        if (fused) {
+          // all into region 0 (at most kGroupTarget <= region_cap records), and into the table
+          int ci[kU];
+          wave_alloc_n<kU>(&sm.n_reg[0], ok, ci);
+#pragma unroll
+          for (int u = 0; u < kU; ++u)
+            if (ok[u]) {
+              x.cand[ci[u]] = make_int4(next[u], __float_as_int(nc[u]), src[u], arc[u]);
+              sm.occ[ci[u]] = (unsigned short)table_insert(x, key_of(next[u]), nc[u], arc[u], ci[u]);
+            }
+        } else {
+          push_cands<kU>(x, ok, next, nc, src, arc);
+        }
       }
+      __syncthreads();                             // also keeps ek for this chunk's readers before the next chunk rewrites it
     }
-    __syncthreads();
     prof_mark(sm, kPhEpsExpand);
     const int n_cand = total_candidates(x);
     PassPlan plan;
     plan.make(x, n_cand, n_cand);
+    if (fused) { plan.n_pass = 1; plan.whole = true; }
     for (int ps = 0; ps < plan.n_pass && n_cand > 0; ++ps) {
       int r0, r1, g, G;
       plan.get(ps, r0, r1, g, G);
-      table_clear(sm);
-      if (tid == 0) sm.n_occ = 0;
-      __syncthreads();
-      table_fill<false>(x, r0, r1, g, G, cut, 256);
-      __syncthreads();
+      if (!fused) {
+        table_clear(sm);
+        __syncthreads();
+        table_fill<false>(x, r0, r1, g, G, cut, 256);
+        __syncthreads();
+      }
       prof_mark(sm, kPhEpsTabFill);
       // the winners of the pass apply themselves: per destination, the winning candidate is
       // compared with the state's existing token, found through the state index
