@@ -196,8 +196,8 @@ def main():
     ticks[15] = 0                                   # slot 15 is a count, not a time
     # the timed region proper: `pipeline` batches in flight
     wall = run_steps(len(decs), args.steps, False)[0] if len(decs) > 1 else wall_one
-    names = ["expand", "select", "cutoff+tokens", "eps_expand", "eps_other", "publish", "trace", "other",
-             "tab_clear", "tab_fill", "tab_scan", "eps_tab_fill", "eps_tab_scan", "exp_setup", "exp_loop", "-"]
+    names = ["expand_tail", "select", "tokens", "eps_expand", "eps_round_end", "publish", "trace", "other",
+             "tab_clear", "tab_fill", "tab_winners", "eps_table", "eps_apply", "expand_arcs", "-", "-"]
     print("[bench] phase share of workgroup time (one batch in flight): " +
           ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks) if t) +
           f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / args.steps:.1f} ms",
