@@ -827,19 +827,23 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   const int n_cand = total_candidates(x);
   const unsigned ma = (unsigned)x.s.max_active;
 
-  // ---- 1. select
+  // ---- 1. select, from a sample: the first half of every 4 * kBlock candidates (the order
+  // of the candidates has nothing to do with their costs)
+  int n_sampled = 0;
   for (int r = 0; r < kRegions; ++r) {
     const int n = uni(min(sm.n_reg[r], x.c.region_cap));
     const int4 *cr = x.cand + r * x.c.region_cap;
-    for (int i0 = 0; i0 < n; i0 += kBlock * kUC) {
-      int cb[kUC];
+    constexpr int kHalf = 2;
+    for (int i0 = 0; i0 < n; i0 += kBlock * 2 * kHalf) {
+      int cb[kHalf];
 #pragma unroll
-      for (int u = 0; u < kUC; ++u) { const int i = i0 + u * kBlock + tid; cb[u] = i < n ? cr[i].y : 0; }
+      for (int u = 0; u < kHalf; ++u) { const int i = i0 + u * kBlock + tid; cb[u] = i < n ? cr[i].y : 0; }
 #pragma unroll
-      for (int u = 0; u < kUC; ++u) {
+      for (int u = 0; u < kHalf; ++u) {
         const float c = __int_as_float(cb[u]);
         if (i0 + u * kBlock + tid < n && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
       }
+      n_sampled += min(n - i0, kBlock * kHalf);
     }
   }
   __syncthreads();
@@ -848,9 +852,11 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     unsigned s = h0 + h1 + h2 + h3, inc = s;
     inc = wave_scan_add(inc);
     const unsigned n_in = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
-    const float want = (float)ma * x.s.sel_ratio + 256.0f;
+    // the histogram holds n_sampled of the n_cand candidates: scale the target down, the count up
+    const float frac = (float)n_sampled / (float)max(1, n_cand);
+    const float want = ((float)ma * x.s.sel_ratio + 256.0f) * frac;
     const unsigned target = want < 2.0e9f ? (unsigned)want : 2000000000u;
-    int ks = 256; unsigned nsel = n_in;
+    int ks = 256; unsigned nsel = (unsigned)n_cand;
     if (n_in > target) {
       unsigned run = inc - s;
       int first = 256; unsigned at = 0;
@@ -862,7 +868,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
 #pragma unroll
       for (int sft = 32; sft > 0; sft >>= 1) fm = min(fm, __shfl_xor(fm, sft, 64));
       const unsigned long long own = __ballot(first == fm && fm != 256);
-      nsel = __shfl(at, __ffsll((long long)own) - 1, 64);
+      nsel = (unsigned)((float)__shfl(at, __ffsll((long long)own) - 1, 64) / frac);
       ks = fm + 1;                                   // bins [0, ks) are selected
     }
     if (tid == 0) { sm.k_sel = ks; sm.n_sel = (int)nsel; }
