@@ -19,8 +19,10 @@
 // answers "does this state already have a token" for the epsilon closure.
 //
 // The graph is stored as one array of 16-byte units, a block per state: a header
-// {emitting degree, epsilon degree, state id, final cost}, then the state's epsilon arcs, then
-// its emitting arcs, every arc {next, weight, ilabel, olabel}, padded to 32 bytes.  A state is
+// {state id, final cost, emitting degree, both degrees packed in one word}, then the state's
+// epsilon arcs, then its emitting arcs, every arc {next, weight, ilabel, olabel}, padded to 32
+// bytes.  The packed word sits right before the first arc, so ONE 16-byte load at byte 12 of a
+// block brings the degrees and next/weight/ilabel of the first arc.  A state is
 // named by its block number (byte offset / 32), which is also the recombination key and grows
 // with the state id.  `next` of an arc is the destination's block number plus two flag bits
 // (the destination has epsilon arcs / an epsilon arc enters it), so a token is created from
@@ -104,6 +106,9 @@ constexpr unsigned kFlagHasEps = 0x80000000u;  // `next` of an arc: the destinat
 constexpr unsigned kFlagEpsIn = 0x40000000u;   //                   an epsilon arc enters the destination
 constexpr unsigned kArcEps = 0x40000000u;      // arc ids: unit address, plus this bit for epsilon arcs
 constexpr unsigned kArcMask = 0x3fffffffu;
+constexpr unsigned kPackE = 0xFFFFFu;          // header word 3: emitting degree (20 bits, all ones = see word 2)
+constexpr int kPackXShift = 20;                //                epsilon degree (12 bits)
+constexpr int kMaxEpsDeg = 4094;
 constexpr int kStLattice = WFST_FLAG_LATTICE_OVERFLOW, kStCapacity = WFST_FLAG_CAPACITY;
 
 struct ChanState {            // persists between calls (the per-stream decoder state)
@@ -120,7 +125,7 @@ struct ChanState {            // persists between calls (the per-stream decoder 
 };
 
 struct DevGraph {
-  const int4 *unit;           // state blocks: header {emitting degree, epsilon degree, state id, final cost},
+  const int4 *unit;           // state blocks: header {state id, final cost, emitting degree, packed degrees},
                               // epsilon arcs, emitting arcs {next, weight bits, ilabel, olabel}
   unsigned n_blk;             // 32-byte blocks in `unit` (the state index has one entry per block)
   unsigned start;             // start state: block number + flags, like `next` of an arc
@@ -226,6 +231,15 @@ __device__ __forceinline__ float boost_of(const Smem &sm, int word);
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+
+// 16 bytes at byte 12 of a state block: {packed degrees, first unit's next, weight, ilabel}
+// (4-byte aligned; one global_load_dwordx4).
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef v4i_t __attribute__((aligned(4))) v4i_unaligned_t;
+__device__ __forceinline__ int4 load_block_head(const int4 *unit, int key) {
+  const v4i_t q = *reinterpret_cast<const v4i_unaligned_t *>(reinterpret_cast<const char *>(unit + 2 * (size_t)(unsigned)key) + 12);
+  return make_int4(q.x, q.y, q.z, q.w);
+}
 
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive adds: four
 // shifts inside each row of 16 lanes, then the last lane of row 0 (2) onto row 1 (3) and lane
@@ -522,22 +536,25 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   WaveLds &wl = e.w[wave];
   const int R = (n_tok + kWaveTok - 1) / kWaveTok;
   int r = wave, rn = next_run(sm);
-  int2 tk = make_int2(0, 0), tkn = make_int2(0, 0); int4 hd = make_int4(0, 0, 0, 0), fu = make_int4(0, 0, 1, 0);
+  const int4 kNoHead = make_int4(0, 0, 0, 1);          // no arcs; ilabel 1 keeps the acoustic lookup in range
+  int2 tk = make_int2(0, 0), tkn = make_int2(0, 0); int4 hd = kNoHead;
   if (r * kWaveTok + lane < n_tok) tk = Q[r * kWaveTok + lane];
   if (rn < R && rn * kWaveTok + lane < n_tok) tkn = Q[rn * kWaveTok + lane];
-  if (r * kWaveTok + lane < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk.x; hd = b[0]; fu = b[1]; }
+  if (r * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, tk.x);
   unsigned long long n_arcs = 0;                       // wave-uniform: emitting arcs this wave expanded
   while (r < R) {
     const int base = r * kWaveTok;
     unsigned deg; int first;
     {
       int has[1], src[1], arc[1]; float tc[1]; int4 a0[1];
-      const int ne = hd.x, nx = hd.y;
+      int ne = (int)((unsigned)hd.x & kPackE); const int nx = (int)((unsigned)hd.x >> kPackXShift);
+      if (ne == (int)kPackE) ne = x.g.unit[2 * (size_t)(unsigned)tk.x].z;       // a very large state: exact degree
       has[0] = (int)(ne > 0) & (int)(nx == 0);          // the unit after the header is an emitting arc
       deg = (unsigned)(ne - has[0]);
       first = 2 * tk.x + 1 + nx + has[0];               // unit address of the first arc left
       tc[0] = __int_as_float(tk.y); src[0] = base + lane; arc[0] = 2 * tk.x + 1;
-      a0[0] = has[0] ? fu : make_int4(0, 0, 1, 0);
+      a0[0] = make_int4(hd.y, hd.z, has[0] ? hd.w : 1, 0);
+      if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)tk.x + 1].w;   // the first arc's olabel
       n_arcs += (unsigned)__popcll(__ballot(has[0]));
       if (deg > (unsigned)kHubDeg) {                    // to the shared list, if it has room
         const int h = atomicAdd(&sm.n_hub, 1);
@@ -562,8 +579,8 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
     // the next run's header and the token of the run after it
     const int rnn = next_run(sm);
     tk = tkn;
-    hd = make_int4(0, 0, 0, 0); fu = make_int4(0, 0, 1, 0);
-    if (rn < R && rn * kWaveTok + lane < n_tok) { const int4 *b = x.g.unit + 2 * (size_t)(unsigned)tk.x; hd = b[0]; fu = b[1]; }
+    hd = kNoHead;
+    if (rn < R && rn * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, tk.x);
     tkn = make_int2(0, 0);
     if (rnn < R && rnn * kWaveTok + lane < n_tok) tkn = Q[rnn * kWaveTok + lane];
     // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
@@ -1000,7 +1017,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       unsigned deg[1], ex[1];
       int4 w = make_int4(0, 0, 0, 0);
       if (tid < n_items) w = WL[cb + tid];
-      deg[0] = tid < n_items ? (unsigned)x.g.unit[2 * (size_t)(unsigned)w.y].y : 0u;   // the state's header
+      deg[0] = tid < n_items ? (unsigned)x.g.unit[2 * (size_t)(unsigned)w.y].w >> kPackXShift : 0u;   // the state's header
       if (n_wl <= kBlock) table_clear(sm);         // while the loads are in flight
       {
         // epsilon arcs out of the set (a counter): every token is listed as new exactly once
@@ -1144,7 +1161,7 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
     unsigned long long s = 0;
     for (int i = tid; i < n; i += kBlock) {
       const int2 sc = NQ[i];
-      const int state = x.g.unit[2 * (size_t)(unsigned)sc.x].z;     // the header names the state
+      const int state = x.g.unit[2 * (size_t)(unsigned)sc.x].x;     // the header names the state
       s += mix64(((unsigned long long)(unsigned)state << 32) | (unsigned)sc.y);
     }
     if (s) atomicAdd(&sm.red64, s);
@@ -1202,7 +1219,7 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     const float c = __int_as_float(t.y);
     mr = min(mr, ((unsigned long long)f2ord(c) << 32) | (unsigned)t.x);
     if (a.finalize) {
-      const float fc = x.g.has_final ? __int_as_float(x.g.unit[2 * (size_t)(unsigned)t.x].w) : 0.0f;
+      const float fc = x.g.has_final ? __int_as_float(x.g.unit[2 * (size_t)(unsigned)t.x].y) : 0.0f;
       const float f = c + fc;
       if (f < INFINITY) mf = min(mf, ((unsigned long long)f2ord(f) << 32) | (unsigned)t.x);
     }
@@ -1472,7 +1489,9 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
     all_zero = all_zero && fc == 0.0f;
     int fbits; std::memcpy(&fbits, &fc, 4);
     int4 *b = unit.data() + 2 * (size_t)blk[s];
-    b[0] = make_int4(ne, nx, s, fbits);
+    if (nx > kMaxEpsDeg) return fail(d, WFST_ERR_BAD_GRAPH, "state " + std::to_string(s) + " has more than " + std::to_string(kMaxEpsDeg) + " epsilon arcs");
+    const unsigned packed = std::min<unsigned>((unsigned)ne, kPackE) | ((unsigned)nx << kPackXShift);
+    b[0] = make_int4(s, fbits, ne, (int)packed);
     int4 *xa = b + 1, *ea = b + 1 + nx;
     for (int64_t i = r0; i < r1; ++i) {
       int wbits; std::memcpy(&wbits, &g->weight[i], 4);
