@@ -70,6 +70,43 @@ def cpu_baseline(w, threads, budget_s=15.0):
             "sample": f"first {len(take)} utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall"}
 
 
+def pick_concurrent_streams(torch, n):
+    """n streams whose kernels the runtime really runs side by side.  HIP maps streams onto a few
+    hardware queues; two streams that share one run their kernels one after the other, and which
+    streams share is not visible from the API.  So a short spin kernel is timed alone and on pairs
+    of candidate streams; a pair that takes about as long as one kernel is concurrent."""
+    if n <= 1:
+        return [torch.cuda.Stream() for _ in range(n)]
+    cands = [torch.cuda.Stream() for _ in range(8)]
+    cycles = 20_000_000                                       # roughly 10 ms
+
+    def timed(streams):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for st in streams:
+            with torch.cuda.stream(st):
+                torch.cuda._sleep(cycles)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    timed(cands)                                              # first use creates the queues
+    one = min(timed([cands[0]]) for _ in range(2))
+    chosen = [cands[0]]
+    for st in cands[1:]:
+        if len(chosen) == n:
+            break
+        if all(min(timed([c, st]) for _ in range(2)) < 1.5 * one for c in chosen):
+            chosen.append(st)
+    ok = len(chosen) == n
+    picked = [cands.index(c) for c in chosen]
+    while len(chosen) < n:                                    # none found: take what there is
+        chosen.append(cands[len(chosen)])
+    print(f"[bench] streams: spin kernel {one * 1e3:.1f} ms alone; "
+          f"{'found' if ok else 'did NOT find'} {n} streams that run concurrently (candidates {picked} of 8)",
+          file=sys.stderr, flush=True)
+    return chosen
+
+
 def main_streaming(args):
     """Streaming configuration: the c3_large graph, `channels` concurrent audio streams fed
     16-frame (640 ms) chunks with wfst_advance_chunk, partial hypotheses of every channel
@@ -158,7 +195,7 @@ def main():
     t0 = time.perf_counter()
     decs = [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active)
             for _ in range(max(1, args.pipeline))]
-    streams = [torch.cuda.Stream() for _ in decs]
+    streams = pick_concurrent_streams(torch, len(decs))
     dec = decs[0]
     ll = torch.from_numpy(w.loglikes).cuda()
     outs = [None] * len(decs)
