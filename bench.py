@@ -112,6 +112,7 @@ def main_streaming(args):
     16-frame (640 ms) chunks with wfst_advance_chunk, partial hypotheses of every channel
     fetched after every chunk.  One JSON line: per-chunk latency and channels sustainable
     at real time."""
+    from paper_2311_04996_amd.latency_model import load_table
     import torch
     from paper_2311_04996_amd import Decoder
     from workloads import CONFIGS, ctc_loglikes
@@ -154,7 +155,10 @@ def main_streaming(args):
             "rtfx": n * chunk_s / (float(lat.mean()) * 1e-3),
             "channels_at_realtime_p99": int(n * chunk_s * 1e3 / p99),
             "channels_at_realtime_p50": int(n * chunk_s * 1e3 / p50),
-            "mean_words_per_partial": float(out[1].mean())}
+            "mean_words_per_partial": float(out[1].mean()),
+            # the paper's M/D/1 model (Section "Streaming inference") applied to the measured
+            # compute latency: mean queue and total latency of a chunk request against load
+            "latency_model": load_table(float(lat.mean()) * 1e-3, chunk_s, n)}
     dec.close()
     print(json.dumps(line), flush=True)
 
