@@ -11,12 +11,22 @@
 // Recombination (one token per destination state, lowest (cost, arc id) wins) uses NO global
 // atomics: measured on MI355X, 64-bit global atomics top out near 25 G/s for the whole chip,
 // which bounded an earlier global-hash design.  Instead ExpandArcs appends candidates
-// {dst, cost, source token, arc} to a flat buffer (wave-aggregated, so the stores coalesce);
-// a histogram of the candidate costs selects the few that can survive max-active, and those
-// are reduced in an open-addressing table that lives in LDS (160 KB per CU on gfx950) with
-// LDS compare-and-swap, in as many passes (by hash range of the destination) as the table
-// needs.  A dense per-state index (tagged with the frame epoch, so it never needs clearing)
-// answers "does this state already have a token" for the epsilon closure.
+// {next, cost, source token, arc} to a buffer in four regions (by hash of the destination;
+// wave-aggregated, so the stores coalesce); a histogram of a sample of the candidate costs
+// selects the few that can survive max-active, and those are reduced in an open-addressing
+// table that lives in LDS (160 KB per CU on gfx950) with LDS compare-and-swap, in as many
+// passes (a region, or a hash range of it) as the table needs.  After a pass every inserted
+// candidate looks at its slot again: the one still there is the recombined token of its
+// destination ("winner") and carries its own record on; nobody scans the table.  A dense
+// index by state block (tagged with the frame epoch, so it never needs clearing) answers
+// "does this state already have a token" for the epsilon closure.
+//
+// ExpandArcs has no block-wide barrier: every wave takes runs of 64 tokens from a counter in
+// LDS and expands them on its own (first arc by the owning lane, the other arcs flattened
+// over the wave, very large states shared segment by segment), so the waves drift apart and
+// one wave's memory waits overlap another's arithmetic.  The hot loops are bound by
+// instruction issue (4 waves per SIMD, 4 cycles per wave64 instruction): they are written
+// branch-free where it matters.
 //
 // The graph is stored as one array of 16-byte units, a block per state: a header
 // {state id, final cost, emitting degree, both degrees packed in one word}, then the state's
@@ -37,10 +47,11 @@
 //   state index   one 4-byte entry per 32 bytes of graph: (epoch tag << 16) | token index
 //   worklists     2 x qcap records {token, block number, cost, first time}
 //   lattice       {prev token, arc id} per stored token, frame after frame
-// LDS holds, per phase, either the expansion tables (negated log-likelihood row and, per chunk
-// of 2048 tokens, the prefix sums of their arc counts so that every lane owns one arc of the
-// flattened (token x arc) space regardless of state degree) or the recombination table, plus
-// the 256-bin cost histogram and the running best cost.
+// LDS holds, per phase, either the expansion tables (negated log-likelihood row, a slice per
+// wave with the prefix sums of its run's arc counts, the list of very large states) or the
+// recombination table; beside them the item tables of the epsilon closure, the slot noted for
+// every candidate of a table pass, the word-boost table, the 256-bin cost histogram and the
+// running best cost.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -66,19 +77,12 @@ namespace {
 #endif
 constexpr int kBlock = WFST_BLOCK;            // threads of the workgroup that owns a channel
 constexpr int kWaves = kBlock / 64;
-#ifndef WFST_TPT
-#define WFST_TPT 2
-#endif
 #ifndef WFST_U
 #define WFST_U 2
 #endif
-constexpr int kTPT = WFST_TPT;                // work items per thread per chunk (1, 2 or 4)
-constexpr int kChunk = kBlock * kTPT;
-constexpr int kWaveTok = 64;                  // tokens a wave expands at a time (2 per lane)
+constexpr int kWaveTok = 64;                  // tokens a wave expands at a time (one per lane)
 constexpr int kHubCap = 512;                  // listed high-degree tokens per frame (more are expanded by their wave)
 constexpr int kHubDeg = 256;                  // arcs beyond which a token is listed there
-constexpr int kChunkLog2 = (kTPT == 4 ? 2 : (kTPT == 2 ? 1 : 0)) + (kBlock == 1024 ? 10 : (kBlock == 512 ? 9 : 8));
-static_assert((1 << kChunkLog2) == kChunk, "owner_of searches log2(kChunk) levels");
 constexpr int kMaxV = 2048;
 constexpr int kU = WFST_U;                    // independent memory requests per lane per phase
 #ifndef WFST_UE
