@@ -234,6 +234,31 @@ def test_c2_alone_equals_in_batch(torch_cuda, c2, c2_refs):
                 refs=c2_refs[b:b + 1])
 
 
+def test_candidate_overflow_is_reported_not_fatal(torch_cuda, c2):
+    """A candidate buffer far too small for the pruning settings: the utterances are flagged and
+    stop (nothing faults), and the same decoder then decodes correctly with settings that fit."""
+    from paper_2311_04996_amd import Decoder, FLAG_CAPACITY, FLAG_DEAD
+    torch = torch_cuda
+    n = 2
+    ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[:n])).cuda()
+    dec = Decoder(c2.graph, max_channels=n, max_frames=c2.loglikes.shape[1], max_active_hint=c2.max_active,
+                  candidate_capacity=4096, record_digests=True)
+    _, nwords, cost, flags = dec.decode_batch(ll, c2.lengths[:n], c2.beam, c2.max_active)
+    torch.cuda.synchronize()
+    for b in range(n):
+        assert int(flags[b]) & FLAG_CAPACITY and int(flags[b]) & FLAG_DEAD and int(nwords[b]) == 0
+    beam, max_active = 3.0, 100
+    refs = oracle_batch(c2.graph, c2.loglikes[:n], c2.lengths[:n], beam, max_active)
+    words, nwords, cost, flags = dec.decode_batch(ll, c2.lengths[:n], beam, max_active)
+    torch.cuda.synchronize()
+    for b, r in enumerate(refs):
+        assert int(flags[b]) == r.flags and not int(flags[b]) & FLAG_CAPACITY
+        assert words[b, :int(nwords[b])].cpu().numpy().tolist() == r.words.tolist()
+        cnt, dig = dec.debug_frame_digests(b)
+        assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all()
+    dec.close()
+
+
 @pytest.mark.parametrize("chunk", [1, 16, 37])
 def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk):
     """Per-stream state persists between chunks (Section 'Streaming inference'): any chunking
