@@ -355,6 +355,50 @@ def test_many_duplicate_destinations(torch_cuda):
     dec.close()
 
 
+def _stress_inputs(graph, T, seed, batch=2):
+    from workloads import ctc_loglikes
+    lengths = np.array([T, max(1, T - 3)][:batch], dtype=np.int32)
+    ll = ctc_loglikes(seed, lengths, T, graph.num_classes, sigma=1.0, p_blank=0.5, blank_boost=2.0, token_boost=1.0)
+    return ll, lengths
+
+
+def test_more_high_degree_states_than_the_shared_list_holds(torch_cuda):
+    """1,200 tokens with 300 arcs each: the list of states expanded segment by segment (512
+    entries) overflows, so some are expanded by their own wave; 360 k candidates per frame for
+    1,200 destinations also exercise the passes over many duplicates."""
+    from workloads import dense_graph
+    g = dense_graph(7, 1200, 300, 12)
+    ll, lengths = _stress_inputs(g, 10, 11)
+    check_batch(torch_cuda, g, ll, lengths, 30.0, 100000, max_active_hint=100000)
+    check_batch(torch_cuda, g, ll, lengths, 6.0, 300, max_active_hint=100000)
+
+
+def test_state_with_more_than_a_million_arcs(torch_cuda):
+    """The emitting degree does not fit the packed header word: the exact degree is read."""
+    from workloads import giant_state_graph
+    g = giant_state_graph(8, 1_100_000, 3000, 12)
+    ll, lengths = _stress_inputs(g, 8, 12)
+    check_batch(torch_cuda, g, ll, lengths, 30.0, 100000, max_active_hint=131072)
+
+
+def test_epsilon_rounds_larger_than_one_chunk_and_one_table(torch_cuda):
+    """A closure round with 3,000 items and 9,000 arcs (not fused: several chunks of items, several
+    table passes) after a fused round of one item with 3,000 arcs."""
+    from workloads import eps_layers_graph
+    g = eps_layers_graph(9, 3000, 12)
+    ll, lengths = _stress_inputs(g, 10, 13)
+    check_batch(torch_cuda, g, ll, lengths, 30.0, 100000, max_active_hint=20000)
+    check_batch(torch_cuda, g, ll, lengths, 2.0, 500, max_active_hint=20000)
+
+
+def test_too_many_epsilon_arcs_on_one_state_is_a_bad_graph(torch_cuda):
+    from paper_2311_04996_amd import Decoder, WfstError
+    from workloads import eps_layers_graph
+    with pytest.raises(WfstError) as e:
+        Decoder(eps_layers_graph(9, 5000, 12), max_channels=1, max_frames=4)
+    assert e.value.code == -2
+
+
 def test_state_index_tag_wraps_after_65535_token_sets(torch_cuda, c1):
     """The per-state token index is tagged with a 16-bit epoch; a channel that lives longer
     than 65,535 frames must renew it.  66,000 frames of the tiny configuration, streamed."""

@@ -5,10 +5,12 @@ and is the only code shared by the CPU oracle's tests and the HIP path's tests
 and benchmark.  Everything is a deterministic function of an integer seed.
 """
 from .graphs import (Graph, tiny_lexicon_graph, tlg_shaped_graph, ctc_topology_graph,
-                     micro_graph, permute_arcs_within_states)
+                     micro_graph, permute_arcs_within_states, dense_graph, giant_state_graph,
+                     eps_layers_graph)
 from .loglikes import ctc_loglikes, random_lengths
 from .configs import CONFIGS, make_config, boost_tables
 
 __all__ = ["Graph", "tiny_lexicon_graph", "tlg_shaped_graph", "ctc_topology_graph",
-           "micro_graph", "permute_arcs_within_states", "ctc_loglikes", "random_lengths",
+           "micro_graph", "permute_arcs_within_states", "dense_graph", "giant_state_graph",
+           "eps_layers_graph", "ctc_loglikes", "random_lengths",
            "CONFIGS", "make_config", "boost_tables"]

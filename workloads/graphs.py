@@ -246,3 +246,62 @@ def permute_arcs_within_states(g: Graph, seed: int) -> Graph:
     return Graph(g.num_states, g.start_state, g.num_classes, g.row_offsets.copy(),
                  g.next_state[perm], g.ilabel[perm], g.olabel[perm], g.weight[perm],
                  g.final_cost.copy(), dict(g.meta or {}, permuted=seed))
+
+
+# --------------------------------------------------------------------------------------
+# Stress shapes for the decoder's less common paths (not paper workloads).
+# --------------------------------------------------------------------------------------
+def _csr(num_states, start, V, src, dst, il, ol, w, final_cost=None, meta=None) -> Graph:
+    """Arrays of arcs (any order) -> Graph; arcs of a state keep their given relative order."""
+    src = np.asarray(src, dtype=np.int64)
+    order = np.argsort(src, kind="stable")
+    off = np.zeros(num_states + 1, dtype=np.int64)
+    np.cumsum(np.bincount(src, minlength=num_states), out=off[1:])
+    fc = np.zeros(num_states, dtype=np.float32) if final_cost is None else np.asarray(final_cost, np.float32)
+    return Graph(num_states, start, V, off, np.asarray(dst, np.int32)[order], np.asarray(il, np.int32)[order],
+                 np.asarray(ol, np.int32)[order], np.asarray(w, np.float32)[order], fc, meta or {})
+
+
+def dense_graph(seed: int, num_states: int, degree: int, num_classes: int, num_words: int = 50) -> Graph:
+    """Every state has `degree` emitting arcs to uniform destinations (no epsilon arcs)."""
+    rng = np.random.default_rng([seed, 0xDE45E])
+    A = num_states * degree
+    src = np.repeat(np.arange(num_states), degree)
+    dst = rng.integers(0, num_states, A)
+    il = rng.integers(1, num_classes + 1, A)
+    ol = np.where(rng.random(A) < 0.05, rng.integers(1, num_words + 1, A), 0)
+    w = -np.log(rng.uniform(0.001, 1.0, A))
+    return _csr(num_states, 0, num_classes, src, dst, il, ol, w)
+
+
+def giant_state_graph(seed: int, fan: int, num_states: int, num_classes: int, num_words: int = 50) -> Graph:
+    """The start state has `fan` emitting arcs; every other state has 3 (one back to the start)."""
+    rng = np.random.default_rng([seed, 0x61A47])
+    rest = num_states - 1
+    src = np.concatenate([np.zeros(fan, np.int64), np.repeat(np.arange(1, num_states), 3)])
+    dst = np.concatenate([rng.integers(1, num_states, fan),
+                          np.stack([np.zeros(rest, np.int64), rng.integers(1, num_states, rest),
+                                    rng.integers(1, num_states, rest)], axis=1).ravel()])
+    A = len(src)
+    il = rng.integers(1, num_classes + 1, A)
+    ol = np.where(rng.random(A) < 0.05, rng.integers(1, num_words + 1, A), 0)
+    w = -np.log(rng.uniform(0.001, 1.0, A))
+    return _csr(num_states, 0, num_classes, src, dst, il, ol, w)
+
+
+def eps_layers_graph(seed: int, width: int, num_classes: int, fan: int = 3, num_words: int = 50) -> Graph:
+    """Start state -> `width` states over epsilon arcs -> `fan` states each of a second layer of
+    `width` states over epsilon arcs (so a closure round has `width` items and `fan * width`
+    arcs); every second-layer state has two emitting arcs, one of them back to the start."""
+    rng = np.random.default_rng([seed, 0xE9517])
+    S = 1 + 2 * width
+    l1 = np.arange(1, 1 + width); l2 = np.arange(1 + width, S)
+    src = [np.zeros(width, np.int64), np.repeat(l1, fan), np.repeat(l2, 2)]
+    dst = [l1, rng.integers(1 + width, S, width * fan),
+           np.stack([np.zeros(width, np.int64), rng.integers(1 + width, S, width)], axis=1).ravel()]
+    il = [np.zeros(width, np.int64), np.zeros(width * fan, np.int64), rng.integers(1, num_classes + 1, 2 * width)]
+    src, dst, il = np.concatenate(src), np.concatenate(dst), np.concatenate(il)
+    A = len(src)
+    ol = np.where(rng.random(A) < 0.1, rng.integers(1, num_words + 1, A), 0)
+    w = -np.log(rng.uniform(0.01, 1.0, A))
+    return _csr(S, 0, num_classes, src, dst, il, ol, w)
