@@ -257,6 +257,16 @@ __device__ __forceinline__ unsigned wave_scan_add(unsigned v) {
   v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
   return v;
 }
+// Minimum over the 64 lanes (same data-parallel steps; lanes shifted in from outside hold ~0).
+__device__ __forceinline__ unsigned wave_min(unsigned v) {
+  v = min(v, (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, 0x111, 0xf, 0xf, false));
+  v = min(v, (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, 0x112, 0xf, 0xf, false));
+  v = min(v, (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, 0x114, 0xf, 0xf, false));
+  v = min(v, (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, 0x118, 0xf, 0xf, false));
+  v = min(v, (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, 0x142, 0xa, 0xf, false));
+  v = min(v, (unsigned)__builtin_amdgcn_update_dpp(-1, (int)v, 0x143, 0xc, 0xf, false));
+  return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
+}
 __device__ __forceinline__ unsigned wave_sum(unsigned v) {
   return (unsigned)__builtin_amdgcn_readlane((int)wave_scan_add(v), 63);
 }
@@ -471,8 +481,12 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
     o = min(o, ok[u] ? f2ord(nc[u]) : kOrdNone);
     next[u] = a[u].x;
   }
-  // running best: only lanes that would lower it touch the LDS word (rare after the first arcs)
-  if (o < bo) atomicMin(&sm.best_ord, o);
+  // running best: lowered by one lane, and only if some lane of the wave has a lower cost
+  // (rare after the first arcs)
+  if (__ballot(o < bo) != 0ull) {
+    const unsigned m = wave_min(o);
+    if ((threadIdx.x & 63) == 0) atomicMin(&sm.best_ord, m);
+  }
   push_cands<N>(x, ok, next, nc, src, arc);
 }
 
