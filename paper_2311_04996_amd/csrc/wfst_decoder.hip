@@ -653,15 +653,19 @@ __device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc
   TableLds &t = x.sm.u.t;
   unsigned s = (hash_state(dst) >> 6) & kTabMask;
   // one compare-and-swap per probe: it returns the slot's key, or claims the slot if it was free
+  int old;
   for (int probes = 0;; ++probes) {
-    const int old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
+    old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
     if (old == kKeyEmpty || old == dst) break;
     s = (s + 1) & kTabMask;
     if (probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return -1; }   // table full
   }
   const unsigned oc = f2ord(cost);
   const unsigned long long mine = ((unsigned long long)oc << 32) | (unsigned)idx;
-  unsigned long long cur = t.vals[s];
+  // a slot this lane has just claimed still holds the empty value (unless another candidate of
+  // the same destination was quicker: then the swap below fails once and returns that value)
+  unsigned long long cur = kValEmpty;
+  if (old != kKeyEmpty) cur = t.vals[s];
   for (;;) {
     const unsigned cc = (unsigned)(cur >> 32);
     bool better = oc < cc;
