@@ -77,7 +77,16 @@ typedef struct {
   int32_t max_active_hint;        /* sizes the per-channel work buffers; 0 = 10000 */
   int32_t candidate_capacity;     /* candidate records per channel and frame, 0 = 16 * max_active_hint */
   int32_t record_digests;         /* 1: keep per-frame token-set digests (slower; for tests) */
+  int32_t loglike_dtype;          /* element type of every `loglikes` argument of this decoder:
+                                     WFST_LOGLIKE_F32 (0), _F16 (1, IEEE binary16) or _BF16 (2).
+                                     16-bit rows are widened to fp32 when a frame is staged; all
+                                     cost arithmetic stays fp32, so the result is exactly that of
+                                     the fp32 decoder fed the widened values */
 } wfst_opts;
+
+#define WFST_LOGLIKE_F32 0
+#define WFST_LOGLIKE_F16 1
+#define WFST_LOGLIKE_BF16 2
 
 /*
  * Word boosting (paper, Section "Word boosting"): the table of a single-state boosting
@@ -111,7 +120,8 @@ int32_t wfst_decoder_destroy(wfst_decoder *dec);
  *   remain, only those in the lowest bins of a 256-bin histogram over [best, best+beam];
  *   epsilon closure under the same cutoff; backpointers appended to the channel's lattice.
  * Then the best token (with final costs if any token is final) is traced back.
- *   loglikes : DEVICE, float [B][T][V] contiguous, V == graph.num_classes; rows t >= lengths[b]
+ *   loglikes : DEVICE, [B][T][V] contiguous, float (or the 16-bit type chosen in
+ *              opts.loglike_dtype; the parameter is then a pointer to those), V == graph.num_classes; rows t >= lengths[b]
  *              are never read.  Must stay valid until the stream has finished the call.
  *   lengths  : HOST, int32 [B], 0 <= lengths[b] <= min(T, max_frames_per_channel)
  *   words    : [B][max_words] int32, nwords [B] int32, cost [B] float, flags [B] int32

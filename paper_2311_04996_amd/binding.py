@@ -17,6 +17,7 @@ WFST_OK = 0
 ERRORS = {-1: "INVALID_ARG", -2: "BAD_GRAPH", -3: "OOM", -4: "LATTICE_OVERFLOW",
           -5: "BAD_CHANNEL", -6: "HIP", -7: "CAPACITY"}
 FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPACITY = 1, 2, 4, 8, 16
+LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
            "wfst_init_channel",
@@ -54,7 +55,8 @@ class wfst_opts(C.Structure):
     _fields_ = [("max_channels", C.c_int32), ("max_frames_per_channel", C.c_int32),
                 ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
                 ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
-                ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32)]
+                ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32),
+                ("loglike_dtype", C.c_int32)]
 
 
 _lib = None
@@ -108,7 +110,7 @@ class Decoder:
 
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
                  lattice_bytes_per_channel=0, outputs_on_host=False, candidate_capacity=0,
-                 record_digests=False):
+                 record_digests=False, loglike_dtype="float32"):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
                 np.ascontiguousarray(graph.next_state, dtype=np.int32),
@@ -120,7 +122,8 @@ class Decoder:
                            *[None if a is None else a.ctypes.data for a in arrs])
         self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
                               int(outputs_on_host), max_active_hint, candidate_capacity,
-                              int(record_digests))
+                              int(record_digests), LOGLIKE_DTYPES[loglike_dtype])
+        self.loglike_dtype = loglike_dtype
         self.V = graph.num_classes
         self.max_words = max_words
         self.outputs_on_host = bool(outputs_on_host)
@@ -152,7 +155,7 @@ class Decoder:
         Returns (words [B, max_words], nwords [B], cost [B], flags [B]); torch CUDA tensors, or
         numpy arrays when the decoder was created with outputs_on_host."""
         import torch
-        assert loglikes.is_cuda and loglikes.dtype == torch.float32 and loglikes.is_contiguous()
+        assert loglikes.is_cuda and loglikes.dtype == getattr(torch, self.loglike_dtype) and loglikes.is_contiguous()
         B, T, V = loglikes.shape
         lengths = np.ascontiguousarray(lengths, dtype=np.int32)
         assert lengths.shape == (B,)
@@ -192,7 +195,7 @@ class Decoder:
     def advance_chunk(self, channels, loglikes, nframes, stream=None):
         """loglikes: CUDA float32 [n, C, V]; channels, nframes: host int32 [n]."""
         import torch
-        assert loglikes.is_cuda and loglikes.dtype == torch.float32 and loglikes.is_contiguous()
+        assert loglikes.is_cuda and loglikes.dtype == getattr(torch, self.loglike_dtype) and loglikes.is_contiguous()
         n, Cn, V = loglikes.shape
         channels = np.ascontiguousarray(channels, dtype=np.int32)
         nframes = np.ascontiguousarray(nframes, dtype=np.int32)

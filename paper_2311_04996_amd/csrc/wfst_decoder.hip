@@ -153,7 +153,8 @@ struct DevChannels {
 
 struct LaunchArgs {
   const int *chan, *nfr, *io;  // device [n]: channel id, frames to consume, row in loglikes/outputs
-  const float *ll; long long ll_stride; int V;
+  const void *ll; long long ll_stride; int V;   // rows of V elements; fp32, or fp16 / bf16 widened when staged
+  int ll_dtype;
   int mode, finalize;
   float beam, scale; int max_active;
   int *words, *nwords; float *cost; int *flags; int max_words;
@@ -1344,13 +1345,25 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     stop = finish_set(x, NQ, 0u);
   }
 
-  const float *ll = a.ll + (long long)io * a.ll_stride;
+  const long long ll0 = (long long)io * a.ll_stride;
   for (int t = 0; t < nfr; ++t) {
     if (stop || x.s.status) break;
     if (x.s.frame >= c.max_frames) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
     renew_index_if_wrapping(x);
-    const float *row = ll + (long long)t * a.V;
-    for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
+    {
+      // the frame's acoustic costs; 16-bit log-likelihoods are widened exactly
+      const long long r0 = ll0 + (long long)t * a.V;
+      if (a.ll_dtype == WFST_LOGLIKE_F32) {
+        const float *row = static_cast<const float *>(a.ll) + r0;
+        for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
+      } else if (a.ll_dtype == WFST_LOGLIKE_F16) {
+        const _Float16 *row = static_cast<const _Float16 *>(a.ll) + r0;
+        for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -(float)row[v];
+      } else {
+        const unsigned short *row = static_cast<const unsigned short *>(a.ll) + r0;
+        for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -__uint_as_float((unsigned)row[v] << 16);
+      }
+    }
     for (int h = tid; h < kHubCap; h += kBlock) { sm.u.e.hub.ready[h] = 0; sm.u.e.hub.seg_next[h] = 0; }
     if (tid == 0) { sm.next_run = kWaves; sm.done_waves = 0; sm.n_hub = 0; }
     __syncthreads();
@@ -1648,6 +1661,8 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
   *out = nullptr;
   if (opts->max_channels < 1 || opts->max_frames_per_channel < 1 || opts->max_words < 1)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "max_channels, max_frames_per_channel and max_words must be >= 1");
+  if (opts->loglike_dtype < WFST_LOGLIKE_F32 || opts->loglike_dtype > WFST_LOGLIKE_BF16)
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "loglike_dtype must be WFST_LOGLIKE_F32, _F16 or _BF16");
   if (opts->candidate_capacity < 0 || (opts->candidate_capacity > 0 && opts->candidate_capacity < 4096))
     return fail(nullptr, WFST_ERR_INVALID_ARG, "candidate_capacity must be 0 or >= 4096");
   if (graph->num_classes > kMaxV)
@@ -1713,7 +1728,7 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *d, const float *loglikes, const 
   for (int i = 0; i < B; ++i) nfr[i] = lengths[order[i]];
   const bool host_out = d->opts.outputs_on_host != 0;
   LaunchArgs a{};
-  a.ll = loglikes; a.ll_stride = (long long)T * V; a.V = V;
+  a.ll = loglikes; a.ll_stride = (long long)T * V; a.V = V; a.ll_dtype = d->opts.loglike_dtype;
   a.mode = kModeInit | kModeFinal; a.finalize = 1;
   a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
   a.words = host_out ? d->o_words : words; a.nwords = host_out ? d->o_nwords : nwords;
@@ -1766,7 +1781,7 @@ int32_t wfst_advance_chunk(wfst_decoder *d, const int32_t *channels, int32_t n, 
     chan[i] = channels[i]; nfr[i] = nframes[i]; io[i] = i;
   }
   LaunchArgs a{};
-  a.ll = loglikes; a.ll_stride = (long long)C * V; a.V = V; a.mode = 0;
+  a.ll = loglikes; a.ll_stride = (long long)C * V; a.V = V; a.mode = 0; a.ll_dtype = d->opts.loglike_dtype;
   return launch(d, chan, nfr, io, a, static_cast<hipStream_t>(stream));
 }
 

@@ -35,12 +35,12 @@ def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, thre
 
 
 def check_batch(torch, graph, loglikes, lengths, beam, max_active, max_words=256, refs=None,
-                max_active_hint=None, check_counters=True, boosts=None, **deckw):
+                max_active_hint=None, check_counters=True, boosts=None, device_loglikes=None, **deckw):
     from paper_2311_04996_amd import Decoder
     B, T, V = loglikes.shape
     dec = Decoder(graph, max_channels=max(B, 1), max_frames=max(T, 1), max_words=max_words,
                   max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True, **deckw)
-    ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda()
+    ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda() if device_loglikes is None else device_loglikes
     words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active, boosts=boosts)
     torch.cuda.synchronize()
     words, nwords, cost, flags = words.cpu().numpy(), nwords.cpu().numpy(), cost.cpu().numpy(), flags.cpu().numpy()
@@ -389,6 +389,19 @@ def test_epsilon_rounds_larger_than_one_chunk_and_one_table(torch_cuda):
     ll, lengths = _stress_inputs(g, 10, 13)
     check_batch(torch_cuda, g, ll, lengths, 30.0, 100000, max_active_hint=20000)
     check_batch(torch_cuda, g, ll, lengths, 2.0, 500, max_active_hint=20000)
+
+
+@pytest.mark.parametrize("dtype", ["float16", "bfloat16"])
+def test_sixteen_bit_loglikes_equal_the_oracle_on_the_widened_values(torch_cuda, c1, c2, dtype):
+    """Rows given as fp16 / bf16 are widened to fp32 when a frame is staged; everything after is
+    the fp32 decoder, so the result is exactly the oracle's on the widened log-likelihoods."""
+    torch = torch_cuda
+    for w, n in ((c1, 1), (c2, 3)):
+        ll16 = torch.from_numpy(np.ascontiguousarray(w.loglikes[:n])).to(getattr(torch, dtype))
+        widened = ll16.to(torch.float32).numpy()
+        assert not np.array_equal(widened, w.loglikes[:n])          # the rounding is real
+        check_batch(torch, w.graph, widened, w.lengths[:n], w.beam, w.max_active,
+                    max_active_hint=w.max_active, device_loglikes=ll16.cuda(), loglike_dtype=dtype)
 
 
 def test_too_many_epsilon_arcs_on_one_state_is_a_bad_graph(torch_cuda):

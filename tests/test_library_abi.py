@@ -51,7 +51,7 @@ def test_product_does_not_import_the_oracle():
                 assert "oracle" not in src.lower(), (f, "mentions the oracle")
 
 
-def _create(lib, arcs, S, V, final=None):
+def _create(lib, arcs, S, V, final=None, loglike_dtype=0):
     import numpy as np
     from paper_2311_04996_amd.binding import wfst_graph_csr, wfst_opts
     from workloads.graphs import _from_arc_list
@@ -59,7 +59,7 @@ def _create(lib, arcs, S, V, final=None):
     keep = [g.row_offsets, g.next_state, g.ilabel, g.olabel, g.weight, g.final_cost]
     cg = wfst_graph_csr(g.num_states, g.start_state, g.num_classes, g.num_arcs,
                         *[a.ctypes.data for a in keep])
-    o = wfst_opts(1, 10, 8, 0, 0, 100, 0, 0)
+    o = wfst_opts(1, 10, 8, 0, 0, 100, 0, 0, loglike_dtype)
     h = ctypes.c_void_p()
     rc = lib.wfst_decoder_create(ctypes.byref(cg), ctypes.byref(o), ctypes.byref(h))
     return rc, lib.wfst_last_error(None).decode()
@@ -74,3 +74,8 @@ def test_bad_graphs_are_rejected_before_touching_the_gpu(lib):
     assert rc == -2 and "weight" in msg
     rc, msg = _create(lib, [(0, 1, 1, -3, 0.5)], 2, 1)
     assert rc == -2 and "olabel" in msg
+    # more epsilon arcs out of one state than the state header's 12-bit field holds
+    rc, msg = _create(lib, [(0, 1, 0, 0, 0.5)] * 5000, 2, 1)
+    assert rc == -2 and "epsilon arcs" in msg
+    rc, msg = _create(lib, [(0, 1, 1, 0, 0.5)], 2, 1, loglike_dtype=7)
+    assert rc == -1 and "loglike_dtype" in msg
