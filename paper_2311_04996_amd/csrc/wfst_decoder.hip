@@ -97,7 +97,7 @@ constexpr int kUC = WFST_UC;                  // ... when survivors become token
 constexpr int kRegions = 4;                   // candidate buffer regions (by destination hash)
 constexpr int kTabSlots = WFST_TAB;           // LDS recombination table (power of two)
 constexpr unsigned kTabMask = kTabSlots - 1;
-constexpr int kGroupTarget = kTabSlots * 9 / 16;  // mean candidates reduced per table pass (load 0.56)
+constexpr int kGroupTarget = kTabSlots * 12 / 16; // mean candidates reduced per table pass (load 0.75)
 constexpr int kBoostSlots = 2048;             // per-channel word-boost table (open addressing)
 constexpr int kBoostMax = 1024;               // entries it may hold
 constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
