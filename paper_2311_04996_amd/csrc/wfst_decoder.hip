@@ -86,10 +86,10 @@ constexpr int kHubDeg = 256;                  // arcs beyond which a token is li
 constexpr int kMaxV = 2048;
 constexpr int kU = WFST_U;                    // independent memory requests per lane per phase
 #ifndef WFST_UE
-#define WFST_UE 4
+#define WFST_UE 2
 #endif
 #ifndef WFST_UC
-#define WFST_UC 4
+#define WFST_UC 2
 #endif
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
