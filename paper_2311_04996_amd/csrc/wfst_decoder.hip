@@ -82,7 +82,7 @@ constexpr int kWaves = kBlock / 64;
 #endif
 constexpr int kWaveTok = 64;                  // tokens a wave expands at a time (one per lane)
 constexpr int kHubCap = 512;                  // listed high-degree tokens per frame (more are expanded by their wave)
-constexpr int kHubDeg = 256;                  // arcs beyond which a token is listed there
+constexpr int kHubDeg = 512;                  // arcs beyond which a token is listed there
 constexpr int kMaxV = 2048;
 constexpr int kU = WFST_U;                    // independent memory requests per lane per phase
 #ifndef WFST_UE
@@ -750,7 +750,7 @@ template <bool kSelect>
 __device__ __forceinline__ void table_winners(Ctx &x, int r0, int r1, int g, int G, const Cutoff &cut, int k_sel) {
   TableLds &t = x.sm.u.t;
   const int tid = threadIdx.x;
-  constexpr int kW = 4;
+  constexpr int kW = 2;
   int pos0 = 0;
   for (int r = r0; r < r1; ++r) {
     const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
