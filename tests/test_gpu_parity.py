@@ -363,11 +363,11 @@ def _stress_inputs(graph, T, seed, batch=2):
 
 
 def test_more_high_degree_states_than_the_shared_list_holds(torch_cuda):
-    """1,200 tokens with 300 arcs each: the list of states expanded segment by segment (512
-    entries) overflows, so some are expanded by their own wave; 360 k candidates per frame for
+    """1,200 tokens with 600 arcs each: the list of states expanded segment by segment (512
+    entries) overflows, so some are expanded by their own wave; 720 k candidates per frame for
     1,200 destinations also exercise the passes over many duplicates."""
     from workloads import dense_graph
-    g = dense_graph(7, 1200, 300, 12)
+    g = dense_graph(7, 1200, 600, 12)
     ll, lengths = _stress_inputs(g, 10, 11)
     check_batch(torch_cuda, g, ll, lengths, 30.0, 100000, max_active_hint=100000)
     check_batch(torch_cuda, g, ll, lengths, 6.0, 300, max_active_hint=100000)
