@@ -420,40 +420,15 @@ static_assert(kRegions == 4, "region_of takes two hash bits");
 template <int N>
 __device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int (&next)[N], const float (&nc)[N],
                                            const int (&src)[N], const int (&arc)[N]) {
-  const int lane = threadIdx.x & 63;
-  typedef unsigned long long u64;
-  int r[N], rank[N]; int off[N][kRegions]; int cnt[kRegions];
-#pragma unroll
-  for (int q = 0; q < kRegions; ++q) cnt[q] = 0;
-#pragma unroll
-  for (int u = 0; u < N; ++u) {
-    r[u] = region_of(key_of(next[u]));
-    // three ballots give the four per-region lane masks with scalar logic
-    const u64 bk = __ballot(ok[u]), b0 = __ballot((r[u] & 1) != 0), b1 = __ballot((r[u] & 2) != 0);
-    const u64 m[kRegions] = {bk & ~b1 & ~b0, bk & ~b1 & b0, bk & b1 & ~b0, bk & b1 & b0};
-    const u64 lo = (r[u] & 1) ? m[1] : m[0], hi = (r[u] & 1) ? m[3] : m[2];
-    const u64 own = (r[u] & 2) ? hi : lo;                    // lanes of this lane's region
-    rank[u] = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(own >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)own, 0u));
-#pragma unroll
-    for (int q = 0; q < kRegions; ++q) { off[u][q] = cnt[q]; cnt[q] += __popcll(m[q]); }
-  }
-  // lanes 0..3 reserve the runs of regions 0..3 with one LDS atomic instruction
-  int base[kRegions];
-  {
-    const int mine = lane == 0 ? cnt[0] : lane == 1 ? cnt[1] : lane == 2 ? cnt[2] : cnt[3];
-    int got = 0;
-    if (lane < kRegions && mine) got = atomicAdd(&x.sm.n_reg[lane], mine);
-#pragma unroll
-    for (int q = 0; q < kRegions; ++q) base[q] = __builtin_amdgcn_readlane(got, q);
-  }
   const int cap = x.c.region_cap;
 #pragma unroll
   for (int u = 0; u < N; ++u) {
-    const int s0 = (r[u] & 1) ? base[1] + off[u][1] : base[0] + off[u][0];
-    const int s1 = (r[u] & 1) ? base[3] + off[u][3] : base[2] + off[u][2];
-    const int slot = ((r[u] & 2) ? s1 : s0) + rank[u];
+    const int r = region_of(key_of(next[u]));
     if (ok[u]) {
-      if (slot < cap) x.cand[r[u] * cap + slot] = make_int4(next[u], __float_as_int(nc[u]), src[u], arc[u]);
+      // one LDS atomic instruction for the whole wave: the hardware serialises the lanes of a
+      // region and hands them consecutive slots, in far fewer issue slots than ballots would take
+      const int slot = atomicAdd(&x.sm.n_reg[r], 1);
+      if (slot < cap) x.cand[r * cap + slot] = make_int4(next[u], __float_as_int(nc[u]), src[u], arc[u]);
       else atomicOr(&x.sm.status, kStCapacity);
     }
   }
