@@ -94,12 +94,19 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
 constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
-constexpr int kRegions = 4;                   // candidate buffer regions (by destination hash)
+#ifndef WFST_REGION_BITS
+#define WFST_REGION_BITS 2
+#endif
+constexpr int kRegionBits = WFST_REGION_BITS;
+constexpr int kRegions = 1 << kRegionBits;    // candidate buffer regions (by destination hash)
 constexpr int kTabSlots = WFST_TAB;           // LDS recombination table (power of two)
 constexpr unsigned kTabMask = kTabSlots - 1;
 constexpr int kGroupTarget = kTabSlots * 12 / 16; // mean candidates reduced per table pass (load 0.75)
-constexpr int kBoostSlots = 2048;             // per-channel word-boost table (open addressing)
-constexpr int kBoostMax = 1024;               // entries it may hold
+#ifndef WFST_BOOST
+#define WFST_BOOST 2048
+#endif
+constexpr int kBoostSlots = WFST_BOOST;       // per-channel word-boost table (open addressing)
+constexpr int kBoostMax = kBoostSlots / 2;    // entries it may hold
 constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
@@ -219,7 +226,7 @@ __device__ __forceinline__ float ord2f(unsigned o) {
 // -0 becomes +0 (costs are compared by their bits); every other value is unchanged.
 __device__ __forceinline__ float canon(float x) { return x + 0.0f; }
 __device__ __forceinline__ unsigned hash_state(int s) { return (unsigned)s * 0x9E3779B1u; }
-__host__ __device__ inline unsigned boost_slot(int word) { return ((unsigned)word * 0x9E3779B1u) >> 21; }   // 11 bits
+__host__ __device__ inline unsigned boost_slot(int word) { return (((unsigned)word * 0x9E3779B1u) >> 16) & (kBoostSlots - 1); }
 __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   x += 0x9E3779B97F4A7C15ull;
   x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -409,8 +416,7 @@ __device__ __forceinline__ void owners_of(const unsigned *pre, int n, unsigned f
 
 // Region of the candidate buffer a destination state belongs to (top hash bits).
 __device__ __forceinline__ int key_of(int next) { return (int)((unsigned)next & kKeyMask); }
-__device__ __forceinline__ int region_of(int key) { return (int)(hash_state(key) >> 30); }
-static_assert(kRegions == 4, "region_of takes two hash bits");
+__device__ __forceinline__ int region_of(int key) { return (int)(hash_state(key) >> (32 - kRegionBits)); }
 
 // Append a batch of N candidates per lane to their destinations' regions.  The wave counts
 // its candidates per region with ballots, lane 0 reserves one run per region (kRegions
@@ -661,7 +667,8 @@ __device__ __forceinline__ void table_clear(Smem &sm) {
 
 // Sub-group of a destination state when one region is reduced in G table passes.
 __device__ __forceinline__ int group_of(int dst, int G) {
-  return (int)((((hash_state(dst) >> 19) & 0x7ffu) * (unsigned)G) >> 11);   // hash bits 19..29 scaled to [0, G)
+  // the 11 hash bits below the region's, scaled to [0, G)
+  return (int)((((hash_state(dst) >> (21 - kRegionBits)) & 0x7ffu) * (unsigned)G) >> 11);
 }
 
 // One table pass over regions [r0, r1): every candidate of sub-group g (of G) that is selected
