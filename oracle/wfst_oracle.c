@@ -35,6 +35,17 @@
  *       pseudo-code): on every arc, emitting or epsilon, whose olabel is in the utterance's
  *       boost table, the table's score is added after the other terms:
  *       ((c + w) + (-loglike)) + b[olabel], resp. (c + w) + b[olabel].
+ *   R10 lattice output.  The paper only says that the stored tokens and backpointers let the
+ *       host build "a lattice or least cost path" (Section "Algorithm description") and gives
+ *       no definition, so this one is this build's own: the nodes are the tokens of all
+ *       closed sets A_0..A_T; there is a link for every graph arc between two stored tokens
+ *       (an emitting arc from a token of A_{t-1} to a token of A_t, read against row t-1; an
+ *       epsilon arc between two tokens of the same A_t) whose cost through the arc,
+ *       computed from the source token's stored cost exactly as in R2/R9, is finite and
+ *       satisfies (cost - stored cost of the destination token) <= lattice_beam in fp32.
+ *       The backpointer arcs are the links with difference 0.  Pinned by the tests only
+ *       through what the definition implies (complete path set on unpruned micro graphs,
+ *       best path = the decoder's); against the paper it is "parity unpinned".
  *
  * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
  * Viterbi, greedy CTC collapse on the normal CTC topology, closed-form histogram cases,
@@ -450,4 +461,69 @@ done:
   for (int32_t t = 0; t <= len; ++t) free(lat[t]);
   free(lat); free(lat_n); free(cur.t); free(nxt.t); free(map); free(boost);
   return rc;
+}
+
+/*
+ * Lattice links (R10) between the closed token sets of one utterance, which the caller got
+ * from oracle_decode's dump (set_off [len+2], set_states, set_costs).  Outputs, one entry per
+ * link, ordered by frame, then epsilon links before emitting links, then source token, then
+ * arc: l_frame = t of the destination set A_t; l_src / l_dst = token positions inside their
+ * sets (the source of an emitting link lies in A_{t-1}, of an epsilon link in A_t); l_arc =
+ * global arc id (R3); l_cost = cost through the arc.  Returns the number of links (only the
+ * first `cap` are written), or -1 on bad arguments.
+ */
+int64_t oracle_lattice_links(const oracle_prepared *p, const float *loglikes, int64_t row_stride,
+                             int32_t len, const oracle_opts *o, float lattice_beam,
+                             const int64_t *set_off, const int32_t *set_states, const float *set_costs,
+                             int64_t cap, int32_t *l_frame, int32_t *l_src, int32_t *l_dst,
+                             int32_t *l_arc, float *l_cost) {
+  if (!p || !o || len < 0 || !set_off || !(lattice_beam >= 0.0f)) return -1;
+  float *boost = NULL;
+  if (o->boost_n > 0) {
+    int32_t max_ol = 0;
+    for (int64_t a = 0; a < p->Ae; ++a) if (p->e_ol[a] > max_ol) max_ol = p->e_ol[a];
+    for (int64_t a = 0; a < p->Ax; ++a) if (p->x_ol[a] > max_ol) max_ol = p->x_ol[a];
+    boost = (float *)calloc((size_t)max_ol + 1, sizeof(float));
+    for (int32_t i = 0; i < o->boost_n; ++i)
+      if (o->boost_ids[i] > 0 && o->boost_ids[i] <= max_ol) boost[o->boost_ids[i]] = o->boost_scores[i];
+  }
+  int32_t *where = (int32_t *)malloc(sizeof(int32_t) * p->S);     /* state -> position in A_t */
+  for (int32_t s = 0; s < p->S; ++s) where[s] = -1;
+  int64_t n = 0;
+#define PUT(T, I, J, A, C_) do { if (n < cap) { l_frame[n] = (T); l_src[n] = (I); l_dst[n] = (J); \
+                                               l_arc[n] = (int32_t)(A); l_cost[n] = (C_); } ++n; } while (0)
+  for (int32_t t = 0; t <= len; ++t) {
+    const int32_t *S1 = set_states + set_off[t]; const float *C1 = set_costs + set_off[t];
+    const int32_t n1 = (int32_t)(set_off[t + 1] - set_off[t]);
+    for (int32_t j = 0; j < n1; ++j) where[S1[j]] = j;
+    /* epsilon arcs between two tokens of A_t */
+    for (int32_t i = 0; i < n1; ++i) {
+      for (int64_t a = p->x_off[S1[i]]; a < p->x_off[S1[i] + 1]; ++a) {
+        float nc = canon(C1[i] + p->x_w[a]);
+        if (boost && p->x_ol[a] != 0) nc = canon(nc + boost[p->x_ol[a]]);
+        const int32_t j = where[p->x_next[a]];
+        if (!(nc < INFINITY) || j < 0) continue;
+        if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, p->Ae + a, nc);
+      }
+    }
+    /* emitting arcs from the tokens of A_{t-1}, against row t-1 */
+    if (t > 0) {
+      const int32_t *S0 = set_states + set_off[t - 1]; const float *C0 = set_costs + set_off[t - 1];
+      const int32_t n0 = (int32_t)(set_off[t] - set_off[t - 1]);
+      const float *L = loglikes + (int64_t)(t - 1) * row_stride;
+      for (int32_t i = 0; i < n0; ++i) {
+        for (int64_t a = p->e_off[S0[i]]; a < p->e_off[S0[i] + 1]; ++a) {
+          float nc = canon((C0[i] + p->e_w[a]) + (-L[p->e_il[a] - 1]));
+          if (boost && p->e_ol[a] != 0) nc = canon(nc + boost[p->e_ol[a]]);
+          const int32_t j = where[p->e_next[a]];
+          if (!(nc < INFINITY) || j < 0) continue;
+          if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, a, nc);
+        }
+      }
+    }
+    for (int32_t j = 0; j < n1; ++j) where[S1[j]] = -1;
+  }
+#undef PUT
+  free(where); free(boost);
+  return n;
 }

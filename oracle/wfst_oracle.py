@@ -71,6 +71,11 @@ def _load():
                                        C.POINTER(_Opts), C.c_void_p, C.POINTER(_Result),
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
+        _lib.oracle_lattice_links.restype = C.c_int64
+        _lib.oracle_lattice_links.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                              C.POINTER(_Opts), C.c_float, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -111,6 +116,31 @@ class OracleResult:
     @property
     def dead(self) -> bool:
         return bool(self.flags & 4)
+
+
+@dataclass
+class OracleLattice:
+    """Token sets A_0..A_T (set_off, states, costs) and the links between them.  A link's src /
+    dst are positions inside their sets: the source of an emitting link (arc < num_emitting)
+    lies in A_{frame-1}, of an epsilon link in A_frame."""
+    result: OracleResult
+    set_off: np.ndarray
+    states: np.ndarray
+    costs: np.ndarray
+    frame: np.ndarray
+    src: np.ndarray
+    dst: np.ndarray
+    arc: np.ndarray
+    cost: np.ndarray
+    num_emitting: int
+
+    def src_global(self) -> np.ndarray:
+        """Index of every link's source token in the concatenated token arrays."""
+        emit = self.arc < self.num_emitting
+        return self.set_off[self.frame - emit.astype(np.int32)] + self.src
+
+    def dst_global(self) -> np.ndarray:
+        return self.set_off[self.frame] + self.dst
 
 
 class Oracle:
@@ -186,6 +216,37 @@ class Oracle:
         return OracleResult(words[:res.nwords].copy(), float(res.cost), int(res.flags),
                             np.array(list(res.counters), dtype=np.int64),
                             None if path is None else path[:res.path_len].copy(), dc, ds, frames)
+
+    def lattice(self, loglikes, length=None, beam=17.0, max_active=10000, lattice_beam=np.inf,
+                boost=None) -> "OracleLattice":
+        """Decode, then list the lattice links between the stored token sets (reading R10 in
+        the C source): every arc between two stored tokens whose cost through the arc is within
+        `lattice_beam` of the destination token's cost."""
+        lib = _load()
+        ll = np.asarray(loglikes, dtype=np.float32)
+        n = ll.shape[0] if length is None else int(length)
+        res = self.decode(ll, n, beam, max_active, want_frames=True, want_path=True, boost=boost)
+        off = np.zeros(n + 2, np.int64)
+        off[1:] = np.cumsum([len(s) for s, _ in res.frames])
+        st = np.ascontiguousarray(np.concatenate([s for s, _ in res.frames]), dtype=np.int32)
+        co = np.ascontiguousarray(np.concatenate([c for _, c in res.frames]), dtype=np.float32)
+        if boost is not None:
+            b_ids = np.ascontiguousarray(boost[0], dtype=np.int32)
+            b_sc = np.ascontiguousarray(boost[1], dtype=np.float32)
+            o = _Opts(beam, max_active, 0, 1, 0, 0, len(b_ids), b_ids.ctypes.data, b_sc.ctypes.data)
+        else:
+            o = _Opts(beam, max_active, 0, 1, 0, 0, 0, None, None)
+        args = (self._p, ll.ctypes.data, ll.strides[0] // 4, n, C.byref(o), float(lattice_beam),
+                off.ctypes.data, st.ctypes.data, co.ctypes.data)
+        m = lib.oracle_lattice_links(*args, 0, None, None, None, None, None)
+        if m < 0:
+            raise RuntimeError("oracle_lattice_links rejected its arguments")
+        fr, src, dst, arc = (np.zeros(m, np.int32) for _ in range(4))
+        cost = np.zeros(m, np.float32)
+        m2 = lib.oracle_lattice_links(*args, m, fr.ctypes.data, src.ctypes.data, dst.ctypes.data,
+                                      arc.ctypes.data, cost.ctypes.data)
+        assert m2 == m
+        return OracleLattice(res, off, st, co, fr, src, dst, arc, cost, self.num_emitting)
 
     def eps_closure(self, states, costs, best, beam, k_keep=256, order=0, seed=0):
         lib = _load()

@@ -5,6 +5,8 @@
   Bellman-Ford relaxation of epsilon arcs.
 * greedy_ctc: argmax per frame, collapse repeats, drop blanks.
 * resum_path: cost of a given arc sequence, fp32 in the decoder's association and fp64.
+* all_paths: every path of a micro graph as its arc sequence (for the lattice pins).
+* trellis_alphas: the fp64 trellis of every frame (for the lattice-beam rule).
 """
 from __future__ import annotations
 
@@ -119,3 +121,49 @@ def resum_path(g, ll, orig_arcs):
             words.append(int(g.olabel[a]))
         s = int(g.next_state[a])
     return float(c32), c64, s, t, words
+
+
+def all_paths(g, ll):
+    """Every path from the start state that consumes exactly len(ll) frames (epsilon arcs
+    anywhere), as {tuple of arc indices: (fp64 cost without final cost, end state)}."""
+    T = ll.shape[0]
+    out = {}
+
+    def rec(s, t, cost, arcs):
+        if t == T:
+            out[arcs] = (cost, s)
+        for a in g.arcs_of(s):
+            il, w = int(g.ilabel[a]), float(g.weight[a])
+            if il == 0:
+                rec(int(g.next_state[a]), t, cost + w, arcs + (a,))
+            elif t < T:
+                rec(int(g.next_state[a]), t + 1, cost + w - float(ll[t, il - 1]), arcs + (a,))
+
+    rec(g.start_state, 0, 0.0, ())
+    return out
+
+
+def trellis_alphas(g, ll):
+    """[T+1][S] fp64: least cost of reaching each state having consumed t frames (dense
+    dynamic programme, epsilon arcs relaxed to the fixpoint)."""
+    src, e, x = _split(g)
+    S, T = g.num_states, ll.shape[0]
+    w = g.weight.astype(np.float64)
+
+    def relax_eps(alpha):
+        for _ in range(S + 1):
+            new = alpha.copy()
+            np.minimum.at(new, g.next_state[x], alpha[src[x]] + w[x])
+            if np.array_equal(new, alpha):
+                return alpha
+            alpha = new
+        raise RuntimeError("epsilon relaxation did not converge")
+
+    alphas = np.full((T + 1, S), np.inf)
+    alphas[0, g.start_state] = 0.0
+    alphas[0] = relax_eps(alphas[0])
+    for t in range(T):
+        new = np.full(S, np.inf)
+        np.minimum.at(new, g.next_state[e], alphas[t][src[e]] + w[e] - ll[t].astype(np.float64)[g.ilabel[e] - 1])
+        alphas[t + 1] = relax_eps(new)
+    return alphas
