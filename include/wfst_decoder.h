@@ -82,6 +82,9 @@ typedef struct {
                                      16-bit rows are widened to fp32 when a frame is staged; all
                                      cost arithmetic stays fp32, so the result is exactly that of
                                      the fp32 decoder fed the widened values */
+  int32_t keep_token_records;     /* 1: keep {state, cost} of every stored token beside its
+                                     backpointer (as much memory again as the lattice arena), which
+                                     wfst_get_lattice needs; 0: only the best path can be read back */
 } wfst_opts;
 
 #define WFST_LOGLIKE_F32 0
@@ -166,6 +169,43 @@ int32_t wfst_get_partial(wfst_decoder *dec, int32_t ch, int32_t finalize, int32_
 int32_t wfst_get_partial_batch(wfst_decoder *dec, const int32_t *channels, int32_t n, int32_t finalize,
                                int32_t *words, int32_t *nwords, float *cost, int32_t *flags,
                                void *stream);
+
+/*
+ * Lattice output.  The paper says only that the stored tokens and backpointers let the host
+ * construct "a lattice or least cost path" (Section "Algorithm description") and defines no
+ * lattice; the definition here is this library's own.  Nodes are the stored tokens of channel
+ * `ch`: the closed token sets A_0..A_f (f = frames consumed since its init), numbered
+ * consecutively, A_t = [frame_off[t], frame_off[t+1]).  There is a link for every arc of the
+ * graph between two stored tokens -- an emitting arc from a token of A_{t-1} to a token of A_t,
+ * an epsilon arc between two tokens of the same A_t -- whose cost through the arc (the source
+ * token's stored cost plus arc weight, acoustic cost and boost score, added in the decoder's
+ * own order and precision) is finite and at most `lattice_beam` above the destination token's
+ * stored cost.  The best path's backpointers are links of difference 0, so the lattice's least
+ * cost path is the decoder's; lattice_beam = +inf keeps every arc between stored tokens.
+ *
+ * Needs opts.keep_token_records.  `loglikes`: DEVICE, the utterance's f rows of V elements
+ * (dense, element type opts.loglike_dtype) with the values it was decoded with; the decoder
+ * does not keep them.  tok_state / tok_cost [tok_cap] and links [link_cap]: DEVICE, caller
+ * owned, written in no particular link order.  frame_off [f+2], n_tokens, n_links: HOST.  The
+ * call runs on `stream` and returns after it has finished.  If tok_cap or link_cap is too
+ * small the call returns WFST_ERR_CAPACITY with *n_tokens and *n_links set to what is needed
+ * (entries beyond the capacities are not written).  Other errors: INVALID_ARG (no records
+ * kept, null pointer, negative or NaN lattice_beam), BAD_CHANNEL, CAPACITY (the channel
+ * itself stopped on an overflow: its token sets are incomplete), HIP.
+ */
+typedef struct {
+  int32_t src, dst;               /* token numbers */
+  int32_t ilabel, olabel;         /* of the arc; ilabel 0 = epsilon link */
+  float graph_cost;               /* arc weight */
+  float acoustic_cost;            /* -loglikes[frame-1][ilabel-1]; 0 for an epsilon link */
+  float cost;                     /* cost through the arc (includes the boost score, if any) */
+  int32_t frame;                  /* t of the set A_t the destination token is in */
+} wfst_lattice_link;
+
+int32_t wfst_get_lattice(wfst_decoder *dec, int32_t ch, const void *loglikes, float lattice_beam,
+                         int32_t *tok_state, float *tok_cost, int64_t tok_cap, int64_t *frame_off,
+                         wfst_lattice_link *links, int64_t link_cap,
+                         int64_t *n_tokens, int64_t *n_links, void *stream);
 
 /*
  * Test and measurement hooks.  All outputs are HOST memory; each call synchronises the

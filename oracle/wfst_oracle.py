@@ -225,7 +225,16 @@ class Oracle:
         lib = _load()
         ll = np.asarray(loglikes, dtype=np.float32)
         n = ll.shape[0] if length is None else int(length)
-        res = self.decode(ll, n, beam, max_active, want_frames=True, want_path=True, boost=boost)
+        cap = (n + 1) * max(4096, 4 * min(max_active, 1 << 20))
+        while True:                                   # the closure can grow a set well past max_active
+            try:
+                res = self.decode(ll, n, beam, max_active, want_frames=True, want_path=True, boost=boost,
+                                  frames_cap=cap)
+                break
+            except RuntimeError as e:
+                if "-2" not in str(e) or cap > (1 << 31):
+                    raise
+                cap *= 4
         off = np.zeros(n + 2, np.int64)
         off[1:] = np.cumsum([len(s) for s, _ in res.frames])
         st = np.ascontiguousarray(np.concatenate([s for s, _ in res.frames]), dtype=np.int32)

@@ -21,7 +21,8 @@ LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
            "wfst_init_channel",
-           "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_debug_frame_digests",
+           "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
+           "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
 
@@ -56,7 +57,18 @@ class wfst_opts(C.Structure):
                 ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
                 ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
                 ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32),
-                ("loglike_dtype", C.c_int32)]
+                ("loglike_dtype", C.c_int32), ("keep_token_records", C.c_int32)]
+
+
+class wfst_lattice_link(C.Structure):
+    _fields_ = [("src", C.c_int32), ("dst", C.c_int32), ("ilabel", C.c_int32), ("olabel", C.c_int32),
+                ("graph_cost", C.c_float), ("acoustic_cost", C.c_float), ("cost", C.c_float),
+                ("frame", C.c_int32)]
+
+
+LINK_DTYPE = np.dtype([("src", np.int32), ("dst", np.int32), ("ilabel", np.int32), ("olabel", np.int32),
+                       ("graph_cost", np.float32), ("acoustic_cost", np.float32), ("cost", np.float32),
+                       ("frame", np.int32)])
 
 
 _lib = None
@@ -93,8 +105,10 @@ def load_library():
     lib.wfst_last_kernel_ms.restype = f32
     lib.wfst_last_error.argtypes = [p]
     lib.wfst_last_error.restype = C.c_char_p
-    for name in EXPORTS[:12]:
-        getattr(lib, name).restype = i32
+    lib.wfst_get_lattice.argtypes = [p, i32, p, f32, p, p, i64, p, p, i64, p, p, p]
+    for name in EXPORTS:
+        if name not in ("wfst_device_bytes", "wfst_last_kernel_ms", "wfst_last_error"):
+            getattr(lib, name).restype = i32
     _lib = lib
     return lib
 
@@ -110,7 +124,7 @@ class Decoder:
 
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
                  lattice_bytes_per_channel=0, outputs_on_host=False, candidate_capacity=0,
-                 record_digests=False, loglike_dtype="float32"):
+                 record_digests=False, loglike_dtype="float32", keep_token_records=False):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
                 np.ascontiguousarray(graph.next_state, dtype=np.int32),
@@ -122,7 +136,7 @@ class Decoder:
                            *[None if a is None else a.ctypes.data for a in arrs])
         self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
                               int(outputs_on_host), max_active_hint, candidate_capacity,
-                              int(record_digests), LOGLIKE_DTYPES[loglike_dtype])
+                              int(record_digests), LOGLIKE_DTYPES[loglike_dtype], int(keep_token_records))
         self.loglike_dtype = loglike_dtype
         self.V = graph.num_classes
         self.max_words = max_words
@@ -242,6 +256,37 @@ class Decoder:
                                                     ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3]),
                                                     _stream_ptr(stream)))
         return out
+
+    def get_lattice(self, ch, loglikes, lattice_beam, stream=None, tok_cap=None, link_cap=None):
+        """wfst_get_lattice for channel `ch`; `loglikes` [frames, V] is the utterance's device
+        tensor it was decoded with.  Returns a `Lattice` (host arrays).  Without capacities the
+        call is made twice: once to learn the sizes, once with buffers of that size."""
+        import torch
+        from .lattice import Lattice
+        assert loglikes.is_cuda and loglikes.dtype == getattr(torch, self.loglike_dtype) and loglikes.is_contiguous()
+        assert loglikes.ndim == 2 and loglikes.shape[1] == self.V
+        off = np.zeros(self.opts.max_frames_per_channel + 2, np.int64)
+        nt, nl = C.c_int64(), C.c_int64()
+
+        def call(tc, lc):
+            st = torch.zeros(max(tc, 1), dtype=torch.int32, device="cuda")
+            co = torch.zeros(max(tc, 1), dtype=torch.float32, device="cuda")
+            lk = torch.zeros(max(lc, 1) * LINK_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
+            rc = self.lib.wfst_get_lattice(self.h, ch, loglikes.data_ptr(), float(lattice_beam),
+                                           st.data_ptr(), co.data_ptr(), tc, off.ctypes.data, lk.data_ptr(), lc,
+                                           C.byref(nt), C.byref(nl), _stream_ptr(stream))
+            return rc, st, co, lk
+
+        if tok_cap is None or link_cap is None:
+            rc, *_ = call(0, 0)
+            if rc not in (WFST_OK, -7) or (rc == -7 and nt.value == 0 and nl.value == 0):
+                self._check(rc)
+            tok_cap, link_cap = nt.value, nl.value
+        rc, st, co, lk = call(tok_cap, link_cap)
+        self._check(rc)
+        links = lk.cpu().numpy()[:nl.value * LINK_DTYPE.itemsize].view(LINK_DTYPE).copy()
+        return Lattice(off[:loglikes.shape[0] + 2].copy(), st.cpu().numpy()[:nt.value].copy(),
+                       co.cpu().numpy()[:nt.value].copy(), links)
 
     # ---- hooks
     def debug_frame_digests(self, ch):

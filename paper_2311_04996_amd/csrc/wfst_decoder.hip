@@ -152,6 +152,7 @@ struct DevChannels {
   int4 *wl;                                    // 2 buffers {token, block number, cost, 1 = new token}
   unsigned *index;                             // [n_blk] (epoch tag << 16) | token index
   int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
+  int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
   long long *counters;                         // [24]: 8 workload counters, 16 phase tick sums
@@ -1171,6 +1172,11 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
     }
     if (s) atomicAdd(&sm.red64, s);
   }
+  if (x.c.tokrec) {                              // lattice output wants the closed set's final records
+    int2 *rec = x.c.tokrec + (x.lat - x.c.lattice);
+    for (int i = tid; i < n; i += kBlock)
+      if (lat_base + (unsigned)i < x.c.lat_cap) rec[lat_base + i] = NQ[i];
+  }
   __syncthreads();
   if (tid == 0) {
     x.frame_off[f] = lat_base;
@@ -1385,6 +1391,179 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   }
 }
 
+
+// ------------------------------------------------------------------ lattice links
+// One workgroup per closed token set A_t of one channel, after decoding.  The set's tokens go
+// into an LDS hash (block number -> position in A_t); then every epsilon arc of the tokens of
+// A_t and every emitting arc of the tokens of A_{t-1} is expanded once more, exactly as the
+// decoder did, and its destination looked up: if a token is there and the cost through the arc
+// is within the lattice beam of that token's stored cost, the arc is a link.  Sets too large
+// for one table are taken in passes over hash groups of their keys.
+constexpr int kLatSlots = 16384;
+constexpr int kLatGroup = 8192;               // mean keys per pass (load 0.5)
+constexpr int kLatHeavy = 1024;               // tokens with many arcs, expanded by the whole workgroup
+constexpr int kLatHeavyDeg = 64;
+constexpr int kLatErrTable = 1;
+struct LatLds {
+  int keys[kLatSlots];
+  unsigned short pos[kLatSlots];
+  float ac[kMaxV];
+  int bk[kBoostSlots]; float bv[kBoostSlots];
+  int heavy[kLatHeavy];
+  int n_heavy;
+};
+struct LatticeArgs {
+  int ch, frames;
+  const void *ll; int V, ll_dtype;
+  float lattice_beam;
+  int *tok_state; float *tok_cost; long long tok_cap;
+  wfst_lattice_link *links; long long link_cap;
+  unsigned long long *ctr;                    // [0] links found, [1] error bits
+};
+
+struct LatPass {                              // block-uniform view of one pass
+  const DevGraph &g; LatLds &sm; const LatticeArgs &a;
+  const int2 *dst_rec; unsigned dst_base;     // records and first token number of A_t
+  int t, p, P; bool boosted;
+};
+
+__device__ __forceinline__ int lat_group(int key, int P) {
+  return (int)(((hash_state(key) >> 20) * (unsigned)P) >> 12);
+}
+
+// One arc (unit address u) out of the token numbered `src` with cost tc.
+template <bool kEps>
+__device__ __forceinline__ void lat_arc(const LatPass &q, int u, float tc, unsigned src) {
+  const int4 ar = q.g.unit[u];
+  const int key = key_of(ar.x);
+  if (q.P > 1 && lat_group(key, q.P) != q.p) return;
+  const float w = __int_as_float(ar.y);
+  float acst = 0.0f, nc;
+  if (kEps) nc = canon(tc + w);
+  else { acst = q.sm.ac[ar.z - 1]; nc = canon((tc + w) + acst); }
+  if (q.boosted && ar.w != 0) {
+    unsigned h = boost_slot(ar.w);
+    float b = 0.0f;
+    for (;;) {
+      const int k = q.sm.bk[h];
+      if (k == ar.w) { b = q.sm.bv[h]; break; }
+      if (k == 0) break;
+      h = (h + 1) & (kBoostSlots - 1);
+    }
+    nc = canon(nc + b);
+  }
+  if (!(nc < INFINITY)) return;
+  unsigned sl = (hash_state(key) >> 6) & (kLatSlots - 1);
+  int probes = 0;
+  while (q.sm.keys[sl] != key) {
+    if (q.sm.keys[sl] == kKeyEmpty || ++probes >= kLatSlots) return;       // no token for that state
+    sl = (sl + 1) & (kLatSlots - 1);
+  }
+  const unsigned j = q.sm.pos[sl];
+  const float cj = __int_as_float(q.dst_rec[j].y);
+  if (!((nc - cj) <= q.a.lattice_beam)) return;
+  const unsigned long long at = atomicAdd(&q.a.ctr[0], 1ull);
+  if (at < (unsigned long long)q.a.link_cap) {
+    wfst_lattice_link L;
+    L.src = (int)src; L.dst = (int)(q.dst_base + j); L.ilabel = kEps ? 0 : ar.z; L.olabel = ar.w;
+    L.graph_cost = w; L.acoustic_cost = acst; L.cost = nc; L.frame = q.t;
+    q.a.links[at] = L;
+  }
+}
+
+// All epsilon (kEps) or emitting arcs of the n tokens rec[0..n), numbered from `base`.
+template <bool kEps>
+__device__ __forceinline__ void lat_expand(const LatPass &q, const int2 *rec, unsigned n, unsigned base) {
+  const int tid = threadIdx.x;
+  if (tid == 0) q.sm.n_heavy = 0;
+  __syncthreads();
+  for (unsigned i = tid; i < n; i += kBlock) {
+    const int2 tk = rec[i];
+    const int4 hd = q.g.unit[2 * (size_t)(unsigned)tk.x];
+    const int nx = (int)((unsigned)hd.w >> kPackXShift);
+    int ne = (int)((unsigned)hd.w & kPackE);
+    if (ne == (int)kPackE) ne = hd.z;
+    const int first = 2 * tk.x + 1 + (kEps ? 0 : nx), deg = kEps ? nx : ne;
+    bool mine = deg <= kLatHeavyDeg;
+    if (!mine) {
+      const int h = atomicAdd(&q.sm.n_heavy, 1);
+      if (h < kLatHeavy) q.sm.heavy[h] = (int)i; else mine = true;   // list full: this thread does it alone
+    }
+    if (mine)
+      for (int k = 0; k < deg; ++k) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
+  }
+  __syncthreads();
+  const int nh = min(q.sm.n_heavy, kLatHeavy);
+  for (int h = 0; h < nh; ++h) {
+    const unsigned i = (unsigned)q.sm.heavy[h];
+    const int2 tk = rec[i];
+    const int4 hd = q.g.unit[2 * (size_t)(unsigned)tk.x];
+    const int nx = (int)((unsigned)hd.w >> kPackXShift);
+    int ne = (int)((unsigned)hd.w & kPackE);
+    if (ne == (int)kPackE) ne = hd.z;
+    const int first = 2 * tk.x + 1 + (kEps ? 0 : nx), deg = kEps ? nx : ne;
+    for (int k = tid; k < deg; k += kBlock) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevChannels c, LatticeArgs a) {
+  __shared__ LatLds sm;
+  const int tid = threadIdx.x;
+  const int t = blockIdx.x;
+  const unsigned *off = c.frame_off + (size_t)a.ch * (c.max_frames + 2);
+  const int2 *rec = c.tokrec + (size_t)a.ch * c.lat_cap;
+  const unsigned o1 = off[t], n1 = off[t + 1] - o1;
+  const unsigned o0 = t ? off[t - 1] : 0u, n0 = t ? o1 - o0 : 0u;
+  // the set's tokens, by state id
+  for (unsigned i = tid; i < n1; i += kBlock) {
+    const int2 tk = rec[o1 + i];
+    if ((long long)(o1 + i) < a.tok_cap) {
+      a.tok_state[o1 + i] = g.unit[2 * (size_t)(unsigned)tk.x].x;
+      a.tok_cost[o1 + i] = __int_as_float(tk.y);
+    }
+  }
+  if (t > 0) {                                  // the acoustic costs the arcs into A_t were taken with
+    const long long r0 = (long long)(t - 1) * a.V;
+    if (a.ll_dtype == WFST_LOGLIKE_F32) {
+      const float *row = static_cast<const float *>(a.ll) + r0;
+      for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -row[v];
+    } else if (a.ll_dtype == WFST_LOGLIKE_F16) {
+      const _Float16 *row = static_cast<const _Float16 *>(a.ll) + r0;
+      for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -(float)row[v];
+    } else {
+      const unsigned short *row = static_cast<const unsigned short *>(a.ll) + r0;
+      for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -__uint_as_float((unsigned)row[v] << 16);
+    }
+  }
+  const bool boosted = c.st[a.ch].boost_n > 0;
+  if (boosted)
+    for (int i = tid; i < kBoostSlots; i += kBlock) {
+      sm.bk[i] = c.boost_keys[(size_t)a.ch * kBoostSlots + i];
+      sm.bv[i] = c.boost_vals[(size_t)a.ch * kBoostSlots + i];
+    }
+  const int P = max(1, (int)((n1 + kLatGroup - 1) / kLatGroup));
+  for (int p = 0; p < P; ++p) {
+    for (int sl = tid; sl < kLatSlots; sl += kBlock) sm.keys[sl] = kKeyEmpty;
+    __syncthreads();
+    for (unsigned j = tid; j < n1; j += kBlock) {
+      const int key = rec[o1 + j].x;
+      if (P > 1 && lat_group(key, P) != p) continue;
+      unsigned sl = (hash_state(key) >> 6) & (kLatSlots - 1);
+      int probes = 0;
+      while (atomicCAS(&sm.keys[sl], kKeyEmpty, key) != kKeyEmpty) {
+        if (++probes >= kLatSlots) { atomicOr(&a.ctr[1], (unsigned long long)kLatErrTable); break; }
+        sl = (sl + 1) & (kLatSlots - 1);
+      }
+      if (probes < kLatSlots) sm.pos[sl] = (unsigned short)j;
+    }
+    __syncthreads();
+    const LatPass q{g, sm, a, rec + o1, o1, t, p, P, boosted};
+    lat_expand<true>(q, rec + o1, n1, o1);
+    if (t > 0) lat_expand<false>(q, rec + o0, n0, o0);
+  }
+}
+
 }  // namespace
 
 // =================================================================================== host
@@ -1398,6 +1577,7 @@ struct wfst_decoder {
   // per-launch parameter staging (ring, so back-to-back async launches never share a slot)
   static constexpr int kRing = 8;
   int *d_params = nullptr;  int ring_pos = 0;
+  unsigned long long *d_lat_ctr = nullptr;   // lattice kernel: links found, error bits
   std::vector<int> h_params[kRing];
   // device staging for host-side outputs
   int *o_words = nullptr, *o_nwords = nullptr, *o_flags = nullptr; float *o_cost = nullptr;
@@ -1551,6 +1731,7 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
   if ((rc = dev_alloc(d, &c.frame_off, N * (size_t)(c.max_frames + 2)))) return rc;
+  if (o.keep_token_records && (rc = dev_alloc(d, &c.tokrec, N * (size_t)c.lat_cap))) return rc;
   if (o.record_digests) {
     if ((rc = dev_alloc(d, &c.dig_sum, N * (size_t)(c.max_frames + 1)))) return rc;
     if ((rc = dev_alloc(d, &c.dig_cnt, N * (size_t)(c.max_frames + 1)))) return rc;
@@ -1567,6 +1748,7 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_boost), N * (2 * kBoostSlots + 1) * sizeof(int)));
   d->boost_on_dev.assign(N, 0);
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
+  if ((rc = dev_alloc(d, &d->d_lat_ctr, (size_t)2))) return rc;
   if (o.outputs_on_host) {
     if ((rc = dev_alloc(d, &d->o_words, N * (size_t)o.max_words))) return rc;
     if ((rc = dev_alloc(d, &d->o_nwords, N))) return rc;
@@ -1838,6 +2020,50 @@ int32_t wfst_debug_frame_digests(wfst_decoder *d, int32_t ch, uint64_t *digest, 
   const size_t base = (size_t)ch * (d->c.max_frames + 1);
   HIP_TRY(d, hipMemcpy(digest, d->c.dig_sum + base, m * sizeof(uint64_t), hipMemcpyDeviceToHost));
   HIP_TRY(d, hipMemcpy(count, d->c.dig_cnt + base, m * sizeof(int), hipMemcpyDeviceToHost));
+  return WFST_OK;
+}
+
+int32_t wfst_get_lattice(wfst_decoder *d, int32_t ch, const void *loglikes, float lattice_beam,
+                         int32_t *tok_state, float *tok_cost, int64_t tok_cap, int64_t *frame_off,
+                         wfst_lattice_link *links, int64_t link_cap,
+                         int64_t *n_tokens, int64_t *n_links, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  if (!d->c.tokrec) return fail(d, WFST_ERR_INVALID_ARG, "the decoder was created without keep_token_records");
+  if (!frame_off || !n_tokens || !n_links || tok_cap < 0 || link_cap < 0 || (tok_cap && (!tok_state || !tok_cost)) ||
+      (link_cap && !links))
+    return fail(d, WFST_ERR_INVALID_ARG, "null output or negative capacity");
+  if (!(lattice_beam >= 0.0f)) return fail(d, WFST_ERR_INVALID_ARG, "lattice_beam must be >= 0");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ChanState s;
+  HIP_TRY(d, hipMemcpyAsync(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  if (s.status & (kStLattice | kStCapacity))
+    return fail(d, WFST_ERR_CAPACITY, "the channel stopped on an overflow: its token sets are incomplete");
+  const int f = s.frame;
+  if (f > 0 && !loglikes) return fail(d, WFST_ERR_INVALID_ARG, "null loglikes");
+  std::vector<unsigned> off((size_t)f + 2);
+  HIP_TRY(d, hipMemcpyAsync(off.data(), d->c.frame_off + (size_t)ch * (d->c.max_frames + 2), off.size() * sizeof(unsigned),
+                            hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipMemsetAsync(d->d_lat_ctr, 0, 2 * sizeof(unsigned long long), st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  for (int t = 0; t <= f + 1; ++t) frame_off[t] = (int64_t)off[t];
+  *n_tokens = (int64_t)off[(size_t)f + 1];
+  LatticeArgs a{};
+  a.ch = ch; a.frames = f; a.ll = loglikes; a.V = d->V; a.ll_dtype = d->opts.loglike_dtype;
+  a.lattice_beam = lattice_beam;
+  a.tok_state = tok_state; a.tok_cost = tok_cost; a.tok_cap = tok_cap;
+  a.links = links; a.link_cap = link_cap; a.ctr = d->d_lat_ctr;
+  hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
+  HIP_TRY(d, hipGetLastError());
+  unsigned long long ctr[2] = {0, 0};
+  HIP_TRY(d, hipMemcpyAsync(ctr, d->d_lat_ctr, sizeof(ctr), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  *n_links = (int64_t)ctr[0];
+  if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
+  if (*n_tokens > tok_cap || *n_links > link_cap)
+    return fail(d, WFST_ERR_CAPACITY, "lattice needs room for " + std::to_string(*n_tokens) + " tokens and " +
+                                          std::to_string(*n_links) + " links");
   return WFST_OK;
 }
 

@@ -1,0 +1,191 @@
+"""GPU parity of the lattice output (wfst_get_lattice) against the oracle's lattice links.
+
+Bar: the token numbering may differ, everything else is bit-exact: per frame the same multiset
+of (state, cost bits) tokens, and the same multiset of links
+(frame, source state, destination state, ilabel, olabel, weight bits, cost bits).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+INF = float("inf")
+IMAX = 2**31 - 1
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch
+
+
+def _sorted_rows(cols):
+    rows = np.stack([np.asarray(c).astype(np.int64) for c in cols], axis=1)
+    return rows[np.lexsort(rows.T[::-1])]
+
+
+def oracle_rows(o, g, L):
+    gids, inv = np.unique(L.arc, return_inverse=True)
+    orig = np.array([o.original_arc(int(a)) for a in gids], dtype=np.int64)[inv] if len(gids) else np.zeros(0, np.int64)
+    return _sorted_rows([L.frame, L.states[L.src_global()], L.states[L.dst_global()], g.ilabel[orig], g.olabel[orig],
+                         g.weight[orig].view(np.uint32), L.cost.view(np.uint32)])
+
+
+def gpu_rows(lat):
+    k = lat.links
+    return _sorted_rows([k["frame"], lat.state[k["src"]], lat.state[k["dst"]], k["ilabel"], k["olabel"],
+                         k["graph_cost"].view(np.uint32), k["cost"].view(np.uint32)])
+
+
+def check_lattice(torch, g, ll, length, beam, ma, lattice_beam, boost=None, hint=None, dtype="float32",
+                  streaming_chunk=None):
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    o = Oracle(g)
+    lld = torch.from_numpy(np.ascontiguousarray(ll[None, :max(length, 1)])).to(getattr(torch, dtype)).cuda()
+    ll_ref = lld[0].float().cpu().numpy()
+    L = o.lattice(ll_ref, length, beam=beam, max_active=ma, lattice_beam=lattice_beam, boost=boost)
+    dec = Decoder(g, max_channels=1, max_frames=max(length, 1), max_active_hint=hint or min(ma, 20000),
+                  keep_token_records=True, loglike_dtype=dtype)
+    if streaming_chunk is None:
+        dec.decode_batch(lld, [length], beam, ma, boosts=None if boost is None else [boost])
+    else:
+        dec.init_channel(0, beam, ma, boost=boost)
+        for t0 in range(0, length, streaming_chunk):
+            n = min(streaming_chunk, length - t0)
+            dec.advance_chunk([0], lld[:, t0:t0 + n].contiguous(), [n])
+    lat = dec.get_lattice(0, lld[0, :length].contiguous(), lattice_beam)
+    dec.close()
+    assert lat.frame_off.tolist() == L.set_off.tolist()
+    for t in range(length + 1):
+        a, b = int(L.set_off[t]), int(L.set_off[t + 1])
+        got = sorted(zip(lat.state[a:b].tolist(), lat.cost[a:b].view(np.uint32).tolist()))
+        want = sorted(zip(L.states[a:b].tolist(), L.costs[a:b].view(np.uint32).tolist()))
+        assert got == want, f"token set of frame {t} differs"
+    want, got = oracle_rows(o, g, L), gpu_rows(lat)
+    assert got.shape == want.shape, f"{len(got)} links, the oracle has {len(want)}"
+    assert (got == want).all(), f"links differ first at sorted row {np.nonzero((got != want).any(axis=1))[0][0]}"
+    k = lat.links
+    emit = k["ilabel"] != 0
+    src_frame = np.searchsorted(lat.frame_off, k["src"], side="right") - 1
+    dst_frame = np.searchsorted(lat.frame_off, k["dst"], side="right") - 1
+    assert (dst_frame == k["frame"]).all() and (src_frame == k["frame"] - emit).all()
+    ac = np.zeros(len(k), np.float32)
+    ac[emit] = -ll_ref[k["frame"][emit] - 1, k["ilabel"][emit] - 1]
+    assert (k["acoustic_cost"].view(np.uint32) == ac.view(np.uint32)).all()
+    return lat, L
+
+
+def test_lattice_on_micro_graphs(torch_cuda):
+    """Ties, negative epsilon weights, a start state with epsilon arcs, boosts, three lattice beams."""
+    from workloads import micro_graph
+    from workloads.graphs import Graph
+    for seed in range(12):
+        rng = np.random.default_rng(400 + seed)
+        V, T = 3, int(rng.integers(1, 9))
+        g = micro_graph(700 + seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+        if seed % 2:
+            g = Graph(g.num_states, g.num_states - 1, V, g.row_offsets, g.next_state, g.ilabel, g.olabel, g.weight,
+                      g.final_cost, {})
+        ll = -(rng.integers(0, 40, size=(T, V)).astype(np.float32) / 8.0)
+        boost = None if seed % 3 else (rng.choice(5, size=3, replace=False).astype(np.int32) + 1,
+                                       -(rng.integers(1, 9, size=3).astype(np.float32) / 4.0))
+        for beam, ma in ((INF, IMAX), (3.0, 6)):
+            for lb in (0.0, 1.5, INF):
+                check_lattice(torch_cuda, g, ll, T, beam, ma, lb, boost=boost, hint=1000)
+
+
+def test_lattice_c1(torch_cuda, c1):
+    lat, L = check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, 2.0)
+    assert len(lat.links) > len(lat.state)
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, INF)
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 37, 4.0, 50, 0.0)
+
+
+def test_lattice_of_a_streamed_channel_and_sixteen_bit_rows(torch_cuda, c1):
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, 3.0, streaming_chunk=16)
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 60, c1.beam, c1.max_active, 3.0, dtype="float16")
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 60, c1.beam, c1.max_active, 3.0, dtype="bfloat16")
+
+
+def test_lattice_c2_utterance(torch_cuda, c2):
+    b = int(np.argmin(np.abs(c2.lengths - 120)))
+    check_lattice(torch_cuda, c2.graph, c2.loglikes[b], int(min(c2.lengths[b], 120)), c2.beam, c2.max_active, 4.0)
+
+
+def test_token_sets_larger_than_one_lookup_table(torch_cuda):
+    """30,000 active tokens per frame: the set is looked up in several passes over hash groups."""
+    from workloads import ctc_loglikes, dense_graph
+    g = dense_graph(17, 30000, 4, 12)
+    ll = ctc_loglikes(17, np.array([11], np.int32), 11, 12, sigma=1.0, p_blank=0.5, blank_boost=2.0, token_boost=1.0)[0]
+    lat, _ = check_lattice(torch_cuda, g, ll, 11, 60.0, 100000, 6.0, hint=32768)
+    assert np.diff(lat.frame_off).max() > 16384
+
+
+def test_states_with_many_arcs(torch_cuda):
+    """1,200 tokens of 600 arcs (more than the list of shared tokens holds) and a state with
+    1.1 million arcs."""
+    from workloads import ctc_loglikes, dense_graph, giant_state_graph
+    g = dense_graph(7, 1200, 600, 12)
+    ll = ctc_loglikes(11, np.array([4], np.int32), 4, 12, sigma=1.0, p_blank=0.5, blank_boost=2.0, token_boost=1.0)[0]
+    check_lattice(torch_cuda, g, ll, 4, 30.0, 100000, 1.0, hint=100000)
+    g = giant_state_graph(8, 1_100_000, 3000, 12)
+    check_lattice(torch_cuda, g, ll, 4, 30.0, 100000, 3.0, hint=131072)
+
+
+def test_epsilon_layers(torch_cuda):
+    from workloads import ctc_loglikes, eps_layers_graph
+    g = eps_layers_graph(9, 3000, 12)
+    ll = ctc_loglikes(13, np.array([6], np.int32), 6, 12, sigma=1.0, p_blank=0.5, blank_boost=2.0, token_boost=1.0)[0]
+    check_lattice(torch_cuda, g, ll, 6, 30.0, 100000, 2.0, hint=20000)
+    check_lattice(torch_cuda, g, ll, 6, 2.0, 500, INF, hint=20000)
+
+
+def test_nbest_of_the_lattice_equals_exhaustive_enumeration(torch_cuda):
+    """Unpruned micro graphs, lattice beam +inf: the n least path costs through the GPU's lattice
+    (with final costs) are those of all paths of the graph."""
+    from workloads import micro_graph
+    from checkers import all_paths
+    for seed in range(10):
+        rng = np.random.default_rng(1200 + seed)
+        S, V, T = int(rng.integers(3, 8)), 3, int(rng.integers(1, 5))
+        g = micro_graph(330 + seed, num_states=S, num_classes=V, max_deg=3, dyadic=True, p_eps=0.3)
+        ll = -(rng.integers(0, 40, size=(T, V)).astype(np.float32) / 8.0)
+        lat, _ = check_lattice(torch_cuda, g, ll, T, INF, IMAX, INF, hint=1000)
+        paths = all_paths(g, ll)
+        fin = g.final_cost.astype(np.float64)
+        any_final = any(np.isfinite(fin[s]) for _, s in paths.values())
+        want = sorted(c + (fin[s] if any_final else 0.0) for c, s in paths.values() if not any_final or np.isfinite(fin[s]))
+        got = lat.nbest(len(want) + 5, g.start_state, g.final_cost if any_final else None)
+        assert [c for c, _, _ in got] == want    # dyadic costs: exact in fp64
+        for c, links, words in got[:3]:          # the links of a path chain from the start token
+            tok = lat.start_token(g.start_state)
+            for k in links:
+                assert lat.links["src"][k] == tok
+                tok = int(lat.links["dst"][k])
+
+
+def test_lattice_errors(torch_cuda, c1):
+    from paper_2311_04996_amd import Decoder, WfstError
+    torch = torch_cuda
+    ll = torch.from_numpy(c1.loglikes).cuda()
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active)
+    dec.decode_batch(ll, c1.lengths, c1.beam, c1.max_active)
+    with pytest.raises(WfstError, match="keep_token_records"):
+        dec.get_lattice(0, ll[0], 1.0)
+    dec.close()
+    dec = Decoder(c1.graph, max_channels=1, max_frames=100, max_active_hint=c1.max_active, keep_token_records=True)
+    dec.decode_batch(ll, c1.lengths, c1.beam, c1.max_active)
+    for bad in (-1.0, float("nan")):
+        with pytest.raises(WfstError, match="lattice_beam"):
+            dec.get_lattice(0, ll[0], bad)
+    with pytest.raises(WfstError, match="channel"):
+        dec.get_lattice(3, ll[0], 1.0)
+    with pytest.raises(WfstError, match="needs room for"):
+        dec.get_lattice(0, ll[0], 1.0, tok_cap=10, link_cap=10)
+    full = dec.get_lattice(0, ll[0], 1.0)
+    again = dec.get_lattice(0, ll[0], 1.0, tok_cap=len(full.state), link_cap=len(full.links))
+    assert (gpu_rows(full) == gpu_rows(again)).all()
+    dec.close()

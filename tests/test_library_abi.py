@@ -34,6 +34,14 @@ def test_binding_lists_the_same_names():
     assert sorted(EXPORTS) == declared_functions()
 
 
+def test_link_record_layout():
+    import numpy as np
+    from paper_2311_04996_amd.binding import LINK_DTYPE, wfst_lattice_link
+    assert ctypes.sizeof(wfst_lattice_link) == 32 == LINK_DTYPE.itemsize
+    for name, _ in wfst_lattice_link._fields_:
+        assert getattr(wfst_lattice_link, name).offset == LINK_DTYPE.fields[name][1]
+
+
 def test_null_arguments_are_errors_not_crashes(lib):
     h = ctypes.c_void_p()
     assert lib.wfst_decoder_create(None, None, ctypes.byref(h)) == -1
