@@ -1244,10 +1244,16 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   for (int i = tid; i < n; i += kBlock)
     if (Q[i].x == best_state) sm.sel_idx = i;
   __syncthreads();
+  // One lane follows the backpointers.  The words come out last to first: they go into a ring
+  // in LDS (the recombination table is idle now) that keeps the latest max_words of them, i.e.
+  // the first max_words of the path, and all lanes then write them out in path order.  Only
+  // when max_words exceeds the ring is the chain walked twice (count, then write).
+  int *ring = sm.u.t.keys;
+  const bool one_walk = a.max_words <= kTabSlots;
   if (tid == 0) {
     int nw = 0;
     bool broken = false;
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = one_walk ? 1 : 0; pass < 2; ++pass) {
       int f = x.s.frame, i = sm.sel_idx, k = 0;
       for (unsigned step = 0;; ++step) {
         // every chain ends at the start token; the bounds only guard against a damaged lattice
@@ -1258,7 +1264,8 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
         if (bp.y < 0) break;
         const int ol = x.g.unit[(unsigned)bp.y & kArcMask].w;
         if (ol != 0) {
-          if (pass == 1) { const int pos = nw - 1 - k; if (pos < a.max_words) words[pos] = ol; }
+          if (one_walk) ring[k % a.max_words] = ol;
+          else if (pass == 1) { const int pos = nw - 1 - k; if (pos < a.max_words) words[pos] = ol; }
           ++k;
         }
         i = bp.x;
@@ -1273,6 +1280,12 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     a.cost[io] = ord2f((unsigned)(best >> 32));
     a.flags[io] = flags;
     sm.red64 = 0;
+    sm.sel_idx = nw;
+  }
+  __syncthreads();
+  if (one_walk) {
+    const int nw = sm.sel_idx;                   // word k of the walk (0 = last word) sits in ring[k % max_words]
+    for (int p = tid; p < min(nw, a.max_words); p += kBlock) words[p] = ring[(nw - 1 - p) % a.max_words];
   }
   __syncthreads();
 }
