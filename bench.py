@@ -238,7 +238,7 @@ def main():
     # the timed region proper: `pipeline` batches in flight
     wall = run_steps(len(decs), args.steps, False)[0] if len(decs) > 1 else wall_one
     names = ["expand_tail", "select", "tokens", "eps_expand", "eps_round_end", "publish", "trace", "other",
-             "tab_clear", "tab_fill", "tab_winners", "eps_table", "eps_apply", "expand_arcs", "-", "-"]
+             "tab_clear", "tab_fill", "tab_winners", "eps_table", "eps_new_tokens", "expand_arcs", "eps_meet", "-"]
     print("[bench] phase share of workgroup time (one batch in flight): " +
           ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks) if t) +
           f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / args.steps:.1f} ms",

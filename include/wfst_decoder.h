@@ -232,9 +232,10 @@ int32_t wfst_get_counters(wfst_decoder *dec, int64_t counters[8], int32_t reset)
  *   [0] ExpandArcs over emitting arcs, [1] recombination, [2] cutoff + compaction,
  *   [3] epsilon expansion, [4] epsilon recombination, [5] publishing the token set,
  *   [6] final choice + traceback, [7] everything else (row staging, init);
- *   [8..12] split of [1] and [4]: table clear, fill, scan; epsilon table clear+fill, scan
- *   (these are counted instead of, not on top of, [1] and [4]); [13], [14] split of [0]: chunk
- *   set-up, arc loop; [15] is not a time: the number of frames whose recombination had to be
+ *   [8..12] split of [1] and [4]: table clear, fill, winners; epsilon table clear+fill, new
+ *   tokens out of the table (these are counted instead of, not on top of, [1] and [4]);
+ *   [13] the arc loops of [0]; [14] epsilon closure: the set's tokens looking their states up
+ *   in the table; [15] is not a time: the number of frames whose recombination had to be
  *   redone with every candidate selected.
  */
 int32_t wfst_debug_phase_ticks(wfst_decoder *dec, int64_t ticks[16], int32_t reset);

@@ -17,9 +17,10 @@
 // table that lives in LDS (160 KB per CU on gfx950) with LDS compare-and-swap, in as many
 // passes (a region, or a hash range of it) as the table needs.  After a pass every inserted
 // candidate looks at its slot again: the one still there is the recombined token of its
-// destination ("winner") and carries its own record on; nobody scans the table.  A dense
-// index by state block (tagged with the frame epoch, so it never needs clearing) answers
-// "does this state already have a token" for the epsilon closure.
+// destination ("winner") and carries its own record on; nobody scans the table.  In the
+// epsilon closure "does this state already have a token" is answered the other way round: the
+// tokens of the set look their own state up in the round's table, so there is no state -> token
+// index in memory at all.
 //
 // ExpandArcs has no block-wide barrier: every wave takes runs of 64 tokens from a counter in
 // LDS and expands them on its own (first arc by the owning lane, the other arcs flattened
@@ -34,8 +35,8 @@
 // bytes.  The packed word sits right before the first arc, so ONE 16-byte load at byte 12 of a
 // block brings the degrees and next/weight/ilabel of the first arc.  A state is
 // named by its block number (byte offset / 32), which is also the recombination key and grows
-// with the state id.  `next` of an arc is the destination's block number plus two flag bits
-// (the destination has epsilon arcs / an epsilon arc enters it), so a token is created from
+// with the state id.  `next` of an arc is the destination's block number plus a flag bit
+// (the destination has epsilon arcs), so a token is created from
 // the arc alone and the only random graph read per token is the 32-byte header + first arc
 // when the token is expanded.  An arc's id is its unit address (epsilon arcs have bit 30 set),
 // which orders arcs exactly as (emitting before epsilon, state, position) does.
@@ -44,7 +45,6 @@
 //   token queue   2 x qcap records {block number, cost}
 //   candidates    cand_cap records {next (block number + flags), cost, source token, arc id}
 //   winners       recombined in-beam tokens before the max-active cutoff is known
-//   state index   one 4-byte entry per 32 bytes of graph: (epoch tag << 16) | token index
 //   worklists     2 x qcap records {token, block number, cost, first time}
 //   lattice       {prev token, arc id} per stored token, frame after frame
 // LDS holds, per phase, either the expansion tables (negated log-likelihood row, a slice per
@@ -107,14 +107,13 @@ constexpr int kGroupTarget = kTabSlots * 12 / 16; // mean candidates reduced per
 #endif
 constexpr int kBoostSlots = WFST_BOOST;       // per-channel word-boost table (open addressing)
 constexpr int kBoostMax = kBoostSlots / 2;    // entries it may hold
-constexpr int kQueueMax = 65536;              // token index is 16 bits in the state index
+constexpr int kQueueMax = 65536;              // tokens per closed set
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
 constexpr unsigned kOrdNone = 0xFFFFFFFFu;
 constexpr int kModeInit = 1, kModeFinal = 2;
 constexpr unsigned kKeyMask = 0x1fffffffu;     // block number of a state (32-byte units)
 constexpr unsigned kFlagHasEps = 0x80000000u;  // `next` of an arc: the destination has epsilon arcs
-constexpr unsigned kFlagEpsIn = 0x40000000u;   //                   an epsilon arc enters the destination
 constexpr unsigned kArcEps = 0x40000000u;      // arc ids: unit address, plus this bit for epsilon arcs
 constexpr unsigned kArcMask = 0x3fffffffu;
 constexpr unsigned kPackE = 0xFFFFFu;          // header word 3: emitting degree (20 bits, all ones = see word 2)
@@ -130,7 +129,6 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   unsigned lat_used;          // lattice entries in use
   int max_active;
   float beam, scale;          // scale = 256 / beam, computed once on the host
-  unsigned epoch;             // closed sets published since create (tags the state index)
   float sel_ratio;            // candidates taken into recombination per max_active (adaptive)
   int boost_n;                // entries of the channel's word-boost table (0 = none); set by the host
 };
@@ -138,7 +136,7 @@ struct ChanState {            // persists between calls (the per-stream decoder 
 struct DevGraph {
   const int4 *unit;           // state blocks: header {state id, final cost, emitting degree, packed degrees},
                               // epsilon arcs, emitting arcs {next, weight bits, ilabel, olabel}
-  unsigned n_blk;             // 32-byte blocks in `unit` (the state index has one entry per block)
+  unsigned n_blk;             // 32-byte blocks in `unit`
   unsigned start;             // start state: block number + flags, like `next` of an arc
   int has_final;              // 0: every state is final with cost 0
   int S;
@@ -150,7 +148,6 @@ struct DevChannels {
   int4 *win;        int win_cap;               // recombined tokens before the max-active cutoff (their candidate records)
   int2 *queue;      int qcap;                  // 2 buffers {block number, cost}
   int4 *wl;                                    // 2 buffers {token, block number, cost, 1 = new token}
-  unsigned *index;                             // [n_blk] (epoch tag << 16) | token index
   int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
   int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
   unsigned *frame_off; int max_frames;
@@ -312,7 +309,7 @@ struct Cutoff {
 struct Ctx {                  // block-uniform view of one channel
   const DevGraph &g; const DevChannels &c; Smem &sm;
   int4 *cand; int4 *win;
-  int2 *q0; int4 *wl0; unsigned *index; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
+  int2 *q0; int4 *wl0; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
 };
@@ -331,7 +328,7 @@ __device__ __forceinline__ float boost_of(const Smem &sm, int word) {
 
 // Phase timing with the constant-rate wall clock (thread 0 only; a few scalar reads per frame).
 enum { kPhExpand = 0, kPhSelect, kPhCutoff, kPhEpsExpand, kPhEpsRecombine, kPhFinish, kPhTrace, kPhOther,
-       kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan, kPhExpSetup, kPhExpLoop };
+       kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan, kPhExpSetup, kPhEpsMeet };
 __device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
   if (threadIdx.x == 0) {
     const long long now = (long long)wall_clock64();
@@ -340,8 +337,6 @@ __device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
   }
 }
 
-// Tag of the token set under construction; 0 is never a valid tag (the index starts zeroed).
-__device__ __forceinline__ unsigned set_tag(unsigned epoch) { return epoch % 65535u + 1u; }
 
 // Block-wide exclusive scan of N values per thread (thread t owns items N*t ..).
 // Returns the total; ex[k] receives the exclusive prefix of the thread's k-th item.
@@ -797,8 +792,7 @@ __device__ __forceinline__ int total_candidates(const Ctx &x) {
 
 // ------------------------------------------------------------------ token creation
 // New tokens of the set under construction (N per lane), made from the winning arc alone:
-// queue record, backpointer, state index entry if an epsilon arc can enter the state (only
-// those are ever looked up), and an entry in the next epsilon worklist if the state has
+// queue record, backpointer, and an entry in the next epsilon worklist if the state has
 // epsilon arcs.  next[] is the arc's destination with its flag bits.  `also[]` appends
 // existing tokens (tok[]) that were improved and must be expanded again.  Called by all
 // lanes of the wave.
@@ -806,7 +800,7 @@ template <int N>
 __device__ __forceinline__ void make_tokens(Ctx &x, const int (&make)[N], const int (&ti)[N], const int (&next)[N],
                                             const int (&costbits)[N], const int (&prev)[N], const int (&arc)[N],
                                             const int (&also)[N], const int (&tok)[N],
-                                            int2 *NQ, unsigned lat_base, int4 *WLN, unsigned tag16) {
+                                            int2 *NQ, unsigned lat_base, int4 *WLN) {
   int want[2 * N]; int wi[2 * N];
 #pragma unroll
   for (int u = 0; u < N; ++u) {
@@ -815,7 +809,6 @@ __device__ __forceinline__ void make_tokens(Ctx &x, const int (&make)[N], const 
     if (make[u]) {
       NQ[ti[u]] = make_int2(key, costbits[u]);
       x.lat[lat_base + ti[u]] = make_int2(prev[u], arc[u]);
-      if ((unsigned)next[u] & kFlagEpsIn) x.index[key] = tag16 | (unsigned)ti[u];
     }
     want[u] = make[u] & (int)has_eps;
     want[N + u] = also[u] & (int)has_eps;
@@ -963,7 +956,6 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   prof_mark(sm, kPhOther);
 
   // ---- 4. survivors become tokens
-  const unsigned tag16 = set_tag(x.s.epoch) << 16;
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kUC) {
     int kp[kUC]; int4 cr[kUC];
@@ -984,7 +976,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       }
       st[u] = cr[u].x; cb[u] = cr[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
     }
-    make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN, tag16);
+    make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN);
   }
   __syncthreads();
   if (tid == 0) sm.ctr[kCtKept] += min(sm.n_next, x.c.qcap);
@@ -996,16 +988,17 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
 // ------------------------------------------------------------------ epsilon closure
 // Least fixpoint under the frozen predicate `cut`.  The worklist holds the tokens created
 // or improved in the previous round that have epsilon arcs, with their arc ranges.  Each
-// round's candidates are recombined in the LDS table; the per-destination best is compared
-// with the state's existing token (found through the state index) and updates it in place
-// or becomes a new token; either way that token is expanded in the next round.
+// round's candidates are recombined in the LDS table; then the tokens the set already has look
+// their own state up in the table: a token whose state is there is compared with the
+// per-destination best, takes its cost and backpointer if that is better, and removes the entry;
+// what is left in the table are destinations without a token, which become new tokens.  Either
+// way the token is expanded in the next round.
 // On entry WL0 = x.wl0 + sel*qcap holds n_wl entries.
 __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
   Smem &sm = x.sm;
   EpsLds &ek = sm.ek;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
-  const unsigned tag = set_tag(x.s.epoch);
   const bool boosted = x.s.boost_n > 0;
   int n_wl = uni(min(sm.n_wl_next, x.c.qcap));
   __syncthreads();
@@ -1088,55 +1081,70 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         __syncthreads();
       }
       prof_mark(sm, kPhEpsTabFill);
-      // the winners of the pass apply themselves: per destination, the winning candidate is
-      // compared with the state's existing token, found through the state index
+      // the tokens of the set meet the table: each looks its own state up; if the pass has a
+      // best candidate for it, the better of the two stays the state's token (cost, then arc id)
+      // and the entry is taken out, so that only destinations without a token remain
+      __syncthreads();
+      {
+        const int n_have = uni(min(sm.n_next, x.c.qcap));
+        for (int i0 = 0; i0 < n_have; i0 += kBlock * kU) {
+          int improve[kU], tok[kU], none[kU], nx[kU], cb[kU], pv[kU], ar[kU]; int2 tk[kU];
+#pragma unroll
+          for (int k = 0; k < kU; ++k) { tok[k] = i0 + k * kBlock + tid; tk[k] = NQ[min(tok[k], n_have - 1)]; }
+#pragma unroll
+          for (int k = 0; k < kU; ++k) {
+            improve[k] = 0; none[k] = 0; nx[k] = 0; cb[k] = 0; pv[k] = 0; ar[k] = 0;
+            unsigned sl = (hash_state(tk[k].x) >> 6) & kTabMask;
+            int probes = 0, key = tok[k] < n_have ? t.keys[sl] : kKeyEmpty;
+            while (key != tk[k].x && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
+            if (key == tk[k].x && tok[k] < n_have) {
+              const unsigned long long v = t.vals[sl];
+              t.vals[sl] = kValEmpty;                      // this destination has its token
+              const float nc = ord2f((unsigned)(v >> 32)), oc = __int_as_float(tk[k].y);
+              bool better = (nc < oc) & (v != kValEmpty);
+              if (nc == oc && v != kValEmpty) better = (unsigned)x.cand[(unsigned)v].w < (unsigned)x.lat[lat_base + tok[k]].y;
+              if (better) {                                  // new cost and backpointer in place, expand again
+                const int4 rec = x.cand[(unsigned)v];
+                NQ[tok[k]].y = rec.y;
+                x.lat[lat_base + tok[k]] = make_int2(rec.z, rec.w);
+                improve[k] = 1; nx[k] = rec.x; cb[k] = rec.y;
+              }
+            }
+          }
+          make_tokens<kU>(x, none, tok, nx, cb, pv, ar, improve, tok, NQ, lat_base, WLN);
+        }
+      }
+      __syncthreads();
+      prof_mark(sm, kPhEpsMeet);
+      // the winners left in the table become new tokens
       int pos0 = 0;
       for (int r = r0; r < r1; ++r) {
         const int n = uni(min(sm.n_reg[r], x.c.region_cap));
         const int base = r * x.c.region_cap;
         for (int i0 = 0; i0 < n; i0 += kBlock * kU) {
-          int4 rec[kU]; unsigned ix[kU]; int tok[kU];
-          float oc[kU]; unsigned oa[kU]; int occ[kU], exists[kU];
+          int4 rec[kU]; int fresh[kU];
 #pragma unroll
           for (int k = 0; k < kU; ++k) {
             const int i = i0 + k * kBlock + tid;
             int slot = -1;
             if (i < n) slot = slot_of_candidate<false>(x, pos0 + i, base + i, g, G, cut, 256);
-            occ[k] = (int)(slot >= 0);
-            if (occ[k]) occ[k] = (int)((unsigned)t.vals[slot] == (unsigned)(base + i));
-            rec[k] = make_int4(0, 0, 0, 0); ix[k] = 0;
-            if (occ[k]) { rec[k] = x.cand[base + i]; ix[k] = x.index[t.keys[slot]]; }
+            fresh[k] = (int)(slot >= 0);
+            if (fresh[k]) fresh[k] = (int)((unsigned)t.vals[slot] == (unsigned)(base + i));
+            rec[k] = make_int4(0, 0, 0, 0);
+            if (fresh[k]) rec[k] = x.cand[base + i];
           }
-#pragma unroll
-          for (int k = 0; k < kU; ++k) {
-            exists[k] = occ[k] & (int)((ix[k] >> 16) == tag);
-            tok[k] = (int)(ix[k] & 0xffffu);
-            oc[k] = 0.0f; oa[k] = 0;
-            if (exists[k]) { oc[k] = __int_as_float(NQ[tok[k]].y); oa[k] = (unsigned)x.lat[lat_base + tok[k]].y; }
-          }
-          int fresh[kU], improve[kU], good[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
-#pragma unroll
-          for (int k = 0; k < kU; ++k) {
-            const float nc = __int_as_float(rec[k].y);
-            improve[k] = exists[k] & ((int)(nc < oc[k]) | ((int)(nc == oc[k]) & (int)((unsigned)rec[k].w < oa[k])));
-            fresh[k] = occ[k] & (int)!exists[k];
-          }
+          int good[kU], no[kU]; int ni[kU], cb[kU], pv[kU], ar[kU], nx[kU];
           wave_alloc_n<kU>(&sm.n_next, fresh, ni);
 #pragma unroll
           for (int k = 0; k < kU; ++k) {
-            good[k] = fresh[k];
+            good[k] = fresh[k]; no[k] = 0;
             if (fresh[k]) {
               if (ni[k] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[k] = false; }
               else if (lat_base + (unsigned)ni[k] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[k] = false; }
             }
-            // an existing token that got better: new cost and backpointer in place, expand again
-            if (improve[k]) {
-              NQ[tok[k]].y = rec[k].y;
-              x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
-            }
             cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w; nx[k] = rec[k].x;
           }
-          make_tokens<kU>(x, good, ni, nx, cb, pv, ar, improve, tok, NQ, lat_base, WLN, tag << 16);
+          make_tokens<kU>(x, good, ni, nx, cb, pv, ar, no, ni, NQ, lat_base, WLN);
         }
         pos0 += (n + kBlock - 1) / kBlock * kBlock;
       }
@@ -1191,19 +1199,9 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
   x.s.lat_used = lat_base + (unsigned)n;
   x.s.n_tok = n;
   x.s.cur ^= 1;
-  x.s.epoch++;
   const bool stop = uni(sm.status) != 0;     // nobody writes status between these two barriers
   __syncthreads();
   return stop;
-}
-
-// The state index is tagged with epoch % 65535 + 1: when the tag is about to repeat, entries
-// written 65535 sets ago would look current again, so the whole index is zeroed first.
-__device__ __forceinline__ void renew_index_if_wrapping(Ctx &x) {
-  if (x.s.epoch != 0 && x.s.epoch % 65535u == 0) {
-    for (unsigned s = threadIdx.x; s < x.g.n_blk; s += kBlock) x.index[s] = 0;
-    __syncthreads();
-  }
 }
 
 // ------------------------------------------------------------------ final choice + traceback
@@ -1300,7 +1298,6 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.win = c.win + (size_t)ch * c.win_cap;
   x.q0 = c.queue + (size_t)ch * 2 * c.qcap;
   x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
-  x.index = c.index + (size_t)ch * g.n_blk;
   x.lat = c.lattice + (size_t)ch * c.lat_cap;
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
@@ -1308,7 +1305,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.s = c.st[ch];
   x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
-  x.s.scale = uni(x.s.scale); x.s.epoch = uni(x.s.epoch); x.s.sel_ratio = uni(x.s.sel_ratio);
+  x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio);
   x.s.boost_n = uni(x.s.boost_n);
   if (x.s.boost_n > 0)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
@@ -1332,13 +1329,12 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     // start token, closed over epsilon arcs with best = 0 and no bin limit
     x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
-    renew_index_if_wrapping(x);
     int2 *NQ = x.q0 + c.qcap;
     if (tid == 0) sm.n_next = 1;
     {
       const int mk[1] = {tid == 0}, no[1] = {false};
       const int z[1] = {0}, st[1] = {(int)g.start}, m1[1] = {-1};
-      make_tokens<1>(x, mk, z, st, z, m1, m1, no, z, NQ, 0u, x.wl0, set_tag(x.s.epoch) << 16);
+      make_tokens<1>(x, mk, z, st, z, m1, m1, no, z, NQ, 0u, x.wl0);
     }
     __syncthreads();
     Cutoff cut{0.0f, x.s.beam, x.s.scale, 256};
@@ -1350,7 +1346,6 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   for (int t = 0; t < nfr; ++t) {
     if (stop || x.s.status) break;
     if (x.s.frame >= c.max_frames) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
-    renew_index_if_wrapping(x);
     {
       // the frame's acoustic costs; 16-bit log-likelihoods are widened exactly
       const long long r0 = ll0 + (long long)t * a.V;
@@ -1393,7 +1388,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     // copies, so that the pointers of the frame loop above never live in memory: only then
     // does the compiler know they are global and keep them in registers.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
-    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.index, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
+    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
     select_and_trace(x2, a2, io);
   }
   prof_mark(sm, kPhTrace);
@@ -1675,7 +1670,7 @@ int validate_graph(const wfst_graph_csr *g, std::string &why, int64_t &Ae, int64
 // Lay the graph out as state blocks (see the top of this file).
 int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
   const int32_t S = g->num_states;
-  std::vector<char> eps_in(S, 0), has_eps(S, 0);
+  std::vector<char> has_eps(S, 0);
   std::vector<unsigned> &blk = d->blk_of_state;
   blk.assign((size_t)S + 1, 0);
   uint64_t units = 0;
@@ -1685,10 +1680,10 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
     units += n + (n & 1);
     if (units / 2 > (uint64_t)kKeyMask) return fail(d, WFST_ERR_BAD_GRAPH, "graph larger than 2^29 blocks of 32 bytes");
     for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i)
-      if (g->ilabel[i] == 0) { eps_in[g->next_state[i]] = 1; has_eps[s] = 1; }
+      if (g->ilabel[i] == 0) has_eps[s] = 1;
   }
   blk[S] = (unsigned)(units / 2);
-  auto named = [&](int32_t s) { return blk[s] | (has_eps[s] ? kFlagHasEps : 0u) | (eps_in[s] ? kFlagEpsIn : 0u); };
+  auto named = [&](int32_t s) { return blk[s] | (has_eps[s] ? kFlagHasEps : 0u); };
   std::vector<int4> unit(units, make_int4(0, 0, 0, 0));
   bool all_zero = true;
   for (int32_t s = 0; s < S; ++s) {
@@ -1739,7 +1734,6 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.st, N))) return rc;
   if ((rc = dev_alloc(d, &c.cand, N * (size_t)c.cand_cap))) return rc;
   if ((rc = dev_alloc(d, &c.win, N * c.win_cap))) return rc;
-  if ((rc = dev_alloc(d, &c.index, N * (size_t)d->g.n_blk))) return rc;
   if ((rc = dev_alloc(d, &c.queue, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
@@ -1753,7 +1747,6 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipMemset(c.st, 0, N * sizeof(ChanState)));
   HIP_TRY(d, hipMemset(c.counters, 0, 24 * sizeof(long long)));
   HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
-  HIP_TRY(d, hipMemset(c.index, 0, N * (size_t)d->g.n_blk * sizeof(unsigned)));   // tag 0 = no token
   if ((rc = dev_alloc(d, &c.boost_keys, N * kBoostSlots))) return rc;
   if ((rc = dev_alloc(d, &c.boost_vals, N * kBoostSlots))) return rc;
   HIP_TRY(d, hipMemset(c.boost_keys, 0, N * kBoostSlots * sizeof(int)));

@@ -412,9 +412,9 @@ def test_too_many_epsilon_arcs_on_one_state_is_a_bad_graph(torch_cuda):
     assert e.value.code == -2
 
 
-def test_state_index_tag_wraps_after_65535_token_sets(torch_cuda, c1):
-    """The per-state token index is tagged with a 16-bit epoch; a channel that lives longer
-    than 65,535 frames must renew it.  66,000 frames of the tiny configuration, streamed."""
+def test_a_channel_that_lives_for_66000_frames(torch_cuda, c1):
+    """A long stream: 66,000 frames of the tiny configuration in 660 chunks (costs grow to ~1e5,
+    the lattice arena and the frame offsets are used far beyond an utterance's length)."""
     from oracle import Oracle
     from paper_2311_04996_amd import Decoder
     torch = torch_cuda
