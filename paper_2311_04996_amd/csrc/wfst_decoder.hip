@@ -35,8 +35,8 @@
 // bytes.  The packed word sits right before the first arc, so ONE 16-byte load at byte 12 of a
 // block brings the degrees and next/weight/ilabel of the first arc.  A state is
 // named by its block number (byte offset / 32), which is also the recombination key and grows
-// with the state id.  `next` of an arc is the destination's block number plus a flag bit
-// (the destination has epsilon arcs), so a token is created from
+// with the state id.  `next` of an arc is the destination's block number plus two flag bits
+// (the destination has epsilon arcs / an epsilon arc enters it), so a token is created from
 // the arc alone and the only random graph read per token is the 32-byte header + first arc
 // when the token is expanded.  An arc's id is its unit address (epsilon arcs have bit 30 set),
 // which orders arcs exactly as (emitting before epsilon, state, position) does.
@@ -93,6 +93,9 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 #endif
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
+#ifndef WFST_UM
+#define WFST_UM 2
+#endif
 constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
 #ifndef WFST_REGION_BITS
 #define WFST_REGION_BITS 2
@@ -114,6 +117,7 @@ constexpr unsigned kOrdNone = 0xFFFFFFFFu;
 constexpr int kModeInit = 1, kModeFinal = 2;
 constexpr unsigned kKeyMask = 0x1fffffffu;     // block number of a state (32-byte units)
 constexpr unsigned kFlagHasEps = 0x80000000u;  // `next` of an arc: the destination has epsilon arcs
+constexpr unsigned kFlagEpsIn = 0x40000000u;   //                   an epsilon arc enters the destination
 constexpr unsigned kArcEps = 0x40000000u;      // arc ids: unit address, plus this bit for epsilon arcs
 constexpr unsigned kArcMask = 0x3fffffffu;
 constexpr unsigned kPackE = 0xFFFFFu;          // header word 3: emitting degree (20 bits, all ones = see word 2)
@@ -200,8 +204,9 @@ struct Smem {
   unsigned wave_tot[kWaves];
   unsigned best_ord;
   int n_reg[kRegions];        // candidates per region
-  int n_occ, n_hub, next_run, done_waves;
+  int n_pairs, n_hub, next_run, done_waves;
   int n_win, n_next, n_wl_next, status;
+  int n_in, n_emit, n_back;   // tokens of the emitting step an epsilon arc can enter (they come first), all of them; back counter
   int k_sel, n_sel, k_keep, redo;
   unsigned long long red64, red64b;
   long long ctr[8];
@@ -934,6 +939,13 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       } else if (k_sel < 256) {
         redo = 1;                                   // too many duplicates among the selected
       }
+      {
+        // survivors of the cutoff: the recombined tokens in bins below kk
+        const unsigned below = (4 * tid < kk ? h0 : 0u) + (4 * tid + 1 < kk ? h1 : 0u) + (4 * tid + 2 < kk ? h2 : 0u) +
+                               (4 * tid + 3 < kk ? h3 : 0u);
+        const unsigned n_keep = wave_sum(below);
+        if (tid == 0) sm.n_emit = (int)min(n_keep, 0x7fffffffu);
+      }
       if (tid == 0) {
         sm.k_keep = kk; sm.redo = redo;
         // next frame's selection: enough candidates for max_active distinct destinations
@@ -957,6 +969,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
 
   // ---- 4. survivors become tokens
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
+  const int n_emit = uni(sm.n_emit);
   for (int i0 = 0; i0 < n_win; i0 += kBlock * kUC) {
     int kp[kUC]; int4 cr[kUC];
 #pragma unroll
@@ -965,10 +978,19 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       cr[u] = x.win[min(i, n_win - 1)];
       kp[u] = (int)(i < n_win) & (int)(cut.bin(__int_as_float(cr[u].y)) < cut.k_keep);
     }
-    int ti[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; int good[kUC], no[kUC];
-    wave_alloc_n<kUC>(&sm.n_next, kp, ti);
+    // tokens an epsilon arc can enter are numbered from the front, the others from the back of
+    // the n_emit survivors: the closure then only has to look at the front part
+    int ti[kUC], tb[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; int good[kUC], no[kUC], kin[kUC], kout[kUC];
 #pragma unroll
     for (int u = 0; u < kUC; ++u) {
+      kin[u] = kp[u] & (int)(((unsigned)cr[u].x & kFlagEpsIn) != 0);
+      kout[u] = kp[u] & (int)!kin[u];
+    }
+    wave_alloc_n<kUC>(&sm.n_next, kin, ti);
+    wave_alloc_n<kUC>(&sm.n_back, kout, tb);
+#pragma unroll
+    for (int u = 0; u < kUC; ++u) {
+      if (kout[u]) ti[u] = n_emit - 1 - tb[u];
       good[u] = kp[u]; no[u] = false; none[u] = 0;
       if (kp[u]) {
         if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
@@ -979,7 +1001,11 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN);
   }
   __syncthreads();
-  if (tid == 0) sm.ctr[kCtKept] += min(sm.n_next, x.c.qcap);
+  if (tid == 0) {
+    sm.n_in = min(sm.n_next, x.c.qcap);            // the front part
+    sm.n_next = n_emit; sm.n_back = 0;
+    sm.ctr[kCtKept] += min(n_emit, x.c.qcap);
+  }
   if (tid < kRegions) sm.n_reg[tid] = 0;
   __syncthreads();
   prof_mark(sm, kPhCutoff);
@@ -1083,32 +1109,80 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       prof_mark(sm, kPhEpsTabFill);
       // the tokens of the set meet the table: each looks its own state up; if the pass has a
       // best candidate for it, the better of the two stays the state's token (cost, then arc id)
-      // and the entry is taken out, so that only destinations without a token remain
-      __syncthreads();
+      // and the entry is taken out, so that only destinations without a token remain.  The scan
+      // itself touches no memory but the (prefetched) queue records: tokens that got better are
+      // listed in LDS (the expansion tables are idle) and take their new cost and backpointer
+      // afterwards, all candidate records in flight at once.
       {
-        const int n_have = uni(min(sm.n_next, x.c.qcap));
-        for (int i0 = 0; i0 < n_have; i0 += kBlock * kU) {
-          int improve[kU], tok[kU], none[kU], nx[kU], cb[kU], pv[kU], ar[kU]; int2 tk[kU];
+        // only tokens that an epsilon arc can enter: the front part of the emitting step's tokens
+        // [0, n_in) and everything the closure itself has made so far [n_emit, n_next)
+        const int n_in = uni(sm.n_in), n_skip = uni(min(sm.n_emit, x.c.qcap)) - n_in;
+        const int n_have = n_in + max(0, uni(min(sm.n_next, x.c.qcap)) - n_in - n_skip);
+        constexpr int kM = WFST_UM;
+        constexpr int kPairs = (int)(sizeof(EpsLds) / sizeof(int2));
+        int2 *pairs = reinterpret_cast<int2 *>(&sm.ek);      // {token, candidate index}
+        int2 tkn[kM];
 #pragma unroll
-          for (int k = 0; k < kU; ++k) { tok[k] = i0 + k * kBlock + tid; tk[k] = NQ[min(tok[k], n_have - 1)]; }
+        for (int k = 0; k < kM; ++k) {
+          const int v = min(k * kBlock + tid, max(n_have - 1, 0));
+          tkn[k] = NQ[v < n_in ? v : v + n_skip];
+        }
+        if (tid == 0) sm.n_pairs = 0;
+        __syncthreads();
+        for (int i0 = 0; i0 < n_have; i0 += kBlock * kM) {
+          int2 tk[kM];
 #pragma unroll
-          for (int k = 0; k < kU; ++k) {
-            improve[k] = 0; none[k] = 0; nx[k] = 0; cb[k] = 0; pv[k] = 0; ar[k] = 0;
+          for (int k = 0; k < kM; ++k) {
+            tk[k] = tkn[k];
+            const int v = min(i0 + (kM + k) * kBlock + tid, n_have - 1);
+            tkn[k] = NQ[v < n_in ? v : v + n_skip];
+          }
+#pragma unroll
+          for (int k = 0; k < kM; ++k) {
+            const int vi = i0 + k * kBlock + tid;
+            const int tok = vi < n_in ? vi : vi + n_skip;
             unsigned sl = (hash_state(tk[k].x) >> 6) & kTabMask;
-            int probes = 0, key = tok[k] < n_have ? t.keys[sl] : kKeyEmpty;
+            int probes = 0, key = vi < n_have ? t.keys[sl] : kKeyEmpty;
             while (key != tk[k].x && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
-            if (key == tk[k].x && tok[k] < n_have) {
+            if (key == tk[k].x && vi < n_have) {
               const unsigned long long v = t.vals[sl];
               t.vals[sl] = kValEmpty;                      // this destination has its token
               const float nc = ord2f((unsigned)(v >> 32)), oc = __int_as_float(tk[k].y);
               bool better = (nc < oc) & (v != kValEmpty);
-              if (nc == oc && v != kValEmpty) better = (unsigned)x.cand[(unsigned)v].w < (unsigned)x.lat[lat_base + tok[k]].y;
-              if (better) {                                  // new cost and backpointer in place, expand again
-                const int4 rec = x.cand[(unsigned)v];
-                NQ[tok[k]].y = rec.y;
-                x.lat[lat_base + tok[k]] = make_int2(rec.z, rec.w);
-                improve[k] = 1; nx[k] = rec.x; cb[k] = rec.y;
+              if (nc == oc && v != kValEmpty) better = (unsigned)x.cand[(unsigned)v].w < (unsigned)x.lat[lat_base + tok].y;
+              if (better) {
+                const int at = atomicAdd(&sm.n_pairs, 1);
+                if (at < kPairs) pairs[at] = make_int2(tok, (int)(unsigned)v);
+                else {                                       // list full: apply it here
+                  const int4 rec = x.cand[(unsigned)v];
+                  NQ[tok].y = rec.y;
+                  x.lat[lat_base + tok] = make_int2(rec.z, rec.w);
+                  if ((unsigned)rec.x & kFlagHasEps) {
+                    const int wi = atomicAdd(&sm.n_wl_next, 1);
+                    WLN[wi] = make_int4(tok, key_of(rec.x), rec.y, 0);
+                  }
+                }
               }
+            }
+          }
+        }
+        __syncthreads();
+        const int n_pairs = uni(min(sm.n_pairs, kPairs));
+        for (int i0 = 0; i0 < n_pairs; i0 += kBlock * kU) {
+          int improve[kU], tok[kU], none[kU], nx[kU], cb[kU], pv[kU], ar[kU]; int4 rec[kU];
+#pragma unroll
+          for (int k = 0; k < kU; ++k) {
+            const int i = i0 + k * kBlock + tid;
+            const int2 pr = pairs[min(i, n_pairs - 1)];
+            improve[k] = (int)(i < n_pairs); tok[k] = pr.x; none[k] = 0; pv[k] = 0; ar[k] = 0;
+            rec[k] = x.cand[(unsigned)pr.y];
+          }
+#pragma unroll
+          for (int k = 0; k < kU; ++k) {
+            nx[k] = rec[k].x; cb[k] = rec[k].y;
+            if (improve[k]) {                                // new cost and backpointer in place, expand again
+              NQ[tok[k]].y = rec[k].y;
+              x.lat[lat_base + tok[k]] = make_int2(rec[k].z, rec[k].w);
             }
           }
           make_tokens<kU>(x, none, tok, nx, cb, pv, ar, improve, tok, NQ, lat_base, WLN);
@@ -1314,7 +1388,8 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     }
 
   if (tid == 0) {
-    sm.best_ord = kOrdNone; sm.n_occ = 0; sm.n_hub = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.best_ord = kOrdNone; sm.n_pairs = 0; sm.n_hub = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
+    sm.n_in = 0; sm.n_emit = 0; sm.n_back = 0;
     for (int r = 0; r < kRegions; ++r) sm.n_reg[r] = 0;
     sm.status = 0; sm.red64 = 0; sm.red64b = 0; sm.k_keep = 256; sm.k_sel = 256; sm.n_sel = 0; sm.redo = 0;
     for (int i = 0; i < 16; ++i) sm.prof[i] = 0;
@@ -1330,7 +1405,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
     int2 *NQ = x.q0 + c.qcap;
-    if (tid == 0) sm.n_next = 1;
+    if (tid == 0) { sm.n_next = 1; sm.n_in = 1; sm.n_emit = 1; }
     {
       const int mk[1] = {tid == 0}, no[1] = {false};
       const int z[1] = {0}, st[1] = {(int)g.start}, m1[1] = {-1};
@@ -1670,7 +1745,7 @@ int validate_graph(const wfst_graph_csr *g, std::string &why, int64_t &Ae, int64
 // Lay the graph out as state blocks (see the top of this file).
 int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
   const int32_t S = g->num_states;
-  std::vector<char> has_eps(S, 0);
+  std::vector<char> eps_in(S, 0), has_eps(S, 0);
   std::vector<unsigned> &blk = d->blk_of_state;
   blk.assign((size_t)S + 1, 0);
   uint64_t units = 0;
@@ -1680,10 +1755,10 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
     units += n + (n & 1);
     if (units / 2 > (uint64_t)kKeyMask) return fail(d, WFST_ERR_BAD_GRAPH, "graph larger than 2^29 blocks of 32 bytes");
     for (int64_t i = g->row_offsets[s]; i < g->row_offsets[s + 1]; ++i)
-      if (g->ilabel[i] == 0) has_eps[s] = 1;
+      if (g->ilabel[i] == 0) { eps_in[g->next_state[i]] = 1; has_eps[s] = 1; }
   }
   blk[S] = (unsigned)(units / 2);
-  auto named = [&](int32_t s) { return blk[s] | (has_eps[s] ? kFlagHasEps : 0u); };
+  auto named = [&](int32_t s) { return blk[s] | (has_eps[s] ? kFlagHasEps : 0u) | (eps_in[s] ? kFlagEpsIn : 0u); };
   std::vector<int4> unit(units, make_int4(0, 0, 0, 0));
   bool all_zero = true;
   for (int32_t s = 0; s < S; ++s) {
