@@ -93,6 +93,9 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 #endif
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
+#ifndef WFST_SEL_STRIDE
+#define WFST_SEL_STRIDE 2                     // the selection histogram reads 1 / WFST_SEL_STRIDE of the candidates
+#endif
 #ifndef WFST_UM
 #define WFST_UM 2
 #endif
@@ -855,7 +858,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     const int n = uni(min(sm.n_reg[r], x.c.region_cap));
     const int4 *cr = x.cand + r * x.c.region_cap;
     constexpr int kHalf = 2;
-    for (int i0 = 0; i0 < n; i0 += kBlock * 2 * kHalf) {
+    for (int i0 = 0; i0 < n; i0 += kBlock * WFST_SEL_STRIDE * kHalf) {
       int cb[kHalf];
 #pragma unroll
       for (int u = 0; u < kHalf; ++u) { const int i = i0 + u * kBlock + tid; cb[u] = i < n ? cr[i].y : 0; }
