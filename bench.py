@@ -163,6 +163,56 @@ def main_streaming(args):
     print(json.dumps(line), flush=True)
 
 
+def main_lattice(args):
+    """Lattice output (wfst_get_lattice) on utterances of the c3_large workload: the batch is
+    decoded with token records kept, then the lattice of every utterance is generated with the
+    outputs left in device memory.  One JSON line: links found per second."""
+    import torch
+    from paper_2311_04996_amd import Decoder
+    from workloads import make_config
+    w = make_config(args.workload, batch=args.batch or 8)
+    B, T, V = w.loglikes.shape
+    dec = Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active,
+                  keep_token_records=True)
+    ll = torch.from_numpy(w.loglikes).cuda()
+    dec.get_counters(reset=True)
+    dec.decode_batch(ll, w.lengths, w.beam, w.max_active)
+    torch.cuda.synchronize()
+    counters = dec.get_counters()
+    rows = [ll[b, :int(w.lengths[b])].contiguous() for b in range(B)]
+    sizes = []
+    for b in range(B):                                # sizes (and warm-up)
+        _, _, _, _, nt, nl = dec.get_lattice(b, rows[b], args.lattice_beam, on_device=True)
+        sizes.append((nt, nl))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for b in range(B):
+            dec.get_lattice(b, rows[b], args.lattice_beam, tok_cap=sizes[b][0], link_cap=sizes[b][1], on_device=True)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    ntok, nlink = sum(s[0] for s in sizes), sum(s[1] for s in sizes)
+    arcs = int(counters[1] + counters[2])
+    frames = int(w.lengths.sum())
+    # bytes the method has to move: per frame a log-likelihood row; per token its record when its
+    # set is put into the lookup table and again (with the 16-byte header of its state) when its
+    # arcs are expanded, state and cost written out; per arc its 16-byte record; per link 32 bytes
+    abytes = frames * V * 4 + ntok * (8 + 8 + 16 + 8) + arcs * 16 + nlink * 32
+    achieved = abytes / dt / 1e9
+    line = {"metric": "lattice links found per second (wfst_get_lattice, outputs on device)", "value": nlink / dt,
+            "unit": "links/s", "n_gpus": 1, "steps": args.steps, "warmup": 1, "ms_per_step": 1e3 * dt,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": args.workload, "utterances": B, "frames": frames, "lattice_beam": args.lattice_beam,
+                       "tokens": ntok, "links": nlink, "arcs_expanded": arcs, "beam": w.beam, "max_active": w.max_active},
+            "ms_per_utterance": 1e3 * dt / B, "audio_s_per_s": w.audio_seconds / dt,
+            "timing": "wall clock around the calls (each launches wfst_lattice_kernel and waits for it)",
+            "roofline": {"bound": "hbm", "kernel": "wfst_lattice_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                         "algorithmic_bytes_per_step": abytes}}
+    dec.close()
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--channels", type=int, default=512, help="streaming mode: concurrent channels")
@@ -174,6 +224,11 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (profiling aid)")
+    ap.add_argument("--loglike-dtype", default="float32", choices=["float32", "float16", "bfloat16"],
+                    help="element type of the log-likelihoods handed to the decoder (costs stay fp32)")
+    ap.add_argument("--lattice-beam", type=float, default=None,
+                    help="lattice mode: decode --batch utterances (default 8) with token records kept and time "
+                         "wfst_get_lattice with this lattice beam for each of them")
     ap.add_argument("--pipeline", type=int, default=3,
                     help="decoders (each with its own stream) that take the steps in turn, so that the "
                          "next batch fills the compute units the previous one no longer uses")
@@ -190,6 +245,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.workload == "c4_streaming":
         return main_streaming(args)
+    if args.lattice_beam is not None:
+        return main_lattice(args)
 
     t0 = time.perf_counter()
     w = make_config(args.workload, batch=args.batch)
@@ -197,11 +254,12 @@ def main():
     print(f"[bench] {args.workload}: S={w.graph.num_states} A={w.graph.num_arcs} B={B} T={T} V={V} "
           f"audio={w.audio_seconds:.1f}s generated in {time.perf_counter() - t0:.1f}s", file=sys.stderr, flush=True)
     t0 = time.perf_counter()
-    decs = [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active)
+    decs = [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active,
+                    loglike_dtype=args.loglike_dtype)
             for _ in range(max(1, args.pipeline))]
     streams = pick_concurrent_streams(torch, len(decs))
     dec = decs[0]
-    ll = torch.from_numpy(w.loglikes).cuda()
+    ll = torch.from_numpy(w.loglikes).cuda().to(getattr(torch, args.loglike_dtype))
     outs = [None] * len(decs)
     torch.cuda.synchronize()
     print(f"[bench] decoder ready in {time.perf_counter() - t0:.1f}s, {dec.device_bytes() / 2**30:.1f} GiB on device",
@@ -269,7 +327,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
                    "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
-                   "beam": w.beam, "max_active": w.max_active, "batches_in_flight": len(decs)},
+                   "beam": w.beam, "max_active": w.max_active, "batches_in_flight": len(decs),
+                   "loglike_dtype": args.loglike_dtype},
         "one_batch_in_flight": {"value": w.audio_seconds / (wall_one / args.steps),
                                 "ms_per_step": 1e3 * wall_one / args.steps},
         "arcs_expanded_per_s": arcs / (wall / args.steps),

@@ -186,7 +186,7 @@ int32_t wfst_get_partial_batch(wfst_decoder *dec, const int32_t *channels, int32
  * Needs opts.keep_token_records.  `loglikes`: DEVICE, the utterance's f rows of V elements
  * (dense, element type opts.loglike_dtype) with the values it was decoded with; the decoder
  * does not keep them.  tok_state / tok_cost [tok_cap] and links [link_cap]: DEVICE, caller
- * owned, written in no particular link order.  frame_off [f+2], n_tokens, n_links: HOST.  The
+ * owned; the links are ordered by `frame`, in no particular order inside a frame.  frame_off [f+2], n_tokens, n_links: HOST.  The
  * call runs on `stream` and returns after it has finished.  If tok_cap or link_cap is too
  * small the call returns WFST_ERR_CAPACITY with *n_tokens and *n_links set to what is needed
  * (entries beyond the capacities are not written).  Other errors: INVALID_ARG (no records

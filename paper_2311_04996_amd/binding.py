@@ -257,10 +257,12 @@ class Decoder:
                                                     _stream_ptr(stream)))
         return out
 
-    def get_lattice(self, ch, loglikes, lattice_beam, stream=None, tok_cap=None, link_cap=None):
+    def get_lattice(self, ch, loglikes, lattice_beam, stream=None, tok_cap=None, link_cap=None, on_device=False):
         """wfst_get_lattice for channel `ch`; `loglikes` [frames, V] is the utterance's device
-        tensor it was decoded with.  Returns a `Lattice` (host arrays).  Without capacities the
-        call is made twice: once to learn the sizes, once with buffers of that size."""
+        tensor it was decoded with.  Returns a `Lattice` (host arrays), or with on_device=True the
+        tuple (frame_off, state tensor, cost tensor, link bytes tensor, n_tokens, n_links) with the
+        outputs left in device memory.  Without capacities the call is made twice: once to
+        learn the sizes, once with buffers of that size."""
         import torch
         from .lattice import Lattice
         assert loglikes.is_cuda and loglikes.dtype == getattr(torch, self.loglike_dtype) and loglikes.is_contiguous()
@@ -284,6 +286,8 @@ class Decoder:
             tok_cap, link_cap = nt.value, nl.value
         rc, st, co, lk = call(tok_cap, link_cap)
         self._check(rc)
+        if on_device:
+            return off[:loglikes.shape[0] + 2].copy(), st, co, lk, nt.value, nl.value
         links = lk.cpu().numpy()[:nl.value * LINK_DTYPE.itemsize].view(LINK_DTYPE).copy()
         return Lattice(off[:loglikes.shape[0] + 2].copy(), st.cpu().numpy()[:nt.value].copy(),
                        co.cpu().numpy()[:nt.value].copy(), links)

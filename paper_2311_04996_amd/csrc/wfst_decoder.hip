@@ -1484,11 +1484,16 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
 // A_t and every emitting arc of the tokens of A_{t-1} is expanded once more, exactly as the
 // decoder did, and its destination looked up: if a token is there and the cost through the arc
 // is within the lattice beam of that token's stored cost, the arc is a link.  Sets too large
-// for one table are taken in passes over hash groups of their keys.
+// for one table are taken in passes over hash groups of their keys.  The kernel runs twice: the
+// first run only counts the links of every set, a small scan turns the counts into each set's
+// place in the output, and the second run writes the links there (ordered by set; one counter
+// in memory for all workgroups would serialise them: measured 3x slower).
 constexpr int kLatSlots = 16384;
-constexpr int kLatGroup = 8192;               // mean keys per pass (load 0.5)
-constexpr int kLatHeavy = 1024;               // tokens with many arcs, expanded by the whole workgroup
-constexpr int kLatHeavyDeg = 64;
+constexpr int kLatGroup = 11264;              // mean keys per pass (load 0.69)
+constexpr int kLatHeavy = 1024;               // tokens with very many arcs, expanded by the whole workgroup
+constexpr int kLatHeavyDeg = 4096;
+constexpr int kLatMedium = 6144;              // tokens with more than a few arcs, expanded by one wave each
+constexpr int kLatLightDeg = 3;
 constexpr int kLatErrTable = 1;
 struct LatLds {
   int keys[kLatSlots];
@@ -1496,7 +1501,9 @@ struct LatLds {
   float ac[kMaxV];
   int bk[kBoostSlots]; float bv[kBoostSlots];
   int heavy[kLatHeavy];
-  int n_heavy;
+  unsigned short medium[kLatMedium];
+  int n_heavy, n_medium, next_medium;
+  unsigned n_links;                           // links of this set so far
 };
 struct LatticeArgs {
   int ch, frames;
@@ -1504,13 +1511,16 @@ struct LatticeArgs {
   float lattice_beam;
   int *tok_state; float *tok_cost; long long tok_cap;
   wfst_lattice_link *links; long long link_cap;
-  unsigned long long *ctr;                    // [0] links found, [1] error bits
+  unsigned long long *ctr;                    // [0] links found (written by the scan), [1] error bits
+  unsigned long long *set_links;              // [frames + 1] links per set, then (after the scan) before each set
+  int write;                                  // 0: count only; 1: write the links
 };
 
 struct LatPass {                              // block-uniform view of one pass
   const DevGraph &g; LatLds &sm; const LatticeArgs &a;
   const int2 *dst_rec; unsigned dst_base;     // records and first token number of A_t
   int t, p, P; bool boosted;
+  unsigned long long links_base;              // where this set's links go
 };
 
 __device__ __forceinline__ int lat_group(int key, int P) {
@@ -1548,8 +1558,9 @@ __device__ __forceinline__ void lat_arc(const LatPass &q, int u, float tc, unsig
   const unsigned j = q.sm.pos[sl];
   const float cj = __int_as_float(q.dst_rec[j].y);
   if (!((nc - cj) <= q.a.lattice_beam)) return;
-  const unsigned long long at = atomicAdd(&q.a.ctr[0], 1ull);
-  if (at < (unsigned long long)q.a.link_cap) {
+  const unsigned k = atomicAdd(&q.sm.n_links, 1u);
+  const unsigned long long at = q.links_base + k;
+  if (q.a.write && at < (unsigned long long)q.a.link_cap) {
     wfst_lattice_link L;
     L.src = (int)src; L.dst = (int)(q.dst_base + j); L.ilabel = kEps ? 0 : ar.z; L.olabel = ar.w;
     L.graph_cost = w; L.acoustic_cost = acst; L.cost = nc; L.frame = q.t;
@@ -1557,37 +1568,63 @@ __device__ __forceinline__ void lat_arc(const LatPass &q, int u, float tc, unsig
   }
 }
 
-// All epsilon (kEps) or emitting arcs of the n tokens rec[0..n), numbered from `base`.
+// First arc (unit address) and number of epsilon (kEps) or emitting arcs of a token's state.
+template <bool kEps>
+__device__ __forceinline__ void lat_arcs_of(const DevGraph &g, int key, int &first, int &deg) {
+  const int4 hd = g.unit[2 * (size_t)(unsigned)key];
+  const int nx = (int)((unsigned)hd.w >> kPackXShift);
+  int ne = (int)((unsigned)hd.w & kPackE);
+  if (ne == (int)kPackE) ne = hd.z;
+  first = 2 * key + 1 + (kEps ? 0 : nx);
+  deg = kEps ? nx : ne;
+}
+
+// All epsilon (kEps) or emitting arcs of the n tokens rec[0..n), numbered from `base`.  A
+// token with a few arcs is expanded by the lane that reads it; one with more is listed and
+// taken by a whole wave (the waves take listed tokens from a counter); one with thousands of
+// arcs is expanded by the whole workgroup.  A token that finds its list full is expanded by
+// its own lane.
 template <bool kEps>
 __device__ __forceinline__ void lat_expand(const LatPass &q, const int2 *rec, unsigned n, unsigned base) {
-  const int tid = threadIdx.x;
-  if (tid == 0) q.sm.n_heavy = 0;
+  const int tid = threadIdx.x, lane = tid & 63;
+  if (tid == 0) { q.sm.n_heavy = 0; q.sm.n_medium = 0; q.sm.next_medium = 0; }
   __syncthreads();
   for (unsigned i = tid; i < n; i += kBlock) {
     const int2 tk = rec[i];
-    const int4 hd = q.g.unit[2 * (size_t)(unsigned)tk.x];
-    const int nx = (int)((unsigned)hd.w >> kPackXShift);
-    int ne = (int)((unsigned)hd.w & kPackE);
-    if (ne == (int)kPackE) ne = hd.z;
-    const int first = 2 * tk.x + 1 + (kEps ? 0 : nx), deg = kEps ? nx : ne;
-    bool mine = deg <= kLatHeavyDeg;
+    int first, deg;
+    lat_arcs_of<kEps>(q.g, tk.x, first, deg);
+    bool mine = deg <= kLatLightDeg;
     if (!mine) {
-      const int h = atomicAdd(&q.sm.n_heavy, 1);
-      if (h < kLatHeavy) q.sm.heavy[h] = (int)i; else mine = true;   // list full: this thread does it alone
+      if (deg > kLatHeavyDeg) {
+        const int h = atomicAdd(&q.sm.n_heavy, 1);
+        if (h < kLatHeavy) q.sm.heavy[h] = (int)i; else mine = true;
+      } else {
+        const int h = atomicAdd(&q.sm.n_medium, 1);
+        if (h < kLatMedium) q.sm.medium[h] = (unsigned short)i; else mine = true;
+      }
     }
     if (mine)
       for (int k = 0; k < deg; ++k) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
   }
   __syncthreads();
+  const int nm = min(q.sm.n_medium, kLatMedium);
+  for (;;) {
+    int m = 0;
+    if (lane == 0) m = atomicAdd(&q.sm.next_medium, 1);
+    m = uni(m);
+    if (m >= nm) break;
+    const unsigned i = q.sm.medium[m];
+    const int2 tk = rec[i];
+    int first, deg;
+    lat_arcs_of<kEps>(q.g, tk.x, first, deg);
+    for (int k = lane; k < deg; k += 64) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
+  }
   const int nh = min(q.sm.n_heavy, kLatHeavy);
   for (int h = 0; h < nh; ++h) {
     const unsigned i = (unsigned)q.sm.heavy[h];
     const int2 tk = rec[i];
-    const int4 hd = q.g.unit[2 * (size_t)(unsigned)tk.x];
-    const int nx = (int)((unsigned)hd.w >> kPackXShift);
-    int ne = (int)((unsigned)hd.w & kPackE);
-    if (ne == (int)kPackE) ne = hd.z;
-    const int first = 2 * tk.x + 1 + (kEps ? 0 : nx), deg = kEps ? nx : ne;
+    int first, deg;
+    lat_arcs_of<kEps>(q.g, tk.x, first, deg);
     for (int k = tid; k < deg; k += kBlock) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
   }
   __syncthreads();
@@ -1629,6 +1666,8 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
       sm.bv[i] = c.boost_vals[(size_t)a.ch * kBoostSlots + i];
     }
   const int P = max(1, (int)((n1 + kLatGroup - 1) / kLatGroup));
+  const unsigned long long links_base = a.write ? a.set_links[t] : 0ull;
+  if (tid == 0) sm.n_links = 0;
   for (int p = 0; p < P; ++p) {
     for (int sl = tid; sl < kLatSlots; sl += kBlock) sm.keys[sl] = kKeyEmpty;
     __syncthreads();
@@ -1644,10 +1683,30 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
       if (probes < kLatSlots) sm.pos[sl] = (unsigned short)j;
     }
     __syncthreads();
-    const LatPass q{g, sm, a, rec + o1, o1, t, p, P, boosted};
+    const LatPass q{g, sm, a, rec + o1, o1, t, p, P, boosted, links_base};
     lat_expand<true>(q, rec + o1, n1, o1);
     if (t > 0) lat_expand<false>(q, rec + o0, n0, o0);
   }
+  if (tid == 0 && !a.write) a.set_links[t] = sm.n_links;     // lat_expand ends with a barrier
+}
+
+// Exclusive prefix sums of v[0..n) in place, the total into *total (one workgroup).
+__global__ __launch_bounds__(kBlock) void wfst_lattice_scan(unsigned long long *v, int n, unsigned long long *total) {
+  __shared__ unsigned long long part[kBlock];
+  const int tid = threadIdx.x;
+  const int per = (n + kBlock - 1) / kBlock, lo = min(n, tid * per), hi = min(n, lo + per);
+  unsigned long long s = 0;
+  for (int i = lo; i < hi; ++i) s += v[i];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long run = 0;
+    for (int i = 0; i < kBlock; ++i) { const unsigned long long x = part[i]; part[i] = run; run += x; }
+    *total = run;
+  }
+  __syncthreads();
+  unsigned long long run = part[tid];
+  for (int i = lo; i < hi; ++i) { const unsigned long long x = v[i]; v[i] = run; run += x; }
 }
 
 }  // namespace
@@ -1664,6 +1723,7 @@ struct wfst_decoder {
   static constexpr int kRing = 8;
   int *d_params = nullptr;  int ring_pos = 0;
   unsigned long long *d_lat_ctr = nullptr;   // lattice kernel: links found, error bits
+  unsigned long long *d_set_links = nullptr; // [max_frames + 2] links per token set of the channel being read out
   std::vector<int> h_params[kRing];
   // device staging for host-side outputs
   int *o_words = nullptr, *o_nwords = nullptr, *o_flags = nullptr; float *o_cost = nullptr;
@@ -1833,6 +1893,7 @@ int alloc_channels(wfst_decoder *d) {
   d->boost_on_dev.assign(N, 0);
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
   if ((rc = dev_alloc(d, &d->d_lat_ctr, (size_t)2))) return rc;
+  if (o.keep_token_records && (rc = dev_alloc(d, &d->d_set_links, (size_t)c.max_frames + 2))) return rc;
   if (o.outputs_on_host) {
     if ((rc = dev_alloc(d, &d->o_words, N * (size_t)o.max_words))) return rc;
     if ((rc = dev_alloc(d, &d->o_nwords, N))) return rc;
@@ -2137,14 +2198,23 @@ int32_t wfst_get_lattice(wfst_decoder *d, int32_t ch, const void *loglikes, floa
   a.ch = ch; a.frames = f; a.ll = loglikes; a.V = d->V; a.ll_dtype = d->opts.loglike_dtype;
   a.lattice_beam = lattice_beam;
   a.tok_state = tok_state; a.tok_cost = tok_cost; a.tok_cap = tok_cap;
-  a.links = links; a.link_cap = link_cap; a.ctr = d->d_lat_ctr;
+  a.links = links; a.link_cap = link_cap; a.ctr = d->d_lat_ctr; a.set_links = d->d_set_links;
+  a.write = 0;                                  // first run: links per set
   hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
+  HIP_TRY(d, hipGetLastError());
+  hipLaunchKernelGGL(wfst_lattice_scan, dim3(1), dim3(kBlock), 0, st, d->d_set_links, f + 1, d->d_lat_ctr);
   HIP_TRY(d, hipGetLastError());
   unsigned long long ctr[2] = {0, 0};
   HIP_TRY(d, hipMemcpyAsync(ctr, d->d_lat_ctr, sizeof(ctr), hipMemcpyDeviceToHost, st));
   HIP_TRY(d, hipStreamSynchronize(st));
   *n_links = (int64_t)ctr[0];
   if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
+  if (*n_tokens <= tok_cap && *n_links <= link_cap && *n_links > 0) {
+    a.write = 1;                                // second run: every set writes its links at its place
+    hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
+    HIP_TRY(d, hipGetLastError());
+    HIP_TRY(d, hipStreamSynchronize(st));
+  }
   if (*n_tokens > tok_cap || *n_links > link_cap)
     return fail(d, WFST_ERR_CAPACITY, "lattice needs room for " + std::to_string(*n_tokens) + " tokens and " +
                                           std::to_string(*n_links) + " links");
