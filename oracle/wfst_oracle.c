@@ -46,6 +46,14 @@
  *       The backpointer arcs are the links with difference 0.  Pinned by the tests only
  *       through what the definition implies (complete path set on unpruned micro graphs,
  *       best path = the decoder's); against the paper it is "parity unpinned".
+ *   R11 cost offsets (an option; the paper is silent on cost renormalisation).  After the prune
+ *       step of a frame, with b the best cost of the recombined set, every surviving token's
+ *       cost c becomes (c - b) in fp32 and the closure's frozen predicate uses best = 0; the
+ *       b's are summed in fp64 and the sum is added back to the cost that is reported:
+ *       cost = (float)((double)c_final + sum).  Stored token costs (digests, dumps) are the
+ *       rebased ones.  Costs then stay of the order of the beam however long the stream is.
+ *       Pins: identical results on exactly representable (dyadic) inputs, and a smaller error
+ *       against an fp64 trellis on a long stream.  Not combined with the lattice output.
  *
  * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
  * Viterbi, greedy CTC collapse on the normal CTC topology, closed-form histogram cases,
@@ -90,6 +98,7 @@ typedef struct {
   int32_t boost_n;
   const int32_t *boost_ids;
   const float *boost_scores;
+  int32_t cost_offset;     /* R11: 1 = rebase the token costs to the best cost after every prune step */
 } oracle_opts;
 
 typedef struct {
@@ -328,6 +337,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
   tokvec cur = { 0, 0, 0 }, nxt = { 0, 0, 0 };
   int64_t dump_used = 0;
   cutoff_t k; k.beam = o->beam; k.scale = 256.0f / o->beam;
+  double offset_sum = 0.0;                      /* R11 */
   /* boost table as a dense array over output labels (absent words add exactly 0) */
   float *boost = NULL;
   if (o->boost_n > 0) {
@@ -408,6 +418,11 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     }
     nxt.n = m;
     res->counters[3] += m;
+    if (o->cost_offset && m > 0) {              /* R11 */
+      for (int32_t i = 0; i < m; ++i) nxt.t[i].cost = canon(nxt.t[i].cost - best);
+      offset_sum += (double)best;
+      k.best = 0.0f;
+    }
     /* ---- epsilon closure under the frozen predicate (R6) */
     eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1, boost);
     { tokvec tmp = cur; cur = nxt; nxt = tmp; }
@@ -432,7 +447,8 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
         if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }
       }
     }
-    res->cost = bf; res->flags = any_final ? FLAG_FINAL : 0;
+    res->cost = o->cost_offset ? (float)((double)bf + offset_sum) : bf;
+    res->flags = any_final ? FLAG_FINAL : 0;
     /* walk back: an epsilon arc's prev indexes the same frame, an emitting arc's the one before */
     int32_t plen = 0, pcap = 1024; int32_t *rev = (int32_t *)malloc(sizeof(int32_t) * pcap);
     int32_t f = len, i = bi;

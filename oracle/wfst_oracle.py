@@ -31,7 +31,8 @@ class _Graph(C.Structure):
 class _Opts(C.Structure):
     _fields_ = [("beam", C.c_float), ("max_active", C.c_int32), ("max_words", C.c_int32),
                 ("finalize", C.c_int32), ("worklist_order", C.c_int32), ("order_seed", C.c_uint64),
-                ("boost_n", C.c_int32), ("boost_ids", C.c_void_p), ("boost_scores", C.c_void_p)]
+                ("boost_n", C.c_int32), ("boost_ids", C.c_void_p), ("boost_scores", C.c_void_p),
+                ("cost_offset", C.c_int32)]
 
 
 class _Result(C.Structure):
@@ -175,8 +176,10 @@ class Oracle:
 
     def decode(self, loglikes, length=None, beam=17.0, max_active=10000, max_words=1024,
                finalize=True, worklist_order=0, order_seed=0, want_path=False,
-               want_digests=False, want_frames=False, frames_cap=None, boost=None) -> OracleResult:
-        """boost: optional (word_ids, scores) table of the utterance (Section "Word boosting")."""
+               want_digests=False, want_frames=False, frames_cap=None, boost=None,
+               cost_offset=False) -> OracleResult:
+        """boost: optional (word_ids, scores) table of the utterance (Section "Word boosting").
+        cost_offset: rebase the token costs after every prune step (reading R11 in the C source)."""
         lib = _load()
         ll = np.asarray(loglikes, dtype=np.float32)
         assert ll.ndim == 2 and ll.shape[1] == self.V and ll.strides[1] == 4
@@ -187,9 +190,10 @@ class Oracle:
             b_sc = np.ascontiguousarray(boost[1], dtype=np.float32)
             assert b_ids.shape == b_sc.shape
             o = _Opts(beam, max_active, max_words, int(bool(finalize)), worklist_order, order_seed,
-                      len(b_ids), b_ids.ctypes.data, b_sc.ctypes.data)
+                      len(b_ids), b_ids.ctypes.data, b_sc.ctypes.data, int(bool(cost_offset)))
         else:
-            o = _Opts(beam, max_active, max_words, int(bool(finalize)), worklist_order, order_seed, 0, None, None)
+            o = _Opts(beam, max_active, max_words, int(bool(finalize)), worklist_order, order_seed, 0, None, None,
+                      int(bool(cost_offset)))
         res = _Result()
         words = np.zeros(max(1, max_words), dtype=np.int32)
         dc = np.zeros(n + 1, dtype=np.int32) if want_digests else None
