@@ -85,6 +85,14 @@ typedef struct {
   int32_t keep_token_records;     /* 1: keep {state, cost} of every stored token beside its
                                      backpointer (as much memory again as the lattice arena), which
                                      wfst_get_lattice needs; 0: only the best path can be read back */
+  int32_t cost_offset;            /* 1: after the prune step of every frame the surviving tokens' costs
+                                     are rebased to the best cost of that frame (c - best, fp32) and the
+                                     offsets are summed in fp64 and added back to every cost that is
+                                     reported, so that costs keep their fp32 resolution on streams of any
+                                     length (the paper is silent on cost renormalisation; without it a
+                                     stream of 40,000 frames loses the exact best path to rounding).
+                                     Results can differ from cost_offset = 0 in the last bits of costs
+                                     and in near-ties.  Not combined with keep_token_records */
 } wfst_opts;
 
 #define WFST_LOGLIKE_F32 0

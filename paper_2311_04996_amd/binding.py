@@ -57,7 +57,7 @@ class wfst_opts(C.Structure):
                 ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
                 ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
                 ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32),
-                ("loglike_dtype", C.c_int32), ("keep_token_records", C.c_int32)]
+                ("loglike_dtype", C.c_int32), ("keep_token_records", C.c_int32), ("cost_offset", C.c_int32)]
 
 
 class wfst_lattice_link(C.Structure):
@@ -124,7 +124,7 @@ class Decoder:
 
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
                  lattice_bytes_per_channel=0, outputs_on_host=False, candidate_capacity=0,
-                 record_digests=False, loglike_dtype="float32", keep_token_records=False):
+                 record_digests=False, loglike_dtype="float32", keep_token_records=False, cost_offset=False):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
                 np.ascontiguousarray(graph.next_state, dtype=np.int32),
@@ -136,7 +136,8 @@ class Decoder:
                            *[None if a is None else a.ctypes.data for a in arrs])
         self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
                               int(outputs_on_host), max_active_hint, candidate_capacity,
-                              int(record_digests), LOGLIKE_DTYPES[loglike_dtype], int(keep_token_records))
+                              int(record_digests), LOGLIKE_DTYPES[loglike_dtype], int(keep_token_records),
+                              int(cost_offset))
         self.loglike_dtype = loglike_dtype
         self.V = graph.num_classes
         self.max_words = max_words

@@ -129,6 +129,7 @@ constexpr int kMaxEpsDeg = 4094;
 constexpr int kStLattice = WFST_FLAG_LATTICE_OVERFLOW, kStCapacity = WFST_FLAG_CAPACITY;
 
 struct ChanState {            // persists between calls (the per-stream decoder state)
+  double offset;              // cost offsets: sum of the best costs the token costs were rebased by
   int frame;                  // frames consumed since init
   int n_tok;                  // size of the current closed token set
   int cur;                    // which queue buffer holds it
@@ -157,6 +158,7 @@ struct DevChannels {
   int4 *wl;                                    // 2 buffers {token, block number, cost, 1 = new token}
   int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
   int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
+  int cost_offset;                             // 1: token costs are rebased to the best cost after every prune step
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
   long long *counters;                         // [24]: 8 workload counters, 16 phase tick sums
@@ -249,6 +251,12 @@ __device__ __forceinline__ float boost_of(const Smem &sm, int word);
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+__device__ __forceinline__ double uni(double v) {
+  const long long b = __double_as_longlong(v);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(b & 0xffffffffll));
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32));
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
 
 // 16 bytes at byte 12 of a state block: {packed degrees, first unit's next, weight, ilabel}
 // (4-byte aligned; one global_load_dwordx4).
@@ -1000,6 +1008,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
         else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
       }
       st[u] = cr[u].x; cb[u] = cr[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
+      if (x.c.cost_offset) cb[u] = __float_as_int(canon(__int_as_float(cr[u].y) - cut.best));
     }
     make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN);
   }
@@ -1010,6 +1019,10 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     sm.ctr[kCtKept] += min(n_emit, x.c.qcap);
   }
   if (tid < kRegions) sm.n_reg[tid] = 0;
+  if (x.c.cost_offset && n_emit > 0) {           // the stored costs are relative to this frame's best from here on
+    x.s.offset = uni(x.s.offset + (double)cut.best);
+    cut.best = 0.0f;
+  }
   __syncthreads();
   prof_mark(sm, kPhCutoff);
 }
@@ -1352,7 +1365,7 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     if (nw > a.max_words) flags |= WFST_FLAG_TRUNCATED;
     if (broken) { flags |= WFST_FLAG_CAPACITY; nw = 0; }
     a.nwords[io] = min(nw, a.max_words);
-    a.cost[io] = ord2f((unsigned)(best >> 32));
+    a.cost[io] = x.c.cost_offset ? (float)((double)ord2f((unsigned)(best >> 32)) + x.s.offset) : ord2f((unsigned)(best >> 32));
     a.flags[io] = flags;
     sm.red64 = 0;
     sm.sel_idx = nw;
@@ -1382,7 +1395,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.s = c.st[ch];
   x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
-  x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio);
+  x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio); x.s.offset = uni(x.s.offset);
   x.s.boost_n = uni(x.s.boost_n);
   if (x.s.boost_n > 0)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
@@ -1405,7 +1418,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   bool stop = false;
   if (a.mode & kModeInit) {
     // start token, closed over epsilon arcs with best = 0 and no bin limit
-    x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0;
+    x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0; x.s.offset = 0.0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
     int2 *NQ = x.q0 + c.qcap;
     if (tid == 0) { sm.n_next = 1; sm.n_in = 1; sm.n_emit = 1; }
@@ -1877,6 +1890,7 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
   if ((rc = dev_alloc(d, &c.frame_off, N * (size_t)(c.max_frames + 2)))) return rc;
   if (o.keep_token_records && (rc = dev_alloc(d, &c.tokrec, N * (size_t)c.lat_cap))) return rc;
+  c.cost_offset = o.cost_offset ? 1 : 0;
   if (o.record_digests) {
     if ((rc = dev_alloc(d, &c.dig_sum, N * (size_t)(c.max_frames + 1)))) return rc;
     if ((rc = dev_alloc(d, &c.dig_cnt, N * (size_t)(c.max_frames + 1)))) return rc;
@@ -1972,6 +1986,8 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
     return fail(nullptr, WFST_ERR_INVALID_ARG, "max_channels, max_frames_per_channel and max_words must be >= 1");
   if (opts->loglike_dtype < WFST_LOGLIKE_F32 || opts->loglike_dtype > WFST_LOGLIKE_BF16)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "loglike_dtype must be WFST_LOGLIKE_F32, _F16 or _BF16");
+  if (opts->cost_offset && opts->keep_token_records)
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "cost_offset and keep_token_records cannot be combined");
   if (opts->candidate_capacity < 0 || (opts->candidate_capacity > 0 && opts->candidate_capacity < 4096))
     return fail(nullptr, WFST_ERR_INVALID_ARG, "candidate_capacity must be 0 or >= 4096");
   if (graph->num_classes > kMaxV)

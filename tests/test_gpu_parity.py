@@ -35,17 +35,20 @@ def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, thre
 
 
 def check_batch(torch, graph, loglikes, lengths, beam, max_active, max_words=256, refs=None,
-                max_active_hint=None, check_counters=True, boosts=None, device_loglikes=None, **deckw):
+                max_active_hint=None, check_counters=True, boosts=None, device_loglikes=None, cost_offset=False,
+                **deckw):
     from paper_2311_04996_amd import Decoder
     B, T, V = loglikes.shape
     dec = Decoder(graph, max_channels=max(B, 1), max_frames=max(T, 1), max_words=max_words,
-                  max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True, **deckw)
+                  max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True,
+                  cost_offset=cost_offset, **deckw)
     ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda() if device_loglikes is None else device_loglikes
     words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active, boosts=boosts)
     torch.cuda.synchronize()
     words, nwords, cost, flags = words.cpu().numpy(), nwords.cpu().numpy(), cost.cpu().numpy(), flags.cpu().numpy()
     if refs is None:
-        refs = oracle_batch(graph, loglikes, lengths, beam, max_active, max_words, boosts=boosts)
+        refs = oracle_batch(graph, loglikes, lengths, beam, max_active, max_words, boosts=boosts,
+                            cost_offset=cost_offset)
     near_ties = 0
     for b, r in enumerate(refs):
         cnt, dig = dec.debug_frame_digests(b)
@@ -497,3 +500,54 @@ def test_c5_boosted_medium_batch_matches_oracle(torch_cuda):
     refs = check_batch(torch_cuda, w.graph, w.loglikes, w.lengths, w.beam, w.max_active, boosts=w.boosts)
     plain = oracle_batch(w.graph, w.loglikes[:4], w.lengths[:4], w.beam, w.max_active)
     assert any(r.cost != p.cost for r, p in zip(refs, plain)), "the tables must matter"
+
+
+# ------------------------------------------------------------------------------- cost offsets
+def test_cost_offsets_match_the_oracle_with_the_same_option(torch_cuda, c1, c2):
+    """Token costs rebased after every prune step: token sets (rebased costs), words, cost and
+    flags equal the oracle's with cost_offset, on the tiny configuration, micro graphs with
+    ties and negative epsilon weights, boosted utterances and part of the medium batch."""
+    from workloads import micro_graph
+    check_batch(torch_cuda, c1.graph, c1.loglikes, c1.lengths, c1.beam, c1.max_active, cost_offset=True)
+    check_batch(torch_cuda, c1.graph, c1.loglikes, c1.lengths, 4.0, 50, max_active_hint=2000, cost_offset=True)
+    for seed in range(8):
+        rng = np.random.default_rng(5000 + seed)
+        V, T, B = 3, 9, 4
+        g = micro_graph(2000 + seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+        ll = -(rng.integers(0, 40, size=(B, T, V)).astype(np.float32) / 8.0)
+        lengths = rng.integers(1, T + 1, size=B).astype(np.int32)
+        boosts = [(rng.choice(5, size=3, replace=False).astype(np.int32) + 1,
+                   -(rng.integers(1, 9, size=3).astype(np.float32) / 4.0)) for _ in range(B)]
+        boosts[2] = None
+        for beam, ma in ((INF, IMAX), (3.0, 6)):
+            check_batch(torch_cuda, g, ll, lengths, beam, ma, max_active_hint=1000, boosts=boosts, cost_offset=True)
+    n = 6
+    check_batch(torch_cuda, c2.graph, c2.loglikes[:n], c2.lengths[:n], c2.beam, c2.max_active, cost_offset=True)
+
+
+def test_cost_offsets_in_a_streamed_channel(torch_cuda, c2):
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    b = 1
+    L = int(c2.lengths[b])
+    ref = Oracle(c2.graph).decode(c2.loglikes[b], length=L, beam=c2.beam, max_active=c2.max_active,
+                                  want_digests=True, cost_offset=True)
+    dec = Decoder(c2.graph, max_channels=1, max_frames=L, max_active_hint=c2.max_active, record_digests=True,
+                  cost_offset=True)
+    ll = torch.from_numpy(c2.loglikes[b:b + 1]).cuda()
+    dec.init_channel(0, c2.beam, c2.max_active)
+    for t0 in range(0, L, 37):
+        n = min(37, L - t0)
+        dec.advance_chunk([0], ll[:, t0:t0 + n].contiguous(), [n])
+    cnt, dig = dec.debug_frame_digests(0)
+    assert (cnt == ref.digest_count).all() and (dig == ref.digest_sum).all()
+    w, c, f = dec.get_partial(0, finalize=True)
+    assert w.tolist() == ref.words.tolist() and c == np.float32(ref.cost) and f == ref.flags
+    dec.close()
+
+
+def test_cost_offsets_and_token_records_are_refused_together(torch_cuda, c1):
+    from paper_2311_04996_amd import Decoder, WfstError
+    with pytest.raises(WfstError, match="cannot be combined"):
+        Decoder(c1.graph, max_channels=1, max_frames=10, keep_token_records=True, cost_offset=True)
