@@ -551,3 +551,35 @@ def test_cost_offsets_and_token_records_are_refused_together(torch_cuda, c1):
     from paper_2311_04996_amd import Decoder, WfstError
     with pytest.raises(WfstError, match="cannot be combined"):
         Decoder(c1.graph, max_channels=1, max_frames=10, keep_token_records=True, cost_offset=True)
+
+
+# ------------------------------------------------------------------------------- a sweep of small configurations
+def test_random_small_configurations(torch_cuda):
+    """Thirty seeded combinations of graph shape (epsilon share up to 45 %, hubs of up to 700 arcs),
+    class count, beam, max-active, batch and length mix (0- and 1-frame utterances included),
+    half of them with cost offsets, a third with 16-bit rows."""
+    from workloads import ctc_loglikes, tlg_shaped_graph
+    torch = torch_cuda
+    for seed in range(30):
+        rng = np.random.default_rng(9100 + seed)
+        S = int(rng.integers(300, 6000))
+        V = int(rng.choice([2, 5, 33, 129, 700]))
+        g = tlg_shaped_graph(4000 + seed, S, int(S * rng.uniform(1.5, 6.0)), num_classes=V,
+                             alpha=float(rng.uniform(1.6, 3.0)), k_max=int(rng.choice([20, 200, 700])),
+                             p_eps=float(rng.uniform(0.0, 0.45)), num_words=200)
+        B = int(rng.integers(1, 7))
+        T = int(rng.integers(1, 40))
+        lengths = rng.integers(0, T + 1, size=B).astype(np.int32)
+        lengths[int(rng.integers(0, B))] = T
+        ll = ctc_loglikes(seed, lengths, T, V, sigma=float(rng.uniform(0.5, 3.0)), p_blank=float(rng.uniform(0.2, 0.8)),
+                          blank_boost=float(rng.uniform(1, 6)), token_boost=float(rng.uniform(1, 5)))
+        beam = float(rng.choice([0.5, 3.0, 9.0, 17.0, 40.0]))
+        ma = int(rng.choice([1, 7, 100, 1500, 20000]))
+        kw = {"cost_offset": bool(seed % 2)}
+        if seed % 3 == 0:
+            dt = "float16" if seed % 2 else "bfloat16"
+            dev = torch.from_numpy(ll).to(getattr(torch, dt)).cuda()
+            check_batch(torch, g, dev.float().cpu().numpy(), lengths, beam, ma, max_active_hint=4000,
+                        device_loglikes=dev, loglike_dtype=dt, **kw)
+        else:
+            check_batch(torch, g, ll, lengths, beam, ma, max_active_hint=4000, **kw)
