@@ -119,6 +119,14 @@ def _stream_ptr(stream):
     return C.c_void_p(s.cuda_stream)
 
 
+def _on(stream):
+    """Context in which torch allocates (and zero-fills) on the stream the kernel will run on: a
+    fill queued on another stream could land after the kernel has written its outputs."""
+    import contextlib
+    import torch
+    return contextlib.nullcontext() if stream is None else torch.cuda.stream(stream)
+
+
 class Decoder:
     """Owns one wfst_decoder handle.  Method names mirror the C entry points."""
 
@@ -180,10 +188,11 @@ class Decoder:
                        np.zeros(B, np.float32), np.zeros(B, np.int32))
             else:
                 dev = loglikes.device
-                out = (torch.zeros((B, self.max_words), dtype=torch.int32, device=dev),
-                       torch.zeros(B, dtype=torch.int32, device=dev),
-                       torch.zeros(B, dtype=torch.float32, device=dev),
-                       torch.zeros(B, dtype=torch.int32, device=dev))
+                with _on(stream):
+                    out = (torch.zeros((B, self.max_words), dtype=torch.int32, device=dev),
+                           torch.zeros(B, dtype=torch.int32, device=dev),
+                           torch.zeros(B, dtype=torch.float32, device=dev),
+                           torch.zeros(B, dtype=torch.int32, device=dev))
         ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
         if boosts is None:
             self._check(self.lib.wfst_decode_batch(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
@@ -228,12 +237,15 @@ class Decoder:
             self._check(self.lib.wfst_get_partial(self.h, ch, int(finalize), w.ctypes.data, cap, n.ctypes.data,
                                                   c.ctypes.data, f.ctypes.data, _stream_ptr(stream)))
             return w[:n[0]].copy(), float(c[0]), int(f[0])
-        w = torch.zeros(cap, dtype=torch.int32, device="cuda")
-        n = torch.zeros(1, dtype=torch.int32, device="cuda")
-        c = torch.zeros(1, dtype=torch.float32, device="cuda")
-        f = torch.zeros(1, dtype=torch.int32, device="cuda")
+        with _on(stream):
+            w = torch.zeros(cap, dtype=torch.int32, device="cuda")
+            n = torch.zeros(1, dtype=torch.int32, device="cuda")
+            c = torch.zeros(1, dtype=torch.float32, device="cuda")
+            f = torch.zeros(1, dtype=torch.int32, device="cuda")
         self._check(self.lib.wfst_get_partial(self.h, ch, int(finalize), w.data_ptr(), cap, n.data_ptr(),
                                               c.data_ptr(), f.data_ptr(), _stream_ptr(stream)))
+        if stream is not None:
+            stream.synchronize()                 # the copies below run on torch's current stream
         k = int(n.item())
         return w[:k].cpu().numpy(), float(c.item()), int(f.item())
 
@@ -248,10 +260,11 @@ class Decoder:
                 out = (np.zeros((n, self.max_words), np.int32), np.zeros(n, np.int32),
                        np.zeros(n, np.float32), np.zeros(n, np.int32))
             else:
-                out = (torch.zeros((n, self.max_words), dtype=torch.int32, device="cuda"),
-                       torch.zeros(n, dtype=torch.int32, device="cuda"),
-                       torch.zeros(n, dtype=torch.float32, device="cuda"),
-                       torch.zeros(n, dtype=torch.int32, device="cuda"))
+                with _on(stream):
+                    out = (torch.zeros((n, self.max_words), dtype=torch.int32, device="cuda"),
+                           torch.zeros(n, dtype=torch.int32, device="cuda"),
+                           torch.zeros(n, dtype=torch.float32, device="cuda"),
+                           torch.zeros(n, dtype=torch.int32, device="cuda"))
         ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
         self._check(self.lib.wfst_get_partial_batch(self.h, channels.ctypes.data, n, int(finalize),
                                                     ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3]),
@@ -272,9 +285,10 @@ class Decoder:
         nt, nl = C.c_int64(), C.c_int64()
 
         def call(tc, lc):
-            st = torch.zeros(max(tc, 1), dtype=torch.int32, device="cuda")
-            co = torch.zeros(max(tc, 1), dtype=torch.float32, device="cuda")
-            lk = torch.zeros(max(lc, 1) * LINK_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
+            with _on(stream):
+                st = torch.zeros(max(tc, 1), dtype=torch.int32, device="cuda")
+                co = torch.zeros(max(tc, 1), dtype=torch.float32, device="cuda")
+                lk = torch.zeros(max(lc, 1) * LINK_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
             rc = self.lib.wfst_get_lattice(self.h, ch, loglikes.data_ptr(), float(lattice_beam),
                                            st.data_ptr(), co.data_ptr(), tc, off.ctypes.data, lk.data_ptr(), lc,
                                            C.byref(nt), C.byref(nl), _stream_ptr(stream))

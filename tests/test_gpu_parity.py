@@ -336,7 +336,22 @@ def test_c3_full_batch_sampled_against_oracle(torch_cuda):
         assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all(), f"utt {b}: token sets differ"
         assert words[b, :nwords[b]].tolist() == r.words.tolist(), f"utt {b}: words differ"
         assert cost[b] == np.float32(r.cost) and int(flags[b]) == r.flags
-    dec.close()
+    # the launch configuration bench.py times: three decoders, each on its own stream, the batch
+    # decoded by all three at once; every output of every decoder must equal the first run's
+    decs = [dec] + [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active,
+                            record_digests=True) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in decs]
+    torch.cuda.synchronize()
+    outs = [d.decode_batch(ll, w.lengths, w.beam, w.max_active, stream=st) for d, st in zip(decs, streams)]
+    torch.cuda.synchronize()
+    for k, out in enumerate(outs):
+        assert (out[0].cpu().numpy() == words).all() and (out[1].cpu().numpy() == nwords).all(), f"decoder {k}"
+        assert (out[2].cpu().numpy() == cost).all() and (out[3].cpu().numpy() == flags).all(), f"decoder {k}"
+        for b, r in list(zip(sample.tolist(), refs))[:3]:
+            cnt, dig = decs[k].debug_frame_digests(b)
+            assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all(), f"decoder {k}, utt {b}"
+    for d in decs:
+        d.close()
 
 
 # ------------------------------------------------------------------------------- internal paths
