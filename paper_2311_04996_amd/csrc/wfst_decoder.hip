@@ -1743,6 +1743,7 @@ struct wfst_decoder {
   // word-boost tables: pinned host staging per channel (keys, values, count) + what is on the device
   int *h_boost = nullptr;            // [channels][2 * kBoostSlots + 1]
   std::vector<int> boost_on_dev;     // entries of the table each channel currently has on the device
+  std::vector<hipEvent_t> boost_ev;  // per channel: recorded after the copies out of its staging area
   std::vector<unsigned> blk_of_state;  // [S + 1] block number of every state (and the block count)
   std::vector<int> state_of_blk;       // inverse, built when a debug call first needs it
   hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
@@ -1953,6 +1954,11 @@ int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st
   if (n > 0 && (!t->word_ids || !t->scores)) return fail(d, WFST_ERR_INVALID_ARG, "null boost table arrays");
   int *h = d->h_boost + (size_t)ch * (2 * kBoostSlots + 1);
   int *keys = h; float *vals = reinterpret_cast<float *>(h + kBoostSlots); int *cnt = h + 2 * kBoostSlots;
+  // the channel's staging area is pinned memory that earlier asynchronous copies may still be
+  // reading (a boosted call returns before its copies have run): wait for them before rewriting it
+  if (d->boost_ev.empty()) d->boost_ev.assign((size_t)d->opts.max_channels, nullptr);
+  if (d->boost_ev[ch]) HIP_TRY(d, hipEventSynchronize(d->boost_ev[ch]));
+  else HIP_TRY(d, hipEventCreateWithFlags(&d->boost_ev[ch], hipEventDisableTiming));
   std::memset(h, 0, (2 * kBoostSlots + 1) * sizeof(int));
   for (int i = 0; i < n; ++i) {
     const int w = t->word_ids[i];
@@ -1971,6 +1977,7 @@ int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st
     HIP_TRY(d, hipMemcpyAsync(d->c.boost_vals + (size_t)ch * kBoostSlots, vals, kBoostSlots * sizeof(float), hipMemcpyHostToDevice, st));
   }
   HIP_TRY(d, hipMemcpyAsync(&d->c.st[ch].boost_n, cnt, sizeof(int), hipMemcpyHostToDevice, st));
+  HIP_TRY(d, hipEventRecord(d->boost_ev[ch], st));
   d->boost_on_dev[ch] = n;
   return WFST_OK;
 }
@@ -2014,6 +2021,7 @@ int32_t wfst_decoder_destroy(wfst_decoder *d) {
   if (d->h_boost) (void)hipHostFree(d->h_boost);
   if (d->ev0) (void)hipEventDestroy(d->ev0);
   if (d->ev1) (void)hipEventDestroy(d->ev1);
+  for (hipEvent_t e : d->boost_ev) if (e) (void)hipEventDestroy(e);
   delete d;
   return WFST_OK;
 }

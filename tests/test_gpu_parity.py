@@ -598,3 +598,31 @@ def test_random_small_configurations(torch_cuda):
                         device_loglikes=dev, loglike_dtype=dt, **kw)
         else:
             check_batch(torch, g, ll, lengths, beam, ma, max_active_hint=4000, **kw)
+
+
+def test_boost_tables_change_from_call_to_call_without_waiting(torch_cuda):
+    """Boosted batches back to back on one decoder, a different table per utterance and per call,
+    no synchronisation between the calls: the tables are staged in pinned memory that the
+    previous call's copies may still be reading."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    from workloads import ctc_loglikes, tlg_shaped_graph
+    torch = torch_cuda
+    g = tlg_shaped_graph(77, 3000, 15000, num_classes=33, p_eps=0.2, num_words=60, p_olabel=0.5)
+    B, T = 6, 30
+    lengths = np.full(B, T, np.int32)
+    ll = ctc_loglikes(78, lengths, T, 33, sigma=1.5, p_blank=0.5, blank_boost=3.0, token_boost=2.0)
+    dev = torch.from_numpy(ll).cuda()
+    rng = np.random.default_rng(79)
+    calls = [[(rng.choice(60, size=20, replace=False).astype(np.int32) + 1,
+               -rng.uniform(0.5, 4.0, size=20).astype(np.float32)) for _ in range(B)] for _ in range(6)]
+    dec = Decoder(g, max_channels=B, max_frames=T, max_active_hint=2000)
+    outs = [dec.decode_batch(dev, lengths, 12.0, 1500, boosts=bs) for bs in calls]
+    torch.cuda.synchronize()
+    o = Oracle(g)
+    for bs, out in zip(calls, outs):
+        words, nwords, cost = out[0].cpu().numpy(), out[1].cpu().numpy(), out[2].cpu().numpy()
+        for b in range(B):
+            r = o.decode(ll[b], beam=12.0, max_active=1500, boost=bs[b])
+            assert words[b, :nwords[b]].tolist() == r.words.tolist() and cost[b] == np.float32(r.cost)
+    dec.close()
