@@ -201,18 +201,19 @@ struct TableLds {             // live while candidates are being recombined
 };
 struct Smem {
   union { ExpandLds e; TableLds t; } u;
-  EpsLds ek;                  // beside the table: a small round's candidates go into it while they are made
+  EpsLds ek;                  // beside the table: a round's candidates go into the table while its items are
+                              // expanded; afterwards the same memory lists the tokens that got better
   unsigned hist[256];
   unsigned wave_tot[kWaves];
   unsigned best_ord;
   int n_reg[kRegions];        // candidates per region
-  int n_pairs, n_hub, next_run, done_waves;
+  int n_pairs, n_hub, next_run, done_waves;   // improved tokens listed; listed hub states; ExpandArcs run counter; waves done listing
   int n_win, n_next, n_wl_next, status;
   int n_in, n_emit, n_back;   // tokens of the emitting step an epsilon arc can enter (they come first), all of them; back counter
   int k_sel, n_sel, k_keep, redo;
   unsigned long long red64, red64b;
   long long ctr[8];
-  unsigned short occ[kTabSlots];   // occupied table slots, compacted
+  unsigned short occ[kTabSlots];   // table slot of the candidate at each position of a pass (0xFFFF: not inserted)
   int bk[kBoostSlots]; float bv[kBoostSlots];   // the channel's word-boost table, if it has one
   long long prof[16];         // wall-clock ticks per phase (thread 0)
   long long prof_t0;
