@@ -155,3 +155,29 @@ def test_links_grow_with_the_lattice_beam(c1):
             assert prev <= cur
         prev = cur
     assert len(prev) > len(L.states)            # a real lattice: more links than tokens
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_boosted_lattice_equals_the_lattice_of_the_composed_graph(seed):
+    """Word boosting on the fly (scores added on arcs whose output label is in the table) against
+    the same graph with the scores added to the arc weights beforehand: same token sets, same
+    links, same costs.  Dyadic values, so both orders of addition are exact."""
+    rng = np.random.default_rng(9500 + seed)
+    V, T = 3, int(rng.integers(1, 8))
+    g = micro_graph(800 + seed, num_states=int(rng.integers(4, 30)), num_classes=V, max_deg=4, dyadic=True,
+                    p_eps=0.35, neg_eps=False)
+    ll = dyadic_loglikes(200 + seed, T, V)
+    ids = np.array([1, 3, 5], np.int32)
+    scores = -(rng.integers(1, 9, size=3).astype(np.float32) / 4.0)
+    b = np.zeros(int(g.olabel.max()) + 1, np.float32)
+    b[ids[ids < len(b)]] = scores[ids < len(b)]
+    g2 = Graph(g.num_states, g.start_state, V, g.row_offsets, g.next_state, g.ilabel, g.olabel,
+               (g.weight + b[g.olabel]).astype(np.float32), g.final_cost, {})
+    for beam, ma, lb in ((INF, IMAX, INF), (3.0, 6, 1.0)):
+        o1, o2 = Oracle(g), Oracle(g2)
+        L1 = o1.lattice(ll, beam=beam, max_active=ma, lattice_beam=lb, boost=(ids, scores))
+        L2 = o2.lattice(ll, beam=beam, max_active=ma, lattice_beam=lb)
+        assert L1.set_off.tolist() == L2.set_off.tolist()
+        key = lambda L, o: sorted((int(f), o.original_arc(int(a)), float(c)) for f, a, c in zip(L.frame, L.arc, L.cost))
+        assert key(L1, o1) == key(L2, o2)
+        assert L1.result.words.tolist() == L2.result.words.tolist() and L1.result.cost == L2.result.cost
