@@ -92,7 +92,9 @@ typedef struct {
                                      length (the paper is silent on cost renormalisation; without it a
                                      stream of 40,000 frames loses the exact best path to rounding).
                                      Results can differ from cost_offset = 0 in the last bits of costs
-                                     and in near-ties.  Not combined with keep_token_records */
+                                     and in near-ties.  Stored token costs, and with them the costs in a
+                                     lattice, are the rebased ones (a link's cost is in the base of the
+                                     token it enters) */
 } wfst_opts;
 
 #define WFST_LOGLIKE_F32 0

@@ -53,7 +53,8 @@
  *       cost = (float)((double)c_final + sum).  Stored token costs (digests, dumps) are the
  *       rebased ones.  Costs then stay of the order of the beam however long the stream is.
  *       Pins: identical results on exactly representable (dyadic) inputs, and a smaller error
- *       against an fp64 trellis on a long stream.  Not combined with the lattice output.
+ *       against an fp64 trellis on a long stream.  In the lattice (R10) the cost of an emitting
+ *       link into A_t is rebased like the tokens of A_t: (cost through the arc) - b_t.
  *
  * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
  * Viterbi, greedy CTC collapse on the normal CTC topology, closed-form histogram cases,
@@ -319,14 +320,17 @@ typedef struct { int32_t prev, arc; } bp_t;
  *   digest_count/digest_sum [len+1]: per closed token set A_0..A_len, its size and the sum
  *     over tokens of mix64(state<<32 | cost bits) modulo 2^64;
  *   path_arcs [path_cap]: global arc ids of the best path in order (res->path_len of them);
- *   dump_off [len+2], dump_states/dump_costs [dump_cap]: every closed token set.
+ *   dump_off [len+2], dump_states/dump_costs [dump_cap]: every closed token set;
+ *   frame_best [len+1]: with cost offsets (R11) the best cost b_t that the tokens of A_t were
+ *     rebased by (0 for A_0, for empty sets and without offsets).
  * Returns 0, or -1 on bad arguments, -2 if a dump/path buffer is too small.
  */
 int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t row_stride,
                       int32_t len, const oracle_opts *o, int32_t *words, oracle_result *res,
                       int32_t *digest_count, uint64_t *digest_sum,
                       int32_t *path_arcs, int32_t path_cap,
-                      int64_t *dump_off, int32_t *dump_states, float *dump_costs, int64_t dump_cap) {
+                      int64_t *dump_off, int32_t *dump_states, float *dump_costs, int64_t dump_cap,
+                      float *frame_best) {
   if (!p || !o || !res || len < 0 || o->max_words < 0 || !(o->beam >= 0.0f)) return -1;
   memset(res, 0, sizeof(*res));
   int32_t rc = 0;
@@ -349,6 +353,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       if (o->boost_ids[i] > 0 && o->boost_ids[i] <= max_ol) boost[o->boost_ids[i]] = o->boost_scores[i];
   }
 
+  if (frame_best) frame_best[0] = 0.0f;
   /* initial set: start token, closed over epsilon arcs with best = 0 and no bin limit */
   { token_t t = { p->start, 0.0f, -1, -1 }; map[p->start] = 0; tv_push(&cur, t); }
   k.best = 0.0f; k.k_keep = 256;
@@ -418,10 +423,12 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     }
     nxt.n = m;
     res->counters[3] += m;
+    if (frame_best) frame_best[t + 1] = 0.0f;
     if (o->cost_offset && m > 0) {              /* R11 */
       for (int32_t i = 0; i < m; ++i) nxt.t[i].cost = canon(nxt.t[i].cost - best);
       offset_sum += (double)best;
       k.best = 0.0f;
+      if (frame_best) frame_best[t + 1] = best;
     }
     /* ---- epsilon closure under the frozen predicate (R6) */
     eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1, boost);
@@ -485,12 +492,14 @@ done:
  * link, ordered by frame, then epsilon links before emitting links, then source token, then
  * arc: l_frame = t of the destination set A_t; l_src / l_dst = token positions inside their
  * sets (the source of an emitting link lies in A_{t-1}, of an epsilon link in A_t); l_arc =
- * global arc id (R3); l_cost = cost through the arc.  Returns the number of links (only the
- * first `cap` are written), or -1 on bad arguments.
+ * global arc id (R3); l_cost = cost through the arc.  frame_best: NULL, or the per-set offsets
+ * of a decode with cost offsets (R11).  Returns the number of links (only the first `cap` are
+ * written), or -1 on bad arguments.
  */
 int64_t oracle_lattice_links(const oracle_prepared *p, const float *loglikes, int64_t row_stride,
                              int32_t len, const oracle_opts *o, float lattice_beam,
                              const int64_t *set_off, const int32_t *set_states, const float *set_costs,
+                             const float *frame_best,
                              int64_t cap, int32_t *l_frame, int32_t *l_src, int32_t *l_dst,
                              int32_t *l_arc, float *l_cost) {
   if (!p || !o || len < 0 || !set_off || !(lattice_beam >= 0.0f)) return -1;
@@ -531,6 +540,7 @@ int64_t oracle_lattice_links(const oracle_prepared *p, const float *loglikes, in
         for (int64_t a = p->e_off[S0[i]]; a < p->e_off[S0[i] + 1]; ++a) {
           float nc = canon((C0[i] + p->e_w[a]) + (-L[p->e_il[a] - 1]));
           if (boost && p->e_ol[a] != 0) nc = canon(nc + boost[p->e_ol[a]]);
+          if (frame_best) nc = canon(nc - frame_best[t]);    /* into the cost base of A_t */
           const int32_t j = where[p->e_next[a]];
           if (!(nc < INFINITY) || j < 0) continue;
           if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, a, nc);

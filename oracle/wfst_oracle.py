@@ -71,11 +71,11 @@ def _load():
         _lib.oracle_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                        C.POINTER(_Opts), C.c_void_p, C.POINTER(_Result),
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         _lib.oracle_lattice_links.restype = C.c_int64
         _lib.oracle_lattice_links.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                               C.POINTER(_Opts), C.c_float, C.c_void_p, C.c_void_p,
-                                              C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
 
@@ -105,6 +105,7 @@ class OracleResult:
     digest_count: np.ndarray | None = None       # [len+1]
     digest_sum: np.ndarray | None = None         # [len+1] uint64
     frames: list | None = field(default=None)    # per closed set: (states, costs)
+    frame_best: np.ndarray | None = None         # [len+1] offsets the sets were rebased by (cost offsets)
 
     @property
     def reached_final(self) -> bool:
@@ -208,9 +209,10 @@ class Oracle:
         else:
             cap, doff, dst, dco = 0, None, None, None
         ptr = lambda a: None if a is None else a.ctypes.data
+        fbest = np.zeros(n + 1, dtype=np.float32) if want_frames else None
         rc = lib.oracle_decode(self._p, ll.ctypes.data, ll.strides[0] // 4, n, C.byref(o),
                                words.ctypes.data, C.byref(res), ptr(dc), ptr(ds), ptr(path), pcap,
-                               ptr(doff), ptr(dst), ptr(dco), cap)
+                               ptr(doff), ptr(dst), ptr(dco), cap, ptr(fbest))
         if rc != 0:
             raise RuntimeError(f"oracle_decode failed: {rc}")
         frames = None
@@ -219,10 +221,10 @@ class Oracle:
                       for t in range(n + 1)]
         return OracleResult(words[:res.nwords].copy(), float(res.cost), int(res.flags),
                             np.array(list(res.counters), dtype=np.int64),
-                            None if path is None else path[:res.path_len].copy(), dc, ds, frames)
+                            None if path is None else path[:res.path_len].copy(), dc, ds, frames, fbest)
 
     def lattice(self, loglikes, length=None, beam=17.0, max_active=10000, lattice_beam=np.inf,
-                boost=None) -> "OracleLattice":
+                boost=None, cost_offset=False) -> "OracleLattice":
         """Decode, then list the lattice links between the stored token sets (reading R10 in
         the C source): every arc between two stored tokens whose cost through the arc is within
         `lattice_beam` of the destination token's cost."""
@@ -233,7 +235,7 @@ class Oracle:
         while True:                                   # the closure can grow a set well past max_active
             try:
                 res = self.decode(ll, n, beam, max_active, want_frames=True, want_path=True, boost=boost,
-                                  frames_cap=cap)
+                                  frames_cap=cap, cost_offset=cost_offset)
                 break
             except RuntimeError as e:
                 if "-2" not in str(e) or cap > (1 << 31):
@@ -246,11 +248,12 @@ class Oracle:
         if boost is not None:
             b_ids = np.ascontiguousarray(boost[0], dtype=np.int32)
             b_sc = np.ascontiguousarray(boost[1], dtype=np.float32)
-            o = _Opts(beam, max_active, 0, 1, 0, 0, len(b_ids), b_ids.ctypes.data, b_sc.ctypes.data)
+            o = _Opts(beam, max_active, 0, 1, 0, 0, len(b_ids), b_ids.ctypes.data, b_sc.ctypes.data, int(cost_offset))
         else:
-            o = _Opts(beam, max_active, 0, 1, 0, 0, 0, None, None)
+            o = _Opts(beam, max_active, 0, 1, 0, 0, 0, None, None, int(cost_offset))
+        fb = np.ascontiguousarray(res.frame_best, dtype=np.float32) if cost_offset else None
         args = (self._p, ll.ctypes.data, ll.strides[0] // 4, n, C.byref(o), float(lattice_beam),
-                off.ctypes.data, st.ctypes.data, co.ctypes.data)
+                off.ctypes.data, st.ctypes.data, co.ctypes.data, None if fb is None else fb.ctypes.data)
         m = lib.oracle_lattice_links(*args, 0, None, None, None, None, None)
         if m < 0:
             raise RuntimeError("oracle_lattice_links rejected its arguments")

@@ -156,6 +156,7 @@ struct DevChannels {
   int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
   int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
   int cost_offset;                             // 1: token costs are rebased to the best cost after every prune step
+  float *frame_best;                           // nullptr, or [channels][max_frames + 1]: the offset every token set was rebased by
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
   long long *counters;                         // [24]: 8 workload counters, 16 phase tick sums
@@ -1020,6 +1021,10 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     sm.ctr[kCtKept] += min(n_emit, x.c.qcap);
   }
   if (tid < kRegions) sm.n_reg[tid] = 0;
+  if (x.c.frame_best && tid == 0) {              // the lattice kernel needs it for links across this frame's boundary
+    const size_t chan = (size_t)(x.frame_off - x.c.frame_off) / (size_t)(x.c.max_frames + 2);
+    x.c.frame_best[chan * (size_t)(x.c.max_frames + 1) + (size_t)x.s.frame + 1] = n_emit > 0 ? cut.best : 0.0f;
+  }
   if (x.c.cost_offset && n_emit > 0) {           // the stored costs are relative to this frame's best from here on
     x.s.offset = uni(x.s.offset + (double)cut.best);
     cut.best = 0.0f;
@@ -1535,6 +1540,7 @@ struct LatPass {                              // block-uniform view of one pass
   const int2 *dst_rec; unsigned dst_base;     // records and first token number of A_t
   int t, p, P; bool boosted;
   unsigned long long links_base;              // where this set's links go
+  bool rebase; float set_best;                // cost offsets: the tokens of A_t were rebased by set_best
 };
 
 __device__ __forceinline__ int lat_group(int key, int P) {
@@ -1562,6 +1568,7 @@ __device__ __forceinline__ void lat_arc(const LatPass &q, int u, float tc, unsig
     }
     nc = canon(nc + b);
   }
+  if (!kEps && q.rebase) nc = canon(nc - q.set_best);      // into the cost base of A_t, as the decoder did
   if (!(nc < INFINITY)) return;
   unsigned sl = (hash_state(key) >> 6) & (kLatSlots - 1);
   int probes = 0;
@@ -1697,7 +1704,9 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
       if (probes < kLatSlots) sm.pos[sl] = (unsigned short)j;
     }
     __syncthreads();
-    const LatPass q{g, sm, a, rec + o1, o1, t, p, P, boosted, links_base};
+    const bool rebase = c.frame_best != nullptr && t > 0;
+    const float set_best = rebase ? c.frame_best[(size_t)a.ch * (c.max_frames + 1) + t] : 0.0f;
+    const LatPass q{g, sm, a, rec + o1, o1, t, p, P, boosted, links_base, rebase, set_best};
     lat_expand<true>(q, rec + o1, n1, o1);
     if (t > 0) lat_expand<false>(q, rec + o0, n0, o0);
   }
@@ -1893,6 +1902,7 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.frame_off, N * (size_t)(c.max_frames + 2)))) return rc;
   if (o.keep_token_records && (rc = dev_alloc(d, &c.tokrec, N * (size_t)c.lat_cap))) return rc;
   c.cost_offset = o.cost_offset ? 1 : 0;
+  if (o.cost_offset && o.keep_token_records && (rc = dev_alloc(d, &c.frame_best, N * (size_t)(c.max_frames + 1)))) return rc;
   if (o.record_digests) {
     if ((rc = dev_alloc(d, &c.dig_sum, N * (size_t)(c.max_frames + 1)))) return rc;
     if ((rc = dev_alloc(d, &c.dig_cnt, N * (size_t)(c.max_frames + 1)))) return rc;
@@ -1994,8 +2004,6 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
     return fail(nullptr, WFST_ERR_INVALID_ARG, "max_channels, max_frames_per_channel and max_words must be >= 1");
   if (opts->loglike_dtype < WFST_LOGLIKE_F32 || opts->loglike_dtype > WFST_LOGLIKE_BF16)
     return fail(nullptr, WFST_ERR_INVALID_ARG, "loglike_dtype must be WFST_LOGLIKE_F32, _F16 or _BF16");
-  if (opts->cost_offset && opts->keep_token_records)
-    return fail(nullptr, WFST_ERR_INVALID_ARG, "cost_offset and keep_token_records cannot be combined");
   if (opts->candidate_capacity < 0 || (opts->candidate_capacity > 0 && opts->candidate_capacity < 4096))
     return fail(nullptr, WFST_ERR_INVALID_ARG, "candidate_capacity must be 0 or >= 4096");
   if (graph->num_classes > kMaxV)

@@ -40,15 +40,16 @@ def gpu_rows(lat):
 
 
 def check_lattice(torch, g, ll, length, beam, ma, lattice_beam, boost=None, hint=None, dtype="float32",
-                  streaming_chunk=None):
+                  streaming_chunk=None, cost_offset=False):
     from oracle import Oracle
     from paper_2311_04996_amd import Decoder
     o = Oracle(g)
     lld = torch.from_numpy(np.ascontiguousarray(ll[None, :max(length, 1)])).to(getattr(torch, dtype)).cuda()
     ll_ref = lld[0].float().cpu().numpy()
-    L = o.lattice(ll_ref, length, beam=beam, max_active=ma, lattice_beam=lattice_beam, boost=boost)
+    L = o.lattice(ll_ref, length, beam=beam, max_active=ma, lattice_beam=lattice_beam, boost=boost,
+                  cost_offset=cost_offset)
     dec = Decoder(g, max_channels=1, max_frames=max(length, 1), max_active_hint=hint or min(ma, 20000),
-                  keep_token_records=True, loglike_dtype=dtype)
+                  keep_token_records=True, loglike_dtype=dtype, cost_offset=cost_offset)
     if streaming_chunk is None:
         dec.decode_batch(lld, [length], beam, ma, boosts=None if boost is None else [boost])
     else:
@@ -189,3 +190,19 @@ def test_lattice_errors(torch_cuda, c1):
     again = dec.get_lattice(0, ll[0], 1.0, tok_cap=len(full.state), link_cap=len(full.links))
     assert (gpu_rows(full) == gpu_rows(again)).all()
     dec.close()
+
+
+def test_lattice_with_cost_offsets(torch_cuda, c1):
+    """Token costs rebased every frame: links across a frame boundary are rebased like the tokens
+    they enter; equal to the oracle with the same option, batch and streamed."""
+    from workloads import micro_graph
+    for seed in range(6):
+        rng = np.random.default_rng(480 + seed)
+        V, T = 3, int(rng.integers(1, 9))
+        g = micro_graph(770 + seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+        ll = -(rng.integers(0, 40, size=(T, V)).astype(np.float32) / 8.0)
+        for beam, ma, lb in ((INF, IMAX, INF), (3.0, 6, 1.5)):
+            check_lattice(torch_cuda, g, ll, T, beam, ma, lb, hint=1000, cost_offset=True)
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, 2.0, cost_offset=True)
+    check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, 2.0, cost_offset=True,
+                  streaming_chunk=16)

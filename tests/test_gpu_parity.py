@@ -562,12 +562,6 @@ def test_cost_offsets_in_a_streamed_channel(torch_cuda, c2):
     dec.close()
 
 
-def test_cost_offsets_and_token_records_are_refused_together(torch_cuda, c1):
-    from paper_2311_04996_amd import Decoder, WfstError
-    with pytest.raises(WfstError, match="cannot be combined"):
-        Decoder(c1.graph, max_channels=1, max_frames=10, keep_token_records=True, cost_offset=True)
-
-
 # ------------------------------------------------------------------------------- a sweep of small configurations
 def test_random_small_configurations(torch_cuda):
     """Thirty seeded combinations of graph shape (epsilon share up to 45 %, hubs of up to 700 arcs),

@@ -57,3 +57,21 @@ def test_offsets_keep_a_long_stream_precise():
     want, _ = greedy_ctc(ll)
     assert off.words.tolist() == want.tolist()
     assert plain.words.tolist() != want.tolist()
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_lattice_with_offsets_has_the_same_links_and_differences(seed):
+    """Dyadic inputs: with cost offsets the lattice has the same links, and every link's cost
+    exceeds its destination token's stored cost by exactly as much as without offsets."""
+    rng = np.random.default_rng(3500 + seed)
+    V, T = 3, int(rng.integers(1, 9))
+    g = micro_graph(1700 + seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+    ll = -(rng.integers(0, 40, size=(T, V)).astype(np.float32) / 8.0)
+    o = Oracle(g)
+    for beam, ma, lb in ((INF, IMAX, INF), (3.0, 6, 1.5), (3.0, 6, 0.0)):
+        a = o.lattice(ll, beam=beam, max_active=ma, lattice_beam=lb)
+        b = o.lattice(ll, beam=beam, max_active=ma, lattice_beam=lb, cost_offset=True)
+        def rows(L):
+            diff = L.cost.astype(np.float64) - L.costs[L.dst_global()].astype(np.float64)
+            return sorted(zip(L.frame.tolist(), L.states[L.src_global()].tolist(), L.arc.tolist(), diff.tolist()))
+        assert rows(a) == rows(b)
