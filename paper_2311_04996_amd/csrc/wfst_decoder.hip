@@ -1164,9 +1164,12 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
             const int vi = i0 + k * kBlock + tid;
             const int tok = vi < n_in ? vi : vi + n_skip;
             unsigned sl = (hash_state(tk[k].x) >> 6) & kTabMask;
-            int probes = 0, key = vi < n_have ? t.keys[sl] : kKeyEmpty;
+            // (a token that did not fit the lattice arena was never written: the channel stops after
+            // this frame, and its queue position must not be looked at)
+            const bool real = vi < n_have && lat_base + (unsigned)tok < x.c.lat_cap;
+            int probes = 0, key = real ? t.keys[sl] : kKeyEmpty;
             while (key != tk[k].x && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
-            if (key == tk[k].x && vi < n_have) {
+            if (key == tk[k].x && real) {
               const unsigned long long v = t.vals[sl];
               t.vals[sl] = kValEmpty;                      // this destination has its token
               const float nc = ord2f((unsigned)(v >> 32)), oc = __int_as_float(tk[k].y);

@@ -620,3 +620,31 @@ def test_boost_tables_change_from_call_to_call_without_waiting(torch_cuda):
             r = o.decode(ll[b], beam=12.0, max_active=1500, boost=bs[b])
             assert words[b, :nwords[b]].tolist() == r.words.tolist() and cost[b] == np.float32(r.cost)
     dec.close()
+
+
+def test_lattice_arena_overflow_in_a_batch_does_not_touch_the_neighbours(torch_cuda, c2):
+    """An arena too small for the long utterances of the batch: they stop with the overflow flag
+    (also when it strikes in the middle of an epsilon closure), and the utterances that fit -
+    whose arenas lie right behind the overflowing ones - still equal the oracle."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder, FLAG_LATTICE_OVERFLOW
+    torch = torch_cuda
+    n = 8
+    lengths = c2.lengths[:n].copy()
+    fit = int(np.sort(lengths)[n // 2])                       # about half of them fit
+    entries = int(1.05 * 9000 * (fit + 1))
+    dec = Decoder(c2.graph, max_channels=n, max_frames=int(lengths.max()), max_active_hint=c2.max_active,
+                  lattice_bytes_per_channel=8 * entries)
+    ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[:n])).cuda()
+    words, nwords, cost, flags = [t.cpu().numpy() for t in dec.decode_batch(ll, lengths, c2.beam, c2.max_active)]
+    dec.close()
+    o = Oracle(c2.graph)
+    n_over = 0
+    for b in range(n):
+        if flags[b] & FLAG_LATTICE_OVERFLOW:
+            n_over += 1
+            assert nwords[b] == 0
+            continue
+        r = o.decode(c2.loglikes[b], length=int(lengths[b]), beam=c2.beam, max_active=c2.max_active)
+        assert words[b, :nwords[b]].tolist() == r.words.tolist() and cost[b] == np.float32(r.cost) and flags[b] == r.flags
+    assert 0 < n_over < n
