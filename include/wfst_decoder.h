@@ -168,6 +168,10 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *dec, const float *loglikes, cons
  *                       cost [1], flags [1] follow opts.outputs_on_host.
  *   wfst_get_partial_batch: the same for n channels (HOST int32 channels[n]) in one launch;
  *                       words [n][max_words], nwords [n], cost [n], flags [n].
+ * The traceback behind a (partial) result is incremental: the library remembers the path of the
+ * channel's previous traceback and stops where the new one meets it, so a result after every
+ * chunk costs a walk over the new frames, not over the whole stream (only with cap ==
+ * opts.max_words; another cap takes the full walk).
  */
 int32_t wfst_init_channel(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
                           const wfst_boost_table *boost, void *stream);

@@ -227,10 +227,11 @@ class Decoder:
         self._check(self.lib.wfst_advance_chunk(self.h, channels.ctypes.data, n, loglikes.data_ptr(),
                                                 nframes.ctypes.data, Cn, V, _stream_ptr(stream)))
 
-    def get_partial(self, ch, finalize=False, stream=None):
-        """Returns (words ndarray, cost, flags) of the channel's best hypothesis so far."""
+    def get_partial(self, ch, finalize=False, stream=None, cap=None):
+        """Returns (words ndarray, cost, flags) of the channel's best hypothesis so far (at most
+        `cap` words, default the decoder's max_words)."""
         import torch
-        cap = self.max_words
+        cap = self.max_words if cap is None else int(cap)
         if self.outputs_on_host:
             w, n = np.zeros(cap, np.int32), np.zeros(1, np.int32)
             c, f = np.zeros(1, np.float32), np.zeros(1, np.int32)

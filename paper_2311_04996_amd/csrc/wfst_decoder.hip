@@ -135,6 +135,7 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   int max_active;
   float beam, scale;          // scale = 256 / beam, computed once on the host
   float sel_ratio;            // candidates taken into recombination per max_active (adaptive)
+  int path_frames;            // the traced-path marks of frames 1..path_frames are valid (0: none)
   int boost_n;                // entries of the channel's word-boost table (0 = none); set by the host
 };
 
@@ -156,6 +157,10 @@ struct DevChannels {
   int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
   int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
   int cost_offset;                             // 1: token costs are rebased to the best cost after every prune step
+  // the path of the last traceback, so that the next one can stop where it meets it:
+  int *path_tok, *path_nw;                     // [channels][max_frames + 1] per frame: the token the path enters the
+                                               // set with (over an emitting arc); words on the path up to and incl. that arc
+  int *path_words; int max_words;              // [channels][max_words] its words
   float *frame_best;                           // nullptr, or [channels][max_frames + 1]: the offset every token set was rebased by
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
@@ -212,6 +217,7 @@ struct Smem {
   int n_win, n_next, n_wl_next, status;
   int n_in, n_emit, n_back;   // tokens of the emitting step an epsilon arc can enter (they come first), all of them; back counter
   int k_sel, n_sel, k_keep, redo;
+  int path_frames, trace_from, trace_words;   // traceback: new marks valid up to; where the walk stopped; words before that
   unsigned long long red64, red64b;
   long long ctr[8];
   unsigned short occ[kTabSlots];   // table slot of the candidate at each position of a pass (0xFFFF: not inserted)
@@ -1345,10 +1351,21 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   // in LDS (the recombination table is idle now) that keeps the latest max_words of them, i.e.
   // the first max_words of the path, and all lanes then write them out in path order.  Only
   // when max_words exceeds the ring is the chain walked twice (count, then write).
+  // The walk is incremental: the previous traceback of the channel left, per frame, the token
+  // with which its path entered that frame's set and the number of words up to there, and
+  // its words.  Backpointers of stored frames never change, so when the new walk reaches such a
+  // token the rest of the path is the old one: the walk stops and the old words are kept.  A
+  // partial result after every chunk then costs a walk over the new frames (plus the distance
+  // to where the two paths join) instead of over the whole stream.
   int *ring = sm.u.t.keys;
   const bool one_walk = a.max_words <= kTabSlots;
+  const bool inc = one_walk && x.c.path_tok != nullptr && a.max_words == x.c.max_words;
+  const size_t chan = (size_t)(x.frame_off - x.c.frame_off) / (size_t)(x.c.max_frames + 2);
+  int *ptok = inc ? x.c.path_tok + chan * (size_t)(x.c.max_frames + 1) : nullptr;
+  int *pnw = inc ? x.c.path_nw + chan * (size_t)(x.c.max_frames + 1) : nullptr;
+  int *pwords = inc ? x.c.path_words + chan * (size_t)x.c.max_words : nullptr;
   if (tid == 0) {
-    int nw = 0;
+    int nw = 0, f_stop = 0, w_stop = 0;
     bool broken = false;
     for (int pass = one_walk ? 1 : 0; pass < 2; ++pass) {
       int f = x.s.frame, i = sm.sel_idx, k = 0;
@@ -1359,6 +1376,11 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
         if (li >= x.s.lat_used) { broken = true; break; }
         const int2 bp = x.lat[li];
         if (bp.y < 0) break;
+        const bool emitting = !((unsigned)bp.y & kArcEps);
+        if (inc && emitting) {
+          if (f <= x.s.path_frames && ptok[f] == i) { f_stop = f; w_stop = pnw[f]; break; }   // the old path from here on
+          ptok[f] = i; pnw[f] = k;                  // k: words after this arc; turned into words up to it below
+        }
         const int ol = x.g.unit[(unsigned)bp.y & kArcMask].w;
         if (ol != 0) {
           if (one_walk) ring[k % a.max_words] = ol;
@@ -1366,10 +1388,11 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
           ++k;
         }
         i = bp.x;
-        if (!((unsigned)bp.y & kArcEps)) --f;                  // an emitting arc consumed a frame
+        if (emitting) --f;                                      // an emitting arc consumed a frame
       }
       nw = k;
     }
+    nw += w_stop;
     if (any_final) flags |= WFST_FLAG_REACHED_FINAL;
     if (nw > a.max_words) flags |= WFST_FLAG_TRUNCATED;
     if (broken) { flags |= WFST_FLAG_CAPACITY; nw = 0; }
@@ -1378,11 +1401,22 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     a.flags[io] = flags;
     sm.red64 = 0;
     sm.sel_idx = nw;
+    sm.trace_from = f_stop; sm.trace_words = w_stop;
+    sm.path_frames = (inc && !broken) ? x.s.frame : 0;
   }
   __syncthreads();
   if (one_walk) {
-    const int nw = sm.sel_idx;                   // word k of the walk (0 = last word) sits in ring[k % max_words]
-    for (int p = tid; p < min(nw, a.max_words); p += kBlock) words[p] = ring[(nw - 1 - p) % a.max_words];
+    const int nw = sm.sel_idx, w_stop = sm.trace_words;   // new word k of the walk (0 = last word) sits in ring[k % max_words]
+    const int k_new = nw - w_stop;
+    if (inc) {
+      // marks of the frames walked: words after the arc -> words up to and including it
+      for (int f = sm.trace_from + 1 + tid; f <= x.s.frame; f += kBlock) pnw[f] = nw - pnw[f];
+      for (int p = w_stop + tid; p < min(nw, a.max_words); p += kBlock) pwords[p] = ring[(k_new - 1 - (p - w_stop)) % a.max_words];
+      __syncthreads();
+      for (int p = tid; p < min(nw, a.max_words); p += kBlock) words[p] = pwords[p];
+    } else {
+      for (int p = tid; p < min(nw, a.max_words); p += kBlock) words[p] = ring[(nw - 1 - p) % a.max_words];
+    }
   }
   __syncthreads();
 }
@@ -1427,7 +1461,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   bool stop = false;
   if (a.mode & kModeInit) {
     // start token, closed over epsilon arcs with best = 0 and no bin limit
-    x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0; x.s.offset = 0.0;
+    x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0; x.s.offset = 0.0; x.s.path_frames = 0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
     int2 *NQ = x.q0 + c.qcap;
     if (tid == 0) { sm.n_next = 1; sm.n_in = 1; sm.n_emit = 1; }
@@ -1489,7 +1523,9 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     // does the compiler know they are global and keep them in registers.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
     Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
+    if (tid == 0) sm.path_frames = x.s.path_frames;
     select_and_trace(x2, a2, io);
+    if (tid == 0) x.s.path_frames = sm.path_frames;      // thread 0's copy is the one that is stored
   }
   prof_mark(sm, kPhTrace);
   if (tid == 0) {
@@ -1905,6 +1941,10 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.frame_off, N * (size_t)(c.max_frames + 2)))) return rc;
   if (o.keep_token_records && (rc = dev_alloc(d, &c.tokrec, N * (size_t)c.lat_cap))) return rc;
   c.cost_offset = o.cost_offset ? 1 : 0;
+  c.max_words = o.max_words;
+  if ((rc = dev_alloc(d, &c.path_tok, N * (size_t)(c.max_frames + 1)))) return rc;
+  if ((rc = dev_alloc(d, &c.path_nw, N * (size_t)(c.max_frames + 1)))) return rc;
+  if ((rc = dev_alloc(d, &c.path_words, N * (size_t)o.max_words))) return rc;
   if (o.cost_offset && o.keep_token_records && (rc = dev_alloc(d, &c.frame_best, N * (size_t)(c.max_frames + 1)))) return rc;
   if (o.record_digests) {
     if ((rc = dev_alloc(d, &c.dig_sum, N * (size_t)(c.max_frames + 1)))) return rc;

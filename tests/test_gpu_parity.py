@@ -648,3 +648,35 @@ def test_lattice_arena_overflow_in_a_batch_does_not_touch_the_neighbours(torch_c
         r = o.decode(c2.loglikes[b], length=int(lengths[b]), beam=c2.beam, max_active=c2.max_active)
         assert words[b, :nwords[b]].tolist() == r.words.tolist() and cost[b] == np.float32(r.cost) and flags[b] == r.flags
     assert 0 < n_over < n
+
+
+def test_partial_results_after_every_chunk_equal_the_oracle_on_the_prefix(torch_cuda, c2):
+    """The traceback is incremental (it stops where it meets the path of the previous one):
+    after every chunk the partial hypothesis, with and without final costs, must be exactly the
+    oracle's result on the frames consumed so far; also with a word limit that truncates, and
+    with a caller buffer of another size (which takes the full walk)."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    b = 2
+    L = min(int(c2.lengths[b]), 230)
+    o = Oracle(c2.graph)
+    for max_words, chunk in ((256, 16), (5, 23)):
+        dec = Decoder(c2.graph, max_channels=2, max_frames=L, max_words=max_words, max_active_hint=c2.max_active)
+        ll = torch.from_numpy(c2.loglikes[b:b + 1, :L]).cuda()
+        dec.init_channel(1, c2.beam, c2.max_active)
+        for t0 in range(0, L, chunk):
+            n = min(chunk, L - t0)
+            dec.advance_chunk([1], ll[:, t0:t0 + n].contiguous(), [n])
+            for fin in (False, True, False):
+                w, c, f = dec.get_partial(1, finalize=fin)
+                r = o.decode(c2.loglikes[b], length=t0 + n, beam=c2.beam, max_active=c2.max_active,
+                             max_words=max_words, finalize=fin)
+                assert w.tolist() == r.words.tolist() and c == np.float32(r.cost) and f == r.flags, (t0, fin)
+            if t0 % (3 * chunk) == 0:            # a buffer of another size: no marks, full walk, same words
+                w, c, f = dec.get_partial(1, finalize=False, cap=max_words + 3) if max_words == 5 else (None, None, None)
+                if w is not None:
+                    r = o.decode(c2.loglikes[b], length=t0 + n, beam=c2.beam, max_active=c2.max_active,
+                                 max_words=max_words + 3, finalize=False)
+                    assert w.tolist() == r.words.tolist() and f == r.flags
+        dec.close()
