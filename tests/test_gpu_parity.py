@@ -443,8 +443,13 @@ def test_a_channel_that_lives_for_66000_frames(torch_cuda, c1):
                   record_digests=True, lattice_bytes_per_channel=8 * 400 * (reps * T + 1))
     chunk = torch.from_numpy(c1.loglikes).cuda()
     dec.init_channel(0, 8.0, 300)
-    for _ in range(reps):
+    o = Oracle(c1.graph)
+    for k in range(reps):
         dec.advance_chunk([0], chunk, [T])
+        if k in (4, 5, 329, 330):                 # partial results on the way (the traceback is incremental)
+            w, c, f = dec.get_partial(0, finalize=False)
+            r = o.decode(ll_host[:(k + 1) * T], beam=8.0, max_active=300, max_words=64, finalize=False)
+            assert w.tolist() == r.words.tolist() and c == np.float32(r.cost) and f == r.flags, k
     cnt, dig = dec.debug_frame_digests(0)
     assert len(cnt) == reps * T + 1
     bad = np.nonzero((cnt != ref.digest_count) | (dig != ref.digest_sum))[0]
