@@ -127,6 +127,8 @@ def tlg_shaped_graph(seed: int, num_states: int, target_arcs: int, num_classes: 
 
     def total(xm):
         return int(np.minimum(k_max, np.floor(xm * tail)).sum())
+    if S * int(k_max) < want:
+        raise ValueError(f"target_arcs {target_arcs} cannot be reached with {S} states of at most 1 + {k_max} arcs")
     lo, hi = 0.0, 1.0
     while total(hi) < want:
         hi *= 2.0
