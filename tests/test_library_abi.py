@@ -87,3 +87,15 @@ def test_bad_graphs_are_rejected_before_touching_the_gpu(lib):
     assert rc == -2 and "epsilon arcs" in msg
     rc, msg = _create(lib, [(0, 1, 1, 0, 0.5)], 2, 1, loglike_dtype=7)
     assert rc == -1 and "loglike_dtype" in msg
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own."""
+    import subprocess
+    src = tmp_path / "h.c"
+    src.write_text('#include "wfst_decoder.h"\nint main(void) { wfst_opts o; wfst_lattice_link l; (void)o; (void)l;'
+                   ' return sizeof(wfst_lattice_link) == 32 ? 0 : 1; }\n')
+    exe = tmp_path / "h"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
+                           "-I" + os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    assert subprocess.call([str(exe)]) == 0
