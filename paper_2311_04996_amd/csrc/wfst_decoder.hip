@@ -93,6 +93,9 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 #endif
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
+#ifndef WFST_SEL_EVERY
+#define WFST_SEL_EVERY 4                      // the selection histogram reads one run of 64 candidates out of this many
+#endif
 #ifndef WFST_UM
 #define WFST_UM 2
 #endif
@@ -864,26 +867,27 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   const int n_cand = total_candidates(x);
   const unsigned ma = (unsigned)x.s.max_active;
 
-  // ---- 1. select, from a sample: half of the candidates
+  // ---- 1. select, from a sample of the candidates
   int n_sampled = 0;
   for (int r = 0; r < kRegions; ++r) {
     const int n = uni(min(sm.n_reg[r], x.c.region_cap));
     const int4 *cr = x.cand + r * x.c.region_cap;
     constexpr int kHalf = 2;
-    // every other run of 64 records (a wave reads one run): candidates arrive roughly in the
+    // one run of 64 records in kEvery (a wave reads one run): candidates arrive roughly in the
     // order of the token queue, which is not free of cost trends, so the sample is interleaved finely
-    const int mine = (tid >> 6) * 128 + (tid & 63);
-    for (int i0 = 0; i0 < n; i0 += 2 * kBlock * kHalf) {
+    constexpr int kEvery = WFST_SEL_EVERY;          // one run of 64 records out of kEvery
+    const int mine = (tid >> 6) * (64 * kEvery) + (tid & 63);
+    for (int i0 = 0; i0 < n; i0 += kEvery * kBlock * kHalf) {
       int cb[kHalf];
 #pragma unroll
-      for (int u = 0; u < kHalf; ++u) { const int i = i0 + u * 2 * kBlock + mine; cb[u] = i < n ? cr[i].y : 0; }
+      for (int u = 0; u < kHalf; ++u) { const int i = i0 + u * kEvery * kBlock + mine; cb[u] = i < n ? cr[i].y : 0; }
 #pragma unroll
       for (int u = 0; u < kHalf; ++u) {
         const float c = __int_as_float(cb[u]);
-        if (i0 + u * 2 * kBlock + mine < n && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+        if (i0 + u * kEvery * kBlock + mine < n && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
       }
-      const int span = min(n - i0, 2 * kBlock * kHalf);
-      n_sampled += (span >> 7) * 64 + min(span & 127, 64);
+      const int span = min(n - i0, kEvery * kBlock * kHalf);
+      n_sampled += span / (64 * kEvery) * 64 + min(span % (64 * kEvery), 64);
     }
   }
   __syncthreads();
