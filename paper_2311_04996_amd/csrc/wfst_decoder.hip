@@ -97,7 +97,7 @@ constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave
 #define WFST_SEL_EVERY 4                      // the selection histogram reads one run of 64 candidates out of this many
 #endif
 #ifndef WFST_UM
-#define WFST_UM 2
+#define WFST_UM 1
 #endif
 constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
 #ifndef WFST_REGION_BITS
