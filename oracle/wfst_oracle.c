@@ -342,6 +342,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
   int64_t dump_used = 0;
   cutoff_t k; k.beam = o->beam; k.scale = 256.0f / o->beam;
   double offset_sum = 0.0;                      /* R11 */
+  float *cost_buf = NULL; int32_t cost_cap = 0;
   /* boost table as a dense array over output labels (absent words add exactly 0) */
   float *boost = NULL;
   if (o->boost_n > 0) {
@@ -402,19 +403,16 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       }
     }
     res->counters[7] += nxt.n;
-    /* ---- Prune: beam from the best cost, max-active through the histogram (R4, R5) */
-    float best = INFINITY;
-    for (int32_t i = 0; i < nxt.n; ++i) if (nxt.t[i].cost < best) best = nxt.t[i].cost;
-    k.best = best; k.k_keep = 256;
-    int32_t hist[256]; memset(hist, 0, sizeof(hist));
-    int32_t n_in = 0;
-    for (int32_t i = 0; i < nxt.n; ++i)
-      if ((nxt.t[i].cost - best) <= k.beam) { hist[bin_of(nxt.t[i].cost, &k)]++; ++n_in; }
+    /* ---- Prune: beam from the best cost, max-active through the histogram (R4, R5): the
+     * one cutoff routine, applied to the costs of the recombined set */
+    if (nxt.n > cost_cap) { cost_cap = nxt.n * 2; cost_buf = (float *)realloc(cost_buf, sizeof(float) * cost_cap); }
+    for (int32_t i = 0; i < nxt.n; ++i) cost_buf[i] = nxt.t[i].cost;
+    float best; int32_t k_keep, hist[256];
+    int32_t n_in = oracle_cutoff(cost_buf, nxt.n, o->beam, o->max_active, &best, &k_keep, hist);
+    k.best = best; k.k_keep = k_keep;
     if (n_in > o->max_active) {
-      int64_t run = 0; int32_t ks = 256;
-      for (int32_t j = 0; j < 256; ++j) { run += hist[j]; if (run > o->max_active) { ks = j; break; } }
-      if (ks < 1) { ks = 1; res->counters[6]++; }
-      k.k_keep = ks; res->counters[5]++;
+      res->counters[5]++;
+      if (hist[0] > o->max_active) res->counters[6]++;
     }
     int32_t m = 0;
     for (int32_t i = 0; i < nxt.n; ++i) {
@@ -482,7 +480,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
   }
 done:
   for (int32_t t = 0; t <= len; ++t) free(lat[t]);
-  free(lat); free(lat_n); free(cur.t); free(nxt.t); free(map); free(boost);
+  free(lat); free(lat_n); free(cur.t); free(nxt.t); free(map); free(boost); free(cost_buf);
   return rc;
 }
 
