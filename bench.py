@@ -131,8 +131,7 @@ def main_streaming(args):
                   outputs_on_host=True)
     chans = np.arange(n, dtype=np.int32)
     nfr = np.full(n, C, np.int32)
-    for ch in range(n):
-        dec.init_channel(ch, float(c["beam"]), int(c["max_active"]))
+    dec.init_channels(chans, float(c["beam"]), int(c["max_active"]))
     torch.cuda.synchronize()
     print(f"[bench] streaming: {n} channels x {n_chunks}+{warm} chunks of {C} frames, "
           f"{dec.device_bytes() / 2**30:.1f} GiB on device", file=sys.stderr, flush=True)

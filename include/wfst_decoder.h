@@ -161,12 +161,15 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *dec, const float *loglikes, cons
  * no gather/scatter is needed between chunks).
  *   wfst_init_channel : reset channel `ch` to the start token closed over epsilon arcs, and
  *                       fix its beam / max_active and its word-boost table (NULL = none).
+ *   wfst_init_channels: the same for n channels (HOST int32 channels[n], distinct) in one launch,
+ *                       for a burst of new streams; boosts is NULL or a HOST array of n table
+ *                       pointers (NULL entries = no table).
  *   wfst_advance_chunk: feed n channels (HOST int32 channels[n], distinct) nframes[i] <= C
  *                       frames each from DEVICE loglikes [n][C][V]; nframes is HOST.
  *   wfst_get_partial  : best hypothesis of channel `ch` so far.  finalize = 0 ignores final
  *                       costs (partial result), 1 applies them.  words [cap], nwords [1],
  *                       cost [1], flags [1] follow opts.outputs_on_host.
- *   wfst_get_partial_batch: the same for n channels (HOST int32 channels[n]) in one launch;
+ *   wfst_get_partial_batch: the same for n channels (HOST int32 channels[n], distinct) in one launch;
  *                       words [n][max_words], nwords [n], cost [n], flags [n].
  * The traceback behind a (partial) result is incremental: the library remembers the path of the
  * channel's previous traceback and stops where the new one meets it, so a result after every
@@ -175,6 +178,8 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *dec, const float *loglikes, cons
  */
 int32_t wfst_init_channel(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
                           const wfst_boost_table *boost, void *stream);
+int32_t wfst_init_channels(wfst_decoder *dec, const int32_t *channels, int32_t n, float beam,
+                           int32_t max_active, const wfst_boost_table *const *boosts, void *stream);
 int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n,
                            const float *loglikes, const int32_t *nframes, int32_t C, int32_t V,
                            void *stream);

@@ -20,7 +20,7 @@ FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPAC
 LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
-           "wfst_init_channel",
+           "wfst_init_channel", "wfst_init_channels",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
            "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
@@ -85,13 +85,14 @@ def load_library():
     # PyTorch ships its own HIP runtime; import it first so that this library binds to the
     # same libamdhip64 instance (two runtimes in one process do not share the device).
     import torch  # noqa: F401
-    lib = C.CDLL(os.environ.get("WFST_DECODER_LIB", LIB_PATH))   # override: tuning builds only
+    lib = C.CDLL(LIB_PATH)
     p, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     lib.wfst_decoder_create.argtypes = [C.POINTER(wfst_graph_csr), C.POINTER(wfst_opts), C.POINTER(p)]
     lib.wfst_decoder_destroy.argtypes = [p]
     lib.wfst_decode_batch.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p]
     lib.wfst_decode_batch_boosted.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p, p]
     lib.wfst_init_channel.argtypes = [p, i32, f32, i32, p, p]
+    lib.wfst_init_channels.argtypes = [p, p, i32, f32, i32, p, p]
     lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
     lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
     lib.wfst_get_partial_batch.argtypes = [p, p, i32, i32, p, p, p, p, p]
@@ -215,6 +216,19 @@ class Decoder:
         else:
             t, keep = _boost_struct(boost)
             self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, C.byref(t), _stream_ptr(stream)))
+
+    def init_channels(self, channels, beam, max_active, stream=None, boosts=None):
+        """wfst_init_channels: reset several channels in one launch; boosts: None or one entry
+        per channel, each None or a (word_ids, scores) table."""
+        channels = np.ascontiguousarray(channels, dtype=np.int32)
+        n = len(channels)
+        arr = None
+        if boosts is not None:
+            assert len(boosts) == n
+            keep = [None if t is None else _boost_struct(t) for t in boosts]
+            arr = (C.c_void_p * n)(*[None if k is None else C.addressof(k[0]) for k in keep])
+        self._check(self.lib.wfst_init_channels(self.h, channels.ctypes.data, n, beam, max_active, arr,
+                                                _stream_ptr(stream)))
 
     def advance_chunk(self, channels, loglikes, nframes, stream=None):
         """loglikes: CUDA float32 [n, C, V]; channels, nframes: host int32 [n]."""

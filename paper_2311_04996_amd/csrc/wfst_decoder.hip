@@ -671,8 +671,12 @@ __device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc
   for (;;) {
     const unsigned cc = (unsigned)(cur >> 32);
     bool better = oc < cc;
-    if (oc == cc && cur != kValEmpty)
-      better = (unsigned)arc < (unsigned)x.cand[(unsigned)cur].w;     // exact tie: lower arc id
+    if (oc == cc && cur != kValEmpty) {
+      // exact tie: lower arc id.  The other record may have been written by another wave just
+      // before it published the index (fused closure rounds): acquire pairs with its release
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      better = (unsigned)arc < (unsigned)x.cand[(unsigned)cur].w;
+    }
     if (!better) break;
     const unsigned long long prev = atomicCAS(&t.vals[s], cur, mine);
     if (prev == cur) break;
@@ -1114,10 +1118,13 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
           wave_alloc_n<kU>(&sm.n_reg[0], ok, ci);
 #pragma unroll
           for (int u = 0; u < kU; ++u)
-            if (ok[u]) {
-              x.cand[ci[u]] = make_int4(next[u], __float_as_int(nc[u]), src[u], arc[u]);
-              sm.occ[ci[u]] = (unsigned short)table_insert(x, key_of(next[u]), nc[u], arc[u], ci[u]);
-            }
+            if (ok[u]) x.cand[ci[u]] = make_int4(next[u], __float_as_int(nc[u]), src[u], arc[u]);
+          // the records must be visible to the other waves before their indices are published in
+          // the table: an exact cost tie makes the other wave read this record's arc id
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+#pragma unroll
+          for (int u = 0; u < kU; ++u)
+            if (ok[u]) sm.occ[ci[u]] = (unsigned short)table_insert(x, key_of(next[u]), nc[u], arc[u], ci[u]);
         } else {
           push_cands<kU>(x, ok, next, nc, src, arc);
         }
@@ -1799,6 +1806,7 @@ struct wfst_decoder {
   std::vector<hipEvent_t> boost_ev;  // per channel: recorded after the copies out of its staging area
   std::vector<unsigned> blk_of_state;  // [S + 1] block number of every state (and the block count)
   std::vector<int> state_of_blk;       // inverse, built when a debug call first needs it
+  std::vector<unsigned> h_off;         // wfst_get_lattice: the channel's frame offsets on the host
   hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
   std::string err;
 };
@@ -2040,6 +2048,63 @@ int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st
   return WFST_OK;
 }
 
+
+// wfst_get_lattice: `ctr` (2 words) and `set_links` (frames + 2 words) are DEVICE scratch,
+// `off` is HOST scratch for frames + 2 offsets; frames_cap is what those hold.
+int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float lattice_beam,
+                     int32_t *tok_state, float *tok_cost, int64_t tok_cap, int64_t *frame_off,
+                     wfst_lattice_link *links, int64_t link_cap, int64_t *n_tokens, int64_t *n_links,
+                     hipStream_t st, unsigned long long *ctr_dev, unsigned long long *set_links_dev,
+                     unsigned *off, int frames_cap) {
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  if (!frame_off || !n_tokens || !n_links || tok_cap < 0 || link_cap < 0 || (tok_cap && (!tok_state || !tok_cost)) ||
+      (link_cap && !links))
+    return fail(d, WFST_ERR_INVALID_ARG, "null output or negative capacity");
+  if (!(lattice_beam >= 0.0f)) return fail(d, WFST_ERR_INVALID_ARG, "lattice_beam must be >= 0");
+  ChanState s;
+  HIP_TRY(d, hipMemcpyAsync(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  if (s.status & (kStLattice | kStCapacity))
+    return fail(d, WFST_ERR_CAPACITY, "the channel stopped on an overflow: its token sets are incomplete");
+  const int f = s.frame;
+  if (f < 0 || f > frames_cap)
+    return fail(d, WFST_ERR_CAPACITY, "the channel has " + std::to_string(f) + " frames; this call takes at most " +
+                                          std::to_string(frames_cap));
+  if (f > 0 && !loglikes) return fail(d, WFST_ERR_INVALID_ARG, "null loglikes");
+  HIP_TRY(d, hipMemcpyAsync(off, d->c.frame_off + (size_t)ch * (d->c.max_frames + 2), ((size_t)f + 2) * sizeof(unsigned),
+                            hipMemcpyDeviceToHost, st));
+  // the counters must start at zero; the per-set counts are all written by the first run
+  HIP_TRY(d, hipMemsetAsync(ctr_dev, 0, 2 * sizeof(unsigned long long), st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  for (int t = 0; t <= f + 1; ++t) frame_off[t] = (int64_t)off[t];
+  *n_tokens = (int64_t)off[(size_t)f + 1];
+  LatticeArgs a{};
+  a.ch = ch; a.frames = f; a.ll = loglikes; a.V = d->V; a.ll_dtype = d->opts.loglike_dtype;
+  a.lattice_beam = lattice_beam;
+  a.tok_state = tok_state; a.tok_cost = tok_cost; a.tok_cap = tok_cap;
+  a.links = links; a.link_cap = link_cap; a.ctr = ctr_dev; a.set_links = set_links_dev;
+  a.write = 0;                                  // first run: links per set
+  hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
+  HIP_TRY(d, hipGetLastError());
+  hipLaunchKernelGGL(wfst_lattice_scan, dim3(1), dim3(kBlock), 0, st, set_links_dev, f + 1, ctr_dev);
+  HIP_TRY(d, hipGetLastError());
+  unsigned long long ctr[2] = {0, 0};
+  HIP_TRY(d, hipMemcpyAsync(ctr, ctr_dev, sizeof(ctr), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  *n_links = (int64_t)ctr[0];
+  if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
+  if (*n_tokens <= tok_cap && *n_links <= link_cap && *n_links > 0) {
+    a.write = 1;                                // second run: every set writes its links at its place
+    hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
+    HIP_TRY(d, hipGetLastError());
+    HIP_TRY(d, hipStreamSynchronize(st));
+  }
+  if (*n_tokens > tok_cap || *n_links > link_cap)
+    return fail(d, WFST_ERR_CAPACITY, "lattice needs room for " + std::to_string(*n_tokens) + " tokens and " +
+                                          std::to_string(*n_links) + " links");
+  return WFST_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -2153,6 +2218,31 @@ int32_t wfst_init_channel(wfst_decoder *d, int32_t ch, float beam, int32_t max_a
   return launch(d, {ch}, {0}, {0}, a, static_cast<hipStream_t>(stream));
 }
 
+int32_t wfst_init_channels(wfst_decoder *d, const int32_t *channels, int32_t n, float beam, int32_t max_active,
+                           const wfst_boost_table *const *boosts, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (n < 0 || (n > 0 && !channels)) return fail(d, WFST_ERR_INVALID_ARG, "null or negative argument");
+  if (n == 0) return WFST_OK;
+  if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
+  if (n > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "more channels than max_channels");
+  std::vector<char> seen(d->opts.max_channels, 0);
+  std::vector<int> chan(n), zero(n, 0);
+  for (int i = 0; i < n; ++i) {
+    if (channels[i] < 0 || channels[i] >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+    if (seen[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel listed twice");
+    seen[channels[i]] = 1;
+    chan[i] = channels[i];
+  }
+  for (int i = 0; i < n; ++i) {
+    const int rcb = set_boost(d, chan[i], boosts ? boosts[i] : nullptr, static_cast<hipStream_t>(stream));
+    if (rcb) return rcb;
+  }
+  LaunchArgs a{};
+  a.V = d->V; a.mode = kModeInit;
+  a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
+  return launch(d, chan, zero, zero, a, static_cast<hipStream_t>(stream));   // one workgroup per channel, one launch
+}
+
 int32_t wfst_advance_chunk(wfst_decoder *d, const int32_t *channels, int32_t n, const float *loglikes,
                            const int32_t *nframes, int32_t C, int32_t V, void *stream) {
   if (!d) return WFST_ERR_INVALID_ARG;
@@ -2207,8 +2297,12 @@ int32_t wfst_get_partial_batch(wfst_decoder *d, const int32_t *channels, int32_t
   if (!channels || !words || !nwords || !cost || !flags) return fail(d, WFST_ERR_INVALID_ARG, "null argument");
   if (n > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "more channels than max_channels");
   std::vector<int> chan(n), nfr(n, 0), io(n);
+  std::vector<char> seen(d->opts.max_channels, 0);
   for (int i = 0; i < n; ++i) {
     if (channels[i] < 0 || channels[i] >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+    // two workgroups on one channel would both rewrite the marks of its traced path
+    if (seen[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel listed twice");
+    seen[channels[i]] = 1;
     chan[i] = channels[i]; io[i] = i;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -2253,52 +2347,12 @@ int32_t wfst_get_lattice(wfst_decoder *d, int32_t ch, const void *loglikes, floa
                          wfst_lattice_link *links, int64_t link_cap,
                          int64_t *n_tokens, int64_t *n_links, void *stream) {
   if (!d) return WFST_ERR_INVALID_ARG;
-  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
   if (!d->c.tokrec) return fail(d, WFST_ERR_INVALID_ARG, "the decoder was created without keep_token_records");
-  if (!frame_off || !n_tokens || !n_links || tok_cap < 0 || link_cap < 0 || (tok_cap && (!tok_state || !tok_cost)) ||
-      (link_cap && !links))
-    return fail(d, WFST_ERR_INVALID_ARG, "null output or negative capacity");
-  if (!(lattice_beam >= 0.0f)) return fail(d, WFST_ERR_INVALID_ARG, "lattice_beam must be >= 0");
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  ChanState s;
-  HIP_TRY(d, hipMemcpyAsync(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost, st));
-  HIP_TRY(d, hipStreamSynchronize(st));
-  if (s.status & (kStLattice | kStCapacity))
-    return fail(d, WFST_ERR_CAPACITY, "the channel stopped on an overflow: its token sets are incomplete");
-  const int f = s.frame;
-  if (f > 0 && !loglikes) return fail(d, WFST_ERR_INVALID_ARG, "null loglikes");
-  std::vector<unsigned> off((size_t)f + 2);
-  HIP_TRY(d, hipMemcpyAsync(off.data(), d->c.frame_off + (size_t)ch * (d->c.max_frames + 2), off.size() * sizeof(unsigned),
-                            hipMemcpyDeviceToHost, st));
-  HIP_TRY(d, hipMemsetAsync(d->d_lat_ctr, 0, 2 * sizeof(unsigned long long), st));
-  HIP_TRY(d, hipStreamSynchronize(st));
-  for (int t = 0; t <= f + 1; ++t) frame_off[t] = (int64_t)off[t];
-  *n_tokens = (int64_t)off[(size_t)f + 1];
-  LatticeArgs a{};
-  a.ch = ch; a.frames = f; a.ll = loglikes; a.V = d->V; a.ll_dtype = d->opts.loglike_dtype;
-  a.lattice_beam = lattice_beam;
-  a.tok_state = tok_state; a.tok_cost = tok_cost; a.tok_cap = tok_cap;
-  a.links = links; a.link_cap = link_cap; a.ctr = d->d_lat_ctr; a.set_links = d->d_set_links;
-  a.write = 0;                                  // first run: links per set
-  hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
-  HIP_TRY(d, hipGetLastError());
-  hipLaunchKernelGGL(wfst_lattice_scan, dim3(1), dim3(kBlock), 0, st, d->d_set_links, f + 1, d->d_lat_ctr);
-  HIP_TRY(d, hipGetLastError());
-  unsigned long long ctr[2] = {0, 0};
-  HIP_TRY(d, hipMemcpyAsync(ctr, d->d_lat_ctr, sizeof(ctr), hipMemcpyDeviceToHost, st));
-  HIP_TRY(d, hipStreamSynchronize(st));
-  *n_links = (int64_t)ctr[0];
-  if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
-  if (*n_tokens <= tok_cap && *n_links <= link_cap && *n_links > 0) {
-    a.write = 1;                                // second run: every set writes its links at its place
-    hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
-    HIP_TRY(d, hipGetLastError());
-    HIP_TRY(d, hipStreamSynchronize(st));
-  }
-  if (*n_tokens > tok_cap || *n_links > link_cap)
-    return fail(d, WFST_ERR_CAPACITY, "lattice needs room for " + std::to_string(*n_tokens) + " tokens and " +
-                                          std::to_string(*n_links) + " links");
-  return WFST_OK;
+  // the kernels' scratch (counters, links per token set) is what the decoder allocated at create
+  d->h_off.resize((size_t)d->c.max_frames + 2);
+  return get_lattice_impl(d, ch, loglikes, lattice_beam, tok_state, tok_cost, tok_cap, frame_off, links, link_cap,
+                          n_tokens, n_links, static_cast<hipStream_t>(stream), d->d_lat_ctr, d->d_set_links,
+                          d->h_off.data(), d->c.max_frames);
 }
 
 int32_t wfst_debug_get_tokens(wfst_decoder *d, int32_t ch, int32_t *states, float *costs, int32_t cap, int32_t *n) {

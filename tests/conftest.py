@@ -22,3 +22,10 @@ def c1():
 def c2():
     from workloads import make_config
     return make_config("c2_medium")
+
+
+@pytest.fixture(scope="session")
+def c3_graph():
+    """The 10 M-state graph of configurations 3 and 4 (about 20 s to generate, 0.6 GB)."""
+    from workloads.configs import make_graph
+    return make_graph("c3_large")
