@@ -227,6 +227,21 @@ int32_t wfst_get_lattice(wfst_decoder *dec, int32_t ch, const void *loglikes, fl
                          int64_t *n_tokens, int64_t *n_links, void *stream);
 
 /*
+ * wfst_get_lattice for callers that must not allocate (code between graph captures, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same results, but the call allocates
+ * nothing, neither device nor host memory.  The kernels' scratch (two counters and the number of
+ * links of every token set) lives in a static device array of 32 KB inside the library instead of
+ * in memory the decoder allocated; every GPU the library runs on holds its own copy until the
+ * process ends.  Limits: the channel may have consumed at most 4094 frames (else WFST_ERR_CAPACITY).
+ * All decoders and calls on one GPU share that array: calls of this entry point that overlap in
+ * time on one GPU race with each other (calls of wfst_get_lattice do not use it).
+ */
+int32_t wfst_get_lattice_noalloc(wfst_decoder *dec, int32_t ch, const void *loglikes, float lattice_beam,
+                                 int32_t *tok_state, float *tok_cost, int64_t tok_cap, int64_t *frame_off,
+                                 wfst_lattice_link *links, int64_t link_cap,
+                                 int64_t *n_tokens, int64_t *n_links, void *stream);
+
+/*
  * Test and measurement hooks.  All outputs are HOST memory; each call synchronises the
  * device first.
  *   wfst_debug_frame_digests: needs opts.record_digests.  For the closed token sets A_0..A_f

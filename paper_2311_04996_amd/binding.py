@@ -22,6 +22,7 @@ LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
            "wfst_init_channel", "wfst_init_channels",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
+           "wfst_get_lattice_noalloc",
            "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
@@ -107,6 +108,7 @@ def load_library():
     lib.wfst_last_error.argtypes = [p]
     lib.wfst_last_error.restype = C.c_char_p
     lib.wfst_get_lattice.argtypes = [p, i32, p, f32, p, p, i64, p, p, i64, p, p, p]
+    lib.wfst_get_lattice_noalloc.argtypes = lib.wfst_get_lattice.argtypes
     for name in EXPORTS:
         if name not in ("wfst_device_bytes", "wfst_last_kernel_ms", "wfst_last_error"):
             getattr(lib, name).restype = i32
@@ -285,6 +287,17 @@ class Decoder:
                                                     ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3]),
                                                     _stream_ptr(stream)))
         return out
+
+    def get_lattice_noalloc(self, ch, loglikes, lattice_beam, tok_state, tok_cost, links, frame_off, stream=None):
+        """wfst_get_lattice_noalloc: every buffer is the caller's (tok_state int32 / tok_cost float32
+        CUDA tensors, links a CUDA uint8 tensor of 32-byte records, frame_off a host int64 array).
+        Returns (n_tokens, n_links); raises on any status but OK."""
+        nt, nl = C.c_int64(), C.c_int64()
+        self._check(self.lib.wfst_get_lattice_noalloc(
+            self.h, ch, loglikes.data_ptr(), float(lattice_beam), tok_state.data_ptr(), tok_cost.data_ptr(),
+            tok_state.numel(), frame_off.ctypes.data, links.data_ptr(), links.numel() // LINK_DTYPE.itemsize,
+            C.byref(nt), C.byref(nl), _stream_ptr(stream)))
+        return nt.value, nl.value
 
     def get_lattice(self, ch, loglikes, lattice_beam, stream=None, tok_cap=None, link_cap=None, on_device=False):
         """wfst_get_lattice for channel `ch`; `loglikes` [frames, V] is the utterance's device

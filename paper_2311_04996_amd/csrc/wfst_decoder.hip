@@ -58,6 +58,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <numeric>
 #include <string>
 #include <vector>
@@ -127,6 +128,10 @@ constexpr unsigned kPackE = 0xFFFFFu;          // header word 3: emitting degree
 constexpr int kPackXShift = 20;                //                epsilon degree (12 bits)
 constexpr int kMaxEpsDeg = 4094;
 constexpr int kStLattice = WFST_FLAG_LATTICE_OVERFLOW, kStCapacity = WFST_FLAG_CAPACITY;
+constexpr int kScratchFrames = 4094;             // most frames a channel may have for wfst_get_lattice_noalloc
+constexpr int kHostHead = 24;                    // host staging of the lattice calls: words before the frame offsets
+constexpr int kScratchWords = 2 + kScratchFrames + 2;
+constexpr int kScratchDevices = 64;
 
 struct ChanState {            // persists between calls (the per-stream decoder state)
   double offset;              // cost offsets: sum of the best costs the token costs were rebased by
@@ -1806,7 +1811,8 @@ struct wfst_decoder {
   std::vector<hipEvent_t> boost_ev;  // per channel: recorded after the copies out of its staging area
   std::vector<unsigned> blk_of_state;  // [S + 1] block number of every state (and the block count)
   std::vector<int> state_of_blk;       // inverse, built when a debug call first needs it
-  std::vector<unsigned> h_off;         // wfst_get_lattice: the channel's frame offsets on the host
+  std::vector<unsigned> h_off;         // wfst_get_lattice: channel state, counters and frame offsets on the host
+  unsigned *h_pinned = nullptr;        // the same for wfst_get_lattice_noalloc: pinned, allocated at create
   hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
   std::string err;
 };
@@ -1975,6 +1981,8 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
   if ((rc = dev_alloc(d, &d->d_lat_ctr, (size_t)2))) return rc;
   if (o.keep_token_records && (rc = dev_alloc(d, &d->d_set_links, (size_t)c.max_frames + 2))) return rc;
+  if (o.keep_token_records)
+    HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_pinned), (kHostHead + kScratchFrames + 2) * sizeof(unsigned)));
   if (o.outputs_on_host) {
     if ((rc = dev_alloc(d, &d->o_words, N * (size_t)o.max_words))) return rc;
     if ((rc = dev_alloc(d, &d->o_nwords, N))) return rc;
@@ -2049,19 +2057,50 @@ int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st
 }
 
 
-// wfst_get_lattice: `ctr` (2 words) and `set_links` (frames + 2 words) are DEVICE scratch,
+// ---- scratch of the entry point that allocates nothing
+// Device memory for the lattice kernels' counters and per-set link counts that belongs to the
+// loaded code object instead of to an allocation: every GPU the library runs on holds its own
+// copy for the life of the process.  In host code the array's NAME is only a handle; the address
+// each device holds is asked for once per device (scratch_address) and kept.
+}  // namespace
+static __device__ __align__(256) unsigned long long scratch[kScratchWords];
+namespace {
+std::mutex g_scratch_mu;
+unsigned long long *g_scratch_ptr[kScratchDevices] = {};
+
+// Address of `scratch` on the current device (asked for once per device, with that device current).
+int scratch_address(wfst_decoder *d, unsigned long long **out) {
+  int dev = -1;
+  HIP_TRY(d, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kScratchDevices) return fail(d, WFST_ERR_HIP, "device ordinal beyond the scratch table");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(d, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(d, WFST_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = static_cast<unsigned long long *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return WFST_OK;
+}
+
+// Both lattice entry points: `ctr` (2 words) and `set_links` (frames + 2 words) are DEVICE scratch,
 // `off` is HOST scratch for frames + 2 offsets; frames_cap is what those hold.
 int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float lattice_beam,
                      int32_t *tok_state, float *tok_cost, int64_t tok_cap, int64_t *frame_off,
                      wfst_lattice_link *links, int64_t link_cap, int64_t *n_tokens, int64_t *n_links,
                      hipStream_t st, unsigned long long *ctr_dev, unsigned long long *set_links_dev,
-                     unsigned *off, int frames_cap) {
+                     unsigned *host, int frames_cap) {
+  // `host`: kHostHead words for the channel state and the two counters, then frames_cap + 2 offsets
+  static_assert(sizeof(ChanState) + 2 * sizeof(unsigned long long) <= kHostHead * sizeof(unsigned), "head too small");
+  ChanState &s = *reinterpret_cast<ChanState *>(host);
+  unsigned long long *ctr = reinterpret_cast<unsigned long long *>(host + kHostHead - 4);
+  unsigned *off = host + kHostHead;
   if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
   if (!frame_off || !n_tokens || !n_links || tok_cap < 0 || link_cap < 0 || (tok_cap && (!tok_state || !tok_cost)) ||
       (link_cap && !links))
     return fail(d, WFST_ERR_INVALID_ARG, "null output or negative capacity");
   if (!(lattice_beam >= 0.0f)) return fail(d, WFST_ERR_INVALID_ARG, "lattice_beam must be >= 0");
-  ChanState s;
   HIP_TRY(d, hipMemcpyAsync(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost, st));
   HIP_TRY(d, hipStreamSynchronize(st));
   if (s.status & (kStLattice | kStCapacity))
@@ -2088,8 +2127,8 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
   HIP_TRY(d, hipGetLastError());
   hipLaunchKernelGGL(wfst_lattice_scan, dim3(1), dim3(kBlock), 0, st, set_links_dev, f + 1, ctr_dev);
   HIP_TRY(d, hipGetLastError());
-  unsigned long long ctr[2] = {0, 0};
-  HIP_TRY(d, hipMemcpyAsync(ctr, ctr_dev, sizeof(ctr), hipMemcpyDeviceToHost, st));
+  ctr[0] = ctr[1] = 0;
+  HIP_TRY(d, hipMemcpyAsync(ctr, ctr_dev, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
   HIP_TRY(d, hipStreamSynchronize(st));
   *n_links = (int64_t)ctr[0];
   if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
@@ -2131,6 +2170,11 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
     d->err = "hipEventCreate failed"; rc = WFST_ERR_HIP;
   }
   if (rc) { g_create_err = d->err; wfst_decoder_destroy(d); return rc; }
+  {
+    // learn this device's address of the static scratch now rather than in the first call that needs it
+    unsigned long long *p = nullptr;
+    if (scratch_address(d, &p) != WFST_OK) { d->err.clear(); (void)hipGetLastError(); }
+  }
   *out = d;
   return WFST_OK;
 }
@@ -2140,6 +2184,7 @@ int32_t wfst_decoder_destroy(wfst_decoder *d) {
   (void)hipDeviceSynchronize();
   for (void *p : d->allocs) (void)hipFree(p);
   if (d->h_boost) (void)hipHostFree(d->h_boost);
+  if (d->h_pinned) (void)hipHostFree(d->h_pinned);
   if (d->ev0) (void)hipEventDestroy(d->ev0);
   if (d->ev1) (void)hipEventDestroy(d->ev1);
   for (hipEvent_t e : d->boost_ev) if (e) (void)hipEventDestroy(e);
@@ -2349,10 +2394,27 @@ int32_t wfst_get_lattice(wfst_decoder *d, int32_t ch, const void *loglikes, floa
   if (!d) return WFST_ERR_INVALID_ARG;
   if (!d->c.tokrec) return fail(d, WFST_ERR_INVALID_ARG, "the decoder was created without keep_token_records");
   // the kernels' scratch (counters, links per token set) is what the decoder allocated at create
-  d->h_off.resize((size_t)d->c.max_frames + 2);
+  d->h_off.resize((size_t)d->c.max_frames + 2 + kHostHead);
   return get_lattice_impl(d, ch, loglikes, lattice_beam, tok_state, tok_cost, tok_cap, frame_off, links, link_cap,
                           n_tokens, n_links, static_cast<hipStream_t>(stream), d->d_lat_ctr, d->d_set_links,
                           d->h_off.data(), d->c.max_frames);
+}
+
+int32_t wfst_get_lattice_noalloc(wfst_decoder *d, int32_t ch, const void *loglikes, float lattice_beam,
+                                 int32_t *tok_state, float *tok_cost, int64_t tok_cap, int64_t *frame_off,
+                                 wfst_lattice_link *links, int64_t link_cap,
+                                 int64_t *n_tokens, int64_t *n_links, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (!d->c.tokrec) return fail(d, WFST_ERR_INVALID_ARG, "the decoder was created without keep_token_records");
+  unsigned long long *ptr = nullptr;
+  const int rc = scratch_address(d, &ptr);      // this device's copy of the static array
+  if (rc) return rc;
+  // words 0, 1 of the scratch: links found / error bits; from word 2 on: links per token set.
+  // The host side of the small copies is pinned memory the decoder got at create, so the runtime
+  // needs no staging buffer of its own either.
+  return get_lattice_impl(d, ch, loglikes, lattice_beam, tok_state, tok_cost, tok_cap, frame_off, links, link_cap,
+                          n_tokens, n_links, static_cast<hipStream_t>(stream), ptr, ptr + 2, d->h_pinned,
+                          kScratchFrames);
 }
 
 int32_t wfst_debug_get_tokens(wfst_decoder *d, int32_t ch, int32_t *states, float *costs, int32_t cap, int32_t *n) {
