@@ -56,6 +56,21 @@
  *       against an fp64 trellis on a long stream.  In the lattice (R10) the cost of an emitting
  *       link into A_t is rebased like the tokens of A_t: (cost through the arc) - b_t.
  *
+ *   R12 boosting acceptor with several states (Section "Word boosting": the graph is composed on
+ *       the fly with a boosting acceptor B, TLG o B; the paper's B has one state, its figure
+ *       "Example word boosting WFSA" shows the failure arc taken when no word arc matches, and
+ *       its conclusions name phrase boosting as the extension).  B is a deterministic acceptor over
+ *       OUTPUT labels: arcs (from, label, to, score), state 0 = root.  A token is a pair (graph
+ *       state, B state); there is at most one token per pair and frame, so recombination,
+ *       the epsilon closure and the stored sets are keyed by the pair.  On an arc with output label
+ *       o != 0 taken by a token in B state b: if b has an arc on o, the token moves to its
+ *       destination and the arc's score is added after the other terms (as in R9); otherwise the
+ *       failure arc leads to the root at no cost and o is tried once more there (root arc on o:
+ *       its destination and score; none: the token stays in the root, nothing is added).  Arcs
+ *       without output label leave b unchanged.  A B with the single state 0 and self-loops is
+ *       exactly the table of R9.  Final choice ties: lower graph state, then lower B state.
+ *       Digest of a token: the pair's B state enters the mix (0 leaves the R1-R11 digest unchanged).
+ *
  * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
  * Viterbi, greedy CTC collapse on the normal CTC topology, closed-form histogram cases,
  * Dijkstra for the epsilon closure, traceback cost re-summation).  Absolute outputs are
@@ -100,6 +115,10 @@ typedef struct {
   const int32_t *boost_ids;
   const float *boost_scores;
   int32_t cost_offset;     /* R11: 1 = rebase the token costs to the best cost after every prune step */
+  /* R12: boosting acceptor with bfst_states > 0 states (then the table above must be empty) */
+  int32_t bfst_states, bfst_arcs;
+  const int32_t *bfst_from, *bfst_label, *bfst_to;
+  const float *bfst_score;
 } oracle_opts;
 
 typedef struct {
@@ -235,7 +254,10 @@ int32_t oracle_keep(float c, float best, float beam, int32_t k_keep) {
 }
 
 /* ------------------------------------------------------------------ token sets */
-typedef struct { int32_t state; float cost; int32_t prev; int32_t arc; } token_t;
+typedef struct { int32_t state; float cost; int32_t prev; int32_t arc;
+                 int32_t b;      /* state of the boosting acceptor (R12); 0 without one */
+                 int32_t link;   /* next token of the same graph state, or -1 */
+} token_t;
 typedef struct { token_t *t; int32_t n, cap; } tokvec;
 
 static void tv_push(tokvec *v, token_t x) {
@@ -243,6 +265,43 @@ static void tv_push(tokvec *v, token_t x) {
   v->t[v->n++] = x;
 }
 static float canon(float x) { return x == 0.0f ? 0.0f : x; }   /* -0.0 -> +0.0 */
+
+/* One token per (graph state, B state).  head[s] starts the chain of the tokens of graph state s
+ * (one per B state; a single token without a boosting acceptor), -1 if there is none. */
+static int32_t tok_find(const tokvec *v, const int32_t *head, int32_t s, int32_t b) {
+  for (int32_t q = head[s]; q >= 0; q = v->t[q].link) if (v->t[q].b == b) return q;
+  return -1;
+}
+static int32_t tok_add(tokvec *v, int32_t *head, int32_t s, int32_t b, float cost, int32_t prev, int32_t arc) {
+  token_t t = { s, cost, prev, arc, b, head[s] };
+  head[s] = v->n;
+  tv_push(v, t);
+  return v->n - 1;
+}
+
+/* What an output label does to a token (R9, R12). */
+typedef struct {
+  const float *table;      /* R9: dense over output labels, or NULL */
+  int32_t n_states, n_arcs;                     /* R12 */
+  const int32_t *from, *label, *to; const float *score;
+} booster;
+/* arc of B out of state b on label o, or -1 */
+static int32_t bfst_arc(const booster *B, int32_t b, int32_t o) {
+  for (int32_t i = 0; i < B->n_arcs; ++i) if (B->from[i] == b && B->label[i] == o) return i;
+  return -1;
+}
+/* Token in B state b takes an arc with output label o != 0: returns the new B state; *add says
+ * whether a score is added and *score which. */
+static int32_t boost_step(const booster *B, int32_t b, int32_t o, int *add, float *score) {
+  *add = 0; *score = 0.0f;
+  if (B->table) { *add = 1; *score = B->table[o]; return 0; }
+  if (B->n_states <= 0) return 0;
+  int32_t i = bfst_arc(B, b, o);
+  if (i < 0 && b != 0) i = bfst_arc(B, 0, o);   /* failure arc to the root, then once more */
+  if (i < 0) return 0;
+  *add = 1; *score = B->score[i];
+  return B->to[i];
+}
 
 static uint64_t mix64(uint64_t x) {
   x += 0x9E3779B97F4A7C15ull;
@@ -253,31 +312,36 @@ static uint64_t mix64(uint64_t x) {
 static uint64_t rng_next(uint64_t *s) { *s += 0x9E3779B97F4A7C15ull; return mix64(*s); }
 
 /* Epsilon closure (R6) of the token set `v` in place, under the frozen predicate `k`.
- * map[state] = index of the state's token in v, or -1.  The worklist is consumed from the
- * front (order 0), from the back (1) or at a seeded random position (2); `head` only moves
+ * head[state] = chain of the state's tokens in v (tok_find).  The worklist is consumed from the
+ * front (order 0), from the back (1) or at a seeded random position (2); `head_` only moves
  * in order 0.  The result does not depend on the order. */
-static void eps_closure(const oracle_prepared *p, tokvec *v, int32_t *map, const cutoff_t *k,
-                        int32_t order, uint64_t seed, const float *boost) {
-  int32_t *wl = NULL; int32_t wn = 0, wcap = 0, head = 0;
+static void eps_closure(const oracle_prepared *p, tokvec *v, int32_t *head, const cutoff_t *k,
+                        int32_t order, uint64_t seed, const booster *B) {
+  int32_t *wl = NULL; int32_t wn = 0, wcap = 0, head_ = 0;
   for (int32_t i = 0; i < v->n; ++i) {
     if (wn == wcap) { wcap = wcap ? wcap * 2 : 1024; wl = (int32_t *)realloc(wl, sizeof(int32_t) * wcap); }
     wl[wn++] = i;
   }
-  while (head < wn) {
+  while (head_ < wn) {
     int32_t j;
-    if (order == 0) j = wl[head++];
+    if (order == 0) j = wl[head_++];
     else if (order == 1) j = wl[--wn];
-    else { int32_t r = head + (int32_t)(rng_next(&seed) % (uint64_t)(wn - head)); j = wl[r]; wl[r] = wl[--wn]; }
-    int32_t s = v->t[j].state; float c = v->t[j].cost;
+    else { int32_t r = head_ + (int32_t)(rng_next(&seed) % (uint64_t)(wn - head_)); j = wl[r]; wl[r] = wl[--wn]; }
+    int32_t s = v->t[j].state; float c = v->t[j].cost; int32_t b = v->t[j].b;
     for (int64_t a = p->x_off[s]; a < p->x_off[s + 1]; ++a) {
       float nc = canon(c + p->x_w[a]);
-      if (boost && p->x_ol[a] != 0) nc = canon(nc + boost[p->x_ol[a]]);
+      int32_t nb = b;
+      if (B && p->x_ol[a] != 0) {
+        int add; float sc;
+        nb = boost_step(B, b, p->x_ol[a], &add, &sc);
+        if (add) nc = canon(nc + sc);
+      }
       if (!(nc < INFINITY)) continue;
       if (!keep(nc, k)) continue;
       int32_t d = p->x_next[a]; int32_t gid = (int32_t)(p->Ae + a);
-      int32_t q = map[d];
+      int32_t q = tok_find(v, head, d, nb);
       if (q < 0) {
-        token_t t = { d, nc, j, gid }; map[d] = v->n; q = v->n; tv_push(v, t);
+        q = tok_add(v, head, d, nb, nc, j, gid);
       } else if (nc < v->t[q].cost || (nc == v->t[q].cost && gid < v->t[q].arc)) {
         v->t[q].cost = nc; v->t[q].prev = j; v->t[q].arc = gid;
       } else continue;
@@ -298,7 +362,7 @@ int32_t oracle_eps_closure(const oracle_prepared *p, const int32_t *states, cons
   int32_t *map = (int32_t *)malloc(sizeof(int32_t) * p->S);
   for (int32_t s = 0; s < p->S; ++s) map[s] = -1;
   tokvec v = { 0, 0, 0 };
-  for (int32_t i = 0; i < n; ++i) { token_t t = { states[i], costs[i], -1, -1 }; map[states[i]] = v.n; tv_push(&v, t); }
+  for (int32_t i = 0; i < n; ++i) tok_add(&v, map, states[i], 0, costs[i], -1, -1);
   eps_closure(p, &v, map, &k, order, seed, NULL);
   int32_t ret = v.n;
   if (ret > cap) ret = -1;
@@ -318,9 +382,10 @@ typedef struct { int32_t prev, arc; } bp_t;
  * Decode one utterance.  loglikes: [len][V] row-major (row stride `row_stride` floats).
  * words: [opts->max_words].  Optional outputs (NULL to skip):
  *   digest_count/digest_sum [len+1]: per closed token set A_0..A_len, its size and the sum
- *     over tokens of mix64(state<<32 | cost bits) modulo 2^64;
+ *     over tokens of mix64((state<<32 | cost bits) ^ B state * 0x9E3779B97F4A7C15) modulo 2^64;
  *   path_arcs [path_cap]: global arc ids of the best path in order (res->path_len of them);
- *   dump_off [len+2], dump_states/dump_costs [dump_cap]: every closed token set;
+ *   dump_off [len+2], dump_states/dump_costs (and dump_bstates, may be NULL) [dump_cap]: every
+ *     closed token set;
  *   frame_best [len+1]: with cost offsets (R11) the best cost b_t that the tokens of A_t were
  *     rebased by (0 for A_0, for empty sets and without offsets).
  * Returns 0, or -1 on bad arguments, -2 if a dump/path buffer is too small.
@@ -330,8 +395,17 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
                       int32_t *digest_count, uint64_t *digest_sum,
                       int32_t *path_arcs, int32_t path_cap,
                       int64_t *dump_off, int32_t *dump_states, float *dump_costs, int64_t dump_cap,
-                      float *frame_best) {
+                      float *frame_best, int32_t *dump_bstates) {
   if (!p || !o || !res || len < 0 || o->max_words < 0 || !(o->beam >= 0.0f)) return -1;
+  if (o->bfst_states > 0) {                     /* R12: a well-formed deterministic acceptor, and no table beside it */
+    if (o->boost_n > 0 || o->bfst_arcs < 0) return -1;
+    for (int32_t i = 0; i < o->bfst_arcs; ++i) {
+      if (o->bfst_from[i] < 0 || o->bfst_from[i] >= o->bfst_states || o->bfst_to[i] < 0 ||
+          o->bfst_to[i] >= o->bfst_states || o->bfst_label[i] <= 0 || !isfinite(o->bfst_score[i])) return -1;
+      for (int32_t j = 0; j < i; ++j)
+        if (o->bfst_from[j] == o->bfst_from[i] && o->bfst_label[j] == o->bfst_label[i]) return -1;
+    }
+  }
   memset(res, 0, sizeof(*res));
   int32_t rc = 0;
   int32_t *map = (int32_t *)malloc(sizeof(int32_t) * p->S);
@@ -354,11 +428,14 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       if (o->boost_ids[i] > 0 && o->boost_ids[i] <= max_ol) boost[o->boost_ids[i]] = o->boost_scores[i];
   }
 
+  booster Bst = { boost, o->bfst_states, o->bfst_arcs, o->bfst_from, o->bfst_label, o->bfst_to, o->bfst_score };
+  const booster *B = (boost || o->bfst_states > 0) ? &Bst : NULL;
+
   if (frame_best) frame_best[0] = 0.0f;
-  /* initial set: start token, closed over epsilon arcs with best = 0 and no bin limit */
-  { token_t t = { p->start, 0.0f, -1, -1 }; map[p->start] = 0; tv_push(&cur, t); }
+  /* initial set: start token (in the root of B), closed over epsilon arcs with best = 0 and no bin limit */
+  tok_add(&cur, map, p->start, 0, 0.0f, -1, -1);
   k.best = 0.0f; k.k_keep = 256;
-  eps_closure(p, &cur, map, &k, o->worklist_order, o->order_seed, boost);
+  eps_closure(p, &cur, map, &k, o->worklist_order, o->order_seed, B);
 
   for (int32_t t = 0; t <= len; ++t) {
     /* ---- store the closed set A_t: backpointers, digest, counters, dump */
@@ -368,7 +445,8 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     for (int32_t i = 0; i < cur.n; ++i) {
       lat[t][i].prev = cur.t[i].prev; lat[t][i].arc = cur.t[i].arc;
       uint32_t cb; memcpy(&cb, &cur.t[i].cost, 4);
-      dsum += mix64(((uint64_t)(uint32_t)cur.t[i].state << 32) | cb);
+      dsum += mix64((((uint64_t)(uint32_t)cur.t[i].state << 32) | cb) ^
+                    ((uint64_t)(uint32_t)cur.t[i].b * 0x9E3779B97F4A7C15ull));
       res->counters[2] += p->x_off[cur.t[i].state + 1] - p->x_off[cur.t[i].state];
     }
     res->counters[4] += cur.n;
@@ -377,7 +455,10 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     if (dump_off) {
       dump_off[t] = dump_used;
       if (dump_used + cur.n > dump_cap) { rc = -2; goto done; }
-      for (int32_t i = 0; i < cur.n; ++i) { dump_states[dump_used + i] = cur.t[i].state; dump_costs[dump_used + i] = cur.t[i].cost; }
+      for (int32_t i = 0; i < cur.n; ++i) {
+        dump_states[dump_used + i] = cur.t[i].state; dump_costs[dump_used + i] = cur.t[i].cost;
+        if (dump_bstates) dump_bstates[dump_used + i] = cur.t[i].b;
+      }
       dump_used += cur.n; dump_off[t + 1] = dump_used;
     }
     if (t == len) break;
@@ -388,15 +469,20 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
     nxt.n = 0;
     res->counters[0] += cur.n;
     for (int32_t i = 0; i < cur.n; ++i) {
-      int32_t s = cur.t[i].state; float c = cur.t[i].cost;
+      int32_t s = cur.t[i].state; float c = cur.t[i].cost; int32_t b = cur.t[i].b;
       res->counters[1] += p->e_off[s + 1] - p->e_off[s];
       for (int64_t a = p->e_off[s]; a < p->e_off[s + 1]; ++a) {
         float ac = -L[p->e_il[a] - 1];
         float nc = canon((c + p->e_w[a]) + ac);
-        if (boost && p->e_ol[a] != 0) nc = canon(nc + boost[p->e_ol[a]]);
+        int32_t nb = b;
+        if (B && p->e_ol[a] != 0) {
+          int add; float sc;
+          nb = boost_step(B, b, p->e_ol[a], &add, &sc);
+          if (add) nc = canon(nc + sc);
+        }
         if (!(nc < INFINITY)) continue;
-        int32_t d = p->e_next[a]; int32_t q = map[d];
-        if (q < 0) { token_t nt = { d, nc, i, (int32_t)a }; map[d] = nxt.n; tv_push(&nxt, nt); }
+        int32_t d = p->e_next[a]; int32_t q = tok_find(&nxt, map, d, nb);
+        if (q < 0) tok_add(&nxt, map, d, nb, nc, i, (int32_t)a);
         else if (nc < nxt.t[q].cost || (nc == nxt.t[q].cost && (int32_t)a < nxt.t[q].arc)) {
           nxt.t[q].cost = nc; nxt.t[q].prev = i; nxt.t[q].arc = (int32_t)a;
         }
@@ -415,10 +501,11 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       if (hist[0] > o->max_active) res->counters[6]++;
     }
     int32_t m = 0;
-    for (int32_t i = 0; i < nxt.n; ++i) {
-      if (keep(nxt.t[i].cost, &k)) { nxt.t[m] = nxt.t[i]; map[nxt.t[m].state] = m; ++m; }
-      else map[nxt.t[i].state] = -1;
-    }
+    for (int32_t i = 0; i < nxt.n; ++i) map[nxt.t[i].state] = -1;
+    for (int32_t i = 0; i < nxt.n; ++i)
+      if (keep(nxt.t[i].cost, &k)) {               /* survivors move up; their chains are rebuilt */
+        nxt.t[m] = nxt.t[i]; nxt.t[m].link = map[nxt.t[m].state]; map[nxt.t[m].state] = m; ++m;
+      }
     nxt.n = m;
     res->counters[3] += m;
     if (frame_best) frame_best[t + 1] = 0.0f;
@@ -429,7 +516,7 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       if (frame_best) frame_best[t + 1] = best;
     }
     /* ---- epsilon closure under the frozen predicate (R6) */
-    eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1, boost);
+    eps_closure(p, &nxt, map, &k, o->worklist_order, o->order_seed + (uint64_t)t + 1, B);
     { tokvec tmp = cur; cur = nxt; nxt = tmp; }
   }
 
@@ -442,14 +529,16 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
       for (int32_t i = 0; i < cur.n; ++i) {
         float f = cur.t[i].cost + p->final_cost[cur.t[i].state];
         if (!(f < INFINITY)) continue;
-        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }
+        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||
+            (f == bf && cur.t[i].state == cur.t[bi].state && cur.t[i].b < cur.t[bi].b)) { bi = i; bf = f; }
         any_final = 1;
       }
     }
     if (!any_final) {
       for (int32_t i = 0; i < cur.n; ++i) {
         float f = cur.t[i].cost;
-        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }
+        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||
+            (f == bf && cur.t[i].state == cur.t[bi].state && cur.t[i].b < cur.t[bi].b)) { bi = i; bf = f; }
       }
     }
     res->cost = o->cost_offset ? (float)((double)bf + offset_sum) : bf;
@@ -501,6 +590,7 @@ int64_t oracle_lattice_links(const oracle_prepared *p, const float *loglikes, in
                              int64_t cap, int32_t *l_frame, int32_t *l_src, int32_t *l_dst,
                              int32_t *l_arc, float *l_cost) {
   if (!p || !o || len < 0 || !set_off || !(lattice_beam >= 0.0f)) return -1;
+  if (o->bfst_states > 0) return -1;            /* the lattice definition (R10) is over graph states only */
   float *boost = NULL;
   if (o->boost_n > 0) {
     int32_t max_ol = 0;

@@ -32,7 +32,9 @@ class _Opts(C.Structure):
     _fields_ = [("beam", C.c_float), ("max_active", C.c_int32), ("max_words", C.c_int32),
                 ("finalize", C.c_int32), ("worklist_order", C.c_int32), ("order_seed", C.c_uint64),
                 ("boost_n", C.c_int32), ("boost_ids", C.c_void_p), ("boost_scores", C.c_void_p),
-                ("cost_offset", C.c_int32)]
+                ("cost_offset", C.c_int32),
+                ("bfst_states", C.c_int32), ("bfst_arcs", C.c_int32), ("bfst_from", C.c_void_p),
+                ("bfst_label", C.c_void_p), ("bfst_to", C.c_void_p), ("bfst_score", C.c_void_p)]
 
 
 class _Result(C.Structure):
@@ -71,7 +73,7 @@ def _load():
         _lib.oracle_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                        C.POINTER(_Opts), C.c_void_p, C.POINTER(_Result),
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         _lib.oracle_lattice_links.restype = C.c_int64
         _lib.oracle_lattice_links.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                               C.POINTER(_Opts), C.c_float, C.c_void_p, C.c_void_p,
@@ -105,6 +107,7 @@ class OracleResult:
     digest_count: np.ndarray | None = None       # [len+1]
     digest_sum: np.ndarray | None = None         # [len+1] uint64
     frames: list | None = field(default=None)    # per closed set: (states, costs)
+    frames_b: list | None = field(default=None)  # per closed set: the tokens' boosting-acceptor states
     frame_best: np.ndarray | None = None         # [len+1] offsets the sets were rebased by (cost offsets)
 
     @property
@@ -178,8 +181,10 @@ class Oracle:
     def decode(self, loglikes, length=None, beam=17.0, max_active=10000, max_words=1024,
                finalize=True, worklist_order=0, order_seed=0, want_path=False,
                want_digests=False, want_frames=False, frames_cap=None, boost=None,
-               cost_offset=False) -> OracleResult:
+               cost_offset=False, boost_fst=None) -> OracleResult:
         """boost: optional (word_ids, scores) table of the utterance (Section "Word boosting").
+        boost_fst: optional boosting acceptor with several states (reading R12 in the C source), an
+        object with num_states and arrays arc_from, arc_label, arc_to, arc_score.
         cost_offset: rebase the token costs after every prune step (reading R11 in the C source)."""
         lib = _load()
         ll = np.asarray(loglikes, dtype=np.float32)
@@ -195,6 +200,16 @@ class Oracle:
         else:
             o = _Opts(beam, max_active, max_words, int(bool(finalize)), worklist_order, order_seed, 0, None, None,
                       int(bool(cost_offset)))
+        if boost_fst is not None:
+            assert boost is None
+            f_from = np.ascontiguousarray(boost_fst.arc_from, dtype=np.int32)
+            f_lab = np.ascontiguousarray(boost_fst.arc_label, dtype=np.int32)
+            f_to = np.ascontiguousarray(boost_fst.arc_to, dtype=np.int32)
+            f_sc = np.ascontiguousarray(boost_fst.arc_score, dtype=np.float32)
+            assert f_from.shape == f_lab.shape == f_to.shape == f_sc.shape
+            o.bfst_states, o.bfst_arcs = int(boost_fst.num_states), len(f_from)
+            o.bfst_from, o.bfst_label = f_from.ctypes.data, f_lab.ctypes.data
+            o.bfst_to, o.bfst_score = f_to.ctypes.data, f_sc.ctypes.data
         res = _Result()
         words = np.zeros(max(1, max_words), dtype=np.int32)
         dc = np.zeros(n + 1, dtype=np.int32) if want_digests else None
@@ -206,22 +221,24 @@ class Oracle:
             doff = np.zeros(n + 2, dtype=np.int64)
             dst = np.zeros(cap, dtype=np.int32)
             dco = np.zeros(cap, dtype=np.float32)
+            dbs = np.zeros(cap, dtype=np.int32)
         else:
-            cap, doff, dst, dco = 0, None, None, None
+            cap, doff, dst, dco, dbs = 0, None, None, None, None
         ptr = lambda a: None if a is None else a.ctypes.data
         fbest = np.zeros(n + 1, dtype=np.float32) if want_frames else None
         rc = lib.oracle_decode(self._p, ll.ctypes.data, ll.strides[0] // 4, n, C.byref(o),
                                words.ctypes.data, C.byref(res), ptr(dc), ptr(ds), ptr(path), pcap,
-                               ptr(doff), ptr(dst), ptr(dco), cap, ptr(fbest))
+                               ptr(doff), ptr(dst), ptr(dco), cap, ptr(fbest), ptr(dbs))
         if rc != 0:
             raise RuntimeError(f"oracle_decode failed: {rc}")
-        frames = None
+        frames = frames_b = None
         if want_frames:
             frames = [(dst[doff[t]:doff[t + 1]].copy(), dco[doff[t]:doff[t + 1]].copy())
                       for t in range(n + 1)]
+            frames_b = [dbs[doff[t]:doff[t + 1]].copy() for t in range(n + 1)]
         return OracleResult(words[:res.nwords].copy(), float(res.cost), int(res.flags),
                             np.array(list(res.counters), dtype=np.int64),
-                            None if path is None else path[:res.path_len].copy(), dc, ds, frames, fbest)
+                            None if path is None else path[:res.path_len].copy(), dc, ds, frames, frames_b, fbest)
 
     def lattice(self, loglikes, length=None, beam=17.0, max_active=10000, lattice_beam=np.inf,
                 boost=None, cost_offset=False) -> "OracleLattice":

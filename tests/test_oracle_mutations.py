@@ -13,7 +13,7 @@ import sys
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-PIN_FILES = ["tests/test_oracle_decode_pins.py", "tests/test_oracle_pins.py"]
+PIN_FILES = ["tests/test_oracle_decode_pins.py", "tests/test_oracle_pins.py", "tests/test_oracle_boost_fst.py"]
 
 # (name, text in wfst_oracle.c, replacement); the text must occur exactly once
 MUTANTS = [
@@ -48,11 +48,11 @@ MUTANTS = [
      "(nc == v->t[q].cost && gid < v->t[q].arc)",
      "(nc == v->t[q].cost && gid > v->t[q].arc)"),
     ("final tie (with final costs) goes to the higher state",
-     "if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }\n        any_final = 1;",
-     "if (bi < 0 || f < bf || (f == bf && cur.t[i].state > cur.t[bi].state)) { bi = i; bf = f; }\n        any_final = 1;"),
+     "        if (!(f < INFINITY)) continue;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||",
+     "        if (!(f < INFINITY)) continue;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state > cur.t[bi].state) ||"),
     ("final tie (no final state) goes to the higher state",
-     "        float f = cur.t[i].cost;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state)) { bi = i; bf = f; }",
-     "        float f = cur.t[i].cost;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state > cur.t[bi].state)) { bi = i; bf = f; }"),
+     "        float f = cur.t[i].cost;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||",
+     "        float f = cur.t[i].cost;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state > cur.t[bi].state) ||"),
     ("cutoff not frozen: closure uses no bin limit",
      "    k.best = best; k.k_keep = k_keep;\n",
      "    k.best = best; k.k_keep = 256; (void)k_keep;\n"),
@@ -62,6 +62,24 @@ MUTANTS = [
     ("label k reads column k",
      "float ac = -L[p->e_il[a] - 1];",
      "float ac = -L[p->e_il[a] % p->V];"),
+    ("boosting acceptor: a mismatch does not retry at the root",
+     "  if (i < 0 && b != 0) i = bfst_arc(B, 0, o);",
+     "  (void)0;"),
+    ("boosting acceptor: a mismatch leaves the B state where it was",
+     "  if (i < 0) return 0;\n  *add = 1; *score = B->score[i];",
+     "  if (i < 0) return b;\n  *add = 1; *score = B->score[i];"),
+    ("boosting acceptor: the B state is not part of the recombination key",
+     "if (v->t[q].b == b) return q;",
+     "return q;"),
+    ("boosting acceptor: epsilon arcs with output labels do not move B",
+     "        nb = boost_step(B, b, p->x_ol[a], &add, &sc);",
+     "        boost_step(B, b, p->x_ol[a], &add, &sc);"),
+    ("boosting acceptor: matched arc does not move B",
+     "  *add = 1; *score = B->score[i];\n  return B->to[i];",
+     "  *add = 1; *score = B->score[i];\n  return b;"),
+    ("boosting acceptor: final tie prefers the higher B state",
+     "        if (!(f < INFINITY)) continue;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||\n            (f == bf && cur.t[i].state == cur.t[bi].state && cur.t[i].b < cur.t[bi].b))",
+     "        if (!(f < INFINITY)) continue;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||\n            (f == bf && cur.t[i].state == cur.t[bi].state && cur.t[i].b > cur.t[bi].b))"),
     ("final cost ignored",
      "float f = cur.t[i].cost + p->final_cost[cur.t[i].state];",
      "float f = cur.t[i].cost;"),

@@ -9,8 +9,9 @@ from .graphs import (Graph, tiny_lexicon_graph, tlg_shaped_graph, ctc_topology_g
                      eps_layers_graph)
 from .loglikes import ctc_loglikes, random_lengths
 from .configs import CONFIGS, make_config, boost_tables
+from .boost import BoostFst, boost_trie, boost_fsts, random_targets
 
 __all__ = ["Graph", "tiny_lexicon_graph", "tlg_shaped_graph", "ctc_topology_graph",
            "micro_graph", "permute_arcs_within_states", "dense_graph", "giant_state_graph",
            "eps_layers_graph", "ctc_loglikes", "random_lengths",
-           "CONFIGS", "make_config", "boost_tables"]
+           "CONFIGS", "make_config", "boost_tables", "BoostFst", "boost_trie", "boost_fsts", "random_targets"]

@@ -7,6 +7,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
+from .boost import boost_fsts
 from .graphs import Graph, tiny_lexicon_graph, tlg_shaped_graph
 from .loglikes import ctc_loglikes, random_lengths
 
@@ -36,6 +37,14 @@ CONFIGS = {
                      batch=32, len_lo=50, len_hi=875, seed=2,
                      ll=dict(sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0),
                      beam=17.0, max_active=7000, boost=dict(seed=5, per_utt=100, score=-2.0)),
+    # config 5: config 2, every utterance composed on the fly with its own boosting acceptor of 100
+    # targets of 1-4 output labels (trie; a decoder takes the failure arc to the root on a mismatch)
+    "c5_boost_fst": dict(graph=("tlg", dict(seed=2, num_states=200_000, target_arcs=1_000_000,
+                                            num_classes=129, alpha=1.8, k_max=5000, p_eps=0.15,
+                                            num_words=20_000)),
+                         batch=32, len_lo=50, len_hi=875, seed=2,
+                         ll=dict(sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0),
+                         beam=17.0, max_active=7000, boost_fst=dict(seed=5, per_utt=100, max_len=4, score=-2.0)),
     # a scaled-down graph of the c3 family for quick runs (not a reported configuration)
     "c3_mini": dict(graph=("tlg", dict(seed=3, num_states=1_000_000, target_arcs=3_000_000,
                                        num_classes=129, alpha=1.8, k_max=5000, p_eps=0.20,
@@ -66,6 +75,7 @@ class Workload:
     beam: float
     max_active: int
     boosts: list | None = None   # per-utterance (word ids, scores) or None
+    boost_fsts: list | None = None   # per-utterance boosting acceptors (workloads.boost.BoostFst) or None
 
     @property
     def audio_seconds(self) -> float:
@@ -87,4 +97,8 @@ def make_config(name: str, batch: int | None = None, graph: Graph | None = None)
     boosts = None
     if "boost" in c:
         boosts = boost_tables(c["boost"]["seed"], B, int(g.meta["num_words"]), c["boost"]["per_utt"], c["boost"]["score"])
-    return Workload(name, g, lengths, ll, float(c["beam"]), int(c["max_active"]), boosts)
+    fsts = None
+    if "boost_fst" in c:
+        fsts = boost_fsts(c["boost_fst"]["seed"], B, int(g.meta["num_words"]), c["boost_fst"]["per_utt"],
+                          c["boost_fst"]["max_len"], c["boost_fst"]["score"])
+    return Workload(name, g, lengths, ll, float(c["beam"]), int(c["max_active"]), boosts, fsts)
