@@ -69,6 +69,10 @@
  *       its destination and score; none: the token stays in the root, nothing is added).  Arcs
  *       without output label leave b unchanged.  A B with the single state 0 and self-loops is
  *       exactly the table of R9.  Final choice ties: lower graph state, then lower B state.
+ *       Recombination ties (R3): two tokens of one graph state can take the SAME arc into the same
+ *       pair (both fall back to the root, say); after (cost, arc id) the lower B state of the
+ *       source token wins, which makes the order total again (an arc of the product is a graph
+ *       arc plus the B state it is taken in).
  *       Digest of a token: the pair's B state enters the mix (0 leaves the R1-R11 digest unchanged).
  *
  * parity pins: see tests/test_oracle_*.py (exhaustive path enumeration, fp64 trellis
@@ -342,7 +346,8 @@ static void eps_closure(const oracle_prepared *p, tokvec *v, int32_t *head, cons
       int32_t q = tok_find(v, head, d, nb);
       if (q < 0) {
         q = tok_add(v, head, d, nb, nc, j, gid);
-      } else if (nc < v->t[q].cost || (nc == v->t[q].cost && gid < v->t[q].arc)) {
+      } else if (nc < v->t[q].cost || (nc == v->t[q].cost && gid < v->t[q].arc) ||
+                 (nc == v->t[q].cost && gid == v->t[q].arc && b < v->t[v->t[q].prev].b)) {
         v->t[q].cost = nc; v->t[q].prev = j; v->t[q].arc = gid;
       } else continue;
       if (wn == wcap) { wcap = wcap ? wcap * 2 : 1024; wl = (int32_t *)realloc(wl, sizeof(int32_t) * wcap); }
@@ -483,7 +488,8 @@ int32_t oracle_decode(const oracle_prepared *p, const float *loglikes, int64_t r
         if (!(nc < INFINITY)) continue;
         int32_t d = p->e_next[a]; int32_t q = tok_find(&nxt, map, d, nb);
         if (q < 0) tok_add(&nxt, map, d, nb, nc, i, (int32_t)a);
-        else if (nc < nxt.t[q].cost || (nc == nxt.t[q].cost && (int32_t)a < nxt.t[q].arc)) {
+        else if (nc < nxt.t[q].cost || (nc == nxt.t[q].cost && (int32_t)a < nxt.t[q].arc) ||
+                 (nc == nxt.t[q].cost && (int32_t)a == nxt.t[q].arc && b < cur.t[nxt.t[q].prev].b)) {
           nxt.t[q].cost = nc; nxt.t[q].prev = i; nxt.t[q].arc = (int32_t)a;
         }
       }

@@ -127,6 +127,25 @@ def test_final_tie_lower_graph_state_then_lower_b_state():
         assert r.words.tolist() == [C_]                     # the token in the root of B
 
 
+def test_same_arc_taken_in_two_b_states_lower_source_b_state_wins():
+    """Tokens (state 3, root) and (state 3, B state 1) at equal cost both take the arc 3 -> 4 whose
+    label C matches nowhere, so both land in (4, root) with the same cost and the same arc id:
+    the hypothesis that came out of the lower B state is kept.  Emitting and epsilon variant, and
+    both orders of creation of the two tokens."""
+    fst = BoostFst(2, np.array([0, 1], np.int32), np.array([A, B_], np.int32), np.array([1, 0], np.int32),
+                   np.array([-1.0, -8.0], np.float32))
+    for eps in (False, True):
+        for first_a in (True, False):
+            via_a, via_d = (0, 1, 1, A, 2.0), (0, 2, 1, D, 1.0)          # A: 2 - 1 = 1, into B state 1; D: 1, root
+            arcs = ([via_a, via_d] if first_a else [via_d, via_a]) + \
+                [(1, 3, 1, 0, 1.0), (2, 3, 1, 0, 1.0), (3, 4, 0 if eps else 1, C_, 1.0)]
+            if eps:
+                arcs.append((4, 4, 1, 0, 0.0))
+            g = _from_arc_list(5, 0, 1, arcs, [INF, INF, INF, INF, 0.0])
+            r = Oracle(g).decode(np.zeros((3, 1), np.float32), beam=INF, max_active=IMAX, boost_fst=fst)
+            assert r.cost == 3.0 and r.words.tolist() == [D, C_]
+
+
 # ---------------------------------------------------------------- one label per target = the table
 def test_single_label_targets_equal_the_table_path(c1, c2):
     """Targets of one label: B is the paper's one-state acceptor, a self-loop per word.  Token sets,

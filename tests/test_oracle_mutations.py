@@ -80,6 +80,15 @@ MUTANTS = [
     ("boosting acceptor: final tie prefers the higher B state",
      "        if (!(f < INFINITY)) continue;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||\n            (f == bf && cur.t[i].state == cur.t[bi].state && cur.t[i].b < cur.t[bi].b))",
      "        if (!(f < INFINITY)) continue;\n        if (bi < 0 || f < bf || (f == bf && cur.t[i].state < cur.t[bi].state) ||\n            (f == bf && cur.t[i].state == cur.t[bi].state && cur.t[i].b > cur.t[bi].b))"),
+    ("boosting acceptor: same arc from two B states, first arrival wins (emitting)",
+     " ||\n                 (nc == nxt.t[q].cost && (int32_t)a == nxt.t[q].arc && b < cur.t[nxt.t[q].prev].b)) {",
+     ") {"),
+    ("boosting acceptor: same arc from two B states, first arrival wins (epsilon)",
+     " ||\n                 (nc == v->t[q].cost && gid == v->t[q].arc && b < v->t[v->t[q].prev].b)) {",
+     ") {"),
+    ("boosting acceptor: same arc from two B states, higher source B state wins",
+     "(int32_t)a == nxt.t[q].arc && b < cur.t[nxt.t[q].prev].b",
+     "(int32_t)a == nxt.t[q].arc && b > cur.t[nxt.t[q].prev].b"),
     ("final cost ignored",
      "float f = cur.t[i].cost + p->final_cost[cur.t[i].state];",
      "float f = cur.t[i].cost;"),
