@@ -117,6 +117,33 @@ typedef struct {
 } wfst_boost_table;
 
 /*
+ * Boosting acceptor with several states, for boosting sequences of output labels (phrases); the
+ * paper composes the graph on the fly with a boosting acceptor B (Section "Word boosting", TLG o B),
+ * draws B with one state, a self-loop per boosted word and a failure arc for every other word
+ * (figure "Example word boosting WFSA"), and names phrases as the extension (Conclusions).
+ * B is deterministic over the graph's OUTPUT labels: n_arcs arcs (arc_from, arc_label > 0, arc_to,
+ * arc_score), states 0..n_states-1, root 0, at most one arc per (state, label).  A hypothesis is a
+ * pair (graph state, B state), hypotheses are recombined per pair, and max-active counts pairs.
+ * On a graph arc with output label o taken in B state b: if b has an arc on o, its score is added
+ * after the other terms and the hypothesis moves to its destination; otherwise the failure arc
+ * leads to the root at no cost and o is tried once more there (the root's arc on o if it has one;
+ * else the hypothesis stays in the root and nothing is added).  Arcs without output label leave b
+ * unchanged.  n_states == 1 is exactly wfst_boost_table.  Typical B: the trie of the target
+ * sequences with every node that has no continuation merged into the root.
+ * HOST arrays, copied during the call.  Limits: n_arcs <= 1024; n_states <= 4096 and
+ * n_states <= 2^(29 - bits needed for the graph's 32-byte block count) (INVALID_ARG otherwise);
+ * finite scores.  wfst_get_lattice is not available for a channel decoded with n_states > 1.
+ */
+typedef struct {
+  int32_t n_states;
+  int32_t n_arcs;
+  const int32_t *arc_from;        /* [n_arcs] */
+  const int32_t *arc_label;       /* [n_arcs] */
+  const int32_t *arc_to;          /* [n_arcs] */
+  const float *arc_score;         /* [n_arcs] */
+} wfst_boost_fst;
+
+/*
  * Build a decoder: validates the graph, splits emitting and epsilon arcs (global arc ids:
  * emitting arcs 0..Ae-1 in (state, given order), epsilon arcs Ae.. likewise), uploads it and
  * allocates the per-channel state.  Errors: INVALID_ARG, BAD_GRAPH, OOM, HIP.
@@ -155,6 +182,13 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *dec, const float *loglikes, cons
                                   const wfst_boost_table *const *boosts, void *stream,
                                   int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
 
+/* The same with a boosting acceptor per utterance: fsts is a HOST array of B pointers (NULL entries,
+ * or NULL for the whole array: no boosting). */
+int32_t wfst_decode_batch_boost_fst(wfst_decoder *dec, const float *loglikes, const int32_t *lengths,
+                                    int32_t B, int32_t T, int32_t V, float beam, int32_t max_active,
+                                    const wfst_boost_fst *const *fsts, void *stream,
+                                    int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
+
 /*
  * Streaming (Section "Streaming inference": the decoder state kept per audio stream is its
  * set of active tokens; here it lives permanently in the channel's slot in GPU memory, so
@@ -178,6 +212,9 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *dec, const float *loglikes, cons
  */
 int32_t wfst_init_channel(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
                           const wfst_boost_table *boost, void *stream);
+/* wfst_init_channel with a boosting acceptor of several states (NULL = none) for the stream. */
+int32_t wfst_init_channel_boost_fst(wfst_decoder *dec, int32_t ch, float beam, int32_t max_active,
+                                    const wfst_boost_fst *fst, void *stream);
 int32_t wfst_init_channels(wfst_decoder *dec, const int32_t *channels, int32_t n, float beam,
                            int32_t max_active, const wfst_boost_table *const *boosts, void *stream);
 int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n,
@@ -248,6 +285,8 @@ int32_t wfst_get_lattice_noalloc(wfst_decoder *dec, int32_t ch, const void *logl
  *     of channel ch (f = frames consumed): count[t] = |A_t| and digest[t] = sum over tokens
  *     of mix(state, cost bits) modulo 2^64.  Writes min(f+1, cap) entries, *n = f+1.
  *   wfst_debug_get_tokens: current token set of channel ch (any order).
+ *   wfst_debug_get_token_pairs: the same with each token's state in the boosting acceptor
+ *     (bstates [cap], may be NULL).
  *   wfst_get_counters: sums over all channels since create or the last reset:
  *     [0] tokens expanded, [1] emitting arcs out of them, [2] epsilon arcs out of every
  *     closed token set, [3] tokens surviving the prune step (before the closure), [4] tokens stored,
@@ -258,6 +297,8 @@ int32_t wfst_debug_frame_digests(wfst_decoder *dec, int32_t ch, uint64_t *digest
                                  int32_t cap, int32_t *n);
 int32_t wfst_debug_get_tokens(wfst_decoder *dec, int32_t ch, int32_t *states, float *costs,
                               int32_t cap, int32_t *n);
+int32_t wfst_debug_get_token_pairs(wfst_decoder *dec, int32_t ch, int32_t *states, int32_t *bstates,
+                                   float *costs, int32_t cap, int32_t *n);
 int32_t wfst_get_counters(wfst_decoder *dec, int64_t counters[8], int32_t reset);
 
 /*

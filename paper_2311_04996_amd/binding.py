@@ -20,11 +20,11 @@ FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPAC
 LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
-           "wfst_init_channel", "wfst_init_channels",
+           "wfst_decode_batch_boost_fst", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
            "wfst_get_lattice_noalloc",
            "wfst_debug_frame_digests",
-           "wfst_debug_get_tokens", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
+           "wfst_debug_get_tokens", "wfst_debug_get_token_pairs", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
 
 
@@ -51,6 +51,19 @@ def _boost_struct(boost):
     sc = np.ascontiguousarray(boost[1], dtype=np.float32)
     assert ids.shape == sc.shape and ids.ndim == 1
     return wfst_boost_table(len(ids), ids.ctypes.data, sc.ctypes.data), (ids, sc)
+
+
+class wfst_boost_fst(C.Structure):
+    _fields_ = [("n_states", C.c_int32), ("n_arcs", C.c_int32), ("arc_from", C.c_void_p),
+                ("arc_label", C.c_void_p), ("arc_to", C.c_void_p), ("arc_score", C.c_void_p)]
+
+
+def _fst_struct(fst):
+    """Object with num_states, arc_from, arc_label, arc_to, arc_score -> (wfst_boost_fst, arrays to keep alive)."""
+    a = (np.ascontiguousarray(fst.arc_from, dtype=np.int32), np.ascontiguousarray(fst.arc_label, dtype=np.int32),
+         np.ascontiguousarray(fst.arc_to, dtype=np.int32), np.ascontiguousarray(fst.arc_score, dtype=np.float32))
+    assert a[0].shape == a[1].shape == a[2].shape == a[3].shape and a[0].ndim == 1
+    return wfst_boost_fst(int(fst.num_states), len(a[0]), *[x.ctypes.data for x in a]), a
 
 
 class wfst_opts(C.Structure):
@@ -93,6 +106,9 @@ def load_library():
     lib.wfst_decode_batch.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p]
     lib.wfst_decode_batch_boosted.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p, p]
     lib.wfst_init_channel.argtypes = [p, i32, f32, i32, p, p]
+    lib.wfst_init_channel_boost_fst.argtypes = [p, i32, f32, i32, p, p]
+    lib.wfst_decode_batch_boost_fst.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p, p]
+    lib.wfst_debug_get_token_pairs.argtypes = [p, i32, p, p, p, i32, p]
     lib.wfst_init_channels.argtypes = [p, p, i32, f32, i32, p, p]
     lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
     lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
@@ -175,9 +191,11 @@ class Decoder:
             raise WfstError(rc, self.lib.wfst_last_error(self.h).decode())
 
     # ---- offline
-    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None, boosts=None):
+    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None, boosts=None, boost_fsts=None):
         """loglikes: CUDA float32 tensor [B, T, V]; lengths: int32 host array [B].
         boosts: optional list of B entries, each None or a (word_ids, scores) table.
+        boost_fsts: optional list of B entries, each None or a boosting acceptor (an object with
+        num_states, arc_from, arc_label, arc_to, arc_score).
         Returns (words [B, max_words], nwords [B], cost [B], flags [B]); torch CUDA tensors, or
         numpy arrays when the decoder was created with outputs_on_host."""
         import torch
@@ -197,6 +215,14 @@ class Decoder:
                            torch.zeros(B, dtype=torch.float32, device=dev),
                            torch.zeros(B, dtype=torch.int32, device=dev))
         ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
+        if boost_fsts is not None:
+            assert boosts is None and len(boost_fsts) == B
+            keep = [None if f is None else _fst_struct(f) for f in boost_fsts]
+            arr = (C.c_void_p * B)(*[None if k is None else C.addressof(k[0]) for k in keep])
+            self._check(self.lib.wfst_decode_batch_boost_fst(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
+                                                             beam, max_active, arr, _stream_ptr(stream),
+                                                             ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3])))
+            return out
         if boosts is None:
             self._check(self.lib.wfst_decode_batch(self.h, loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
                                                    beam, max_active, _stream_ptr(stream),
@@ -211,9 +237,14 @@ class Decoder:
         return out
 
     # ---- streaming
-    def init_channel(self, ch, beam, max_active, stream=None, boost=None):
-        """boost: None or a (word_ids, scores) table for this stream."""
-        if boost is None:
+    def init_channel(self, ch, beam, max_active, stream=None, boost=None, boost_fst=None):
+        """boost: None or a (word_ids, scores) table for this stream; boost_fst: None or a boosting
+        acceptor with several states."""
+        if boost_fst is not None:
+            assert boost is None
+            t, keep = _fst_struct(boost_fst)
+            self._check(self.lib.wfst_init_channel_boost_fst(self.h, ch, beam, max_active, C.byref(t), _stream_ptr(stream)))
+        elif boost is None:
             self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, None, _stream_ptr(stream)))
         else:
             t, keep = _boost_struct(boost)
@@ -346,6 +377,13 @@ class Decoder:
         st, co, n = np.zeros(cap, np.int32), np.zeros(cap, np.float32), C.c_int32()
         self._check(self.lib.wfst_debug_get_tokens(self.h, ch, st.ctypes.data, co.ctypes.data, cap, C.byref(n)))
         return st[:n.value].copy(), co[:n.value].copy()
+
+    def debug_get_token_pairs(self, ch, cap=1 << 20):
+        """(graph states, boosting-acceptor states, costs) of the channel's current token set."""
+        st, bs, co, n = np.zeros(cap, np.int32), np.zeros(cap, np.int32), np.zeros(cap, np.float32), C.c_int32()
+        self._check(self.lib.wfst_debug_get_token_pairs(self.h, ch, st.ctypes.data, bs.ctypes.data, co.ctypes.data,
+                                                        cap, C.byref(n)))
+        return st[:n.value].copy(), bs[:n.value].copy(), co[:n.value].copy()
 
     def get_counters(self, reset=False):
         c = np.zeros(8, np.int64)

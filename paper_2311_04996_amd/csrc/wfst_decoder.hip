@@ -56,6 +56,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -112,8 +113,10 @@ constexpr int kGroupTarget = kTabSlots * 12 / 16; // mean candidates reduced per
 #ifndef WFST_BOOST
 #define WFST_BOOST 2048
 #endif
-constexpr int kBoostSlots = WFST_BOOST;       // per-channel word-boost table (open addressing)
-constexpr int kBoostMax = kBoostSlots / 2;    // entries it may hold
+constexpr int kBoostSlots = WFST_BOOST;       // per-channel table of the boosting acceptor's arcs (open addressing)
+constexpr int kBoostMax = kBoostSlots / 2;    // arcs it may hold
+constexpr int kBoostStage = 3 * kBoostSlots + 2;   // host staging of one channel's acceptor, in words
+constexpr int kBoostStateBits = 12;           // states of a boosting acceptor: at most 4096 (and what the keys have room for)
 constexpr int kQueueMax = 65536;              // tokens per closed set
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
@@ -144,7 +147,8 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   float beam, scale;          // scale = 256 / beam, computed once on the host
   float sel_ratio;            // candidates taken into recombination per max_active (adaptive)
   int path_frames;            // the traced-path marks of frames 1..path_frames are valid (0: none)
-  int boost_n;                // entries of the channel's word-boost table (0 = none); set by the host
+  int boost_n;                // arcs of the channel's boosting acceptor (0 = none); set by the host
+  int boost_states;           // its states (1: the paper's one-state acceptor, a table word -> score); set by the host
 };
 
 struct DevGraph {
@@ -154,6 +158,9 @@ struct DevGraph {
   unsigned start;             // start state: block number + flags, like `next` of an arc
   int has_final;              // 0: every state is final with cost 0
   int S;
+  // A token is keyed by (state of the boosting acceptor, graph state): key = (b << blk_bits) | block
+  // number, in 29 bits; without an acceptor b = 0 and the key is the block number.
+  int blk_bits; unsigned blk_mask;
 };
 
 struct DevChannels {
@@ -173,7 +180,8 @@ struct DevChannels {
   unsigned *frame_off; int max_frames;
   unsigned long long *dig_sum; int *dig_cnt;   // nullptr unless digests are recorded
   long long *counters;                         // [24]: 8 workload counters, 16 phase tick sums
-  int *boost_keys; float *boost_vals;          // [channels][kBoostSlots]; key 0 = free slot
+  int *boost_keys; float *boost_vals;          // [channels][kBoostSlots] arcs of the boosting acceptor by output label
+  unsigned *boost_from_to;                     //   (key 0 = free slot): score, and from state | to state << 16
 };
 
 struct LaunchArgs {
@@ -189,18 +197,19 @@ struct EpsLds {               // epsilon expansion: one worklist item per thread
   unsigned pre[kBlock + 1];   // exclusive prefix sums of the items' arc counts
   int abase[kBlock];          // unit address of the item's first arc minus its prefix
   float tcost[kBlock];        // cost of the item's token
-  int ttok[kBlock];           // the item's token
+  int ttok[kBlock];           // the item's token | its state in the boosting acceptor << 16
 };
-struct WaveLds {              // ExpandArcs: the work items of one wave (2 tokens per lane)
+struct WaveLds {              // ExpandArcs: the work items of one wave (one token per lane)
   unsigned pre[kWaveTok + 1];
   int abase[kWaveTok];
   float tcost[kWaveTok];
+  int tb[kWaveTok];           // the token's state in the boosting acceptor (only written when there is one)
 };
 struct HubLds {               // ExpandArcs: states with so many arcs that all waves share them
   int first[kHubCap];         // unit address of the first arc to expand
   int deg[kHubCap];           // arcs to expand
   float tcost[kHubCap];
-  int ttok[kHubCap];
+  int ttok[kHubCap];          // token | its state in the boosting acceptor << 16
   int ready[kHubCap];         // set after the entry is written
   int seg_next[kHubCap];      // next segment of kHubSeg arcs nobody has taken yet
 };
@@ -229,7 +238,8 @@ struct Smem {
   unsigned long long red64, red64b;
   long long ctr[8];
   unsigned short occ[kTabSlots];   // table slot of the candidate at each position of a pass (0xFFFF: not inserted)
-  int bk[kBoostSlots]; float bv[kBoostSlots];   // the channel's word-boost table, if it has one
+  int bk[kBoostSlots]; float bv[kBoostSlots];   // the channel's boosting acceptor, if it has one: per arc its output label,
+  unsigned bft[kBoostSlots];                    //   score, and from state | to state << 16
   long long prof[16];         // wall-clock ticks per phase (thread 0)
   long long prof_t0;
   int sel_idx;
@@ -255,9 +265,10 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   return x ^ (x >> 31);
 }
 
-// Word boosting (paper, Section "Word boosting"): score of the single-state boosting acceptor
-// for output label `word` (never 0), 0 if the word is not in the utterance's table.
-__device__ __forceinline__ float boost_of(const Smem &sm, int word);
+// Word boosting (paper, Section "Word boosting": the graph composed on the fly with a boosting
+// acceptor B): a token in state b of B takes an arc with output label `word` (never 0).  Returns
+// the score to add (0 if none) and sets nb to the token's new state in B.
+__device__ __forceinline__ float boost_step(const Smem &sm, int b, int word, int &nb);
 
 // Values read from LDS or global memory that are the same in every lane: tell the compiler,
 // so that they live in scalar registers and control flow on them is scalar.
@@ -341,18 +352,33 @@ struct Ctx {                  // block-uniform view of one channel
   int2 *q0; int4 *wl0; int2 *lat; unsigned *frame_off;   // q0/wl0: two buffers of qcap
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
+  const int2 *srcq;           // the queue the candidates' source tokens are in (ties between two takes of one arc)
 };
 // workload counters of this launch, kept in LDS (thread 0 adds the block-uniform ones)
 enum { kCtTok = 0, kCtEarc, kCtXarc, kCtKept, kCtStored, kCtMaxAct, kCtBin0, kCtFrames };
 
-__device__ __forceinline__ float boost_of(const Smem &sm, int word) {
+// B's arcs are hashed by output label; arcs with the same label (out of different states of B)
+// follow each other in the probe sequence.  If state b has an arc on the label, that arc is taken;
+// otherwise B's failure arc leads to the root (state 0) at no cost and the label is tried once
+// more there: the root's arc on it if there is one, else the token stays in the root and nothing
+// is added.  One walk finds both candidates.  With the one-state acceptor of the paper (b is always
+// 0) this is the lookup of the word's score in a table.
+__device__ __forceinline__ float boost_step(const Smem &sm, int b, int word, int &nb) {
   unsigned h = boost_slot(word);
+  float root_score = 0.0f; int root_to = 0;
   for (;;) {
     const int k = sm.bk[h];
-    if (k == word) return sm.bv[h];
-    if (k == 0) return 0.0f;                 // the table is never full (kBoostMax < kBoostSlots)
+    if (k == 0) break;                       // the table is never full (kBoostMax < kBoostSlots)
+    if (k == word) {
+      const unsigned ft = sm.bft[h];
+      const int from = (int)(ft & 0xffffu);
+      if (from == b) { nb = (int)(ft >> 16); return sm.bv[h]; }
+      if (from == 0) { root_to = (int)(ft >> 16); root_score = sm.bv[h]; }
+    }
     h = (h + 1) & (kBoostSlots - 1);
   }
+  nb = root_to;
+  return root_score;
 }
 
 // Phase timing with the constant-rate wall clock (thread 0 only; a few scalar reads per frame).
@@ -473,7 +499,8 @@ __device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int
 // Cost, beam test and append for N emitting arcs per lane (all 64 lanes of the wave call it).
 template <int N>
 __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[N], const float (&tc)[N],
-                                          const int (&src)[N], const int (&arc)[N], float beam, bool boosted) {
+                                          const int (&src)[N], const int (&arc)[N], const int (&tb)[N],
+                                          float beam, bool boosted) {
   Smem &sm = x.sm;
   const unsigned bo = __hip_atomic_load(&sm.best_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   const float rb = bo == kOrdNone ? INFINITY : ord2f(bo);
@@ -482,11 +509,15 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
 #pragma unroll
   for (int u = 0; u < N; ++u) {
     nc[u] = canon((tc[u] + __int_as_float(a[u].y)) + sm.u.e.ac[a[u].z - 1]);
-    if (boosted && a[u].w != 0 && ok[u]) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // + b[olabel]
+    next[u] = a[u].x;
+    if (boosted) {                             // the destination's key carries the token's state in B
+      int nb = tb[u];
+      if (a[u].w != 0 && ok[u]) nc[u] = canon(nc[u] + boost_step(sm, tb[u], a[u].w, nb));   // + B's score
+      next[u] |= nb << x.g.blk_bits;
+    }
     // predicates are combined with & and selects: no short-circuit branches in the hot loop
     ok[u] &= (int)(nc[u] < INFINITY) & (int)!((nc[u] - rb) > beam);
     o = min(o, ok[u] ? f2ord(nc[u]) : kOrdNone);
-    next[u] = a[u].x;
   }
   // running best: lowered by one lane, and only if some lane of the wave has a lower cost
   // (rare after the first arcs)
@@ -501,7 +532,7 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
 template <int N>
 __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, unsigned f0, unsigned M, float beam, bool boosted) {
   const int lane = threadIdx.x & 63;
-  int ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N];
+  int ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N]; int tb[N];
 #pragma unroll
   for (int u = 0; u < N; ++u) {                // arc fetch, N in flight
     const unsigned f = f0 + u * 64 + lane;
@@ -511,25 +542,26 @@ __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, u
     arc[u] = wl.abase[j] + (int)fs;
     src[u] = base + j;
     tc[u] = wl.tcost[j];
+    tb[u] = boosted ? wl.tb[j] : 0;
     a[u] = x.g.unit[arc[u]];
   }
-  emit_arcs<N>(x, ok, a, tc, src, arc, beam, boosted);
+  emit_arcs<N>(x, ok, a, tc, src, arc, tb, beam, boosted);
 }
 
 // Arcs [f0, f0 + 64N) of one listed high-degree state (all lanes of the wave call it).
 template <int N>
 __device__ __forceinline__ void hub_arcs(Ctx &x, int first, int deg, float cost, int tok, int f0, float beam, bool boosted) {
   const int lane = threadIdx.x & 63;
-  int ok[N], src[N], arc[N]; int4 a[N]; float tc[N];
+  int ok[N], src[N], arc[N], tb[N]; int4 a[N]; float tc[N];
 #pragma unroll
   for (int u = 0; u < N; ++u) {
     const int f = f0 + u * 64 + lane;
     ok[u] = f < deg;
     arc[u] = first + (ok[u] ? f : deg - 1);      // lanes past the end repeat the last arc (no branch)
-    src[u] = tok; tc[u] = cost;
+    src[u] = tok & 0xffff; tb[u] = (int)((unsigned)tok >> 16); tc[u] = cost;
     a[u] = x.g.unit[arc[u]];
   }
-  emit_arcs<N>(x, ok, a, tc, src, arc, beam, boosted);
+  emit_arcs<N>(x, ok, a, tc, src, arc, tb, beam, boosted);
 }
 
 // Next run of kWaveTok tokens for this wave (a block-wide counter in LDS; wave-uniform).
@@ -562,34 +594,38 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   const int R = (n_tok + kWaveTok - 1) / kWaveTok;
   int r = wave, rn = next_run(sm);
   const int4 kNoHead = make_int4(0, 0, 0, 1);          // no arcs; ilabel 1 keeps the acoustic lookup in range
+  const unsigned bm = x.g.blk_mask; const int bbits = x.g.blk_bits;   // a token's key: (state in B << bbits) | block
   int2 tk = make_int2(0, 0), tkn = make_int2(0, 0); int4 hd = kNoHead;
   if (r * kWaveTok + lane < n_tok) tk = Q[r * kWaveTok + lane];
   if (rn < R && rn * kWaveTok + lane < n_tok) tkn = Q[rn * kWaveTok + lane];
-  if (r * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, tk.x);
+  if (r * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, (int)((unsigned)tk.x & bm));
   unsigned long long n_arcs = 0;                       // wave-uniform: emitting arcs this wave expanded
   while (r < R) {
     const int base = r * kWaveTok;
     unsigned deg; int first;
     {
-      int has[1], src[1], arc[1]; float tc[1]; int4 a0[1];
+      int has[1], src[1], arc[1], tb[1]; float tc[1]; int4 a0[1];
+      const int blk = (int)((unsigned)tk.x & bm);
+      tb[0] = (int)((unsigned)tk.x >> bbits);           // 0 without a boosting acceptor
       int ne = (int)((unsigned)hd.x & kPackE); const int nx = (int)((unsigned)hd.x >> kPackXShift);
-      if (ne == (int)kPackE) ne = x.g.unit[2 * (size_t)(unsigned)tk.x].z;       // a very large state: exact degree
+      if (ne == (int)kPackE) ne = x.g.unit[2 * (size_t)(unsigned)blk].z;        // a very large state: exact degree
       has[0] = (int)(ne > 0) & (int)(nx == 0);          // the unit after the header is an emitting arc
       deg = (unsigned)(ne - has[0]);
-      first = 2 * tk.x + 1 + nx + has[0];               // unit address of the first arc left
-      tc[0] = __int_as_float(tk.y); src[0] = base + lane; arc[0] = 2 * tk.x + 1;
+      first = 2 * blk + 1 + nx + has[0];                // unit address of the first arc left
+      tc[0] = __int_as_float(tk.y); src[0] = base + lane; arc[0] = 2 * blk + 1;
       a0[0] = make_int4(hd.y, hd.z, has[0] ? hd.w : 1, 0);
-      if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)tk.x + 1].w;   // the first arc's olabel
+      if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)blk + 1].w;    // the first arc's olabel
       n_arcs += (unsigned)__popcll(__ballot(has[0]));
       if (deg > (unsigned)kHubDeg) {                    // to the shared list, if it has room
         const int h = atomicAdd(&sm.n_hub, 1);
         if (h < kHubCap) {
-          hb.first[h] = first; hb.deg[h] = (int)deg; hb.tcost[h] = tc[0]; hb.ttok[h] = src[0];
+          hb.first[h] = first; hb.deg[h] = (int)deg; hb.tcost[h] = tc[0]; hb.ttok[h] = src[0] | (tb[0] << 16);
           __hip_atomic_store(&hb.ready[h], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
           deg = 0;
         }
       }
-      emit_arcs<1>(x, has, a0, tc, src, arc, beam, boosted);
+      emit_arcs<1>(x, has, a0, tc, src, arc, tb, beam, boosted);
+      if (boosted) wl.tb[lane] = tb[0];
     }
     // exclusive prefix sums of the run's arc counts (item j = lane)
     const unsigned inc = wave_scan_add(deg);
@@ -605,7 +641,7 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
     const int rnn = next_run(sm);
     tk = tkn;
     hd = kNoHead;
-    if (rn < R && rn * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, tk.x);
+    if (rn < R && rn * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, (int)((unsigned)tk.x & bm));
     tkn = make_int2(0, 0);
     if (rnn < R && rnn * kWaveTok + lane < n_tok) tkn = Q[rnn * kWaveTok + lane];
     // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
@@ -656,7 +692,9 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
 // Lower the destination's table entry to this candidate if (cost, arc id) is smaller.
 // The value word carries the candidate's index, so the winner's record can be fetched
 // afterwards; exact cost ties are decided by the arc ids of the two records.
-__device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc, int idx) {
+// With a boosting acceptor two tokens of one graph state can take the same arc into the same
+// (graph state, B state) pair; then the lower B state of the source token wins (src = its index).
+__device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc, int src, int idx) {
   TableLds &t = x.sm.u.t;
   unsigned s = (hash_state(dst) >> 6) & kTabMask;
   // one compare-and-swap per probe: it returns the slot's key, or claims the slot if it was free
@@ -680,7 +718,9 @@ __device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc
       // exact tie: lower arc id.  The other record may have been written by another wave just
       // before it published the index (fused closure rounds): acquire pairs with its release
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-      better = (unsigned)arc < (unsigned)x.cand[(unsigned)cur].w;
+      const int4 other = x.cand[(unsigned)cur];
+      better = (unsigned)arc < (unsigned)other.w;
+      if (arc == other.w) better = (unsigned)x.srcq[src].x < (unsigned)x.srcq[other.z].x;   // same graph state: the keys order like the B states
     }
     if (!better) break;
     const unsigned long long prev = atomicCAS(&t.vals[s], cur, mine);
@@ -723,7 +763,7 @@ __device__ __forceinline__ void table_fill(Ctx &x, int r0, int r1, int g, int G,
       int take = (int)(G == 1) | (int)(group_of(key, G) == g);
       if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
       int slot = -1;
-      if (take) slot = table_insert(x, key, c, cd.w, base + i);
+      if (take) slot = table_insert(x, key, c, cd.w, cd.z, base + i);
       if (pos0 + i < kTabSlots) x.sm.occ[pos0 + i] = (unsigned short)slot;
     }
     pos0 += (n + kBlock - 1) / kBlock * kBlock;
@@ -868,6 +908,7 @@ __device__ __forceinline__ void make_tokens(Ctx &x, const int (&make)[N], const 
 // 4. the survivors become tokens.
 __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned lat_base, int4 *WLN, Cutoff &cut) {
   Smem &sm = x.sm;
+  x.srcq = x.q0 + x.s.cur * x.c.qcap;          // the candidates come out of the current token set
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
   const unsigned bo = uni(sm.best_ord);
@@ -1067,6 +1108,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
   const bool boosted = x.s.boost_n > 0;
+  x.srcq = NQ;                                 // the closure's candidates come out of the set under construction
   int n_wl = uni(min(sm.n_wl_next, x.c.qcap));
   __syncthreads();
   if (tid == 0) sm.n_wl_next = 0;
@@ -1083,7 +1125,8 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       unsigned deg[1], ex[1];
       int4 w = make_int4(0, 0, 0, 0);
       if (tid < n_items) w = WL[cb + tid];
-      deg[0] = tid < n_items ? (unsigned)x.g.unit[2 * (size_t)(unsigned)w.y].w >> kPackXShift : 0u;   // the state's header
+      const unsigned wblk = (unsigned)w.y & x.g.blk_mask;     // w.y is the token's key: (state in B, block)
+      deg[0] = tid < n_items ? (unsigned)x.g.unit[2 * (size_t)wblk].w >> kPackXShift : 0u;   // the state's header
       if (n_wl <= kBlock) table_clear(sm);         // while the loads are in flight
       {
         // epsilon arcs out of the set (a counter): every token is listed as new exactly once
@@ -1092,19 +1135,20 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       }
       const unsigned M = block_scan<1>(sm, deg, ex);
       ek.pre[tid] = ex[0];
-      ek.abase[tid] = 2 * w.y + 1 - (int)ex[0];
+      ek.abase[tid] = 2 * (int)wblk + 1 - (int)ex[0];
       ek.tcost[tid] = __int_as_float(w.z);         // the token's cost when it was listed
-      ek.ttok[tid] = w.x;
+      ek.ttok[tid] = w.x | (int)(((unsigned)w.y >> x.g.blk_bits) << 16);
       if (tid == kBlock - 1) ek.pre[kBlock] = M;
       fused = n_wl <= kBlock && M <= (unsigned)min(kGroupTarget, x.c.region_cap);
       __syncthreads();
       for (unsigned f0 = 0; f0 < M; f0 += kBlock * kU) {
-        int ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU];
+        int ok[kU]; int src[kU]; int4 a[kU]; int arc[kU]; float tc[kU]; int j[kU]; int tb[kU];
         owners_of<kU>(ek.pre, n_items, f0, M, ok, j);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           arc[u] = ek.abase[j[u]] + (int)(f0 + u * kBlock + tid);
-          src[u] = ek.ttok[j[u]];
+          src[u] = ek.ttok[j[u]] & 0xffff;
+          tb[u] = (int)((unsigned)ek.ttok[j[u]] >> 16);
           tc[u] = ek.tcost[j[u]];
           a[u] = make_int4(0, 0, 0, 0);
           if (ok[u]) a[u] = x.g.unit[arc[u]];
@@ -1113,9 +1157,13 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
           nc[u] = canon(tc[u] + __int_as_float(a[u].y));
-          if (boosted && ok[u] && a[u].w != 0) nc[u] = canon(nc[u] + boost_of(sm, a[u].w));   // epsilon arcs can carry output labels too
-          ok[u] &= (int)(nc[u] < INFINITY) & (int)cut.keep(nc[u]);
           next[u] = a[u].x; arc[u] |= (int)kArcEps;
+          if (boosted) {                           // epsilon arcs can carry output labels too
+            int nb = tb[u];
+            if (ok[u] && a[u].w != 0) nc[u] = canon(nc[u] + boost_step(sm, tb[u], a[u].w, nb));
+            next[u] |= nb << x.g.blk_bits;
+          }
+          ok[u] &= (int)(nc[u] < INFINITY) & (int)cut.keep(nc[u]);
         }
         if (fused) {
           // all into region 0 (at most kGroupTarget <= region_cap records), and into the table
@@ -1129,7 +1177,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
           __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
 #pragma unroll
           for (int u = 0; u < kU; ++u)
-            if (ok[u]) sm.occ[ci[u]] = (unsigned short)table_insert(x, key_of(next[u]), nc[u], arc[u], ci[u]);
+            if (ok[u]) sm.occ[ci[u]] = (unsigned short)table_insert(x, key_of(next[u]), nc[u], arc[u], src[u], ci[u]);
         } else {
           push_cands<kU>(x, ok, next, nc, src, arc);
         }
@@ -1196,7 +1244,11 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
               t.vals[sl] = kValEmpty;                      // this destination has its token
               const float nc = ord2f((unsigned)(v >> 32)), oc = __int_as_float(tk[k].y);
               bool better = (nc < oc) & (v != kValEmpty);
-              if (nc == oc && v != kValEmpty) better = (unsigned)x.cand[(unsigned)v].w < (unsigned)x.lat[lat_base + tok].y;
+              if (nc == oc && v != kValEmpty) {              // exact tie: lower arc id, then lower B state of the source
+                const int4 cd = x.cand[(unsigned)v]; const int2 bp = x.lat[lat_base + tok];
+                better = (unsigned)cd.w < (unsigned)bp.y;
+                if (cd.w == bp.y) better = (unsigned)NQ[cd.z].x < (unsigned)NQ[bp.x].x;
+              }
               if (better) {
                 const int at = atomicAdd(&sm.n_pairs, 1);
                 if (at < kPairs) pairs[at] = make_int2(tok, (int)(unsigned)v);
@@ -1296,8 +1348,9 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
     unsigned long long s = 0;
     for (int i = tid; i < n; i += kBlock) {
       const int2 sc = NQ[i];
-      const int state = x.g.unit[2 * (size_t)(unsigned)sc.x].x;     // the header names the state
-      s += mix64(((unsigned long long)(unsigned)state << 32) | (unsigned)sc.y);
+      const int state = x.g.unit[2 * (size_t)((unsigned)sc.x & x.g.blk_mask)].x;     // the header names the state
+      const unsigned b = (unsigned)sc.x >> x.g.blk_bits;           // the token's state in the boosting acceptor
+      s += mix64((((unsigned long long)(unsigned)state << 32) | (unsigned)sc.y) ^ ((unsigned long long)b * 0x9E3779B97F4A7C15ull));
     }
     if (s) atomicAdd(&sm.red64, s);
   }
@@ -1343,15 +1396,19 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   }
   if (tid == 0) { sm.red64 = ~0ull; sm.red64b = ~0ull; sm.sel_idx = -1; }
   __syncthreads();
+  // ties go to the lower graph state, then to the lower state of the boosting acceptor: the key
+  // (B state, block) is turned round for the comparison
+  const int bbits = x.g.blk_bits, sbits = 29 - x.g.blk_bits; const unsigned bm = x.g.blk_mask;
   unsigned long long mf = ~0ull, mr = ~0ull;
   for (int i = tid; i < n; i += kBlock) {
     const int2 t = Q[i];
     const float c = __int_as_float(t.y);
-    mr = min(mr, ((unsigned long long)f2ord(c) << 32) | (unsigned)t.x);
+    const unsigned blk = (unsigned)t.x & bm, turned = (blk << sbits) | ((unsigned)t.x >> bbits);
+    mr = min(mr, ((unsigned long long)f2ord(c) << 32) | turned);
     if (a.finalize) {
-      const float fc = x.g.has_final ? __int_as_float(x.g.unit[2 * (size_t)(unsigned)t.x].y) : 0.0f;
+      const float fc = x.g.has_final ? __int_as_float(x.g.unit[2 * (size_t)blk].y) : 0.0f;
       const float f = c + fc;
-      if (f < INFINITY) mf = min(mf, ((unsigned long long)f2ord(f) << 32) | (unsigned)t.x);
+      if (f < INFINITY) mf = min(mf, ((unsigned long long)f2ord(f) << 32) | turned);
     }
   }
   if (mf != ~0ull) atomicMin(&sm.red64, mf);
@@ -1359,9 +1416,10 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   __syncthreads();
   const bool any_final = sm.red64 != ~0ull;
   const unsigned long long best = any_final ? sm.red64 : sm.red64b;
-  const int best_state = (int)(unsigned)(best & 0xffffffffull);
+  const unsigned best_turned = (unsigned)(best & 0xffffffffull);
+  const int best_key = (int)((best_turned >> sbits) | ((best_turned & ((1u << sbits) - 1u)) << bbits));
   for (int i = tid; i < n; i += kBlock)
-    if (Q[i].x == best_state) sm.sel_idx = i;
+    if (Q[i].x == best_key) sm.sel_idx = i;
   __syncthreads();
   // One lane follows the backpointers.  The words come out last to first: they go into a ring
   // in LDS (the recombination table is idle now) that keeps the latest max_words of them, i.e.
@@ -1455,11 +1513,12 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
   x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio); x.s.offset = uni(x.s.offset);
-  x.s.boost_n = uni(x.s.boost_n);
+  x.s.boost_n = uni(x.s.boost_n); x.s.boost_states = uni(x.s.boost_states);
   if (x.s.boost_n > 0)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
       sm.bk[i] = c.boost_keys[(size_t)ch * kBoostSlots + i];
       sm.bv[i] = c.boost_vals[(size_t)ch * kBoostSlots + i];
+      sm.bft[i] = c.boost_from_to[(size_t)ch * kBoostSlots + i];
     }
 
   if (tid == 0) {
@@ -1538,7 +1597,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     // copies, so that the pointers of the frame loop above never live in memory: only then
     // does the compiler know they are global and keep them in registers.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
-    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s};
+    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s, nullptr};
     if (tid == 0) sm.path_frames = x.s.path_frames;
     select_and_trace(x2, a2, io);
     if (tid == 0) x.s.path_frames = sm.path_frames;      // thread 0's copy is the one that is stored
@@ -1806,7 +1865,7 @@ struct wfst_decoder {
   // device staging for host-side outputs
   int *o_words = nullptr, *o_nwords = nullptr, *o_flags = nullptr; float *o_cost = nullptr;
   // word-boost tables: pinned host staging per channel (keys, values, count) + what is on the device
-  int *h_boost = nullptr;            // [channels][2 * kBoostSlots + 1]
+  int *h_boost = nullptr;            // [channels][kBoostStage]: labels, scores, from | to << 16, {arcs, states}
   std::vector<int> boost_on_dev;     // entries of the table each channel currently has on the device
   std::vector<hipEvent_t> boost_ev;  // per channel: recorded after the copies out of its staging area
   std::vector<unsigned> blk_of_state;  // [S + 1] block number of every state (and the block count)
@@ -1927,7 +1986,9 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
   int rc;
   if ((rc = dev_alloc(d, &d_unit, unit.size()))) return rc;
   HIP_TRY(d, hipMemcpy(d_unit, unit.data(), unit.size() * sizeof(int4), hipMemcpyHostToDevice));
-  d->g = DevGraph{d_unit, blk[S], named(g->start_state), all_zero ? 0 : 1, S};
+  int blk_bits = 1;
+  while (blk_bits < 29 && (1u << blk_bits) < blk[S]) ++blk_bits;
+  d->g = DevGraph{d_unit, blk[S], named(g->start_state), all_zero ? 0 : 1, S, blk_bits, (1u << blk_bits) - 1u};
   return WFST_OK;
 }
 
@@ -1974,9 +2035,11 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipMemset(c.frame_off, 0, N * (size_t)(c.max_frames + 2) * sizeof(unsigned)));
   if ((rc = dev_alloc(d, &c.boost_keys, N * kBoostSlots))) return rc;
   if ((rc = dev_alloc(d, &c.boost_vals, N * kBoostSlots))) return rc;
+  if ((rc = dev_alloc(d, &c.boost_from_to, N * kBoostSlots))) return rc;
   HIP_TRY(d, hipMemset(c.boost_keys, 0, N * kBoostSlots * sizeof(int)));
   HIP_TRY(d, hipMemset(c.boost_vals, 0, N * kBoostSlots * sizeof(float)));
-  HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_boost), N * (2 * kBoostSlots + 1) * sizeof(int)));
+  HIP_TRY(d, hipMemset(c.boost_from_to, 0, N * kBoostSlots * sizeof(unsigned)));
+  HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_boost), N * kBoostStage * sizeof(int)));
   d->boost_on_dev.assign(N, 0);
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
   if ((rc = dev_alloc(d, &d->d_lat_ctr, (size_t)2))) return rc;
@@ -2018,44 +2081,68 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
 
 bool valid_prune(float beam, int max_active) { return beam >= 0.0f && max_active >= 1; }
 
-// Give channel `ch` the word-boost table `t` (nullptr or n == 0: none) before its next init.
-// The table becomes an open-addressing hash (key 0 = free) in the channel's slot; the copies
-// are ordered on `st` before the init kernel.
-int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st) {
-  const int n = t ? t->n : 0;
+// Give channel `ch` a boosting acceptor before its next init: n arcs (from state, output label, to
+// state, score) over n_states states, root 0; from / to may be nullptr for the one-state acceptor
+// (the paper's table word -> score).  n == 0: none.  The arcs become an open-addressing hash by
+// label (key 0 = free) in the channel's slot; the copies are ordered on `st` before the init kernel.
+int set_boost(wfst_decoder *d, int ch, int n_states, int n, const int32_t *from, const int32_t *label,
+              const int32_t *to, const float *score, hipStream_t st) {
   if (n == 0 && d->boost_on_dev[ch] == 0) return WFST_OK;
-  if (n < 0 || n > kBoostMax) return fail(d, WFST_ERR_INVALID_ARG, "boost table with more than " + std::to_string(kBoostMax) + " entries");
-  if (n > 0 && (!t->word_ids || !t->scores)) return fail(d, WFST_ERR_INVALID_ARG, "null boost table arrays");
-  int *h = d->h_boost + (size_t)ch * (2 * kBoostSlots + 1);
-  int *keys = h; float *vals = reinterpret_cast<float *>(h + kBoostSlots); int *cnt = h + 2 * kBoostSlots;
+  if (n < 0 || n > kBoostMax) return fail(d, WFST_ERR_INVALID_ARG, "boosting acceptor with more than " + std::to_string(kBoostMax) + " arcs");
+  if (n > 0 && (!label || !score)) return fail(d, WFST_ERR_INVALID_ARG, "null boost arrays");
+  if (n > 0 && n_states > 1) {
+    if (!from || !to) return fail(d, WFST_ERR_INVALID_ARG, "null boost arrays");
+    // a token's key holds (state of the acceptor, graph state) in 29 bits
+    const int room = std::min(kBoostStateBits, 29 - d->g.blk_bits);
+    if (n_states > (1 << room))
+      return fail(d, WFST_ERR_INVALID_ARG, "boosting acceptor with " + std::to_string(n_states) + " states: a graph of " +
+                                               std::to_string(d->g.n_blk) + " blocks leaves room for " + std::to_string(1 << room));
+  }
+  if (n > 0 && n_states < 1) return fail(d, WFST_ERR_INVALID_ARG, "a boosting acceptor needs at least its root state");
+  int *h = d->h_boost + (size_t)ch * kBoostStage;
+  int *keys = h; float *vals = reinterpret_cast<float *>(h + kBoostSlots);
+  unsigned *ft = reinterpret_cast<unsigned *>(h + 2 * kBoostSlots); int *cnt = h + 3 * kBoostSlots;
   // the channel's staging area is pinned memory that earlier asynchronous copies may still be
   // reading (a boosted call returns before its copies have run): wait for them before rewriting it
   if (d->boost_ev.empty()) d->boost_ev.assign((size_t)d->opts.max_channels, nullptr);
   if (d->boost_ev[ch]) HIP_TRY(d, hipEventSynchronize(d->boost_ev[ch]));
   else HIP_TRY(d, hipEventCreateWithFlags(&d->boost_ev[ch], hipEventDisableTiming));
-  std::memset(h, 0, (2 * kBoostSlots + 1) * sizeof(int));
+  std::memset(h, 0, kBoostStage * sizeof(int));
   for (int i = 0; i < n; ++i) {
-    const int w = t->word_ids[i];
-    if (w <= 0) return fail(d, WFST_ERR_INVALID_ARG, "boost word ids must be positive output labels");
-    if (!std::isfinite(t->scores[i])) return fail(d, WFST_ERR_INVALID_ARG, "non-finite boost score");
+    const int w = label[i];
+    const int f = n_states > 1 ? from[i] : 0, t = n_states > 1 ? to[i] : 0;
+    if (w <= 0) return fail(d, WFST_ERR_INVALID_ARG, "boost labels must be positive output labels");
+    if (!std::isfinite(score[i])) return fail(d, WFST_ERR_INVALID_ARG, "non-finite boost score");
+    if (f < 0 || f >= n_states || t < 0 || t >= n_states) return fail(d, WFST_ERR_INVALID_ARG, "boosting acceptor: state out of range");
     unsigned s = boost_slot(w);
     while (keys[s] != 0) {
-      if (keys[s] == w) return fail(d, WFST_ERR_INVALID_ARG, "word id " + std::to_string(w) + " appears twice in the boost table");
+      if (keys[s] == w && (int)(ft[s] & 0xffffu) == f)
+        return fail(d, WFST_ERR_INVALID_ARG, n_states > 1 ? "boosting acceptor: two arcs with label " + std::to_string(w) + " out of one state"
+                                                          : "word id " + std::to_string(w) + " appears twice in the boost table");
       s = (s + 1) & (kBoostSlots - 1);
     }
-    keys[s] = w; vals[s] = t->scores[i];
+    keys[s] = w; vals[s] = score[i]; ft[s] = (unsigned)f | ((unsigned)t << 16);
   }
-  *cnt = n;
+  cnt[0] = n; cnt[1] = n > 0 ? n_states : 0;
   if (n > 0) {
     HIP_TRY(d, hipMemcpyAsync(d->c.boost_keys + (size_t)ch * kBoostSlots, keys, kBoostSlots * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(d, hipMemcpyAsync(d->c.boost_vals + (size_t)ch * kBoostSlots, vals, kBoostSlots * sizeof(float), hipMemcpyHostToDevice, st));
+    HIP_TRY(d, hipMemcpyAsync(d->c.boost_from_to + (size_t)ch * kBoostSlots, ft, kBoostSlots * sizeof(unsigned), hipMemcpyHostToDevice, st));
   }
-  HIP_TRY(d, hipMemcpyAsync(&d->c.st[ch].boost_n, cnt, sizeof(int), hipMemcpyHostToDevice, st));
+  static_assert(offsetof(ChanState, boost_states) == offsetof(ChanState, boost_n) + sizeof(int), "the two are copied together");
+  HIP_TRY(d, hipMemcpyAsync(&d->c.st[ch].boost_n, cnt, 2 * sizeof(int), hipMemcpyHostToDevice, st));
   HIP_TRY(d, hipEventRecord(d->boost_ev[ch], st));
   d->boost_on_dev[ch] = n;
   return WFST_OK;
 }
-
+int set_boost(wfst_decoder *d, int ch, const wfst_boost_table *t, hipStream_t st) {
+  return t ? set_boost(d, ch, 1, t->n, nullptr, t->word_ids, nullptr, t->scores, st)
+           : set_boost(d, ch, 1, 0, nullptr, nullptr, nullptr, nullptr, st);
+}
+int set_boost(wfst_decoder *d, int ch, const wfst_boost_fst *f, hipStream_t st) {
+  return f ? set_boost(d, ch, f->n_states, f->n_arcs, f->arc_from, f->arc_label, f->arc_to, f->arc_score, st)
+           : set_boost(d, ch, 1, 0, nullptr, nullptr, nullptr, nullptr, st);
+}
 
 // ---- scratch of the entry point that allocates nothing
 // Device memory for the lattice kernels' counters and per-set link counts that belongs to the
@@ -2105,6 +2192,9 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
   HIP_TRY(d, hipStreamSynchronize(st));
   if (s.status & (kStLattice | kStCapacity))
     return fail(d, WFST_ERR_CAPACITY, "the channel stopped on an overflow: its token sets are incomplete");
+  if (s.boost_n > 0 && s.boost_states > 1)
+    return fail(d, WFST_ERR_INVALID_ARG, "lattices are defined over graph states: not available for a channel decoded "
+                                         "with a boosting acceptor of several states");
   const int f = s.frame;
   if (f < 0 || f > frames_cap)
     return fail(d, WFST_ERR_CAPACITY, "the channel has " + std::to_string(f) + " frames; this call takes at most " +
@@ -2145,6 +2235,13 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
 }
 
 }  // namespace
+
+namespace {
+int decode_batch_impl(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+                      int32_t T, int32_t V, float beam, int32_t max_active,
+                      const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream,
+                      int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
+}
 
 extern "C" {
 
@@ -2203,6 +2300,38 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *d, const float *loglikes, const 
                                   int32_t T, int32_t V, float beam, int32_t max_active,
                                   const wfst_boost_table *const *boosts, void *stream,
                                   int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
+  return decode_batch_impl(d, loglikes, lengths, B, T, V, beam, max_active, boosts, nullptr, stream, words, nwords,
+                           cost, flags);
+}
+
+int32_t wfst_decode_batch_boost_fst(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+                                    int32_t T, int32_t V, float beam, int32_t max_active,
+                                    const wfst_boost_fst *const *fsts, void *stream,
+                                    int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
+  return decode_batch_impl(d, loglikes, lengths, B, T, V, beam, max_active, nullptr, fsts, stream, words, nwords,
+                           cost, flags);
+}
+
+int32_t wfst_init_channel_boost_fst(wfst_decoder *d, int32_t ch, float beam, int32_t max_active,
+                                    const wfst_boost_fst *fst, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+  if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
+  const int rcb = set_boost(d, ch, fst, static_cast<hipStream_t>(stream));
+  if (rcb) return rcb;
+  LaunchArgs a{};
+  a.V = d->V; a.mode = kModeInit;
+  a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
+  return launch(d, {ch}, {0}, {0}, a, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"
+
+namespace {
+int decode_batch_impl(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+                      int32_t T, int32_t V, float beam, int32_t max_active,
+                      const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream,
+                      int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
   if (!d) return WFST_ERR_INVALID_ARG;
   if (B < 0 || T < 0) return fail(d, WFST_ERR_INVALID_ARG, "negative B or T");
   if (B == 0) return WFST_OK;              // nothing to decode; pointers may be null
@@ -2216,7 +2345,7 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *d, const float *loglikes, const 
       return fail(d, WFST_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, min(T, max_frames_per_channel)]");
   hipStream_t st = static_cast<hipStream_t>(stream);
   for (int b = 0; b < B; ++b) {
-    const int rcb = set_boost(d, b, boosts ? boosts[b] : nullptr, st);
+    const int rcb = fsts ? set_boost(d, b, fsts[b], st) : set_boost(d, b, boosts ? boosts[b] : nullptr, st);
     if (rcb) return rcb;
   }
   // longest utterances first: workgroups are dispatched in order, so the long ones start
@@ -2249,6 +2378,10 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *d, const float *loglikes, const 
   }
   return WFST_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int32_t wfst_init_channel(wfst_decoder *d, int32_t ch, float beam, int32_t max_active,
                           const wfst_boost_table *boost, void *stream) {
@@ -2418,6 +2551,11 @@ int32_t wfst_get_lattice_noalloc(wfst_decoder *d, int32_t ch, const void *loglik
 }
 
 int32_t wfst_debug_get_tokens(wfst_decoder *d, int32_t ch, int32_t *states, float *costs, int32_t cap, int32_t *n) {
+  return wfst_debug_get_token_pairs(d, ch, states, nullptr, costs, cap, n);
+}
+
+int32_t wfst_debug_get_token_pairs(wfst_decoder *d, int32_t ch, int32_t *states, int32_t *bstates, float *costs,
+                                   int32_t cap, int32_t *n) {
   if (!d) return WFST_ERR_INVALID_ARG;
   if (ch < 0 || ch >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
   if (!states || !costs || !n || cap < 0) return fail(d, WFST_ERR_INVALID_ARG, "null output");
@@ -2433,7 +2571,11 @@ int32_t wfst_debug_get_tokens(wfst_decoder *d, int32_t ch, int32_t *states, floa
     d->state_of_blk.assign((size_t)d->g.n_blk + 1, -1);
     for (int32_t st = 0; st < d->g.S; ++st) d->state_of_blk[d->blk_of_state[st]] = st;
   }
-  for (int i = 0; i < m; ++i) { states[i] = d->state_of_blk[(unsigned)q[i].x]; std::memcpy(&costs[i], &q[i].y, 4); }
+  for (int i = 0; i < m; ++i) {
+    states[i] = d->state_of_blk[(unsigned)q[i].x & d->g.blk_mask];
+    if (bstates) bstates[i] = (int)((unsigned)q[i].x >> d->g.blk_bits);
+    std::memcpy(&costs[i], &q[i].y, 4);
+  }
   return WFST_OK;
 }
 

@@ -23,32 +23,34 @@ def torch_cuda():
     return torch
 
 
-def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, threads=16, boosts=None, **kw):
+def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, threads=16, boosts=None,
+                 boost_fsts=None, **kw):
     from oracle import Oracle
     o = Oracle(graph)
 
     def one(b):
         return o.decode(loglikes[b], length=int(lengths[b]), beam=beam, max_active=max_active,
-                        max_words=max_words, want_digests=True, boost=None if boosts is None else boosts[b], **kw)
+                        max_words=max_words, want_digests=True, boost=None if boosts is None else boosts[b],
+                        boost_fst=None if boost_fsts is None else boost_fsts[b], **kw)
     with ThreadPoolExecutor(threads) as ex:
         return list(ex.map(one, range(len(lengths))))
 
 
 def check_batch(torch, graph, loglikes, lengths, beam, max_active, max_words=256, refs=None,
                 max_active_hint=None, check_counters=True, boosts=None, device_loglikes=None, cost_offset=False,
-                **deckw):
+                boost_fsts=None, **deckw):
     from paper_2311_04996_amd import Decoder
     B, T, V = loglikes.shape
     dec = Decoder(graph, max_channels=max(B, 1), max_frames=max(T, 1), max_words=max_words,
                   max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True,
                   cost_offset=cost_offset, **deckw)
     ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda() if device_loglikes is None else device_loglikes
-    words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active, boosts=boosts)
+    words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active, boosts=boosts, boost_fsts=boost_fsts)
     torch.cuda.synchronize()
     words, nwords, cost, flags = words.cpu().numpy(), nwords.cpu().numpy(), cost.cpu().numpy(), flags.cpu().numpy()
     if refs is None:
         refs = oracle_batch(graph, loglikes, lengths, beam, max_active, max_words, boosts=boosts,
-                            cost_offset=cost_offset)
+                            cost_offset=cost_offset, boost_fsts=boost_fsts)
     near_ties = 0
     for b, r in enumerate(refs):
         cnt, dig = dec.debug_frame_digests(b)
@@ -610,6 +612,117 @@ def test_c5_boosted_medium_batch_matches_oracle(torch_cuda):
     refs = check_batch(torch_cuda, w.graph, w.loglikes, w.lengths, w.beam, w.max_active, boosts=w.boosts)
     plain = oracle_batch(w.graph, w.loglikes[:4], w.lengths[:4], w.beam, w.max_active)
     assert any(r.cost != p.cost for r, p in zip(refs, plain)), "the tables must matter"
+
+
+# ------------------------------------------------------------------------------- boosting acceptors with several states
+def _dyadic_fst(rng, n_targets, vocab, max_len=3):
+    from workloads import boost_trie, random_targets
+    fst = boost_trie(random_targets(rng, n_targets, vocab, 1, max_len), -1.0)
+    fst.arc_score[:] = -(rng.integers(1, 9, size=fst.num_arcs).astype(np.float32) / 4.0)
+    return fst
+
+
+def test_boost_fst_on_micro_graphs(torch_cuda):
+    """Phrase targets over a vocabulary of 5 words: long matches, mismatches that fall back to the
+    root, output labels on epsilon arcs, exact ties; hypotheses are (graph state, B state) pairs."""
+    from workloads import micro_graph
+    for seed in range(25):
+        rng = np.random.default_rng(5000 + seed)
+        V, T, B = 3, 9, 4
+        g = micro_graph(1300 + seed, num_states=int(rng.integers(4, 40)), num_classes=V, max_deg=5, p_eps=0.4)
+        ll = -(rng.integers(0, 40, size=(B, T, V)).astype(np.float32) / 8.0)
+        lengths = rng.integers(0, T + 1, size=B).astype(np.int32)
+        fsts = [_dyadic_fst(rng, int(rng.integers(1, 7)), np.arange(1, 6)) for _ in range(B)]
+        fsts[1] = None
+        for beam, ma in ((INF, IMAX), (3.0, 6), (1.0, 2)):
+            check_batch(torch_cuda, g, ll, lengths, beam, ma, max_active_hint=1000, boost_fsts=fsts)
+
+
+def test_boost_fst_token_pairs_of_every_frame(torch_cuda, c1):
+    """The lexicon graph of config 1 with phrases of words that follow each other in it; streamed a
+    frame at a time, every token set dumped as (graph state, B state, cost bits)."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    from workloads import boost_trie
+    torch = torch_cuda
+    g = c1.graph
+    rng = np.random.default_rng(17)
+    # word pairs and triples along arcs of the graph: a word's first arc leaves a state that another word's arcs enter
+    words = np.unique(g.olabel[g.olabel > 0])
+    targets = [rng.choice(words, size=int(rng.integers(1, 4))).tolist() for _ in range(60)]
+    fst = boost_trie(targets, -3.0)
+    assert fst.num_states > 10
+    ref = Oracle(g).decode(c1.loglikes[0], beam=c1.beam, max_active=c1.max_active, boost_fst=fst, want_frames=True)
+    assert any((b != 0).any() for b in ref.frames_b), "the workload must put tokens into inner states of B"
+    dec = Decoder(g, max_channels=1, max_frames=100, max_active_hint=c1.max_active)
+    ll = torch.from_numpy(c1.loglikes).cuda()
+    dec.init_channel(0, c1.beam, c1.max_active, boost_fst=fst)
+    for t in range(101):
+        st, bs, co = dec.debug_get_token_pairs(0)
+        got = sorted(zip(st.tolist(), bs.tolist(), co.view(np.uint32).tolist()))
+        want = sorted(zip(ref.frames[t][0].tolist(), ref.frames_b[t].tolist(), ref.frames[t][1].view(np.uint32).tolist()))
+        assert got == want, f"frame {t}"
+        if t < 100:
+            dec.advance_chunk([0], ll[:, t:t + 1, :].contiguous(), [1])
+    w, c, f = dec.get_partial(0, finalize=True)
+    assert w.tolist() == ref.words.tolist() and c == ref.cost and f == ref.flags
+    dec.close()
+
+
+def test_c5_boost_fst_medium_batch_matches_oracle(torch_cuda):
+    """Config 5 as worded: config 2, every utterance composed on the fly with its own acceptor of
+    100 targets of 1-4 output labels at -2.0 per matched label, failure arcs to the root."""
+    from workloads import make_config
+    w = make_config("c5_boost_fst")
+    assert all(f.num_states > 50 for f in w.boost_fsts)
+    refs = check_batch(torch_cuda, w.graph, w.loglikes, w.lengths, w.beam, w.max_active, boost_fsts=w.boost_fsts)
+    plain = oracle_batch(w.graph, w.loglikes[:4], w.lengths[:4], w.beam, w.max_active)
+    assert any((p.digest_sum != r.digest_sum).any() for p, r in zip(plain, refs))
+
+
+def test_boost_fst_with_frequent_long_matches(torch_cuda, c2):
+    """The config-2 graph with targets drawn from 40 hot words at -4.0: many hypotheses sit in inner
+    states of B, so one graph state often carries several tokens."""
+    from workloads import boost_fsts
+    n = 6
+    fsts = boost_fsts(9, n, int(c2.graph.meta["num_words"]), per_utt=100, max_len=4, score=-4.0, hot_words=40)
+    lengths = np.minimum(c2.lengths[:n], 200)
+    refs = check_batch(torch_cuda, c2.graph, c2.loglikes[:n, :200], lengths, c2.beam, c2.max_active, boost_fsts=fsts)
+    assert sum(len(r.words) for r in refs) > 0
+
+
+def test_boost_fst_streaming_equals_offline_and_errors(torch_cuda, c2):
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder, WfstError
+    from workloads import BoostFst, boost_fsts
+    torch = torch_cuda
+    fst = boost_fsts(9, 1, int(c2.graph.meta["num_words"]), per_utt=100, max_len=4, score=-4.0, hot_words=40)[0]
+    n = 90
+    r = Oracle(c2.graph).decode(c2.loglikes[3], length=n, beam=c2.beam, max_active=c2.max_active, boost_fst=fst,
+                                want_digests=True)
+    dec = Decoder(c2.graph, max_channels=2, max_frames=n, max_active_hint=c2.max_active, record_digests=True,
+                  keep_token_records=True)
+    ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[3:4, :n])).cuda()
+    dec.init_channel(1, c2.beam, c2.max_active, boost_fst=fst)
+    for t0 in range(0, n, 16):
+        k = min(16, n - t0)
+        dec.advance_chunk([1], ll[:, t0:t0 + k].contiguous(), [k])
+    w, c, f = dec.get_partial(1, finalize=True)
+    cnt, dig = dec.debug_frame_digests(1)
+    assert w.tolist() == r.words.tolist() and c == r.cost and f == r.flags
+    assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all()
+    with pytest.raises(WfstError) as e:                       # lattices are over graph states only
+        dec.get_lattice(1, ll[0], 2.0)
+    assert e.value.code == -1
+    many = BoostFst(5000, np.zeros(1, np.int32), np.ones(1, np.int32), np.zeros(1, np.int32), -np.ones(1, np.float32))
+    with pytest.raises(WfstError) as e:                       # more states than the keys have room for
+        dec.init_channel(0, 10.0, 100, boost_fst=many)
+    assert e.value.code == -1
+    twice = BoostFst(2, np.zeros(2, np.int32), np.array([7, 7], np.int32), np.array([1, 0], np.int32), -np.ones(2, np.float32))
+    with pytest.raises(WfstError) as e:                       # not deterministic
+        dec.init_channel(0, 10.0, 100, boost_fst=twice)
+    assert e.value.code == -1
+    dec.close()
 
 
 # ------------------------------------------------------------------------------- cost offsets
