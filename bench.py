@@ -273,7 +273,7 @@ def main():
         for i in range(nsteps):
             k = i % n_dec
             outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
-                                           boosts=w.boosts)
+                                           boosts=w.boosts, boost_fsts=w.boost_fsts)
             if record_ms:
                 ms.append(decs[k].last_kernel_ms())   # HIP events on the launch stream; waits for the kernel
         torch.cuda.synchronize()
@@ -282,7 +282,7 @@ def main():
     for k in range(len(decs)):                       # warmup: every decoder, every buffer touched
         for _ in range(max(1, args.warmup) if args.warmup else 0):
             outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
-                                           boosts=w.boosts)
+                                           boosts=w.boosts, boost_fsts=w.boost_fsts)
     torch.cuda.synchronize()
     for d in decs:
         d.get_counters(reset=True)

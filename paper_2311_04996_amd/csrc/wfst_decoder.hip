@@ -42,7 +42,7 @@
 // which orders arcs exactly as (emitting before epsilon, state, position) does.
 //
 // Per channel, in HBM:
-//   token queue   2 x qcap records {block number, cost}
+//   token queue   2 x qcap records {key (B state, block number) + flag bits of the state, cost}
 //   candidates    cand_cap records {next (block number + flags), cost, source token, arc id}
 //   winners       recombined in-beam tokens before the max-active cutoff is known
 //   worklists     2 x qcap records {token, block number, cost, first time}
@@ -62,6 +62,7 @@
 #include <mutex>
 #include <numeric>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "wfst_decoder.h"
@@ -125,6 +126,9 @@ constexpr int kModeInit = 1, kModeFinal = 2;
 constexpr unsigned kKeyMask = 0x1fffffffu;     // block number of a state (32-byte units)
 constexpr unsigned kFlagHasEps = 0x80000000u;  // `next` of an arc: the destination has epsilon arcs
 constexpr unsigned kFlagEpsIn = 0x40000000u;   //                   an epsilon arc enters the destination
+constexpr unsigned kFlagSimple = 0x20000000u;  //                   the destination's only arc is the graph's usual self-loop
+                                               // (DevGraph::simple_il, simple_w; no output label): a token there is
+                                               // expanded without reading the graph
 constexpr unsigned kArcEps = 0x40000000u;      // arc ids: unit address, plus this bit for epsilon arcs
 constexpr unsigned kArcMask = 0x3fffffffu;
 constexpr unsigned kPackE = 0xFFFFFu;          // header word 3: emitting degree (20 bits, all ones = see word 2)
@@ -161,6 +165,9 @@ struct DevGraph {
   // A token is keyed by (state of the boosting acceptor, graph state): key = (b << blk_bits) | block
   // number, in 29 bits; without an acceptor b = 0 and the key is the block number.
   int blk_bits; unsigned blk_mask;
+  // the self-loop that "simple" states have as their only arc (a CTC graph's blank self-loop):
+  // the most frequent (ilabel, weight) among states with exactly one arc that is a self-loop
+  int simple_il; float simple_w;
 };
 
 struct DevChannels {
@@ -204,6 +211,9 @@ struct WaveLds {              // ExpandArcs: the work items of one wave (one tok
   int abase[kWaveTok];
   float tcost[kWaveTok];
   int tb[kWaveTok];           // the token's state in the boosting acceptor (only written when there is one)
+  int ttok[kWaveTok];         // the token
+  int2 pend[2 * kWaveTok];    // ring: queue records of tokens whose state has to be read from the graph
+  int pend_tok[2 * kWaveTok]; //       and which tokens they are
 };
 struct HubLds {               // ExpandArcs: states with so many arcs that all waves share them
   int first[kHubCap];         // unit address of the first arc to expand
@@ -530,7 +540,7 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
 
 // One step of a wave's flattened loop: arcs f0 + u*64 + lane of its listed work items.
 template <int N>
-__device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, unsigned f0, unsigned M, float beam, bool boosted) {
+__device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, unsigned f0, unsigned M, float beam, bool boosted) {
   const int lane = threadIdx.x & 63;
   int ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N]; int tb[N];
 #pragma unroll
@@ -540,7 +550,7 @@ __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, int base, u
     const unsigned fs = ok[u] ? f : M - 1;       // lanes past the end repeat the last arc (no branch)
     const int j = wave_owner_of(wl.pre, fs);
     arc[u] = wl.abase[j] + (int)fs;
-    src[u] = base + j;
+    src[u] = wl.ttok[j];
     tc[u] = wl.tcost[j];
     tb[u] = boosted ? wl.tb[j] : 0;
     a[u] = x.g.unit[arc[u]];
@@ -571,6 +581,68 @@ __device__ __forceinline__ int next_run(Smem &sm) {
   return uni(r);
 }
 
+// The tokens of one wave's list whose state block has to be read: n <= 64 of them, starting at
+// `head` of the wave's ring.  A lane reads the 32 bytes at the start of its token's block
+// (header + first arc): the first arc is expanded right away by the lane that owns the token, the
+// remaining arcs of the batch are flattened over the 64 lanes (prefix sums in the wave's slice of
+// LDS, one short search per arc), and states with more than kHubDeg arcs are listed for all waves.
+// Returns the emitting arcs expanded (wave-uniform).  All 64 lanes call it.
+__device__ __forceinline__ unsigned dense_run(Ctx &x, WaveLds &wl, int head, int n, float beam, bool boosted) {
+  Smem &sm = x.sm;
+  HubLds &hb = sm.u.e.hub;
+  const int lane = threadIdx.x & 63;
+  const unsigned bm = x.g.blk_mask; const int bbits = x.g.blk_bits;
+  const bool valid = lane < n;
+  const int at = (head + lane) & (2 * kWaveTok - 1);
+  const int2 tk = valid ? wl.pend[at] : make_int2(0, 0);
+  const int tok = valid ? wl.pend_tok[at] : 0;
+  const int blk = (int)((unsigned)tk.x & bm);
+  int4 hd = make_int4(0, 0, 0, 1);                       // no arcs; ilabel 1 keeps the acoustic lookup in range
+  if (valid) hd = load_block_head(x.g.unit, blk);
+  unsigned n_arcs = 0, deg; int first;
+  {
+    int has[1], src[1], arc[1], tb[1]; float tc[1]; int4 a0[1];
+    tb[0] = (int)(((unsigned)tk.x & kKeyMask) >> bbits);  // 0 without a boosting acceptor
+    int ne = (int)((unsigned)hd.x & kPackE); const int nx = (int)((unsigned)hd.x >> kPackXShift);
+    if (ne == (int)kPackE) ne = x.g.unit[2 * (size_t)(unsigned)blk].z;        // a very large state: exact degree
+    has[0] = (int)(ne > 0) & (int)(nx == 0);            // the unit after the header is an emitting arc
+    deg = (unsigned)(ne - has[0]);
+    first = 2 * blk + 1 + nx + has[0];                  // unit address of the first arc left
+    tc[0] = __int_as_float(tk.y); src[0] = tok; arc[0] = 2 * blk + 1;
+    a0[0] = make_int4(hd.y, hd.z, has[0] ? hd.w : 1, 0);
+    if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)blk + 1].w;    // the first arc's olabel
+    n_arcs += (unsigned)__popcll(__ballot(has[0]));
+    if (deg > (unsigned)kHubDeg) {                      // to the shared list, if it has room
+      const int h = atomicAdd(&sm.n_hub, 1);
+      if (h < kHubCap) {
+        hb.first[h] = first; hb.deg[h] = (int)deg; hb.tcost[h] = tc[0]; hb.ttok[h] = src[0] | (tb[0] << 16);
+        __hip_atomic_store(&hb.ready[h], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        deg = 0;
+      }
+    }
+    emit_arcs<1>(x, has, a0, tc, src, arc, tb, beam, boosted);
+    if (boosted) wl.tb[lane] = tb[0];
+  }
+  // exclusive prefix sums of the batch's arc counts (item j = lane)
+  const unsigned inc = wave_scan_add(deg);
+  const unsigned M = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
+  wl.pre[lane] = inc - deg;
+  wl.abase[lane] = first - (int)(inc - deg);
+  wl.tcost[lane] = __int_as_float(tk.y);
+  wl.ttok[lane] = tok;
+  if (lane == 0) wl.pre[kWaveTok] = M;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  n_arcs += M;
+  // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
+  unsigned f0 = 0;
+  for (; f0 + 64 < M; f0 += 64 * kUE) wave_arcs<kUE>(x, wl, f0, M, beam, boosted);
+  if (f0 < M) wave_arcs<1>(x, wl, f0, M, beam, boosted);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  return n_arcs;
+}
+
 // On entry sm.next_run == kWaves, sm.done_waves == 0, sm.n_hub == 0 and the hub list's ready
 // and seg_next words are zero (the caller sets them before its barrier).
 __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
@@ -582,75 +654,62 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   const bool boosted = x.s.boost_n > 0;
   // Every wave expands runs of kWaveTok tokens at its own pace: it takes the next run from a
   // counter, so no wave waits for another until all tokens are done, and one wave's loads
-  // overlap another's arithmetic.  A lane reads the 32 bytes at the start of its token's
-  // state block (header + first arc).  Most states have one emitting arc and no epsilon
-  // arcs: that arc is expanded right away by the lane that owns the token.  The remaining
-  // arcs of the run are flattened over the 64 lanes (prefix sums in the wave's slice of LDS,
-  // one short search per arc).  States with more than kHubDeg arcs are listed instead; when
-  // a wave finds no run left it takes segments of listed states until those are done too.
-  // Loads run one run ahead (tokens two).
+  // overlap another's arithmetic.  Most tokens sit in "simple" states, whose only arc is the
+  // graph's usual self-loop (the queue record says so): their one candidate is made from the
+  // token alone, with no graph read at all.  The other tokens of the run go into the wave's
+  // list, and whenever 64 of them have come together the wave expands them as one dense batch
+  // (dense_run), so that the graph reads and their latency are paid once per 64 such tokens and
+  // not once per run.  States with more than kHubDeg arcs are listed instead; when a wave finds
+  // no run left it takes segments of listed states until those are done too.  Queue records are
+  // loaded two runs ahead.
   static_assert(kWaveTok == 64, "one token per lane");
   WaveLds &wl = e.w[wave];
   const int R = (n_tok + kWaveTok - 1) / kWaveTok;
   int r = wave, rn = next_run(sm);
-  const int4 kNoHead = make_int4(0, 0, 0, 1);          // no arcs; ilabel 1 keeps the acoustic lookup in range
   const unsigned bm = x.g.blk_mask; const int bbits = x.g.blk_bits;   // a token's key: (state in B << bbits) | block
-  int2 tk = make_int2(0, 0), tkn = make_int2(0, 0); int4 hd = kNoHead;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  int2 tk = make_int2(0, 0), tkn = make_int2(0, 0);
   if (r * kWaveTok + lane < n_tok) tk = Q[r * kWaveTok + lane];
   if (rn < R && rn * kWaveTok + lane < n_tok) tkn = Q[rn * kWaveTok + lane];
-  if (r * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, (int)((unsigned)tk.x & bm));
+  int pend_head = 0, pend_n = 0;                       // wave-uniform: the list is ring entries [head, head + n)
   unsigned long long n_arcs = 0;                       // wave-uniform: emitting arcs this wave expanded
   while (r < R) {
     const int base = r * kWaveTok;
-    unsigned deg; int first;
+    const bool valid = base + lane < n_tok;
     {
       int has[1], src[1], arc[1], tb[1]; float tc[1]; int4 a0[1];
-      const int blk = (int)((unsigned)tk.x & bm);
-      tb[0] = (int)((unsigned)tk.x >> bbits);           // 0 without a boosting acceptor
-      int ne = (int)((unsigned)hd.x & kPackE); const int nx = (int)((unsigned)hd.x >> kPackXShift);
-      if (ne == (int)kPackE) ne = x.g.unit[2 * (size_t)(unsigned)blk].z;        // a very large state: exact degree
-      has[0] = (int)(ne > 0) & (int)(nx == 0);          // the unit after the header is an emitting arc
-      deg = (unsigned)(ne - has[0]);
-      first = 2 * blk + 1 + nx + has[0];                // unit address of the first arc left
-      tc[0] = __int_as_float(tk.y); src[0] = base + lane; arc[0] = 2 * blk + 1;
-      a0[0] = make_int4(hd.y, hd.z, has[0] ? hd.w : 1, 0);
-      if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)blk + 1].w;    // the first arc's olabel
+      has[0] = (int)valid & (int)(((unsigned)tk.x & kFlagSimple) != 0);
+      tb[0] = (int)(((unsigned)tk.x & kKeyMask) >> bbits);
+      src[0] = base + lane; tc[0] = __int_as_float(tk.y);
+      arc[0] = 2 * (int)((unsigned)tk.x & bm) + 1;     // the unit after the header
+      a0[0] = make_int4(tk.x, __float_as_int(x.g.simple_w), x.g.simple_il, 0);   // the self-loop: same state, same flags
       n_arcs += (unsigned)__popcll(__ballot(has[0]));
-      if (deg > (unsigned)kHubDeg) {                    // to the shared list, if it has room
-        const int h = atomicAdd(&sm.n_hub, 1);
-        if (h < kHubCap) {
-          hb.first[h] = first; hb.deg[h] = (int)deg; hb.tcost[h] = tc[0]; hb.ttok[h] = src[0] | (tb[0] << 16);
-          __hip_atomic_store(&hb.ready[h], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-          deg = 0;
-        }
-      }
+      const bool other = valid && !has[0];             // (emit_arcs clears has[] of candidates it drops)
       emit_arcs<1>(x, has, a0, tc, src, arc, tb, beam, boosted);
-      if (boosted) wl.tb[lane] = tb[0];
+      const unsigned long long m = __ballot(other);
+      if (other) {
+        const int at = (pend_head + pend_n + __popcll(m & lt)) & (2 * kWaveTok - 1);
+        wl.pend[at] = tk; wl.pend_tok[at] = base + lane;
+      }
+      pend_n += __popcll(m);
     }
-    // exclusive prefix sums of the run's arc counts (item j = lane)
-    const unsigned inc = wave_scan_add(deg);
-    const unsigned M = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
-    wl.pre[lane] = inc - deg;
-    wl.abase[lane] = first - (int)(inc - deg);
-    wl.tcost[lane] = __int_as_float(tk.y);
-    if (lane == 0) wl.pre[kWaveTok] = M;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    n_arcs += M;
-    // the next run's header and the token of the run after it
+    // the queue records of the run after the next
     const int rnn = next_run(sm);
     tk = tkn;
-    hd = kNoHead;
-    if (rn < R && rn * kWaveTok + lane < n_tok) hd = load_block_head(x.g.unit, (int)((unsigned)tk.x & bm));
     tkn = make_int2(0, 0);
     if (rnn < R && rnn * kWaveTok + lane < n_tok) tkn = Q[rnn * kWaveTok + lane];
-    // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
-    unsigned f0 = 0;
-    for (; f0 + 64 < M; f0 += 64 * kUE) wave_arcs<kUE>(x, wl, base, f0, M, beam, boosted);
-    if (f0 < M) wave_arcs<1>(x, wl, base, f0, M, beam, boosted);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
     r = rn; rn = rnn;
+    if (pend_n >= kWaveTok) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      n_arcs += dense_run(x, wl, pend_head, kWaveTok, beam, boosted);
+      pend_head = (pend_head + kWaveTok) & (2 * kWaveTok - 1); pend_n -= kWaveTok;
+    }
+  }
+  if (pend_n > 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    n_arcs += dense_run(x, wl, pend_head, pend_n, beam, boosted);
   }
   // this wave lists no more states
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -880,7 +939,7 @@ __device__ __forceinline__ void make_tokens(Ctx &x, const int (&make)[N], const 
     const int key = key_of(next[u]);
     const bool has_eps = ((unsigned)next[u] & kFlagHasEps) != 0;
     if (make[u]) {
-      NQ[ti[u]] = make_int2(key, costbits[u]);
+      NQ[ti[u]] = make_int2(next[u], costbits[u]);     // the key and the state's flag bits
       x.lat[lat_base + ti[u]] = make_int2(prev[u], arc[u]);
     }
     want[u] = make[u] & (int)has_eps;
@@ -1233,13 +1292,14 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
           for (int k = 0; k < kM; ++k) {
             const int vi = i0 + k * kBlock + tid;
             const int tok = vi < n_in ? vi : vi + n_skip;
-            unsigned sl = (hash_state(tk[k].x) >> 6) & kTabMask;
+            const int tkey = key_of(tk[k].x);
+            unsigned sl = (hash_state(tkey) >> 6) & kTabMask;
             // (a token that did not fit the lattice arena was never written: the channel stops after
             // this frame, and its queue position must not be looked at)
             const bool real = vi < n_have && lat_base + (unsigned)tok < x.c.lat_cap;
             int probes = 0, key = real ? t.keys[sl] : kKeyEmpty;
-            while (key != tk[k].x && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
-            if (key == tk[k].x && real) {
+            while (key != tkey && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
+            if (key == tkey && real) {
               const unsigned long long v = t.vals[sl];
               t.vals[sl] = kValEmpty;                      // this destination has its token
               const float nc = ord2f((unsigned)(v >> 32)), oc = __int_as_float(tk[k].y);
@@ -1349,7 +1409,7 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
     for (int i = tid; i < n; i += kBlock) {
       const int2 sc = NQ[i];
       const int state = x.g.unit[2 * (size_t)((unsigned)sc.x & x.g.blk_mask)].x;     // the header names the state
-      const unsigned b = (unsigned)sc.x >> x.g.blk_bits;           // the token's state in the boosting acceptor
+      const unsigned b = ((unsigned)sc.x & kKeyMask) >> x.g.blk_bits;   // the token's state in the boosting acceptor
       s += mix64((((unsigned long long)(unsigned)state << 32) | (unsigned)sc.y) ^ ((unsigned long long)b * 0x9E3779B97F4A7C15ull));
     }
     if (s) atomicAdd(&sm.red64, s);
@@ -1357,7 +1417,7 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
   if (x.c.tokrec) {                              // lattice output wants the closed set's final records
     int2 *rec = x.c.tokrec + (x.lat - x.c.lattice);
     for (int i = tid; i < n; i += kBlock)
-      if (lat_base + (unsigned)i < x.c.lat_cap) rec[lat_base + i] = NQ[i];
+      if (lat_base + (unsigned)i < x.c.lat_cap) { const int2 q = NQ[i]; rec[lat_base + i] = make_int2(key_of(q.x), q.y); }
   }
   __syncthreads();
   if (tid == 0) {
@@ -1403,7 +1463,7 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   for (int i = tid; i < n; i += kBlock) {
     const int2 t = Q[i];
     const float c = __int_as_float(t.y);
-    const unsigned blk = (unsigned)t.x & bm, turned = (blk << sbits) | ((unsigned)t.x >> bbits);
+    const unsigned blk = (unsigned)t.x & bm, turned = (blk << sbits) | (((unsigned)t.x & kKeyMask) >> bbits);
     mr = min(mr, ((unsigned long long)f2ord(c) << 32) | turned);
     if (a.finalize) {
       const float fc = x.g.has_final ? __int_as_float(x.g.unit[2 * (size_t)blk].y) : 0.0f;
@@ -1419,7 +1479,7 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   const unsigned best_turned = (unsigned)(best & 0xffffffffull);
   const int best_key = (int)((best_turned >> sbits) | ((best_turned & ((1u << sbits) - 1u)) << bbits));
   for (int i = tid; i < n; i += kBlock)
-    if (Q[i].x == best_key) sm.sel_idx = i;
+    if (key_of(Q[i].x) == best_key) sm.sel_idx = i;
   __syncthreads();
   // One lane follows the backpointers.  The words come out last to first: they go into a ring
   // in LDS (the recombination table is idle now) that keeps the latest max_words of them, i.e.
@@ -1961,7 +2021,28 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
       if (g->ilabel[i] == 0) { eps_in[g->next_state[i]] = 1; has_eps[s] = 1; }
   }
   blk[S] = (unsigned)(units / 2);
-  auto named = [&](int32_t s) { return blk[s] | (has_eps[s] ? kFlagHasEps : 0u) | (eps_in[s] ? kFlagEpsIn : 0u); };
+  // "simple" states: exactly one arc, a self-loop without output label, with the (ilabel, weight)
+  // that is most frequent among such states (in a CTC graph the blank self-loop)
+  std::vector<char> simple(S, 0);
+  int simple_il = 1; float simple_w = 0.0f;
+  {
+    std::unordered_map<uint64_t, int64_t> freq;
+    auto lone_loop = [&](int32_t s) {
+      const int64_t i = g->row_offsets[s];
+      return g->row_offsets[s + 1] - i == 1 && g->ilabel[i] != 0 && g->next_state[i] == s && g->olabel[i] == 0;
+    };
+    auto pair_of = [&](int64_t i) { uint32_t wb; std::memcpy(&wb, &g->weight[i], 4); return ((uint64_t)(uint32_t)g->ilabel[i] << 32) | wb; };
+    for (int32_t s = 0; s < S; ++s) if (lone_loop(s)) ++freq[pair_of(g->row_offsets[s])];
+    uint64_t best = 0; int64_t best_n = 0;
+    for (const auto &kv : freq) if (kv.second > best_n || (kv.second == best_n && kv.first < best)) { best = kv.first; best_n = kv.second; }
+    if (best_n > 0) {
+      simple_il = (int)(best >> 32); const uint32_t wb = (uint32_t)best; std::memcpy(&simple_w, &wb, 4);
+      for (int32_t s = 0; s < S; ++s) if (lone_loop(s) && pair_of(g->row_offsets[s]) == best) simple[s] = 1;
+    }
+  }
+  auto named = [&](int32_t s) {
+    return blk[s] | (has_eps[s] ? kFlagHasEps : 0u) | (eps_in[s] ? kFlagEpsIn : 0u) | (simple[s] ? kFlagSimple : 0u);
+  };
   std::vector<int4> unit(units, make_int4(0, 0, 0, 0));
   bool all_zero = true;
   for (int32_t s = 0; s < S; ++s) {
@@ -1988,7 +2069,8 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
   HIP_TRY(d, hipMemcpy(d_unit, unit.data(), unit.size() * sizeof(int4), hipMemcpyHostToDevice));
   int blk_bits = 1;
   while (blk_bits < 29 && (1u << blk_bits) < blk[S]) ++blk_bits;
-  d->g = DevGraph{d_unit, blk[S], named(g->start_state), all_zero ? 0 : 1, S, blk_bits, (1u << blk_bits) - 1u};
+  d->g = DevGraph{d_unit, blk[S], named(g->start_state), all_zero ? 0 : 1, S, blk_bits, (1u << blk_bits) - 1u,
+                  simple_il, simple_w};
   return WFST_OK;
 }
 
@@ -2573,7 +2655,7 @@ int32_t wfst_debug_get_token_pairs(wfst_decoder *d, int32_t ch, int32_t *states,
   }
   for (int i = 0; i < m; ++i) {
     states[i] = d->state_of_blk[(unsigned)q[i].x & d->g.blk_mask];
-    if (bstates) bstates[i] = (int)((unsigned)q[i].x >> d->g.blk_bits);
+    if (bstates) bstates[i] = (int)(((unsigned)q[i].x & kKeyMask) >> d->g.blk_bits);
     std::memcpy(&costs[i], &q[i].y, 4);
   }
   return WFST_OK;
