@@ -44,15 +44,42 @@ def read_traffic(workload):
     return None
 
 
+def cpu_model():
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def calibrate():
+    """Measured ceilings of this GPU (paper_2311_04996_amd/csrc/wfst_probe.hip): a plain device copy,
+    random 128-byte line reads and random 64-bit global atomics, each with the whole chip busy."""
+    from paper_2311_04996_amd.probe import probe_atomics, probe_copy, probe_random_lines
+    return {"copy_gb_per_s": probe_copy(1 << 30, 5),
+            "random_128B_lines_per_s": probe_random_lines(1 << 32, 2048, 256),
+            "random_64bit_atomics_per_s": probe_atomics(1 << 30, 2048, 64),
+            "how": "1 GiB device copy (read + written bytes); 2048 workgroups x 1024 lanes, 8 loads (4 atomics) in "
+                   "flight per lane, uniform over 4 GiB (1 GiB)"}
+
+
 def cpu_baseline(w, threads, budget_s=15.0):
     """The oracle, as it stands, one utterance per thread on a bounded sample of the batch:
-    the first N utterances in batch order, N chosen for about budget_s seconds of wall time."""
+    the first N utterances in batch order, N chosen for about budget_s seconds of wall time.
+    Also the single-thread rate (on the first 120 frames of one utterance)."""
     from concurrent.futures import ThreadPoolExecutor
     from oracle import Oracle
     o = Oracle(w.graph)
+
+    def dec(b, n):
+        return o.decode(w.loglikes[b], length=n, beam=w.beam, max_active=w.max_active,
+                        boost=None if w.boosts is None else w.boosts[b],
+                        boost_fst=None if w.boost_fsts is None else w.boost_fsts[b])
     probe = int(np.argmax(w.lengths >= min(120, int(w.lengths.max()))))
     t0 = time.perf_counter()
-    o.decode(w.loglikes[probe], length=min(120, int(w.lengths[probe])), beam=w.beam, max_active=w.max_active)
+    dec(probe, min(120, int(w.lengths[probe])))
     per_frame = (time.perf_counter() - t0) / min(120, int(w.lengths[probe]))
     frames_budget = budget_s * threads / max(per_frame, 1e-9)
     take, acc = [], 0
@@ -62,12 +89,12 @@ def cpu_baseline(w, threads, budget_s=15.0):
         take.append(b); acc += int(w.lengths[b])
     t0 = time.perf_counter()
     with ThreadPoolExecutor(threads) as ex:
-        list(ex.map(lambda b: o.decode(w.loglikes[b], length=int(w.lengths[b]), beam=w.beam,
-                                       max_active=w.max_active), take))
+        list(ex.map(lambda b: dec(b, int(w.lengths[b])), take))
     dt = time.perf_counter() - t0
     audio = float(w.lengths[take].sum()) * 0.040
     return {"value": audio / dt, "unit": "audio-s/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {len(take)} utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall"}
+            "sample": f"first {len(take)} utterances of the batch ({acc} frames), one per thread, {dt:.1f} s wall",
+            "single_thread_value": 0.040 / per_frame, "nproc": os.cpu_count(), "cpu_model": cpu_model()}
 
 
 def pick_concurrent_streams(torch, n):
@@ -223,6 +250,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (profiling aid)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only measure this GPU's ceilings (device copy, random 128-byte lines, 64-bit atomics) and "
+                         "print them as one JSON line")
     ap.add_argument("--loglike-dtype", default="float32", choices=["float32", "float16", "bfloat16"],
                     help="element type of the log-likelihoods handed to the decoder (costs stay fp32)")
     ap.add_argument("--lattice-beam", type=float, default=None,
@@ -242,6 +272,9 @@ def main():
     from paper_2311_04996_amd import Decoder
     from workloads import make_config
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate:
+        print(json.dumps({"metric": "measured ceilings of this GPU", **calibrate()}), flush=True)
+        return
     if args.workload == "c4_streaming":
         return main_streaming(args)
     if args.lattice_beam is not None:
@@ -260,6 +293,10 @@ def main():
     dec = decs[0]
     ll = torch.from_numpy(w.loglikes).cuda().to(getattr(torch, args.loglike_dtype))
     outs = [None] * len(decs)
+    # the results of every step are copied to (pinned) host memory on the step's own stream, inside the timed region
+    host = [[torch.empty((B, 512), dtype=torch.int32, pin_memory=True), torch.empty(B, dtype=torch.int32, pin_memory=True),
+             torch.empty(B, dtype=torch.float32, pin_memory=True), torch.empty(B, dtype=torch.int32, pin_memory=True)]
+            for _ in decs]
     torch.cuda.synchronize()
     print(f"[bench] decoder ready in {time.perf_counter() - t0:.1f}s, {dec.device_bytes() / 2**30:.1f} GiB on device",
           file=sys.stderr, flush=True)
@@ -274,6 +311,9 @@ def main():
             k = i % n_dec
             outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
                                            boosts=w.boosts, boost_fsts=w.boost_fsts)
+            with torch.cuda.stream(streams[k]):
+                for h, o in zip(host[k], outs[k]):
+                    h.copy_(o, non_blocking=True)
             if record_ms:
                 ms.append(decs[k].last_kernel_ms())   # HIP events on the launch stream; waits for the kernel
         torch.cuda.synchronize()
@@ -319,6 +359,8 @@ def main():
     abytes = algorithmic_bytes(counters, V)
     achieved = abytes / (kms * 1e-3) / 1e9
     traffic = read_traffic(args.workload)
+    cal = calibrate()
+    achieved_at_value = abytes / (ms_per_step * 1e-3) / 1e9
     line = {
         "metric": f"RTFx (audio-s decoded/s) at batch {B}", "value": rtfx, "unit": "audio-s/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -334,9 +376,22 @@ def main():
         "arcs_expanded_per_step": arcs,
         "tokens_per_frame": float(counters[4]) / max(1, int(counters[7])),
         "hbm_frac_of_peak": achieved / HBM_PEAK_GBS,
+        "timed_region": "K decode_batch calls (init, all frames, final choice, traceback) plus the copy of their "
+                        "results to pinned host memory, between two device synchronisations; log-likelihoods resident",
         "roofline": {"bound": "hbm", "kernel": KERNEL, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms},
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, summary under profiles/ "
+                                       "(not measured in this run)",
+                     "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms,
+                     "note": "achieved / frac: algorithmic bytes over the kernel's own duration with ONE batch in flight "
+                             "(HIP events on the launch stream); *_at_value: over ms_per_step of the timed region, "
+                             f"{len(decs)} batches in flight",
+                     "achieved_at_value": achieved_at_value, "frac_at_value": achieved_at_value / HBM_PEAK_GBS,
+                     "peak_measured_copy": cal["copy_gb_per_s"], "frac_of_measured_copy": achieved / cal["copy_gb_per_s"],
+                     "frac_of_measured_copy_at_value": achieved_at_value / cal["copy_gb_per_s"],
+                     "measured_random_128B_lines_per_s": cal["random_128B_lines_per_s"],
+                     "measured_random_64bit_atomics_per_s": cal["random_64bit_atomics_per_s"],
+                     "measured_how": cal["how"]},
     }
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)

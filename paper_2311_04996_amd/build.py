@@ -9,6 +9,9 @@ ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libwfstdec.so")
 SOURCES = [os.path.join(_HERE, "csrc", "wfst_decoder.hip")]
 HEADERS = [os.path.join(ROOT, "include", "wfst_decoder.h")]
+# measured ceilings of the chip (copy, random lines, atomics): a library of its own, used by bench.py
+PROBE_LIB_PATH = os.path.join(_HERE, "libwfstprobe.so")
+PROBE_SOURCES = [os.path.join(_HERE, "csrc", "wfst_probe.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -19,12 +22,13 @@ HIPCC_FLAGS = [
 
 
 def build_library(verbose: bool = False) -> str:
-    """Always recompiles.  Returns the path of the shared library."""
+    """Always recompiles both libraries.  Returns the path of the decoder's shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH] + SOURCES
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.check_call(cmd, stderr=None if verbose else subprocess.DEVNULL)
+    for out, src in ((LIB_PATH, SOURCES), (PROBE_LIB_PATH, PROBE_SOURCES)):
+        cmd = [hipcc] + HIPCC_FLAGS + ["-o", out] + src
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.check_call(cmd, stderr=None if verbose else subprocess.DEVNULL)
     return LIB_PATH
 
 

@@ -16,10 +16,30 @@ def lib():
     return load_library()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "wfst_decoder.h")).read()
+def declared_functions(header="wfst_decoder.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(wfst_[a-z_]+)\s*\(", text)))
+
+
+def test_every_header_is_covered():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["wfst_decoder.h", "wfst_probe.h"]
+
+
+def test_probe_library_exports_what_its_header_declares():
+    from paper_2311_04996_amd.build import PROBE_LIB_PATH, build_library
+    from paper_2311_04996_amd.probe import EXPORTS, load_probe_library
+    if not os.path.exists(PROBE_LIB_PATH):
+        build_library()
+    lib = load_probe_library()
+    names = declared_functions("wfst_probe.h")
+    assert names == sorted(EXPORTS) and len(names) == 3
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/wfst_probe.h but not exported"
+    out = ctypes.c_double()
+    assert lib.wfst_probe_copy(0, 1, ctypes.byref(out)) == -1          # bad arguments: rejected before any GPU call
+    assert lib.wfst_probe_random_lines(1 << 30, 0, 64, ctypes.byref(out)) == -1
+    assert lib.wfst_probe_atomics(1 << 30, 4, 64, None) == -1
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -93,7 +113,7 @@ def test_header_is_plain_c(tmp_path):
     """The boundary is a C ABI: the header must compile as C99 on its own."""
     import subprocess
     src = tmp_path / "h.c"
-    src.write_text('#include "wfst_decoder.h"\nint main(void) { wfst_opts o; wfst_lattice_link l; (void)o; (void)l;'
+    src.write_text('#include "wfst_decoder.h"\n#include "wfst_probe.h"\nint main(void) { wfst_opts o; wfst_lattice_link l; (void)o; (void)l;'
                    ' return sizeof(wfst_lattice_link) == 32 ? 0 : 1; }\n')
     exe = tmp_path / "h"
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
