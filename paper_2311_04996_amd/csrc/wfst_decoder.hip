@@ -223,10 +223,12 @@ struct HubLds {               // ExpandArcs: states with so many arcs that all w
   int ready[kHubCap];         // set after the entry is written
   int seg_next[kHubCap];      // next segment of kHubSeg arcs nobody has taken yet
 };
-struct ExpandLds {            // live while arcs are being expanded
+constexpr int kFilterBits = 1 << 17;           // destinations of a frame's candidates, hashed to one bit each
+struct ExpandLds {            // live while arcs are being expanded (and until the first table pass begins)
   float ac[kMaxV];
   WaveLds w[kWaves];
   HubLds hub;
+  unsigned filter[kFilterBits / 32];          // bit set: some candidate of the buffer may go to a state with this hash
 };
 struct TableLds {             // live while candidates are being recombined
   unsigned long long vals[kTabSlots];   // (orderable cost << 32) | candidate index
@@ -237,13 +239,16 @@ struct Smem {
   EpsLds ek;                  // beside the table: a round's candidates go into the table while its items are
                               // expanded; afterwards the same memory lists the tokens that got better
   unsigned hist[256];
+  unsigned hist2[256];        // selection: a sample of the candidates in the buffer
+  unsigned hist3[256];        // the self-loop candidates that no candidate of the buffer can meet (exact, all bins)
+  float stay_ac;              // this frame's acoustic cost of the simple states' self-loop
   unsigned wave_tot[kWaves];
   unsigned best_ord;
   int n_reg[kRegions];        // candidates per region
   int n_pairs, n_hub, next_run, done_waves;   // improved tokens listed; listed hub states; ExpandArcs run counter; waves done listing
-  int n_win, n_next, n_wl_next, status;
+  int n_win, n_next, n_wl_next, status, n_cont;
   int n_in, n_emit, n_back;   // tokens of the emitting step an epsilon arc can enter (they come first), all of them; back counter
-  int k_sel, n_sel, k_keep, redo;
+  int k_sel, n_sel, n_sel_c, k_keep, redo;
   int path_frames, trace_from, trace_words;   // traceback: new marks valid up to; where the walk stopped; words before that
   unsigned long long red64, red64b;
   long long ctr[8];
@@ -394,6 +399,7 @@ __device__ __forceinline__ float boost_step(const Smem &sm, int b, int word, int
 // Phase timing with the constant-rate wall clock (thread 0 only; a few scalar reads per frame).
 enum { kPhExpand = 0, kPhSelect, kPhCutoff, kPhEpsExpand, kPhEpsRecombine, kPhFinish, kPhTrace, kPhOther,
        kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan, kPhExpSetup, kPhEpsMeet };
+constexpr int kPhStayMeet = kPhTabFill;          // counted with the table fill
 __device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
   if (threadIdx.x == 0) {
     const long long now = (long long)wall_clock64();
@@ -484,7 +490,9 @@ __device__ __forceinline__ int region_of(int key) { return (int)(hash_state(key)
 // independent LDS atomics), and every candidate gets a slot in its region's run; lanes
 // that hit the same region write consecutive 16-byte records, so the stores coalesce.
 // Must be called by all 64 lanes of the wave.
-template <int N>
+__device__ __forceinline__ unsigned filter_bit(int key) { return (hash_state(key) >> 9) & (kFilterBits - 1); }
+
+template <int N, bool kFilter = false>
 __device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int (&next)[N], const float (&nc)[N],
                                            const int (&src)[N], const int (&arc)[N]) {
   const int cap = x.c.region_cap;
@@ -492,6 +500,10 @@ __device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int
   for (int u = 0; u < N; ++u) {
     const int r = region_of(key_of(next[u]));
     if (ok[u]) {
+      if (kFilter) {                           // emitting step: the destination's bit, for the tokens that stay put
+        const unsigned fb = filter_bit(key_of(next[u]));
+        atomicOr(&x.sm.u.e.filter[fb >> 5], 1u << (fb & 31));
+      }
       // one LDS atomic instruction for the whole wave: the hardware serialises the lanes of a
       // region and hands them consecutive slots, in far fewer issue slots than ballots would take
       const int slot = atomicAdd(&x.sm.n_reg[r], 1);
@@ -500,6 +512,10 @@ __device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int
     }
   }
 }
+
+// Cost of the self-loop candidate of a token (cost c) in a simple state, in the association of
+// every emitting arc: (c + w) + acoustic cost.
+__device__ __forceinline__ float stay_cost(const Ctx &x, float c) { return canon((c + x.g.simple_w) + x.sm.stay_ac); }
 
 // ------------------------------------------------------------------ ExpandArcs (emitting)
 // For every token of the current set and every emitting arc:
@@ -535,7 +551,7 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
     const unsigned m = wave_min(o);
     if ((threadIdx.x & 63) == 0) atomicMin(&sm.best_ord, m);
   }
-  push_cands<N>(x, ok, next, nc, src, arc);
+  push_cands<N, true>(x, ok, next, nc, src, arc);
 }
 
 // One step of a wave's flattened loop: arcs f0 + u*64 + lane of its listed work items.
@@ -666,7 +682,6 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   WaveLds &wl = e.w[wave];
   const int R = (n_tok + kWaveTok - 1) / kWaveTok;
   int r = wave, rn = next_run(sm);
-  const unsigned bm = x.g.blk_mask; const int bbits = x.g.blk_bits;   // a token's key: (state in B << bbits) | block
   const unsigned long long lt = (1ull << lane) - 1ull;
   int2 tk = make_int2(0, 0), tkn = make_int2(0, 0);
   if (r * kWaveTok + lane < n_tok) tk = Q[r * kWaveTok + lane];
@@ -677,15 +692,20 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
     const int base = r * kWaveTok;
     const bool valid = base + lane < n_tok;
     {
-      int has[1], src[1], arc[1], tb[1]; float tc[1]; int4 a0[1];
-      has[0] = (int)valid & (int)(((unsigned)tk.x & kFlagSimple) != 0);
-      tb[0] = (int)(((unsigned)tk.x & kKeyMask) >> bbits);
-      src[0] = base + lane; tc[0] = __int_as_float(tk.y);
-      arc[0] = 2 * (int)((unsigned)tk.x & bm) + 1;     // the unit after the header
-      a0[0] = make_int4(tk.x, __float_as_int(x.g.simple_w), x.g.simple_il, 0);   // the self-loop: same state, same flags
-      n_arcs += (unsigned)__popcll(__ballot(has[0]));
-      const bool other = valid && !has[0];             // (emit_arcs clears has[] of candidates it drops)
-      emit_arcs<1>(x, has, a0, tc, src, arc, tb, beam, boosted);
+      // The self-loop candidate of a token in a simple state is never written anywhere: it is
+      // (the token's own key, stay_cost(token cost)) and is made again from the queue record
+      // wherever it is needed (selection, recombination, token creation).  Here it only lowers
+      // the running best.
+      const bool simple = valid && ((unsigned)tk.x & kFlagSimple) != 0;
+      const float nc = stay_cost(x, __int_as_float(tk.y));
+      const unsigned bo = __hip_atomic_load(&sm.best_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const unsigned o = (simple && nc < INFINITY) ? f2ord(nc) : kOrdNone;
+      if (__ballot(o < bo) != 0ull) {
+        const unsigned mo = wave_min(o);
+        if (lane == 0) atomicMin(&sm.best_ord, mo);
+      }
+      n_arcs += (unsigned)__popcll(__ballot(simple));
+      const bool other = valid && !simple;
       const unsigned long long m = __ballot(other);
       if (other) {
         const int at = (pend_head + pend_n + __popcll(m & lt)) & (2 * kWaveTok - 1);
@@ -889,25 +909,71 @@ __device__ __forceinline__ void table_winners(Ctx &x, int r0, int r1, int g, int
   }
 }
 
+// Tokens in simple states whose self-loop candidate may meet a candidate of the buffer (their
+// key's filter bit was set) were listed as {token, queue record}: they look their key up in the
+// table of the pass that covers it.  If the table has an entry for the key, the better of the two
+// (cost, then arc id) remains: when it is the self-loop, the entry's candidate index is replaced
+// by one that no candidate has, so that the winners' sweep finds no winner there.  A self-loop
+// candidate that is the best of its key is histogrammed and marked in staybits.  Every listed
+// token meets exactly one pass.
+__device__ __forceinline__ void stay_meet(Ctx &x, const int4 *CL, int n_cont, unsigned *staybits,
+                                          int r0, int r1, int g, int G, const Cutoff &cut, int k_sel) {
+  TableLds &t = x.sm.u.t;
+  constexpr unsigned kIdxStay = 0xFFFFFFFFu;
+  for (int e = threadIdx.x; e < n_cont; e += kBlock) {
+    const int4 c = CL[e];                        // {token, key + flags, cost, -}
+    const int i = c.x, key = key_of(c.y);
+    const int reg = region_of(key);
+    if (reg < r0 || reg >= r1 || (G > 1 && group_of(key, G) != g)) continue;
+    const float nc = stay_cost(x, __int_as_float(c.z));
+    if (!(cut.bin(nc) < k_sel)) continue;        // (it is inside the beam: only those were listed)
+    unsigned sl = (hash_state(key) >> 6) & kTabMask;
+    int probes = 0, k = t.keys[sl];
+    while (k != key && k != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; k = t.keys[sl]; }
+    bool win = true;
+    if (k == key) {
+      const unsigned long long v = t.vals[sl];
+      const unsigned oc = f2ord(nc), cc = (unsigned)(v >> 32);
+      const unsigned my_arc = 2u * ((unsigned)c.y & x.g.blk_mask) + 1u;
+      win = oc < cc;
+      if (oc == cc) win = my_arc < (unsigned)x.cand[(unsigned)v].w;          // exact tie: lower arc id
+      if (win) t.vals[sl] = ((unsigned long long)oc << 32) | kIdxStay;
+    }
+    if (win) {
+      atomicAdd(&x.sm.hist[cut.bin(nc)], 1u);
+      atomicOr(&staybits[i >> 5], 1u << (i & 31));
+    }
+  }
+}
+
 // The table passes that reduce n_sel selected candidates: one pass over everything if they
 // fit one table, else every region on its own in as many sub-group passes as it needs.
 struct PassPlan {
-  int n_pass; bool whole; int per_region[kRegions];
-  __device__ __forceinline__ void make(const Ctx &x, int n_sel, int n_all) {
+  int n_pass; bool whole, halves; int per_region[kRegions];
+  // every_region: also regions without candidates get a pass (the emitting step, where the self-loop
+  // candidates of the tokens meet the table of their region's pass)
+  __device__ __forceinline__ void make(const Ctx &x, int n_sel, int n_all, bool every_region = false) {
+    static_assert(kRegions == 4, "the halves are regions {0, 1} and {2, 3}");
     whole = n_sel <= kGroupTarget;
+    halves = false;
     n_pass = whole ? 1 : 0;
+    float est_r[kRegions];
 #pragma unroll
     for (int r = 0; r < kRegions; ++r) {
       const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
       // selected candidates of the region, estimated from its share of all candidates
-      const float est = (float)n_sel * (float)n / (float)max(1, n_all) * 1.15f + 64.0f;
-      per_region[r] = (whole || n == 0) ? 0 : (int)(est / (float)kGroupTarget) + 1;
+      est_r[r] = (float)n_sel * (float)n / (float)max(1, n_all) * 1.15f + 64.0f;
+      per_region[r] = (whole || (n == 0 && !every_region)) ? 0 : (int)(est_r[r] / (float)kGroupTarget) + 1;
       n_pass += per_region[r];
+    }
+    if (!whole && every_region && est_r[0] + est_r[1] <= (float)kGroupTarget && est_r[2] + est_r[3] <= (float)kGroupTarget) {
+      halves = true; n_pass = 2;                  // two regions per pass
     }
   }
   // pass p covers regions [r0, r1) and sub-group g of G
   __device__ __forceinline__ void get(int p, int &r0, int &r1, int &g, int &G) const {
     if (whole) { r0 = 0; r1 = kRegions; g = 0; G = 1; return; }
+    if (halves) { r0 = 2 * p; r1 = 2 * p + 2; g = 0; G = 1; return; }
     int r = 0, n = per_region[0];               // no dynamic indexing: the plan stays in registers
 #pragma unroll
     for (int q = 0; q < kRegions - 1; ++q) if (r == q && p >= per_region[q]) { p -= per_region[q]; r = q + 1; n = per_region[q + 1]; }
@@ -976,16 +1042,50 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   const int n_cand = total_candidates(x);
   const unsigned ma = (unsigned)x.s.max_active;
 
-  // ---- 1. select, from a sample of the candidates
+  const int2 *Q = x.srcq;                      // the current token set: its simple tokens carry implicit candidates
+  const int n_tok = x.s.n_tok;
+  // bit i of staybits: token i's self-loop candidate is the recombined token of its state (the
+  // closure's tables are idle now).  The tokens whose candidate may meet one of the buffer are
+  // listed in the second worklist buffer, which nobody uses before the closure's first round ends.
+  unsigned *staybits = reinterpret_cast<unsigned *>(&sm.ek);
+  int4 *CL = x.wl0 + x.c.qcap;
+  static_assert(sizeof(EpsLds) * 8 >= kQueueMax, "one bit per token of the set");
+  if (tid < 256) { sm.hist2[tid] = 0; sm.hist3[tid] = 0; }
+  if (tid == 0) sm.n_cont = 0;
+  __syncthreads();
+
+  // ---- 0. the tokens that stay where they are.  One sweep over the token set, while the filter of
+  // the buffer's destinations is still there: a self-loop candidate inside the beam whose key's
+  // bit is clear meets no other candidate, so it is the recombined token of its state: marked and
+  // histogrammed (exactly, in every bin).  The few whose bit is set are left for the table passes.
+  for (int i0 = 0; i0 < n_tok; i0 += kBlock) {
+    const int i = i0 + tid;
+    const int2 q = i < n_tok ? Q[i] : make_int2(0, 0);
+    const float nc = stay_cost(x, __int_as_float(q.y));
+    const int in = (int)(i < n_tok) & (int)(((unsigned)q.x & kFlagSimple) != 0) & (int)(nc < INFINITY) & (int)cut.in_beam(nc);
+    const unsigned fb = filter_bit(key_of(q.x));
+    const int cont = in & (int)((sm.u.e.filter[fb >> 5] >> (fb & 31)) & 1u);
+    const int alone = in & (int)!cont;
+    if (alone) atomicAdd(&sm.hist3[cut.bin(nc)], 1u);
+    const unsigned long long ma_ = __ballot(alone);
+    const int lane = tid & 63;                   // the wave's 64 tokens are two words of the bit set
+    if (lane == 0) staybits[i >> 5] = (unsigned)ma_;
+    if (lane == 32) staybits[i >> 5] = (unsigned)(ma_ >> 32);
+    const int cn[1] = {cont}; int ci[1];
+    wave_alloc_n<1>(&sm.n_cont, cn, ci);         // at most one entry per token: the list cannot overflow its qcap records
+    if (cont) CL[ci[0]] = make_int4(i, q.x, q.y, 0);
+  }
+
+  // ---- 1. select: the exact histogram of the tokens that stay plus a sample of the buffer
   int n_sampled = 0;
+  constexpr int kHalf = 2;
+  // one run of 64 records in kEvery (a wave reads one run): candidates arrive roughly in the
+  // order of the token queue, which is not free of cost trends, so the sample is interleaved finely
+  constexpr int kEvery = WFST_SEL_EVERY;            // one run of 64 records out of kEvery
+  const int mine = (tid >> 6) * (64 * kEvery) + (tid & 63);
   for (int r = 0; r < kRegions; ++r) {
     const int n = uni(min(sm.n_reg[r], x.c.region_cap));
     const int4 *cr = x.cand + r * x.c.region_cap;
-    constexpr int kHalf = 2;
-    // one run of 64 records in kEvery (a wave reads one run): candidates arrive roughly in the
-    // order of the token queue, which is not free of cost trends, so the sample is interleaved finely
-    constexpr int kEvery = WFST_SEL_EVERY;          // one run of 64 records out of kEvery
-    const int mine = (tid >> 6) * (64 * kEvery) + (tid & 63);
     for (int i0 = 0; i0 < n; i0 += kEvery * kBlock * kHalf) {
       int cb[kHalf];
 #pragma unroll
@@ -993,7 +1093,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
 #pragma unroll
       for (int u = 0; u < kHalf; ++u) {
         const float c = __int_as_float(cb[u]);
-        if (i0 + u * kEvery * kBlock + mine < n && cut.in_beam(c)) atomicAdd(&sm.hist[cut.bin(c)], 1u);
+        if (i0 + u * kEvery * kBlock + mine < n && cut.in_beam(c)) atomicAdd(&sm.hist2[cut.bin(c)], 1u);
       }
       const int span = min(n - i0, kEvery * kBlock * kHalf);
       n_sampled += span / (64 * kEvery) * 64 + min(span % (64 * kEvery), 64);
@@ -1001,41 +1101,47 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   }
   __syncthreads();
   if (tid < 64) {
-    const unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
-    unsigned s = h0 + h1 + h2 + h3, inc = s;
-    inc = wave_scan_add(inc);
+    // bins of the tokens that stay (exact) plus the buffer's sample scaled up to the whole buffer
+    const float up = (float)max(1, n_cand) / (float)max(1, n_sampled);
+    float hb[4]; unsigned hs[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { hs[j] = sm.hist3[4 * tid + j]; hb[j] = (float)sm.hist2[4 * tid + j] * up; }
+    const unsigned s = hs[0] + hs[1] + hs[2] + hs[3] + (unsigned)(hb[0] + hb[1] + hb[2] + hb[3]);
+    const unsigned inc = wave_scan_add(s);
     const unsigned n_in = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
-    // the histogram holds n_sampled of the n_cand candidates: scale the target down, the count up
-    const float frac = (float)n_sampled / (float)max(1, n_cand);
-    const float want = ((float)ma * x.s.sel_ratio + 256.0f) * frac;
+    const float want = (float)ma * x.s.sel_ratio + 256.0f;
     const unsigned target = want < 2.0e9f ? (unsigned)want : 2000000000u;
-    int ks = 256; unsigned nsel = (unsigned)n_cand;
+    int ks = 256; unsigned nsel = (unsigned)(n_cand + n_tok), nsel_c = (unsigned)n_cand;
     if (n_in > target) {
-      unsigned run = inc - s;
-      int first = 256; unsigned at = 0;
-      run += h0; if (run >= target && first == 256) { first = 4 * tid; at = run; }
-      run += h1; if (run >= target && first == 256) { first = 4 * tid + 1; at = run; }
-      run += h2; if (run >= target && first == 256) { first = 4 * tid + 2; at = run; }
-      run += h3; if (run >= target && first == 256) { first = 4 * tid + 3; at = run; }
+      float run = (float)(inc - s), run_c = 0.0f;
+      int first = 256; float at = 0.0f, at_c = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        run += (float)hs[j] + hb[j]; run_c += hb[j];
+        if (run >= (float)target && first == 256) { first = 4 * tid + j; at = run; at_c = run_c; }
+      }
       int fm = first;
 #pragma unroll
       for (int sft = 32; sft > 0; sft >>= 1) fm = min(fm, __shfl_xor(fm, sft, 64));
-      const unsigned long long own = __ballot(first == fm && fm != 256);
-      nsel = (unsigned)((float)__shfl(at, __ffsll((long long)own) - 1, 64) / frac);
+      const int owner = __ffsll((long long)__ballot(first == fm && fm != 256)) - 1;
+      // the buffer's share of the selected: whole lanes before the owner, and the owner's bins up to there
+      const float lane_c = hb[0] + hb[1] + hb[2] + hb[3];
+      const float before_c = (float)wave_sum((tid & 63) < owner ? (unsigned)lane_c : 0u);
+      nsel = (unsigned)__shfl(at, owner, 64);
+      nsel_c = min((unsigned)n_cand, (unsigned)(before_c + __shfl(at_c, owner, 64)));
       ks = fm + 1;                                   // bins [0, ks) are selected
     }
-    if (tid == 0) { sm.k_sel = ks; sm.n_sel = (int)nsel; }
+    if (tid == 0) { sm.k_sel = ks; sm.n_sel = (int)nsel; sm.n_sel_c = (int)nsel_c; }
   }
   __syncthreads();
-  if (tid < 256) sm.hist[tid] = 0;
-  int k_sel = uni(sm.k_sel), n_sel = uni(sm.n_sel);
-  __syncthreads();
+  int k_sel = uni(sm.k_sel), n_sel = uni(sm.n_sel), n_sel_c = uni(sm.n_sel_c);
+  const int n_cont = uni(sm.n_cont);
   prof_mark(sm, kPhSelect);
 
   for (int attempt = 0; attempt < 2; ++attempt) {
     // ---- 2. recombine the selected candidates, G table passes
     PassPlan plan;
-    plan.make(x, n_sel, n_cand);
+    plan.make(x, n_sel_c, n_cand, true);
     for (int ps = 0; ps < plan.n_pass; ++ps) {
       int r0, r1, g, G;
       plan.get(ps, r0, r1, g, G);
@@ -1045,13 +1151,20 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       table_fill<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
       prof_mark(sm, kPhTabFill);
+      stay_meet(x, CL, n_cont, staybits, r0, r1, g, G, cut, k_sel);
+      __syncthreads();
+      prof_mark(sm, kPhStayMeet);
       table_winners<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
       prof_mark(sm, kPhTabScan);
     }
     // ---- 3. cutoff from the histogram of recombined tokens
     if (tid < 64) {
-      const unsigned h0 = sm.hist[4 * tid], h1 = sm.hist[4 * tid + 1], h2 = sm.hist[4 * tid + 2], h3 = sm.hist[4 * tid + 3];
+      // recombined tokens in the selected bins: the table passes' winners and the tokens that stay alone
+      const unsigned h0 = 4 * tid < k_sel ? sm.hist[4 * tid] + sm.hist3[4 * tid] : 0u;
+      const unsigned h1 = 4 * tid + 1 < k_sel ? sm.hist[4 * tid + 1] + sm.hist3[4 * tid + 1] : 0u;
+      const unsigned h2 = 4 * tid + 2 < k_sel ? sm.hist[4 * tid + 2] + sm.hist3[4 * tid + 2] : 0u;
+      const unsigned h3 = 4 * tid + 3 < k_sel ? sm.hist[4 * tid + 3] + sm.hist3[4 * tid + 3] : 0u;
       unsigned s = h0 + h1 + h2 + h3, inc = s;
       inc = wave_scan_add(inc);
       const unsigned n_u = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
@@ -1092,8 +1205,12 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     if (tid == 0) sm.prof[15]++;                   // counted, not timed: re-recombinations
     __syncthreads();
     if (tid < 256) sm.hist[tid] = 0;
+    for (int e = tid; e < n_cont; e += kBlock) {   // the listed ones meet the tables again
+      const int i = CL[e].x;
+      atomicAnd(&staybits[i >> 5], ~(1u << (i & 31)));
+    }
     if (tid == 0) { sm.n_win = 0; sm.redo = 0; }
-    k_sel = 256; n_sel = n_cand;
+    k_sel = 256; n_sel = n_cand + n_tok; n_sel_c = n_cand;
     __syncthreads();
   }
   cut.k_keep = uni(sm.k_keep);
@@ -1130,6 +1247,39 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       }
       st[u] = cr[u].x; cb[u] = cr[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
       if (x.c.cost_offset) cb[u] = __float_as_int(canon(__int_as_float(cr[u].y) - cut.best));
+    }
+    make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN);
+  }
+  // ... and the tokens that stay where they are: the marked self-loop candidates, made from the
+  // queue records of the current set
+  for (int i0 = 0; i0 < n_tok; i0 += kBlock * kUC) {
+    int kp[kUC]; int2 q[kUC]; float nc[kUC];
+#pragma unroll
+    for (int u = 0; u < kUC; ++u) {
+      const int i = i0 + u * kBlock + tid;
+      q[u] = Q[min(i, n_tok - 1)];
+      nc[u] = stay_cost(x, __int_as_float(q[u].y));
+      kp[u] = (int)(i < n_tok) & (int)((staybits[min(i, n_tok - 1) >> 5] >> (i & 31)) & 1u) & (int)(cut.bin(nc[u]) < cut.k_keep);
+    }
+    int ti[kUC], tb[kUC], st[kUC], cb[kUC], pv[kUC], ar[kUC], none[kUC]; int good[kUC], no[kUC], kin[kUC], kout[kUC];
+#pragma unroll
+    for (int u = 0; u < kUC; ++u) {
+      kin[u] = kp[u] & (int)(((unsigned)q[u].x & kFlagEpsIn) != 0);
+      kout[u] = kp[u] & (int)!kin[u];
+    }
+    wave_alloc_n<kUC>(&sm.n_next, kin, ti);
+    wave_alloc_n<kUC>(&sm.n_back, kout, tb);
+#pragma unroll
+    for (int u = 0; u < kUC; ++u) {
+      if (kout[u]) ti[u] = n_emit - 1 - tb[u];
+      good[u] = kp[u]; no[u] = false; none[u] = 0;
+      if (kp[u]) {
+        if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
+        else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
+      }
+      st[u] = q[u].x; cb[u] = __float_as_int(nc[u]); pv[u] = i0 + u * kBlock + tid;
+      ar[u] = 2 * (int)((unsigned)q[u].x & x.g.blk_mask) + 1;     // the self-loop: the unit after the header
+      if (x.c.cost_offset) cb[u] = __float_as_int(canon(nc[u] - cut.best));
     }
     make_tokens<kUC>(x, good, ti, st, cb, pv, ar, no, none, NQ, lat_base, WLN);
   }
@@ -1618,18 +1768,20 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     {
       // the frame's acoustic costs; 16-bit log-likelihoods are widened exactly
       const long long r0 = ll0 + (long long)t * a.V;
+      const int vs = g.simple_il - 1;          // the class of the simple states' self-loop: kept beside the table too
       if (a.ll_dtype == WFST_LOGLIKE_F32) {
         const float *row = static_cast<const float *>(a.ll) + r0;
-        for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -row[v];
+        for (int v = tid; v < a.V; v += kBlock) { const float c = -row[v]; sm.u.e.ac[v] = c; if (v == vs) sm.stay_ac = c; }
       } else if (a.ll_dtype == WFST_LOGLIKE_F16) {
         const _Float16 *row = static_cast<const _Float16 *>(a.ll) + r0;
-        for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -(float)row[v];
+        for (int v = tid; v < a.V; v += kBlock) { const float c = -(float)row[v]; sm.u.e.ac[v] = c; if (v == vs) sm.stay_ac = c; }
       } else {
         const unsigned short *row = static_cast<const unsigned short *>(a.ll) + r0;
-        for (int v = tid; v < a.V; v += kBlock) sm.u.e.ac[v] = -__uint_as_float((unsigned)row[v] << 16);
+        for (int v = tid; v < a.V; v += kBlock) { const float c = -__uint_as_float((unsigned)row[v] << 16); sm.u.e.ac[v] = c; if (v == vs) sm.stay_ac = c; }
       }
     }
     for (int h = tid; h < kHubCap; h += kBlock) { sm.u.e.hub.ready[h] = 0; sm.u.e.hub.seg_next[h] = 0; }
+    for (int h = tid; h < kFilterBits / 32; h += kBlock) sm.u.e.filter[h] = 0u;
     if (tid == 0) { sm.next_run = kWaves; sm.done_waves = 0; sm.n_hub = 0; }
     __syncthreads();
     const int2 *Q = x.q0 + x.s.cur * c.qcap;
