@@ -259,8 +259,8 @@ def main():
                     help="lattice mode: decode --batch utterances (default 8) with token records kept and time "
                          "wfst_get_lattice with this lattice beam for each of them")
     ap.add_argument("--pipeline", type=int, default=3,
-                    help="decoders (each with its own stream) that take the steps in turn, so that the "
-                         "next batch fills the compute units the previous one no longer uses")
+                    help="batch slots of the one decoder (each with its own stream) that take the steps in turn, so "
+                         "that the next batch fills the compute units the previous one no longer uses")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (utterances are independent; more GPUs "
@@ -286,54 +286,56 @@ def main():
     print(f"[bench] {args.workload}: S={w.graph.num_states} A={w.graph.num_arcs} B={B} T={T} V={V} "
           f"audio={w.audio_seconds:.1f}s generated in {time.perf_counter() - t0:.1f}s", file=sys.stderr, flush=True)
     t0 = time.perf_counter()
-    decs = [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active,
-                    loglike_dtype=args.loglike_dtype)
-            for _ in range(max(1, args.pipeline))]
-    streams = pick_concurrent_streams(torch, len(decs))
-    dec = decs[0]
+    # ONE decoder: the batches in flight are its batch slots (shared graph), and a slot's lattice
+    # memory is shared out by utterance length, so it is sized for the batch's mean length
+    n_slots = max(1, args.pipeline)
+    mean_frames = float(w.lengths.mean())
+    dec = Decoder(w.graph, max_channels=B * n_slots, max_frames=T, max_words=512, max_active_hint=w.max_active,
+                  loglike_dtype=args.loglike_dtype, batch_slots=n_slots, lattice_by_length=True,
+                  lattice_bytes_per_channel=int(8 * 1.5 * w.max_active * (mean_frames + 2)))
+    streams = pick_concurrent_streams(torch, n_slots)
     ll = torch.from_numpy(w.loglikes).cuda().to(getattr(torch, args.loglike_dtype))
-    outs = [None] * len(decs)
+    outs = [None] * n_slots
     # the results of every step are copied to (pinned) host memory on the step's own stream, inside the timed region
     host = [[torch.empty((B, 512), dtype=torch.int32, pin_memory=True), torch.empty(B, dtype=torch.int32, pin_memory=True),
              torch.empty(B, dtype=torch.float32, pin_memory=True), torch.empty(B, dtype=torch.int32, pin_memory=True)]
-            for _ in decs]
+            for _ in range(n_slots)]
     torch.cuda.synchronize()
     print(f"[bench] decoder ready in {time.perf_counter() - t0:.1f}s, {dec.device_bytes() / 2**30:.1f} GiB on device",
           file=sys.stderr, flush=True)
 
-    def run_steps(n_dec, nsteps, record_ms):
-        """nsteps decode_batch calls taken in turn by the first n_dec decoders (each on its own
+    def run_steps(n_use, nsteps, record_ms):
+        """nsteps decode_batch calls taken in turn by the first n_use batch slots (each on its own
         stream); returns the wall time between two device synchronisations."""
         ms = []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(nsteps):
-            k = i % n_dec
-            outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
-                                           boosts=w.boosts, boost_fsts=w.boost_fsts)
+            k = i % n_use
+            outs[k] = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
+                                       boosts=w.boosts, boost_fsts=w.boost_fsts, slot=k)
             with torch.cuda.stream(streams[k]):
                 for h, o in zip(host[k], outs[k]):
                     h.copy_(o, non_blocking=True)
             if record_ms:
-                ms.append(decs[k].last_kernel_ms())   # HIP events on the launch stream; waits for the kernel
+                ms.append(dec.slot_kernel_ms(k))      # HIP events on the launch stream; waits for the kernel
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ms
 
-    for k in range(len(decs)):                       # warmup: every decoder, every buffer touched
+    for k in range(n_slots):                         # warmup: every slot, every buffer touched
         for _ in range(max(1, args.warmup) if args.warmup else 0):
-            outs[k] = decs[k].decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
-                                           boosts=w.boosts, boost_fsts=w.boost_fsts)
+            outs[k] = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
+                                       boosts=w.boosts, boost_fsts=w.boost_fsts, slot=k)
     torch.cuda.synchronize()
-    for d in decs:
-        d.get_counters(reset=True)
-        d.debug_phase_ticks(reset=True)
+    dec.get_counters(reset=True)
+    dec.debug_phase_ticks(reset=True)
     # one batch in flight: the kernel's own duration (for the roofline) and the unpipelined rate
     wall_one, kernel_ms = run_steps(1, args.steps, True)
-    counters = decs[0].get_counters() // max(1, args.steps)
-    ticks = decs[0].debug_phase_ticks()
+    counters = dec.get_counters() // max(1, args.steps)
+    ticks = dec.debug_phase_ticks()
     ticks[15] = 0                                   # slot 15 is a count, not a time
     # the timed region proper: `pipeline` batches in flight
-    wall = run_steps(len(decs), args.steps, False)[0] if len(decs) > 1 else wall_one
+    wall = run_steps(n_slots, args.steps, False)[0] if n_slots > 1 else wall_one
     names = ["expand_tail", "select", "tokens", "eps_expand", "eps_round_end", "publish", "trace", "other",
              "tab_clear", "tab_fill", "tab_winners", "eps_table", "eps_new_tokens", "expand_arcs", "eps_meet", "-"]
     print("[bench] phase share of workgroup time (one batch in flight): " +
@@ -368,8 +370,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
                    "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
-                   "beam": w.beam, "max_active": w.max_active, "batches_in_flight": len(decs),
-                   "loglike_dtype": args.loglike_dtype},
+                   "beam": w.beam, "max_active": w.max_active, "batches_in_flight": n_slots,
+                   "loglike_dtype": args.loglike_dtype, "decoders": 1,
+                   "device_gib": round(dec.device_bytes() / 2**30, 1)},
         "one_batch_in_flight": {"value": w.audio_seconds / (wall_one / args.steps),
                                 "ms_per_step": 1e3 * wall_one / args.steps},
         "arcs_expanded_per_s": arcs / (wall / args.steps),
@@ -385,7 +388,7 @@ def main():
                      "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms,
                      "note": "achieved / frac: algorithmic bytes over the kernel's own duration with ONE batch in flight "
                              "(HIP events on the launch stream); *_at_value: over ms_per_step of the timed region, "
-                             f"{len(decs)} batches in flight",
+                             f"{n_slots} batches in flight",
                      "achieved_at_value": achieved_at_value, "frac_at_value": achieved_at_value / HBM_PEAK_GBS,
                      "peak_measured_copy": cal["copy_gb_per_s"], "frac_of_measured_copy": achieved / cal["copy_gb_per_s"],
                      "frac_of_measured_copy_at_value": achieved_at_value / cal["copy_gb_per_s"],
@@ -396,8 +399,7 @@ def main():
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         line["cpu_baseline"] = cpu_baseline(w, threads)
-    for d in decs:
-        d.close()
+    dec.close()
     print(json.dumps(line), flush=True)
 
 

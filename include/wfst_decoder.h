@@ -17,7 +17,9 @@
  *     enqueued on it; device outputs are valid once the stream has reached the end of the
  *     call's work.  With opts.outputs_on_host != 0 the call copies results to host memory and
  *     synchronises the stream before returning.
- *   - Calls on one decoder must not overlap in time (one stream at a time per decoder).
+ *   - Calls on one decoder must not overlap in time (one stream at a time per decoder), except
+ *     wfst_decode_batch_slot calls on different batch slots.  A decoder is not thread-safe on the
+ *     host: issue its calls from one thread.
  *   - Labels: ilabel 0 = epsilon; ilabel k >= 1 reads log-likelihood column k-1 (so the CTC
  *     blank, class 0, is ilabel 1); olabel 0 = no output (cf. the olabel != 0 test in the
  *     figure "Pseudo-code of Expand Arcs").
@@ -95,6 +97,27 @@ typedef struct {
                                      and in near-ties.  Stored token costs, and with them the costs in a
                                      lattice, are the rebased ones (a link's cost is in the base of the
                                      token it enters) */
+  int32_t batch_slots;            /* 0 or 1: one.  n > 1: the channels are n equal groups ("slots"), and
+                                     wfst_decode_batch_slot calls on DIFFERENT slots may be in flight at the same
+                                     time (each on its own stream), sharing the graph: while one batch's long
+                                     utterances finish, the next batch's take the free compute units.  max_channels
+                                     must be a multiple of n; a batch has at most max_channels / n utterances */
+  int32_t recycle_lattice;        /* 1: a channel's backpointer memory is a ring over whole frames, so a stream can
+                                     run for any number of frames (the per-stream state is the set of active tokens,
+                                     Section "Streaming inference"; backpointers are kept only as far back as results
+                                     still need them).  A (partial) result then needs the path of the channel's
+                                     previous result: it is exact as long as the new best path joins that path
+                                     within the frames the ring still holds (max_frames_per_channel frames and
+                                     lattice_bytes_per_channel bytes back); otherwise the call reports
+                                     WFST_FLAG_LATTICE_OVERFLOW and no words.  Ask for results at least that often.
+                                     Needs lattice_bytes_per_channel >= 16 B x the token queue size (2 full token
+                                     sets); excludes keep_token_records.  max_frames_per_channel then bounds only a
+                                     single wfst_decode_batch utterance, not a stream */
+  int32_t lattice_by_length;      /* 1: wfst_decode_batch* shares a slot's backpointer memory (channels of the slot x
+                                     lattice_bytes_per_channel) out among the batch's utterances in proportion to
+                                     their lengths instead of equally, so lattice_bytes_per_channel can be sized for
+                                     the MEAN utterance.  Such a call takes the memory of every channel of its slot:
+                                     channels of that slot used for streaming must be initialised again afterwards */
 } wfst_opts;
 
 #define WFST_LOGLIKE_F32 0
@@ -188,6 +211,16 @@ int32_t wfst_decode_batch_boost_fst(wfst_decoder *dec, const float *loglikes, co
                                     int32_t B, int32_t T, int32_t V, float beam, int32_t max_active,
                                     const wfst_boost_fst *const *fsts, void *stream,
                                     int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
+
+/* wfst_decode_batch on batch slot `slot` (opts.batch_slots): utterance b uses channel
+ * slot * (max_channels / batch_slots) + b.  Calls on different slots may overlap in time when they
+ * are given different streams; calls on one slot may not.  boosts / fsts: NULL, or one of them a
+ * HOST array of B table / acceptor pointers.  loglikes as in wfst_decode_batch (element type
+ * opts.loglike_dtype).  With host outputs the call synchronises its stream before returning. */
+int32_t wfst_decode_batch_slot(wfst_decoder *dec, int32_t slot, const void *loglikes, const int32_t *lengths,
+                               int32_t B, int32_t T, int32_t V, float beam, int32_t max_active,
+                               const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts,
+                               void *stream, int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
 
 /*
  * Streaming (Section "Streaming inference": the decoder state kept per audio stream is its
@@ -324,6 +357,8 @@ int64_t wfst_device_bytes(const wfst_decoder *dec);
  * Returns a negative value if no kernel has been launched.
  */
 float wfst_last_kernel_ms(wfst_decoder *dec);
+/* The same for the most recent wfst_decode_batch* kernel of one batch slot. */
+float wfst_slot_kernel_ms(wfst_decoder *dec, int32_t slot);
 
 const char *wfst_last_error(const wfst_decoder *dec);
 

@@ -20,7 +20,7 @@ FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPAC
 LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
-           "wfst_decode_batch_boost_fst", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels",
+           "wfst_decode_batch_boost_fst", "wfst_decode_batch_slot", "wfst_slot_kernel_ms", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
            "wfst_get_lattice_noalloc",
            "wfst_debug_frame_digests",
@@ -71,7 +71,8 @@ class wfst_opts(C.Structure):
                 ("max_words", C.c_int32), ("lattice_bytes_per_channel", C.c_int64),
                 ("outputs_on_host", C.c_int32), ("max_active_hint", C.c_int32),
                 ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32),
-                ("loglike_dtype", C.c_int32), ("keep_token_records", C.c_int32), ("cost_offset", C.c_int32)]
+                ("loglike_dtype", C.c_int32), ("keep_token_records", C.c_int32), ("cost_offset", C.c_int32),
+                ("batch_slots", C.c_int32), ("recycle_lattice", C.c_int32), ("lattice_by_length", C.c_int32)]
 
 
 class wfst_lattice_link(C.Structure):
@@ -121,12 +122,15 @@ def load_library():
     lib.wfst_device_bytes.restype = i64
     lib.wfst_last_kernel_ms.argtypes = [p]
     lib.wfst_last_kernel_ms.restype = f32
+    lib.wfst_slot_kernel_ms.argtypes = [p, i32]
+    lib.wfst_slot_kernel_ms.restype = f32
+    lib.wfst_decode_batch_slot.argtypes = [p, i32, p, p, i32, i32, i32, f32, i32, p, p, p, p, p, p, p]
     lib.wfst_last_error.argtypes = [p]
     lib.wfst_last_error.restype = C.c_char_p
     lib.wfst_get_lattice.argtypes = [p, i32, p, f32, p, p, i64, p, p, i64, p, p, p]
     lib.wfst_get_lattice_noalloc.argtypes = lib.wfst_get_lattice.argtypes
     for name in EXPORTS:
-        if name not in ("wfst_device_bytes", "wfst_last_kernel_ms", "wfst_last_error"):
+        if name not in ("wfst_device_bytes", "wfst_last_kernel_ms", "wfst_slot_kernel_ms", "wfst_last_error"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -151,7 +155,8 @@ class Decoder:
 
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
                  lattice_bytes_per_channel=0, outputs_on_host=False, candidate_capacity=0,
-                 record_digests=False, loglike_dtype="float32", keep_token_records=False, cost_offset=False):
+                 record_digests=False, loglike_dtype="float32", keep_token_records=False, cost_offset=False,
+                 batch_slots=0, recycle_lattice=False, lattice_by_length=False):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
                 np.ascontiguousarray(graph.next_state, dtype=np.int32),
@@ -164,7 +169,7 @@ class Decoder:
         self.opts = wfst_opts(max_channels, max_frames, max_words, lattice_bytes_per_channel,
                               int(outputs_on_host), max_active_hint, candidate_capacity,
                               int(record_digests), LOGLIKE_DTYPES[loglike_dtype], int(keep_token_records),
-                              int(cost_offset))
+                              int(cost_offset), int(batch_slots), int(recycle_lattice), int(lattice_by_length))
         self.loglike_dtype = loglike_dtype
         self.V = graph.num_classes
         self.max_words = max_words
@@ -191,7 +196,8 @@ class Decoder:
             raise WfstError(rc, self.lib.wfst_last_error(self.h).decode())
 
     # ---- offline
-    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None, boosts=None, boost_fsts=None):
+    def decode_batch(self, loglikes, lengths, beam, max_active, stream=None, out=None, boosts=None, boost_fsts=None,
+                     slot=None):
         """loglikes: CUDA float32 tensor [B, T, V]; lengths: int32 host array [B].
         boosts: optional list of B entries, each None or a (word_ids, scores) table.
         boost_fsts: optional list of B entries, each None or a boosting acceptor (an object with
@@ -215,6 +221,18 @@ class Decoder:
                            torch.zeros(B, dtype=torch.float32, device=dev),
                            torch.zeros(B, dtype=torch.int32, device=dev))
         ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
+        if slot is not None:                       # wfst_decode_batch_slot: several batches in flight on one decoder
+            keep = arr_t = arr_f = None
+            if boosts is not None:
+                keep = [None if t is None else _boost_struct(t) for t in boosts]
+                arr_t = (C.c_void_p * B)(*[None if k is None else C.addressof(k[0]) for k in keep])
+            if boost_fsts is not None:
+                keep = [None if f is None else _fst_struct(f) for f in boost_fsts]
+                arr_f = (C.c_void_p * B)(*[None if k is None else C.addressof(k[0]) for k in keep])
+            self._check(self.lib.wfst_decode_batch_slot(self.h, int(slot), loglikes.data_ptr(), lengths.ctypes.data, B, T, V,
+                                                        beam, max_active, arr_t, arr_f, _stream_ptr(stream),
+                                                        ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3])))
+            return out
         if boost_fsts is not None:
             assert boosts is None and len(boost_fsts) == B
             keep = [None if f is None else _fst_struct(f) for f in boost_fsts]
@@ -400,3 +418,6 @@ class Decoder:
 
     def last_kernel_ms(self):
         return float(self.lib.wfst_last_kernel_ms(self.h))
+
+    def slot_kernel_ms(self, slot):
+        return float(self.lib.wfst_slot_kernel_ms(self.h, int(slot)))

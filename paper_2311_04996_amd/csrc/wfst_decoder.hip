@@ -153,6 +153,7 @@ struct ChanState {            // persists between calls (the per-stream decoder 
   int path_frames;            // the traced-path marks of frames 1..path_frames are valid (0: none)
   int boost_n;                // arcs of the channel's boosting acceptor (0 = none); set by the host
   int boost_states;           // its states (1: the paper's one-state acceptor, a table word -> score); set by the host
+  int lat_epoch;              // recycled lattice arena: how often the write position has gone back to the start
 };
 
 struct DevGraph {
@@ -176,7 +177,11 @@ struct DevChannels {
   int4 *win;        int win_cap;               // recombined tokens before the max-active cutoff (their candidate records)
   int2 *queue;      int qcap;                  // 2 buffers {block number, cost}
   int4 *wl;                                    // 2 buffers {token, block number, cost, 1 = new token}
-  int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}
+  int2 *lattice;    unsigned lat_cap;          // {prev token, arc id}; lat_cap: entries per channel when shared out equally
+  const unsigned long long *lat_start;         // [channels] where the channel's arena begins in `lattice` (and `tokrec`)
+  const unsigned *lat_capn;                    // [channels] and how many entries it has
+  int recycle;                                 // 1: a channel's arena is a ring over whole frames (streams of any length)
+  int *frame_ep;                               // [channels][max_frames + 2] the epoch each frame's tokens were stored in
   int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
   int cost_offset;                             // 1: token costs are rebased to the best cost after every prune step
   // the path of the last traceback, so that the next one can stop where it meets it:
@@ -368,6 +373,7 @@ struct Ctx {                  // block-uniform view of one channel
   unsigned long long *dig_sum; int *dig_cnt;
   ChanState s;
   const int2 *srcq;           // the queue the candidates' source tokens are in (ties between two takes of one arc)
+  unsigned lat_cap;           // entries of the channel's lattice arena
 };
 // workload counters of this launch, kept in LDS (thread 0 adds the block-uniform ones)
 enum { kCtTok = 0, kCtEarc, kCtXarc, kCtKept, kCtStored, kCtMaxAct, kCtBin0, kCtFrames };
@@ -1243,7 +1249,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       good[u] = kp[u]; no[u] = false; none[u] = 0;
       if (kp[u]) {
         if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
-        else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
+        else if (lat_base + (unsigned)ti[u] >= x.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
       }
       st[u] = cr[u].x; cb[u] = cr[u].y; pv[u] = cr[u].z; ar[u] = cr[u].w;
       if (x.c.cost_offset) cb[u] = __float_as_int(canon(__int_as_float(cr[u].y) - cut.best));
@@ -1275,7 +1281,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       good[u] = kp[u]; no[u] = false; none[u] = 0;
       if (kp[u]) {
         if (ti[u] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[u] = false; }
-        else if (lat_base + (unsigned)ti[u] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
+        else if (lat_base + (unsigned)ti[u] >= x.lat_cap) { atomicOr(&sm.status, kStLattice); good[u] = false; }
       }
       st[u] = q[u].x; cb[u] = __float_as_int(nc[u]); pv[u] = i0 + u * kBlock + tid;
       ar[u] = 2 * (int)((unsigned)q[u].x & x.g.blk_mask) + 1;     // the self-loop: the unit after the header
@@ -1290,7 +1296,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     sm.ctr[kCtKept] += min(n_emit, x.c.qcap);
   }
   if (tid < kRegions) sm.n_reg[tid] = 0;
-  if (x.c.frame_best && tid == 0) {              // the lattice kernel needs it for links across this frame's boundary
+  if (x.c.frame_best && tid == 0 && x.s.frame + 1 <= x.c.max_frames) {   // the lattice kernel needs it for links across this frame's boundary
     const size_t chan = (size_t)(x.frame_off - x.c.frame_off) / (size_t)(x.c.max_frames + 2);
     x.c.frame_best[chan * (size_t)(x.c.max_frames + 1) + (size_t)x.s.frame + 1] = n_emit > 0 ? cut.best : 0.0f;
   }
@@ -1446,7 +1452,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
             unsigned sl = (hash_state(tkey) >> 6) & kTabMask;
             // (a token that did not fit the lattice arena was never written: the channel stops after
             // this frame, and its queue position must not be looked at)
-            const bool real = vi < n_have && lat_base + (unsigned)tok < x.c.lat_cap;
+            const bool real = vi < n_have && lat_base + (unsigned)tok < x.lat_cap;
             int probes = 0, key = real ? t.keys[sl] : kKeyEmpty;
             while (key != tkey && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
             if (key == tkey && real) {
@@ -1523,7 +1529,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
             good[k] = fresh[k]; no[k] = 0;
             if (fresh[k]) {
               if (ni[k] >= x.c.qcap) { atomicOr(&sm.status, kStCapacity); good[k] = false; }
-              else if (lat_base + (unsigned)ni[k] >= x.c.lat_cap) { atomicOr(&sm.status, kStLattice); good[k] = false; }
+              else if (lat_base + (unsigned)ni[k] >= x.lat_cap) { atomicOr(&sm.status, kStLattice); good[k] = false; }
             }
             cb[k] = rec[k].y; pv[k] = rec[k].z; ar[k] = rec[k].w; nx[k] = rec[k].x;
           }
@@ -1567,13 +1573,15 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
   if (x.c.tokrec) {                              // lattice output wants the closed set's final records
     int2 *rec = x.c.tokrec + (x.lat - x.c.lattice);
     for (int i = tid; i < n; i += kBlock)
-      if (lat_base + (unsigned)i < x.c.lat_cap) { const int2 q = NQ[i]; rec[lat_base + i] = make_int2(key_of(q.x), q.y); }
+      if (lat_base + (unsigned)i < x.lat_cap) { const int2 q = NQ[i]; rec[lat_base + i] = make_int2(key_of(q.x), q.y); }
   }
   __syncthreads();
   if (tid == 0) {
-    x.frame_off[f] = lat_base;
-    x.frame_off[f + 1] = lat_base + (unsigned)n;
-    if (x.dig_sum) { x.dig_sum[f] = sm.red64; x.dig_cnt[f] = n; }
+    const int F = x.c.max_frames + 2;            // the per-frame tables are rings (a recycled channel outlives them)
+    x.frame_off[f % F] = lat_base;
+    x.frame_off[(f + 1) % F] = lat_base + (unsigned)n;
+    x.c.frame_ep[(x.frame_off - x.c.frame_off) + f % F] = x.s.lat_epoch;
+    if (x.dig_sum && f <= x.c.max_frames) { x.dig_sum[f] = sm.red64; x.dig_cnt[f] = n; }
     sm.ctr[kCtStored] += n;
     sm.red64 = 0; sm.n_win = 0; sm.n_next = 0; sm.n_wl_next = 0;
     sm.best_ord = kOrdNone;
@@ -1650,20 +1658,31 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
   int *pwords = inc ? x.c.path_words + chan * (size_t)x.c.max_words : nullptr;
   if (tid == 0) {
     int nw = 0, f_stop = 0, w_stop = 0;
-    bool broken = false;
+    bool broken = false, gone = false;
+    const int F = x.c.max_frames + 2, FM = x.c.max_frames + 1;   // the per-frame tables are rings
+    const int *fep = x.c.frame_ep + (x.frame_off - x.c.frame_off);
     for (int pass = one_walk ? 1 : 0; pass < 2; ++pass) {
       int f = x.s.frame, i = sm.sel_idx, k = 0;
       for (unsigned step = 0;; ++step) {
         // every chain ends at the start token; the bounds only guard against a damaged lattice
-        if (f < 0 || i < 0 || step > x.s.lat_used) { broken = true; break; }
-        const unsigned li = x.frame_off[f] + (unsigned)i;
-        if (li >= x.s.lat_used) { broken = true; break; }
+        if (f < 0 || i < 0 || step > 0x40000000u) { broken = true; break; }
+        const unsigned off = x.frame_off[f % F];
+        if (x.c.recycle) {
+          // is the frame still there?  Its slot of the per-frame tables, and its tokens: stored in
+          // this epoch, or in the one before at a place the write position has not reached again
+          const int ep = fep[f % F];
+          const bool here = x.s.frame - f <= x.c.max_frames &&
+                            (ep == x.s.lat_epoch || (ep == x.s.lat_epoch - 1 && off >= x.s.lat_used));
+          if (!here) { gone = true; break; }
+        } else if (off + (unsigned)i >= x.s.lat_used) { broken = true; break; }
+        const unsigned li = off + (unsigned)i;
+        if (li >= x.lat_cap) { broken = true; break; }
         const int2 bp = x.lat[li];
         if (bp.y < 0) break;
         const bool emitting = !((unsigned)bp.y & kArcEps);
         if (inc && emitting) {
-          if (f <= x.s.path_frames && ptok[f] == i) { f_stop = f; w_stop = pnw[f]; break; }   // the old path from here on
-          ptok[f] = i; pnw[f] = k;                  // k: words after this arc; turned into words up to it below
+          if (f <= x.s.path_frames && ptok[f % FM] == i) { f_stop = f; w_stop = pnw[f % FM]; break; }   // the old path from here on
+          ptok[f % FM] = i; pnw[f % FM] = k;        // k: words after this arc; turned into words up to it below
         }
         const int ol = x.g.unit[(unsigned)bp.y & kArcMask].w;
         if (ol != 0) {
@@ -1680,6 +1699,9 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     if (any_final) flags |= WFST_FLAG_REACHED_FINAL;
     if (nw > a.max_words) flags |= WFST_FLAG_TRUNCATED;
     if (broken) { flags |= WFST_FLAG_CAPACITY; nw = 0; }
+    // a recycled arena no longer holds the frames this path runs through before it meets the path of
+    // the previous result (results were asked for too rarely for the arena's size)
+    if (gone) { flags |= WFST_FLAG_LATTICE_OVERFLOW; nw = 0; broken = true; }
     a.nwords[io] = min(nw, a.max_words);
     a.cost[io] = x.c.cost_offset ? (float)((double)ord2f((unsigned)(best >> 32)) + x.s.offset) : ord2f((unsigned)(best >> 32));
     a.flags[io] = flags;
@@ -1694,7 +1716,8 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
     const int k_new = nw - w_stop;
     if (inc) {
       // marks of the frames walked: words after the arc -> words up to and including it
-      for (int f = sm.trace_from + 1 + tid; f <= x.s.frame; f += kBlock) pnw[f] = nw - pnw[f];
+      const int FM = x.c.max_frames + 1;
+      for (int f = sm.trace_from + 1 + tid; f <= x.s.frame; f += kBlock) pnw[f % FM] = nw - pnw[f % FM];
       for (int p = w_stop + tid; p < min(nw, a.max_words); p += kBlock) pwords[p] = ring[(k_new - 1 - (p - w_stop)) % a.max_words];
       __syncthreads();
       for (int p = tid; p < min(nw, a.max_words); p += kBlock) words[p] = pwords[p];
@@ -1715,7 +1738,8 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.win = c.win + (size_t)ch * c.win_cap;
   x.q0 = c.queue + (size_t)ch * 2 * c.qcap;
   x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
-  x.lat = c.lattice + (size_t)ch * c.lat_cap;
+  x.lat = c.lattice + c.lat_start[ch];
+  x.lat_cap = uni(c.lat_capn[ch]);
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
   x.dig_cnt = c.dig_cnt ? c.dig_cnt + (size_t)ch * (c.max_frames + 1) : nullptr;
@@ -1723,7 +1747,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
   x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio); x.s.offset = uni(x.s.offset);
-  x.s.boost_n = uni(x.s.boost_n); x.s.boost_states = uni(x.s.boost_states);
+  x.s.boost_n = uni(x.s.boost_n); x.s.boost_states = uni(x.s.boost_states); x.s.lat_epoch = uni(x.s.lat_epoch);
   if (x.s.boost_n > 0)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
       sm.bk[i] = c.boost_keys[(size_t)ch * kBoostSlots + i];
@@ -1747,6 +1771,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   if (a.mode & kModeInit) {
     // start token, closed over epsilon arcs with best = 0 and no bin limit
     x.s.frame = 0; x.s.n_tok = 0; x.s.cur = 0; x.s.status = 0; x.s.lat_used = 0; x.s.offset = 0.0; x.s.path_frames = 0;
+    x.s.lat_epoch = 0;
     x.s.beam = a.beam; x.s.scale = a.scale; x.s.max_active = a.max_active; x.s.sel_ratio = 1.5f;
     int2 *NQ = x.q0 + c.qcap;
     if (tid == 0) { sm.n_next = 1; sm.n_in = 1; sm.n_emit = 1; }
@@ -1764,7 +1789,10 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   const long long ll0 = (long long)io * a.ll_stride;
   for (int t = 0; t < nfr; ++t) {
     if (stop || x.s.status) break;
-    if (x.s.frame >= c.max_frames) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
+    if (x.s.frame >= c.max_frames && !c.recycle) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }
+    // a recycled arena is a ring over whole frames: a frame's tokens (at most qcap) never straddle
+    // its end, the write position goes back to the start instead and the epoch counts that
+    if (c.recycle && x.s.lat_used + (unsigned)c.qcap > x.lat_cap) { x.s.lat_used = 0; x.s.lat_epoch++; }
     {
       // the frame's acoustic costs; 16-bit log-likelihoods are widened exactly
       const long long r0 = ll0 + (long long)t * a.V;
@@ -1809,7 +1837,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     // copies, so that the pointers of the frame loop above never live in memory: only then
     // does the compiler know they are global and keep them in registers.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
-    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s, nullptr};
+    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s, nullptr, x.lat_cap};
     if (tid == 0) sm.path_frames = x.s.path_frames;
     select_and_trace(x2, a2, io);
     if (tid == 0) x.s.path_frames = sm.path_frames;      // thread 0's copy is the one that is stored
@@ -1982,7 +2010,7 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
   const int tid = threadIdx.x;
   const int t = blockIdx.x;
   const unsigned *off = c.frame_off + (size_t)a.ch * (c.max_frames + 2);
-  const int2 *rec = c.tokrec + (size_t)a.ch * c.lat_cap;
+  const int2 *rec = c.tokrec + c.lat_start[a.ch];
   const unsigned o1 = off[t], n1 = off[t + 1] - o1;
   const unsigned o0 = t ? off[t - 1] : 0u, n0 = t ? o1 - o0 : 0u;
   // the set's tokens, by state id
@@ -2084,7 +2112,18 @@ struct wfst_decoder {
   std::vector<int> state_of_blk;       // inverse, built when a debug call first needs it
   std::vector<unsigned> h_off;         // wfst_get_lattice: channel state, counters and frame offsets on the host
   unsigned *h_pinned = nullptr;        // the same for wfst_get_lattice_noalloc: pinned, allocated at create
-  hipEvent_t ev0 = nullptr, ev1 = nullptr; bool timed = false;
+  // batch slots: wfst_decode_batch_slot calls on different slots may be in flight together
+  int n_slots = 1, slot_channels = 0;
+  std::vector<hipEvent_t> ev0, ev1;    // per slot (+ one pair for the calls that name channels): around the last kernel
+  std::vector<char> timed;
+  // lattice memory: every slot's channels share one pool, shared out equally (streaming) or by
+  // utterance length (a batch decode)
+  unsigned long long *d_lat_start = nullptr; unsigned *d_lat_capn = nullptr;
+  std::vector<unsigned long long> eq_start; std::vector<unsigned> eq_capn;       // the equal shares
+  std::vector<unsigned long long> h_start[kRing]; std::vector<unsigned> h_capn[kRing];   // staging
+  int part_pos = 0, last_timed = -1;
+  std::vector<char> slot_by_length;    // the slot's pool is currently shared out by length
+  std::vector<char> chan_ready;        // the channel has been initialised since its arena was last moved
   std::string err;
 };
 
@@ -2250,8 +2289,23 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &c.win, N * c.win_cap))) return rc;
   if ((rc = dev_alloc(d, &c.queue, N * 2 * c.qcap))) return rc;
   if ((rc = dev_alloc(d, &c.wl, N * 2 * c.qcap))) return rc;
+  c.recycle = o.recycle_lattice ? 1 : 0;
+  if (c.recycle && (int64_t)c.lat_cap < 2LL * c.qcap)
+    return fail(d, WFST_ERR_INVALID_ARG, "recycle_lattice needs room for two full token sets per channel: at least " +
+                                             std::to_string(16LL * c.qcap) + " lattice bytes per channel");
   if ((rc = dev_alloc(d, &c.lattice, N * (size_t)c.lat_cap))) return rc;
   if ((rc = dev_alloc(d, &c.frame_off, N * (size_t)(c.max_frames + 2)))) return rc;
+  if ((rc = dev_alloc(d, &c.frame_ep, N * (size_t)(c.max_frames + 2)))) return rc;
+  HIP_TRY(d, hipMemset(c.frame_ep, 0, N * (size_t)(c.max_frames + 2) * sizeof(int)));
+  if ((rc = dev_alloc(d, &d->d_lat_start, N))) return rc;
+  if ((rc = dev_alloc(d, &d->d_lat_capn, N))) return rc;
+  d->eq_start.resize(N); d->eq_capn.assign(N, c.lat_cap);
+  for (size_t ch = 0; ch < N; ++ch) d->eq_start[ch] = (unsigned long long)ch * c.lat_cap;
+  HIP_TRY(d, hipMemcpy(d->d_lat_start, d->eq_start.data(), N * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  HIP_TRY(d, hipMemcpy(d->d_lat_capn, d->eq_capn.data(), N * sizeof(unsigned), hipMemcpyHostToDevice));
+  c.lat_start = d->d_lat_start; c.lat_capn = d->d_lat_capn;
+  d->slot_by_length.assign((size_t)d->n_slots, 0);
+  d->chan_ready.assign(N, 0);
   if (o.keep_token_records && (rc = dev_alloc(d, &c.tokrec, N * (size_t)c.lat_cap))) return rc;
   c.cost_offset = o.cost_offset ? 1 : 0;
   c.max_words = o.max_words;
@@ -2291,8 +2345,10 @@ int alloc_channels(wfst_decoder *d) {
 }
 
 // Stage {channel, frames, io row} triples and launch one workgroup per entry.
+// `slot`: whose pair of timing events brackets the kernel (n_slots = the calls that name channels).
 int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int> &nfr,
-           const std::vector<int> &io, LaunchArgs a, hipStream_t st) {
+           const std::vector<int> &io, LaunchArgs a, hipStream_t st, int slot_id = -1) {
+  if (slot_id < 0) slot_id = d->n_slots;
   const int n = (int)chan.size();
   if (n == 0) return WFST_OK;
   const size_t N = (size_t)d->opts.max_channels;
@@ -2305,11 +2361,47 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
   d->ring_pos = (d->ring_pos + 1) % wfst_decoder::kRing;
   HIP_TRY(d, hipMemcpyAsync(slot, pack.data(), pack.size() * sizeof(int), hipMemcpyHostToDevice, st));
   a.chan = slot; a.nfr = slot + n; a.io = slot + 2 * n;
-  HIP_TRY(d, hipEventRecord(d->ev0, st));
+  HIP_TRY(d, hipEventRecord(d->ev0[slot_id], st));
   hipLaunchKernelGGL(wfst_channel_kernel, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
   HIP_TRY(d, hipGetLastError());
-  HIP_TRY(d, hipEventRecord(d->ev1, st));
-  d->timed = true;
+  HIP_TRY(d, hipEventRecord(d->ev1[slot_id], st));
+  d->timed[slot_id] = 1;
+  d->last_timed = slot_id;
+  return WFST_OK;
+}
+
+// Share out the lattice pool of a slot among its first n channels in proportion to want[] (frames
+// each will store) -- or, with want == nullptr, equally among all its channels -- and send the
+// new placement to the device on `st`.  The arenas of the slot's channels move: none of them is
+// initialised any more.
+int partition_slot(wfst_decoder *d, int slot, const int32_t *want, int n, hipStream_t st) {
+  const int sc = d->slot_channels, ch0 = slot * sc;
+  std::vector<unsigned long long> &hs = d->h_start[d->part_pos]; std::vector<unsigned> &hc = d->h_capn[d->part_pos];
+  d->part_pos = (d->part_pos + 1) % wfst_decoder::kRing;
+  hs.assign(d->eq_start.begin() + ch0, d->eq_start.begin() + ch0 + sc);
+  hc.assign(d->eq_capn.begin() + ch0, d->eq_capn.begin() + ch0 + sc);
+  if (want) {
+    const unsigned long long pool = (unsigned long long)sc * d->c.lat_cap;
+    unsigned long long total = 0, at = d->eq_start[ch0];
+    for (int b = 0; b < n; ++b) total += (unsigned long long)want[b] + 2;
+    for (int b = 0; b < sc; ++b) {
+      unsigned long long cap = b < n ? (unsigned long long)((long double)pool * ((unsigned long long)want[b] + 2) / (long double)total) : 0;
+      cap = std::min<unsigned long long>(cap, 0x7ffffffeull);
+      hs[b] = at; hc[b] = (unsigned)cap; at += cap;
+    }
+  }
+  HIP_TRY(d, hipMemcpyAsync(d->d_lat_start + ch0, hs.data(), sc * sizeof(unsigned long long), hipMemcpyHostToDevice, st));
+  HIP_TRY(d, hipMemcpyAsync(d->d_lat_capn + ch0, hc.data(), sc * sizeof(unsigned), hipMemcpyHostToDevice, st));
+  d->slot_by_length[slot] = want ? 1 : 0;
+  std::fill(d->chan_ready.begin() + ch0, d->chan_ready.begin() + ch0 + sc, 0);
+  return WFST_OK;
+}
+
+// Before a channel is initialised on its own: its slot's pool must be shared out equally.
+int ready_for_init(wfst_decoder *d, int ch, hipStream_t st) {
+  const int slot = ch / d->slot_channels;
+  if (d->slot_by_length[slot]) { const int rc = partition_slot(d, slot, nullptr, 0, st); if (rc) return rc; }
+  d->chan_ready[ch] = 1;
   return WFST_OK;
 }
 
@@ -2471,7 +2563,7 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
 }  // namespace
 
 namespace {
-int decode_batch_impl(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+int decode_batch_impl(wfst_decoder *d, int slot, const void *loglikes, const int32_t *lengths, int32_t B,
                       int32_t T, int32_t V, float beam, int32_t max_active,
                       const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream,
                       int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
@@ -2493,13 +2585,21 @@ int32_t wfst_decoder_create(const wfst_graph_csr *graph, const wfst_opts *opts, 
   std::string why; int64_t Ae = 0, Ax = 0;
   int rc = validate_graph(graph, why, Ae, Ax);
   if (rc) return fail(nullptr, rc, why);
+  if (opts->batch_slots < 0 || (opts->batch_slots > 1 && opts->max_channels % opts->batch_slots != 0))
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "batch_slots must be >= 0 and divide max_channels");
+  if (opts->recycle_lattice && opts->keep_token_records)
+    return fail(nullptr, WFST_ERR_INVALID_ARG, "recycle_lattice and keep_token_records exclude each other (a lattice needs every frame)");
   wfst_decoder *d = new wfst_decoder();
   d->opts = *opts; d->V = graph->num_classes;
+  d->n_slots = std::max(1, opts->batch_slots); d->slot_channels = opts->max_channels / d->n_slots;
   rc = upload_graph(d, graph);
   if (!rc) rc = alloc_channels(d);
-  if (!rc && (hipEventCreate(&d->ev0) != hipSuccess || hipEventCreate(&d->ev1) != hipSuccess)) {
-    d->err = "hipEventCreate failed"; rc = WFST_ERR_HIP;
-  }
+  d->ev0.assign((size_t)d->n_slots + 1, nullptr); d->ev1.assign((size_t)d->n_slots + 1, nullptr);
+  d->timed.assign((size_t)d->n_slots + 1, 0);
+  for (int i = 0; !rc && i <= d->n_slots; ++i)
+    if (hipEventCreate(&d->ev0[i]) != hipSuccess || hipEventCreate(&d->ev1[i]) != hipSuccess) {
+      d->err = "hipEventCreate failed"; rc = WFST_ERR_HIP;
+    }
   if (rc) { g_create_err = d->err; wfst_decoder_destroy(d); return rc; }
   {
     // learn this device's address of the static scratch now rather than in the first call that needs it
@@ -2516,8 +2616,8 @@ int32_t wfst_decoder_destroy(wfst_decoder *d) {
   for (void *p : d->allocs) (void)hipFree(p);
   if (d->h_boost) (void)hipHostFree(d->h_boost);
   if (d->h_pinned) (void)hipHostFree(d->h_pinned);
-  if (d->ev0) (void)hipEventDestroy(d->ev0);
-  if (d->ev1) (void)hipEventDestroy(d->ev1);
+  for (hipEvent_t e : d->ev0) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : d->ev1) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : d->boost_ev) if (e) (void)hipEventDestroy(e);
   delete d;
   return WFST_OK;
@@ -2534,7 +2634,7 @@ int32_t wfst_decode_batch_boosted(wfst_decoder *d, const float *loglikes, const 
                                   int32_t T, int32_t V, float beam, int32_t max_active,
                                   const wfst_boost_table *const *boosts, void *stream,
                                   int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
-  return decode_batch_impl(d, loglikes, lengths, B, T, V, beam, max_active, boosts, nullptr, stream, words, nwords,
+  return decode_batch_impl(d, 0, loglikes, lengths, B, T, V, beam, max_active, boosts, nullptr, stream, words, nwords,
                            cost, flags);
 }
 
@@ -2542,7 +2642,16 @@ int32_t wfst_decode_batch_boost_fst(wfst_decoder *d, const float *loglikes, cons
                                     int32_t T, int32_t V, float beam, int32_t max_active,
                                     const wfst_boost_fst *const *fsts, void *stream,
                                     int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
-  return decode_batch_impl(d, loglikes, lengths, B, T, V, beam, max_active, nullptr, fsts, stream, words, nwords,
+  return decode_batch_impl(d, 0, loglikes, lengths, B, T, V, beam, max_active, nullptr, fsts, stream, words, nwords,
+                           cost, flags);
+}
+
+int32_t wfst_decode_batch_slot(wfst_decoder *d, int32_t slot, const void *loglikes, const int32_t *lengths, int32_t B,
+                               int32_t T, int32_t V, float beam, int32_t max_active,
+                               const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream,
+                               int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
+  if (d && boosts && fsts) return fail(d, WFST_ERR_INVALID_ARG, "give word-boost tables or boosting acceptors, not both");
+  return decode_batch_impl(d, slot, loglikes, lengths, B, T, V, beam, max_active, boosts, fsts, stream, words, nwords,
                            cost, flags);
 }
 
@@ -2553,6 +2662,8 @@ int32_t wfst_init_channel_boost_fst(wfst_decoder *d, int32_t ch, float beam, int
   if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
   const int rcb = set_boost(d, ch, fst, static_cast<hipStream_t>(stream));
   if (rcb) return rcb;
+  const int rcr = ready_for_init(d, ch, static_cast<hipStream_t>(stream));
+  if (rcr) return rcr;
   LaunchArgs a{};
   a.V = d->V; a.mode = kModeInit;
   a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
@@ -2562,48 +2673,61 @@ int32_t wfst_init_channel_boost_fst(wfst_decoder *d, int32_t ch, float beam, int
 }  // extern "C"
 
 namespace {
-int decode_batch_impl(wfst_decoder *d, const float *loglikes, const int32_t *lengths, int32_t B,
+int decode_batch_impl(wfst_decoder *d, int slot, const void *loglikes, const int32_t *lengths, int32_t B,
                       int32_t T, int32_t V, float beam, int32_t max_active,
                       const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream,
                       int32_t *words, int32_t *nwords, float *cost, int32_t *flags) {
   if (!d) return WFST_ERR_INVALID_ARG;
+  if (slot < 0 || slot >= d->n_slots) return fail(d, WFST_ERR_INVALID_ARG, "batch slot out of range");
+  const int ch0 = slot * d->slot_channels;
   if (B < 0 || T < 0) return fail(d, WFST_ERR_INVALID_ARG, "negative B or T");
   if (B == 0) return WFST_OK;              // nothing to decode; pointers may be null
   if (!lengths || !words || !nwords || !cost || !flags || (T > 0 && !loglikes))
     return fail(d, WFST_ERR_INVALID_ARG, "null argument");
   if (V != d->V) return fail(d, WFST_ERR_INVALID_ARG, "V differs from the graph's num_classes");
   if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
-  if (B > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "batch larger than max_channels");
+  if (B > d->slot_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "batch larger than the channels of a slot (max_channels / batch_slots)");
   for (int b = 0; b < B; ++b)
     if (lengths[b] < 0 || lengths[b] > T || lengths[b] > d->opts.max_frames_per_channel)
       return fail(d, WFST_ERR_INVALID_ARG, "lengths[" + std::to_string(b) + "] outside [0, min(T, max_frames_per_channel)]");
   hipStream_t st = static_cast<hipStream_t>(stream);
   for (int b = 0; b < B; ++b) {
-    const int rcb = fsts ? set_boost(d, b, fsts[b], st) : set_boost(d, b, boosts ? boosts[b] : nullptr, st);
+    const int rcb = fsts ? set_boost(d, ch0 + b, fsts[b], st) : set_boost(d, ch0 + b, boosts ? boosts[b] : nullptr, st);
     if (rcb) return rcb;
   }
+  // the slot's lattice memory: in proportion to the utterances' lengths if the decoder was created
+  // for that, else the equal shares (put back if a by-length batch left them otherwise)
+  if (d->opts.lattice_by_length && !d->c.recycle) {
+    const int rcp = partition_slot(d, slot, lengths, B, st);
+    if (rcp) return rcp;
+  } else if (d->slot_by_length[slot]) {
+    const int rcp = partition_slot(d, slot, nullptr, 0, st);
+    if (rcp) return rcp;
+  }
+  for (int b = 0; b < B; ++b) d->chan_ready[ch0 + b] = 1;
   // longest utterances first: workgroups are dispatched in order, so the long ones start
   // at once and the short ones fill in behind them
-  std::vector<int> order(B), nfr(B);
+  std::vector<int> order(B), nfr(B), chan(B);
   std::iota(order.begin(), order.end(), 0);
   std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return lengths[x] > lengths[y]; });
-  for (int i = 0; i < B; ++i) nfr[i] = lengths[order[i]];
+  for (int i = 0; i < B; ++i) { nfr[i] = lengths[order[i]]; chan[i] = ch0 + order[i]; }
   const bool host_out = d->opts.outputs_on_host != 0;
   LaunchArgs a{};
   a.ll = loglikes; a.ll_stride = (long long)T * V; a.V = V; a.ll_dtype = d->opts.loglike_dtype;
   a.mode = kModeInit | kModeFinal; a.finalize = 1;
   a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
-  a.words = host_out ? d->o_words : words; a.nwords = host_out ? d->o_nwords : nwords;
-  a.cost = host_out ? d->o_cost : cost;    a.flags = host_out ? d->o_flags : flags;
+  // (host outputs are staged in device memory per channel, so the slots do not share any of it)
+  const size_t mw = (size_t)d->opts.max_words;
+  a.words = host_out ? d->o_words + ch0 * mw : words; a.nwords = host_out ? d->o_nwords + ch0 : nwords;
+  a.cost = host_out ? d->o_cost + ch0 : cost;         a.flags = host_out ? d->o_flags + ch0 : flags;
   a.max_words = d->opts.max_words;
-  int rc = launch(d, order, nfr, order, a, st);
+  int rc = launch(d, chan, nfr, order, a, st, slot);
   if (rc) return rc;
   if (host_out) {
-    const size_t mw = (size_t)d->opts.max_words;
-    HIP_TRY(d, hipMemcpyAsync(words, d->o_words, B * mw * sizeof(int), hipMemcpyDeviceToHost, st));
-    HIP_TRY(d, hipMemcpyAsync(nwords, d->o_nwords, B * sizeof(int), hipMemcpyDeviceToHost, st));
-    HIP_TRY(d, hipMemcpyAsync(cost, d->o_cost, B * sizeof(float), hipMemcpyDeviceToHost, st));
-    HIP_TRY(d, hipMemcpyAsync(flags, d->o_flags, B * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(words, d->o_words + ch0 * mw, B * mw * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(nwords, d->o_nwords + ch0, B * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(cost, d->o_cost + ch0, B * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(flags, d->o_flags + ch0, B * sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(d, hipStreamSynchronize(st));
     for (int b = 0; b < B; ++b) {
       if (flags[b] & WFST_FLAG_LATTICE_OVERFLOW) return fail(d, WFST_ERR_LATTICE_OVERFLOW, "utterance " + std::to_string(b) + " ran out of lattice memory");
@@ -2624,6 +2748,8 @@ int32_t wfst_init_channel(wfst_decoder *d, int32_t ch, float beam, int32_t max_a
   if (!valid_prune(beam, max_active)) return fail(d, WFST_ERR_INVALID_ARG, "beam must be >= 0 and max_active >= 1");
   const int rcb = set_boost(d, ch, boost, static_cast<hipStream_t>(stream));
   if (rcb) return rcb;
+  const int rcr = ready_for_init(d, ch, static_cast<hipStream_t>(stream));
+  if (rcr) return rcr;
   LaunchArgs a{};
   a.V = d->V; a.mode = kModeInit;
   a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
@@ -2648,6 +2774,8 @@ int32_t wfst_init_channels(wfst_decoder *d, const int32_t *channels, int32_t n, 
   for (int i = 0; i < n; ++i) {
     const int rcb = set_boost(d, chan[i], boosts ? boosts[i] : nullptr, static_cast<hipStream_t>(stream));
     if (rcb) return rcb;
+    const int rcr = ready_for_init(d, chan[i], static_cast<hipStream_t>(stream));
+    if (rcr) return rcr;
   }
   LaunchArgs a{};
   a.V = d->V; a.mode = kModeInit;
@@ -2668,6 +2796,7 @@ int32_t wfst_advance_chunk(wfst_decoder *d, const int32_t *channels, int32_t n, 
     if (channels[i] < 0 || channels[i] >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
     if (seen[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel listed twice");
     seen[channels[i]] = 1;
+    if (!d->chan_ready[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel " + std::to_string(channels[i]) + " has not been initialised (or a batch decode has since taken its slot's lattice memory)");
     if (nframes[i] < 0 || nframes[i] > C) return fail(d, WFST_ERR_INVALID_ARG, "nframes outside [0, C]");
     chan[i] = channels[i]; nfr[i] = nframes[i]; io[i] = i;
   }
@@ -2832,10 +2961,19 @@ int32_t wfst_debug_phase_ticks(wfst_decoder *d, int64_t ticks[16], int32_t reset
 int64_t wfst_device_bytes(const wfst_decoder *d) { return d ? d->dev_bytes : 0; }
 
 float wfst_last_kernel_ms(wfst_decoder *d) {
-  if (!d || !d->timed) return -1.0f;
-  if (hipEventSynchronize(d->ev1) != hipSuccess) return -1.0f;
+  if (!d || d->last_timed < 0) return -1.0f;
+  const int s = d->last_timed;
+  if (hipEventSynchronize(d->ev1[s]) != hipSuccess) return -1.0f;
   float ms = -1.0f;
-  if (hipEventElapsedTime(&ms, d->ev0, d->ev1) != hipSuccess) return -1.0f;
+  if (hipEventElapsedTime(&ms, d->ev0[s], d->ev1[s]) != hipSuccess) return -1.0f;
+  return ms;
+}
+
+float wfst_slot_kernel_ms(wfst_decoder *d, int32_t slot) {
+  if (!d || slot < 0 || slot >= d->n_slots || !d->timed[slot]) return -1.0f;
+  if (hipEventSynchronize(d->ev1[slot]) != hipSuccess) return -1.0f;
+  float ms = -1.0f;
+  if (hipEventElapsedTime(&ms, d->ev0[slot], d->ev1[slot]) != hipSuccess) return -1.0f;
   return ms;
 }
 

@@ -888,3 +888,111 @@ def test_partial_results_after_every_chunk_equal_the_oracle_on_the_prefix(torch_
                                  max_words=max_words + 3, finalize=False)
                     assert w.tolist() == r.words.tolist() and f == r.flags
         dec.close()
+
+
+# ------------------------------------------------------------------------------- batch slots, shared lattice memory
+def test_batches_in_flight_on_one_decoder(torch_cuda, c2, c2_refs):
+    """One decoder, three batch slots: three batches decoded at the same time on three streams,
+    the slot's lattice memory shared out by utterance length (sized for the mean length); every
+    result equals the oracle's.  Then streaming on a slot a batch decode has used."""
+    from paper_2311_04996_amd import Decoder, WfstError
+    torch = torch_cuda
+    B, T = 8, int(c2.lengths[:24].max())
+    mean_frames = float(c2.lengths[:24].mean())
+    dec = Decoder(c2.graph, max_channels=3 * B, max_frames=T, max_active_hint=c2.max_active, record_digests=True,
+                  batch_slots=3, lattice_by_length=True,
+                  lattice_bytes_per_channel=int(8 * 1.35 * 8200 * (mean_frames + 2)))
+    plain = Decoder(c2.graph, max_channels=B, max_frames=T, max_active_hint=c2.max_active)
+    assert dec.device_bytes() < 3 * plain.device_bytes() * 0.75      # shared graph, arenas for the mean length
+    plain.close()
+    lls = [torch.from_numpy(np.ascontiguousarray(c2.loglikes[k * B:(k + 1) * B, :T])).cuda() for k in range(3)]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    for rep in range(2):
+        outs = [dec.decode_batch(lls[k], c2.lengths[k * B:(k + 1) * B], c2.beam, c2.max_active, stream=streams[k], slot=k)
+                for k in range(3)]
+        torch.cuda.synchronize()
+        for k, out in enumerate(outs):
+            words, nwords, cost, flags = (x.cpu().numpy() for x in out)
+            for b in range(B):
+                r = c2_refs[k * B + b]
+                assert words[b, :nwords[b]].tolist() == r.words.tolist() and cost[b] == np.float32(r.cost) and flags[b] == r.flags
+                cnt, dig = dec.debug_frame_digests(k * B + b)
+                assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all(), (rep, k, b)
+            assert dec.slot_kernel_ms(k) > 0
+    # a channel of slot 1 as a stream: its slot's memory goes back to equal shares, the other channels
+    # of that slot must be initialised again before use
+    from oracle import Oracle
+    ch = B + 2
+    dec.init_channel(ch, c2.beam, c2.max_active)
+    n = 48
+    dec.advance_chunk([ch], lls[0][:1, :n].contiguous(), [n])
+    w, c, f = dec.get_partial(ch, finalize=True)
+    r = Oracle(c2.graph).decode(c2.loglikes[0], length=n, beam=c2.beam, max_active=c2.max_active)
+    assert w.tolist() == r.words.tolist() and c == np.float32(r.cost) and f == r.flags
+    with pytest.raises(WfstError) as e:
+        dec.advance_chunk([B + 3], lls[0][:1, :n].contiguous(), [n])
+    assert e.value.code == -5
+    with pytest.raises(WfstError) as e:                          # a batch larger than a slot
+        dec.decode_batch(torch.cat([lls[0], lls[1]]), c2.lengths[:2 * B], c2.beam, c2.max_active, slot=0)
+    assert e.value.code == -5
+    dec.close()
+
+
+# ------------------------------------------------------------------------------- streams of any length
+def test_recycled_lattice_stream_ten_times_the_window(torch_cuda, c2):
+    """recycle_lattice: a channel streams 2,000 frames through a window of 200 frames (per-frame
+    tables) and a lattice arena of about 250 frames of tokens, in chunks of 16 with a partial
+    result after every chunk.  The partials (and the final result) equal the oracle's on the
+    prefix, and no overflow is flagged: the arena is a ring behind what results still need."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder, FLAG_LATTICE_OVERFLOW, FLAG_CAPACITY
+    torch = torch_cuda
+    window, total, chunk = 200, 2000, 16
+    utts = [4, 11]
+    lls = [np.concatenate([c2.loglikes[u, :c2.lengths[u]]] * (total // int(c2.lengths[u]) + 1))[:total] for u in utts]
+    o = Oracle(c2.graph)
+    checkpoints = [16, 208, 400, 992, 1600, 2000]
+    with ThreadPoolExecutor(16) as ex:
+        refs = list(ex.map(lambda a: o.decode(lls[a[0]], length=a[1], beam=c2.beam, max_active=c2.max_active,
+                                              max_words=512, finalize=False),
+                           [(i, n) for i in range(2) for n in checkpoints]))
+    refs = {(i, n): r for (i, n), r in zip([(i, n) for i in range(2) for n in checkpoints], refs)}
+    dec = Decoder(c2.graph, max_channels=2, max_frames=window, max_words=512, max_active_hint=c2.max_active,
+                  recycle_lattice=True, lattice_bytes_per_channel=8 * 8200 * 250)
+    dev = torch.from_numpy(np.stack(lls)).cuda()
+    dec.init_channels([0, 1], c2.beam, c2.max_active)
+    for t0 in range(0, total, chunk):
+        n = min(chunk, total - t0)
+        dec.advance_chunk([0, 1], dev[:, t0:t0 + n].contiguous(), [n, n])
+        words, nwords, cost, flags = (x.cpu().numpy() for x in dec.get_partial_batch([0, 1], finalize=False))
+        assert not (flags & (FLAG_LATTICE_OVERFLOW | FLAG_CAPACITY)).any(), t0
+        if t0 + n in checkpoints:
+            for i in range(2):
+                r = refs[(i, t0 + n)]
+                assert words[i, :nwords[i]].tolist() == r.words.tolist(), (i, t0 + n)
+                assert cost[i] == np.float32(r.cost) and flags[i] == r.flags, (i, t0 + n)
+    assert len(refs[(0, total)].words) > 40
+    dec.close()
+
+
+def test_recycled_lattice_reports_a_result_asked_for_too_late(torch_cuda, c2):
+    """No result for longer than the ring holds: the traceback cannot reach the start any more, which
+    is reported as a flag (nothing faults); a decoder whose arena holds the stream is fine."""
+    from paper_2311_04996_amd import Decoder, FLAG_LATTICE_OVERFLOW, WfstError
+    torch = torch_cuda
+    total = 600
+    u = int(np.argmax(c2.lengths))
+    ll = torch.from_numpy(np.concatenate([c2.loglikes[u, :c2.lengths[u]]] * 2)[None, :total].copy()).cuda()
+    dec = Decoder(c2.graph, max_channels=1, max_frames=100, max_words=64, max_active_hint=c2.max_active,
+                  recycle_lattice=True, lattice_bytes_per_channel=8 * 8200 * 120)
+    dec.init_channel(0, c2.beam, c2.max_active)
+    for t0 in range(0, total, 100):
+        dec.advance_chunk([0], ll[:, t0:t0 + 100].contiguous(), [100])
+    w, c, f = dec.get_partial(0, finalize=False)
+    assert f & FLAG_LATTICE_OVERFLOW and len(w) == 0 and np.isfinite(c)
+    dec.close()
+    with pytest.raises(WfstError) as e:                       # too little memory for two token sets
+        Decoder(c2.graph, max_channels=1, max_frames=100, max_active_hint=c2.max_active, recycle_lattice=True,
+                lattice_bytes_per_channel=8 * 20000)
+    assert e.value.code == -1
