@@ -110,7 +110,10 @@ constexpr int kRegionBits = WFST_REGION_BITS;
 constexpr int kRegions = 1 << kRegionBits;    // candidate buffer regions (by destination hash)
 constexpr int kTabSlots = WFST_TAB;           // LDS recombination table (power of two)
 constexpr unsigned kTabMask = kTabSlots - 1;
-constexpr int kGroupTarget = kTabSlots * 12 / 16; // mean candidates reduced per table pass (load 0.75)
+#ifndef WFST_GT
+#define WFST_GT 12
+#endif
+constexpr int kGroupTarget = kTabSlots * WFST_GT / 16; // mean candidates reduced per table pass (load 0.75)
 #ifndef WFST_BOOST
 #define WFST_BOOST 2048
 #endif
@@ -774,6 +777,21 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
 }
 
 // ------------------------------------------------------------------ recombination in LDS
+// Probe sequence of a key in the LDS table: double hashing (an odd step from other hash bits visits
+// every slot of the power-of-two table).  At the loads the passes run at, an insert then takes
+// about half the probes of linear probing, and every probe is an LDS round trip.
+#ifndef WFST_STEP_SHIFT
+#define WFST_STEP_SHIFT 19
+#endif
+__device__ __forceinline__ unsigned probe_start(int key) { return (hash_state(key) >> 6) & kTabMask; }
+__device__ __forceinline__ unsigned probe_step(int key) {
+#ifdef WFST_LINEAR
+  return 1u;
+#else
+  return ((hash_state(key) >> WFST_STEP_SHIFT) | 1u) & kTabMask;
+#endif
+}
+
 // Lower the destination's table entry to this candidate if (cost, arc id) is smaller.
 // The value word carries the candidate's index, so the winner's record can be fetched
 // afterwards; exact cost ties are decided by the arc ids of the two records.
@@ -781,13 +799,14 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
 // (graph state, B state) pair; then the lower B state of the source token wins (src = its index).
 __device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc, int src, int idx) {
   TableLds &t = x.sm.u.t;
-  unsigned s = (hash_state(dst) >> 6) & kTabMask;
+  unsigned s = probe_start(dst);
+  const unsigned step = probe_step(dst);
   // one compare-and-swap per probe: it returns the slot's key, or claims the slot if it was free
   int old;
   for (int probes = 0;; ++probes) {
     old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
     if (old == kKeyEmpty || old == dst) break;
-    s = (s + 1) & kTabMask;
+    s = (s + step) & kTabMask;
     if (probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return -1; }   // table full
   }
   const unsigned oc = f2ord(cost);
@@ -870,9 +889,10 @@ __device__ __forceinline__ int slot_of_candidate(Ctx &x, int pos, int idx, int g
   int take = (int)(G == 1) | (int)(group_of(key, G) == g);
   if (kSelect) take &= (int)cut.in_beam(c) & (int)(cut.bin(c) < k_sel);
   if (!take) return -1;
-  unsigned s = (hash_state(key) >> 6) & kTabMask;
+  unsigned s = probe_start(key);
+  const unsigned step = probe_step(key);
   int probes = 0;
-  while (t.keys[s] != key && probes < kTabSlots) { s = (s + 1) & kTabMask; ++probes; }
+  while (t.keys[s] != key && probes < kTabSlots) { s = (s + step) & kTabMask; ++probes; }
   return probes < kTabSlots ? (int)s : -1;
 }
 
@@ -933,9 +953,10 @@ __device__ __forceinline__ void stay_meet(Ctx &x, const int4 *CL, int n_cont, un
     if (reg < r0 || reg >= r1 || (G > 1 && group_of(key, G) != g)) continue;
     const float nc = stay_cost(x, __int_as_float(c.z));
     if (!(cut.bin(nc) < k_sel)) continue;        // (it is inside the beam: only those were listed)
-    unsigned sl = (hash_state(key) >> 6) & kTabMask;
+    unsigned sl = probe_start(key);
+    const unsigned step = probe_step(key);
     int probes = 0, k = t.keys[sl];
-    while (k != key && k != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; k = t.keys[sl]; }
+    while (k != key && k != kKeyEmpty && probes < kTabSlots) { sl = (sl + step) & kTabMask; ++probes; k = t.keys[sl]; }
     bool win = true;
     if (k == key) {
       const unsigned long long v = t.vals[sl];
@@ -1449,12 +1470,13 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
             const int vi = i0 + k * kBlock + tid;
             const int tok = vi < n_in ? vi : vi + n_skip;
             const int tkey = key_of(tk[k].x);
-            unsigned sl = (hash_state(tkey) >> 6) & kTabMask;
+            unsigned sl = probe_start(tkey);
+            const unsigned step = probe_step(tkey);
             // (a token that did not fit the lattice arena was never written: the channel stops after
             // this frame, and its queue position must not be looked at)
             const bool real = vi < n_have && lat_base + (unsigned)tok < x.lat_cap;
             int probes = 0, key = real ? t.keys[sl] : kKeyEmpty;
-            while (key != tkey && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + 1) & kTabMask; ++probes; key = t.keys[sl]; }
+            while (key != tkey && key != kKeyEmpty && probes < kTabSlots) { sl = (sl + step) & kTabMask; ++probes; key = t.keys[sl]; }
             if (key == tkey && real) {
               const unsigned long long v = t.vals[sl];
               t.vals[sl] = kValEmpty;                      // this destination has its token
