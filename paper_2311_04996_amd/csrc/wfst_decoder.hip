@@ -1595,7 +1595,7 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
   if (x.c.tokrec) {                              // lattice output wants the closed set's final records
     int2 *rec = x.c.tokrec + (x.lat - x.c.lattice);
     for (int i = tid; i < n; i += kBlock)
-      if (lat_base + (unsigned)i < x.lat_cap) { const int2 q = NQ[i]; rec[lat_base + i] = make_int2(key_of(q.x), q.y); }
+      if (lat_base + (unsigned)i < x.lat_cap) { const int2 q = NQ[i]; rec[lat_base + i] = make_int2((int)((unsigned)q.x & (kKeyMask | kFlagSimple)), q.y); }
   }
   __syncthreads();
   if (tid == 0) {
@@ -1885,9 +1885,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
 // in memory for all workgroups would serialise them: measured 3x slower).
 constexpr int kLatSlots = 16384;
 constexpr int kLatGroup = 11264;              // mean keys per pass (load 0.69)
-constexpr int kLatHeavy = 1024;               // tokens with very many arcs, expanded by the whole workgroup
-constexpr int kLatHeavyDeg = 4096;
-constexpr int kLatMedium = 6144;              // tokens with more than a few arcs, expanded by one wave each
+constexpr int kLatListed = 2048;              // tokens with more than a few arcs: listed, their arcs flattened over the workgroup
 constexpr int kLatLightDeg = 3;
 constexpr int kLatErrTable = 1;
 struct LatLds {
@@ -1895,9 +1893,12 @@ struct LatLds {
   unsigned short pos[kLatSlots];
   float ac[kMaxV];
   int bk[kBoostSlots]; float bv[kBoostSlots];
-  int heavy[kLatHeavy];
-  unsigned short medium[kLatMedium];
-  int n_heavy, n_medium, next_medium;
+  unsigned short listed[kLatListed];          // position of the token in its set
+  int lfirst[kLatListed];                     // unit address of its first arc minus its prefix
+  float lcost[kLatListed];
+  unsigned lpre[kLatListed + 1];              // arc counts, then their exclusive prefix sums
+  unsigned wave_tot[kWaves];
+  int n_listed;
   unsigned n_links;                           // links of this set so far
 };
 struct LatticeArgs {
@@ -1925,8 +1926,7 @@ __device__ __forceinline__ int lat_group(int key, int P) {
 
 // One arc (unit address u) out of the token numbered `src` with cost tc.
 template <bool kEps>
-__device__ __forceinline__ void lat_arc(const LatPass &q, int u, float tc, unsigned src) {
-  const int4 ar = q.g.unit[u];
+__device__ __forceinline__ void lat_arc(const LatPass &q, const int4 ar, float tc, unsigned src) {
   const int key = key_of(ar.x);
   if (q.P > 1 && lat_group(key, q.P) != q.p) return;
   const float w = __int_as_float(ar.y);
@@ -1976,53 +1976,70 @@ __device__ __forceinline__ void lat_arcs_of(const DevGraph &g, int key, int &fir
   deg = kEps ? nx : ne;
 }
 
-// All epsilon (kEps) or emitting arcs of the n tokens rec[0..n), numbered from `base`.  A
-// token with a few arcs is expanded by the lane that reads it; one with more is listed and
-// taken by a whole wave (the waves take listed tokens from a counter); one with thousands of
-// arcs is expanded by the whole workgroup.  A token that finds its list full is expanded by
-// its own lane.
+// All epsilon (kEps) or emitting arcs of the n tokens rec[0..n), numbered from `base`.  A token
+// in a simple state needs no graph read at all; one with a few arcs is expanded by the lane that
+// reads it; the others are listed, and the arcs of all listed tokens are flattened over the
+// workgroup (prefix sums over the list, one binary search per arc), so that a state with thousands
+// of arcs is shared by all lanes and the arc reads are in flight together.  A token that finds
+// the list full is expanded by its own lane.
 template <bool kEps>
 __device__ __forceinline__ void lat_expand(const LatPass &q, const int2 *rec, unsigned n, unsigned base) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  if (tid == 0) { q.sm.n_heavy = 0; q.sm.n_medium = 0; q.sm.next_medium = 0; }
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  LatLds &sm = q.sm;
+  if (tid == 0) sm.n_listed = 0;
   __syncthreads();
   for (unsigned i = tid; i < n; i += kBlock) {
-    const int2 tk = rec[i];
+    int2 tk = rec[i];
+    if ((unsigned)tk.x & kFlagSimple) {
+      // a simple state: no epsilon arcs, and its one emitting arc is the graph's usual self-loop,
+      // known without reading the graph
+      tk.x = key_of(tk.x);
+      if (!kEps) lat_arc<kEps>(q, make_int4(tk.x, __float_as_int(q.g.simple_w), q.g.simple_il, 0), __int_as_float(tk.y), base + i);
+      continue;
+    }
     int first, deg;
     lat_arcs_of<kEps>(q.g, tk.x, first, deg);
     bool mine = deg <= kLatLightDeg;
     if (!mine) {
-      if (deg > kLatHeavyDeg) {
-        const int h = atomicAdd(&q.sm.n_heavy, 1);
-        if (h < kLatHeavy) q.sm.heavy[h] = (int)i; else mine = true;
-      } else {
-        const int h = atomicAdd(&q.sm.n_medium, 1);
-        if (h < kLatMedium) q.sm.medium[h] = (unsigned short)i; else mine = true;
-      }
+      const int h = atomicAdd(&sm.n_listed, 1);
+      if (h < kLatListed) { sm.listed[h] = (unsigned short)i; sm.lfirst[h] = first; sm.lcost[h] = __int_as_float(tk.y); sm.lpre[h] = (unsigned)deg; }
+      else mine = true;
     }
     if (mine)
-      for (int k = 0; k < deg; ++k) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
+      for (int k = 0; k < deg; ++k) lat_arc<kEps>(q, q.g.unit[first + k], __int_as_float(tk.y), base + i);
   }
   __syncthreads();
-  const int nm = min(q.sm.n_medium, kLatMedium);
-  for (;;) {
-    int m = 0;
-    if (lane == 0) m = atomicAdd(&q.sm.next_medium, 1);
-    m = uni(m);
-    if (m >= nm) break;
-    const unsigned i = q.sm.medium[m];
-    const int2 tk = rec[i];
-    int first, deg;
-    lat_arcs_of<kEps>(q.g, tk.x, first, deg);
-    for (int k = lane; k < deg; k += 64) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
-  }
-  const int nh = min(q.sm.n_heavy, kLatHeavy);
-  for (int h = 0; h < nh; ++h) {
-    const unsigned i = (unsigned)q.sm.heavy[h];
-    const int2 tk = rec[i];
-    int first, deg;
-    lat_arcs_of<kEps>(q.g, tk.x, first, deg);
-    for (int k = tid; k < deg; k += kBlock) lat_arc<kEps>(q, first + k, __int_as_float(tk.y), base + i);
+  const int nl = min(sm.n_listed, kLatListed);
+  // exclusive prefix sums of the listed tokens' arc counts: two entries per thread
+  static_assert(kLatListed == 2 * kBlock, "two list entries per thread");
+  const unsigned d0 = 2 * tid < nl ? sm.lpre[2 * tid] : 0u, d1 = 2 * tid + 1 < nl ? sm.lpre[2 * tid + 1] : 0u;
+  const unsigned inc = wave_scan_add(d0 + d1);
+  if (lane == 63) sm.wave_tot[wave] = inc;
+  __syncthreads();
+  unsigned before = 0, M = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) { const unsigned t = sm.wave_tot[w]; if (w < wave) before += t; M += t; }
+  const unsigned ex0 = before + inc - d0 - d1;
+  if (2 * tid < nl) { sm.lpre[2 * tid] = ex0; sm.lfirst[2 * tid] -= (int)ex0; }
+  if (2 * tid + 1 < nl) { sm.lpre[2 * tid + 1] = ex0 + d0; sm.lfirst[2 * tid + 1] -= (int)(ex0 + d0); }
+  if (tid == 0) sm.lpre[nl] = M;
+  __syncthreads();
+  constexpr int kLU = 2;                         // arc reads in flight per lane
+  for (unsigned f0 = 0; f0 < M; f0 += kBlock * kLU) {
+    int4 ar[kLU]; int j[kLU]; bool ok[kLU];
+#pragma unroll
+    for (int u = 0; u < kLU; ++u) {
+      const unsigned f = f0 + u * kBlock + tid;
+      ok[u] = f < M;
+      int lo = 0, hi = nl;                       // last j with lpre[j] <= f
+      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (sm.lpre[mid] <= (ok[u] ? f : 0u)) lo = mid; else hi = mid; }
+      j[u] = lo;
+      ar[u] = make_int4(0, 0, 1, 0);
+      if (ok[u]) ar[u] = q.g.unit[sm.lfirst[lo] + (int)f];
+    }
+#pragma unroll
+    for (int u = 0; u < kLU; ++u)
+      if (ok[u]) lat_arc<kEps>(q, ar[u], sm.lcost[j[u]], base + sm.listed[j[u]]);
   }
   __syncthreads();
 }
@@ -2039,7 +2056,7 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
   for (unsigned i = tid; i < n1; i += kBlock) {
     const int2 tk = rec[o1 + i];
     if ((long long)(o1 + i) < a.tok_cap) {
-      a.tok_state[o1 + i] = g.unit[2 * (size_t)(unsigned)tk.x].x;
+      a.tok_state[o1 + i] = g.unit[2 * (size_t)(unsigned)key_of(tk.x)].x;
       a.tok_cost[o1 + i] = __int_as_float(tk.y);
     }
   }
@@ -2069,7 +2086,7 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
     for (int sl = tid; sl < kLatSlots; sl += kBlock) sm.keys[sl] = kKeyEmpty;
     __syncthreads();
     for (unsigned j = tid; j < n1; j += kBlock) {
-      const int key = rec[o1 + j].x;
+      const int key = key_of(rec[o1 + j].x);
       if (P > 1 && lat_group(key, P) != p) continue;
       unsigned sl = (hash_state(key) >> 6) & (kLatSlots - 1);
       int probes = 0;
@@ -2536,7 +2553,12 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
       (link_cap && !links))
     return fail(d, WFST_ERR_INVALID_ARG, "null output or negative capacity");
   if (!(lattice_beam >= 0.0f)) return fail(d, WFST_ERR_INVALID_ARG, "lattice_beam must be >= 0");
+  // first of two synchronisations: the channel's state and its frame offsets (as many as the host
+  // buffer holds; which of them are in use is known from the state)
+  const int n_off = std::min(d->c.max_frames, frames_cap) + 2;
   HIP_TRY(d, hipMemcpyAsync(&s, d->c.st + ch, sizeof(s), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipMemcpyAsync(off, d->c.frame_off + (size_t)ch * (d->c.max_frames + 2), (size_t)n_off * sizeof(unsigned),
+                            hipMemcpyDeviceToHost, st));
   HIP_TRY(d, hipStreamSynchronize(st));
   if (s.status & (kStLattice | kStCapacity))
     return fail(d, WFST_ERR_CAPACITY, "the channel stopped on an overflow: its token sets are incomplete");
@@ -2548,11 +2570,8 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
     return fail(d, WFST_ERR_CAPACITY, "the channel has " + std::to_string(f) + " frames; this call takes at most " +
                                           std::to_string(frames_cap));
   if (f > 0 && !loglikes) return fail(d, WFST_ERR_INVALID_ARG, "null loglikes");
-  HIP_TRY(d, hipMemcpyAsync(off, d->c.frame_off + (size_t)ch * (d->c.max_frames + 2), ((size_t)f + 2) * sizeof(unsigned),
-                            hipMemcpyDeviceToHost, st));
   // the counters must start at zero; the per-set counts are all written by the first run
   HIP_TRY(d, hipMemsetAsync(ctr_dev, 0, 2 * sizeof(unsigned long long), st));
-  HIP_TRY(d, hipStreamSynchronize(st));
   for (int t = 0; t <= f + 1; ++t) frame_off[t] = (int64_t)off[t];
   *n_tokens = (int64_t)off[(size_t)f + 1];
   LatticeArgs a{};
@@ -2565,17 +2584,18 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
   HIP_TRY(d, hipGetLastError());
   hipLaunchKernelGGL(wfst_lattice_scan, dim3(1), dim3(kBlock), 0, st, set_links_dev, f + 1, ctr_dev);
   HIP_TRY(d, hipGetLastError());
-  ctr[0] = ctr[1] = 0;
-  HIP_TRY(d, hipMemcpyAsync(ctr, ctr_dev, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
-  HIP_TRY(d, hipStreamSynchronize(st));
-  *n_links = (int64_t)ctr[0];
-  if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
-  if (*n_tokens <= tok_cap && *n_links <= link_cap && *n_links > 0) {
-    a.write = 1;                                // second run: every set writes its links at its place
+  if (link_cap > 0 && *n_tokens <= tok_cap) {
+    // second run, queued right behind the scan: every set writes its links at its place; entries
+    // beyond link_cap are not written, so nothing has to be known on the host before it starts
+    a.write = 1;
     hipLaunchKernelGGL(wfst_lattice_kernel, dim3(f + 1), dim3(kBlock), 0, st, d->g, d->c, a);
     HIP_TRY(d, hipGetLastError());
-    HIP_TRY(d, hipStreamSynchronize(st));
   }
+  ctr[0] = ctr[1] = 0;
+  HIP_TRY(d, hipMemcpyAsync(ctr, ctr_dev, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));         // second and last synchronisation
+  *n_links = (int64_t)ctr[0];
+  if (ctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
   if (*n_tokens > tok_cap || *n_links > link_cap)
     return fail(d, WFST_ERR_CAPACITY, "lattice needs room for " + std::to_string(*n_tokens) + " tokens and " +
                                           std::to_string(*n_links) + " links");

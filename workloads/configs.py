@@ -45,6 +45,15 @@ CONFIGS = {
                          batch=32, len_lo=50, len_hi=875, seed=2,
                          ll=dict(sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0),
                          beam=17.0, max_active=7000, boost_fst=dict(seed=5, per_utt=100, max_len=4, score=-2.0)),
+    # config 3 on a graph in which no state has the blank self-loop alone: every state has 1-3 more
+    # arcs (not a configuration of the paper's workloads; it shows what the decoder does when the
+    # shortcut for self-loop-only states never applies)
+    "c3_branchy": dict(graph=("tlg", dict(seed=3, num_states=10_000_000, target_arcs=40_000_000,
+                                          num_classes=129, alpha=1.8, k_max=5000, p_eps=0.20,
+                                          num_words=200_000, extra_lo=1, extra_hi=3)),
+                       batch=256, len_lo=50, len_hi=875, seed=3,
+                       ll=dict(sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0),
+                       beam=17.0, max_active=10000),
     # a scaled-down graph of the c3 family for quick runs (not a reported configuration)
     "c3_mini": dict(graph=("tlg", dict(seed=3, num_states=1_000_000, target_arcs=3_000_000,
                                        num_classes=129, alpha=1.8, k_max=5000, p_eps=0.20,

@@ -111,19 +111,23 @@ def tiny_lexicon_graph(seed: int = 1, num_words: int = 200, num_chars: int = 28,
 def tlg_shaped_graph(seed: int, num_states: int, target_arcs: int, num_classes: int = 129,
                      alpha: float = 1.8, k_max: int = 5000, p_eps: float = 0.15,
                      p_olabel: float = 0.2, num_words: int = 20000,
-                     w_lo: float = 0.001) -> Graph:
+                     w_lo: float = 0.001, extra_lo: int = 0, extra_hi: int = 0) -> Graph:
     """Out-degree 1 + min(k_max, floor(x_min * u^(-1/(alpha-1)))) with x_min bisected so the
     total is ~target_arcs.  Arc 0 of every state is a blank self-loop (weight 0).  Every
     other arc is, with probability p_eps, an epsilon backoff arc to a state of strictly
     lower level (levels 0..3 seeded per state; level-0 states have none, so the epsilon
     sub-graph is a DAG), else an emitting arc with a uniform non-blank ilabel, a uniform
     destination, and an output word with probability p_olabel.  Weights -log U(w_lo, 1).
-    Every state is final with cost 0; start state 0, which is given the largest degree."""
+    Every state is final with cost 0; start state 0, which is given the largest degree.
+    With extra_hi > 0 every state gets U{extra_lo..extra_hi} more arcs on top (a "branchy" graph
+    in which no state has the self-loop alone); the power-law part then fills what is left of
+    target_arcs."""
     rng = np.random.default_rng(seed)
     S, V = int(num_states), int(num_classes)
     u = rng.random(S)
     tail = u ** (-1.0 / (alpha - 1.0))
-    want = max(0, int(target_arcs) - S)
+    flat = rng.integers(extra_lo, extra_hi + 1, size=S).astype(np.int64) if extra_hi > 0 else np.zeros(S, np.int64)
+    want = max(0, int(target_arcs) - S - int(flat.sum()))
 
     def total(xm):
         return int(np.minimum(k_max, np.floor(xm * tail)).sum())
@@ -139,7 +143,7 @@ def tlg_shaped_graph(seed: int, num_states: int, target_arcs: int, num_classes: 
         else:
             hi = mid
     x_min = hi
-    extra = np.minimum(k_max, np.floor(x_min * tail)).astype(np.int64)
+    extra = np.minimum(k_max, np.floor(x_min * tail)).astype(np.int64) + flat
     hub = int(np.argmax(extra))                   # the start state is a hub, like a TLG root
     extra[0], extra[hub] = extra[hub], extra[0]
     deg = 1 + extra
