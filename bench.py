@@ -255,6 +255,8 @@ def main():
                          "print them as one JSON line")
     ap.add_argument("--loglike-dtype", default="float32", choices=["float32", "float16", "bfloat16"],
                     help="element type of the log-likelihoods handed to the decoder (costs stay fp32)")
+    ap.add_argument("--narrow-arcs", action="store_true",
+                    help="8-byte emitting-arc records with binary16 weights (the graph's emitting weights are rounded)")
     ap.add_argument("--lattice-beam", type=float, default=None,
                     help="lattice mode: decode --batch utterances (default 8) with token records kept and time "
                          "wfst_get_lattice with this lattice beam for each of them")
@@ -292,6 +294,7 @@ def main():
     mean_frames = float(w.lengths.mean())
     dec = Decoder(w.graph, max_channels=B * n_slots, max_frames=T, max_words=512, max_active_hint=w.max_active,
                   loglike_dtype=args.loglike_dtype, batch_slots=n_slots, lattice_by_length=True,
+                  narrow_arcs=args.narrow_arcs,
                   lattice_bytes_per_channel=int(8 * 1.5 * w.max_active * (mean_frames + 2)))
     streams = pick_concurrent_streams(torch, n_slots)
     ll = torch.from_numpy(w.loglikes).cuda().to(getattr(torch, args.loglike_dtype))
@@ -371,7 +374,7 @@ def main():
         "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
                    "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
                    "beam": w.beam, "max_active": w.max_active, "batches_in_flight": n_slots,
-                   "loglike_dtype": args.loglike_dtype, "decoders": 1,
+                   "loglike_dtype": args.loglike_dtype, "decoders": 1, "narrow_arcs": bool(args.narrow_arcs),
                    "device_gib": round(dec.device_bytes() / 2**30, 1)},
         "one_batch_in_flight": {"value": w.audio_seconds / (wall_one / args.steps),
                                 "ms_per_step": 1e3 * wall_one / args.steps},

@@ -118,6 +118,13 @@ typedef struct {
                                      their lengths instead of equally, so lattice_bytes_per_channel can be sized for
                                      the MEAN utterance.  Such a call takes the memory of every channel of its slot:
                                      channels of that slot used for streaming must be initialised again afterwards */
+  int32_t narrow_arcs;            /* 1: beside the full arc records the graph gets 8-byte records of its emitting
+                                     arcs {destination, weight as IEEE binary16, ilabel, has-output-label bit},
+                                     which ExpandArcs reads for states with several arcs (half the bytes per arc;
+                                     the graph itself takes 8 more bytes per arc).  Every emitting arc's weight is
+                                     rounded to binary16 (BAD_GRAPH if it does not fit) for ALL uses, so results are
+                                     exactly those of this decoder on a graph with the rounded weights; epsilon arcs
+                                     keep fp32 weights */
 } wfst_opts;
 
 #define WFST_LOGLIKE_F32 0

@@ -172,6 +172,10 @@ struct DevGraph {
   // the self-loop that "simple" states have as their only arc (a CTC graph's blank self-loop):
   // the most frequent (ilabel, weight) among states with exactly one arc that is a self-loop
   int simple_il; float simple_w;
+  // narrow arc records (an option): for every unit that is an emitting arc, 8 bytes {next, weight as
+  // IEEE binary16 << 16 | has-output-label << 12 | ilabel}; the loops over the arcs of states with
+  // several arcs read these instead of the 16-byte units.  nullptr: not built.
+  const int2 *earc8;
 };
 
 struct DevChannels {
@@ -563,6 +567,18 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
   push_cands<N, true>(x, ok, next, nc, src, arc);
 }
 
+// An emitting arc {next, weight, ilabel, olabel} by its unit address: from the narrow records if
+// the graph has them (8 bytes instead of 16; the output label, which only boosting looks at here,
+// is then fetched from the full record of the few arcs that have one).
+__device__ __forceinline__ int4 load_emitting_arc(const DevGraph &g, int arc, bool want_olabel) {
+  if (g.earc8 == nullptr) return g.unit[arc];
+  const int2 e = g.earc8[arc];
+  const float w = (float)__builtin_bit_cast(_Float16, (unsigned short)((unsigned)e.y >> 16));
+  int ol = 0;
+  if (want_olabel && ((unsigned)e.y & 0x1000u)) ol = g.unit[arc].w;
+  return make_int4(e.x, __float_as_int(w), (int)((unsigned)e.y & 0xfffu), ol);
+}
+
 // One step of a wave's flattened loop: arcs f0 + u*64 + lane of its listed work items.
 template <int N>
 __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, unsigned f0, unsigned M, float beam, bool boosted) {
@@ -578,7 +594,7 @@ __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, unsigned f0
     src[u] = wl.ttok[j];
     tc[u] = wl.tcost[j];
     tb[u] = boosted ? wl.tb[j] : 0;
-    a[u] = x.g.unit[arc[u]];
+    a[u] = load_emitting_arc(x.g, arc[u], boosted);
   }
   emit_arcs<N>(x, ok, a, tc, src, arc, tb, beam, boosted);
 }
@@ -594,7 +610,7 @@ __device__ __forceinline__ void hub_arcs(Ctx &x, int first, int deg, float cost,
     ok[u] = f < deg;
     arc[u] = first + (ok[u] ? f : deg - 1);      // lanes past the end repeat the last arc (no branch)
     src[u] = tok & 0xffff; tb[u] = (int)((unsigned)tok >> 16); tc[u] = cost;
-    a[u] = x.g.unit[arc[u]];
+    a[u] = load_emitting_arc(x.g, arc[u], boosted);
   }
   emit_arcs<N>(x, ok, a, tc, src, arc, tb, beam, boosted);
 }
@@ -2261,7 +2277,11 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
       const int64_t i = g->row_offsets[s];
       return g->row_offsets[s + 1] - i == 1 && g->ilabel[i] != 0 && g->next_state[i] == s && g->olabel[i] == 0;
     };
-    auto pair_of = [&](int64_t i) { uint32_t wb; std::memcpy(&wb, &g->weight[i], 4); return ((uint64_t)(uint32_t)g->ilabel[i] << 32) | wb; };
+    // (with narrow arc records an emitting arc's weight is its binary16 rounding everywhere)
+    auto pair_of = [&](int64_t i) {
+      const float w = d->opts.narrow_arcs ? (float)(_Float16)g->weight[i] : g->weight[i];
+      uint32_t wb; std::memcpy(&wb, &w, 4); return ((uint64_t)(uint32_t)g->ilabel[i] << 32) | wb;
+    };
     for (int32_t s = 0; s < S; ++s) if (lone_loop(s)) ++freq[pair_of(g->row_offsets[s])];
     uint64_t best = 0; int64_t best_n = 0;
     for (const auto &kv : freq) if (kv.second > best_n || (kv.second == best_n && kv.first < best)) { best = kv.first; best_n = kv.second; }
@@ -2274,6 +2294,8 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
     return blk[s] | (has_eps[s] ? kFlagHasEps : 0u) | (eps_in[s] ? kFlagEpsIn : 0u) | (simple[s] ? kFlagSimple : 0u);
   };
   std::vector<int4> unit(units, make_int4(0, 0, 0, 0));
+  const bool narrow = d->opts.narrow_arcs != 0;
+  std::vector<int2> earc8(narrow ? units : 0, make_int2(0, 0));
   bool all_zero = true;
   for (int32_t s = 0; s < S; ++s) {
     const int64_t r0 = g->row_offsets[s], r1 = g->row_offsets[s + 1];
@@ -2288,9 +2310,23 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
     b[0] = make_int4(s, fbits, ne, (int)packed);
     int4 *xa = b + 1, *ea = b + 1 + nx;
     for (int64_t i = r0; i < r1; ++i) {
-      int wbits; std::memcpy(&wbits, &g->weight[i], 4);
+      float w = g->weight[i];
+      unsigned short hbits = 0;
+      if (narrow && g->ilabel[i] != 0) {
+        // the weight of an emitting arc becomes its nearest binary16 value EVERYWHERE (also in the
+        // full record), so the decoder is the fp32 decoder on a graph with those weights
+        const _Float16 h = (_Float16)w;
+        w = (float)h;
+        if (!std::isfinite(w)) return fail(d, WFST_ERR_BAD_GRAPH, "narrow_arcs: the weight of arc " + std::to_string(i) + " does not fit binary16");
+        std::memcpy(&hbits, &h, 2);
+      }
+      int wbits; std::memcpy(&wbits, &w, 4);
       const int4 arc = make_int4((int)named(g->next_state[i]), wbits, g->ilabel[i], g->olabel[i]);
-      if (g->ilabel[i] == 0) *xa++ = arc; else *ea++ = arc;
+      if (g->ilabel[i] == 0) *xa++ = arc;
+      else {
+        if (narrow) earc8[(size_t)(ea - unit.data())] = make_int2(arc.x, (int)(((unsigned)hbits << 16) | (g->olabel[i] != 0 ? 0x1000u : 0u) | (unsigned)g->ilabel[i]));
+        *ea++ = arc;
+      }
     }
   }
   int4 *d_unit;
@@ -2299,8 +2335,13 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
   HIP_TRY(d, hipMemcpy(d_unit, unit.data(), unit.size() * sizeof(int4), hipMemcpyHostToDevice));
   int blk_bits = 1;
   while (blk_bits < 29 && (1u << blk_bits) < blk[S]) ++blk_bits;
+  int2 *d_earc8 = nullptr;
+  if (narrow) {
+    if ((rc = dev_alloc(d, &d_earc8, earc8.size()))) return rc;
+    HIP_TRY(d, hipMemcpy(d_earc8, earc8.data(), earc8.size() * sizeof(int2), hipMemcpyHostToDevice));
+  }
   d->g = DevGraph{d_unit, blk[S], named(g->start_state), all_zero ? 0 : 1, S, blk_bits, (1u << blk_bits) - 1u,
-                  simple_il, simple_w};
+                  simple_il, simple_w, d_earc8};
   return WFST_OK;
 }
 

@@ -996,3 +996,48 @@ def test_recycled_lattice_reports_a_result_asked_for_too_late(torch_cuda, c2):
         Decoder(c2.graph, max_channels=1, max_frames=100, max_active_hint=c2.max_active, recycle_lattice=True,
                 lattice_bytes_per_channel=8 * 20000)
     assert e.value.code == -1
+
+
+# ------------------------------------------------------------------------------- narrow arc records
+def _with_binary16_emitting_weights(g):
+    """The graph the decoder decodes with narrow_arcs: emitting arcs' weights rounded to IEEE binary16."""
+    from workloads.graphs import Graph
+    w = g.weight.copy()
+    e = g.ilabel != 0
+    w[e] = w[e].astype(np.float16).astype(np.float32)
+    return Graph(g.num_states, g.start_state, g.num_classes, g.row_offsets, g.next_state, g.ilabel, g.olabel, w,
+                 g.final_cost, g.meta)
+
+
+def test_narrow_arc_records_equal_the_oracle_on_the_rounded_weights(torch_cuda, c1, c2):
+    """8-byte emitting-arc records (binary16 weights): bit-exact against the oracle fed the graph with
+    the rounded weights; and the rounding is real (the plain graph gives other token sets).  Config 1,
+    part of config 2 (hub states, boosting reads output labels from the full records), a dense graph
+    whose states all have 600 arcs, micro graphs with ties."""
+    from workloads import dense_graph, micro_graph
+    for w, n, T in ((c1, 1, 100), (c2, 4, 150)):
+        g16 = _with_binary16_emitting_weights(w.graph)
+        assert not np.array_equal(g16.weight, w.graph.weight)
+        lengths = np.minimum(w.lengths[:n], T)
+        refs = oracle_batch(g16, w.loglikes[:n, :T], lengths, w.beam, w.max_active)
+        check_batch(torch_cuda, w.graph, w.loglikes[:n, :T], lengths, w.beam, w.max_active, refs=refs, narrow_arcs=True)
+        plain = oracle_batch(w.graph, w.loglikes[:1, :T], lengths[:1], w.beam, w.max_active)
+        assert (plain[0].digest_sum != refs[0].digest_sum).any()
+    from workloads import boost_tables
+    g16 = _with_binary16_emitting_weights(c2.graph)
+    boosts = boost_tables(5, 2, int(c2.graph.meta["num_words"]), 100, -2.0)
+    lengths = np.minimum(c2.lengths[:2], 100)
+    refs = oracle_batch(g16, c2.loglikes[:2, :100], lengths, c2.beam, c2.max_active, boosts=boosts)
+    check_batch(torch_cuda, c2.graph, c2.loglikes[:2, :100], lengths, c2.beam, c2.max_active, refs=refs, boosts=boosts,
+                narrow_arcs=True)
+    g = dense_graph(7, 1200, 600, 12)
+    ll, lengths = _stress_inputs(g, 10, 11)
+    refs = oracle_batch(_with_binary16_emitting_weights(g), ll, lengths, 6.0, 300)
+    check_batch(torch_cuda, g, ll, lengths, 6.0, 300, max_active_hint=100000, refs=refs, narrow_arcs=True)
+    for seed in range(8):
+        rng = np.random.default_rng(seed)
+        g = micro_graph(seed, num_states=int(rng.integers(4, 40)), num_classes=3, max_deg=5, p_eps=0.4, dyadic=False)
+        ll = -(rng.integers(0, 40, size=(3, 9, 3)).astype(np.float32) / 8.0)
+        lengths = rng.integers(0, 10, size=3).astype(np.int32)
+        refs = oracle_batch(_with_binary16_emitting_weights(g), ll, lengths, 3.0, 6)
+        check_batch(torch_cuda, g, ll, lengths, 3.0, 6, max_active_hint=1000, refs=refs, narrow_arcs=True)
