@@ -154,8 +154,12 @@ def main_streaming(args):
     # chunk-major copy: [chunk][channel][C][V], the layout a batching server hands over
     chunks = torch.from_numpy(np.ascontiguousarray(
         ll.reshape(n, n_chunks + warm, C, g.num_classes).transpose(1, 0, 2, 3))).cuda()
-    dec = Decoder(g, max_channels=n, max_frames=T, max_words=512, max_active_hint=c["max_active"],
-                  outputs_on_host=True)
+    # --recycle-window W: every channel's backpointer memory is a ring over W frames, so the streams
+    # could go on for any length (a result is flagged if its path joins the previous result's path
+    # further back than that; on this graph hypotheses stay apart for hundreds of frames)
+    W = args.recycle_window
+    dec = Decoder(g, max_channels=n, max_frames=W if W else T, max_words=512, max_active_hint=c["max_active"],
+                  outputs_on_host=True, recycle_lattice=bool(W))
     chans = np.arange(n, dtype=np.int32)
     nfr = np.full(n, C, np.int32)
     dec.init_channels(chans, float(c["beam"]), int(c["max_active"]))
@@ -168,7 +172,10 @@ def main_streaming(args):
         dec.advance_chunk(chans, chunks[k], nfr)
         out = dec.get_partial_batch(chans, finalize=False, out=out)          # host outputs: synchronises
         lat.append(time.perf_counter() - t0)
+        assert not (out[3] & (8 | 16)).any(), (f"chunk {k}: a channel overflowed a buffer (flags "
+                                               f"{sorted(set(out[3].tolist()))}): the run is invalid")
     assert not (out[3] & (8 | 16)).any(), "a channel overflowed a buffer: the run is invalid"
+    device_gib = dec.device_bytes() / 2**30
     lat = np.array(lat[warm:]) * 1e3
     p50, p99 = float(np.percentile(lat, 50)), float(np.percentile(lat, 99))
     chunk_s = C * 0.040
@@ -176,7 +183,8 @@ def main_streaming(args):
             "value": p50, "unit": "ms", "n_gpus": 1, "steps": n_chunks, "warmup": warm, "ms_per_step": float(lat.mean()),
             "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
             "config": {"workload": "c4_streaming", "channels": n, "chunk_frames": C, "states": g.num_states,
-                       "arcs": g.num_arcs, "beam": c["beam"], "max_active": c["max_active"]},
+                       "arcs": g.num_arcs, "beam": c["beam"], "max_active": c["max_active"],
+                       "recycled_lattice_window_frames": W or None, "device_gib": round(device_gib, 1)},
             "p50_ms": p50, "p99_ms": p99, "max_ms": float(lat.max()),
             "rtfx": n * chunk_s / (float(lat.mean()) * 1e-3),
             "channels_at_realtime_p99": int(n * chunk_s * 1e3 / p99),
@@ -243,6 +251,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--channels", type=int, default=512, help="streaming mode: concurrent channels")
     ap.add_argument("--chunks", type=int, default=50, help="streaming mode: timed chunks")
+    ap.add_argument("--recycle-window", type=int, default=0,
+                    help="streaming mode: recycle every channel's lattice memory as a ring over this many frames")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=9)
     ap.add_argument("--warmup", type=int, default=1)

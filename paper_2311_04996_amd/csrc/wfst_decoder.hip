@@ -97,7 +97,7 @@ constexpr int kU = WFST_U;                    // independent memory requests per
 constexpr int kUE = WFST_UE;                  // ... in ExpandArcs over emitting arcs
 constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave takes at a time
 #ifndef WFST_SEL_EVERY
-#define WFST_SEL_EVERY 4                      // the selection histogram reads one run of 64 candidates out of this many
+#define WFST_SEL_EVERY 8                      // the selection histogram reads one run of 64 candidates out of this many
 #endif
 #ifndef WFST_UM
 #define WFST_UM 1
@@ -570,8 +570,9 @@ __device__ __forceinline__ void emit_arcs(Ctx &x, int (&ok)[N], const int4 (&a)[
 // An emitting arc {next, weight, ilabel, olabel} by its unit address: from the narrow records if
 // the graph has them (8 bytes instead of 16; the output label, which only boosting looks at here,
 // is then fetched from the full record of the few arcs that have one).
+template <bool kNarrow>
 __device__ __forceinline__ int4 load_emitting_arc(const DevGraph &g, int arc, bool want_olabel) {
-  if (g.earc8 == nullptr) return g.unit[arc];
+  if (!kNarrow) return g.unit[arc];
   const int2 e = g.earc8[arc];
   const float w = (float)__builtin_bit_cast(_Float16, (unsigned short)((unsigned)e.y >> 16));
   int ol = 0;
@@ -580,7 +581,7 @@ __device__ __forceinline__ int4 load_emitting_arc(const DevGraph &g, int arc, bo
 }
 
 // One step of a wave's flattened loop: arcs f0 + u*64 + lane of its listed work items.
-template <int N>
+template <int N, bool kNarrow>
 __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, unsigned f0, unsigned M, float beam, bool boosted) {
   const int lane = threadIdx.x & 63;
   int ok[N]; int src[N]; int4 a[N]; int arc[N]; float tc[N]; int tb[N];
@@ -594,13 +595,13 @@ __device__ __forceinline__ void wave_arcs(Ctx &x, const WaveLds &wl, unsigned f0
     src[u] = wl.ttok[j];
     tc[u] = wl.tcost[j];
     tb[u] = boosted ? wl.tb[j] : 0;
-    a[u] = load_emitting_arc(x.g, arc[u], boosted);
+    a[u] = load_emitting_arc<kNarrow>(x.g, arc[u], boosted);
   }
   emit_arcs<N>(x, ok, a, tc, src, arc, tb, beam, boosted);
 }
 
 // Arcs [f0, f0 + 64N) of one listed high-degree state (all lanes of the wave call it).
-template <int N>
+template <int N, bool kNarrow>
 __device__ __forceinline__ void hub_arcs(Ctx &x, int first, int deg, float cost, int tok, int f0, float beam, bool boosted) {
   const int lane = threadIdx.x & 63;
   int ok[N], src[N], arc[N], tb[N]; int4 a[N]; float tc[N];
@@ -610,7 +611,7 @@ __device__ __forceinline__ void hub_arcs(Ctx &x, int first, int deg, float cost,
     ok[u] = f < deg;
     arc[u] = first + (ok[u] ? f : deg - 1);      // lanes past the end repeat the last arc (no branch)
     src[u] = tok & 0xffff; tb[u] = (int)((unsigned)tok >> 16); tc[u] = cost;
-    a[u] = load_emitting_arc(x.g, arc[u], boosted);
+    a[u] = load_emitting_arc<kNarrow>(x.g, arc[u], boosted);
   }
   emit_arcs<N>(x, ok, a, tc, src, arc, tb, beam, boosted);
 }
@@ -628,6 +629,7 @@ __device__ __forceinline__ int next_run(Smem &sm) {
 // remaining arcs of the batch are flattened over the 64 lanes (prefix sums in the wave's slice of
 // LDS, one short search per arc), and states with more than kHubDeg arcs are listed for all waves.
 // Returns the emitting arcs expanded (wave-uniform).  All 64 lanes call it.
+template <bool kNarrow>
 __device__ __forceinline__ unsigned dense_run(Ctx &x, WaveLds &wl, int head, int n, float beam, bool boosted) {
   Smem &sm = x.sm;
   HubLds &hb = sm.u.e.hub;
@@ -677,8 +679,8 @@ __device__ __forceinline__ unsigned dense_run(Ctx &x, WaveLds &wl, int head, int
   n_arcs += M;
   // 64 * kUE arcs per step; a short rest takes the cheaper single-arc step
   unsigned f0 = 0;
-  for (; f0 + 64 < M; f0 += 64 * kUE) wave_arcs<kUE>(x, wl, f0, M, beam, boosted);
-  if (f0 < M) wave_arcs<1>(x, wl, f0, M, beam, boosted);
+  for (; f0 + 64 < M; f0 += 64 * kUE) wave_arcs<kUE, kNarrow>(x, wl, f0, M, beam, boosted);
+  if (f0 < M) wave_arcs<1, kNarrow>(x, wl, f0, M, beam, boosted);
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
   return n_arcs;
@@ -686,6 +688,7 @@ __device__ __forceinline__ unsigned dense_run(Ctx &x, WaveLds &wl, int head, int
 
 // On entry sm.next_run == kWaves, sm.done_waves == 0, sm.n_hub == 0 and the hub list's ready
 // and seg_next words are zero (the caller sets them before its barrier).
+template <bool kNarrow>
 __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
@@ -747,14 +750,14 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
     if (pend_n >= kWaveTok) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      n_arcs += dense_run(x, wl, pend_head, kWaveTok, beam, boosted);
+      n_arcs += dense_run<kNarrow>(x, wl, pend_head, kWaveTok, beam, boosted);
       pend_head = (pend_head + kWaveTok) & (2 * kWaveTok - 1); pend_n -= kWaveTok;
     }
   }
   if (pend_n > 0) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    n_arcs += dense_run(x, wl, pend_head, pend_n, beam, boosted);
+    n_arcs += dense_run<kNarrow>(x, wl, pend_head, pend_n, beam, boosted);
   }
   // this wave lists no more states
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -782,8 +785,8 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
       const int f0 = seg * kHubSeg;
       if (f0 >= deg) { ++h; continue; }
       const int first = uni(hb.first[h]), tok = uni(hb.ttok[h]); const float cost = uni(hb.tcost[h]);
-      if (deg - f0 > 64) hub_arcs<kUE>(x, first, deg, cost, tok, f0, beam, boosted);
-      else hub_arcs<1>(x, first, deg, cost, tok, f0, beam, boosted);
+      if (deg - f0 > 64) hub_arcs<kUE, kNarrow>(x, first, deg, cost, tok, f0, beam, boosted);
+      else hub_arcs<1, kNarrow>(x, first, deg, cost, tok, f0, beam, boosted);
       n_arcs += (unsigned)min(kHubSeg, deg - f0);
     }
   }
@@ -1767,6 +1770,9 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
 }
 
 // ------------------------------------------------------------------ the channel kernel
+// kNarrow: the graph has the 8-byte emitting-arc records and the arc loops read them (a variant of
+// the kernel of its own, so that the usual one carries none of it).
+template <bool kNarrow>
 __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
@@ -1855,7 +1861,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     const unsigned lat_base = x.s.lat_used;
     if (tid == 0) { sm.ctr[kCtTok] += x.s.n_tok; sm.ctr[kCtFrames]++; }
     prof_mark(sm, kPhOther);
-    emit_expand(x, Q, x.s.n_tok);
+    emit_expand<kNarrow>(x, Q, x.s.n_tok);
     prof_mark(sm, kPhExpand);
     Cutoff cut;
     recombine_and_prune(x, NQ, lat_base, x.wl0, cut);
@@ -2442,7 +2448,8 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
   HIP_TRY(d, hipMemcpyAsync(slot, pack.data(), pack.size() * sizeof(int), hipMemcpyHostToDevice, st));
   a.chan = slot; a.nfr = slot + n; a.io = slot + 2 * n;
   HIP_TRY(d, hipEventRecord(d->ev0[slot_id], st));
-  hipLaunchKernelGGL(wfst_channel_kernel, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  if (d->g.earc8) hipLaunchKernelGGL(wfst_channel_kernel<true>, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  else hipLaunchKernelGGL(wfst_channel_kernel<false>, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
   HIP_TRY(d, hipGetLastError());
   HIP_TRY(d, hipEventRecord(d->ev1[slot_id], st));
   d->timed[slot_id] = 1;
