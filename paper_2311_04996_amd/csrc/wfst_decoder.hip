@@ -9,8 +9,8 @@
 // traceback runs on the device).
 //
 // Recombination (one token per destination state, lowest (cost, arc id) wins) uses NO global
-// atomics: measured on MI355X, 64-bit global atomics top out near 25 G/s for the whole chip,
-// which bounded an earlier global-hash design.  Instead ExpandArcs appends candidates
+// atomics: measured on MI355X, random 64-bit global atomics top out near 20 G/s for the whole
+// chip, which bounded an earlier global-hash design.  Instead ExpandArcs appends candidates
 // {next, cost, source token, arc} to a buffer in four regions (by hash of the destination;
 // wave-aggregated, so the stores coalesce); a histogram of a sample of the candidate costs
 // selects the few that can survive max-active, and those are reduced in an open-addressing
@@ -25,7 +25,11 @@
 // ExpandArcs has no block-wide barrier: every wave takes runs of 64 tokens from a counter in
 // LDS and expands them on its own (first arc by the owning lane, the other arcs flattened
 // over the wave, very large states shared segment by segment), so the waves drift apart and
-// one wave's memory waits overlap another's arithmetic.  The hot loops are bound by
+// one wave's memory waits overlap another's arithmetic.  A token in a "simple" state (its only
+// arc is the graph's most frequent self-loop: in a CTC graph the blank self-loop, where most
+// hypotheses sit) is expanded from its queue record alone, and its candidate is never written:
+// a bit filter of the buffer's destinations tells which of these tokens can meet another
+// candidate at all; the rest are the recombined tokens of their states as they stand.  The hot loops are bound by
 // instruction issue (4 waves per SIMD, 4 cycles per wave64 instruction): they are written
 // branch-free where it matters.
 //
@@ -35,8 +39,8 @@
 // bytes.  The packed word sits right before the first arc, so ONE 16-byte load at byte 12 of a
 // block brings the degrees and next/weight/ilabel of the first arc.  A state is
 // named by its block number (byte offset / 32), which is also the recombination key and grows
-// with the state id.  `next` of an arc is the destination's block number plus two flag bits
-// (the destination has epsilon arcs / an epsilon arc enters it), so a token is created from
+// with the state id.  `next` of an arc is the destination's block number plus three flag bits
+// (the destination has epsilon arcs / an epsilon arc enters it / it is a simple state), so a token is created from
 // the arc alone and the only random graph read per token is the 32-byte header + first arc
 // when the token is expanded.  An arc's id is its unit address (epsilon arcs have bit 30 set),
 // which orders arcs exactly as (emitting before epsilon, state, position) does.
