@@ -136,6 +136,9 @@ constexpr unsigned kFlagEpsIn = 0x40000000u;   //                   an epsilon a
 constexpr unsigned kFlagSimple = 0x20000000u;  //                   the destination's only arc is the graph's usual self-loop
                                                // (DevGraph::simple_il, simple_w; no output label): a token there is
                                                // expanded without reading the graph
+constexpr unsigned kLoopFirst = 0x80000000u;   // ilabel word of a state's first arc: the state has no epsilon arcs and this arc is
+                                               // the usual self-loop (like a simple state's, but other arcs may follow)
+constexpr int kLabelMask = 0xffff;             // ... the label itself
 constexpr unsigned kArcEps = 0x40000000u;      // arc ids: unit address, plus this bit for epsilon arcs
 constexpr unsigned kArcMask = 0x3fffffffu;
 constexpr unsigned kPackE = 0xFFFFFu;          // header word 3: emitting degree (20 bits, all ones = see word 2)
@@ -530,6 +533,14 @@ __device__ __forceinline__ void push_cands(Ctx &x, const int (&ok)[N], const int
   }
 }
 
+// Two bit sets over the tokens of the current set live in the closure's item tables, which are idle
+// between the end of one frame's closure and the next: bit i of `staybits`: token i's implied
+// self-loop candidate is the recombined token of its state; bit i of `hasstay`: token i is in a
+// state with other arcs whose first arc is the usual self-loop (set while arcs are expanded).
+__device__ __forceinline__ unsigned *staybits_of(Smem &sm) { return reinterpret_cast<unsigned *>(&sm.ek); }
+__device__ __forceinline__ unsigned *hasstay_bits(Smem &sm) { return reinterpret_cast<unsigned *>(&sm.ek) + kQueueMax / 32; }
+static_assert(sizeof(EpsLds) >= 2 * (kQueueMax / 8), "two bits per token of the set");
+
 // Cost of the self-loop candidate of a token (cost c) in a simple state, in the association of
 // every emitting arc: (c + w) + acoustic cost.
 __device__ __forceinline__ float stay_cost(const Ctx &x, float c) { return canon((c + x.g.simple_w) + x.sm.stay_ac); }
@@ -656,9 +667,24 @@ __device__ __forceinline__ unsigned dense_run(Ctx &x, WaveLds &wl, int head, int
     deg = (unsigned)(ne - has[0]);
     first = 2 * blk + 1 + nx + has[0];                  // unit address of the first arc left
     tc[0] = __int_as_float(tk.y); src[0] = tok; arc[0] = 2 * blk + 1;
-    a0[0] = make_int4(hd.y, hd.z, has[0] ? hd.w : 1, 0);
-    if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)blk + 1].w;    // the first arc's olabel
+    a0[0] = make_int4(hd.y, hd.z, has[0] ? (hd.w & kLabelMask) : 1, 0);
     n_arcs += (unsigned)__popcll(__ballot(has[0]));
+    {
+      // The first arc is the usual self-loop: its candidate is not made here.  Like the one of a
+      // token in a simple state it is implied by the token's queue record (the bit set `hasstay`
+      // says for which tokens); here it only lowers the running best.
+      const int loop = has[0] & (int)((unsigned)hd.w >> 31);
+      const float nc = stay_cost(x, tc[0]);
+      const unsigned bo = __hip_atomic_load(&sm.best_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const unsigned o = (loop && nc < INFINITY) ? f2ord(nc) : kOrdNone;
+      if (__ballot(o < bo) != 0ull) {
+        const unsigned mo = wave_min(o);
+        if (lane == 0) atomicMin(&sm.best_ord, mo);
+      }
+      if (loop) atomicOr(&hasstay_bits(sm)[tok >> 5], 1u << (tok & 31));
+      has[0] &= (int)!loop;
+    }
+    if (boosted && has[0]) a0[0].w = x.g.unit[2 * (size_t)(unsigned)blk + 1].w;    // the first arc's olabel
     if (deg > (unsigned)kHubDeg) {                      // to the shared list, if it has room
       const int h = atomicAdd(&sm.n_hub, 1);
       if (h < kHubCap) {
@@ -1097,9 +1123,9 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   // bit i of staybits: token i's self-loop candidate is the recombined token of its state (the
   // closure's tables are idle now).  The tokens whose candidate may meet one of the buffer are
   // listed in the second worklist buffer, which nobody uses before the closure's first round ends.
-  unsigned *staybits = reinterpret_cast<unsigned *>(&sm.ek);
+  unsigned *staybits = staybits_of(sm);
+  const unsigned *hasstay = hasstay_bits(sm);
   int4 *CL = x.wl0 + x.c.qcap;
-  static_assert(sizeof(EpsLds) * 8 >= kQueueMax, "one bit per token of the set");
   if (tid < 256) { sm.hist2[tid] = 0; sm.hist3[tid] = 0; }
   if (tid == 0) sm.n_cont = 0;
   __syncthreads();
@@ -1112,7 +1138,8 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     const int i = i0 + tid;
     const int2 q = i < n_tok ? Q[i] : make_int2(0, 0);
     const float nc = stay_cost(x, __int_as_float(q.y));
-    const int in = (int)(i < n_tok) & (int)(((unsigned)q.x & kFlagSimple) != 0) & (int)(nc < INFINITY) & (int)cut.in_beam(nc);
+    const int stays = (int)(((unsigned)q.x & kFlagSimple) != 0) | (int)((hasstay[min(i, n_tok - 1) >> 5] >> (i & 31)) & 1u);
+    const int in = (int)(i < n_tok) & stays & (int)(nc < INFINITY) & (int)cut.in_beam(nc);
     const unsigned fb = filter_bit(key_of(q.x));
     const int cont = in & (int)((sm.u.e.filter[fb >> 5] >> (fb & 31)) & 1u);
     const int alone = in & (int)!cont;
@@ -1858,6 +1885,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     }
     for (int h = tid; h < kHubCap; h += kBlock) { sm.u.e.hub.ready[h] = 0; sm.u.e.hub.seg_next[h] = 0; }
     for (int h = tid; h < kFilterBits / 32; h += kBlock) sm.u.e.filter[h] = 0u;
+    for (int h = tid; h < kQueueMax / 32; h += kBlock) hasstay_bits(sm)[h] = 0u;
     if (tid == 0) { sm.next_run = kWaves; sm.done_waves = 0; sm.n_hub = 0; }
     __syncthreads();
     const int2 *Q = x.q0 + x.s.cur * c.qcap;
@@ -1958,7 +1986,7 @@ __device__ __forceinline__ void lat_arc(const LatPass &q, const int4 ar, float t
   const float w = __int_as_float(ar.y);
   float acst = 0.0f, nc;
   if (kEps) nc = canon(tc + w);
-  else { acst = q.sm.ac[ar.z - 1]; nc = canon((tc + w) + acst); }
+  else { acst = q.sm.ac[(ar.z & kLabelMask) - 1]; nc = canon((tc + w) + acst); }
   if (q.boosted && ar.w != 0) {
     unsigned h = boost_slot(ar.w);
     float b = 0.0f;
@@ -1985,7 +2013,7 @@ __device__ __forceinline__ void lat_arc(const LatPass &q, const int4 ar, float t
   const unsigned long long at = q.links_base + k;
   if (q.a.write && at < (unsigned long long)q.a.link_cap) {
     wfst_lattice_link L;
-    L.src = (int)src; L.dst = (int)(q.dst_base + j); L.ilabel = kEps ? 0 : ar.z; L.olabel = ar.w;
+    L.src = (int)src; L.dst = (int)(q.dst_base + j); L.ilabel = kEps ? 0 : (ar.z & kLabelMask); L.olabel = ar.w;
     L.graph_cost = w; L.acoustic_cost = acst; L.cost = nc; L.frame = q.t;
     q.a.links[at] = L;
   }
@@ -2277,27 +2305,33 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
       if (g->ilabel[i] == 0) { eps_in[g->next_state[i]] = 1; has_eps[s] = 1; }
   }
   blk[S] = (unsigned)(units / 2);
-  // "simple" states: exactly one arc, a self-loop without output label, with the (ilabel, weight)
-  // that is most frequent among such states (in a CTC graph the blank self-loop)
-  std::vector<char> simple(S, 0);
+  // The usual self-loop: the (ilabel, weight) that is most frequent among first arcs that are
+  // self-loops without output label, over the states without epsilon arcs (in a CTC graph the
+  // blank self-loop).  A state whose first arc is that self-loop is a "loop-first" state; one
+  // that has no other arc is "simple".
+  std::vector<char> simple(S, 0), loop_first(S, 0);
   int simple_il = 1; float simple_w = 0.0f;
   {
     std::unordered_map<uint64_t, int64_t> freq;
-    auto lone_loop = [&](int32_t s) {
+    auto starts_with_loop = [&](int32_t s) {
       const int64_t i = g->row_offsets[s];
-      return g->row_offsets[s + 1] - i == 1 && g->ilabel[i] != 0 && g->next_state[i] == s && g->olabel[i] == 0;
+      return g->row_offsets[s + 1] > i && !has_eps[s] && g->next_state[i] == s && g->olabel[i] == 0;
     };
     // (with narrow arc records an emitting arc's weight is its binary16 rounding everywhere)
     auto pair_of = [&](int64_t i) {
       const float w = d->opts.narrow_arcs ? (float)(_Float16)g->weight[i] : g->weight[i];
       uint32_t wb; std::memcpy(&wb, &w, 4); return ((uint64_t)(uint32_t)g->ilabel[i] << 32) | wb;
     };
-    for (int32_t s = 0; s < S; ++s) if (lone_loop(s)) ++freq[pair_of(g->row_offsets[s])];
+    for (int32_t s = 0; s < S; ++s) if (starts_with_loop(s)) ++freq[pair_of(g->row_offsets[s])];
     uint64_t best = 0; int64_t best_n = 0;
     for (const auto &kv : freq) if (kv.second > best_n || (kv.second == best_n && kv.first < best)) { best = kv.first; best_n = kv.second; }
     if (best_n > 0) {
       simple_il = (int)(best >> 32); const uint32_t wb = (uint32_t)best; std::memcpy(&simple_w, &wb, 4);
-      for (int32_t s = 0; s < S; ++s) if (lone_loop(s) && pair_of(g->row_offsets[s]) == best) simple[s] = 1;
+      for (int32_t s = 0; s < S; ++s)
+        if (starts_with_loop(s) && pair_of(g->row_offsets[s]) == best) {
+          loop_first[s] = 1;
+          simple[s] = g->row_offsets[s + 1] - g->row_offsets[s] == 1;
+        }
     }
   }
   auto named = [&](int32_t s) {
@@ -2331,7 +2365,8 @@ int upload_graph(wfst_decoder *d, const wfst_graph_csr *g) {
         std::memcpy(&hbits, &h, 2);
       }
       int wbits; std::memcpy(&wbits, &w, 4);
-      const int4 arc = make_int4((int)named(g->next_state[i]), wbits, g->ilabel[i], g->olabel[i]);
+      int4 arc = make_int4((int)named(g->next_state[i]), wbits, g->ilabel[i], g->olabel[i]);
+      if (i == r0 && loop_first[s]) arc.z |= (int)kLoopFirst;       // (the narrow record keeps the plain label)
       if (g->ilabel[i] == 0) *xa++ = arc;
       else {
         if (narrow) earc8[(size_t)(ea - unit.data())] = make_int2(arc.x, (int)(((unsigned)hbits << 16) | (g->olabel[i] != 0 ? 0x1000u : 0u) | (unsigned)g->ilabel[i]));

@@ -491,6 +491,27 @@ def test_state_with_more_than_a_million_arcs(torch_cuda):
     check_batch(torch_cuda, g, ll, lengths, 30.0, 100000, max_active_hint=131072)
 
 
+def test_self_loop_candidates_that_tie_exactly_with_candidates_of_other_arcs(torch_cuda):
+    """Tokens that stay on the usual self-loop of their state are never written as candidates; they
+    meet the candidates of other arcs only if one of those goes to the same state.  Dyadic weights
+    and log-likelihoods make the two tie exactly on cost nearly everywhere, so the arc ids decide,
+    and the words (output labels sit on half of the arcs) show who won.  States with the
+    self-loop alone, with more arcs after it, with epsilon arcs, with self-loops of other kinds
+    (another label, a weight, an output label) and without any are all there."""
+    from workloads import loop_tie_graph
+    for seed, S, V in ((3, 400, 5), (4, 3000, 3), (5, 20000, 4), (6, 20000, 2)):
+        g = loop_tie_graph(seed, S, V)
+        rng = np.random.default_rng([seed, 77])
+        T = 40
+        lengths = np.array([T, T - 7, 1], np.int32)
+        ll = (-0.5 * rng.integers(0, 7, size=(3, T, V))).astype(np.float32)
+        for beam, ma in ((8.0, 100000), (4.0, 200), (6.0, 1500)):
+            check_batch(torch_cuda, g, ll, lengths, beam, ma, max_active_hint=20000)
+        boosts = [(np.arange(1, 30, 3, dtype=np.int32), np.full(10, -0.5, np.float32)),
+                  (np.array([2, 5], np.int32), np.array([-1.0, 0.5], np.float32)), None]
+        check_batch(torch_cuda, g, ll, lengths, 6.0, 1500, max_active_hint=20000, boosts=boosts)
+
+
 def test_epsilon_rounds_larger_than_one_chunk_and_one_table(torch_cuda):
     """A closure round with 3,000 items and 9,000 arcs (not fused: several chunks of items, several
     table passes) after a fused round of one item with 3,000 arcs."""

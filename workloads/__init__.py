@@ -6,12 +6,12 @@ and benchmark.  Everything is a deterministic function of an integer seed.
 """
 from .graphs import (Graph, tiny_lexicon_graph, tlg_shaped_graph, ctc_topology_graph,
                      micro_graph, permute_arcs_within_states, dense_graph, giant_state_graph,
-                     eps_layers_graph)
+                     eps_layers_graph, loop_tie_graph)
 from .loglikes import ctc_loglikes, random_lengths
 from .configs import CONFIGS, make_config, boost_tables
 from .boost import BoostFst, boost_trie, boost_fsts, random_targets
 
 __all__ = ["Graph", "tiny_lexicon_graph", "tlg_shaped_graph", "ctc_topology_graph",
            "micro_graph", "permute_arcs_within_states", "dense_graph", "giant_state_graph",
-           "eps_layers_graph", "ctc_loglikes", "random_lengths",
+           "eps_layers_graph", "loop_tie_graph", "ctc_loglikes", "random_lengths",
            "CONFIGS", "make_config", "boost_tables", "BoostFst", "boost_trie", "boost_fsts", "random_targets"]

@@ -311,3 +311,36 @@ def eps_layers_graph(seed: int, width: int, num_classes: int, fan: int = 3, num_
     ol = np.where(rng.random(A) < 0.1, rng.integers(1, num_words + 1, A), 0)
     w = -np.log(rng.uniform(0.01, 1.0, A))
     return _csr(S, 0, num_classes, src, dst, il, ol, w)
+
+
+def loop_tie_graph(seed: int, num_states: int, num_classes: int, p_loop: float = 0.85, max_extra: int = 3,
+                   p_eps: float = 0.1, num_words: int = 30) -> Graph:
+    """Exact cost ties around self-loops.  A share p_loop of the states starts with a blank
+    self-loop (ilabel 1, weight 0, no output label); the others start with some other arc or a
+    self-loop of another kind (another label, a weight, an output label).  Every state has
+    0..max_extra more arcs to uniform destinations, many of them with the blank label as well, with
+    weights from {0, 0.5, 1} and output labels on half of them; a share p_eps of the extra arcs are
+    epsilon arcs (weight 0 or 0.5) to a higher-numbered state.  With log-likelihoods that are
+    multiples of 0.5 every cost is a small dyadic number, so the candidate of a self-loop and the
+    candidates of arcs entering the same state tie exactly all the time."""
+    rng = np.random.default_rng([seed, 0x7E100])
+    S, V = int(num_states), int(num_classes)
+    src, dst, il, ol, w = [], [], [], [], []
+    for s in range(S):
+        u = rng.random()
+        if u < p_loop:
+            src.append(s); dst.append(s); il.append(1); ol.append(0); w.append(0.0)
+        elif u < p_loop + 0.05:                                  # a self-loop with an output label
+            src.append(s); dst.append(s); il.append(1); ol.append(int(rng.integers(1, num_words + 1))); w.append(0.0)
+        elif u < p_loop + 0.10:                                  # a self-loop with another label or weight
+            src.append(s); dst.append(s); il.append(int(rng.integers(1, V + 1))); ol.append(0); w.append(float(rng.choice([0.0, 0.5])))
+        for _ in range(8 if s == 0 else int(rng.integers(0, max_extra + 1))):    # the start state leads somewhere
+            if rng.random() < p_eps and s + 1 < S:
+                src.append(s); dst.append(int(rng.integers(s + 1, S))); il.append(0)
+                w.append(float(rng.choice([0.0, 0.5])))
+            else:
+                src.append(s); dst.append(int(rng.integers(0, S)))
+                il.append(1 if rng.random() < 0.5 else int(rng.integers(1, V + 1)))
+                w.append(float(rng.choice([0.0, 0.5, 1.0])))
+            ol.append(int(rng.integers(1, num_words + 1)) if rng.random() < 0.5 else 0)
+    return _csr(S, 0, V, src, dst, il, ol, w)
