@@ -304,6 +304,29 @@ int32_t wfst_get_lattice(wfst_decoder *dec, int32_t ch, const void *loglikes, fl
                          int64_t *n_tokens, int64_t *n_links, void *stream);
 
 /*
+ * wfst_get_lattice (same definition of the lattice, Section "Algorithm description" as read above)
+ * for n DISTINCT channels in one call: all their token sets go through the kernels together -- two
+ * launches and two synchronisations in all, instead of per channel.
+ *   loglikes   DEVICE [n][T][V] (element type opts.loglike_dtype): the rows of channels[k] start at
+ *              element k*T*V; every channel must have consumed at most T frames
+ *   tok_state / tok_cost [tok_cap], links [link_cap]   DEVICE, caller owned: the channels' tokens
+ *              and links one after the other in the order of `channels`
+ *   tok_first, link_first [n + 1]   HOST: channel k's tokens are entries [tok_first[k], tok_first[k+1]),
+ *              its links [link_first[k], link_first[k+1])
+ *   frame_off  HOST [n][T + 2]: row k as wfst_get_lattice's frame_off for channels[k] (entries after
+ *              the channel's last set repeat its token count)
+ * Token numbers (frame_off, src and dst of a link) count from 0 within each channel, as in
+ * wfst_get_lattice.  If a capacity is too small: WFST_ERR_CAPACITY with tok_first[n] and
+ * link_first[n] set to the totals needed (call with capacities 0 to learn them).  Other errors as
+ * wfst_get_lattice, plus BAD_CHANNEL for a channel listed twice and INVALID_ARG for a channel with
+ * more than T frames.  The first call allocates pinned host staging memory.
+ */
+int32_t wfst_get_lattice_batch(wfst_decoder *dec, const int32_t *channels, int32_t n, const void *loglikes,
+                               int32_t T, float lattice_beam, int32_t *tok_state, float *tok_cost,
+                               int64_t tok_cap, int64_t *frame_off, wfst_lattice_link *links,
+                               int64_t link_cap, int64_t *tok_first, int64_t *link_first, void *stream);
+
+/*
  * wfst_get_lattice for callers that must not allocate (code between graph captures, tight serving
  * loops, harnesses that forbid hipMalloc): same arguments, same results, but the call allocates
  * nothing, neither device nor host memory.  The kernels' scratch (two counters and the number of

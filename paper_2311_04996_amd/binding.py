@@ -22,7 +22,7 @@ LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
            "wfst_decode_batch_boost_fst", "wfst_decode_batch_slot", "wfst_slot_kernel_ms", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels",
            "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
-           "wfst_get_lattice_noalloc",
+           "wfst_get_lattice_noalloc", "wfst_get_lattice_batch",
            "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_debug_get_token_pairs", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
@@ -130,6 +130,7 @@ def load_library():
     lib.wfst_last_error.restype = C.c_char_p
     lib.wfst_get_lattice.argtypes = [p, i32, p, f32, p, p, i64, p, p, i64, p, p, p]
     lib.wfst_get_lattice_noalloc.argtypes = lib.wfst_get_lattice.argtypes
+    lib.wfst_get_lattice_batch.argtypes = [p, p, i32, p, i32, f32, p, p, i64, p, p, i64, p, p, p]
     for name in EXPORTS:
         if name not in ("wfst_device_bytes", "wfst_last_kernel_ms", "wfst_slot_kernel_ms", "wfst_last_error"):
             getattr(lib, name).restype = i32
@@ -385,6 +386,52 @@ class Decoder:
         links = lk.cpu().numpy()[:nl.value * LINK_DTYPE.itemsize].view(LINK_DTYPE).copy()
         return Lattice(off[:loglikes.shape[0] + 2].copy(), st.cpu().numpy()[:nt.value].copy(),
                        co.cpu().numpy()[:nt.value].copy(), links)
+
+    def get_lattice_batch(self, channels, loglikes, lengths, lattice_beam, stream=None, tok_cap=None, link_cap=None,
+                          on_device=False):
+        """wfst_get_lattice_batch: the lattices of several channels in one call.  `loglikes` [n, T, V] is
+        the device tensor the channels were decoded with (channel channels[k] = row k, which has
+        consumed lengths[k] frames).  Returns a list
+        of `Lattice` (host arrays), or with on_device=True the tuple (frame_off [n, T+2], tok_first,
+        link_first, state tensor, cost tensor, link bytes tensor) with the outputs left in device
+        memory.  Without capacities the call is made twice: once to learn the sizes."""
+        import torch
+        from .lattice import Lattice
+        channels = np.ascontiguousarray(channels, dtype=np.int32)
+        n = len(channels)
+        assert loglikes.is_cuda and loglikes.dtype == getattr(torch, self.loglike_dtype) and loglikes.is_contiguous()
+        assert loglikes.ndim == 3 and loglikes.shape[0] == n and loglikes.shape[2] == self.V
+        T = int(loglikes.shape[1])
+        off = np.zeros((n, T + 2), np.int64)
+        tf, lf = np.zeros(n + 1, np.int64), np.zeros(n + 1, np.int64)
+
+        def call(tc, lc):
+            with _on(stream):
+                st = torch.zeros(max(tc, 1), dtype=torch.int32, device="cuda")
+                co = torch.zeros(max(tc, 1), dtype=torch.float32, device="cuda")
+                lk = torch.zeros(max(lc, 1) * LINK_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
+            rc = self.lib.wfst_get_lattice_batch(self.h, channels.ctypes.data, n, loglikes.data_ptr(), T,
+                                                 float(lattice_beam), st.data_ptr(), co.data_ptr(), tc,
+                                                 off.ctypes.data, lk.data_ptr(), lc, tf.ctypes.data, lf.ctypes.data,
+                                                 _stream_ptr(stream))
+            return rc, st, co, lk
+
+        if tok_cap is None or link_cap is None:
+            rc, *_ = call(0, 0)
+            if rc not in (WFST_OK, -7) or (rc == -7 and tf[n] == 0 and lf[n] == 0):
+                self._check(rc)
+            tok_cap, link_cap = int(tf[n]), int(lf[n])
+        rc, st, co, lk = call(tok_cap, link_cap)
+        self._check(rc)
+        if on_device:
+            return off, tf.copy(), lf.copy(), st, co, lk
+        sth, coh = st.cpu().numpy(), co.cpu().numpy()
+        lkh = lk.cpu().numpy()[:int(lf[n]) * LINK_DTYPE.itemsize].view(LINK_DTYPE)
+        out = []
+        for k in range(n):
+            out.append(Lattice(off[k, :int(lengths[k]) + 2].copy(), sth[tf[k]:tf[k + 1]].copy(),
+                               coh[tf[k]:tf[k + 1]].copy(), lkh[lf[k]:lf[k + 1]].copy()))
+        return out
 
     # ---- hooks
     def debug_frame_digests(self, ch):

@@ -1964,6 +1964,10 @@ struct LatticeArgs {
   unsigned long long *ctr;                    // [0] links found (written by the scan), [1] error bits
   unsigned long long *set_links;              // [frames + 1] links per set, then (after the scan) before each set
   int write;                                  // 0: count only; 1: write the links
+  // several channels in one launch: workgroup b takes set blocks[b].y of channel blocks[b].x, the
+  // blocks[b].z-th channel of the call, whose rows start ll_stride elements after the previous
+  // channel's and whose tokens are written from tok_first[blocks[b].z] on; set_links is per workgroup
+  const int4 *blocks; const long long *tok_first; long long ll_stride;
 };
 
 struct LatPass {                              // block-uniform view of one pass
@@ -2101,21 +2105,26 @@ __device__ __forceinline__ void lat_expand(const LatPass &q, const int2 *rec, un
 __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevChannels c, LatticeArgs a) {
   __shared__ LatLds sm;
   const int tid = threadIdx.x;
-  const int t = blockIdx.x;
-  const unsigned *off = c.frame_off + (size_t)a.ch * (c.max_frames + 2);
-  const int2 *rec = c.tokrec + c.lat_start[a.ch];
+  int t = blockIdx.x, ch = a.ch;
+  long long tok0 = 0, ll0 = 0;
+  if (a.blocks) {
+    const int4 b = a.blocks[blockIdx.x];
+    ch = uni(b.x); t = uni(b.y); tok0 = a.tok_first[uni(b.z)]; ll0 = (long long)uni(b.z) * a.ll_stride;
+  }
+  const unsigned *off = c.frame_off + (size_t)ch * (c.max_frames + 2);
+  const int2 *rec = c.tokrec + c.lat_start[ch];
   const unsigned o1 = off[t], n1 = off[t + 1] - o1;
   const unsigned o0 = t ? off[t - 1] : 0u, n0 = t ? o1 - o0 : 0u;
   // the set's tokens, by state id
   for (unsigned i = tid; i < n1; i += kBlock) {
     const int2 tk = rec[o1 + i];
-    if ((long long)(o1 + i) < a.tok_cap) {
-      a.tok_state[o1 + i] = g.unit[2 * (size_t)(unsigned)key_of(tk.x)].x;
-      a.tok_cost[o1 + i] = __int_as_float(tk.y);
+    if (tok0 + (long long)(o1 + i) < a.tok_cap) {
+      a.tok_state[tok0 + o1 + i] = g.unit[2 * (size_t)(unsigned)key_of(tk.x)].x;
+      a.tok_cost[tok0 + o1 + i] = __int_as_float(tk.y);
     }
   }
   if (t > 0) {                                  // the acoustic costs the arcs into A_t were taken with
-    const long long r0 = (long long)(t - 1) * a.V;
+    const long long r0 = ll0 + (long long)(t - 1) * a.V;
     if (a.ll_dtype == WFST_LOGLIKE_F32) {
       const float *row = static_cast<const float *>(a.ll) + r0;
       for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -row[v];
@@ -2127,14 +2136,14 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
       for (int v = tid; v < a.V; v += kBlock) sm.ac[v] = -__uint_as_float((unsigned)row[v] << 16);
     }
   }
-  const bool boosted = c.st[a.ch].boost_n > 0;
+  const bool boosted = c.st[ch].boost_n > 0;
   if (boosted)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
-      sm.bk[i] = c.boost_keys[(size_t)a.ch * kBoostSlots + i];
-      sm.bv[i] = c.boost_vals[(size_t)a.ch * kBoostSlots + i];
+      sm.bk[i] = c.boost_keys[(size_t)ch * kBoostSlots + i];
+      sm.bv[i] = c.boost_vals[(size_t)ch * kBoostSlots + i];
     }
   const int P = max(1, (int)((n1 + kLatGroup - 1) / kLatGroup));
-  const unsigned long long links_base = a.write ? a.set_links[t] : 0ull;
+  const unsigned long long links_base = a.write ? a.set_links[blockIdx.x] : 0ull;
   if (tid == 0) sm.n_links = 0;
   for (int p = 0; p < P; ++p) {
     for (int sl = tid; sl < kLatSlots; sl += kBlock) sm.keys[sl] = kKeyEmpty;
@@ -2152,12 +2161,12 @@ __global__ __launch_bounds__(kBlock) void wfst_lattice_kernel(DevGraph g, DevCha
     }
     __syncthreads();
     const bool rebase = c.frame_best != nullptr && t > 0;
-    const float set_best = rebase ? c.frame_best[(size_t)a.ch * (c.max_frames + 1) + t] : 0.0f;
+    const float set_best = rebase ? c.frame_best[(size_t)ch * (c.max_frames + 1) + t] : 0.0f;
     const LatPass q{g, sm, a, rec + o1, o1, t, p, P, boosted, links_base, rebase, set_best};
     lat_expand<true>(q, rec + o1, n1, o1);
     if (t > 0) lat_expand<false>(q, rec + o0, n0, o0);
   }
-  if (tid == 0 && !a.write) a.set_links[t] = sm.n_links;     // lat_expand ends with a barrier
+  if (tid == 0 && !a.write) a.set_links[blockIdx.x] = sm.n_links;     // lat_expand ends with a barrier
 }
 
 // Exclusive prefix sums of v[0..n) in place, the total into *total (one workgroup).
@@ -2205,6 +2214,9 @@ struct wfst_decoder {
   std::vector<int> state_of_blk;       // inverse, built when a debug call first needs it
   std::vector<unsigned> h_off;         // wfst_get_lattice: channel state, counters and frame offsets on the host
   unsigned *h_pinned = nullptr;        // the same for wfst_get_lattice_noalloc: pinned, allocated at create
+  // wfst_get_lattice_batch: which (channel, set) every workgroup takes, where each channel's tokens go
+  int4 *d_lat_blocks = nullptr; long long *d_tok_first = nullptr;
+  char *h_lat_batch = nullptr; size_t h_lat_batch_bytes = 0;     // pinned staging, allocated by the first such call
   // batch slots: wfst_decode_batch_slot calls on different slots may be in flight together
   int n_slots = 1, slot_channels = 0;
   std::vector<hipEvent_t> ev0, ev1;    // per slot (+ one pair for the calls that name channels): around the last kernel
@@ -2456,7 +2468,11 @@ int alloc_channels(wfst_decoder *d) {
   d->boost_on_dev.assign(N, 0);
   if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
   if ((rc = dev_alloc(d, &d->d_lat_ctr, (size_t)2))) return rc;
-  if (o.keep_token_records && (rc = dev_alloc(d, &d->d_set_links, (size_t)c.max_frames + 2))) return rc;
+  if (o.keep_token_records) {                   // one entry per token set of every channel (a call may take them all)
+    if ((rc = dev_alloc(d, &d->d_set_links, N * ((size_t)c.max_frames + 1) + 2))) return rc;
+    if ((rc = dev_alloc(d, &d->d_lat_blocks, N * ((size_t)c.max_frames + 1)))) return rc;
+    if ((rc = dev_alloc(d, &d->d_tok_first, N + 1))) return rc;
+  }
   if (o.keep_token_records)
     HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_pinned), (kHostHead + kScratchFrames + 2) * sizeof(unsigned)));
   if (o.outputs_on_host) {
@@ -2689,6 +2705,110 @@ int get_lattice_impl(wfst_decoder *d, int32_t ch, const void *loglikes, float la
   return WFST_OK;
 }
 
+// wfst_get_lattice for n channels at once: one count run, one scan and one write run over all
+// their token sets, two synchronisations.
+int get_lattice_batch_impl(wfst_decoder *d, const int32_t *channels, int32_t n, const void *loglikes, int32_t T,
+                           float lattice_beam, int32_t *tok_state, float *tok_cost, int64_t tok_cap,
+                           int64_t *frame_off, wfst_lattice_link *links, int64_t link_cap,
+                           int64_t *tok_first, int64_t *link_first, hipStream_t st) {
+  const int N = d->opts.max_channels, F = d->c.max_frames;
+  if (n < 0 || (n && !channels) || !frame_off || !tok_first || !link_first || tok_cap < 0 || link_cap < 0 ||
+      (tok_cap && (!tok_state || !tok_cost)) || (link_cap && !links) || T < 0)
+    return fail(d, WFST_ERR_INVALID_ARG, "null argument or negative size");
+  if (!(lattice_beam >= 0.0f)) return fail(d, WFST_ERR_INVALID_ARG, "lattice_beam must be >= 0");
+  tok_first[0] = link_first[0] = 0;
+  if (n == 0) return WFST_OK;
+  int lo = N, hi = -1;
+  {
+    std::vector<char> seen((size_t)N, 0);
+    for (int k = 0; k < n; ++k) {
+      const int ch = channels[k];
+      if (ch < 0 || ch >= N) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+      if (seen[ch]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel " + std::to_string(ch) + " listed twice");
+      seen[ch] = 1; lo = std::min(lo, ch); hi = std::max(hi, ch);
+    }
+  }
+  // pinned staging: states and frame offsets of channels lo..hi, the workgroup list, where each channel's
+  // tokens start, the scanned links per workgroup, the counters
+  const size_t n_blocks_max = (size_t)N * ((size_t)F + 1);
+  const size_t b_state = 0, b_off = b_state + (size_t)N * sizeof(ChanState),
+               b_blocks = (b_off + (size_t)N * ((size_t)F + 2) * sizeof(unsigned) + 15) / 16 * 16,
+               b_first = b_blocks + n_blocks_max * sizeof(int4), b_links = b_first + ((size_t)N + 1) * sizeof(long long),
+               b_ctr = b_links + (n_blocks_max + 2) * sizeof(unsigned long long), b_end = b_ctr + 2 * sizeof(unsigned long long);
+  if (!d->h_lat_batch) {
+    HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_lat_batch), b_end));
+    d->h_lat_batch_bytes = b_end;
+  }
+  char *H = d->h_lat_batch;
+  ChanState *hs = reinterpret_cast<ChanState *>(H + b_state);
+  unsigned *hoff = reinterpret_cast<unsigned *>(H + b_off);
+  int4 *hblk = reinterpret_cast<int4 *>(H + b_blocks);
+  long long *hfirst = reinterpret_cast<long long *>(H + b_first);
+  unsigned long long *hlinks = reinterpret_cast<unsigned long long *>(H + b_links);
+  unsigned long long *hctr = reinterpret_cast<unsigned long long *>(H + b_ctr);
+  // first synchronisation: what the channels hold
+  HIP_TRY(d, hipMemcpyAsync(hs + lo, d->c.st + lo, (size_t)(hi - lo + 1) * sizeof(ChanState), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipMemcpyAsync(hoff + (size_t)lo * (F + 2), d->c.frame_off + (size_t)lo * (F + 2),
+                            (size_t)(hi - lo + 1) * (F + 2) * sizeof(unsigned), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));
+  size_t nb = 0; long long ntok = 0;
+  for (int k = 0; k < n; ++k) {
+    const int ch = channels[k];
+    const ChanState &s = hs[ch];
+    if (s.status & (kStLattice | kStCapacity))
+      return fail(d, WFST_ERR_CAPACITY, "channel " + std::to_string(ch) + " stopped on an overflow: its token sets are incomplete");
+    if (s.boost_n > 0 && s.boost_states > 1)
+      return fail(d, WFST_ERR_INVALID_ARG, "lattices are defined over graph states: not available for a channel decoded "
+                                           "with a boosting acceptor of several states");
+    const int f = s.frame;
+    if (f < 0 || f > F || f > T)
+      return fail(d, WFST_ERR_INVALID_ARG, "channel " + std::to_string(ch) + " has " + std::to_string(f) +
+                                               " frames, more than the T = " + std::to_string(T) + " rows per channel");
+    if (f > 0 && !loglikes) return fail(d, WFST_ERR_INVALID_ARG, "null loglikes");
+    const unsigned *off = hoff + (size_t)ch * (F + 2);
+    int64_t *fo = frame_off + (size_t)k * ((size_t)T + 2);
+    for (int t = 0; t <= f + 1; ++t) fo[t] = (int64_t)off[t];
+    for (int t = f + 2; t < T + 2; ++t) fo[t] = (int64_t)off[f + 1];
+    hfirst[k] = ntok; tok_first[k] = ntok;
+    for (int t = 0; t <= f; ++t) hblk[nb++] = make_int4(ch, t, k, 0);
+    ntok += (long long)off[(size_t)f + 1];
+  }
+  hfirst[n] = ntok; tok_first[n] = ntok;
+  HIP_TRY(d, hipMemcpyAsync(d->d_lat_blocks, hblk, nb * sizeof(int4), hipMemcpyHostToDevice, st));
+  HIP_TRY(d, hipMemcpyAsync(d->d_tok_first, hfirst, ((size_t)n + 1) * sizeof(long long), hipMemcpyHostToDevice, st));
+  HIP_TRY(d, hipMemsetAsync(d->d_lat_ctr, 0, 2 * sizeof(unsigned long long), st));
+  LatticeArgs a{};
+  a.ch = 0; a.frames = 0; a.ll = loglikes; a.V = d->V; a.ll_dtype = d->opts.loglike_dtype;
+  a.lattice_beam = lattice_beam;
+  a.tok_state = tok_state; a.tok_cost = tok_cost; a.tok_cap = tok_cap;
+  a.links = links; a.link_cap = link_cap; a.ctr = d->d_lat_ctr; a.set_links = d->d_set_links;
+  a.blocks = d->d_lat_blocks; a.tok_first = d->d_tok_first; a.ll_stride = (long long)T * d->V;
+  a.write = 0;
+  hipLaunchKernelGGL(wfst_lattice_kernel, dim3((unsigned)nb), dim3(kBlock), 0, st, d->g, d->c, a);
+  HIP_TRY(d, hipGetLastError());
+  hipLaunchKernelGGL(wfst_lattice_scan, dim3(1), dim3(kBlock), 0, st, d->d_set_links, (int)nb, d->d_lat_ctr);
+  HIP_TRY(d, hipGetLastError());
+  if (link_cap > 0 && ntok <= tok_cap) {
+    a.write = 1;
+    hipLaunchKernelGGL(wfst_lattice_kernel, dim3((unsigned)nb), dim3(kBlock), 0, st, d->g, d->c, a);
+    HIP_TRY(d, hipGetLastError());
+  }
+  hctr[0] = hctr[1] = 0;
+  HIP_TRY(d, hipMemcpyAsync(hlinks, d->d_set_links, nb * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipMemcpyAsync(hctr, d->d_lat_ctr, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+  HIP_TRY(d, hipStreamSynchronize(st));         // second and last synchronisation
+  {
+    size_t b = 0;
+    for (int k = 0; k < n; ++k) { link_first[k] = (int64_t)hlinks[b]; b += (size_t)hs[channels[k]].frame + 1; }
+    link_first[n] = (int64_t)hctr[0];
+  }
+  if (hctr[1]) return fail(d, WFST_ERR_CAPACITY, "lattice kernel: a token set overflowed its lookup table");
+  if (ntok > tok_cap || link_first[n] > link_cap)
+    return fail(d, WFST_ERR_CAPACITY, "the lattices need room for " + std::to_string(ntok) + " tokens and " +
+                                          std::to_string(link_first[n]) + " links");
+  return WFST_OK;
+}
+
 }  // namespace
 
 namespace {
@@ -2745,6 +2865,7 @@ int32_t wfst_decoder_destroy(wfst_decoder *d) {
   for (void *p : d->allocs) (void)hipFree(p);
   if (d->h_boost) (void)hipHostFree(d->h_boost);
   if (d->h_pinned) (void)hipHostFree(d->h_pinned);
+  if (d->h_lat_batch) (void)hipHostFree(d->h_lat_batch);
   for (hipEvent_t e : d->ev0) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : d->ev1) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : d->boost_ev) if (e) (void)hipEventDestroy(e);
@@ -3023,6 +3144,16 @@ int32_t wfst_get_lattice(wfst_decoder *d, int32_t ch, const void *loglikes, floa
   return get_lattice_impl(d, ch, loglikes, lattice_beam, tok_state, tok_cost, tok_cap, frame_off, links, link_cap,
                           n_tokens, n_links, static_cast<hipStream_t>(stream), d->d_lat_ctr, d->d_set_links,
                           d->h_off.data(), d->c.max_frames);
+}
+
+int32_t wfst_get_lattice_batch(wfst_decoder *d, const int32_t *channels, int32_t n, const void *loglikes, int32_t T,
+                               float lattice_beam, int32_t *tok_state, float *tok_cost, int64_t tok_cap,
+                               int64_t *frame_off, wfst_lattice_link *links, int64_t link_cap,
+                               int64_t *tok_first, int64_t *link_first, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (!d->c.tokrec) return fail(d, WFST_ERR_INVALID_ARG, "the decoder was created without keep_token_records");
+  return get_lattice_batch_impl(d, channels, n, loglikes, T, lattice_beam, tok_state, tok_cost, tok_cap, frame_off,
+                                links, link_cap, tok_first, link_first, static_cast<hipStream_t>(stream));
 }
 
 int32_t wfst_get_lattice_noalloc(wfst_decoder *d, int32_t ch, const void *loglikes, float lattice_beam,

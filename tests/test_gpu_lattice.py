@@ -206,3 +206,48 @@ def test_lattice_with_cost_offsets(torch_cuda, c1):
     check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, 2.0, cost_offset=True)
     check_lattice(torch_cuda, c1.graph, c1.loglikes[0], 100, c1.beam, c1.max_active, 2.0, cost_offset=True,
                   streaming_chunk=16)
+
+
+def test_lattices_of_several_channels_in_one_call(torch_cuda, c2):
+    """wfst_get_lattice_batch: utterances of different lengths (one of zero frames), one of them
+    boosted, their channels named in another order than they were decoded in; every lattice against
+    the oracle's, token sets and links, and against the one-channel call."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder, WfstError
+    torch = torch_cuda
+    g = c2.graph
+    pick = [0, 3, 5, 7, 9]
+    T = 60
+    lengths = np.array([60, 0, 23, 41, 1], np.int32)
+    ll = np.ascontiguousarray(c2.loglikes[pick, :T])
+    boost = (np.arange(1, 2000, 7, dtype=np.int32), np.full(len(range(1, 2000, 7)), -1.5, np.float32))
+    boosts = [None, None, boost, None, None]
+    dec = Decoder(g, max_channels=8, max_frames=T, max_active_hint=c2.max_active, keep_token_records=True)
+    lld = torch.from_numpy(ll).cuda()
+    dec.decode_batch(lld, lengths, c2.beam, c2.max_active, boosts=boosts)
+    order = np.array([3, 0, 4, 2, 1], np.int32)                      # channel b holds utterance b
+    lats = dec.get_lattice_batch(order, lld[torch.from_numpy(order.astype(np.int64)).cuda()].contiguous(), lengths[order], 3.0)
+    o = Oracle(g)
+    for k, b in enumerate(order):
+        n = int(lengths[b])
+        L = o.lattice(ll[b], n, beam=c2.beam, max_active=c2.max_active, lattice_beam=3.0, boost=boosts[b])
+        lat = lats[k]
+        assert lat.frame_off.tolist() == L.set_off.tolist(), f"utterance {b}"
+        for t in range(n + 1):
+            a, e = int(L.set_off[t]), int(L.set_off[t + 1])
+            got = sorted(zip(lat.state[a:e].tolist(), lat.cost[a:e].view(np.uint32).tolist()))
+            want = sorted(zip(L.states[a:e].tolist(), L.costs[a:e].view(np.uint32).tolist()))
+            assert got == want, f"utterance {b}: token set of frame {t} differs"
+        want, got = oracle_rows(o, g, L), gpu_rows(lat)
+        assert got.shape == want.shape and (got == want).all(), f"utterance {b}: links differ"
+        one = dec.get_lattice(int(b), lld[b, :n].contiguous(), 3.0)
+        assert (gpu_rows(one) == got).all()
+    # errors: a channel twice, too few rows, capacities
+    with pytest.raises(WfstError, match="twice"):
+        dec.get_lattice_batch([0, 0], lld[:2].contiguous(), lengths[:2], 3.0)
+    with pytest.raises(WfstError, match="rows per channel"):
+        dec.get_lattice_batch([0], lld[:1, :10].contiguous(), [10], 3.0)
+    with pytest.raises(WfstError, match="need room for"):
+        dec.get_lattice_batch([0, 2], lld[[0, 2]].contiguous(), lengths[[0, 2]], 3.0, tok_cap=10, link_cap=10)
+    assert dec.get_lattice_batch([], lld[:0].contiguous(), [], 3.0) == []
+    dec.close()
