@@ -106,6 +106,9 @@ constexpr int kHubSeg = 64 * kUE;             // arcs of a listed state one wave
 #ifndef WFST_UM
 #define WFST_UM 1
 #endif
+#ifndef WFST_USW
+#define WFST_USW 2                            // queue records in flight per lane when the staying tokens are sorted out
+#endif
 constexpr int kUC = WFST_UC;                  // ... when survivors become tokens
 #ifndef WFST_REGION_BITS
 #define WFST_REGION_BITS 2
@@ -1134,23 +1137,35 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   // the buffer's destinations is still there: a self-loop candidate inside the beam whose key's
   // bit is clear meets no other candidate, so it is the recombined token of its state: marked and
   // histogrammed (exactly, in every bin).  The few whose bit is set are left for the table passes.
-  for (int i0 = 0; i0 < n_tok; i0 += kBlock) {
-    const int i = i0 + tid;
-    const int2 q = i < n_tok ? Q[i] : make_int2(0, 0);
-    const float nc = stay_cost(x, __int_as_float(q.y));
-    const int stays = (int)(((unsigned)q.x & kFlagSimple) != 0) | (int)((hasstay[min(i, n_tok - 1) >> 5] >> (i & 31)) & 1u);
-    const int in = (int)(i < n_tok) & stays & (int)(nc < INFINITY) & (int)cut.in_beam(nc);
-    const unsigned fb = filter_bit(key_of(q.x));
-    const int cont = in & (int)((sm.u.e.filter[fb >> 5] >> (fb & 31)) & 1u);
-    const int alone = in & (int)!cont;
-    if (alone) atomicAdd(&sm.hist3[cut.bin(nc)], 1u);
-    const unsigned long long ma_ = __ballot(alone);
-    const int lane = tid & 63;                   // the wave's 64 tokens are two words of the bit set
-    if (lane == 0) staybits[i >> 5] = (unsigned)ma_;
-    if (lane == 32) staybits[i >> 5] = (unsigned)(ma_ >> 32);
-    const int cn[1] = {cont}; int ci[1];
-    wave_alloc_n<1>(&sm.n_cont, cn, ci);         // at most one entry per token: the list cannot overflow its qcap records
-    if (cont) CL[ci[0]] = make_int4(i, q.x, q.y, 0);
+  constexpr int kS = WFST_USW;                   // queue records in flight per lane
+  for (int i0 = 0; i0 < n_tok; i0 += kBlock * kS) {
+    int2 q[kS]; int cn[kS], ci[kS];
+#pragma unroll
+    for (int u = 0; u < kS; ++u) {
+      const int i = i0 + u * kBlock + tid;
+      q[u] = i < n_tok ? Q[i] : make_int2(0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < kS; ++u) {
+      const int i = i0 + u * kBlock + tid;         // (whole waves beyond the set write words nobody reads)
+      const float nc = stay_cost(x, __int_as_float(q[u].y));
+      const int stays = (int)(((unsigned)q[u].x & kFlagSimple) != 0) | (int)((hasstay[(i & (kQueueMax - 1)) >> 5] >> (i & 31)) & 1u);
+      const int in = (int)(i < n_tok) & stays & (int)(nc < INFINITY) & (int)cut.in_beam(nc);
+      const unsigned fb = filter_bit(key_of(q[u].x));
+      cn[u] = in & (int)((sm.u.e.filter[fb >> 5] >> (fb & 31)) & 1u);
+      const int alone = in & (int)!cn[u];
+      if (alone) atomicAdd(&sm.hist3[cut.bin(nc)], 1u);
+      const unsigned long long ma_ = __ballot(alone);
+      const int lane = tid & 63;                   // the wave's 64 tokens are two words of the bit set
+      if (i < kQueueMax) {
+        if (lane == 0) staybits[i >> 5] = (unsigned)ma_;
+        if (lane == 32) staybits[i >> 5] = (unsigned)(ma_ >> 32);
+      }
+    }
+    wave_alloc_n<kS>(&sm.n_cont, cn, ci);          // at most one entry per token: the list cannot overflow its qcap records
+#pragma unroll
+    for (int u = 0; u < kS; ++u)
+      if (cn[u]) CL[ci[u]] = make_int4(i0 + u * kBlock + tid, q[u].x, q[u].y, 0);
   }
 
   // ---- 1. select: the exact histogram of the tokens that stay plus a sample of the buffer
