@@ -1,5 +1,7 @@
 """Pins for the oracle's word boosting (paper, Section "Word boosting"): the utterance is decoded
 as if the graph were TLG o B for a single-state acceptor B given as a table word id -> score."""
+import os
+
 import numpy as np
 import pytest
 
@@ -48,16 +50,20 @@ def test_two_word_table_like_the_paper_figure():
     """Figure "Example word boosting WFSA": "fish" boosted by 6, "fox" by 2 (negative scores,
     since the decoder minimises).  Three competing one-arc words; costs worked out by hand."""
     FISH, FOX, DOG = 1, 2, 3
+    here = os.path.dirname(os.path.abspath(__file__))
+    amounts = dict(ln.split() for ln in open(os.path.join(here, "golden", "word_boosting_wfsa.txt")) if ln[0] != "#")
+    fish, fox = -float(amounts["fish"]), -float(amounts["fox"])       # boosted = negative score
+    assert (fish, fox) == (-6.0, -2.0)
     arcs = [(0, 1, 2, FISH, 7.0), (0, 1, 3, FOX, 3.5), (0, 1, 4, DOG, 1.0), (1, 1, 1, 0, 0.0)]
     g = _from_arc_list(2, 0, 4, arcs, [INF, 0.0])
     ll = np.array([[-9.0, -1.0, -1.0, -1.0], [-0.5, -9.0, -9.0, -9.0]], np.float32)
     o = Oracle(g)
     plain = o.decode(ll, beam=50.0)
     assert plain.words.tolist() == [DOG] and plain.cost == 1.0 + 1.0 + 0.5
-    boosted = o.decode(ll, beam=50.0, boost=([FISH, FOX], [-6.0, -2.0]))
+    boosted = o.decode(ll, beam=50.0, boost=([FISH, FOX], [fish, fox]))
     #   fish: 7.0 + 1.0 - 6.0 + 0.5 = 2.5 ; fox: 3.5 + 1.0 - 2.0 + 0.5 = 3.0 ; dog: 2.5 (tie with fish!)
     assert boosted.cost == 2.5
-    only_fox = o.decode(ll, beam=50.0, boost=([FOX], [-2.0 - 1.0]))
+    only_fox = o.decode(ll, beam=50.0, boost=([FOX], [fox - 1.0]))
     assert only_fox.words.tolist() == [FOX] and only_fox.cost == 3.5 + 1.0 - 3.0 + 0.5
 
 
