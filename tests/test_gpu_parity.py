@@ -512,6 +512,20 @@ def test_self_loop_candidates_that_tie_exactly_with_candidates_of_other_arcs(tor
         check_batch(torch_cuda, g, ll, lengths, 6.0, 1500, max_active_hint=20000, boosts=boosts)
 
 
+def test_branchy_graph_where_no_state_has_the_self_loop_alone(torch_cuda):
+    """Every state has the blank self-loop and one to three more arcs (the shape of the c3_branchy
+    measurement at a tenth of its size): no token can skip the graph read, every token's
+    self-loop candidate is implied, max-active binds on every frame."""
+    from workloads import ctc_loglikes, random_lengths, tlg_shaped_graph
+    g = tlg_shaped_graph(31, 1_000_000, 4_000_000, num_classes=129, alpha=1.8, k_max=5000, p_eps=0.2,
+                         num_words=50_000, extra_lo=1, extra_hi=3)
+    lengths = random_lengths(31, 12, 40, 160)
+    T = int(lengths.max())
+    ll = ctc_loglikes(31, lengths, T, 129, sigma=2.0, p_blank=0.65, blank_boost=6.0, token_boost=4.0)
+    refs = check_batch(torch_cuda, g, ll, lengths, 17.0, 10000, max_active_hint=10000)
+    assert sum(int(r.counters[5]) for r in refs) > 0.8 * int(lengths.sum())
+
+
 def test_epsilon_rounds_larger_than_one_chunk_and_one_table(torch_cuda):
     """A closure round with 3,000 items and 9,000 arcs (not fused: several chunks of items, several
     table passes) after a fused round of one item with 3,000 arcs."""
