@@ -144,16 +144,16 @@ def main_streaming(args):
     from paper_2311_04996_amd import Decoder
     from workloads import CONFIGS, ctc_loglikes
     from workloads.configs import make_graph
-    C, n_chunks, warm = 16, args.chunks, 5
+    C, n_chunks, warm, extra = 16, args.chunks, 5, 10
     n = args.channels
     c = CONFIGS["c3_large"]
     g = make_graph("c3_large")
-    T = C * (n_chunks + warm)
+    T = C * (n_chunks + warm + extra)
     lengths = np.full(n, T, np.int32)
     ll = ctc_loglikes(4, lengths, T, g.num_classes, **c["ll"])                 # seed 4: the streaming config
     # chunk-major copy: [chunk][channel][C][V], the layout a batching server hands over
     chunks = torch.from_numpy(np.ascontiguousarray(
-        ll.reshape(n, n_chunks + warm, C, g.num_classes).transpose(1, 0, 2, 3))).cuda()
+        ll.reshape(n, n_chunks + warm + extra, C, g.num_classes).transpose(1, 0, 2, 3))).cuda()
     # --recycle-window W: every channel's backpointer memory is a ring over W frames, so the streams
     # could go on for any length (a result is flagged if its path joins the previous result's path
     # further back than that; on this graph hypotheses stay apart for hundreds of frames)
@@ -164,7 +164,7 @@ def main_streaming(args):
     nfr = np.full(n, C, np.int32)
     dec.init_channels(chans, float(c["beam"]), int(c["max_active"]))
     torch.cuda.synchronize()
-    print(f"[bench] streaming: {n} channels x {n_chunks}+{warm} chunks of {C} frames, "
+    print(f"[bench] streaming: {n} channels x {n_chunks}+{warm}+{extra} chunks of {C} frames, "
           f"{dec.device_bytes() / 2**30:.1f} GiB on device", file=sys.stderr, flush=True)
     lat, out = [], None
     for k in range(n_chunks + warm):
@@ -174,6 +174,17 @@ def main_streaming(args):
         lat.append(time.perf_counter() - t0)
         assert not (out[3] & (8 | 16)).any(), (f"chunk {k}: a channel overflowed a buffer (flags "
                                                f"{sorted(set(out[3].tolist()))}): the run is invalid")
+    assert not (out[3] & (8 | 16)).any(), "a channel overflowed a buffer: the run is invalid"
+    # where a chunk's time goes: a few more chunks with a synchronisation between the two calls
+    t_adv, t_ker, t_par = [], [], []
+    for k in range(n_chunks + warm, n_chunks + warm + extra):
+        t0 = time.perf_counter()
+        dec.advance_chunk(chans, chunks[k], nfr)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        t_ker.append(dec.last_kernel_ms())
+        out = dec.get_partial_batch(chans, finalize=False, out=out)
+        t_adv.append(1e3 * (t1 - t0)); t_par.append(1e3 * (time.perf_counter() - t1))
     assert not (out[3] & (8 | 16)).any(), "a channel overflowed a buffer: the run is invalid"
     device_gib = dec.device_bytes() / 2**30
     lat = np.array(lat[warm:]) * 1e3
@@ -190,6 +201,9 @@ def main_streaming(args):
             "channels_at_realtime_p99": int(n * chunk_s * 1e3 / p99),
             "channels_at_realtime_p50": int(n * chunk_s * 1e3 / p50),
             "mean_words_per_partial": float(out[1].mean()),
+            "breakdown_ms": {"advance_chunk": float(np.median(t_adv)), "advance_chunk_kernel": float(np.median(t_ker)),
+                             "get_partial_batch": float(np.median(t_par)),
+                             "how": f"medians of {extra} more chunks with a synchronisation between the two calls"},
             # the paper's M/D/1 model (Section "Streaming inference") applied to the measured
             # compute latency: mean queue and total latency of a chunk request against load
             "latency_model": load_table(float(lat.mean()) * 1e-3, chunk_s, n)}
