@@ -260,6 +260,14 @@ int32_t wfst_init_channels(wfst_decoder *dec, const int32_t *channels, int32_t n
 int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n,
                            const float *loglikes, const int32_t *nframes, int32_t C, int32_t V,
                            void *stream);
+/* wfst_advance_chunk followed by wfst_get_partial_batch on the same channels, in ONE launch: every
+ * channel consumes its frames and then reports its partial (finalize = 0) or final hypothesis
+ * (Section "Streaming inference": the serving loop wants a transcript after every chunk).  Same
+ * arguments, outputs, results and errors as the two calls made one after the other. */
+int32_t wfst_advance_chunk_partial(wfst_decoder *dec, const int32_t *channels, int32_t n,
+                                   const float *loglikes, const int32_t *nframes, int32_t C, int32_t V,
+                                   int32_t finalize, int32_t *words, int32_t *nwords, float *cost,
+                                   int32_t *flags, void *stream);
 int32_t wfst_get_partial(wfst_decoder *dec, int32_t ch, int32_t finalize, int32_t *words,
                          int32_t cap, int32_t *nwords, float *cost, int32_t *flags, void *stream);
 int32_t wfst_get_partial_batch(wfst_decoder *dec, const int32_t *channels, int32_t n, int32_t finalize,

@@ -21,7 +21,7 @@ LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
            "wfst_decode_batch_boost_fst", "wfst_decode_batch_slot", "wfst_slot_kernel_ms", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels",
-           "wfst_advance_chunk", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
+           "wfst_advance_chunk", "wfst_advance_chunk_partial", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
            "wfst_get_lattice_noalloc", "wfst_get_lattice_batch",
            "wfst_debug_frame_digests",
            "wfst_debug_get_tokens", "wfst_debug_get_token_pairs", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_device_bytes",
@@ -113,6 +113,7 @@ def load_library():
     lib.wfst_debug_get_token_pairs.argtypes = [p, i32, p, p, p, i32, p]
     lib.wfst_init_channels.argtypes = [p, p, i32, f32, i32, p, p]
     lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
+    lib.wfst_advance_chunk_partial.argtypes = [p, p, i32, p, p, i32, i32, i32, p, p, p, p, p]
     lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
     lib.wfst_get_partial_batch.argtypes = [p, p, i32, i32, p, p, p, p, p]
     lib.wfst_debug_frame_digests.argtypes = [p, i32, p, p, i32, p]
@@ -294,6 +295,35 @@ class Decoder:
         assert channels.shape == (n,) and nframes.shape == (n,)
         self._check(self.lib.wfst_advance_chunk(self.h, channels.ctypes.data, n, loglikes.data_ptr(),
                                                 nframes.ctypes.data, Cn, V, _stream_ptr(stream)))
+
+    def _partial_outputs(self, n, stream):
+        import torch
+        if self.outputs_on_host:
+            return (np.zeros((n, self.max_words), np.int32), np.zeros(n, np.int32),
+                    np.zeros(n, np.float32), np.zeros(n, np.int32))
+        with _on(stream):
+            return (torch.zeros((n, self.max_words), dtype=torch.int32, device="cuda"),
+                    torch.zeros(n, dtype=torch.int32, device="cuda"),
+                    torch.zeros(n, dtype=torch.float32, device="cuda"),
+                    torch.zeros(n, dtype=torch.int32, device="cuda"))
+
+    def advance_chunk_partial(self, channels, loglikes, nframes, finalize=False, stream=None, out=None):
+        """wfst_advance_chunk_partial: advance_chunk and get_partial_batch in one launch.  Returns
+        (words [n, max_words], nwords [n], cost [n], flags [n]) like get_partial_batch."""
+        import torch
+        assert loglikes.is_cuda and loglikes.dtype == getattr(torch, self.loglike_dtype) and loglikes.is_contiguous()
+        n, Cn, V = loglikes.shape
+        channels = np.ascontiguousarray(channels, dtype=np.int32)
+        nframes = np.ascontiguousarray(nframes, dtype=np.int32)
+        assert channels.shape == (n,) and nframes.shape == (n,)
+        if out is None:
+            out = self._partial_outputs(n, stream)
+        ptr = (lambda a: a.ctypes.data) if self.outputs_on_host else (lambda t: t.data_ptr())
+        self._check(self.lib.wfst_advance_chunk_partial(self.h, channels.ctypes.data, n, loglikes.data_ptr(),
+                                                        nframes.ctypes.data, Cn, V, int(finalize),
+                                                        ptr(out[0]), ptr(out[1]), ptr(out[2]), ptr(out[3]),
+                                                        _stream_ptr(stream)))
+        return out
 
     def get_partial(self, ch, finalize=False, stream=None, cap=None):
         """Returns (words ndarray, cost, flags) of the channel's best hypothesis so far (at most

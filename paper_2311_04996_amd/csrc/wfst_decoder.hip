@@ -3070,6 +3070,49 @@ int32_t wfst_advance_chunk(wfst_decoder *d, const int32_t *channels, int32_t n, 
   return launch(d, chan, nfr, io, a, static_cast<hipStream_t>(stream));
 }
 
+int32_t wfst_advance_chunk_partial(wfst_decoder *d, const int32_t *channels, int32_t n, const float *loglikes,
+                                   const int32_t *nframes, int32_t C, int32_t V, int32_t finalize,
+                                   int32_t *words, int32_t *nwords, float *cost, int32_t *flags, void *stream) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (n < 0 || C < 0 || (n > 0 && (!channels || !nframes)) || (n > 0 && C > 0 && !loglikes))
+    return fail(d, WFST_ERR_INVALID_ARG, "null or negative argument");
+  if (n == 0) return WFST_OK;
+  if (!words || !nwords || !cost || !flags) return fail(d, WFST_ERR_INVALID_ARG, "null output");
+  if (V != d->V) return fail(d, WFST_ERR_INVALID_ARG, "V differs from the graph's num_classes");
+  if (n > d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "more channels than max_channels");
+  std::vector<char> seen(d->opts.max_channels, 0);
+  std::vector<int> chan(n), nfr(n), io(n);
+  for (int i = 0; i < n; ++i) {
+    if (channels[i] < 0 || channels[i] >= d->opts.max_channels) return fail(d, WFST_ERR_BAD_CHANNEL, "channel out of range");
+    if (seen[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel listed twice");
+    seen[channels[i]] = 1;
+    if (!d->chan_ready[channels[i]]) return fail(d, WFST_ERR_BAD_CHANNEL, "channel " + std::to_string(channels[i]) + " has not been initialised (or a batch decode has since taken its slot's lattice memory)");
+    if (nframes[i] < 0 || nframes[i] > C) return fail(d, WFST_ERR_INVALID_ARG, "nframes outside [0, C]");
+    chan[i] = channels[i]; nfr[i] = nframes[i]; io[i] = i;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool host_out = d->opts.outputs_on_host != 0;
+  // one launch: every channel's workgroup consumes its frames and then, with the token set still
+  // at hand, chooses the best token and walks the new part of its path
+  LaunchArgs a{};
+  a.ll = loglikes; a.ll_stride = (long long)C * V; a.V = V; a.ll_dtype = d->opts.loglike_dtype;
+  a.mode = kModeFinal; a.finalize = finalize ? 1 : 0;
+  a.words = host_out ? d->o_words : words; a.nwords = host_out ? d->o_nwords : nwords;
+  a.cost = host_out ? d->o_cost : cost;    a.flags = host_out ? d->o_flags : flags;
+  a.max_words = d->opts.max_words;
+  int rc = launch(d, chan, nfr, io, a, st);
+  if (rc) return rc;
+  if (host_out) {
+    const size_t mw = (size_t)d->opts.max_words;
+    HIP_TRY(d, hipMemcpyAsync(words, d->o_words, n * mw * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(nwords, d->o_nwords, n * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(cost, d->o_cost, n * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipMemcpyAsync(flags, d->o_flags, n * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(d, hipStreamSynchronize(st));
+  }
+  return WFST_OK;
+}
+
 int32_t wfst_get_partial(wfst_decoder *d, int32_t ch, int32_t finalize, int32_t *words, int32_t cap,
                          int32_t *nwords, float *cost, int32_t *flags, void *stream) {
   if (!d) return WFST_ERR_INVALID_ARG;

@@ -925,6 +925,52 @@ def test_partial_results_after_every_chunk_equal_the_oracle_on_the_prefix(torch_
         dec.close()
 
 
+def test_advance_and_partial_in_one_launch(torch_cuda, c2):
+    """wfst_advance_chunk_partial: the frames of a chunk and the partial hypotheses of the same
+    channels in one launch; after every chunk exactly the oracle's result on the frames so far, for
+    channels that advance by different numbers of frames (one of them by none), device and host
+    outputs, and a final call that applies the final costs."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    pick = [1, 4, 6]
+    L = 150
+    ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[pick, :L])).cuda()
+    o = Oracle(c2.graph)
+    chunk = 20
+    for host in (False, True):
+        dec = Decoder(c2.graph, max_channels=4, max_frames=L, max_words=64, max_active_hint=c2.max_active,
+                      outputs_on_host=host)
+        chans = np.array([3, 0, 2], np.int32)
+        dec.init_channels(chans, c2.beam, c2.max_active)
+        done = np.zeros(3, np.int64)
+        step = np.array([20, 13, 0], np.int32)                   # the third channel only advances every other chunk
+        for k in range(6):
+            nfr = step.copy()
+            nfr[2] = 20 if k % 2 else 0
+            buf = torch.zeros((3, chunk, c2.graph.num_classes), dtype=torch.float32, device="cuda")
+            for i in range(3):
+                buf[i, :nfr[i]] = ll[i, done[i]:done[i] + nfr[i]]
+            fin = k == 5
+            words, nwords, cost, flags = dec.advance_chunk_partial(chans, buf, nfr, finalize=fin)
+            done += nfr
+            if not host:
+                torch.cuda.synchronize()
+                words, nwords, cost, flags = (t.cpu().numpy() for t in (words, nwords, cost, flags))
+            for i in range(3):
+                r = o.decode(c2.loglikes[pick[i]], length=int(done[i]), beam=c2.beam, max_active=c2.max_active,
+                             max_words=64, finalize=fin)
+                assert words[i, :nwords[i]].tolist() == r.words.tolist(), (host, k, i)
+                assert cost[i] == np.float32(r.cost) and int(flags[i]) == r.flags, (host, k, i)
+            # the separate call afterwards reports the same
+            w2 = dec.get_partial_batch(chans, finalize=fin)
+            if not host:
+                torch.cuda.synchronize()
+                w2 = tuple(t.cpu().numpy() for t in w2)
+            assert (w2[1] == nwords).all() and (w2[2] == cost).all() and (w2[3] == flags).all()
+        dec.close()
+
+
 # ------------------------------------------------------------------------------- batch slots, shared lattice memory
 def test_batches_in_flight_on_one_decoder(torch_cuda, c2, c2_refs):
     """One decoder, three batch slots: three batches decoded at the same time on three streams,
