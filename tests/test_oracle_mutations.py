@@ -1,7 +1,9 @@
 """The oracle's pins must notice a mistake: every mutant below is a copy of oracle/ with ONE
 plausible error planted in wfst_oracle.c (a comparison flipped, a tie-break reversed, a limit
 changed), and the pin tests are run against that copy in a child process.  A mutant that passes
-them means that part of the oracle is held by nothing but itself.
+them means that part of the oracle is held by nothing but itself.  The decode loop, its prune
+rule, its tie-breaks and the boosting acceptor are checked against the pins of the decode proper;
+the word-boost table, the lattice output and the cost offsets against the pins of those options.
 
 Everything here runs on the CPU; the mistakes are planted in the oracle only.
 """
@@ -14,6 +16,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PIN_FILES = ["tests/test_oracle_decode_pins.py", "tests/test_oracle_pins.py", "tests/test_oracle_boost_fst.py"]
+# pins of the options: word-boost table, lattice output, cost offsets
+OPTION_PIN_FILES = ["tests/test_oracle_boost.py", "tests/test_oracle_lattice.py", "tests/test_oracle_offset.py"]
 
 # (name, text in wfst_oracle.c, replacement); the text must occur exactly once
 MUTANTS = [
@@ -95,10 +99,54 @@ MUTANTS = [
 ]
 
 
-def _run_pins(tmp_root):
+# the same for the optional parts: (name, text, replacement), run against OPTION_PIN_FILES
+OPTION_MUTANTS = [
+    ("lattice: an emitting link exactly lattice_beam above the destination is left out",
+     "if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, a, nc);",
+     "if ((nc - C1[j]) < lattice_beam) PUT(t, i, j, a, nc);"),
+    ("lattice: an epsilon link exactly lattice_beam above the destination is left out",
+     "if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, p->Ae + a, nc);",
+     "if ((nc - C1[j]) < lattice_beam) PUT(t, i, j, p->Ae + a, nc);"),
+    ("lattice: links are measured against the source token's cost",
+     "if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, a, nc);",
+     "if ((nc - C0[i]) <= lattice_beam) PUT(t, i, j, a, nc);"),
+    ("lattice: epsilon arcs are not links",
+     "if ((nc - C1[j]) <= lattice_beam) PUT(t, i, j, p->Ae + a, nc);",
+     "(void)j;"),
+    ("lattice: the boost of an epsilon arc's word is forgotten",
+     "        if (boost && p->x_ol[a] != 0) nc = canon(nc + boost[p->x_ol[a]]);\n        const int32_t j = where[p->x_next[a]];",
+     "        const int32_t j = where[p->x_next[a]];"),
+    ("lattice with cost offsets: a link is rebased by the wrong set's offset",
+     "if (frame_best) nc = canon(nc - frame_best[t]);",
+     "if (frame_best && t > 1) nc = canon(nc - frame_best[t - 1]);"),
+    ("lattice with cost offsets: links across a frame boundary are not rebased",
+     "if (frame_best) nc = canon(nc - frame_best[t]);",
+     "(void)frame_best;"),
+    ("cost offsets: the closure still measures against the old best",
+     "      offset_sum += (double)best;\n      k.best = 0.0f;",
+     "      offset_sum += (double)best;"),
+    ("cost offsets: the offsets are not added back",
+     "      offset_sum += (double)best;\n",
+     "      offset_sum += 0.0;\n"),
+    ("word boost table: emitting arcs with a word are not boosted",
+     "          nb = boost_step(B, b, p->e_ol[a], &add, &sc);\n          if (add) nc = canon(nc + sc);",
+     "          nb = boost_step(B, b, p->e_ol[a], &add, &sc);\n          (void)add;"),
+    ("word boost table: epsilon arcs with a word are not boosted",
+     "        nb = boost_step(B, b, p->x_ol[a], &add, &sc);\n        if (add) nc = canon(nc + sc);",
+     "        nb = boost_step(B, b, p->x_ol[a], &add, &sc);\n        (void)add;"),
+    ("word boost table: the score of the next word id is taken",
+     "if (B->table) { *add = 1; *score = B->table[o]; return 0; }",
+     "if (B->table) { *add = 1; *score = B->table[o > 1 ? o - 1 : o]; return 0; }"),
+    ("word boost: the score is subtracted",
+     "        if (boost && p->e_ol[a] != 0) nc = canon(nc + boost[p->e_ol[a]]);\n          if (frame_best)",
+     "        if (boost && p->e_ol[a] != 0) nc = canon(nc - boost[p->e_ol[a]]);\n          if (frame_best)"),
+]
+
+
+def _run_pins(tmp_root, pin_files=None):
     env = dict(os.environ, PYTHONPATH=os.pathsep.join([tmp_root, ROOT]))
     # the child's working directory comes first on its module path: the copy there shadows oracle/
-    files = [os.path.join(ROOT, f) for f in PIN_FILES]
+    files = [os.path.join(ROOT, f) for f in (pin_files or PIN_FILES)]
     probe = subprocess.run([sys.executable, "-c", "import oracle; print(oracle.__file__)"],
                            cwd=tmp_root, env=env, capture_output=True, text=True)
     assert probe.stdout.strip().startswith(tmp_root), (probe.stdout, probe.stderr)
@@ -128,4 +176,15 @@ def test_unmutated_copy_passes(tmp_path):
 @pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
 def test_mutant_is_caught(tmp_path, name, old, new):
     r = _run_pins(_copy_oracle(tmp_path, old, new))
+    assert r.returncode == 1 and "failed" in r.stdout, f"mutant survived ({name}):\n" + r.stdout[-1500:] + r.stderr[-1500:]
+
+
+def test_unmutated_copy_passes_the_option_pins(tmp_path):
+    r = _run_pins(_copy_oracle(tmp_path), OPTION_PIN_FILES)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+@pytest.mark.parametrize("name,old,new", OPTION_MUTANTS, ids=[m[0] for m in OPTION_MUTANTS])
+def test_option_mutant_is_caught(tmp_path, name, old, new):
+    r = _run_pins(_copy_oracle(tmp_path, old, new), OPTION_PIN_FILES)
     assert r.returncode == 1 and "failed" in r.stdout, f"mutant survived ({name}):\n" + r.stdout[-1500:] + r.stderr[-1500:]
