@@ -44,6 +44,56 @@ def read_traffic(workload):
     return None
 
 
+def measure_traffic(child_args, timeout_s=180):
+    """HBM bytes per launch of the channel kernel, measured now: two child runs of this script (one
+    batch in flight, 2 timed steps) under `rocprofv3 --pmc`, FETCH_SIZE then WRITE_SIZE (KiB per
+    dispatch), each scaled by what the same counter reads in the same run for the probe's plain copy
+    kernel, which reads and writes exactly 1 GiB per launch.  Returns (bytes, detail) or (None, why)."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+    exe = shutil.which("rocprofv3")
+    if not exe:
+        return None, "rocprofv3 not found"
+    if any(k.startswith("ROCPROF") for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return None, "this process is itself being profiled"
+    work = tempfile.mkdtemp(prefix="wfst_traffic_")
+    env = dict(os.environ, TMPDIR=tempfile.gettempdir(), PYTHONPATH=os.pathsep.join([ROOT, os.environ.get("PYTHONPATH", "")]))
+    detail = {}
+    try:
+        for ctr in ("FETCH_SIZE", "WRITE_SIZE"):
+            out = os.path.join(work, ctr.lower())
+            cmd = [exe, "--pmc", ctr, "-d", out, "-o", ctr.lower(), "--output-format", "csv", "--",
+                   sys.executable, os.path.join(ROOT, "bench.py"), "--pipeline", "1", "--steps", "2", "--warmup", "1",
+                   "--no-cpu-baseline", "--no-traffic"] + child_args
+            try:
+                r = subprocess.run(cmd, cwd=work, env=env, capture_output=True, text=True, timeout=timeout_s)
+            except subprocess.TimeoutExpired:
+                return None, f"the {ctr} run did not finish in {timeout_s} s"
+            if r.returncode != 0:
+                return None, f"the {ctr} run ended with status {r.returncode}: {r.stderr[-300:]}"
+            kern, copy = [], []
+            for f in glob.glob(os.path.join(out, "**", "*counter_collection.csv"), recursive=True):
+                for row in csv.DictReader(open(f)):
+                    if row.get("Counter_Name") != ctr:
+                        continue
+                    if "wfst_channel_kernel" in row["Kernel_Name"]:
+                        kern.append(float(row["Counter_Value"]))
+                    elif "probe_copy" in row["Kernel_Name"]:
+                        copy.append(float(row["Counter_Value"]))
+            if not kern or not copy or min(copy) <= 0:
+                return None, f"no {ctr} values for the kernel or the calibration copy in the profiler's output"
+            kern = kern[-2:]                                    # the timed launches (the first one is the warm-up)
+            scale = (1 << 20) / (sum(copy) / len(copy))         # the copy moves 2^20 KiB each way
+            detail[ctr] = {"kib_per_launch": sum(kern) / len(kern), "copy_kib": sum(copy) / len(copy), "scale": scale}
+        total = sum(d["kib_per_launch"] * d["scale"] * 1024.0 for d in detail.values())
+        return int(total), detail
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
+
+
 def cpu_model():
     try:
         for ln in open("/proc/cpuinfo"):
@@ -291,6 +341,9 @@ def main():
     ap.add_argument("--workload", default="c3_large")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="do not measure the kernel's HBM traffic with two profiler runs of this script (the figure "
+                         "of the committed profile summary is reported instead)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (profiling aid)")
     ap.add_argument("--calibrate", action="store_true",
                     help="only measure this GPU's ceilings (device copy, random 128-byte lines, 64-bit atomics) and "
@@ -405,7 +458,26 @@ def main():
     kms = float(np.mean(kernel_ms))
     abytes = algorithmic_bytes(counters, V)
     achieved = abytes / (kms * 1e-3) / 1e9
-    traffic = read_traffic(args.workload)
+    traffic, traffic_source, traffic_detail = None, None, None
+    if not args.no_traffic:
+        child = ["--workload", args.workload, "--loglike-dtype", args.loglike_dtype]
+        child += ["--batch", str(args.batch)] if args.batch else []
+        child += ["--narrow-arcs"] if args.narrow_arcs else []
+        t0 = time.perf_counter()
+        traffic, traffic_detail = measure_traffic(child)
+        if traffic is not None:
+            traffic_source = ("measured by this run: two child runs of this command with one batch in flight under rocprofv3 "
+                              "--pmc FETCH_SIZE / WRITE_SIZE, scaled by the same counters of the 1 GiB probe_copy launches")
+            print(f"[bench] HBM traffic per launch measured in {time.perf_counter() - t0:.0f} s: {traffic / 1e9:.1f} GB",
+                  file=sys.stderr, flush=True)
+        else:
+            print(f"[bench] HBM traffic not measured ({traffic_detail}); using the committed profile summary",
+                  file=sys.stderr, flush=True)
+    if traffic is None:
+        why = "" if args.no_traffic else f"; a measurement was tried and failed: {traffic_detail}"
+        traffic, traffic_detail = read_traffic(args.workload), None
+        traffic_source = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, summary under profiles/ "
+                          "(not measured in this run" + why + ")")
     cal = calibrate()
     achieved_at_value = abytes / (ms_per_step * 1e-3) / 1e9
     line = {
@@ -428,8 +500,7 @@ def main():
                         "results to pinned host memory, between two device synchronisations; log-likelihoods resident",
         "roofline": {"bound": "hbm", "kernel": KERNEL, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, summary under profiles/ "
-                                       "(not measured in this run)",
+                     "traffic_source": traffic_source, "traffic_detail": traffic_detail,
                      "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms,
                      "note": "achieved / frac: algorithmic bytes over the kernel's own duration with ONE batch in flight "
                              "(HIP events on the launch stream); *_at_value: over ms_per_step of the timed region, "
