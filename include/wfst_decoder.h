@@ -257,6 +257,10 @@ int32_t wfst_init_channel_boost_fst(wfst_decoder *dec, int32_t ch, float beam, i
                                     const wfst_boost_fst *fst, void *stream);
 int32_t wfst_init_channels(wfst_decoder *dec, const int32_t *channels, int32_t n, float beam,
                            int32_t max_active, const wfst_boost_table *const *boosts, void *stream);
+/* wfst_init_channels with a boosting acceptor of several states per stream: fsts is a HOST array of
+ * n acceptor pointers (an entry may be NULL = that stream is not boosted), or NULL. */
+int32_t wfst_init_channels_boost_fst(wfst_decoder *dec, const int32_t *channels, int32_t n, float beam,
+                                     int32_t max_active, const wfst_boost_fst *const *fsts, void *stream);
 int32_t wfst_advance_chunk(wfst_decoder *dec, const int32_t *channels, int32_t n,
                            const float *loglikes, const int32_t *nframes, int32_t C, int32_t V,
                            void *stream);

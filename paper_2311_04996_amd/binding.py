@@ -20,7 +20,7 @@ FLAG_REACHED_FINAL, FLAG_TRUNCATED, FLAG_DEAD, FLAG_LATTICE_OVERFLOW, FLAG_CAPAC
 LOGLIKE_DTYPES = {"float32": 0, "float16": 1, "bfloat16": 2}
 
 EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "wfst_decode_batch_boosted",
-           "wfst_decode_batch_boost_fst", "wfst_decode_batch_slot", "wfst_slot_kernel_ms", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels",
+           "wfst_decode_batch_boost_fst", "wfst_decode_batch_slot", "wfst_slot_kernel_ms", "wfst_init_channel", "wfst_init_channel_boost_fst", "wfst_init_channels", "wfst_init_channels_boost_fst",
            "wfst_advance_chunk", "wfst_advance_chunk_partial", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
            "wfst_get_lattice_noalloc", "wfst_get_lattice_batch",
            "wfst_debug_frame_digests",
@@ -112,6 +112,7 @@ def load_library():
     lib.wfst_decode_batch_boost_fst.argtypes = [p, p, p, i32, i32, i32, f32, i32, p, p, p, p, p, p]
     lib.wfst_debug_get_token_pairs.argtypes = [p, i32, p, p, p, i32, p]
     lib.wfst_init_channels.argtypes = [p, p, i32, f32, i32, p, p]
+    lib.wfst_init_channels_boost_fst.argtypes = [p, p, i32, f32, i32, p, p]
     lib.wfst_advance_chunk.argtypes = [p, p, i32, p, p, i32, i32, p]
     lib.wfst_advance_chunk_partial.argtypes = [p, p, i32, p, p, i32, i32, i32, p, p, p, p, p]
     lib.wfst_get_partial.argtypes = [p, i32, i32, p, i32, p, p, p, p]
@@ -272,12 +273,20 @@ class Decoder:
             t, keep = _boost_struct(boost)
             self._check(self.lib.wfst_init_channel(self.h, ch, beam, max_active, C.byref(t), _stream_ptr(stream)))
 
-    def init_channels(self, channels, beam, max_active, stream=None, boosts=None):
+    def init_channels(self, channels, beam, max_active, stream=None, boosts=None, boost_fsts=None):
         """wfst_init_channels: reset several channels in one launch; boosts: None or one entry
-        per channel, each None or a (word_ids, scores) table."""
+        per channel, each None or a (word_ids, scores) table; boost_fsts (instead): None or one
+        entry per channel, each None or a boosting acceptor (wfst_init_channels_boost_fst)."""
         channels = np.ascontiguousarray(channels, dtype=np.int32)
         n = len(channels)
         arr = None
+        if boost_fsts is not None:
+            assert boosts is None and len(boost_fsts) == n
+            keep = [None if f is None else _fst_struct(f) for f in boost_fsts]
+            arr = (C.c_void_p * n)(*[None if k is None else C.addressof(k[0]) for k in keep])
+            self._check(self.lib.wfst_init_channels_boost_fst(self.h, channels.ctypes.data, n, beam, max_active, arr,
+                                                              _stream_ptr(stream)))
+            return
         if boosts is not None:
             assert len(boosts) == n
             keep = [None if t is None else _boost_struct(t) for t in boosts]

@@ -3021,8 +3021,26 @@ int32_t wfst_init_channel(wfst_decoder *d, int32_t ch, float beam, int32_t max_a
   return launch(d, {ch}, {0}, {0}, a, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+int init_channels_impl(wfst_decoder *d, const int32_t *channels, int32_t n, float beam, int32_t max_active,
+                       const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream);
+}
+
 int32_t wfst_init_channels(wfst_decoder *d, const int32_t *channels, int32_t n, float beam, int32_t max_active,
                            const wfst_boost_table *const *boosts, void *stream) {
+  return init_channels_impl(d, channels, n, beam, max_active, boosts, nullptr, stream);
+}
+
+int32_t wfst_init_channels_boost_fst(wfst_decoder *d, const int32_t *channels, int32_t n, float beam,
+                                     int32_t max_active, const wfst_boost_fst *const *fsts, void *stream) {
+  return init_channels_impl(d, channels, n, beam, max_active, nullptr, fsts, stream);
+}
+
+}  // extern "C"
+
+namespace {
+int init_channels_impl(wfst_decoder *d, const int32_t *channels, int32_t n, float beam, int32_t max_active,
+                       const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts, void *stream) {
   if (!d) return WFST_ERR_INVALID_ARG;
   if (n < 0 || (n > 0 && !channels)) return fail(d, WFST_ERR_INVALID_ARG, "null or negative argument");
   if (n == 0) return WFST_OK;
@@ -3037,7 +3055,8 @@ int32_t wfst_init_channels(wfst_decoder *d, const int32_t *channels, int32_t n, 
     chan[i] = channels[i];
   }
   for (int i = 0; i < n; ++i) {
-    const int rcb = set_boost(d, chan[i], boosts ? boosts[i] : nullptr, static_cast<hipStream_t>(stream));
+    const int rcb = fsts ? set_boost(d, chan[i], fsts[i], static_cast<hipStream_t>(stream))
+                         : set_boost(d, chan[i], boosts ? boosts[i] : nullptr, static_cast<hipStream_t>(stream));
     if (rcb) return rcb;
     const int rcr = ready_for_init(d, chan[i], static_cast<hipStream_t>(stream));
     if (rcr) return rcr;
@@ -3047,6 +3066,9 @@ int32_t wfst_init_channels(wfst_decoder *d, const int32_t *channels, int32_t n, 
   a.beam = beam; a.scale = 256.0f / beam; a.max_active = max_active;
   return launch(d, chan, zero, zero, a, static_cast<hipStream_t>(stream));   // one workgroup per channel, one launch
 }
+}  // namespace
+
+extern "C" {
 
 int32_t wfst_advance_chunk(wfst_decoder *d, const int32_t *channels, int32_t n, const float *loglikes,
                            const int32_t *nframes, int32_t C, int32_t V, void *stream) {

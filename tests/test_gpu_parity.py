@@ -760,6 +760,33 @@ def test_boost_fst_streaming_equals_offline_and_errors(torch_cuda, c2):
     dec.close()
 
 
+def test_streams_set_up_together_each_with_its_own_acceptor(torch_cuda, c2):
+    """wfst_init_channels_boost_fst: three streams set up in one launch, two with acceptors of their
+    own and one without, advanced together with partial results in the same launch."""
+    from oracle import Oracle
+    from paper_2311_04996_amd import Decoder
+    from workloads import boost_fsts
+    torch = torch_cuda
+    fsts = boost_fsts(13, 2, int(c2.graph.meta["num_words"]), per_utt=100, max_len=4, score=-3.0, hot_words=40) + [None]
+    n, pick = 64, [2, 5, 8]
+    ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[pick, :n])).cuda()
+    dec = Decoder(c2.graph, max_channels=4, max_frames=n, max_words=64, max_active_hint=c2.max_active, record_digests=True)
+    chans = np.array([2, 0, 3], np.int32)
+    dec.init_channels(chans, c2.beam, c2.max_active, boost_fsts=fsts)
+    for t0 in range(0, n, 16):
+        out = dec.advance_chunk_partial(chans, ll[:, t0:t0 + 16].contiguous(), [16, 16, 16], finalize=t0 + 16 == n)
+    torch.cuda.synchronize()
+    words, nwords, cost, flags = (t.cpu().numpy() for t in out)
+    o = Oracle(c2.graph)
+    for i in range(3):
+        r = o.decode(c2.loglikes[pick[i]], length=n, beam=c2.beam, max_active=c2.max_active, max_words=64,
+                     boost_fst=fsts[i], want_digests=True)
+        cnt, dig = dec.debug_frame_digests(int(chans[i]))
+        assert (cnt == r.digest_count).all() and (dig == r.digest_sum).all(), i
+        assert words[i, :nwords[i]].tolist() == r.words.tolist() and cost[i] == np.float32(r.cost) and flags[i] == r.flags, i
+    dec.close()
+
+
 # ------------------------------------------------------------------------------- cost offsets
 def test_cost_offsets_match_the_oracle_with_the_same_option(torch_cuda, c1, c2):
     """Token costs rebased after every prune step: token sets (rebased costs), words, cost and
