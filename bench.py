@@ -340,6 +340,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c3_large")
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--max-active", type=int, default=None, help="override the workload's max-active (a sensitivity run, "
+                    "not the configuration the metric is quoted on)")
+    ap.add_argument("--beam", type=float, default=None, help="override the workload's beam (likewise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-traffic", action="store_true",
                     help="do not measure the kernel's HBM traffic with two profiler runs of this script (the figure "
@@ -379,6 +382,10 @@ def main():
 
     t0 = time.perf_counter()
     w = make_config(args.workload, batch=args.batch)
+    if args.max_active is not None:
+        w.max_active = int(args.max_active)
+    if args.beam is not None:
+        w.beam = float(args.beam)
     B, T, V = w.loglikes.shape
     print(f"[bench] {args.workload}: S={w.graph.num_states} A={w.graph.num_arcs} B={B} T={T} V={V} "
           f"audio={w.audio_seconds:.1f}s generated in {time.perf_counter() - t0:.1f}s", file=sys.stderr, flush=True)
@@ -463,6 +470,8 @@ def main():
         child = ["--workload", args.workload, "--loglike-dtype", args.loglike_dtype]
         child += ["--batch", str(args.batch)] if args.batch else []
         child += ["--narrow-arcs"] if args.narrow_arcs else []
+        child += ["--max-active", str(args.max_active)] if args.max_active is not None else []
+        child += ["--beam", str(args.beam)] if args.beam is not None else []
         t0 = time.perf_counter()
         traffic, traffic_detail = measure_traffic(child)
         if traffic is not None:
