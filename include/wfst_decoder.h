@@ -125,6 +125,11 @@ typedef struct {
                                      rounded to binary16 (BAD_GRAPH if it does not fit) for ALL uses, so results are
                                      exactly those of this decoder on a graph with the rounded weights; epsilon arcs
                                      keep fp32 weights */
+  int32_t selection_sample;       /* 0: default (8).  n > 0: before recombination the decoder looks at one run of 64
+                                     candidates out of n (rounded down to a power of two) to estimate which of them can survive
+                                     max-active and how many
+                                     table passes they need.  A tuning knob: results never depend on it (an estimate
+                                     that turns out wrong costs time, the step is then done again) */
 } wfst_opts;
 
 #define WFST_LOGLIKE_F32 0

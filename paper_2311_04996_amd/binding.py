@@ -73,7 +73,7 @@ class wfst_opts(C.Structure):
                 ("candidate_capacity", C.c_int32), ("record_digests", C.c_int32),
                 ("loglike_dtype", C.c_int32), ("keep_token_records", C.c_int32), ("cost_offset", C.c_int32),
                 ("batch_slots", C.c_int32), ("recycle_lattice", C.c_int32), ("lattice_by_length", C.c_int32),
-                ("narrow_arcs", C.c_int32)]
+                ("narrow_arcs", C.c_int32), ("selection_sample", C.c_int32)]
 
 
 class wfst_lattice_link(C.Structure):
@@ -160,7 +160,7 @@ class Decoder:
     def __init__(self, graph, max_channels, max_frames, max_words=256, max_active_hint=10000,
                  lattice_bytes_per_channel=0, outputs_on_host=False, candidate_capacity=0,
                  record_digests=False, loglike_dtype="float32", keep_token_records=False, cost_offset=False,
-                 batch_slots=0, recycle_lattice=False, lattice_by_length=False, narrow_arcs=False):
+                 batch_slots=0, recycle_lattice=False, lattice_by_length=False, narrow_arcs=False, selection_sample=0):
         self.lib = load_library()
         arrs = [np.ascontiguousarray(graph.row_offsets, dtype=np.int64),
                 np.ascontiguousarray(graph.next_state, dtype=np.int32),
@@ -174,7 +174,7 @@ class Decoder:
                               int(outputs_on_host), max_active_hint, candidate_capacity,
                               int(record_digests), LOGLIKE_DTYPES[loglike_dtype], int(keep_token_records),
                               int(cost_offset), int(batch_slots), int(recycle_lattice), int(lattice_by_length),
-                              int(narrow_arcs))
+                              int(narrow_arcs), int(selection_sample))
         self.loglike_dtype = loglike_dtype
         self.V = graph.num_classes
         self.max_words = max_words

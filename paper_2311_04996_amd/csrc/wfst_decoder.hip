@@ -131,6 +131,7 @@ constexpr int kBoostStateBits = 12;           // states of a boosting acceptor: 
 constexpr int kQueueMax = 65536;              // tokens per closed set
 constexpr unsigned long long kValEmpty = ~0ull;
 constexpr int kKeyEmpty = -1;
+constexpr int kKeyNone = -2;                  // no key at all (a probe sequence that gave up)
 constexpr unsigned kOrdNone = 0xFFFFFFFFu;
 constexpr int kModeInit = 1, kModeFinal = 2;
 constexpr unsigned kKeyMask = 0x1fffffffu;     // block number of a state (32-byte units)
@@ -201,6 +202,7 @@ struct DevChannels {
   int *frame_ep;                               // [channels][max_frames + 2] the epoch each frame's tokens were stored in
   int2 *tokrec;                                // nullptr, or beside every backpointer the token's {block number, cost}
   int cost_offset;                             // 1: token costs are rebased to the best cost after every prune step
+  int sel_shift;                               // the pre-selection samples one run of 64 candidates out of 2^sel_shift
   // the path of the last traceback, so that the next one can stop where it meets it:
   int *path_tok, *path_nw;                     // [channels][max_frames + 1] per frame: the token the path enters the
                                                // set with (over an emitting arc); words on the path up to and incl. that arc
@@ -271,6 +273,7 @@ struct Smem {
   int n_win, n_next, n_wl_next, status, n_cont;
   int n_in, n_emit, n_back;   // tokens of the emitting step an epsilon arc can enter (they come first), all of them; back counter
   int k_sel, n_sel, n_sel_c, k_keep, redo;
+  int overfull;               // a table pass met more destinations than the table takes: the passes are planned again
   int path_frames, trace_from, trace_words;   // traceback: new marks valid up to; where the walk stopped; words before that
   unsigned long long red64, red64b;
   long long ctr[8];
@@ -835,6 +838,7 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
 #ifndef WFST_STEP_SHIFT
 #define WFST_STEP_SHIFT 19
 #endif
+constexpr int kProbeLimit = 256;
 __device__ __forceinline__ unsigned probe_start(int key) { return (hash_state(key) >> 6) & kTabMask; }
 __device__ __forceinline__ unsigned probe_step(int key) {
 #ifdef WFST_LINEAR
@@ -859,8 +863,12 @@ __device__ __forceinline__ int table_insert(Ctx &x, int dst, float cost, int arc
     old = atomicCAS(&t.keys[s], kKeyEmpty, dst);
     if (old == kKeyEmpty || old == dst) break;
     s = (s + step) & kTabMask;
-    if (probes >= kTabSlots) { atomicOr(&x.sm.status, kStCapacity); return -1; }   // table full
+    if (probes >= kProbeLimit) { old = kKeyNone; break; }
   }
+  // a probe sequence this long means that the pass has far more destinations than it was planned
+  // for (at the loads passes are planned for, 0.75, one in 10^30 gets here): the caller plans again.
+  // (Leaving the loop first and returning here compiles to a faster loop than returning inside it.)
+  if (old == kKeyNone) { atomicOr(&x.sm.overfull, 1); return -1; }
   const unsigned oc = f2ord(cost);
   const unsigned long long mine = ((unsigned long long)oc << 32) | (unsigned)idx;
   // a slot this lane has just claimed still holds the empty value (unless another candidate of
@@ -1031,9 +1039,11 @@ struct PassPlan {
   int n_pass; bool whole, halves; int per_region[kRegions];
   // every_region: also regions without candidates get a pass (the emitting step, where the self-loop
   // candidates of the tokens meet the table of their region's pass)
-  __device__ __forceinline__ void make(const Ctx &x, int n_sel, int n_all, bool every_region = false) {
+  // mult > 1: a plan made from an estimate turned out too small (a pass overfilled the table): every
+  // region gets mult times the passes
+  __device__ __forceinline__ void make(const Ctx &x, int n_sel, int n_all, bool every_region = false, int mult = 1) {
     static_assert(kRegions == 4, "the halves are regions {0, 1} and {2, 3}");
-    whole = n_sel <= kGroupTarget;
+    whole = n_sel <= kGroupTarget && mult == 1;
     halves = false;
     n_pass = whole ? 1 : 0;
     float est_r[kRegions];
@@ -1042,10 +1052,10 @@ struct PassPlan {
       const int n = uni(min(x.sm.n_reg[r], x.c.region_cap));
       // selected candidates of the region, estimated from its share of all candidates
       est_r[r] = (float)n_sel * (float)n / (float)max(1, n_all) * 1.15f + 64.0f;
-      per_region[r] = (whole || (n == 0 && !every_region)) ? 0 : (int)(est_r[r] / (float)kGroupTarget) + 1;
+      per_region[r] = (whole || (n == 0 && !every_region)) ? 0 : min(2048, ((int)(est_r[r] / (float)kGroupTarget) + 1) * mult);
       n_pass += per_region[r];
     }
-    if (!whole && every_region && est_r[0] + est_r[1] <= (float)kGroupTarget && est_r[2] + est_r[3] <= (float)kGroupTarget) {
+    if (!whole && mult == 1 && every_region && est_r[0] + est_r[1] <= (float)kGroupTarget && est_r[2] + est_r[3] <= (float)kGroupTarget) {
       halves = true; n_pass = 2;                  // two regions per pass
     }
   }
@@ -1173,8 +1183,8 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   constexpr int kHalf = 2;
   // one run of 64 records in kEvery (a wave reads one run): candidates arrive roughly in the
   // order of the token queue, which is not free of cost trends, so the sample is interleaved finely
-  constexpr int kEvery = WFST_SEL_EVERY;            // one run of 64 records out of kEvery
-  const int mine = (tid >> 6) * (64 * kEvery) + (tid & 63);
+  const int sh = x.c.sel_shift, kEvery = 1 << sh;   // one run of 64 records out of kEvery (a power of two)
+  const int mine = ((tid >> 6) << (6 + sh)) + (tid & 63);
   for (int r = 0; r < kRegions; ++r) {
     const int n = uni(min(sm.n_reg[r], x.c.region_cap));
     const int4 *cr = x.cand + r * x.c.region_cap;
@@ -1188,7 +1198,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
         if (i0 + u * kEvery * kBlock + mine < n && cut.in_beam(c)) atomicAdd(&sm.hist2[cut.bin(c)], 1u);
       }
       const int span = min(n - i0, kEvery * kBlock * kHalf);
-      n_sampled += span / (64 * kEvery) * 64 + min(span % (64 * kEvery), 64);
+      n_sampled += ((span >> (6 + sh)) << 6) + min(span & ((64 << sh) - 1), 64);
     }
   }
   __syncthreads();
@@ -1230,10 +1240,16 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   const int n_cont = uni(sm.n_cont);
   prof_mark(sm, kPhSelect);
 
-  for (int attempt = 0; attempt < 2; ++attempt) {
+  // Steps 2 and 3 are done again when the selection turns out wrong: too few distinct destinations
+  // among the selected to decide the cutoff -> once more with everything selected; a pass that met
+  // far more destinations than the table takes (the number of passes comes from an estimate) ->
+  // once more with twice the passes per region.
+  int mult = 1;
+  for (int attempt = 0;; ++attempt) {
     // ---- 2. recombine the selected candidates, G table passes
     PassPlan plan;
-    plan.make(x, n_sel_c, n_cand, true);
+    plan.make(x, n_sel_c, n_cand, true, mult);
+    if (tid == 0) sm.overfull = 0;                 // (the first pass begins with a barrier)
     for (int ps = 0; ps < plan.n_pass; ++ps) {
       int r0, r1, g, G;
       plan.get(ps, r0, r1, g, G);
@@ -1261,7 +1277,9 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       inc = wave_scan_add(inc);
       const unsigned n_u = (unsigned)__builtin_amdgcn_readlane((int)inc, 63);
       int kk = 256, redo = 0;
-      if (n_u > ma) {
+      if (sm.overfull) {
+        redo = 2;                                   // the histogram is worth nothing: more passes
+      } else if (n_u > ma) {
         unsigned run = inc - s;
         int first = 256;
         run += h0; if (run > ma && first == 256) first = 4 * tid;
@@ -1291,9 +1309,10 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       }
     }
     __syncthreads();
-    const bool redo = uni(sm.redo) != 0;
-    x.s.sel_ratio = uni(__uint_as_float((unsigned)sm.red64b));
+    const int redo = uni(sm.redo);
+    if (redo != 2) x.s.sel_ratio = uni(__uint_as_float((unsigned)sm.red64b));
     if (!redo) break;
+    if (attempt >= 12) { if (tid == 0) atomicOr(&sm.status, kStCapacity); break; }   // never expected: 2048 passes per region
     if (tid == 0) sm.prof[15]++;                   // counted, not timed: re-recombinations
     __syncthreads();
     if (tid < 256) sm.hist[tid] = 0;
@@ -1302,7 +1321,8 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       atomicAnd(&staybits[i >> 5], ~(1u << (i & 31)));
     }
     if (tid == 0) { sm.n_win = 0; sm.redo = 0; }
-    k_sel = 256; n_sel = n_cand + n_tok; n_sel_c = n_cand;
+    if (redo == 2) mult *= 2;
+    else { k_sel = 256; n_sel = n_cand + n_tok; n_sel_c = n_cand; }
     __syncthreads();
   }
   cut.k_keep = uni(sm.k_keep);
@@ -1629,8 +1649,10 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
     }
     __syncthreads();
     n_wl = uni(min(sm.n_wl_next, x.c.qcap));
-    const bool stop = uni(sm.status) != 0;
+    // (the closure's passes are planned from exact counts: a table that overfills is not expected)
+    const bool stop = (uni(sm.status) | uni(sm.overfull)) != 0;
     __syncthreads();
+    if (tid == 0 && sm.overfull) { atomicOr(&sm.status, kStCapacity); sm.overfull = 0; }
     if (tid == 0) sm.n_wl_next = 0;
     if (tid < kRegions) sm.n_reg[tid] = 0;
     __syncthreads();
@@ -1850,6 +1872,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     sm.n_in = 0; sm.n_emit = 0; sm.n_back = 0;
     for (int r = 0; r < kRegions; ++r) sm.n_reg[r] = 0;
     sm.status = 0; sm.red64 = 0; sm.red64b = 0; sm.k_keep = 256; sm.k_sel = 256; sm.n_sel = 0; sm.redo = 0;
+    sm.overfull = 0;
     for (int i = 0; i < 16; ++i) sm.prof[i] = 0;
     for (int i = 0; i < 8; ++i) sm.ctr[i] = 0;
     sm.prof_t0 = (long long)wall_clock64();
@@ -2460,6 +2483,11 @@ int alloc_channels(wfst_decoder *d) {
   d->chan_ready.assign(N, 0);
   if (o.keep_token_records && (rc = dev_alloc(d, &c.tokrec, N * (size_t)c.lat_cap))) return rc;
   c.cost_offset = o.cost_offset ? 1 : 0;
+  {
+    const int every = o.selection_sample > 0 ? std::min(o.selection_sample, 4096) : WFST_SEL_EVERY;
+    c.sel_shift = 0;
+    while ((2 << c.sel_shift) <= every) ++c.sel_shift;          // rounded down to a power of two
+  }
   c.max_words = o.max_words;
   if ((rc = dev_alloc(d, &c.path_tok, N * (size_t)(c.max_frames + 1)))) return rc;
   if ((rc = dev_alloc(d, &c.path_nw, N * (size_t)(c.max_frames + 1)))) return rc;

@@ -465,6 +465,24 @@ def test_many_duplicate_destinations(torch_cuda):
     dec.close()
 
 
+@pytest.mark.parametrize("sample", [1, 3, 64, 1000])
+def test_results_do_not_depend_on_the_selection_sample(torch_cuda, c2, c2_refs, sample):
+    """The pre-selection before recombination works from a sample of the candidates (one run of 64
+    in 8 by default).  A coarse sample mis-estimates which candidates can survive and how many table
+    passes they need: too few selected -> everything is recombined again; a pass that overfills the
+    table -> the passes are planned again with twice as many.  Either way the result is the
+    oracle's; with the coarse samples the second paths are really taken."""
+    from paper_2311_04996_amd import Decoder
+    check_batch(torch_cuda, c2.graph, c2.loglikes, c2.lengths, c2.beam, c2.max_active, refs=c2_refs,
+                selection_sample=sample)
+    if sample >= 64:
+        dec = Decoder(c2.graph, max_channels=len(c2.lengths), max_frames=c2.loglikes.shape[1],
+                      max_active_hint=c2.max_active, selection_sample=sample)
+        dec.decode_batch(torch_cuda.from_numpy(c2.loglikes).cuda(), c2.lengths, c2.beam, c2.max_active)
+        assert dec.debug_phase_ticks()[15] > 0
+        dec.close()
+
+
 def _stress_inputs(graph, T, seed, batch=2):
     from workloads import ctc_loglikes
     lengths = np.array([T, max(1, T - 3)][:batch], dtype=np.int32)
