@@ -14,7 +14,7 @@ PROBE_LIB_PATH = os.path.join(_HERE, "libwfstprobe.so")
 PROBE_SOURCES = [os.path.join(_HERE, "csrc", "wfst_probe.hip")]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                       # costs are compared bit for bit: no FMA contraction
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I" + os.path.join(ROOT, "include"),
@@ -24,8 +24,10 @@ HIPCC_FLAGS = [
 def build_library(verbose: bool = False) -> str:
     """Always recompiles both libraries.  Returns the path of the decoder's shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    for out, src in ((LIB_PATH, SOURCES), (PROBE_LIB_PATH, PROBE_SOURCES)):
-        cmd = [hipcc] + HIPCC_FLAGS + ["-o", out] + src
+    # The decoder is optimised for size: its frame loop is about 70 KB of code, more than the
+    # instruction cache holds, and the smaller build measured 2 % faster than -O3 (-O2 1 %, -Oz slower).
+    for out, src, opt in ((LIB_PATH, SOURCES, "-Os"), (PROBE_LIB_PATH, PROBE_SOURCES, "-O3")):
+        cmd = [hipcc, opt] + HIPCC_FLAGS + ["-o", out] + src
         if verbose:
             print(" ".join(cmd))
         subprocess.check_call(cmd, stderr=None if verbose else subprocess.DEVNULL)

@@ -724,14 +724,14 @@ __device__ __forceinline__ unsigned dense_run(Ctx &x, WaveLds &wl, int head, int
 
 // On entry sm.next_run == kWaves, sm.done_waves == 0, sm.n_hub == 0 and the hub list's ready
 // and seg_next words are zero (the caller sets them before its barrier).
-template <bool kNarrow>
+template <bool kNarrow, bool kBoost>
 __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   Smem &sm = x.sm;
   ExpandLds &e = sm.u.e;
   HubLds &hb = e.hub;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float beam = x.s.beam;
-  const bool boosted = x.s.boost_n > 0;
+  const bool boosted = kBoost && x.s.boost_n > 0;
   // Every wave expands runs of kWaveTok tokens at its own pace: it takes the next run from a
   // counter, so no wave waits for another until all tokens are done, and one wave's loads
   // overlap another's arithmetic.  Most tokens sit in "simple" states, whose only arc is the
@@ -1423,12 +1423,13 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
 // what is left in the table are destinations without a token, which become new tokens.  Either
 // way the token is expanded in the next round.
 // On entry WL0 = x.wl0 + sel*qcap holds n_wl entries.
+template <bool kBoost>
 __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base, int sel, const Cutoff &cut) {
   Smem &sm = x.sm;
   EpsLds &ek = sm.ek;
   TableLds &t = sm.u.t;
   const int tid = threadIdx.x;
-  const bool boosted = x.s.boost_n > 0;
+  const bool boosted = kBoost && x.s.boost_n > 0;
   x.srcq = NQ;                                 // the closure's candidates come out of the set under construction
   int n_wl = uni(min(sm.n_wl_next, x.c.qcap));
   __syncthreads();
@@ -1839,8 +1840,10 @@ __device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int i
 
 // ------------------------------------------------------------------ the channel kernel
 // kNarrow: the graph has the 8-byte emitting-arc records and the arc loops read them (a variant of
-// the kernel of its own, so that the usual one carries none of it).
-template <bool kNarrow>
+// the kernel of its own, so that the usual one carries none of it).  kBoost: some channel of the
+// launch has a boosting table or acceptor; the variant without is smaller, and the frame loop is
+// more code than the instruction cache holds, so every kilobyte less of it shows in the time.
+template <bool kNarrow, bool kBoost>
 __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
@@ -1860,7 +1863,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
   x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio); x.s.offset = uni(x.s.offset);
   x.s.boost_n = uni(x.s.boost_n); x.s.boost_states = uni(x.s.boost_states); x.s.lat_epoch = uni(x.s.lat_epoch);
-  if (x.s.boost_n > 0)
+  if (kBoost && x.s.boost_n > 0)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
       sm.bk[i] = c.boost_keys[(size_t)ch * kBoostSlots + i];
       sm.bv[i] = c.boost_vals[(size_t)ch * kBoostSlots + i];
@@ -1895,7 +1898,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     }
     __syncthreads();
     Cutoff cut{0.0f, x.s.beam, x.s.scale, 256};
-    eps_closure(x, NQ, 0u, 0, cut);
+    eps_closure<kBoost>(x, NQ, 0u, 0, cut);
     stop = finish_set(x, NQ, 0u);
   }
 
@@ -1931,11 +1934,11 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     const unsigned lat_base = x.s.lat_used;
     if (tid == 0) { sm.ctr[kCtTok] += x.s.n_tok; sm.ctr[kCtFrames]++; }
     prof_mark(sm, kPhOther);
-    emit_expand<kNarrow>(x, Q, x.s.n_tok);
+    emit_expand<kNarrow, kBoost>(x, Q, x.s.n_tok);
     prof_mark(sm, kPhExpand);
     Cutoff cut;
     recombine_and_prune(x, NQ, lat_base, x.wl0, cut);
-    eps_closure(x, NQ, lat_base, 0, cut);
+    eps_closure<kBoost>(x, NQ, lat_base, 0, cut);
     x.s.frame++;
     stop = finish_set(x, NQ, lat_base);
     prof_mark(sm, kPhFinish);
@@ -2546,8 +2549,15 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
   HIP_TRY(d, hipMemcpyAsync(slot, pack.data(), pack.size() * sizeof(int), hipMemcpyHostToDevice, st));
   a.chan = slot; a.nfr = slot + n; a.io = slot + 2 * n;
   HIP_TRY(d, hipEventRecord(d->ev0[slot_id], st));
-  if (d->g.earc8) hipLaunchKernelGGL(wfst_channel_kernel<true>, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
-  else hipLaunchKernelGGL(wfst_channel_kernel<false>, dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  bool boost = false;                          // does any channel of the launch have a boosting table or acceptor?
+  for (int ch : chan) boost = boost || d->boost_on_dev[ch] > 0;
+  if (d->g.earc8) {
+    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<true, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    else hipLaunchKernelGGL((wfst_channel_kernel<true, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  } else {
+    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<false, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    else hipLaunchKernelGGL((wfst_channel_kernel<false, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  }
   HIP_TRY(d, hipGetLastError());
   HIP_TRY(d, hipEventRecord(d->ev1[slot_id], st));
   d->timed[slot_id] = 1;
