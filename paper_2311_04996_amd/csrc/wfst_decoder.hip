@@ -1711,7 +1711,7 @@ __device__ __forceinline__ bool finish_set(Ctx &x, int2 *NQ, unsigned lat_base) 
 // (block numbers grow with state ids, so they order the same way);
 // then the backpointers are followed to the start token and the non-zero output labels of
 // the arcs are written in path order.
-__device__ __noinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
+__device__ __forceinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, int io) {
   Smem &sm = x.sm;
   const int tid = threadIdx.x;
   const int n = x.s.n_tok;
@@ -1950,9 +1950,10 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   }
   prof_mark(sm, kPhOther);
   if (a.mode & kModeFinal) {
-    // The traceback is a separate function that takes its context by reference.  It gets
-    // copies, so that the pointers of the frame loop above never live in memory: only then
-    // does the compiler know they are global and keep them in registers.
+    // The traceback works on copies of the context, so that the pointers of the frame loop above
+    // never live in memory on its account (only then does the compiler know they are global and
+    // keep them in registers).  Inlined: as a called function it cost the frame loop 1 % (the call
+    // constrains the registers around it); inlined without the copies was no better.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
     Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s, nullptr, x.lat_cap};
     if (tid == 0) sm.path_frames = x.s.path_frames;
