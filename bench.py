@@ -433,19 +433,24 @@ def main():
                                        boosts=w.boosts, boost_fsts=w.boost_fsts, slot=k)
     torch.cuda.synchronize()
     dec.get_counters(reset=True)
-    dec.debug_phase_ticks(reset=True)
     # one batch in flight: the kernel's own duration (for the roofline) and the unpipelined rate
     wall_one, kernel_ms = run_steps(1, args.steps, True)
     counters = dec.get_counters() // max(1, args.steps)
-    ticks = dec.debug_phase_ticks()
-    ticks[15] = 0                                   # slot 15 is a count, not a time
     # the timed region proper: `pipeline` batches in flight
     wall = run_steps(n_slots, args.steps, False)[0] if n_slots > 1 else wall_one
+    # where the workgroups spend their time: one more launch, untimed, with the phase clocks on
+    # (they are off in the timed regions: reading the clock at every phase boundary costs about 1 %)
+    dec.debug_phase_ticks(reset=True)
+    dec.debug_set_phase_timing(True)
+    run_steps(1, 1, False)
+    dec.debug_set_phase_timing(False)
+    ticks = dec.debug_phase_ticks()
+    ticks[15] = 0                                   # slot 15 is a count, not a time
     names = ["expand_tail", "select", "tokens", "eps_expand", "eps_round_end", "publish", "trace", "other",
              "tab_clear", "tab_fill", "tab_winners", "eps_table", "eps_new_tokens", "expand_arcs", "eps_meet", "-"]
     print("[bench] phase share of workgroup time (one batch in flight): " +
           ", ".join(f"{n} {100.0 * t / max(1, ticks.sum()):.1f}%" for n, t in zip(names, ticks) if t) +
-          f"; mean busy time per workgroup {ticks.sum() / 1e5 / B / args.steps:.1f} ms",
+          f"; mean busy time per workgroup {ticks.sum() / 1e5 / B:.1f} ms",
           file=sys.stderr, flush=True)
     for o in outs:
         if o is not None:

@@ -390,9 +390,13 @@ int32_t wfst_get_counters(wfst_decoder *dec, int64_t counters[8], int32_t reset)
  *   [8..12] split of [1] and [4]: table clear, fill, winners; epsilon table clear+fill, new
  *   tokens out of the table (these are counted instead of, not on top of, [1] and [4]);
  *   [13] the arc loops of [0]; [14] epsilon closure: the set's tokens looking their states up
- *   in the table; [15] is not a time: the number of frames whose recombination had to be
- *   redone with every candidate selected.
+ *   in the table; [15] is not a time: the number of times a frame's recombination had to be
+ *   done again (with every candidate selected, or with more table passes).
+ * The times are only taken by launches made while phase timing is on
+ * (wfst_debug_set_phase_timing(dec, 1); off by default: the clock reads at every phase boundary
+ * cost a launch about 1 %; not available with narrow arc records); [15] is always counted.
  */
+int32_t wfst_debug_set_phase_timing(wfst_decoder *dec, int32_t on);
 int32_t wfst_debug_phase_ticks(wfst_decoder *dec, int64_t ticks[16], int32_t reset);
 
 /* Device memory the decoder holds, in bytes (graph + channel state). */

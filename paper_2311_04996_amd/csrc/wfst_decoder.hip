@@ -394,6 +394,7 @@ struct Ctx {                  // block-uniform view of one channel
   ChanState s;
   const int2 *srcq;           // the queue the candidates' source tokens are in (ties between two takes of one arc)
   unsigned lat_cap;           // entries of the channel's lattice arena
+  int prof;                   // phase timing is on (a debug hook: reading the clock stalls wave 0 at every mark)
 };
 // workload counters of this launch, kept in LDS (thread 0 adds the block-uniform ones)
 enum { kCtTok = 0, kCtEarc, kCtXarc, kCtKept, kCtStored, kCtMaxAct, kCtBin0, kCtFrames };
@@ -426,11 +427,11 @@ __device__ __forceinline__ float boost_step(const Smem &sm, int b, int word, int
 enum { kPhExpand = 0, kPhSelect, kPhCutoff, kPhEpsExpand, kPhEpsRecombine, kPhFinish, kPhTrace, kPhOther,
        kPhTabClear, kPhTabFill, kPhTabScan, kPhEpsTabFill, kPhEpsTabScan, kPhExpSetup, kPhEpsMeet };
 constexpr int kPhStayMeet = kPhTabFill;          // counted with the table fill
-__device__ __forceinline__ void prof_mark(Smem &sm, int phase) {
-  if (threadIdx.x == 0) {
+__device__ __forceinline__ void prof_mark(const Ctx &x, int phase) {
+  if (x.prof && threadIdx.x == 0) {
     const long long now = (long long)wall_clock64();
-    sm.prof[phase] += now - sm.prof_t0;
-    sm.prof_t0 = now;
+    x.sm.prof[phase] += now - x.sm.prof_t0;
+    x.sm.prof_t0 = now;
   }
 }
 
@@ -828,7 +829,7 @@ __device__ __forceinline__ void emit_expand(Ctx &x, const int2 *Q, int n_tok) {
   }
   if (lane == 0 && n_arcs) atomicAdd((unsigned long long *)&sm.ctr[kCtEarc], n_arcs);
   __syncthreads();
-  prof_mark(sm, kPhExpSetup);
+  prof_mark(x, kPhExpSetup);
 }
 
 // ------------------------------------------------------------------ recombination in LDS
@@ -1238,7 +1239,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
   __syncthreads();
   int k_sel = uni(sm.k_sel), n_sel = uni(sm.n_sel), n_sel_c = uni(sm.n_sel_c);
   const int n_cont = uni(sm.n_cont);
-  prof_mark(sm, kPhSelect);
+  prof_mark(x, kPhSelect);
 
   // Steps 2 and 3 are done again when the selection turns out wrong: too few distinct destinations
   // among the selected to decide the cutoff -> once more with everything selected; a pass that met
@@ -1255,16 +1256,16 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
       plan.get(ps, r0, r1, g, G);
       table_clear(sm);
       __syncthreads();
-      prof_mark(sm, kPhTabClear);
+      prof_mark(x, kPhTabClear);
       table_fill<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
-      prof_mark(sm, kPhTabFill);
+      prof_mark(x, kPhTabFill);
       stay_meet(x, CL, n_cont, staybits, r0, r1, g, G, cut, k_sel);
       __syncthreads();
-      prof_mark(sm, kPhStayMeet);
+      prof_mark(x, kPhStayMeet);
       table_winners<true>(x, r0, r1, g, G, cut, k_sel);
       __syncthreads();
-      prof_mark(sm, kPhTabScan);
+      prof_mark(x, kPhTabScan);
     }
     // ---- 3. cutoff from the histogram of recombined tokens
     if (tid < 64) {
@@ -1326,7 +1327,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     __syncthreads();
   }
   cut.k_keep = uni(sm.k_keep);
-  prof_mark(sm, kPhOther);
+  prof_mark(x, kPhOther);
 
   // ---- 4. survivors become tokens
   const int n_win = uni(min(sm.n_win, x.c.win_cap));
@@ -1411,7 +1412,7 @@ __device__ __forceinline__ void recombine_and_prune(Ctx &x, int2 *NQ, unsigned l
     cut.best = 0.0f;
   }
   __syncthreads();
-  prof_mark(sm, kPhCutoff);
+  prof_mark(x, kPhCutoff);
 }
 
 // ------------------------------------------------------------------ epsilon closure
@@ -1506,7 +1507,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
       }
       __syncthreads();                             // also keeps ek for this chunk's readers before the next chunk rewrites it
     }
-    prof_mark(sm, kPhEpsExpand);
+    prof_mark(x, kPhEpsExpand);
     const int n_cand = total_candidates(x);
     PassPlan plan;
     plan.make(x, n_cand, n_cand);
@@ -1520,7 +1521,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         table_fill<false>(x, r0, r1, g, G, cut, 256);
         __syncthreads();
       }
-      prof_mark(sm, kPhEpsTabFill);
+      prof_mark(x, kPhEpsTabFill);
       // the tokens of the set meet the table: each looks its own state up; if the pass has a
       // best candidate for it, the better of the two stays the state's token (cost, then arc id)
       // and the entry is taken out, so that only destinations without a token remain.  The scan
@@ -1612,7 +1613,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         }
       }
       __syncthreads();
-      prof_mark(sm, kPhEpsMeet);
+      prof_mark(x, kPhEpsMeet);
       // the winners left in the table become new tokens
       int pos0 = 0;
       for (int r = r0; r < r1; ++r) {
@@ -1646,7 +1647,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
         pos0 += (n + kBlock - 1) / kBlock * kBlock;
       }
       __syncthreads();
-      prof_mark(sm, kPhEpsTabScan);
+      prof_mark(x, kPhEpsTabScan);
     }
     __syncthreads();
     n_wl = uni(min(sm.n_wl_next, x.c.qcap));
@@ -1657,7 +1658,7 @@ __device__ __forceinline__ void eps_closure(Ctx &x, int2 *NQ, unsigned lat_base,
     if (tid == 0) sm.n_wl_next = 0;
     if (tid < kRegions) sm.n_reg[tid] = 0;
     __syncthreads();
-    prof_mark(sm, kPhEpsRecombine);
+    prof_mark(x, kPhEpsRecombine);
     if (stop) break;
     sel ^= 1;
   }
@@ -1843,7 +1844,9 @@ __device__ __forceinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, in
 // the kernel of its own, so that the usual one carries none of it).  kBoost: some channel of the
 // launch has a boosting table or acceptor; the variant without is smaller, and the frame loop is
 // more code than the instruction cache holds, so every kilobyte less of it shows in the time.
-template <bool kNarrow, bool kBoost>
+// kProf: the phases are timed (a debug hook; an instance of its own because even a skipped
+// clock read at every phase boundary costs the frame loop about 1 %).
+template <bool kNarrow, bool kBoost, bool kProf>
 __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
@@ -1855,6 +1858,7 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
   x.lat = c.lattice + c.lat_start[ch];
   x.lat_cap = uni(c.lat_capn[ch]);
+  x.prof = kProf ? 1 : 0;
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
   x.dig_cnt = c.dig_cnt ? c.dig_cnt + (size_t)ch * (c.max_frames + 1) : nullptr;
@@ -1933,34 +1937,34 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
     int2 *NQ = x.q0 + (x.s.cur ^ 1) * c.qcap;
     const unsigned lat_base = x.s.lat_used;
     if (tid == 0) { sm.ctr[kCtTok] += x.s.n_tok; sm.ctr[kCtFrames]++; }
-    prof_mark(sm, kPhOther);
+    prof_mark(x, kPhOther);
     emit_expand<kNarrow, kBoost>(x, Q, x.s.n_tok);
-    prof_mark(sm, kPhExpand);
+    prof_mark(x, kPhExpand);
     Cutoff cut;
     recombine_and_prune(x, NQ, lat_base, x.wl0, cut);
     eps_closure<kBoost>(x, NQ, lat_base, 0, cut);
     x.s.frame++;
     stop = finish_set(x, NQ, lat_base);
-    prof_mark(sm, kPhFinish);
+    prof_mark(x, kPhFinish);
   }
   __syncthreads();
   if (uni(sm.status)) {       // overflow: the channel stops with an empty token set
     x.s.status |= uni(sm.status);
     x.s.n_tok = 0;
   }
-  prof_mark(sm, kPhOther);
+  prof_mark(x, kPhOther);
   if (a.mode & kModeFinal) {
     // The traceback works on copies of the context, so that the pointers of the frame loop above
     // never live in memory on its account (only then does the compiler know they are global and
     // keep them in registers).  Inlined: as a called function it cost the frame loop 1 % (the call
     // constrains the registers around it); inlined without the copies was no better.
     const DevGraph g2 = g; const DevChannels c2 = c; const LaunchArgs a2 = a;
-    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s, nullptr, x.lat_cap};
+    Ctx x2{g2, c2, sm, x.cand, x.win, x.q0, x.wl0, x.lat, x.frame_off, x.dig_sum, x.dig_cnt, x.s, nullptr, x.lat_cap, x.prof};
     if (tid == 0) sm.path_frames = x.s.path_frames;
     select_and_trace(x2, a2, io);
     if (tid == 0) x.s.path_frames = sm.path_frames;      // thread 0's copy is the one that is stored
   }
-  prof_mark(sm, kPhTrace);
+  prof_mark(x, kPhTrace);
   if (tid == 0) {
     c.st[ch] = x.s;
     for (int i = 0; i < 16; ++i) atomicAdd((unsigned long long *)&c.counters[8 + i], (unsigned long long)sm.prof[i]);
@@ -2271,6 +2275,7 @@ struct wfst_decoder {
   int part_pos = 0, last_timed = -1;
   std::vector<char> slot_by_length;    // the slot's pool is currently shared out by length
   std::vector<char> chan_ready;        // the channel has been initialised since its arena was last moved
+  int phase_timing = 0;                // launches time their phases (wfst_debug_set_phase_timing)
   std::string err;
 };
 
@@ -2552,12 +2557,15 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
   HIP_TRY(d, hipEventRecord(d->ev0[slot_id], st));
   bool boost = false;                          // does any channel of the launch have a boosting table or acceptor?
   for (int ch : chan) boost = boost || d->boost_on_dev[ch] > 0;
-  if (d->g.earc8) {
-    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<true, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
-    else hipLaunchKernelGGL((wfst_channel_kernel<true, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  if (d->g.earc8) {                            // (phase timing is not available with narrow arc records)
+    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<true, true, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    else hipLaunchKernelGGL((wfst_channel_kernel<true, false, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  } else if (d->phase_timing) {
+    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<false, true, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    else hipLaunchKernelGGL((wfst_channel_kernel<false, false, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
   } else {
-    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<false, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
-    else hipLaunchKernelGGL((wfst_channel_kernel<false, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<false, true, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    else hipLaunchKernelGGL((wfst_channel_kernel<false, false, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
   }
   HIP_TRY(d, hipGetLastError());
   HIP_TRY(d, hipEventRecord(d->ev1[slot_id], st));
@@ -3326,6 +3334,12 @@ int32_t wfst_get_counters(wfst_decoder *d, int64_t counters[8], int32_t reset) {
   HIP_TRY(d, hipDeviceSynchronize());
   HIP_TRY(d, hipMemcpy(counters, d->c.counters, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
   if (reset) HIP_TRY(d, hipMemset(d->c.counters, 0, 8 * sizeof(int64_t)));
+  return WFST_OK;
+}
+
+int32_t wfst_debug_set_phase_timing(wfst_decoder *d, int32_t on) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  d->phase_timing = on ? 1 : 0;
   return WFST_OK;
 }
 
