@@ -1846,10 +1846,16 @@ __device__ __forceinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, in
 // more code than the instruction cache holds, so every kilobyte less of it shows in the time.
 // kProf: the phases are timed (a debug hook; an instance of its own because even a skipped
 // clock read at every phase boundary costs the frame loop about 1 %).
-template <bool kNarrow, bool kBoost, bool kProf>
-__global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c, LaunchArgs a) {
+// kOpt: the decoder has one of its options on (cost offsets, token records for lattices, a recycled
+// arena, frame digests); the instance without carries none of their code.
+template <bool kNarrow, bool kBoost, bool kProf, bool kOpt>
+__global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c_arg, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
+  DevChannels c = c_arg;
+  if (!kOpt) {                                 // (the host launches this instance only when all of these are off)
+    c.cost_offset = 0; c.recycle = 0; c.tokrec = nullptr; c.frame_best = nullptr; c.dig_sum = nullptr; c.dig_cnt = nullptr;
+  }
   const int ch = uni(a.chan[blockIdx.x]), nfr = uni(a.nfr[blockIdx.x]), io = uni(a.io[blockIdx.x]);
   Ctx x{g, c, sm};
   x.cand = c.cand + (size_t)ch * c.cand_cap;
@@ -2557,16 +2563,19 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
   HIP_TRY(d, hipEventRecord(d->ev0[slot_id], st));
   bool boost = false;                          // does any channel of the launch have a boosting table or acceptor?
   for (int ch : chan) boost = boost || d->boost_on_dev[ch] > 0;
-  if (d->g.earc8) {                            // (phase timing is not available with narrow arc records)
-    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<true, true, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
-    else hipLaunchKernelGGL((wfst_channel_kernel<true, false, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+  const bool opt = d->c.cost_offset || d->c.recycle || d->c.tokrec || d->c.frame_best || d->c.dig_sum;
+#define WFST_LAUNCH(NARROW, BOOST, PROF, OPT) \
+  hipLaunchKernelGGL((wfst_channel_kernel<NARROW, BOOST, PROF, OPT>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a)
+  if (d->g.earc8) {                            // (no lean instances and no phase timing with narrow arc records)
+    if (boost) WFST_LAUNCH(true, true, false, true); else WFST_LAUNCH(true, false, false, true);
   } else if (d->phase_timing) {
-    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<false, true, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
-    else hipLaunchKernelGGL((wfst_channel_kernel<false, false, true>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    if (boost) { if (opt) WFST_LAUNCH(false, true, true, true); else WFST_LAUNCH(false, true, true, false); }
+    else { if (opt) WFST_LAUNCH(false, false, true, true); else WFST_LAUNCH(false, false, true, false); }
   } else {
-    if (boost) hipLaunchKernelGGL((wfst_channel_kernel<false, true, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
-    else hipLaunchKernelGGL((wfst_channel_kernel<false, false, false>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a);
+    if (boost) { if (opt) WFST_LAUNCH(false, true, false, true); else WFST_LAUNCH(false, true, false, false); }
+    else { if (opt) WFST_LAUNCH(false, false, false, true); else WFST_LAUNCH(false, false, false, false); }
   }
+#undef WFST_LAUNCH
   HIP_TRY(d, hipGetLastError());
   HIP_TRY(d, hipEventRecord(d->ev1[slot_id], st));
   d->timed[slot_id] = 1;

@@ -233,6 +233,25 @@ def test_c2_medium_batch_matches_oracle(torch_cuda, c2, c2_refs):
     check_batch(torch_cuda, c2.graph, c2.loglikes, c2.lengths, c2.beam, c2.max_active, refs=c2_refs)
 
 
+def test_c2_decoder_without_any_option(torch_cuda, c2, c2_refs):
+    """A decoder with no option on (no digests, no token records, no cost offsets, no recycling, no
+    boosting) runs the leanest instance of the kernel, the one the throughput is measured with:
+    words, cost bits, flags and counters of the whole batch against the oracle, twice in a row."""
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    dec = Decoder(c2.graph, max_channels=len(c2.lengths), max_frames=c2.loglikes.shape[1], max_active_hint=c2.max_active)
+    ll = torch.from_numpy(c2.loglikes).cuda()
+    for _ in range(2):
+        dec.get_counters(reset=True)
+        words, nwords, cost, flags = (t.cpu().numpy() for t in dec.decode_batch(ll, c2.lengths, c2.beam, c2.max_active))
+        for b, r in enumerate(c2_refs):
+            assert words[b, :nwords[b]].tolist() == r.words.tolist() and int(flags[b]) == r.flags, b
+            assert cost[b] == np.float32(r.cost), b
+        want = np.sum([r.counters for r in c2_refs], axis=0)
+        assert dec.get_counters()[:7].tolist() == want[:7].tolist()
+    dec.close()
+
+
 def test_c2_alone_equals_in_batch(torch_cuda, c2, c2_refs):
     b = 5
     check_batch(torch_cuda, c2.graph, c2.loglikes[b:b + 1], c2.lengths[b:b + 1], c2.beam, c2.max_active,
