@@ -212,6 +212,8 @@ def main_streaming(args):
                   outputs_on_host=True, recycle_lattice=bool(W))
     chans = np.arange(n, dtype=np.int32)
     nfr = np.full(n, C, np.int32)
+    if args.stream_workgroups:
+        dec.set_launch_workgroups(args.stream_workgroups)
     dec.init_channels(chans, float(c["beam"]), int(c["max_active"]))
     torch.cuda.synchronize()
     print(f"[bench] streaming: {n} channels x {n_chunks}+{warm}+{extra} chunks of {C} frames, "
@@ -336,7 +338,7 @@ def main():
     ap.add_argument("--recycle-window", type=int, default=0,
                     help="streaming mode: recycle every channel's lattice memory as a ring over this many frames")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=9)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c3_large")
     ap.add_argument("--batch", type=int, default=None)
@@ -361,6 +363,12 @@ def main():
     ap.add_argument("--pipeline", type=int, default=3,
                     help="batch slots of the one decoder (each with its own stream) that take the steps in turn, so "
                          "that the next batch fills the compute units the previous one no longer uses")
+    ap.add_argument("--stream-workgroups", type=int, default=256,
+                    help="streaming mode: workgroups per launch, which take the channels from a counter on the device "
+                         "(one per compute unit; 0: one per channel)")
+    ap.add_argument("--launch-workgroups", type=int, default=128,
+                    help="with several batches in flight: workgroups per launch, which take the batch's utterances "
+                         "longest first from a counter on the device (wfst_set_launch_workgroups); 0: one per utterance")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (utterances are independent; more GPUs "
@@ -413,10 +421,15 @@ def main():
         """nsteps decode_batch calls taken in turn by the first n_use batch slots (each on its own
         stream); returns the wall time between two device synchronisations."""
         ms = []
+        # one batch in flight: a workgroup per utterance, the whole chip for the one launch; several: each
+        # launch gets a share of the compute units and its workgroups take the utterances from a queue
+        dec.set_launch_workgroups(args.launch_workgroups if n_use > 1 else 0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(nsteps):
             k = i % n_use
+            if n_use > 1 and nsteps % 2 == 1 and i == nsteps - 1:
+                dec.set_launch_workgroups(0)          # two launches of 128 workgroups share the chip; an odd last one has it alone
             outs[k] = dec.decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], out=outs[k],
                                        boosts=w.boosts, boost_fsts=w.boost_fsts, slot=k)
             with torch.cuda.stream(streams[k]):
@@ -502,6 +515,7 @@ def main():
         "config": {"workload": args.workload, "batch": B, "frames": int(w.lengths.sum()),
                    "states": w.graph.num_states, "arcs": w.graph.num_arcs, "classes": V,
                    "beam": w.beam, "max_active": w.max_active, "batches_in_flight": n_slots,
+                   "workgroups_per_launch": (min(B, args.launch_workgroups) if args.launch_workgroups > 0 and n_slots > 1 else B),
                    "loglike_dtype": args.loglike_dtype, "decoders": 1, "narrow_arcs": bool(args.narrow_arcs),
                    "device_gib": round(dec.device_bytes() / 2**30, 1)},
         "one_batch_in_flight": {"value": w.audio_seconds / (wall_one / args.steps),

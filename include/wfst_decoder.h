@@ -234,6 +234,18 @@ int32_t wfst_decode_batch_slot(wfst_decoder *dec, int32_t slot, const void *logl
                                const wfst_boost_table *const *boosts, const wfst_boost_fst *const *fsts,
                                void *stream, int32_t *words, int32_t *nwords, float *cost, int32_t *flags);
 
+/* How many workgroups the launches of this decoder get from now on.  n = 0 (the default): one per
+ * utterance (or channel) of the call.  n > 0: at most n; they take the call's utterances, longest
+ * first, one after the other from a counter on the device, so that all of them are busy until the
+ * call's work runs out and they end at nearly the same time.  This is for several batches in flight
+ * (batch slots): the GPU hands the workgroups of a launch to fixed groups of compute units in launch
+ * order, so with one workgroup per utterance a compute unit that a short utterance has left can
+ * stay idle while the next workgroup in line waits for another group.  With n chosen so that the
+ * launches in flight together hold exactly the GPU's compute units (256 on MI355X: n = 128 for
+ * two or three slots), and a multiple of 32 (8 dies x 4 groups), every workgroup finds a free
+ * compute unit at once.  Results do not depend on n.  Errors: INVALID_ARG (n < 0). */
+int32_t wfst_set_launch_workgroups(wfst_decoder *dec, int32_t n);
+
 /*
  * Streaming (Section "Streaming inference": the decoder state kept per audio stream is its
  * set of active tokens; here it lives permanently in the channel's slot in GPU memory, so

@@ -24,7 +24,7 @@ EXPORTS = ["wfst_decoder_create", "wfst_decoder_destroy", "wfst_decode_batch", "
            "wfst_advance_chunk", "wfst_advance_chunk_partial", "wfst_get_partial", "wfst_get_partial_batch", "wfst_get_lattice",
            "wfst_get_lattice_noalloc", "wfst_get_lattice_batch",
            "wfst_debug_frame_digests",
-           "wfst_debug_get_tokens", "wfst_debug_get_token_pairs", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_debug_set_phase_timing", "wfst_device_bytes",
+           "wfst_debug_get_tokens", "wfst_debug_get_token_pairs", "wfst_get_counters", "wfst_debug_phase_ticks", "wfst_debug_set_phase_timing", "wfst_set_launch_workgroups", "wfst_device_bytes",
            "wfst_last_kernel_ms", "wfst_last_error"]
 
 
@@ -122,6 +122,7 @@ def load_library():
     lib.wfst_get_counters.argtypes = [p, p, i32]
     lib.wfst_debug_phase_ticks.argtypes = [p, p, i32]
     lib.wfst_debug_set_phase_timing.argtypes = [p, i32]
+    lib.wfst_set_launch_workgroups.argtypes = [p, i32]
     lib.wfst_device_bytes.argtypes = [p]
     lib.wfst_device_bytes.restype = i64
     lib.wfst_last_kernel_ms.argtypes = [p]
@@ -496,6 +497,10 @@ class Decoder:
         c = np.zeros(8, np.int64)
         self._check(self.lib.wfst_get_counters(self.h, c.ctypes.data, int(reset)))
         return c
+
+    def set_launch_workgroups(self, n):
+        """At most n workgroups per launch from now on (0: one per utterance); see the header."""
+        self._check(self.lib.wfst_set_launch_workgroups(self.h, int(n)))
 
     def debug_set_phase_timing(self, on=True):
         self._check(self.lib.wfst_debug_set_phase_timing(self.h, int(bool(on))))

@@ -216,7 +216,11 @@ struct DevChannels {
 };
 
 struct LaunchArgs {
-  const int *chan, *nfr, *io;  // device [n]: channel id, frames to consume, row in loglikes/outputs
+  // device: the launch's lists, n_jobs entries each (the launch may have fewer workgroups): ints
+  // [channel id][frames to consume][row in loglikes/outputs][entries of the channel's lattice arena],
+  // then the first entry no workgroup has taken yet (starts at the number of workgroups) and a pad,
+  // then 64-bit [start of the channel's arena in the lattice pool]
+  int *lists; int n_jobs;
   const void *ll; long long ll_stride; int V;   // rows of V elements; fp32, or fp16 / bf16 widened when staged
   int ll_dtype;
   int mode, finalize;
@@ -283,6 +287,7 @@ struct Smem {
   long long prof[16];         // wall-clock ticks per phase (thread 0)
   long long prof_t0;
   int sel_idx;
+  int job;                    // the list entry this workgroup takes next
 };
 
 // ------------------------------------------------------------------------------ helpers
@@ -315,6 +320,9 @@ __device__ __forceinline__ float boost_step(const Smem &sm, int b, int word, int
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+__device__ __forceinline__ unsigned long long uni64(unsigned long long v) {
+  return ((unsigned long long)uni((unsigned)(v >> 32)) << 32) | uni((unsigned)v);
+}
 __device__ __forceinline__ double uni(double v) {
   const long long b = __double_as_longlong(v);
   const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(b & 0xffffffffll));
@@ -1848,7 +1856,7 @@ __device__ __forceinline__ void select_and_trace(Ctx &x, const LaunchArgs &a, in
 // clock read at every phase boundary costs the frame loop about 1 %).
 // kOpt: the decoder has one of its options on (cost offsets, token records for lattices, a recycled
 // arena, frame digests); the instance without carries none of their code.
-template <bool kNarrow, bool kBoost, bool kProf, bool kOpt>
+template <bool kNarrow, bool kBoost, bool kProf, bool kOpt, bool kQueue>
 __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(DevGraph g, DevChannels c_arg, LaunchArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x;
@@ -1856,28 +1864,42 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   if (!kOpt) {                                 // (the host launches this instance only when all of these are off)
     c.cost_offset = 0; c.recycle = 0; c.tokrec = nullptr; c.frame_best = nullptr; c.dig_sum = nullptr; c.dig_cnt = nullptr;
   }
-  const int ch = uni(a.chan[blockIdx.x]), nfr = uni(a.nfr[blockIdx.x]), io = uni(a.io[blockIdx.x]);
+  // A workgroup starts with the list entry of its own number; when that channel is done it takes the
+  // first entry nobody has taken yet, until none is left.  (With one workgroup per entry, the usual
+  // launch, that is one entry each.)  The host lists long utterances first, so a launch with fewer
+  // workgroups than entries ends for all of them at nearly the same time.
+  // The channel's pointers are moved from one channel to the next by the difference of the channel
+  // numbers, and what else a channel needs comes with the lists: so nothing but the lists has to
+  // stay in registers through the frame loop on account of the next channel.
+  int job = blockIdx.x;
+  int ch = uni(a.lists[job]);
   Ctx x{g, c, sm};
   x.cand = c.cand + (size_t)ch * c.cand_cap;
   x.win = c.win + (size_t)ch * c.win_cap;
   x.q0 = c.queue + (size_t)ch * 2 * c.qcap;
   x.wl0 = c.wl + (size_t)ch * 2 * c.qcap;
-  x.lat = c.lattice + c.lat_start[ch];
-  x.lat_cap = uni(c.lat_capn[ch]);
+  x.lat = c.lattice + uni64(reinterpret_cast<const unsigned long long *>(a.lists + 4 * a.n_jobs + 2)[job]);
   x.prof = kProf ? 1 : 0;
   x.frame_off = c.frame_off + (size_t)ch * (c.max_frames + 2);
   x.dig_sum = c.dig_sum ? c.dig_sum + (size_t)ch * (c.max_frames + 1) : nullptr;
   x.dig_cnt = c.dig_cnt ? c.dig_cnt + (size_t)ch * (c.max_frames + 1) : nullptr;
-  x.s = c.st[ch];
+  ChanState *stp = c.st + ch;
+  const int *bkp = c.boost_keys + (size_t)ch * kBoostSlots;
+  const float *bvp = c.boost_vals + (size_t)ch * kBoostSlots;
+  const unsigned *bfp = c.boost_from_to + (size_t)ch * kBoostSlots;
+  for (;;) {
+  const int nfr = uni(a.lists[a.n_jobs + job]), io = uni(a.lists[2 * a.n_jobs + job]);
+  x.lat_cap = uni((unsigned)a.lists[3 * a.n_jobs + job]);
+  x.s = *stp;
   x.s.frame = uni(x.s.frame); x.s.n_tok = uni(x.s.n_tok); x.s.cur = uni(x.s.cur); x.s.status = uni(x.s.status);
   x.s.lat_used = uni(x.s.lat_used); x.s.max_active = uni(x.s.max_active); x.s.beam = uni(x.s.beam);
   x.s.scale = uni(x.s.scale); x.s.sel_ratio = uni(x.s.sel_ratio); x.s.offset = uni(x.s.offset);
   x.s.boost_n = uni(x.s.boost_n); x.s.boost_states = uni(x.s.boost_states); x.s.lat_epoch = uni(x.s.lat_epoch);
   if (kBoost && x.s.boost_n > 0)
     for (int i = tid; i < kBoostSlots; i += kBlock) {
-      sm.bk[i] = c.boost_keys[(size_t)ch * kBoostSlots + i];
-      sm.bv[i] = c.boost_vals[(size_t)ch * kBoostSlots + i];
-      sm.bft[i] = c.boost_from_to[(size_t)ch * kBoostSlots + i];
+      sm.bk[i] = bkp[i];
+      sm.bv[i] = bvp[i];
+      sm.bft[i] = bfp[i];
     }
 
   if (tid == 0) {
@@ -1972,9 +1994,31 @@ __global__ __launch_bounds__(kBlock, WFST_MIN_WAVES) void wfst_channel_kernel(De
   }
   prof_mark(x, kPhTrace);
   if (tid == 0) {
-    c.st[ch] = x.s;
+    *stp = x.s;
     for (int i = 0; i < 16; ++i) atomicAdd((unsigned long long *)&c.counters[8 + i], (unsigned long long)sm.prof[i]);
     for (int i = 0; i < 8; ++i) atomicAdd((unsigned long long *)&c.counters[i], (unsigned long long)sm.ctr[i]);
+    if (kQueue) sm.job = atomicAdd(a.lists + 4 * a.n_jobs, 1);
+  }
+  if (!kQueue) break;          // (an instance of its own: the loop around the whole kernel costs the one-entry case 1.5 %)
+  __syncthreads();             // (also: nobody is still reading this channel's tables when the next one's are set up)
+  const int job_done = job;
+  job = uni(sm.job);
+  if (job >= a.n_jobs) break;
+  {
+    const int ch2 = uni(a.lists[job]);
+    const long long dch = (long long)ch2 - ch;
+    ch = ch2;
+    const unsigned long long *ls = reinterpret_cast<const unsigned long long *>(a.lists + 4 * a.n_jobs + 2);
+    x.lat += (long long)(uni64(ls[job]) - uni64(ls[job_done]));
+    x.cand += dch * c.cand_cap;
+    x.win += dch * c.win_cap;
+    x.q0 += dch * 2 * c.qcap;
+    x.wl0 += dch * 2 * c.qcap;
+    x.frame_off += dch * (c.max_frames + 2);
+    if (x.dig_sum) { x.dig_sum += dch * (c.max_frames + 1); x.dig_cnt += dch * (c.max_frames + 1); }
+    stp += dch;
+    bkp += dch * kBoostSlots; bvp += dch * kBoostSlots; bfp += dch * kBoostSlots;
+  }
   }
 }
 
@@ -2250,7 +2294,7 @@ struct wfst_decoder {
   int V = 0;
   std::vector<void *> allocs;
   int64_t dev_bytes = 0;
-  // per-launch parameter staging (ring, so back-to-back async launches never share a slot)
+  // per-launch lists: on the device one area per batch slot (+ one for the calls that name channels); host staging in a ring
   static constexpr int kRing = 8;
   int *d_params = nullptr;  int ring_pos = 0;
   unsigned long long *d_lat_ctr = nullptr;   // lattice kernel: links found, error bits
@@ -2277,11 +2321,13 @@ struct wfst_decoder {
   // utterance length (a batch decode)
   unsigned long long *d_lat_start = nullptr; unsigned *d_lat_capn = nullptr;
   std::vector<unsigned long long> eq_start; std::vector<unsigned> eq_capn;       // the equal shares
+  std::vector<unsigned long long> cur_start; std::vector<unsigned> cur_capn;     // where every channel's arena is now (what the device arrays hold)
   std::vector<unsigned long long> h_start[kRing]; std::vector<unsigned> h_capn[kRing];   // staging
   int part_pos = 0, last_timed = -1;
   std::vector<char> slot_by_length;    // the slot's pool is currently shared out by length
   std::vector<char> chan_ready;        // the channel has been initialised since its arena was last moved
   int phase_timing = 0;                // launches time their phases (wfst_debug_set_phase_timing)
+  int launch_workgroups = 0;           // most workgroups a launch gets (wfst_set_launch_workgroups); 0: one per list entry
   std::string err;
 };
 
@@ -2491,6 +2537,7 @@ int alloc_channels(wfst_decoder *d) {
   if ((rc = dev_alloc(d, &d->d_lat_capn, N))) return rc;
   d->eq_start.resize(N); d->eq_capn.assign(N, c.lat_cap);
   for (size_t ch = 0; ch < N; ++ch) d->eq_start[ch] = (unsigned long long)ch * c.lat_cap;
+  d->cur_start = d->eq_start; d->cur_capn = d->eq_capn;
   HIP_TRY(d, hipMemcpy(d->d_lat_start, d->eq_start.data(), N * sizeof(unsigned long long), hipMemcpyHostToDevice));
   HIP_TRY(d, hipMemcpy(d->d_lat_capn, d->eq_capn.data(), N * sizeof(unsigned), hipMemcpyHostToDevice));
   c.lat_start = d->d_lat_start; c.lat_capn = d->d_lat_capn;
@@ -2524,7 +2571,7 @@ int alloc_channels(wfst_decoder *d) {
   HIP_TRY(d, hipMemset(c.boost_from_to, 0, N * kBoostSlots * sizeof(unsigned)));
   HIP_TRY(d, hipHostMalloc(reinterpret_cast<void **>(&d->h_boost), N * kBoostStage * sizeof(int)));
   d->boost_on_dev.assign(N, 0);
-  if ((rc = dev_alloc(d, &d->d_params, (size_t)wfst_decoder::kRing * 3 * N))) return rc;
+  if ((rc = dev_alloc(d, &d->d_params, ((size_t)d->n_slots + 1) * (6 * N + 2)))) return rc;
   if ((rc = dev_alloc(d, &d->d_lat_ctr, (size_t)2))) return rc;
   if (o.keep_token_records) {                   // one entry per token set of every channel (a call may take them all)
     if ((rc = dev_alloc(d, &d->d_set_links, N * ((size_t)c.max_frames + 1) + 2))) return rc;
@@ -2551,21 +2598,35 @@ int launch(wfst_decoder *d, const std::vector<int> &chan, const std::vector<int>
   const int n = (int)chan.size();
   if (n == 0) return WFST_OK;
   const size_t N = (size_t)d->opts.max_channels;
-  int *slot = d->d_params + (size_t)d->ring_pos * 3 * N;
+  // workgroups of the launch: one per entry, or at most launch_workgroups, which then take the
+  // entries in list order from a counter that travels with the lists
+  const int n_wg = d->launch_workgroups > 0 ? std::min(n, d->launch_workgroups) : n;
+  // (the lists live on the device until the kernel ends, since its workgroups read them as they go:
+  // one area per batch slot, and one for the calls that name channels; calls that share an area do
+  // not overlap in time, so the stream orders this copy after the last kernel that read the area)
+  int *slot = d->d_params + (size_t)slot_id * (6 * N + 2);
   std::vector<int> &pack = d->h_params[d->ring_pos];
-  pack.resize(3 * (size_t)n);
+  pack.resize(6 * (size_t)n + 2);
   std::copy(chan.begin(), chan.end(), pack.begin());
   std::copy(nfr.begin(), nfr.end(), pack.begin() + n);
   std::copy(io.begin(), io.end(), pack.begin() + 2 * n);
+  for (int i = 0; i < n; ++i) {
+    pack[3 * (size_t)n + i] = (int)d->cur_capn[chan[i]];
+    std::memcpy(&pack[4 * (size_t)n + 2 + 2 * (size_t)i], &d->cur_start[chan[i]], sizeof(unsigned long long));
+  }
+  pack[4 * (size_t)n] = n_wg; pack[4 * (size_t)n + 1] = 0;
   d->ring_pos = (d->ring_pos + 1) % wfst_decoder::kRing;
   HIP_TRY(d, hipMemcpyAsync(slot, pack.data(), pack.size() * sizeof(int), hipMemcpyHostToDevice, st));
-  a.chan = slot; a.nfr = slot + n; a.io = slot + 2 * n;
+  a.lists = slot; a.n_jobs = n;
   HIP_TRY(d, hipEventRecord(d->ev0[slot_id], st));
   bool boost = false;                          // does any channel of the launch have a boosting table or acceptor?
   for (int ch : chan) boost = boost || d->boost_on_dev[ch] > 0;
   const bool opt = d->c.cost_offset || d->c.recycle || d->c.tokrec || d->c.frame_best || d->c.dig_sum;
 #define WFST_LAUNCH(NARROW, BOOST, PROF, OPT) \
-  hipLaunchKernelGGL((wfst_channel_kernel<NARROW, BOOST, PROF, OPT>), dim3(n), dim3(kBlock), 0, st, d->g, d->c, a)
+  do { \
+    if (n_wg < n) hipLaunchKernelGGL((wfst_channel_kernel<NARROW, BOOST, PROF, OPT, true>), dim3(n_wg), dim3(kBlock), 0, st, d->g, d->c, a); \
+    else hipLaunchKernelGGL((wfst_channel_kernel<NARROW, BOOST, PROF, OPT, false>), dim3(n_wg), dim3(kBlock), 0, st, d->g, d->c, a); \
+  } while (0)
   if (d->g.earc8) {                            // (no lean instances and no phase timing with narrow arc records)
     if (boost) WFST_LAUNCH(true, true, false, true); else WFST_LAUNCH(true, false, false, true);
   } else if (d->phase_timing) {
@@ -2603,6 +2664,8 @@ int partition_slot(wfst_decoder *d, int slot, const int32_t *want, int n, hipStr
       hs[b] = at; hc[b] = (unsigned)cap; at += cap;
     }
   }
+  std::copy(hs.begin(), hs.end(), d->cur_start.begin() + ch0);
+  std::copy(hc.begin(), hc.end(), d->cur_capn.begin() + ch0);
   HIP_TRY(d, hipMemcpyAsync(d->d_lat_start + ch0, hs.data(), sc * sizeof(unsigned long long), hipMemcpyHostToDevice, st));
   HIP_TRY(d, hipMemcpyAsync(d->d_lat_capn + ch0, hc.data(), sc * sizeof(unsigned), hipMemcpyHostToDevice, st));
   d->slot_by_length[slot] = want ? 1 : 0;
@@ -3343,6 +3406,13 @@ int32_t wfst_get_counters(wfst_decoder *d, int64_t counters[8], int32_t reset) {
   HIP_TRY(d, hipDeviceSynchronize());
   HIP_TRY(d, hipMemcpy(counters, d->c.counters, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
   if (reset) HIP_TRY(d, hipMemset(d->c.counters, 0, 8 * sizeof(int64_t)));
+  return WFST_OK;
+}
+
+int32_t wfst_set_launch_workgroups(wfst_decoder *d, int32_t n) {
+  if (!d) return WFST_ERR_INVALID_ARG;
+  if (n < 0) return fail(d, WFST_ERR_INVALID_ARG, "launch workgroups must be >= 0");
+  d->launch_workgroups = n;
   return WFST_OK;
 }
 

@@ -38,12 +38,13 @@ def oracle_batch(graph, loglikes, lengths, beam, max_active, max_words=256, thre
 
 def check_batch(torch, graph, loglikes, lengths, beam, max_active, max_words=256, refs=None,
                 max_active_hint=None, check_counters=True, boosts=None, device_loglikes=None, cost_offset=False,
-                boost_fsts=None, **deckw):
+                boost_fsts=None, launch_workgroups=0, **deckw):
     from paper_2311_04996_amd import Decoder
     B, T, V = loglikes.shape
     dec = Decoder(graph, max_channels=max(B, 1), max_frames=max(T, 1), max_words=max_words,
                   max_active_hint=max_active_hint or min(max_active, 20000), record_digests=True,
                   cost_offset=cost_offset, **deckw)
+    dec.set_launch_workgroups(launch_workgroups)
     ll = torch.from_numpy(np.ascontiguousarray(loglikes)).cuda() if device_loglikes is None else device_loglikes
     words, nwords, cost, flags = dec.decode_batch(ll, lengths, beam, max_active, boosts=boosts, boost_fsts=boost_fsts)
     torch.cuda.synchronize()
@@ -252,6 +253,42 @@ def test_c2_decoder_without_any_option(torch_cuda, c2, c2_refs):
     dec.close()
 
 
+@pytest.mark.parametrize("n_wg", [1, 5, 31, 32, 100])
+def test_c2_fewer_workgroups_than_utterances(torch_cuda, c2, c2_refs, n_wg):
+    """wfst_set_launch_workgroups: the launch gets n_wg workgroups, which take the 32 utterances one
+    after the other from a counter on the device (each workgroup decodes several channels in a row,
+    moving its pointers from one to the next).  Token sets of every frame, words, cost bits, flags
+    and counters are the oracle's whatever n_wg is (32 and 100: one workgroup per utterance again)."""
+    check_batch(torch_cuda, c2.graph, c2.loglikes, c2.lengths, c2.beam, c2.max_active, refs=c2_refs,
+                launch_workgroups=n_wg)
+
+
+def test_fewer_workgroups_with_boosting_and_lean_kernel(torch_cuda, c2, c2_refs):
+    """The same through the other instances of the kernel: a decoder without any option (three
+    calls in a row on one decoder, the workgroup count changed in between), and utterances that each
+    have their own boosting acceptor (a workgroup loads the next channel's acceptor into LDS)."""
+    from paper_2311_04996_amd import Decoder
+    torch = torch_cuda
+    dec = Decoder(c2.graph, max_channels=len(c2.lengths), max_frames=c2.loglikes.shape[1], max_active_hint=c2.max_active)
+    ll = torch.from_numpy(c2.loglikes).cuda()
+    for n_wg in (3, 0, 7):
+        dec.set_launch_workgroups(n_wg)
+        dec.get_counters(reset=True)
+        words, nwords, cost, flags = (t.cpu().numpy() for t in dec.decode_batch(ll, c2.lengths, c2.beam, c2.max_active))
+        for b, r in enumerate(c2_refs):
+            assert words[b, :nwords[b]].tolist() == r.words.tolist() and int(flags[b]) == r.flags, (n_wg, b)
+            assert cost[b] == np.float32(r.cost), (n_wg, b)
+        want = np.sum([r.counters for r in c2_refs], axis=0)
+        assert dec.get_counters()[:7].tolist() == want[:7].tolist()
+    dec.close()
+    from workloads import boost_fsts
+    n = 6
+    fsts = boost_fsts(9, n, int(c2.graph.meta["num_words"]), per_utt=100, max_len=4, score=-4.0, hot_words=40)
+    lengths = np.minimum(c2.lengths[:n], 200)
+    check_batch(torch_cuda, c2.graph, c2.loglikes[:n, :200], lengths, c2.beam, c2.max_active, boost_fsts=fsts,
+                launch_workgroups=2)
+
+
 def test_c2_alone_equals_in_batch(torch_cuda, c2, c2_refs):
     b = 5
     check_batch(torch_cuda, c2.graph, c2.loglikes[b:b + 1], c2.lengths[b:b + 1], c2.beam, c2.max_active,
@@ -283,10 +320,11 @@ def test_candidate_overflow_is_reported_not_fatal(torch_cuda, c2):
     dec.close()
 
 
-@pytest.mark.parametrize("chunk", [1, 16, 37])
-def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk):
+@pytest.mark.parametrize("chunk,n_wg", [(1, 0), (16, 0), (37, 0), (16, 3)])
+def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk, n_wg):
     """Per-stream state persists between chunks (Section 'Streaming inference'): any chunking
-    gives the offline result bit for bit, and partial hypotheses depend on the frame count only."""
+    gives the offline result bit for bit, and partial hypotheses depend on the frame count only.
+    (n_wg = 3: the four channels of every launch are taken by three workgroups.)"""
     from oracle import Oracle
     from paper_2311_04996_amd import Decoder
     torch = torch_cuda
@@ -295,6 +333,7 @@ def test_streaming_equals_offline(torch_cuda, c2, c2_refs, chunk):
     lens = np.minimum(c2.lengths[utts], 120 if chunk == 1 else 10**6)
     T = int(lens.max())
     dec = Decoder(c2.graph, max_channels=8, max_frames=T, max_active_hint=c2.max_active, record_digests=True)
+    dec.set_launch_workgroups(n_wg)
     ll = torch.from_numpy(np.ascontiguousarray(c2.loglikes[utts, :T])).cuda()
     for ch in chans:
         dec.init_channel(ch, c2.beam, c2.max_active)
