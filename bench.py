@@ -366,9 +366,10 @@ def main():
     ap.add_argument("--stream-workgroups", type=int, default=256,
                     help="streaming mode: workgroups per launch, which take the channels from a counter on the device "
                          "(one per compute unit; 0: one per channel)")
-    ap.add_argument("--launch-workgroups", type=int, default=128,
+    ap.add_argument("--launch-workgroups", type=int, default=-1,
                     help="with several batches in flight: workgroups per launch, which take the batch's utterances "
-                         "longest first from a counter on the device (wfst_set_launch_workgroups); 0: one per utterance")
+                         "longest first from a counter on the device (wfst_set_launch_workgroups); 0: one per utterance; "
+                         "-1: half of the GPU's compute units (two launches hold the chip between them)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (utterances are independent; more GPUs "
@@ -401,6 +402,8 @@ def main():
     # ONE decoder: the batches in flight are its batch slots (shared graph), and a slot's lattice
     # memory is shared out by utterance length, so it is sized for the batch's mean length
     n_slots = max(1, args.pipeline)
+    if args.launch_workgroups < 0:
+        args.launch_workgroups = torch.cuda.get_device_properties(0).multi_processor_count // 2 // 32 * 32
     mean_frames = float(w.lengths.mean())
     dec = Decoder(w.graph, max_channels=B * n_slots, max_frames=T, max_words=512, max_active_hint=w.max_active,
                   loglike_dtype=args.loglike_dtype, batch_slots=n_slots, lattice_by_length=True,

@@ -430,31 +430,37 @@ def test_c3_full_batch_every_utterance_against_oracle(torch_cuda, c3_graph):
     got = dec.get_counters()
     assert got[:7].tolist() == want[:7].tolist(), (got, want)
     assert got[7] == int(w.lengths.sum())
-    # the launch configuration bench.py times: three decoders, each on its own stream, the batch
-    # decoded by all three at once; every decoder's result is again compared with the oracle
-    decs = [dec] + [Decoder(w.graph, max_channels=B, max_frames=T, max_words=512, max_active_hint=w.max_active,
-                            record_digests=True) for _ in range(2)]
-    streams = [torch.cuda.Stream() for _ in decs]
+    dec.close()
+    # the launch configuration bench.py times: ONE decoder with three batch slots, each slot's batch on
+    # its own stream, 128 workgroups per launch that take the utterances from the device-side queue;
+    # six batches in flight three at a time, every result compared with the oracle again
+    dec = Decoder(w.graph, max_channels=3 * B, max_frames=T, max_words=512, max_active_hint=w.max_active,
+                  record_digests=True, batch_slots=3, lattice_by_length=True,
+                  lattice_bytes_per_channel=int(8 * 1.5 * w.max_active * (float(w.lengths.mean()) + 2)))
+    dec.set_launch_workgroups(128)
+    streams = [torch.cuda.Stream() for _ in range(3)]
     torch.cuda.synchronize()
-    outs = [d.decode_batch(ll, w.lengths, w.beam, w.max_active, stream=st) for d, st in zip(decs, streams)]
-    torch.cuda.synchronize()
-    for k, out in enumerate(outs):
-        ow, on, oc, of = (x.cpu().numpy() for x in out)
-        for b, r in enumerate(refs):
-            assert ow[b, :on[b]].tolist() == r.words.tolist() and oc[b] == np.float32(r.cost) and of[b] == r.flags, \
-                f"decoder {k}, utt {b}"
-        for b in range(0, B, 16):
-            cnt, dig = decs[k].debug_frame_digests(b)
-            assert (cnt == refs[b].digest_count).all() and (dig == refs[b].digest_sum).all(), f"decoder {k}, utt {b}"
-    for d in decs:
-        d.close()
+    for rnd in range(2):
+        outs = [dec.decode_batch(ll, w.lengths, w.beam, w.max_active, stream=streams[k], slot=k) for k in range(3)]
+        torch.cuda.synchronize()
+        for k, out in enumerate(outs):
+            ow, on, oc, of = (x.cpu().numpy() for x in out)
+            for b, r in enumerate(refs):
+                assert ow[b, :on[b]].tolist() == r.words.tolist() and oc[b] == np.float32(r.cost) and of[b] == r.flags, \
+                    f"round {rnd}, slot {k}, utt {b}"
+            for b in range(rnd, B, 16):
+                cnt, dig = dec.debug_frame_digests(k * B + b)
+                assert (cnt == refs[b].digest_count).all() and (dig == refs[b].digest_sum).all(), f"round {rnd}, slot {k}, utt {b}"
+    got = dec.get_counters()
+    assert got[:7].tolist() == (6 * want[:7]).tolist(), (got, want)
+    dec.close()
 
 
 # ------------------------------------------------------------------------------- config 4, full size
 def test_c4_streaming_512_channels_against_oracle(torch_cuda, c3_graph):
     """The streaming configuration bench.py times: the config-3 graph, 512 concurrent channels,
-    16-frame chunks through wfst_advance_chunk, the partial hypotheses of all channels fetched
-    with wfst_get_partial_batch after EVERY chunk.  Every partial result of every channel
+    16-frame chunks, the partial hypotheses of all channels after EVERY chunk (alternately with
+    wfst_advance_chunk + wfst_get_partial_batch and with wfst_advance_chunk_partial).  Every partial result of every channel
     (words, cost bits, flags) is compared with the oracle's decode of that prefix, and at the
     end the token sets of every frame of every channel by count and digest."""
     from oracle import Oracle
@@ -486,10 +492,14 @@ def test_c4_streaming_512_channels_against_oracle(torch_cuda, c3_graph):
                   record_digests=True)
     chans = np.arange(n, dtype=np.int32)
     nfr = np.full(n, C, np.int32)
+    dec.set_launch_workgroups(256)                                    # as bench.py: a workgroup per compute unit, channels from the queue
     dec.init_channels(chans, beam, ma)                                # one launch for the burst of new streams
     for k in range(n_chunks):
-        dec.advance_chunk(chans, chunks[k], nfr)
-        words, nwords, cost, flags = dec.get_partial_batch(chans, finalize=False)
+        if k % 2:                                                     # (bench.py's default: both in one launch)
+            words, nwords, cost, flags = dec.advance_chunk_partial(chans, chunks[k], nfr, finalize=False)
+        else:
+            dec.advance_chunk(chans, chunks[k], nfr)
+            words, nwords, cost, flags = dec.get_partial_batch(chans, finalize=False)
         for ch in range(n):
             r = refs[ch][k]
             assert words[ch, :nwords[ch]].tolist() == r.words.tolist(), f"chunk {k}, channel {ch}: words differ"
