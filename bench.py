@@ -454,6 +454,9 @@ def main():
     counters = dec.get_counters() // max(1, args.steps)
     # the timed region proper: `pipeline` batches in flight
     wall = run_steps(n_slots, args.steps, False)[0] if n_slots > 1 else wall_one
+    # the launches of the timed region itself, by the same HIP events: the last launch of every slot (two of
+    # them hold the chip at a time; a third has been waiting in its queue for compute units, which counts)
+    kms_at_value = [float(dec.slot_kernel_ms(k)) for k in range(min(n_slots, args.steps))] if n_slots > 1 else None
     # where the workgroups spend their time: one more launch, untimed, with the phase clocks on
     # (they are off in the timed regions: reading the clock at every phase boundary costs about 1 %)
     dec.debug_phase_ticks(reset=True)
@@ -533,6 +536,7 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "traffic_source": traffic_source, "traffic_detail": traffic_detail,
                      "algorithmic_bytes_per_launch": abytes, "kernel_ms": kms,
+                     "kernel_ms_of_last_launches_at_value": kms_at_value,
                      "note": "achieved / frac: algorithmic bytes over the kernel's own duration with ONE batch in flight "
                              "(HIP events on the launch stream); *_at_value: over ms_per_step of the timed region, "
                              f"{n_slots} batches in flight",

@@ -208,6 +208,9 @@ def test_argument_errors(torch_cuda, c1):
     with pytest.raises(WfstError) as e:
         dec.decode_batch(ll[:, :50].contiguous(), [50], -1.0, 100)
     assert e.value.code == -1
+    with pytest.raises(WfstError) as e:
+        dec.set_launch_workgroups(-1)
+    assert e.value.code == -1
     dec.close()
 
 
