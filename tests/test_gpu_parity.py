@@ -925,7 +925,8 @@ def test_cost_offsets_in_a_streamed_channel(torch_cuda, c2):
 def test_random_small_configurations(torch_cuda):
     """Thirty seeded combinations of graph shape (epsilon share up to 45 %, hubs of up to 700 arcs),
     class count, beam, max-active, batch and length mix (0- and 1-frame utterances included),
-    half of them with cost offsets, a third with 16-bit rows."""
+    half of them with cost offsets, a third with 16-bit rows, three quarters with fewer workgroups
+    than utterances (1, 2 or 3 for up to 6 utterances)."""
     from workloads import ctc_loglikes, tlg_shaped_graph
     torch = torch_cuda
     for seed in range(30):
@@ -943,7 +944,7 @@ def test_random_small_configurations(torch_cuda):
                           blank_boost=float(rng.uniform(1, 6)), token_boost=float(rng.uniform(1, 5)))
         beam = float(rng.choice([0.5, 3.0, 9.0, 17.0, 40.0]))
         ma = int(rng.choice([1, 7, 100, 1500, 20000]))
-        kw = {"cost_offset": bool(seed % 2)}
+        kw = {"cost_offset": bool(seed % 2), "launch_workgroups": (0, 1, 2, 3)[(seed // 2) % 4]}
         if seed % 3 == 0:
             dt = "float16" if seed % 2 else "bfloat16"
             dev = torch.from_numpy(ll).to(getattr(torch, dt)).cuda()
